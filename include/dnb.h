@@ -1,0 +1,168 @@
+/*
+ * dnb.h -- C ABI of the memory-efficient DenseNet dense block for AMD MI355X (gfx950).
+ *
+ * One dense block (paper, Section 2): x_l = H_l([x_0, x_1, ..., x_{l-1}]) for
+ * l = 1..m, with H_l the pre-activation composite BN -> ReLU -> 1x1 conv (to B
+ * "bottleneck" channels) -> BN -> ReLU -> 3x3 conv (to k "growth" channels),
+ * run forward and backward through the Shared Memory Storage scheme of
+ * Section 4: the concatenated input of a layer goes to shared storage 1, its
+ * BN+ReLU output to shared storage 2 (the bottleneck's second BN+ReLU output to
+ * a third shared buffer); every layer overwrites them and the backward pass
+ * re-populates them by recomputation before ordinary back-propagation, so the
+ * only feature maps that persist are convolution outputs and feature-map memory
+ * is linear in m (Section 4, last paragraph; Section 5).
+ *
+ * Conventions
+ *   - Every pointer named x0, params, y, dy, dx0, dparams, workspace is a DEVICE
+ *     pointer owned by the caller (e.g. torch.empty(...).data_ptr()), at least
+ *     16-byte aligned.  The library never allocates or frees device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  Calls
+ *     enqueue kernels on it and return without synchronising.  Calls that share
+ *     a workspace must be ordered on one stream: the shared buffers are
+ *     overwritten layer by layer.
+ *   - Every function returning int returns DNB_OK (0) or a negative DNB_E_* code;
+ *     nothing throws or aborts.  Only argument and launch errors are reported
+ *     synchronously.
+ *   - Tensors are dense, row-major, in the layout named by the descriptor:
+ *     NCHW (n, c, h, w) or NHWC (n, h, w, c).
+ */
+#ifndef DNB_H_
+#define DNB_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dnb_block dnb_block; /* opaque, host side only */
+
+enum { DNB_OK = 0, DNB_E_BADDESC = -1, DNB_E_NULL = -2, DNB_E_ALIGN = -3, DNB_E_LAUNCH = -4,
+       DNB_E_UNSUPPORTED = -5, DNB_E_RANGE = -6, DNB_E_NOMEM = -7 };
+
+enum { DNB_F32 = 0, DNB_BF16 = 1 };  /* storage type of feature maps; accumulation and BN statistics are fp32 */
+enum { DNB_NCHW = 0, DNB_NHWC = 1 };
+/* Section 5 compares exactly these two ways of running the same arithmetic. */
+enum { DNB_SCHED_SHARED = 0,     /* Section 4: shared storage + recomputation (linear memory)   */
+       DNB_SCHED_STORE_ALL = 1   /* Section 3: every concat / BN output kept (quadratic memory) */ };
+/* Parameter tensors of one layer, in pack order. */
+enum { DNB_P_G1 = 0, DNB_P_B1 = 1, DNB_P_W1 = 2, DNB_P_G2 = 3, DNB_P_B2 = 4, DNB_P_W3 = 5 };
+
+typedef struct {
+  int32_t n, c0, h, w;  /* block input x0 is (n, c0, h, w)                            */
+  int32_t layers;       /* m >= 1                                                     */
+  int32_t growth;       /* k >= 1, channels added per layer                           */
+  int32_t bottleneck;   /* B >= 1, width of the 1x1 conv output (4k in DenseNet-BC)   */
+  int32_t dtype;        /* DNB_F32 | DNB_BF16                                         */
+  int32_t layout;       /* DNB_NCHW | DNB_NHWC                                        */
+  int32_t schedule;     /* DNB_SCHED_*                                                */
+  float eps;            /* BN epsilon (inside the square root)                        */
+} dnb_block_desc;
+
+/* Byte accounting of one block.  With P = n*h*w pixels, s = bytes per element,
+ * C_l = c0 + (l-1)k, C_m the widest layer input and C_out = c0 + m*k:
+ *   shared schedule   : stored = (m*B + m*k) P s        shared = (2 C_m + B) P s
+ *   store-all schedule: stored = (2 sum_l C_l + m(2B + k)) P s   shared = 0
+ *   both              : grad   = (C_out + C_m + B) P s
+ *   peak = stored + shared + grad.
+ * `stored` counts the m*k channels x_1..x_m although they live inside the
+ * caller's output y (they are conv feature maps the method keeps; Section 4). */
+typedef struct {
+  uint64_t stored_fwd_bytes;  /* conv outputs kept from forward to backward                     */
+  uint64_t shared_fwd_bytes;  /* shared storage 1, 2 and 3                                      */
+  uint64_t grad_bytes;        /* gradient slab G (C_out) + the two shared gradient scratch maps */
+  uint64_t peak_bytes;        /* sum of the three lines above: the feature-map memory           */
+  uint64_t stats_bytes;       /* cached fp32 per-channel BN mean and 1/sqrt(var+eps)            */
+  uint64_t scratch_bytes;     /* reduction partials (not feature maps)                          */
+  uint64_t workspace_bytes;   /* what the caller must allocate: everything above that lives in
+                                 the workspace, plus alignment padding                          */
+} dnb_block_memory;
+
+/* Validates the descriptor and builds the host-side plan (buffer offsets, launch
+ * shapes).  Host memory only.  *out is set on success. */
+int dnb_block_create(const dnb_block_desc* desc, dnb_block** out);
+void dnb_block_destroy(dnb_block* b);
+
+/* Feature-map bytes the block needs at its peak (formula above; Section 4/5:
+ * linear in m for DNB_SCHED_SHARED, quadratic for DNB_SCHED_STORE_ALL). */
+size_t dnb_block_peak_bytes(const dnb_block* b);
+/* Size of the single device workspace the caller passes to forward/backward. */
+size_t dnb_block_workspace_bytes(const dnb_block* b);
+int dnb_block_memory_breakdown(const dnb_block* b, dnb_block_memory* out);
+
+/* Parameter pack: fp32, per layer l = 1..m in order
+ *   g1[C_l] b1[C_l] W1[B][C_l] g2[B] b2[B] W3[k][B][3][3]
+ * (first BN scale/bias, 1x1 weights, second BN scale/bias, 3x3 weights, OIHW).
+ * `dparams` has the identical layout.  Offsets and counts are in elements. */
+size_t dnb_block_param_count(const dnb_block* b);
+int dnb_block_param_offset(const dnb_block* b, int layer /*1-based*/, int which /*DNB_P_* */,
+                           size_t* offset, size_t* count);
+
+/* Forward (Section 4, "Putting these pieces together"): for l = 1..m concat ->
+ * storage 1, BN+ReLU -> storage 2, 1x1 conv -> b_l (kept), BN+ReLU -> storage 3,
+ * 3x3 conv -> x_l, written straight into y.
+ *   x0      in   (n, c0, h, w)
+ *   params  in   parameter pack
+ *   y       out  (n, c0 + m*k, h, w) = [x0, x_1, ..., x_m], oldest first
+ *   workspace    >= dnb_block_workspace_bytes; must stay untouched, together with
+ *                y, until the matching backward has run. */
+int dnb_block_forward(dnb_block* b, const void* x0, const void* params, void* y, void* workspace,
+                      void* stream);
+
+/* Backward (Section 4): for l = m..1 re-populate the shared storage by
+ * recomputing concat and BN+ReLU from the kept conv outputs and cached
+ * statistics, then back-propagate through 3x3 conv, BN+ReLU, 1x1 conv, BN+ReLU
+ * and the concatenation (slice-accumulate into the gradient slab).
+ *   y       in   the forward's output (holds x0 and every x_l)
+ *   dy      in   gradient w.r.t. y, same shape
+ *   dx0     out  gradient w.r.t. x0 (overwritten)
+ *   dparams out  gradient pack, fp32, same layout as params (overwritten) */
+int dnb_block_backward(dnb_block* b, const void* params, const void* y, const void* dy, void* dx0,
+                       void* dparams, void* workspace, void* stream);
+
+const char* dnb_status_string(int status);
+
+/* ---- single operations of the path (fp32 NCHW), exported for tests and
+ * micro-benchmarks.  A "slab" is an (n, c, hw) tensor whose image stride
+ * (elements between consecutive n) is given explicitly, so channel ranges of a
+ * wider tensor can be addressed in place. */
+
+/* Section 2 "Contiguous concatenation": dst[i][0:len] = src[i][0:len], i < n. */
+int dnb_op_copy_slab(const void* src, int64_t src_stride, void* dst, int64_t dst_stride, int64_t n,
+                     int64_t len, void* stream);
+/* Scratch (device bytes) the two BN reductions below need for an (n, c, hw) slab. */
+size_t dnb_op_bn_scratch_bytes(int64_t n, int64_t c, int64_t hw);
+/* BN batch statistics per channel: mean and 1/sqrt(biased var + eps). */
+int dnb_op_bn_stats(const void* x, int64_t stride, int64_t n, int64_t c, int64_t hw, float eps,
+                    void* mean, void* istd, void* scratch, void* stream);
+/* out = max(0, gamma*(x-mean)*istd + beta) (BN apply with in-place ReLU, Section 3). */
+int dnb_op_bn_relu(const void* x, int64_t x_stride, void* out, int64_t out_stride, int64_t n,
+                   int64_t c, int64_t hw, const void* gamma, const void* beta, const void* mean,
+                   const void* istd, void* stream);
+/* Reverse of dnb_op_bn_relu.  dact = gradient w.r.t. the post-ReLU output.
+ * dgamma/dbeta are overwritten; du is overwritten (accumulate = 0) or added to. */
+int dnb_op_bn_relu_backward(const void* x, int64_t x_stride, const void* dact, int64_t dact_stride,
+                            void* du, int64_t du_stride, int accumulate, int64_t n, int64_t c,
+                            int64_t hw, const void* gamma, const void* beta, const void* mean,
+                            const void* istd, void* dgamma, void* dbeta, void* scratch,
+                            void* stream);
+/* Convolutions: ks = 1 or 3, stride 1, zero padding (ks-1)/2, no bias,
+ * cross-correlation; weights OIHW (cout, cin, ks, ks).  `scratch` holds split
+ * reduction partials for the weight gradient: dnb_op_conv_wgrad_scratch_bytes. */
+int dnb_op_conv_forward(const void* x, int64_t x_stride, const void* wgt, void* out,
+                        int64_t out_stride, int64_t n, int64_t cin, int64_t cout, int64_t h,
+                        int64_t w, int ks, void* stream);
+int dnb_op_conv_dgrad(const void* dout, int64_t dout_stride, const void* wgt, void* din,
+                      int64_t din_stride, int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w,
+                      int ks, void* stream);
+size_t dnb_op_conv_wgrad_scratch_bytes(int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w,
+                                       int ks);
+int dnb_op_conv_wgrad(const void* x, int64_t x_stride, const void* dout, int64_t dout_stride,
+                      void* dwgt, int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w, int ks,
+                      void* scratch, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DNB_H_ */

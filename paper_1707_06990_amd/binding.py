@@ -1,0 +1,190 @@
+"""Thin ctypes binding of libdnb.so: same names as include/dnb.h, argument
+marshalling only.  Device memory and streams come from PyTorch; every step of
+the path runs in the library's HIP kernels.  There is no fallback: if the
+library is missing, importing this module raises."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdnb.so")
+
+DNB_OK = 0
+DNB_E_BADDESC, DNB_E_NULL, DNB_E_ALIGN, DNB_E_LAUNCH, DNB_E_UNSUPPORTED, DNB_E_RANGE, DNB_E_NOMEM = range(-1, -8, -1)
+DNB_F32, DNB_BF16 = 0, 1
+DNB_NCHW, DNB_NHWC = 0, 1
+DNB_SCHED_SHARED, DNB_SCHED_STORE_ALL = 0, 1
+DNB_P_G1, DNB_P_B1, DNB_P_W1, DNB_P_G2, DNB_P_B2, DNB_P_W3 = range(6)
+
+
+class dnb_block_desc(C.Structure):
+    _fields_ = [("n", C.c_int32), ("c0", C.c_int32), ("h", C.c_int32), ("w", C.c_int32),
+                ("layers", C.c_int32), ("growth", C.c_int32), ("bottleneck", C.c_int32),
+                ("dtype", C.c_int32), ("layout", C.c_int32), ("schedule", C.c_int32),
+                ("eps", C.c_float)]
+
+
+class dnb_block_memory(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("stored_fwd_bytes", "shared_fwd_bytes", "grad_bytes", "peak_bytes",
+                                           "stats_bytes", "scratch_bytes", "workspace_bytes")]
+
+    def as_dict(self):
+        return {n: int(getattr(self, n)) for n, _ in self._fields_}
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} not found: build it first (python -m paper_1707_06990_amd.build "
+                      "or __graft_entry__.build()); there is no fallback path")
+
+_lib = C.CDLL(LIB_PATH)
+_vp, _i64, _sz = C.c_void_p, C.c_int64, C.c_size_t
+
+_SIGS = {
+    "dnb_block_create": (C.c_int, [C.POINTER(dnb_block_desc), C.POINTER(_vp)]),
+    "dnb_block_destroy": (None, [_vp]),
+    "dnb_block_peak_bytes": (_sz, [_vp]),
+    "dnb_block_workspace_bytes": (_sz, [_vp]),
+    "dnb_block_memory_breakdown": (C.c_int, [_vp, C.POINTER(dnb_block_memory)]),
+    "dnb_block_param_count": (_sz, [_vp]),
+    "dnb_block_param_offset": (C.c_int, [_vp, C.c_int, C.c_int, C.POINTER(_sz), C.POINTER(_sz)]),
+    "dnb_block_forward": (C.c_int, [_vp] * 6),
+    "dnb_block_backward": (C.c_int, [_vp] * 8),
+    "dnb_status_string": (C.c_char_p, [C.c_int]),
+    "dnb_op_copy_slab": (C.c_int, [_vp, _i64, _vp, _i64, _i64, _i64, _vp]),
+    "dnb_op_bn_scratch_bytes": (_sz, [_i64, _i64, _i64]),
+    "dnb_op_bn_stats": (C.c_int, [_vp, _i64, _i64, _i64, _i64, C.c_float, _vp, _vp, _vp, _vp]),
+    "dnb_op_bn_relu": (C.c_int, [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp]),
+    "dnb_op_bn_relu_backward": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, C.c_int, _i64, _i64, _i64,
+                                          _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "dnb_op_conv_forward": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp]),
+    "dnb_op_conv_dgrad": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp]),
+    "dnb_op_conv_wgrad_scratch_bytes": (_sz, [_i64, _i64, _i64, _i64, _i64, C.c_int]),
+    "dnb_op_conv_wgrad": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
+}
+for _name, (_res, _args) in _SIGS.items():
+    _f = getattr(_lib, _name)
+    _f.restype = _res
+    _f.argtypes = _args
+
+EXPORTED = tuple(_SIGS)
+
+
+class DnbError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"dnb status {status}: {dnb_status_string(status)}")
+
+
+def _check(status: int) -> None:
+    if status != DNB_OK:
+        raise DnbError(status)
+
+
+def _ptr(t):
+    """Device address of a torch tensor (or a raw int / None)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return stream if isinstance(stream, int) else stream.cuda_stream
+
+
+def dnb_status_string(status: int) -> str:
+    return _lib.dnb_status_string(status).decode()
+
+
+def dnb_block_create(n, c0, h, w, layers, growth, bottleneck, dtype=DNB_F32, layout=DNB_NCHW,
+                     schedule=DNB_SCHED_SHARED, eps=1e-5):
+    desc = dnb_block_desc(n, c0, h, w, layers, growth, bottleneck, dtype, layout, schedule, eps)
+    out = _vp()
+    _check(_lib.dnb_block_create(C.byref(desc), C.byref(out)))
+    return out
+
+
+def dnb_block_destroy(b) -> None:
+    _lib.dnb_block_destroy(b)
+
+
+def dnb_block_peak_bytes(b) -> int:
+    return int(_lib.dnb_block_peak_bytes(b))
+
+
+def dnb_block_workspace_bytes(b) -> int:
+    return int(_lib.dnb_block_workspace_bytes(b))
+
+
+def dnb_block_memory_breakdown(b) -> dict:
+    m = dnb_block_memory()
+    _check(_lib.dnb_block_memory_breakdown(b, C.byref(m)))
+    return m.as_dict()
+
+
+def dnb_block_param_count(b) -> int:
+    return int(_lib.dnb_block_param_count(b))
+
+
+def dnb_block_param_offset(b, layer: int, which: int):
+    off, cnt = _sz(), _sz()
+    _check(_lib.dnb_block_param_offset(b, layer, which, C.byref(off), C.byref(cnt)))
+    return int(off.value), int(cnt.value)
+
+
+def dnb_block_forward(b, x0, params, y, workspace, stream=None) -> None:
+    _check(_lib.dnb_block_forward(b, _ptr(x0), _ptr(params), _ptr(y), _ptr(workspace), _stream(stream)))
+
+
+def dnb_block_backward(b, params, y, dy, dx0, dparams, workspace, stream=None) -> None:
+    _check(_lib.dnb_block_backward(b, _ptr(params), _ptr(y), _ptr(dy), _ptr(dx0), _ptr(dparams),
+                                   _ptr(workspace), _stream(stream)))
+
+
+def dnb_op_copy_slab(src, src_stride, dst, dst_stride, n, length, stream=None) -> None:
+    _check(_lib.dnb_op_copy_slab(_ptr(src), src_stride, _ptr(dst), dst_stride, n, length, _stream(stream)))
+
+
+def dnb_op_bn_scratch_bytes(n, c, hw) -> int:
+    return int(_lib.dnb_op_bn_scratch_bytes(n, c, hw))
+
+
+def dnb_op_bn_stats(x, stride, n, c, hw, eps, mean, istd, scratch, stream=None) -> None:
+    _check(_lib.dnb_op_bn_stats(_ptr(x), stride, n, c, hw, eps, _ptr(mean), _ptr(istd), _ptr(scratch),
+                                _stream(stream)))
+
+
+def dnb_op_bn_relu(x, x_stride, out, out_stride, n, c, hw, gamma, beta, mean, istd, stream=None) -> None:
+    _check(_lib.dnb_op_bn_relu(_ptr(x), x_stride, _ptr(out), out_stride, n, c, hw, _ptr(gamma), _ptr(beta),
+                               _ptr(mean), _ptr(istd), _stream(stream)))
+
+
+def dnb_op_bn_relu_backward(x, x_stride, dact, dact_stride, du, du_stride, accumulate, n, c, hw, gamma, beta,
+                            mean, istd, dgamma, dbeta, scratch, stream=None) -> None:
+    _check(_lib.dnb_op_bn_relu_backward(_ptr(x), x_stride, _ptr(dact), dact_stride, _ptr(du), du_stride,
+                                        int(accumulate), n, c, hw, _ptr(gamma), _ptr(beta), _ptr(mean),
+                                        _ptr(istd), _ptr(dgamma), _ptr(dbeta), _ptr(scratch), _stream(stream)))
+
+
+def dnb_op_conv_forward(x, x_stride, wgt, out, out_stride, n, cin, cout, h, w, ks, stream=None) -> None:
+    _check(_lib.dnb_op_conv_forward(_ptr(x), x_stride, _ptr(wgt), _ptr(out), out_stride, n, cin, cout, h, w,
+                                    ks, _stream(stream)))
+
+
+def dnb_op_conv_dgrad(dout, dout_stride, wgt, din, din_stride, n, cin, cout, h, w, ks, stream=None) -> None:
+    _check(_lib.dnb_op_conv_dgrad(_ptr(dout), dout_stride, _ptr(wgt), _ptr(din), din_stride, n, cin, cout, h,
+                                  w, ks, _stream(stream)))
+
+
+def dnb_op_conv_wgrad_scratch_bytes(n, cin, cout, h, w, ks) -> int:
+    return int(_lib.dnb_op_conv_wgrad_scratch_bytes(n, cin, cout, h, w, ks))
+
+
+def dnb_op_conv_wgrad(x, x_stride, dout, dout_stride, dwgt, n, cin, cout, h, w, ks, scratch, stream=None) -> None:
+    _check(_lib.dnb_op_conv_wgrad(_ptr(x), x_stride, _ptr(dout), dout_stride, _ptr(dwgt), n, cin, cout, h, w,
+                                  ks, _ptr(scratch), _stream(stream)))

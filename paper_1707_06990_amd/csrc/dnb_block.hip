@@ -1,0 +1,412 @@
+// Host side of the dense-block library: descriptor validation, the workspace plan
+// (which buffer lives where, and the exact feature-map byte accounting), the two
+// schedules' kernel sequences, and the C ABI.  No device memory is allocated here.
+#include <new>
+#include <vector>
+
+#include "../../include/dnb.h"
+#include "dnb_internal.h"
+
+using namespace dnb;
+
+struct dnb_block {
+  dnb_block_desc d;
+  int64_t hw, P;
+  int cm, cout;
+  size_t esz;
+  // byte offsets into the workspace
+  std::vector<size_t> off_b;                 // b_l, kept 1x1 conv outputs
+  std::vector<size_t> off_u, off_a, off_a2;  // per layer: storage 1/2/3 (shared schedule: all equal)
+  size_t off_G, off_dS2, off_dS3;
+  size_t off_stat_y;                         // mean[C_out], istd[C_out]
+  std::vector<size_t> off_stat_b;            // per layer mean[B], istd[B]
+  size_t off_part;
+  std::vector<size_t> poff;                  // parameter offsets (elements) per layer
+  size_t pcount;
+  dnb_block_memory mem;
+};
+
+namespace {
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+inline int c_in(const dnb_block_desc& d, int l) { return d.c0 + (l - 1) * d.growth; }
+
+size_t layer_params(const dnb_block_desc& d, int l) {
+  const size_t c = (size_t)c_in(d, l), B = (size_t)d.bottleneck, k = (size_t)d.growth;
+  return 2 * c + B * c + 2 * B + k * B * 9;
+}
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+#define DNB_TRY(expr)                                 \
+  do {                                                \
+    if ((expr) != hipSuccess) return DNB_E_LAUNCH;    \
+  } while (0)
+
+struct LayerParams {
+  const float *g1, *b1, *W1, *g2, *b2, *W3;
+};
+struct LayerGrads {
+  float *g1, *b1, *W1, *g2, *b2, *W3;
+};
+
+template <typename T, typename P>
+T layer_ptrs(const dnb_block* b, P* base, int l) {
+  const size_t c = (size_t)c_in(b->d, l), B = (size_t)b->d.bottleneck;
+  P* p = base + b->poff[l];
+  T r;
+  r.g1 = p; r.b1 = p + c; r.W1 = p + 2 * c; r.g2 = p + 2 * c + B * c; r.b2 = r.g2 + B; r.W3 = r.b2 + B;
+  return r;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* dnb_status_string(int status) {
+  switch (status) {
+    case DNB_OK: return "ok";
+    case DNB_E_BADDESC: return "invalid block descriptor";
+    case DNB_E_NULL: return "null pointer argument";
+    case DNB_E_ALIGN: return "pointer not 16-byte aligned";
+    case DNB_E_LAUNCH: return "kernel launch failed";
+    case DNB_E_UNSUPPORTED: return "dtype/layout/schedule combination not built";
+    case DNB_E_RANGE: return "argument out of range";
+    case DNB_E_NOMEM: return "host allocation failed";
+    default: return "unknown status";
+  }
+}
+
+int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
+  if (!desc || !out) return DNB_E_NULL;
+  const dnb_block_desc& d = *desc;
+  if (d.n < 1 || d.c0 < 1 || d.h < 1 || d.w < 1 || d.layers < 1 || d.growth < 1 || d.bottleneck < 1)
+    return DNB_E_BADDESC;
+  if (!(d.eps >= 0.f)) return DNB_E_BADDESC;
+  if (d.dtype != DNB_F32 && d.dtype != DNB_BF16) return DNB_E_BADDESC;
+  if (d.layout != DNB_NCHW && d.layout != DNB_NHWC) return DNB_E_BADDESC;
+  if (d.schedule != DNB_SCHED_SHARED && d.schedule != DNB_SCHED_STORE_ALL) return DNB_E_BADDESC;
+  if (d.dtype != DNB_F32 || d.layout != DNB_NCHW) return DNB_E_UNSUPPORTED;
+  const int64_t hw = (int64_t)d.h * d.w, P = hw * d.n;
+  const int64_t cout = (int64_t)d.c0 + (int64_t)d.layers * d.growth;
+  if (cout * P >= (int64_t)1 << 31 || (int64_t)d.bottleneck * P >= (int64_t)1 << 31) return DNB_E_RANGE;
+
+  dnb_block* b = new (std::nothrow) dnb_block();
+  if (!b) return DNB_E_NOMEM;
+  b->d = d;
+  b->hw = hw;
+  b->P = P;
+  const int m = d.layers, k = d.growth, B = d.bottleneck;
+  b->cm = c_in(d, m);
+  b->cout = (int)cout;
+  b->esz = 4;
+  const size_t Ps = (size_t)P * b->esz;
+
+  b->poff.assign(m + 2, 0);
+  size_t po = 0;
+  for (int l = 1; l <= m; ++l) { b->poff[l] = po; po += layer_params(d, l); }
+  b->pcount = po;
+
+  // ---- workspace plan; every buffer starts on a 256-byte boundary
+  size_t off = 0, fm_exact = 0;
+  auto carve = [&](size_t bytes, bool feature_map) {
+    const size_t o = off;
+    off = align_up(off + bytes, 256);
+    if (feature_map) fm_exact += bytes;
+    return o;
+  };
+  b->off_b.assign(m + 1, 0);
+  b->off_u.assign(m + 1, 0);
+  b->off_a.assign(m + 1, 0);
+  b->off_a2.assign(m + 1, 0);
+  b->off_stat_b.assign(m + 1, 0);
+  dnb_block_memory& mem = b->mem;
+  mem = dnb_block_memory{};
+  size_t sigma_c = 0;
+  for (int l = 1; l <= m; ++l) sigma_c += (size_t)c_in(d, l);
+  for (int l = 1; l <= m; ++l) b->off_b[l] = carve((size_t)B * Ps, true);
+  if (d.schedule == DNB_SCHED_SHARED) {
+    const size_t s1 = carve((size_t)b->cm * Ps, true), s2 = carve((size_t)b->cm * Ps, true),
+                 s3 = carve((size_t)B * Ps, true);
+    for (int l = 1; l <= m; ++l) { b->off_u[l] = s1; b->off_a[l] = s2; b->off_a2[l] = s3; }
+    mem.stored_fwd_bytes = (uint64_t)((size_t)m * B + (size_t)m * k) * Ps;
+    mem.shared_fwd_bytes = (uint64_t)(2 * (size_t)b->cm + B) * Ps;
+  } else {
+    for (int l = 1; l <= m; ++l) {
+      b->off_u[l] = carve((size_t)c_in(d, l) * Ps, true);
+      b->off_a[l] = carve((size_t)c_in(d, l) * Ps, true);
+      b->off_a2[l] = carve((size_t)B * Ps, true);
+    }
+    mem.stored_fwd_bytes = (uint64_t)(2 * sigma_c + (size_t)m * (2 * B + k)) * Ps;
+    mem.shared_fwd_bytes = 0;
+  }
+  b->off_G = carve((size_t)cout * Ps, true);
+  b->off_dS2 = carve((size_t)b->cm * Ps, true);
+  b->off_dS3 = carve((size_t)B * Ps, true);
+  mem.grad_bytes = (uint64_t)((size_t)cout + b->cm + B) * Ps;
+  mem.peak_bytes = mem.stored_fwd_bytes + mem.shared_fwd_bytes + mem.grad_bytes;
+  // the x_l part of `stored` lives in the caller's y, everything else was carved above
+  if (fm_exact + (size_t)m * k * Ps != mem.peak_bytes) { delete b; return DNB_E_BADDESC; }
+
+  b->off_stat_y = carve((size_t)cout * 2 * sizeof(float), false);
+  for (int l = 1; l <= m; ++l) b->off_stat_b[l] = carve((size_t)B * 2 * sizeof(float), false);
+  mem.stats_bytes = (uint64_t)((size_t)cout * 2 + (size_t)m * B * 2) * sizeof(float);
+
+  size_t part = 0;
+  auto need = [&](size_t floats) { if (floats > part) part = floats; };
+  need(bn_stats_partial_floats(d.n, d.c0, (int)hw));
+  need(bn_stats_partial_floats(d.n, k, (int)hw));
+  need(bn_stats_partial_floats(d.n, B, (int)hw));
+  need(bn_bwd_partial_floats(d.n, B, (int)hw));
+  for (int l = 1; l <= m; ++l) {
+    need(bn_bwd_partial_floats(d.n, c_in(d, l), (int)hw));
+    need(conv_wgrad_partial_floats(d.n, c_in(d, l), B, d.h, d.w, 1));
+  }
+  need(conv_wgrad_partial_floats(d.n, B, k, d.h, d.w, 9));
+  mem.scratch_bytes = (uint64_t)part * sizeof(float);
+  b->off_part = carve(part * sizeof(float), false);
+  mem.workspace_bytes = (uint64_t)off;
+  *out = b;
+  return DNB_OK;
+}
+
+void dnb_block_destroy(dnb_block* b) { delete b; }
+
+size_t dnb_block_peak_bytes(const dnb_block* b) { return b ? (size_t)b->mem.peak_bytes : 0; }
+size_t dnb_block_workspace_bytes(const dnb_block* b) { return b ? (size_t)b->mem.workspace_bytes : 0; }
+
+int dnb_block_memory_breakdown(const dnb_block* b, dnb_block_memory* out) {
+  if (!b || !out) return DNB_E_NULL;
+  *out = b->mem;
+  return DNB_OK;
+}
+
+size_t dnb_block_param_count(const dnb_block* b) { return b ? b->pcount : 0; }
+
+int dnb_block_param_offset(const dnb_block* b, int layer, int which, size_t* offset, size_t* count) {
+  if (!b || !offset || !count) return DNB_E_NULL;
+  if (layer < 1 || layer > b->d.layers || which < DNB_P_G1 || which > DNB_P_W3) return DNB_E_RANGE;
+  const size_t c = (size_t)c_in(b->d, layer), B = (size_t)b->d.bottleneck, k = (size_t)b->d.growth;
+  size_t o = b->poff[layer], n = 0;
+  switch (which) {
+    case DNB_P_G1: n = c; break;
+    case DNB_P_B1: o += c; n = c; break;
+    case DNB_P_W1: o += 2 * c; n = B * c; break;
+    case DNB_P_G2: o += 2 * c + B * c; n = B; break;
+    case DNB_P_B2: o += 2 * c + B * c + B; n = B; break;
+    default: o += 2 * c + B * c + 2 * B; n = k * B * 9; break;
+  }
+  *offset = o;
+  *count = n;
+  return DNB_OK;
+}
+
+int dnb_block_forward(dnb_block* b, const void* x0v, const void* paramsv, void* yv, void* wsv,
+                      void* stream) {
+  if (!b || !x0v || !paramsv || !yv || !wsv) return DNB_E_NULL;
+  if (misaligned(x0v) || misaligned(paramsv) || misaligned(yv) || misaligned(wsv)) return DNB_E_ALIGN;
+  hipStream_t st = (hipStream_t)stream;
+  const dnb_block_desc& d = b->d;
+  const int n = d.n, m = d.layers, k = d.growth, B = d.bottleneck, hw = (int)b->hw;
+  const float* x0 = (const float*)x0v;
+  const float* params = (const float*)paramsv;
+  float* y = (float*)yv;
+  char* ws = (char*)wsv;
+  const int64_t ys = (int64_t)b->cout * hw;  // image stride of y
+  float* mean_y = (float*)(ws + b->off_stat_y);
+  float* istd_y = mean_y + b->cout;
+  float* part = (float*)(ws + b->off_part);
+
+  // y[:, 0:c0] = x0, and the statistics of those channels (every later layer reuses them:
+  // a channel's batch statistics do not depend on which layer consumes it)
+  DNB_TRY(launch_copy_slab(x0, (int64_t)d.c0 * hw, y, ys, n, (int64_t)d.c0 * hw, st));
+  DNB_TRY(launch_bn_stats(y, ys, n, d.c0, hw, d.eps, mean_y, istd_y, part, st));
+  for (int l = 1; l <= m; ++l) {
+    const int c = c_in(d, l);
+    const LayerParams p = layer_ptrs<LayerParams, const float>(b, params, l);
+    float* S1 = (float*)(ws + b->off_u[l]);
+    float* S2 = (float*)(ws + b->off_a[l]);
+    float* S3 = (float*)(ws + b->off_a2[l]);
+    float* bl = (float*)(ws + b->off_b[l]);
+    float* mean_b = (float*)(ws + b->off_stat_b[l]);
+    float* istd_b = mean_b + B;
+    // concat -> storage 1 and BN+ReLU -> storage 2, one pass over the features
+    DNB_TRY(launch_bn_relu(y, ys, S2, (int64_t)c * hw, S1, (int64_t)c * hw, n, c, hw, p.g1, p.b1,
+                           mean_y, istd_y, st));
+    DNB_TRY(launch_conv_igemm(S2, (int64_t)c * hw, WeightView{p.W1, c, 1, 0}, bl, (int64_t)B * hw, n,
+                              c, B, d.h, d.w, 1, st));
+    DNB_TRY(launch_bn_stats(bl, (int64_t)B * hw, n, B, hw, d.eps, mean_b, istd_b, part, st));
+    DNB_TRY(launch_bn_relu(bl, (int64_t)B * hw, S3, (int64_t)B * hw, nullptr, 0, n, B, hw, p.g2, p.b2,
+                           mean_b, istd_b, st));
+    float* xl = y + (int64_t)c * hw;  // x_l goes straight into its channel range of y
+    DNB_TRY(launch_conv_igemm(S3, (int64_t)B * hw, WeightView{p.W3, (int64_t)B * 9, 9, 0}, xl, ys, n,
+                              B, k, d.h, d.w, 9, st));
+    if (l < m)
+      DNB_TRY(launch_bn_stats(xl, ys, n, k, hw, d.eps, mean_y + c, istd_y + c, part, st));
+  }
+  return DNB_OK;
+}
+
+int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const void* dyv,
+                       void* dx0v, void* dparamsv, void* wsv, void* stream) {
+  if (!b || !paramsv || !yv || !dyv || !dx0v || !dparamsv || !wsv) return DNB_E_NULL;
+  if (misaligned(paramsv) || misaligned(yv) || misaligned(dyv) || misaligned(dx0v) ||
+      misaligned(dparamsv) || misaligned(wsv))
+    return DNB_E_ALIGN;
+  hipStream_t st = (hipStream_t)stream;
+  const dnb_block_desc& d = b->d;
+  const int n = d.n, m = d.layers, k = d.growth, B = d.bottleneck, hw = (int)b->hw;
+  const bool recompute = d.schedule == DNB_SCHED_SHARED;
+  const float* params = (const float*)paramsv;
+  const float* y = (const float*)yv;
+  float* dparams = (float*)dparamsv;
+  char* ws = (char*)wsv;
+  const int64_t ys = (int64_t)b->cout * hw;
+  float* mean_y = (float*)(ws + b->off_stat_y);
+  float* istd_y = mean_y + b->cout;
+  float* part = (float*)(ws + b->off_part);
+  float* G = (float*)(ws + b->off_G);      // gradient slab, same shape as y
+  float* dS2 = (float*)(ws + b->off_dS2);  // gradient of storage 2 (widest layer)
+  float* dS3 = (float*)(ws + b->off_dS3);  // gradient of storage 3, then of b_l
+
+  DNB_TRY(launch_copy_slab((const float*)dyv, ys, G, ys, n, ys, st));
+  for (int l = m; l >= 1; --l) {
+    const int c = c_in(d, l);
+    const LayerParams p = layer_ptrs<LayerParams, const float>(b, params, l);
+    const LayerGrads gp = layer_ptrs<LayerGrads, float>(b, dparams, l);
+    float* S1 = (float*)(ws + b->off_u[l]);
+    float* S2 = (float*)(ws + b->off_a[l]);
+    float* S3 = (float*)(ws + b->off_a2[l]);
+    float* bl = (float*)(ws + b->off_b[l]);
+    float* mean_b = (float*)(ws + b->off_stat_b[l]);
+    float* istd_b = mean_b + B;
+    float* gl = G + (int64_t)c * hw;  // complete gradient of x_l: all later layers have added theirs
+
+    if (recompute)  // re-populate storage 3 from the kept b_l and its cached statistics
+      DNB_TRY(launch_bn_relu(bl, (int64_t)B * hw, S3, (int64_t)B * hw, nullptr, 0, n, B, hw, p.g2,
+                             p.b2, mean_b, istd_b, st));
+    DNB_TRY(launch_conv_wgrad(S3, (int64_t)B * hw, gl, ys, gp.W3, n, B, k, d.h, d.w, 9, part, st));
+    DNB_TRY(launch_conv_igemm(gl, ys, WeightView{p.W3, 9, (int64_t)B * 9, 1}, dS3, (int64_t)B * hw, n,
+                              k, B, d.h, d.w, 9, st));
+    DNB_TRY(launch_bn_relu_bwd(bl, (int64_t)B * hw, dS3, (int64_t)B * hw, dS3, (int64_t)B * hw, false,
+                               n, B, hw, p.g2, p.b2, mean_b, istd_b, gp.g2, gp.b2, part, st));
+    if (recompute)  // re-populate storage 1 and 2 for this layer
+      DNB_TRY(launch_bn_relu(y, ys, S2, (int64_t)c * hw, S1, (int64_t)c * hw, n, c, hw, p.g1, p.b1,
+                             mean_y, istd_y, st));
+    DNB_TRY(launch_conv_wgrad(S2, (int64_t)c * hw, dS3, (int64_t)B * hw, gp.W1, n, c, B, d.h, d.w, 1,
+                              part, st));
+    DNB_TRY(launch_conv_igemm(dS3, (int64_t)B * hw, WeightView{p.W1, 1, c, 0}, dS2, (int64_t)c * hw, n,
+                              B, c, d.h, d.w, 1, st));
+    // BN1+ReLU backward, then concat backward: add the slice gradients into the slab
+    DNB_TRY(launch_bn_relu_bwd(S1, (int64_t)c * hw, dS2, (int64_t)c * hw, G, ys, true, n, c, hw, p.g1,
+                               p.b1, mean_y, istd_y, gp.g1, gp.b1, part, st));
+  }
+  DNB_TRY(launch_copy_slab(G, ys, (float*)dx0v, (int64_t)d.c0 * hw, n, (int64_t)d.c0 * hw, st));
+  return DNB_OK;
+}
+
+// ------------------------------------------------------------------ single operations
+
+int dnb_op_copy_slab(const void* src, int64_t src_stride, void* dst, int64_t dst_stride, int64_t n,
+                     int64_t len, void* stream) {
+  if (!src || !dst) return DNB_E_NULL;
+  if (n < 0 || len < 0 || n > 65535) return DNB_E_RANGE;
+  DNB_TRY(launch_copy_slab((const float*)src, src_stride, (float*)dst, dst_stride, (int)n, len,
+                           (hipStream_t)stream));
+  return DNB_OK;
+}
+
+size_t dnb_op_bn_scratch_bytes(int64_t n, int64_t c, int64_t hw) {
+  const size_t a = bn_stats_partial_floats((int)n, (int)c, (int)hw);
+  const size_t b = bn_bwd_partial_floats((int)n, (int)c, (int)hw);
+  return (a > b ? a : b) * sizeof(float);
+}
+
+int dnb_op_bn_stats(const void* x, int64_t stride, int64_t n, int64_t c, int64_t hw, float eps,
+                    void* mean, void* istd, void* scratch, void* stream) {
+  if (!x || !mean || !istd || !scratch) return DNB_E_NULL;
+  if (n < 1 || c < 1 || hw < 1 || c > 65535) return DNB_E_RANGE;
+  DNB_TRY(launch_bn_stats((const float*)x, stride, (int)n, (int)c, (int)hw, eps, (float*)mean,
+                          (float*)istd, (float*)scratch, (hipStream_t)stream));
+  return DNB_OK;
+}
+
+int dnb_op_bn_relu(const void* x, int64_t x_stride, void* out, int64_t out_stride, int64_t n,
+                   int64_t c, int64_t hw, const void* gamma, const void* beta, const void* mean,
+                   const void* istd, void* stream) {
+  if (!x || !out || !gamma || !beta || !mean || !istd) return DNB_E_NULL;
+  if (n < 1 || c < 1 || hw < 1) return DNB_E_RANGE;
+  DNB_TRY(launch_bn_relu((const float*)x, x_stride, (float*)out, out_stride, nullptr, 0, (int)n, (int)c,
+                         (int)hw, (const float*)gamma, (const float*)beta, (const float*)mean,
+                         (const float*)istd, (hipStream_t)stream));
+  return DNB_OK;
+}
+
+int dnb_op_bn_relu_backward(const void* x, int64_t x_stride, const void* dact, int64_t dact_stride,
+                            void* du, int64_t du_stride, int accumulate, int64_t n, int64_t c,
+                            int64_t hw, const void* gamma, const void* beta, const void* mean,
+                            const void* istd, void* dgamma, void* dbeta, void* scratch, void* stream) {
+  if (!x || !dact || !du || !gamma || !beta || !mean || !istd || !dgamma || !dbeta || !scratch)
+    return DNB_E_NULL;
+  if (n < 1 || c < 1 || hw < 1 || c > 65535) return DNB_E_RANGE;
+  DNB_TRY(launch_bn_relu_bwd((const float*)x, x_stride, (const float*)dact, dact_stride, (float*)du,
+                             du_stride, accumulate != 0, (int)n, (int)c, (int)hw, (const float*)gamma,
+                             (const float*)beta, (const float*)mean, (const float*)istd,
+                             (float*)dgamma, (float*)dbeta, (float*)scratch, (hipStream_t)stream));
+  return DNB_OK;
+}
+
+static int conv_args_ok(int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w, int ks) {
+  if (ks != 1 && ks != 3) return DNB_E_UNSUPPORTED;
+  if (n < 1 || cin < 1 || cout < 1 || h < 1 || w < 1 || n > 65535) return DNB_E_RANGE;
+  if (cin * h * w >= ((int64_t)1 << 31) || cout * h * w >= ((int64_t)1 << 31)) return DNB_E_RANGE;
+  return DNB_OK;
+}
+
+int dnb_op_conv_forward(const void* x, int64_t x_stride, const void* wgt, void* out,
+                        int64_t out_stride, int64_t n, int64_t cin, int64_t cout, int64_t h,
+                        int64_t w, int ks, void* stream) {
+  if (!x || !wgt || !out) return DNB_E_NULL;
+  const int rc = conv_args_ok(n, cin, cout, h, w, ks);
+  if (rc) return rc;
+  const int taps = ks * ks;
+  DNB_TRY(launch_conv_igemm((const float*)x, x_stride, WeightView{(const float*)wgt, cin * taps, taps, 0},
+                            (float*)out, out_stride, (int)n, (int)cin, (int)cout, (int)h, (int)w, taps,
+                            (hipStream_t)stream));
+  return DNB_OK;
+}
+
+int dnb_op_conv_dgrad(const void* dout, int64_t dout_stride, const void* wgt, void* din,
+                      int64_t din_stride, int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w,
+                      int ks, void* stream) {
+  if (!dout || !wgt || !din) return DNB_E_NULL;
+  const int rc = conv_args_ok(n, cin, cout, h, w, ks);
+  if (rc) return rc;
+  const int taps = ks * ks;
+  // the data gradient is a convolution of dout with the weights transposed and flipped
+  DNB_TRY(launch_conv_igemm((const float*)dout, dout_stride,
+                            WeightView{(const float*)wgt, taps, cin * taps, taps == 9 ? 1 : 0},
+                            (float*)din, din_stride, (int)n, (int)cout, (int)cin, (int)h, (int)w, taps,
+                            (hipStream_t)stream));
+  return DNB_OK;
+}
+
+size_t dnb_op_conv_wgrad_scratch_bytes(int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w,
+                                       int ks) {
+  if (conv_args_ok(n, cin, cout, h, w, ks)) return 0;
+  return conv_wgrad_partial_floats((int)n, (int)cin, (int)cout, (int)h, (int)w, ks * ks) * sizeof(float);
+}
+
+int dnb_op_conv_wgrad(const void* x, int64_t x_stride, const void* dout, int64_t dout_stride,
+                      void* dwgt, int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w, int ks,
+                      void* scratch, void* stream) {
+  if (!x || !dout || !dwgt || !scratch) return DNB_E_NULL;
+  const int rc = conv_args_ok(n, cin, cout, h, w, ks);
+  if (rc) return rc;
+  DNB_TRY(launch_conv_wgrad((const float*)x, x_stride, (const float*)dout, dout_stride, (float*)dwgt,
+                            (int)n, (int)cin, (int)cout, (int)h, (int)w, ks * ks, (float*)scratch,
+                            (hipStream_t)stream));
+  return DNB_OK;
+}
+
+}  // extern "C"

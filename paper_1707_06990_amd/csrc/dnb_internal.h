@@ -1,0 +1,64 @@
+// Internal declarations shared by the host orchestration and the kernel files of
+// the dense-block library (fp32 NCHW path).  Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dnb {
+
+// ---- element-wise and reduction kernels (HBM-bound) -------------------------------------
+
+// dst[i][0:len] = src[i][0:len] for i < n; strides in elements.
+hipError_t launch_copy_slab(const float* src, int64_t src_stride, float* dst, int64_t dst_stride,
+                            int n, int64_t len, hipStream_t st);
+
+// Per-channel batch statistics of x (n, c, hw; image stride `stride`).
+// `partials` needs bn_stats_partial_floats(n, c) floats of scratch.
+int bn_stats_splits(int n, int c, int hw);
+size_t bn_stats_partial_floats(int n, int c, int hw);
+hipError_t launch_bn_stats(const float* x, int64_t stride, int n, int c, int hw, float eps,
+                           float* mean, float* istd, float* partials, hipStream_t st);
+
+// out = max(0, fma(x, gamma*istd, beta - mean*gamma*istd)); if copy_out != nullptr the raw x
+// is also written there (concatenation and BN+ReLU of the same data in one pass).
+hipError_t launch_bn_relu(const float* x, int64_t x_stride, float* out, int64_t out_stride,
+                          float* copy_out, int64_t copy_stride, int n, int c, int hw,
+                          const float* gamma, const float* beta, const float* mean,
+                          const float* istd, hipStream_t st);
+
+// BN+ReLU backward.  Pass 1 reduces dbeta = sum dz, dgamma = sum dz*xhat with
+// dz = dact * [fma(x,scale,shift) > 0]; pass 2 writes
+// du = gamma*istd*(dz - dbeta/P - xhat*dgamma/P), overwriting or accumulating.
+// `partials` needs bn_bwd_partial_floats(n, c, hw) floats.
+size_t bn_bwd_partial_floats(int n, int c, int hw);
+hipError_t launch_bn_relu_bwd(const float* x, int64_t x_stride, const float* dact,
+                              int64_t dact_stride, float* du, int64_t du_stride, bool accumulate,
+                              int n, int c, int hw, const float* gamma, const float* beta,
+                              const float* mean, const float* istd, float* dgamma, float* dbeta,
+                              float* partials, hipStream_t st);
+
+// ---- convolutions (MFMA implicit GEMM, fp32) -----------------------------------------------
+
+// Weight addressing for the implicit-GEMM kernel: element (m = output channel, c = input
+// channel, t = tap) lives at w[m*sm + c*sc + (flip ? taps-1-t : t)].
+struct WeightView {
+  const float* w;
+  int64_t sm, sc;
+  int flip;
+};
+
+// out[n][m][q] = sum_{c,t} W(m,c,t) * in[n][c][q + shift(t)], zero outside the image.
+// taps = 1 or 9.  Used for forward (W = OIHW as is) and data gradient (transposed, flipped).
+hipError_t launch_conv_igemm(const float* in, int64_t in_stride, WeightView wv, float* out,
+                             int64_t out_stride, int n, int cin, int cout, int h, int w, int taps,
+                             hipStream_t st);
+
+// dW[m][c][t] = sum_{n,q} g[n][m][q] * in[n][c][q + shift(t)]  (OIHW result).
+int conv_wgrad_splits(int n, int cin, int cout, int h, int w, int taps);
+size_t conv_wgrad_partial_floats(int n, int cin, int cout, int h, int w, int taps);
+hipError_t launch_conv_wgrad(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
+                             float* dw, int n, int cin, int cout, int h, int w, int taps,
+                             float* partials, hipStream_t st);
+
+}  // namespace dnb

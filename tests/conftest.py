@@ -17,3 +17,17 @@ def oracle():
     from oracle import oracle as orc
     orc.build()
     return orc
+
+
+@pytest.fixture(scope="session")
+def dnb():
+    """The product binding.  Loads the in-tree library; builds it only if nothing is built."""
+    lib = os.path.join(ROOT, "paper_1707_06990_amd", "libdnb.so")
+    if not os.path.exists(lib):
+        import importlib.util
+        spec = importlib.util.spec_from_file_location("_dnb_build", os.path.join(ROOT, "paper_1707_06990_amd", "build.py"))
+        mod = importlib.util.module_from_spec(spec)
+        spec.loader.exec_module(mod)
+        mod.build()
+    import paper_1707_06990_amd as d
+    return d

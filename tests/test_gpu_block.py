@@ -1,0 +1,98 @@
+"""GPU parity of the dense block (forward + backward through the C ABI) against the
+float64 CPU oracle on the same seeded inputs: outputs, input gradient and every
+parameter gradient; both schedules; bit-equality of the two schedules; byte accounting."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_util import NAMES, assert_close, rel_errors, run_block_gpu, run_block_oracle
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4  # fp32 (the benchmark spec): relative error vs the float64 oracle, L2 and max-abs/max
+
+CFGS = [
+    wl.config1(),                               # the stated small configuration
+    wl.BlockCfg(3, 5, 5, 7, 3, 4, 6),           # nothing a multiple of 4 or 16: scalar paths, ragged tiles
+    wl.BlockCfg(1, 7, 3, 3, 5, 3, 6),
+    wl.BlockCfg(1, 1, 1, 1, 1, 1, 1),           # degenerate: one pixel, one channel, one layer
+    wl.BlockCfg(2, 24, 32, 32, 3, 12, 48),      # first layers of the CIFAR-shaped net at small batch
+    wl.BlockCfg(4, 150, 8, 8, 4, 12, 48),       # deep-layer widths of its last block
+    wl.BlockCfg(2, 48, 16, 16, 3, 24, 96),      # k = 24, B = 96
+]
+IDS = [f"n{c.n}c{c.c0}h{c.h}w{c.w}m{c.layers}k{c.growth}B{c.bottleneck}" for c in CFGS]
+
+
+def compare(gpu, ores, oslices, cfg, tol=TOL):
+    assert_close(gpu["y"], ores.y, tol, "y")
+    assert_close(gpu["dx0"], ores.dx0, tol, "dx0")
+    for l in range(1, cfg.layers + 1):
+        for name in NAMES:
+            a = gpu["dparams"][gpu["slices"][(l, name)]]
+            r = ores.dparams[oslices[(l, name)]]
+            if cfg.pixels == 1 and name in ("g1", "g2", "W1", "W3", "b1"):
+                # one pixel: xhat = 0 everywhere, these gradients are 0 up to rounding noise
+                assert np.all(np.abs(a - r) <= 1e-5), (l, name)
+                continue
+            assert_close(a, r, tol, f"layer {l} d{name}")
+
+
+@pytest.mark.parametrize("cfg", CFGS, ids=IDS)
+@pytest.mark.parametrize("schedule", [0, 1])
+def test_block_matches_oracle(dnb, oracle, cfg, schedule):
+    x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
+    gpu = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=schedule)
+    ores, osl = run_block_oracle(oracle, cfg, x0, lp, dy)
+    compare(gpu, ores, osl, cfg)
+
+
+def test_config1_exact_recipe(dnb, oracle):
+    """The stated small configuration with its own recipe: gamma = 1, beta = 0, seeds 0/1/2."""
+    cfg = wl.config1()
+    x0, lp, dy = wl.make_block_inputs(cfg, 0, 1, 2, affine="ones")
+    gpu = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=0)
+    ores, osl = run_block_oracle(oracle, cfg, x0, lp, dy)
+    compare(gpu, ores, osl, cfg)
+    assert gpu["peak"] == 284672
+
+
+@pytest.mark.parametrize("cfg", CFGS, ids=IDS)
+def test_schedules_bit_identical(dnb, cfg):
+    """Recomputation only re-populates buffers: the shared schedule returns exactly the
+    store-everything schedule's bits (cached statistics, atomic-free reductions)."""
+    x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
+    a = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=0)
+    b = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=1)
+    for key in ("y", "dx0", "dparams"):
+        assert np.array_equal(a[key], b[key]), key
+    assert a["peak"] < b["peak"] or cfg.layers == 1
+
+
+def test_repeated_calls_are_deterministic_and_reuse_workspace(dnb):
+    cfg = CFGS[0]
+    x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
+    a = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=0)
+    b = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=0, poison=False)
+    for key in ("y", "dx0", "dparams"):
+        assert np.array_equal(a[key], b[key]), key
+
+
+def test_output_starts_with_input_and_first_bn_is_normalised(dnb):
+    """y[:, :c0] is x0 bit for bit; the cached statistics normalise every concatenated
+    channel: pre-affine mean ~ 0 and variance ~ v/(v+eps) (BN invariant on GPU output)."""
+    cfg = CFGS[4]
+    x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
+    gpu = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=0)
+    y = gpu["y"].astype(np.float64)
+    assert np.array_equal(gpu["y"][:, :cfg.c0], x0)
+    n, c, h, w = y.shape
+    x = torch.from_numpy(gpu["y"]).cuda()
+    mean = torch.empty(c, device="cuda")
+    istd = torch.empty(c, device="cuda")
+    scratch = torch.empty(dnb.dnb_op_bn_scratch_bytes(n, c, h * w), dtype=torch.uint8, device="cuda")
+    dnb.dnb_op_bn_stats(x, c * h * w, n, c, h * w, cfg.eps, mean, istd, scratch)
+    torch.cuda.synchronize()
+    xhat = (y - mean.cpu().numpy().astype(np.float64)[None, :, None, None]) * istd.cpu().numpy().astype(np.float64)[None, :, None, None]
+    v = y.var(axis=(0, 2, 3))
+    assert np.max(np.abs(xhat.mean(axis=(0, 2, 3)))) < 1e-5
+    np.testing.assert_allclose(xhat.var(axis=(0, 2, 3)), v / (v + cfg.eps), rtol=1e-4)

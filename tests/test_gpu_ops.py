@@ -1,0 +1,166 @@
+"""GPU parity of the single operations (through the C ABI) against the CPU oracle,
+element by element, on seeded inputs whose shapes span several tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import assert_close, dev
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4  # fp32 path vs float64 oracle, relative (L2 and max-abs/max)
+
+
+def rng(seed):
+    return np.random.default_rng(seed)
+
+
+def f32(a):
+    return np.asarray(a, dtype=np.float32)
+
+
+@pytest.mark.parametrize("n,len_,sstride,dstride", [(3, 40, 40, 72), (2, 37, 50, 37), (5, 4096, 8192, 4096), (1, 1, 1, 1)])
+def test_copy_slab(dnb, n, len_, sstride, dstride):
+    src = f32(rng(1).standard_normal((n, sstride)))
+    d_src = dev(src)
+    d_dst = torch.full((n, dstride), -7.0, device="cuda")
+    dnb.dnb_op_copy_slab(d_src, sstride, d_dst, dstride, n, len_)
+    torch.cuda.synchronize()
+    out = d_dst.cpu().numpy()
+    np.testing.assert_array_equal(out[:, :len_], src[:, :len_])
+    assert np.all(out[:, len_:] == -7.0)
+
+
+BN_SHAPES = [(2, 16, 8, 8), (3, 5, 7, 9), (64, 12, 4, 4), (2, 70, 16, 16), (1, 3, 1, 1), (5, 9, 3, 2)]
+
+
+def bn_stats_gpu(dnb, x, eps):
+    n, c, h, w = x.shape
+    d_x = dev(x)
+    mean = torch.empty(c, device="cuda")
+    istd = torch.empty(c, device="cuda")
+    scratch = torch.empty(dnb.dnb_op_bn_scratch_bytes(n, c, h * w), dtype=torch.uint8, device="cuda")
+    dnb.dnb_op_bn_stats(d_x, c * h * w, n, c, h * w, eps, mean, istd, scratch)
+    torch.cuda.synchronize()
+    return d_x, mean, istd, scratch
+
+
+@pytest.mark.parametrize("shape", BN_SHAPES)
+def test_bn_stats_and_apply(dnb, oracle, shape):
+    r = rng(2)
+    n, c, h, w = shape
+    x = f32(r.standard_normal(shape) * r.uniform(0.2, 4, (1, c, 1, 1)) + r.uniform(-2, 2, (1, c, 1, 1)))
+    gamma, beta = f32(1 + 0.3 * r.standard_normal(c)), f32(0.3 * r.standard_normal(c))
+    eps = 1e-5
+    d_x, mean, istd, _ = bn_stats_gpu(dnb, x, eps)
+    z, omean, ovar = oracle.bn_forward(x, gamma, beta, eps)
+    assert_close(mean.cpu().numpy(), omean, TOL, "mean")
+    assert_close(istd.cpu().numpy(), 1 / np.sqrt(ovar + eps), TOL, "istd")
+    out = torch.full(shape, float("nan"), device="cuda")
+    dnb.dnb_op_bn_relu(d_x, c * h * w, out, c * h * w, n, c, h * w, dev(gamma), dev(beta), mean, istd)
+    torch.cuda.synchronize()
+    assert_close(out.cpu().numpy(), oracle.relu(z), TOL, "bn+relu")
+
+
+def test_bn_stats_large_offset_channel(dnb, oracle):
+    """|mean| >> std: a one-pass E[x^2]-E[x]^2 in fp32 would lose the variance."""
+    r = rng(3)
+    x = f32(1000.0 + 0.5 * r.standard_normal((8, 4, 16, 16)))
+    _, mean, istd, _ = bn_stats_gpu(dnb, x, 1e-5)
+    _, omean, ovar = oracle.bn_forward(x, np.ones(4), np.zeros(4), 1e-5)
+    assert_close(istd.cpu().numpy(), 1 / np.sqrt(ovar + 1e-5), 1e-3, "istd")
+
+
+@pytest.mark.parametrize("shape", BN_SHAPES)
+@pytest.mark.parametrize("accumulate", [0, 1])
+def test_bn_relu_backward(dnb, oracle, shape, accumulate):
+    r = rng(4)
+    n, c, h, w = shape
+    x = f32(r.standard_normal(shape) * 1.5 + 0.3)
+    gamma, beta = f32(1 + 0.3 * r.standard_normal(c)), f32(0.3 * r.standard_normal(c))
+    dact = f32(r.standard_normal(shape))
+    base = f32(r.standard_normal(shape))
+    eps = 1e-5
+    d_x, mean, istd, scratch = bn_stats_gpu(dnb, x, eps)
+    du = dev(base.copy())
+    dg = torch.empty(c, device="cuda")
+    db = torch.empty(c, device="cuda")
+    hw = h * w
+    dnb.dnb_op_bn_relu_backward(d_x, c * hw, dev(dact), c * hw, du, c * hw, accumulate, n, c, hw, dev(gamma),
+                                dev(beta), mean, istd, dg, db, scratch)
+    torch.cuda.synchronize()
+    z, omean, ovar = oracle.bn_forward(x, gamma, beta, eps)
+    dz = oracle.relu_backward(oracle.relu(z), dact)
+    odu, odg, odb = oracle.bn_backward(x, dz, gamma, omean, ovar, eps)
+    if accumulate:
+        odu = odu + base
+    if n * hw > 1:
+        assert_close(du.cpu().numpy(), odu, TOL, "du")
+        assert_close(dg.cpu().numpy(), odg, TOL, "dgamma")
+    assert_close(db.cpu().numpy(), odb, TOL, "dbeta")
+
+
+def test_bn_relu_backward_in_place(dnb, oracle):
+    """du may alias dact (the block overwrites the gradient of storage 3 with that of b_l)."""
+    r = rng(5)
+    shape = (4, 48, 8, 8)
+    n, c, h, w = shape
+    x, dact = f32(r.standard_normal(shape)), f32(r.standard_normal(shape))
+    gamma, beta = f32(1 + 0.3 * r.standard_normal(c)), f32(0.3 * r.standard_normal(c))
+    d_x, mean, istd, scratch = bn_stats_gpu(dnb, x, 1e-5)
+    buf = dev(dact.copy())
+    dg, db = torch.empty(c, device="cuda"), torch.empty(c, device="cuda")
+    dnb.dnb_op_bn_relu_backward(d_x, c * 64, buf, c * 64, buf, c * 64, 0, n, c, 64, dev(gamma), dev(beta), mean,
+                                istd, dg, db, scratch)
+    torch.cuda.synchronize()
+    z, omean, ovar = oracle.bn_forward(x, gamma, beta, 1e-5)
+    odu, _, _ = oracle.bn_backward(x, oracle.relu_backward(oracle.relu(z), dact), gamma, omean, ovar, 1e-5)
+    assert_close(buf.cpu().numpy(), odu, TOL, "du in place")
+
+
+CONV_SHAPES = [
+    # n, cin, cout, h, w, ks
+    (2, 16, 48, 8, 8, 1), (2, 48, 12, 8, 8, 3),      # the small block's two convs
+    (3, 20, 12, 9, 7, 3), (1, 5, 3, 1, 1, 3), (2, 7, 5, 2, 3, 3), (1, 17, 33, 5, 5, 1),
+    (2, 52, 48, 32, 32, 1), (2, 48, 12, 32, 32, 3), (2, 96, 24, 16, 16, 3),
+    (1, 70, 100, 6, 6, 1), (2, 9, 200, 5, 4, 1), (1, 12, 48, 11, 13, 3), (4, 30, 64, 7, 7, 3),
+]
+
+
+@pytest.mark.parametrize("n,cin,cout,h,w,ks", CONV_SHAPES)
+def test_conv_forward_dgrad_wgrad(dnb, oracle, n, cin, cout, h, w, ks):
+    r = rng(6)
+    x = f32(r.standard_normal((n, cin, h, w)))
+    wgt = f32(r.standard_normal((cout, cin, ks, ks)) * np.sqrt(2.0 / (cin * ks * ks)))
+    g = f32(r.standard_normal((n, cout, h, w)))
+    hw = h * w
+    d_x, d_w, d_g = dev(x), dev(wgt), dev(g)
+    out = torch.full((n, cout, h, w), float("nan"), device="cuda")
+    dnb.dnb_op_conv_forward(d_x, cin * hw, d_w, out, cout * hw, n, cin, cout, h, w, ks)
+    din = torch.full((n, cin, h, w), float("nan"), device="cuda")
+    dnb.dnb_op_conv_dgrad(d_g, cout * hw, d_w, din, cin * hw, n, cin, cout, h, w, ks)
+    dw = torch.full(wgt.shape, float("nan"), device="cuda")
+    scratch = torch.empty(max(16, dnb.dnb_op_conv_wgrad_scratch_bytes(n, cin, cout, h, w, ks)), dtype=torch.uint8, device="cuda")
+    dnb.dnb_op_conv_wgrad(d_x, cin * hw, d_g, cout * hw, dw, n, cin, cout, h, w, ks, scratch)
+    torch.cuda.synchronize()
+    assert_close(out.cpu().numpy(), oracle.conv_forward(x, wgt), TOL, "forward")
+    assert_close(din.cpu().numpy(), oracle.conv_dgrad(g, wgt), TOL, "dgrad")
+    assert_close(dw.cpu().numpy(), oracle.conv_wgrad(x, g, ks), TOL, "wgrad")
+
+
+def test_conv_on_channel_slices_of_wider_slabs(dnb, oracle):
+    """Input and output addressed in place inside wider tensors (explicit image strides),
+    as the block does with the output slab y and the gradient slab."""
+    r = rng(7)
+    n, cin, cout, h, w = 3, 24, 12, 8, 8
+    hw = h * w
+    wide_in = f32(r.standard_normal((n, cin + 10, h, w)))
+    wgt = f32(r.standard_normal((cout, cin, 3, 3)) * 0.1)
+    d_in = dev(wide_in)
+    wide_out = torch.full((n, 40, h, w), -3.0, device="cuda")
+    x_view = d_in.data_ptr() + 4 * 4 * hw          # channels 4..4+cin
+    o_view = wide_out.data_ptr() + 4 * 20 * hw     # channels 20..32
+    dnb.dnb_op_conv_forward(x_view, (cin + 10) * hw, dev(wgt), o_view, 40 * hw, n, cin, cout, h, w, 3)
+    torch.cuda.synchronize()
+    res = wide_out.cpu().numpy()
+    assert_close(res[:, 20:32], oracle.conv_forward(wide_in[:, 4:4 + cin], wgt), TOL, "slice conv")
+    assert np.all(res[:, :20] == -3.0) and np.all(res[:, 32:] == -3.0)

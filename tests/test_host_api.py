@@ -1,0 +1,138 @@
+"""CPU-side checks of the C-ABI library: it loads, exports everything include/dnb.h
+declares, validates descriptors, and its byte accounting and parameter-pack offsets
+agree with the oracle's independent counts.  No kernel is launched here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "dnb.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(dnb_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(dnb):
+    names = declared_functions()
+    assert "dnb_block_create" in names and "dnb_block_forward" in names
+    assert "dnb_block_backward" in names and "dnb_block_peak_bytes" in names
+    lib = ctypes.CDLL(dnb.binding.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(dnb.EXPORTED) == set(names)
+
+
+def test_status_strings(dnb):
+    assert dnb.dnb_status_string(0) == "ok"
+    for code in range(-7, 0):
+        assert dnb.dnb_status_string(code) not in ("ok", "unknown status")
+    assert dnb.dnb_status_string(-99) == "unknown status"
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(n=0), -1), (dict(c0=0), -1), (dict(layers=0), -1), (dict(growth=0), -1), (dict(bottleneck=0), -1),
+    (dict(h=-1), -1), (dict(eps=-1.0), -1), (dict(dtype=7), -1), (dict(layout=3), -1), (dict(schedule=9), -1),
+    (dict(dtype=1), -5), (dict(layout=1), -5), (dict(n=4096, h=512, w=512), -6)])
+def test_descriptor_validation(dnb, kw, code):
+    base = dict(n=2, c0=16, h=8, w=8, layers=4, growth=12, bottleneck=48)
+    base.update(kw)
+    with pytest.raises(dnb.binding.DnbError) as e:
+        dnb.dnb_block_create(**base)
+    assert e.value.status == code
+
+
+def test_null_arguments_are_errors(dnb):
+    lib = ctypes.CDLL(dnb.binding.LIB_PATH)
+    assert lib.dnb_block_create(None, None) == -2
+    h = dnb.dnb_block_create(2, 16, 8, 8, 4, 12, 48)
+    lib.dnb_block_forward.argtypes = [ctypes.c_void_p] * 6
+    assert lib.dnb_block_forward(h, None, None, None, None, None) == -2
+    assert lib.dnb_block_forward(h, 256, 256, 264, 256, None) == -3  # misaligned y
+    dnb.dnb_block_destroy(h)
+
+
+def sigma_c(cfg):
+    return sum(cfg.c_in(l) for l in range(1, cfg.layers + 1))
+
+
+CFGS = [wl.config1(), wl.BlockCfg(3, 5, 5, 7, 3, 4, 6), wl.BlockCfg(1, 7, 3, 3, 5, 3, 6)] + wl.config2() + wl.config3()
+
+
+@pytest.mark.parametrize("cfg", CFGS, ids=lambda c: f"{c.n}x{c.c0}x{c.h}x{c.w}-m{c.layers}k{c.growth}")
+def test_peak_bytes_formula(dnb, cfg):
+    """Linear-memory formula (shared) and quadratic one (store-all), in bytes."""
+    Ps, m, k, B = cfg.pixels * 4, cfg.layers, cfg.growth, cfg.bottleneck
+    cm, cout = cfg.c_in(m), cfg.c_out
+    grad = (cout + cm + B) * Ps
+    hs = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, m, k, B, schedule=0)
+    ha = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, m, k, B, schedule=1)
+    ms, ma = dnb.dnb_block_memory_breakdown(hs), dnb.dnb_block_memory_breakdown(ha)
+    assert ms["stored_fwd_bytes"] == (m * B + m * k) * Ps
+    assert ms["shared_fwd_bytes"] == (2 * cm + B) * Ps
+    assert ms["grad_bytes"] == grad == ma["grad_bytes"]
+    assert ma["stored_fwd_bytes"] == (2 * sigma_c(cfg) + m * (2 * B + k)) * Ps
+    assert ma["shared_fwd_bytes"] == 0
+    for h, mm in ((hs, ms), (ha, ma)):
+        assert dnb.dnb_block_peak_bytes(h) == mm["peak_bytes"] == mm["stored_fwd_bytes"] + mm["shared_fwd_bytes"] + mm["grad_bytes"]
+        # the workspace holds the feature maps (all but the x_l inside y), statistics, scratch, padding
+        lo = mm["peak_bytes"] - m * k * Ps + mm["stats_bytes"] + mm["scratch_bytes"]
+        assert lo <= mm["workspace_bytes"] == dnb.dnb_block_workspace_bytes(h) <= lo + 256 * (6 * m + 16)
+        dnb.dnb_block_destroy(h)
+
+
+def test_config1_bytes_as_stated(dnb):
+    h = dnb.dnb_block_create(2, 16, 8, 8, 4, 12, 48, schedule=0)
+    assert dnb.dnb_block_peak_bytes(h) == 284672
+    h1 = dnb.dnb_block_create(2, 16, 8, 8, 4, 12, 48, schedule=1)
+    assert dnb.dnb_block_peak_bytes(h1) == 444416
+
+
+@pytest.mark.parametrize("cfg", CFGS[:3])
+def test_peak_bytes_match_oracle_allocation_count(dnb, oracle, cfg):
+    """The library's formula against the elements the oracle's two schedules actually
+    allocate (counted by its allocator), times the element size."""
+    x0, lp, dy = wl.make_block_inputs(cfg)
+    s = oracle.BlockShape(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck, cfg.eps)
+    params = np.zeros(oracle.param_count(s))
+    for sched, name in ((0, "shared"), (1, "naive")):
+        h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck, schedule=sched)
+        res = oracle.block(s, x0, params, dy, schedule=name)
+        assert dnb.dnb_block_peak_bytes(h) == res.peak_elems * 4
+        assert dnb.dnb_block_memory_breakdown(h)["stored_fwd_bytes"] + dnb.dnb_block_memory_breakdown(h)["shared_fwd_bytes"] == res.stored_elems * 4
+        dnb.dnb_block_destroy(h)
+
+
+@pytest.mark.parametrize("cfg", CFGS[:3])
+def test_param_offsets_match_oracle(dnb, oracle, cfg):
+    s = oracle.BlockShape(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck, cfg.eps)
+    h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck)
+    assert dnb.dnb_block_param_count(h) == oracle.param_count(s)
+    for l in range(1, cfg.layers + 1):
+        for which in range(6):
+            off, cnt = dnb.dnb_block_param_offset(h, l, which)
+            sl = oracle.param_slice(s, l, which)
+            assert (off, off + cnt) == (sl.start, sl.stop)
+    with pytest.raises(dnb.binding.DnbError):
+        dnb.dnb_block_param_offset(h, cfg.layers + 1, 0)
+    dnb.dnb_block_destroy(h)
+
+
+def test_memory_is_linear_in_depth_for_shared_schedule(dnb):
+    peaks = {0: [], 1: []}
+    for m in (8, 16, 24, 32):
+        for sched in (0, 1):
+            h = dnb.dnb_block_create(64, 24, 32, 32, m, 12, 48, schedule=sched)
+            peaks[sched].append(dnb.dnb_block_peak_bytes(h))
+            dnb.dnb_block_destroy(h)
+    d2 = lambda v: [v[i + 2] - 2 * v[i + 1] + v[i] for i in range(len(v) - 2)]
+    assert all(x == 0 for x in d2(peaks[0]))
+    assert all(x > 0 for x in d2(peaks[1]))
