@@ -1,0 +1,230 @@
+#!/usr/bin/env python3
+"""Benchmark of the dense-block hot path on one MI355X.
+
+A step = forward + backward of every dense block of the workload (default: the three
+dense blocks of DenseNet-BC L=100, k=12, batch 64, fp32 -- benchmark configs[1]) through
+the C ABI, shared-storage schedule, inputs resident in HBM.  Prints ONE JSON line with
+training images/s, the roofline of the dominant kernel measured live with events on the
+launch stream, the store-everything schedule's rate (recompute overhead), exact peak
+feature-map bytes, and the CPU oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+MFMA_F32_PEAK_TF = 157.3    # MI355X dense fp32 matrix
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3"])
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
+    ap.add_argument("--schedule", default="shared", choices=["shared", "store_all"])
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-compare", action="store_true", help="skip timing the other schedule")
+    return ap.parse_args()
+
+
+def workload_blocks(wl, name, batch):
+    if name == "config1":
+        return [wl.config1()], "dense block n2 c16 8x8 m4 k12 B48 fp32 NCHW"
+    if name == "config2":
+        b = batch or 64
+        return wl.config2(b), f"DenseNet-BC L=100 k=12 batch {b} fp32 NCHW, 3 dense blocks x 16 layers (fwd+bwd)"
+    b = batch or 64
+    return wl.config3(b), f"DenseNet-BC L=250 k=24 batch {b} fp32 NCHW, 3 dense blocks x 41 layers (fwd+bwd)"
+
+
+class BlockRun:
+    """Device buffers + handle of one dense block."""
+
+    def __init__(self, dnb, torch, wl, cfg, schedule, seed):
+        from gpu_util import dev, pack_params_gpu
+        self.cfg = cfg
+        self.h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck,
+                                      schedule=schedule, eps=cfg.eps)
+        x0, lp, dy = wl.make_block_inputs(cfg, seed, seed + 1, seed + 2, affine="ones")
+        self.x0, self.dy = dev(x0), dev(dy)
+        self.params = dev(pack_params_gpu(dnb, self.h, lp))
+        self.dparams = torch.empty_like(self.params)
+        self.y = torch.empty((cfg.n, cfg.c_out, cfg.h, cfg.w), dtype=torch.float32, device="cuda")
+        self.dx0 = torch.empty_like(self.x0)
+        self.ws = torch.empty(dnb.dnb_block_workspace_bytes(self.h), dtype=torch.uint8, device="cuda")
+        self.mem = dnb.dnb_block_memory_breakdown(self.h)
+
+
+def make_step(dnb, runs):
+    def step():
+        for r in runs:
+            dnb.dnb_block_forward(r.h, r.x0, r.params, r.y, r.ws)
+        for r in reversed(runs):
+            dnb.dnb_block_backward(r.h, r.params, r.y, r.dy, r.dx0, r.dparams, r.ws)
+    return step
+
+
+def time_steps(torch, step, steps, warmup, use_graph):
+    """Returns (seconds for `steps` steps, whether a graph was used)."""
+    if use_graph:
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            step()
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            step()
+        run = g.replay
+    else:
+        run = step
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        run()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+def event_time_ms(torch, fn, reps):
+    """Average milliseconds of fn() (one or more launches on the current stream) over reps."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    fn()
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def dominant_kernel_roofline(dnb, torch, runs):
+    """Live measurement of the kernel that takes the largest share of the step (per the
+    committed rocprofv3 summary): the BN+ReLU backward apply pass of the first BN, which reads
+    the layer input, the incoming gradient and the gradient slab and writes the slab
+    (4 * C_l * P * 4 bytes).  Replayed per layer shape of the largest block via the
+    single-op entry point, timed with events on the launch stream."""
+    r = runs[0]
+    cfg = r.cfg
+    hw, n = cfg.h * cfg.w, cfg.n
+    cm = cfg.c_in(cfg.layers)
+    x = torch.randn((n, cm, cfg.h, cfg.w), device="cuda")
+    dact = torch.randn_like(x)
+    G = torch.zeros((n, cfg.c_out, cfg.h, cfg.w), device="cuda")
+    gamma, beta = torch.ones(cm, device="cuda"), torch.zeros(cm, device="cuda")
+    mean, istd = torch.zeros(cm, device="cuda"), torch.ones(cm, device="cuda")
+    dg, db = torch.empty(cm, device="cuda"), torch.empty(cm, device="cuda")
+    scratch = torch.empty(dnb.dnb_op_bn_scratch_bytes(n, cm, hw), dtype=torch.uint8, device="cuda")
+    total_bytes, launches = 0, 0
+
+    def all_layers():
+        for l in range(1, cfg.layers + 1):
+            c = cfg.c_in(l)
+            dnb.dnb_op_bn_relu_backward(x, c * hw, dact, c * hw, G, cfg.c_out * hw, 1, n, c, hw, gamma, beta,
+                                        mean, istd, dg, db, scratch)
+    for l in range(1, cfg.layers + 1):
+        # reduce pass: read x and dact (2 C P); apply pass: read x, dact, G and write G (4 C P)
+        total_bytes += 6 * cfg.c_in(l) * n * hw * 4
+        launches += 1
+    ms = event_time_ms(torch, all_layers, 10)
+    achieved = total_bytes / (ms * 1e-3) / 1e9
+    return {"bound": "hbm", "kernel": "bn_relu_backward (reduce + apply, first BN, block 1 layer shapes)",
+            "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+            "avg_launch_ms": round(ms / launches, 5), "algorithmic_bytes_per_launch": total_bytes // launches}
+
+
+def cpu_baseline(wl, blocks):
+    """The oracle as it stands, on the host cores, same workload shapes (full batch when it
+    finishes in tens of seconds, else a bounded number of images: cost per image is
+    batch independent for its naive loops)."""
+    from gpu_util import run_block_oracle
+    from oracle import oracle as orc
+    batch = blocks[0].n
+    flops_per_img = sum(6 * c.h * c.w * sum(c.c_in(l) * c.bottleneck + 9 * c.bottleneck * c.growth
+                                            for l in range(1, c.layers + 1)) for c in blocks)
+    sample = max(1, min(batch, int(400e9 // max(flops_per_img, 1))))
+    t, passes = 0.0, 0
+    inputs = []
+    for c in blocks:
+        cs = wl.BlockCfg(sample, c.c0, c.h, c.w, c.layers, c.growth, c.bottleneck, c.eps)
+        inputs.append((cs,) + tuple(wl.make_block_inputs(cs)))
+    while t < 10.0 and passes < 20:  # about 10-30 s of CPU work
+        for cs, x0, lp, dy in inputs:
+            t0 = time.perf_counter()
+            run_block_oracle(orc, cs, x0, lp, dy)
+            t += time.perf_counter() - t0
+        passes += 1
+    sample_total = sample * passes
+    return {"value": round(sample_total / t, 3), "unit": "images/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"{passes} pass(es) of {sample} of {batch} images through the same {len(blocks)} dense blocks "
+                      f"(float64, store-everything schedule, fwd+bwd), {t:.1f} s"}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_1707_06990_amd as dnb
+    import workloads as wl
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    blocks, wname = workload_blocks(wl, a.workload, a.batch)
+    batch = blocks[0].n
+    sched = {"shared": dnb.DNB_SCHED_SHARED, "store_all": dnb.DNB_SCHED_STORE_ALL}
+    use_graph = not a.no_graph
+
+    def measure(schedule):
+        runs = [BlockRun(dnb, torch, wl, c, sched[schedule], 10 * i) for i, c in enumerate(blocks)]
+        secs = time_steps(torch, make_step(dnb, runs), a.steps, a.warmup, use_graph)
+        return runs, secs
+
+    runs, secs = measure(a.schedule)
+    value = batch * a.steps / secs
+    out = {
+        "metric": "train images/sec per MI355X (fwd+bwd) + peak feature-map bytes vs depth",
+        "value": round(value, 2), "unit": "images/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(1e3 * secs / a.steps, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wname, "schedule": a.schedule, "launch": "hip_graph" if use_graph else "eager",
+                   "global_batch": batch},
+        "peak_feature_map_bytes": {"per_block": [r.mem["peak_bytes"] for r in runs],
+                                   "total": sum(r.mem["peak_bytes"] for r in runs),
+                                   "workspace_total": sum(r.mem["workspace_bytes"] for r in runs)},
+    }
+    out["roofline"] = dominant_kernel_roofline(dnb, torch, runs)
+    del runs
+    torch.cuda.empty_cache()
+    if not a.no_compare:
+        other = "store_all" if a.schedule == "shared" else "shared"
+        oruns, osecs = measure(other)
+        t_shared, t_all = (secs, osecs) if a.schedule == "shared" else (osecs, secs)
+        out["store_all_images_per_s" if other == "store_all" else "shared_images_per_s"] = round(batch * a.steps / osecs, 2)
+        out["recompute_overhead"] = round(t_shared / t_all - 1.0, 4)
+        out["peak_feature_map_bytes"][other + "_total"] = sum(r.mem["peak_bytes"] for r in oruns)
+        del oruns
+        torch.cuda.empty_cache()
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, blocks)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

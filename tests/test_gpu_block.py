@@ -96,3 +96,43 @@ def test_output_starts_with_input_and_first_bn_is_normalised(dnb):
     v = y.var(axis=(0, 2, 3))
     assert np.max(np.abs(xhat.mean(axis=(0, 2, 3)))) < 1e-5
     np.testing.assert_allclose(xhat.var(axis=(0, 2, 3)), v / (v + cfg.eps), rtol=1e-4)
+
+
+def test_hip_graph_replays_match_eager(dnb):
+    """The block's launch sequence captured in a HIP graph (as the benchmark does): every
+    replay, with eager work and synchronisation in between, reproduces the eager bits."""
+    from gpu_util import dev, pack_params_gpu
+    cfg = CFGS[4]
+    x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
+    eager = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=0)
+    h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck, schedule=0)
+    params = dev(pack_params_gpu(dnb, h, lp))
+    ws = torch.zeros(dnb.dnb_block_workspace_bytes(h), dtype=torch.uint8, device="cuda")
+    y = torch.zeros((cfg.n, cfg.c_out, cfg.h, cfg.w), device="cuda")
+    dx0 = torch.zeros((cfg.n, cfg.c0, cfg.h, cfg.w), device="cuda")
+    dparams = torch.zeros_like(params)
+    x0d, dyd = dev(x0), dev(dy)
+
+    def step():
+        dnb.dnb_block_forward(h, x0d, params, y, ws)
+        dnb.dnb_block_backward(h, params, y, dyd, dx0, dparams, ws)
+
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        step()
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep in range(4):
+        y.fill_(float("nan")); dx0.fill_(float("nan")); dparams.fill_(float("nan")); ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy(), eager["y"]), rep
+        assert np.array_equal(dx0.cpu().numpy(), eager["dx0"]), rep
+        assert np.array_equal(dparams.cpu().numpy(), eager["dparams"]), rep
+        _ = (torch.randn(1000, device="cuda") * 2).sum().item()  # unrelated eager work between replays
+    dnb.dnb_block_destroy(h)
