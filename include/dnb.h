@@ -148,14 +148,16 @@ int dnb_op_bn_relu_backward(const void* x, int64_t x_stride, const void* dact, i
                             const void* istd, void* dgamma, void* dbeta, void* scratch,
                             void* stream);
 /* Convolutions: ks = 1 or 3, stride 1, zero padding (ks-1)/2, no bias,
- * cross-correlation; weights OIHW (cout, cin, ks, ks).  `scratch` holds split
- * reduction partials for the weight gradient: dnb_op_conv_wgrad_scratch_bytes. */
+ * cross-correlation; weights OIHW (cout, cin, ks, ks).  `scratch` holds the re-laid
+ * weights (forward, dgrad: dnb_op_conv_scratch_bytes) or the split reduction partials of
+ * the weight gradient (dnb_op_conv_wgrad_scratch_bytes). */
+size_t dnb_op_conv_scratch_bytes(int64_t cin, int64_t cout, int ks); /* packed weights */
 int dnb_op_conv_forward(const void* x, int64_t x_stride, const void* wgt, void* out,
                         int64_t out_stride, int64_t n, int64_t cin, int64_t cout, int64_t h,
-                        int64_t w, int ks, void* stream);
+                        int64_t w, int ks, void* scratch, void* stream);
 int dnb_op_conv_dgrad(const void* dout, int64_t dout_stride, const void* wgt, void* din,
                       int64_t din_stride, int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w,
-                      int ks, void* stream);
+                      int ks, void* scratch, void* stream);
 size_t dnb_op_conv_wgrad_scratch_bytes(int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w,
                                        int ks);
 int dnb_op_conv_wgrad(const void* x, int64_t x_stride, const void* dout, int64_t dout_stride,

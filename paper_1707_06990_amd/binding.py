@@ -57,8 +57,9 @@ _SIGS = {
     "dnb_op_bn_relu": (C.c_int, [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp]),
     "dnb_op_bn_relu_backward": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, C.c_int, _i64, _i64, _i64,
                                           _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
-    "dnb_op_conv_forward": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp]),
-    "dnb_op_conv_dgrad": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp]),
+    "dnb_op_conv_scratch_bytes": (_sz, [_i64, _i64, C.c_int]),
+    "dnb_op_conv_forward": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
+    "dnb_op_conv_dgrad": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
     "dnb_op_conv_wgrad_scratch_bytes": (_sz, [_i64, _i64, _i64, _i64, _i64, C.c_int]),
     "dnb_op_conv_wgrad": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
 }
@@ -171,14 +172,18 @@ def dnb_op_bn_relu_backward(x, x_stride, dact, dact_stride, du, du_stride, accum
                                         _ptr(istd), _ptr(dgamma), _ptr(dbeta), _ptr(scratch), _stream(stream)))
 
 
-def dnb_op_conv_forward(x, x_stride, wgt, out, out_stride, n, cin, cout, h, w, ks, stream=None) -> None:
+def dnb_op_conv_scratch_bytes(cin, cout, ks) -> int:
+    return int(_lib.dnb_op_conv_scratch_bytes(cin, cout, ks))
+
+
+def dnb_op_conv_forward(x, x_stride, wgt, out, out_stride, n, cin, cout, h, w, ks, scratch, stream=None) -> None:
     _check(_lib.dnb_op_conv_forward(_ptr(x), x_stride, _ptr(wgt), _ptr(out), out_stride, n, cin, cout, h, w,
-                                    ks, _stream(stream)))
+                                    ks, _ptr(scratch), _stream(stream)))
 
 
-def dnb_op_conv_dgrad(dout, dout_stride, wgt, din, din_stride, n, cin, cout, h, w, ks, stream=None) -> None:
+def dnb_op_conv_dgrad(dout, dout_stride, wgt, din, din_stride, n, cin, cout, h, w, ks, scratch, stream=None) -> None:
     _check(_lib.dnb_op_conv_dgrad(_ptr(dout), dout_stride, _ptr(wgt), _ptr(din), din_stride, n, cin, cout, h,
-                                  w, ks, _stream(stream)))
+                                  w, ks, _ptr(scratch), _stream(stream)))
 
 
 def dnb_op_conv_wgrad_scratch_bytes(n, cin, cout, h, w, ks) -> int:

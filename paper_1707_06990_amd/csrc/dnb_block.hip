@@ -21,6 +21,8 @@ struct dnb_block {
   size_t off_stat_y;                         // mean[C_out], istd[C_out]
   std::vector<size_t> off_stat_b;            // per layer mean[B], istd[B]
   size_t off_part;
+  size_t off_pack;                           // packed weights of all layers
+  std::vector<size_t> pk;                    // per layer: float offset of its packed weights
   std::vector<size_t> poff;                  // parameter offsets (elements) per layer
   size_t pcount;
   dnb_block_memory mem;
@@ -163,8 +165,12 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
     need(conv_wgrad_partial_floats(d.n, c_in(d, l), B, d.h, d.w, 1));
   }
   need(conv_wgrad_partial_floats(d.n, B, k, d.h, d.w, 9));
-  mem.scratch_bytes = (uint64_t)part * sizeof(float);
+  b->pk.assign(m + 2, 0);
+  size_t pack = 0;
+  for (int l = 1; l <= m; ++l) { b->pk[l] = pack; pack += packed_layer_floats(c_in(d, l), k, B); }
+  mem.scratch_bytes = (uint64_t)(part + pack) * sizeof(float);
   b->off_part = carve(part * sizeof(float), false);
+  b->off_pack = carve(pack * sizeof(float), false);
   mem.workspace_bytes = (uint64_t)off;
   *out = b;
   return DNB_OK;
@@ -219,6 +225,9 @@ int dnb_block_forward(dnb_block* b, const void* x0v, const void* paramsv, void* 
 
   // y[:, 0:c0] = x0, and the statistics of those channels (every later layer reuses them:
   // a channel's batch statistics do not depend on which layer consumes it)
+  float* pack = (float*)(ws + b->off_pack);
+  const size_t B16 = (size_t)((B + 15) & ~15), k16 = (size_t)((k + 15) & ~15);
+  DNB_TRY(launch_pack_block_weights(params, pack, d.c0, k, B, m, st));
   DNB_TRY(launch_copy_slab(x0, (int64_t)d.c0 * hw, y, ys, n, (int64_t)d.c0 * hw, st));
   DNB_TRY(launch_bn_stats(y, ys, n, d.c0, hw, d.eps, mean_y, istd_y, part, st));
   for (int l = 1; l <= m; ++l) {
@@ -233,14 +242,17 @@ int dnb_block_forward(dnb_block* b, const void* x0v, const void* paramsv, void* 
     // concat -> storage 1 and BN+ReLU -> storage 2, one pass over the features
     DNB_TRY(launch_bn_relu(y, ys, S2, (int64_t)c * hw, S1, (int64_t)c * hw, n, c, hw, p.g1, p.b1,
                            mean_y, istd_y, st));
-    DNB_TRY(launch_conv_igemm(S2, (int64_t)c * hw, WeightView{p.W1, c, 1, 0}, bl, (int64_t)B * hw, n,
-                              c, B, d.h, d.w, 1, st));
+    const size_t c16 = (size_t)((c + 15) & ~15);
+    const float* pk1 = pack + b->pk[l];               // 1x1 forward
+    const float* pk3 = pk1 + 2 * B16 * c16;           // 3x3 forward
+    DNB_TRY(launch_conv_igemm(S2, (int64_t)c * hw, WeightView{p.W1, c, 1, 0}, pk1, bl, (int64_t)B * hw,
+                              n, c, B, d.h, d.w, 1, st));
     DNB_TRY(launch_bn_stats(bl, (int64_t)B * hw, n, B, hw, d.eps, mean_b, istd_b, part, st));
     DNB_TRY(launch_bn_relu(bl, (int64_t)B * hw, S3, (int64_t)B * hw, nullptr, 0, n, B, hw, p.g2, p.b2,
                            mean_b, istd_b, st));
     float* xl = y + (int64_t)c * hw;  // x_l goes straight into its channel range of y
-    DNB_TRY(launch_conv_igemm(S3, (int64_t)B * hw, WeightView{p.W3, (int64_t)B * 9, 9, 0}, xl, ys, n,
-                              B, k, d.h, d.w, 9, st));
+    DNB_TRY(launch_conv_igemm(S3, (int64_t)B * hw, WeightView{p.W3, (int64_t)B * 9, 9, 0}, pk3, xl, ys,
+                              n, B, k, d.h, d.w, 9, st));
     if (l < m)
       DNB_TRY(launch_bn_stats(xl, ys, n, k, hw, d.eps, mean_y + c, istd_y + c, part, st));
   }
@@ -269,6 +281,8 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
   float* dS2 = (float*)(ws + b->off_dS2);  // gradient of storage 2 (widest layer)
   float* dS3 = (float*)(ws + b->off_dS3);  // gradient of storage 3, then of b_l
 
+  const float* pack = (const float*)(ws + b->off_pack);  // packed by the forward pass
+  const size_t B16 = (size_t)((B + 15) & ~15), k16 = (size_t)((k + 15) & ~15);
   DNB_TRY(launch_copy_slab((const float*)dyv, ys, G, ys, n, ys, st));
   for (int l = m; l >= 1; --l) {
     const int c = c_in(d, l);
@@ -286,8 +300,11 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
       DNB_TRY(launch_bn_relu(bl, (int64_t)B * hw, S3, (int64_t)B * hw, nullptr, 0, n, B, hw, p.g2,
                              p.b2, mean_b, istd_b, st));
     DNB_TRY(launch_conv_wgrad(S3, (int64_t)B * hw, gl, ys, gp.W3, n, B, k, d.h, d.w, 9, part, st));
-    DNB_TRY(launch_conv_igemm(gl, ys, WeightView{p.W3, 9, (int64_t)B * 9, 1}, dS3, (int64_t)B * hw, n,
-                              k, B, d.h, d.w, 9, st));
+    const size_t c16 = (size_t)((c + 15) & ~15);
+    const float* pk1t = pack + b->pk[l] + B16 * c16;                    // 1x1 data gradient
+    const float* pk3t = pack + b->pk[l] + 2 * B16 * c16 + 9 * k16 * B16;  // 3x3 data gradient
+    DNB_TRY(launch_conv_igemm(gl, ys, WeightView{p.W3, 9, (int64_t)B * 9, 1}, pk3t, dS3, (int64_t)B * hw,
+                              n, k, B, d.h, d.w, 9, st));
     DNB_TRY(launch_bn_relu_bwd(bl, (int64_t)B * hw, dS3, (int64_t)B * hw, dS3, (int64_t)B * hw, false,
                                n, B, hw, p.g2, p.b2, mean_b, istd_b, gp.g2, gp.b2, part, st));
     if (recompute)  // re-populate storage 1 and 2 for this layer
@@ -295,8 +312,8 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
                              mean_y, istd_y, st));
     DNB_TRY(launch_conv_wgrad(S2, (int64_t)c * hw, dS3, (int64_t)B * hw, gp.W1, n, c, B, d.h, d.w, 1,
                               part, st));
-    DNB_TRY(launch_conv_igemm(dS3, (int64_t)B * hw, WeightView{p.W1, 1, c, 0}, dS2, (int64_t)c * hw, n,
-                              B, c, d.h, d.w, 1, st));
+    DNB_TRY(launch_conv_igemm(dS3, (int64_t)B * hw, WeightView{p.W1, 1, c, 0}, pk1t, dS2, (int64_t)c * hw,
+                              n, B, c, d.h, d.w, 1, st));
     // BN1+ReLU backward, then concat backward: add the slice gradients into the slab
     DNB_TRY(launch_bn_relu_bwd(S1, (int64_t)c * hw, dS2, (int64_t)c * hw, G, ys, true, n, c, hw, p.g1,
                                p.b1, mean_y, istd_y, gp.g1, gp.b1, part, st));
@@ -363,30 +380,37 @@ static int conv_args_ok(int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t
   return DNB_OK;
 }
 
+size_t dnb_op_conv_scratch_bytes(int64_t cin, int64_t cout, int ks) {
+  if ((ks != 1 && ks != 3) || cin < 1 || cout < 1 || cin > (1 << 20) || cout > (1 << 20)) return 0;
+  return packed_weight_floats((int)cout, (int)cin, ks * ks) * sizeof(float);
+}
+
 int dnb_op_conv_forward(const void* x, int64_t x_stride, const void* wgt, void* out,
                         int64_t out_stride, int64_t n, int64_t cin, int64_t cout, int64_t h,
-                        int64_t w, int ks, void* stream) {
-  if (!x || !wgt || !out) return DNB_E_NULL;
+                        int64_t w, int ks, void* scratch, void* stream) {
+  if (!x || !wgt || !out || !scratch) return DNB_E_NULL;
   const int rc = conv_args_ok(n, cin, cout, h, w, ks);
   if (rc) return rc;
   const int taps = ks * ks;
-  DNB_TRY(launch_conv_igemm((const float*)x, x_stride, WeightView{(const float*)wgt, cin * taps, taps, 0},
-                            (float*)out, out_stride, (int)n, (int)cin, (int)cout, (int)h, (int)w, taps,
-                            (hipStream_t)stream));
+  const WeightView wv{(const float*)wgt, cin * taps, taps, 0};
+  DNB_TRY(launch_pack_weights(wv, (int)cout, (int)cin, taps, (float*)scratch, (hipStream_t)stream));
+  DNB_TRY(launch_conv_igemm((const float*)x, x_stride, wv, (const float*)scratch, (float*)out, out_stride,
+                            (int)n, (int)cin, (int)cout, (int)h, (int)w, taps, (hipStream_t)stream));
   return DNB_OK;
 }
 
 int dnb_op_conv_dgrad(const void* dout, int64_t dout_stride, const void* wgt, void* din,
                       int64_t din_stride, int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w,
-                      int ks, void* stream) {
-  if (!dout || !wgt || !din) return DNB_E_NULL;
+                      int ks, void* scratch, void* stream) {
+  if (!dout || !wgt || !din || !scratch) return DNB_E_NULL;
   const int rc = conv_args_ok(n, cin, cout, h, w, ks);
   if (rc) return rc;
   const int taps = ks * ks;
   // the data gradient is a convolution of dout with the weights transposed and flipped
-  DNB_TRY(launch_conv_igemm((const float*)dout, dout_stride,
-                            WeightView{(const float*)wgt, taps, cin * taps, taps == 9 ? 1 : 0},
-                            (float*)din, din_stride, (int)n, (int)cout, (int)cin, (int)h, (int)w, taps,
+  const WeightView wv{(const float*)wgt, taps, cin * taps, taps == 9 ? 1 : 0};
+  DNB_TRY(launch_pack_weights(wv, (int)cin, (int)cout, taps, (float*)scratch, (hipStream_t)stream));
+  DNB_TRY(launch_conv_igemm((const float*)dout, dout_stride, wv, (const float*)scratch, (float*)din,
+                            din_stride, (int)n, (int)cout, (int)cin, (int)h, (int)w, taps,
                             (hipStream_t)stream));
   return DNB_OK;
 }

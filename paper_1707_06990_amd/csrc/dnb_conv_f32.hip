@@ -14,6 +14,17 @@
 
 namespace dnb {
 
+// fast paths (dnb_conv_f32_fast.hip)
+bool conv_fast_ok(const float* in, int64_t in_stride, const float* out, int64_t out_stride, int h,
+                  int w, int taps);
+bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, float* out,
+                      int64_t out_stride, int n, int cin, int cout, int h, int w, int taps,
+                      hipStream_t st);
+size_t conv_wgrad_fast_partial_floats(int n, int cin, int cout, int h, int w, int taps);
+bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
+                       float* partials, int n, int cin, int cout, int h, int w, int taps,
+                       int* splits, hipStream_t st);
+
 namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -229,8 +240,17 @@ __global__ __launch_bounds__(256) void k_sum_partials(const float* __restrict__ 
                                                       int64_t count, float* __restrict__ out) {
   const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (e >= count) return;
+  // fixed summation order (split 0, 1, 2, ...); eight independent loads in flight
   float s = 0.f;
-  for (int i = 0; i < splits; ++i) s += part[(int64_t)i * count + e];
+  int i = 0;
+  for (; i + 8 <= splits; i += 8) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = part[(int64_t)(i + u) * count + e];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
+  for (; i < splits; ++i) s += part[(int64_t)i * count + e];
   out[e] = s;
 }
 
@@ -318,7 +338,7 @@ WgradPlan plan_wgrad(int n, int cin, int cout, int h, int w, int taps) {
   int splits = 1024 / (gy * gz);
   if (splits < 1) splits = 1;
   if (splits > p.total) splits = p.total;
-  if (splits > 256) splits = 256;
+  if (splits > 64) splits = 64;
   p.cps = (p.total + splits - 1) / splits;
   p.splits = (p.total + p.cps - 1) / p.cps;
   const int halo = taps == 9 ? w + 1 : 0;
@@ -331,10 +351,13 @@ WgradPlan plan_wgrad(int n, int cin, int cout, int h, int w, int taps) {
 
 }  // namespace
 
-hipError_t launch_conv_igemm(const float* in, int64_t in_stride, WeightView wv, float* out,
-                             int64_t out_stride, int n, int cin, int cout, int h, int w, int taps,
-                             hipStream_t st) {
+hipError_t launch_conv_igemm(const float* in, int64_t in_stride, WeightView wv, const float* packed,
+                             float* out, int64_t out_stride, int n, int cin, int cout, int h, int w,
+                             int taps, hipStream_t st) {
   if (n <= 0 || cout <= 0 || h <= 0 || w <= 0) return hipSuccess;
+  if (packed && conv_fast_ok(in, in_stride, out, out_stride, h, w, taps) &&
+      launch_conv_fast(in, in_stride, packed, out, out_stride, n, cin, cout, h, w, taps, st))
+    return hipGetLastError();
   const IgemmPlan p = plan_igemm(n, cout, h, w, taps);
   if (p.lds > 64 * 1024) return hipErrorInvalidValue;
   if (taps == 9) return launch_igemm_mt<9>(p, in, in_stride, wv, out, out_stride, cin, cout, h, w, st);
@@ -346,24 +369,30 @@ int conv_wgrad_splits(int n, int cin, int cout, int h, int w, int taps) {
 }
 
 size_t conv_wgrad_partial_floats(int n, int cin, int cout, int h, int w, int taps) {
-  return (size_t)conv_wgrad_splits(n, cin, cout, h, w, taps) * cin * cout * taps;
+  const size_t a = (size_t)conv_wgrad_splits(n, cin, cout, h, w, taps) * cin * cout * taps;
+  const size_t b = conv_wgrad_fast_partial_floats(n, cin, cout, h, w, taps);
+  return a > b ? a : b;
 }
 
 hipError_t launch_conv_wgrad(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
                              float* dw, int n, int cin, int cout, int h, int w, int taps,
                              float* partials, hipStream_t st) {
   if (cin <= 0 || cout <= 0) return hipSuccess;
-  const WgradPlan p = plan_wgrad(n, cin, cout, h, w, taps);
-  if (p.lds > 64 * 1024) return hipErrorInvalidValue;
-  if (taps == 9)
-    hipLaunchKernelGGL((k_conv_wgrad<9, 7>), p.grid, dim3(256), p.lds, st, in, in_stride, g, g_stride,
-                       partials, cin, cout, h, w, p.cpi, p.total, p.cps, p.mtw, p.ctw, p.PA, p.PG);
-  else
-    hipLaunchKernelGGL((k_conv_wgrad<1, 3>), p.grid, dim3(256), p.lds, st, in, in_stride, g, g_stride,
-                       partials, cin, cout, h, w, p.cpi, p.total, p.cps, p.mtw, p.ctw, p.PA, p.PG);
   const int64_t count = (int64_t)cin * cout * taps;
+  int splits = 0;
+  if (!launch_wgrad_fast(in, in_stride, g, g_stride, partials, n, cin, cout, h, w, taps, &splits, st)) {
+    const WgradPlan p = plan_wgrad(n, cin, cout, h, w, taps);
+    if (p.lds > 64 * 1024) return hipErrorInvalidValue;
+    if (taps == 9)
+      hipLaunchKernelGGL((k_conv_wgrad<9, 7>), p.grid, dim3(256), p.lds, st, in, in_stride, g, g_stride,
+                         partials, cin, cout, h, w, p.cpi, p.total, p.cps, p.mtw, p.ctw, p.PA, p.PG);
+    else
+      hipLaunchKernelGGL((k_conv_wgrad<1, 3>), p.grid, dim3(256), p.lds, st, in, in_stride, g, g_stride,
+                         partials, cin, cout, h, w, p.cpi, p.total, p.cps, p.mtw, p.ctw, p.PA, p.PG);
+    splits = p.splits;
+  }
   hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, partials,
-                     p.splits, count, dw);
+                     splits, count, dw);
   return hipGetLastError();
 }
 

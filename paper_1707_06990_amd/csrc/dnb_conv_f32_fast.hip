@@ -1,0 +1,722 @@
+// Fast fp32 NCHW convolution kernels for the shapes DenseNet blocks actually have
+// (pixel counts and strides that are multiples of 4, 16-byte aligned slabs).  Anything else
+// runs on the generic kernels in dnb_conv_f32.hip; both compute the same sums.
+//
+// Common idea: the 16x16x4 fp32 MFMA puts channels on M and pixels on N (forward, data
+// gradient) or channels on both M and N and pixels on K (weight gradient).  A lane never
+// loads single floats from HBM: it loads 4 consecutive pixels (16 bytes) and uses them for
+// four MFMAs -- four N-tiles whose columns interleave (tile t holds pixels 4j+t), or four
+// K-steps.  The order of the K index inside a sum is free, so lane group g takes channels
+// {g, 4+g, 8+g, 12+g} of a 16-channel chunk and a channel tail that is a multiple of 4
+// costs no padding.
+#include "dnb_internal.h"
+
+namespace dnb {
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float4 ldg4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ __forceinline__ float4 zero4() { return make_float4(0.f, 0.f, 0.f, 0.f); }
+__device__ __forceinline__ float elem(const float4& v, int e) {
+  return e == 0 ? v.x : (e == 1 ? v.y : (e == 2 ? v.z : v.w));
+}
+
+// ------------------------------------------------------------------------------- packed weights
+//
+// The fast forward / data-gradient kernels read their A operand straight from global memory
+// (it is small and stays in L2), 16 bytes per lane, so the weights are first re-laid as
+// [tap][Mpad][Kpad], zero padded to multiples of 16, with the K index permuted inside each
+// 16-chunk: position 16*chunk + 4*g + ks holds channel 16*chunk + 4*ks + g.
+
+__device__ __forceinline__ int unperm16(int pos) { return (pos & ~15) + 4 * (pos & 3) + ((pos >> 2) & 3); }
+
+__global__ __launch_bounds__(256) void k_pack_weights(const float* __restrict__ w, int64_t sm, int64_t sc,
+                                                      int flip, int cout, int cin, int taps,
+                                                      float* __restrict__ outp) {
+  const int M16 = (cout + 15) & ~15, K16 = (cin + 15) & ~15;
+  const int64_t total = (int64_t)taps * M16 * K16;
+  for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+    const int pos = (int)(idx % K16);
+    const int64_t rem = idx / K16;
+    const int m = (int)(rem % M16), t = (int)(rem / M16);
+    const int c = unperm16(pos);
+    outp[idx] = (m < cout && c < cin) ? w[(int64_t)m * sm + (int64_t)c * sc + (flip ? taps - 1 - t : t)] : 0.f;
+  }
+}
+
+// All layers of a dense block in one launch (grid.y = layer).  Per layer, in order:
+// 1x1 forward [B16][C16], 1x1 data gradient [C16][B16], 3x3 forward [9][k16][B16],
+// 3x3 data gradient [9][B16][k16] (transposed and flipped).
+__global__ __launch_bounds__(256) void k_pack_block_weights(const float* __restrict__ params,
+                                                            float* __restrict__ packed, int c0, int k,
+                                                            int B) {
+  const int l = blockIdx.y + 1;
+  const int B16 = (B + 15) & ~15, k16 = (k + 15) & ~15;
+  int64_t poff = 0, koff = 0;
+  for (int i = 1; i < l; ++i) {
+    const int c = c0 + (i - 1) * k, c16 = (c + 15) & ~15;
+    poff += 2 * (int64_t)c + (int64_t)B * c + 2 * B + 9 * (int64_t)k * B;
+    koff += 2 * (int64_t)B16 * c16 + 18 * (int64_t)k16 * B16;
+  }
+  const int C = c0 + (l - 1) * k, C16 = (C + 15) & ~15;
+  const float* W1 = params + poff + 2 * C;
+  const float* W3 = W1 + (int64_t)B * C + 2 * B;
+  float* A = packed + koff;
+  const int64_t n1 = (int64_t)B16 * C16, n3 = 9 * (int64_t)k16 * B16, total = 2 * n1 + 2 * n3;
+  for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+    float v = 0.f;
+    if (idx < n1) {
+      const int m = (int)(idx / C16), c = unperm16((int)(idx % C16));
+      if (m < B && c < C) v = W1[(int64_t)m * C + c];
+    } else if (idx < 2 * n1) {
+      const int64_t e = idx - n1;
+      const int cc = (int)(e / B16), o = unperm16((int)(e % B16));
+      if (cc < C && o < B) v = W1[(int64_t)o * C + cc];
+    } else if (idx < 2 * n1 + n3) {
+      const int64_t e = idx - 2 * n1;
+      const int t = (int)(e / (k16 * B16)), rem = (int)(e % (k16 * B16));
+      const int mm = rem / B16, c = unperm16(rem % B16);
+      if (mm < k && c < B) v = W3[((int64_t)mm * B + c) * 9 + t];
+    } else {
+      const int64_t e = idx - 2 * n1 - n3;
+      const int t = (int)(e / (B16 * k16)), rem = (int)(e % (B16 * k16));
+      const int cc = rem / k16, o = unperm16(rem % k16);
+      if (cc < B && o < k) v = W3[((int64_t)o * B + cc) * 9 + (8 - t)];
+    }
+    A[idx] = v;
+  }
+}
+
+// Sums the accumulators of the K-split waves of a workgroup (fixed order 0,1,2,...).  Every
+// wave writes its tiles to LDS; M-tile a is then owned by wave a % nw, which adds the nw copies
+// and keeps the result in its own registers.  red: [nw][MT*NT][64 lanes][4].
+template <int MT, int NT>
+__device__ __forceinline__ void ksplit_reduce(f32x4 (&acc)[MT][NT], float* red, int wave, int lane, int nw) {
+  __syncthreads();
+#pragma unroll
+  for (int a = 0; a < MT; ++a)
+#pragma unroll
+    for (int t = 0; t < NT; ++t)
+      *reinterpret_cast<float4*>(&red[(((wave * MT + a) * NT + t) * 64 + lane) * 4]) =
+          make_float4(acc[a][t][0], acc[a][t][1], acc[a][t][2], acc[a][t][3]);
+  __syncthreads();
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+    if (a % nw == wave) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int w = 0; w < nw; ++w) {
+          const float4 v = *reinterpret_cast<const float4*>(&red[(((w * MT + a) * NT + t) * 64 + lane) * 4]);
+          s[0] += v.x; s[1] += v.y; s[2] += v.z; s[3] += v.w;
+        }
+        acc[a][t] = s;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------- 1x1, fwd/dgrad
+//
+// out[m][q] = sum_c W(m,c) in[c][q].  No LDS in the main loop: each lane streams its pixels of
+// channel 16*chunk+4*ks+g straight from HBM into the B operand and its packed weights from L2
+// into the A operand, one chunk ahead.  The workgroup is one pixel tile (16*PPL pixels):
+//   KSPLIT  : its waves take alternate 16-channel chunks (many loads in flight for a long K,
+//             e.g. the forward 1x1 over the whole concatenation) and are summed through LDS;
+//   !KSPLIT : its waves take different M-tiles of the same pixels (short K, many output
+//             channels: the data gradient of the 1x1).
+template <int MT, int PPL, bool KSPLIT>
+__global__ __launch_bounds__(256) void k_conv1x1_v3(
+    const float* __restrict__ in, int64_t in_stride, const float* __restrict__ Wp, int Kpad,
+    float* __restrict__ out, int64_t out_stride, int cin, int cout, int HW) {
+  extern __shared__ float red[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+  const int j = lane & 15, g = lane >> 4;
+  const int q = blockIdx.x * (16 * PPL) + PPL * j;
+  const int img = blockIdx.z;
+  const bool pix_ok = q < HW;
+  const float* inb = in + (int64_t)img * in_stride + q;
+  const int mbase = KSPLIT ? blockIdx.y * (MT * 16) : (blockIdx.y * nw + wave) * (MT * 16);
+  const int nchunks = Kpad >> 4;
+  const int cstart = KSPLIT ? wave : 0, cstep = KSPLIT ? nw : 1;
+  const float* wrow = Wp + (int64_t)(mbase + j) * Kpad + 4 * g;
+  const bool m_ok = mbase < ((cout + 15) & ~15);  // this wave's first tile exists in the packed rows
+
+  f32x4 acc[MT][PPL];
+#pragma unroll
+  for (int a = 0; a < MT; ++a)
+#pragma unroll
+    for (int t = 0; t < PPL; ++t) acc[a][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  float cur[4][PPL], nxt[4][PPL];
+  float4 wcur[MT], wnxt[MT];
+  auto load_chunk = [&](int ch0, float(&v)[4][PPL], float4(&w4)[MT]) {
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int ch = ch0 + 4 * ks + g;
+      const bool ok = pix_ok && ch < cin;
+      if (PPL == 4) {
+        const float4 t = ok ? ldg4(inb + (int64_t)ch * HW) : zero4();
+        v[ks][0] = t.x; v[ks][1 % PPL] = t.y; v[ks][2 % PPL] = t.z; v[ks][3 % PPL] = t.w;
+      } else {
+        v[ks][0] = ok ? inb[(int64_t)ch * HW] : 0.f;
+      }
+    }
+#pragma unroll
+    for (int a = 0; a < MT; ++a) {
+      // rows of M-tiles past the padded output-channel count do not exist: leave them zero
+      const bool rok = mbase + a * 16 < ((cout + 15) & ~15);
+      w4[a] = rok ? ldg4(wrow + (int64_t)a * 16 * Kpad + ch0) : zero4();
+    }
+  };
+
+  if (m_ok) {
+    if (cstart < nchunks) load_chunk(cstart * 16, cur, wcur);
+    for (int ci = cstart; ci < nchunks; ci += cstep) {
+      const int c0 = ci * 16;
+      const bool more = ci + cstep < nchunks;
+      if (more) load_chunk(c0 + cstep * 16, nxt, wnxt);
+      const int nks = min(4, (cin - c0 + 3) >> 2);
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        if (ks < nks) {
+#pragma unroll
+          for (int a = 0; a < MT; ++a) {
+            const float wa = elem(wcur[a], ks);
+#pragma unroll
+            for (int t = 0; t < PPL; ++t) acc[a][t] = mfma16(wa, cur[ks][t], acc[a][t]);
+          }
+        }
+      }
+      if (more) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+          for (int t = 0; t < PPL; ++t) cur[ks][t] = nxt[ks][t];
+#pragma unroll
+        for (int a = 0; a < MT; ++a) wcur[a] = wnxt[a];
+      }
+    }
+  }
+
+  if (KSPLIT) ksplit_reduce<MT, PPL>(acc, red, wave, lane, nw);
+
+  if (pix_ok) {
+    float* ob = out + (int64_t)img * out_stride + q;
+#pragma unroll
+    for (int a = 0; a < MT; ++a) {
+      if (KSPLIT && a % nw != wave) continue;  // after the reduction M-tile a lives in wave a % nw
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int m = mbase + a * 16 + 4 * g + r;
+        if (m < cout) {
+          if (PPL == 4)
+            *reinterpret_cast<float4*>(ob + (int64_t)m * HW) =
+                make_float4(acc[a][0][r], acc[a][1 % PPL][r], acc[a][2 % PPL][r], acc[a][3 % PPL][r]);
+          else
+            ob[(int64_t)m * HW] = acc[a][0][r];
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------- 3x3, fwd/dgrad
+//
+// The workgroup owns 64 consecutive pixels of one image.  ALL input channels of that pixel
+// range plus one image row of halo on both sides are staged in LDS once, with flat pixel
+// indexing (origin 4 pixels before the halo so every row of taps starts 16-byte aligned).
+// For tap row di a lane reads its 4 pixels and the two neighbours once; the three taps dj
+// are register selections of those 6 values.  Image top/bottom come out of the zero fill
+// of flat indices outside [0, HW); left/right edges only ever touch the two neighbour reads
+// (W is a multiple of 4), which are masked.  Waves split K (forward: 9*B long K, k outputs)
+// or M (data gradient: k*9 short K, B outputs) as in the 1x1 kernel; packed weights come
+// from L2, 16 bytes per lane per (tap, chunk).
+template <int MT, bool KSPLIT>
+__global__ __launch_bounds__(256) void k_conv3x3_v3(
+    const float* __restrict__ in, int64_t in_stride, const float* __restrict__ Wp, int Mpad,
+    int Kpad, float* __restrict__ out, int64_t out_stride, int cin, int cout, int H, int W, int CS) {
+  extern __shared__ float lds[];
+  const int HW = H * W;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthr = blockDim.x, nw = nthr >> 6;
+  const int j = lane & 15, g = lane >> 4;
+  const int q0 = blockIdx.x * 64, img = blockIdx.z;
+  const int origin = q0 - W - 4;
+  const int seg4 = (64 + 2 * W + 8) >> 2;
+  const int pw = 4 * j, q = q0 + pw;
+  const int wc = q % W;
+  const bool maskL = wc == 0, maskR = wc + 3 == W - 1;
+  const float* inb = in + (int64_t)img * in_stride;
+  const int mbase = KSPLIT ? blockIdx.y * (MT * 16) : (blockIdx.y * nw + wave) * (MT * 16);
+  const int nchunks = Kpad >> 4;
+  const int cstart = KSPLIT ? wave : 0, cstep = KSPLIT ? nw : 1;
+
+  const int rows = (cin + 3) & ~3;  // staged channel rows (tail rows zero)
+  for (int row = tid >> 4; row < rows; row += nthr >> 4) {
+    const float* src = inb + (int64_t)row * HW;
+    for (int c4 = tid & 15; c4 < seg4; c4 += 16) {
+      const int qq = origin + 4 * c4;
+      const float4 v = (row < cin && qq >= 0 && qq < HW) ? ldg4(src + qq) : zero4();
+      *reinterpret_cast<float4*>(&lds[row * CS + 4 * c4]) = v;
+    }
+  }
+  __syncthreads();
+
+  f32x4 acc[MT][4];
+#pragma unroll
+  for (int a = 0; a < MT; ++a)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[a][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  if (mbase < Mpad) {
+    for (int ci = cstart; ci < nchunks; ci += cstep) {
+      const int c0 = ci * 16;
+      const int nks = min(4, (cin - c0 + 3) >> 2);
+      float4 w4[9][MT];
+#pragma unroll
+      for (int t = 0; t < 9; ++t)
+#pragma unroll
+        for (int a = 0; a < MT; ++a)
+          w4[t][a] = (mbase + a * 16 < Mpad)
+                         ? ldg4(Wp + ((int64_t)t * Mpad + mbase + a * 16 + j) * Kpad + c0 + 4 * g)
+                         : zero4();
+#pragma unroll
+      for (int di = -1; di <= 1; ++di) {
+        const int base = pw + 4 + W + di * W;
+        float4 V[4];
+        float eL[4], eR[4];
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          if (ks < nks) {
+            const float* rowp = &lds[(c0 + 4 * ks + g) * CS + base];
+            V[ks] = *reinterpret_cast<const float4*>(rowp);
+            eL[ks] = maskL ? 0.f : rowp[-1];
+            eR[ks] = maskR ? 0.f : rowp[4];
+          } else {
+            V[ks] = zero4(); eL[ks] = 0.f; eR[ks] = 0.f;
+          }
+        }
+#pragma unroll
+        for (int dj = -1; dj <= 1; ++dj) {
+          const int t = (di + 1) * 3 + (dj + 1);
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks) {
+            if (ks < nks) {
+              const float b0 = dj < 0 ? eL[ks] : (dj == 0 ? V[ks].x : V[ks].y);
+              const float b1 = dj < 0 ? V[ks].x : (dj == 0 ? V[ks].y : V[ks].z);
+              const float b2 = dj < 0 ? V[ks].y : (dj == 0 ? V[ks].z : V[ks].w);
+              const float b3 = dj < 0 ? V[ks].z : (dj == 0 ? V[ks].w : eR[ks]);
+#pragma unroll
+              for (int a = 0; a < MT; ++a) {
+                const float wa = elem(w4[t][a], ks);
+                acc[a][0] = mfma16(wa, b0, acc[a][0]);
+                acc[a][1] = mfma16(wa, b1, acc[a][1]);
+                acc[a][2] = mfma16(wa, b2, acc[a][2]);
+                acc[a][3] = mfma16(wa, b3, acc[a][3]);
+              }
+            }
+          }
+        }
+      }
+    }
+  }
+
+  if (KSPLIT) ksplit_reduce<MT, 4>(acc, lds, wave, lane, nw);  // reuses the tile's LDS (barrier inside)
+
+  if (q < HW) {
+    float* ob = out + (int64_t)img * out_stride + q;
+#pragma unroll
+    for (int a = 0; a < MT; ++a) {
+      if (KSPLIT && a % nw != wave) continue;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int m = mbase + a * 16 + 4 * g + r;
+        if (m < cout)
+          *reinterpret_cast<float4*>(ob + (int64_t)m * HW) =
+              make_float4(acc[a][0][r], acc[a][1][r], acc[a][2][r], acc[a][3][r]);
+      }
+    }
+  }
+}
+
+// Adds the accumulators of the waves of a workgroup into wave 0, in a fixed order.
+template <int NT>
+__device__ __forceinline__ void reduce_waves(f32x4 (&acc)[NT], float* buf, int wave, int lane, int nw) {
+  for (int w = nw - 1; w >= 1; --w) {
+    __syncthreads();
+    if (wave == w) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+        *reinterpret_cast<float4*>(&buf[(t * 64 + lane) * 4]) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
+    }
+    __syncthreads();
+    if (wave == w - 1) {
+#pragma unroll
+      for (int t = 0; t < NT; ++t) {
+        const float4 v = *reinterpret_cast<const float4*>(&buf[(t * 64 + lane) * 4]);
+        acc[t][0] += v.x; acc[t][1] += v.y; acc[t][2] += v.z; acc[t][3] += v.w;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------- 1x1 wgrad
+//
+// dW[m][c] = sum_{n,q} g[n][m][q] a[n][c][q].  A "step" is 16 pixels: lane (r, kk) loads pixels
+// 4kk..4kk+3 of row r of both operands (16 bytes each) and issues 4 K-steps.  The four waves of
+// a workgroup take alternate steps (together 256 contiguous bytes per row), keep all MTW x CTW
+// tiles in registers, and are summed in LDS at the end; the workgroup writes one partial.
+template <int MTW, int CTW>
+__global__ __launch_bounds__(256) void k_wgrad1x1_fast(
+    const float* __restrict__ a, int64_t a_stride, const float* __restrict__ gout, int64_t g_stride,
+    float* __restrict__ part, int cin, int cout, int HW, int spi, int total_steps, int steps_per_wg) {
+  extern __shared__ float lds[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, kk = lane >> 4;
+  const int c0 = blockIdx.y * (CTW * 16), m0 = blockIdx.z * (MTW * 16);
+  const int s_begin = blockIdx.x * steps_per_wg, s_end = min(total_steps, s_begin + steps_per_wg);
+
+  f32x4 acc[MTW * CTW];
+#pragma unroll
+  for (int t = 0; t < MTW * CTW; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  for (int s = s_begin + wave; s < s_end; s += 4) {
+    const int img = s / spi, q = (s - img * spi) * 16 + 4 * kk;
+    const bool ok = q < HW;
+    float4 A[MTW], Bv[CTW];
+#pragma unroll
+    for (int x = 0; x < MTW; ++x) {
+      const int m = m0 + x * 16 + r;
+      A[x] = (ok && m < cout) ? ldg4(gout + (int64_t)img * g_stride + (int64_t)m * HW + q) : zero4();
+    }
+#pragma unroll
+    for (int y = 0; y < CTW; ++y) {
+      const int c = c0 + y * 16 + r;
+      Bv[y] = (ok && c < cin) ? ldg4(a + (int64_t)img * a_stride + (int64_t)c * HW + q) : zero4();
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+#pragma unroll
+      for (int x = 0; x < MTW; ++x)
+#pragma unroll
+        for (int y = 0; y < CTW; ++y) acc[x * CTW + y] = mfma16(elem(A[x], e), elem(Bv[y], e), acc[x * CTW + y]);
+  }
+
+  reduce_waves<MTW * CTW>(acc, lds, wave, lane, 4);
+  if (wave == 0) {
+    float* pb = part + (int64_t)blockIdx.x * cout * cin;
+#pragma unroll
+    for (int x = 0; x < MTW; ++x)
+#pragma unroll
+      for (int y = 0; y < CTW; ++y) {
+        const int c = c0 + y * 16 + r;
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          const int m = m0 + x * 16 + 4 * kk + rr;
+          if (m < cout && c < cin) pb[(int64_t)m * cin + c] = acc[x * CTW + y][rr];
+        }
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------- 3x3 wgrad
+//
+// dW[m][c][t] = sum_{n,q} g[n][m][q] a[n][c][q+shift(t)].  The workgroup stages CTW*16 channels
+// of a pixel range (plus halo, as in the forward kernel) in LDS; every wave takes its own
+// 16-pixel steps of that range and keeps all MTW x CTW x 9 tiles in registers.  g comes
+// straight from HBM (16 bytes per lane and step).
+template <int MTW, int CTW>
+__global__ __launch_bounds__(256) void k_wgrad3x3_fast(
+    const float* __restrict__ a, int64_t a_stride, const float* __restrict__ gout, int64_t g_stride,
+    float* __restrict__ part, int cin, int cout, int H, int W, int tiles_per_img, int nms, int PA) {
+  extern __shared__ float lds[];
+  const int HW = H * W;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r = lane & 15, kk = lane >> 4;
+  constexpr int CB = CTW * 16, NT = MTW * CTW * 9;
+  const int TPIX = 4 * nms * 16;
+  const int img = blockIdx.x / tiles_per_img, q0 = (blockIdx.x - img * tiles_per_img) * TPIX;
+  const int c0 = blockIdx.y * CB, m0 = blockIdx.z * (MTW * 16);
+  const int origin = q0 - W - 4;
+  const int seg4 = (TPIX + 2 * W + 8) >> 2;
+  const float* ab = a + (int64_t)img * a_stride;
+  const float* gb = gout + (int64_t)img * g_stride;
+
+  for (int row = tid >> 4; row < CB; row += 16) {
+    const int ch = c0 + row;
+    const float* src = ab + (int64_t)ch * HW;
+    for (int c4 = tid & 15; c4 < seg4; c4 += 16) {
+      const int qq = origin + 4 * c4;
+      const float4 v = (ch < cin && qq >= 0 && qq < HW) ? ldg4(src + qq) : zero4();
+      *reinterpret_cast<float4*>(&lds[row * PA + 4 * c4]) = v;
+    }
+  }
+  __syncthreads();
+
+  f32x4 acc[NT];
+#pragma unroll
+  for (int t = 0; t < NT; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  for (int ms = 0; ms < nms; ++ms) {
+    const int pw = (wave * nms + ms) * 16 + 4 * kk, q = q0 + pw;
+    const bool ok = q < HW;
+    float4 A[MTW];
+#pragma unroll
+    for (int x = 0; x < MTW; ++x) {
+      const int m = m0 + x * 16 + r;
+      A[x] = (ok && m < cout) ? ldg4(gb + (int64_t)m * HW + q) : zero4();
+    }
+    const int wc = q % W;
+    const bool maskL = wc == 0, maskR = wc + 3 == W - 1;
+#pragma unroll
+    for (int y = 0; y < CTW; ++y) {
+#pragma unroll
+      for (int di = -1; di <= 1; ++di) {
+        const float* rowp = &lds[(y * 16 + r) * PA + pw + 4 + W + di * W];
+        const float4 V = *reinterpret_cast<const float4*>(rowp);
+        const float eL = maskL ? 0.f : rowp[-1];
+        const float eR = maskR ? 0.f : rowp[4];
+#pragma unroll
+        for (int dj = -1; dj <= 1; ++dj) {
+          const int t = (di + 1) * 3 + (dj + 1);
+          const float b0 = dj < 0 ? eL : (dj == 0 ? V.x : V.y);
+          const float b1 = dj < 0 ? V.x : (dj == 0 ? V.y : V.z);
+          const float b2 = dj < 0 ? V.y : (dj == 0 ? V.z : V.w);
+          const float b3 = dj < 0 ? V.z : (dj == 0 ? V.w : eR);
+#pragma unroll
+          for (int x = 0; x < MTW; ++x) {
+            f32x4& d = acc[(x * CTW + y) * 9 + t];
+            d = mfma16(A[x].x, b0, d);
+            d = mfma16(A[x].y, b1, d);
+            d = mfma16(A[x].z, b2, d);
+            d = mfma16(A[x].w, b3, d);
+          }
+        }
+      }
+    }
+  }
+
+  reduce_waves<NT>(acc, lds, wave, lane, 4);  // reuses the activation tile's LDS (barrier inside)
+  if (wave == 0) {
+    float* pb = part + (int64_t)blockIdx.x * cout * cin * 9;
+#pragma unroll
+    for (int x = 0; x < MTW; ++x)
+#pragma unroll
+      for (int y = 0; y < CTW; ++y) {
+        const int c = c0 + y * 16 + r;
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            const int m = m0 + x * 16 + 4 * kk + rr;
+            if (m < cout && c < cin) pb[((int64_t)m * cin + c) * 9 + t] = acc[(x * CTW + y) * 9 + t][rr];
+          }
+      }
+  }
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int pad4mod32(int v) {  // smallest pitch >= v with pitch % 32 == 4
+  int p = (v + 31) / 32 * 32 + 4;
+  if (p - 32 >= v) p -= 32;
+  return p;
+}
+
+}  // namespace
+
+// ============================================================================ dispatch
+
+bool conv_fast_ok(const float* in, int64_t in_stride, const float* out, int64_t out_stride, int h,
+                  int w, int taps) {
+  const int hw = h * w;
+  if (hw % 4 || in_stride % 4 || out_stride % 4 || !aligned16(in) || !aligned16(out)) return false;
+  if (taps == 9 && (w % 4 || w < 4)) return false;
+  return true;
+}
+
+size_t packed_weight_floats(int cout, int cin, int taps) {
+  return (size_t)taps * ((cout + 15) & ~15) * ((cin + 15) & ~15);
+}
+
+hipError_t launch_pack_weights(WeightView wv, int cout, int cin, int taps, float* packed, hipStream_t st) {
+  const size_t total = packed_weight_floats(cout, cin, taps);
+  unsigned grid = (unsigned)((total + 255) / 256);
+  if (grid > 4096) grid = 4096;
+  hipLaunchKernelGGL(k_pack_weights, dim3(grid), dim3(256), 0, st, wv.w, wv.sm, wv.sc, wv.flip, cout, cin,
+                     taps, packed);
+  return hipGetLastError();
+}
+
+size_t packed_layer_floats(int c, int k, int B) {
+  const size_t B16 = (B + 15) & ~15, k16 = (k + 15) & ~15, c16 = (c + 15) & ~15;
+  return 2 * B16 * c16 + 18 * k16 * B16;
+}
+
+hipError_t launch_pack_block_weights(const float* params, float* packed, int c0, int k, int B, int m,
+                                     hipStream_t st) {
+  const size_t most = packed_layer_floats(c0 + (m - 1) * k, k, B);
+  unsigned gx = (unsigned)((most + 255) / 256);
+  if (gx > 256) gx = 256;
+  hipLaunchKernelGGL(k_pack_block_weights, dim3(gx, (unsigned)m), dim3(256), 0, st, params, packed, c0, k, B);
+  return hipGetLastError();
+}
+
+// Returns false (nothing launched) if the fast path does not cover this shape.
+bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, float* out,
+                      int64_t out_stride, int n, int cin, int cout, int h, int w, int taps,
+                      hipStream_t st) {
+  const int hw = h * w, mtiles = (cout + 15) / 16, M16 = mtiles * 16;
+  const int K16 = (cin + 15) & ~15, nchunks = K16 / 16;
+  if (taps == 1) {
+    const bool ksplit = nchunks >= 4;
+    int nw, mt, gy;
+    if (ksplit) {
+      nw = 4; mt = mtiles >= 3 ? 3 : mtiles; gy = (mtiles + mt - 1) / mt;
+    } else {
+      nw = mtiles >= 4 ? 4 : mtiles;
+      mt = (mtiles + nw - 1) / nw; if (mt > 3) mt = 3;
+      gy = (mtiles + nw * mt - 1) / (nw * mt);
+    }
+    // 64-pixel tiles unless that leaves the chip underfilled (fewer than 2 workgroups per CU)
+    const int ppl = ((int64_t)((hw + 63) / 64) * gy * n >= 512) ? 4 : 1;
+    dim3 grid((unsigned)((hw + 16 * ppl - 1) / (16 * ppl)), (unsigned)gy, (unsigned)n);
+    const size_t lds = ksplit ? (size_t)nw * mt * ppl * 256 * sizeof(float) : 0;
+#define DNB_L(MT, PPL, KS)                                                                          \
+  hipLaunchKernelGGL((k_conv1x1_v3<MT, PPL, KS>), grid, dim3(64 * nw), lds, st, in, in_stride, packed, \
+                     K16, out, out_stride, cin, cout, hw)
+#define DNB_L2(MT)                                                                   \
+  do {                                                                               \
+    if (ksplit) { if (ppl == 4) DNB_L(MT, 4, true); else DNB_L(MT, 1, true); }        \
+    else        { if (ppl == 4) DNB_L(MT, 4, false); else DNB_L(MT, 1, false); }      \
+  } while (0)
+    switch (mt) { case 3: DNB_L2(3); break; case 2: DNB_L2(2); break; default: DNB_L2(1); break; }
+#undef DNB_L2
+#undef DNB_L
+    return true;
+  }
+  const bool ksplit = nchunks >= 3;
+  int nw, mt, gy;
+  if (ksplit) {
+    mt = mtiles >= 2 ? 2 : 1; gy = (mtiles + mt - 1) / mt;
+    nw = (nchunks % 4 == 0) ? 4 : (nchunks % 3 == 0 ? 3 : 4);
+  } else {
+    nw = mtiles >= 4 ? 4 : mtiles;
+    mt = mtiles > 4 ? 2 : 1;
+    gy = (mtiles + nw * mt - 1) / (nw * mt);
+  }
+  const int CS = pad4mod32(64 + 2 * w + 8);
+  const size_t tile = (size_t)((cin + 3) & ~3) * CS, red = ksplit ? (size_t)nw * mt * 4 * 256 : 0;
+  const size_t lds = (tile > red ? tile : red) * sizeof(float);
+  if (lds > 64 * 1024) return false;
+  dim3 grid((unsigned)((hw + 63) / 64), (unsigned)gy, (unsigned)n);
+#define DNB_L(MT, KS)                                                                                  \
+  hipLaunchKernelGGL((k_conv3x3_v3<MT, KS>), grid, dim3(64 * nw), lds, st, in, in_stride, packed, M16,  \
+                     K16, out, out_stride, cin, cout, h, w, CS)
+  if (ksplit) { if (mt == 2) DNB_L(2, true); else DNB_L(1, true); }
+  else        { if (mt == 2) DNB_L(2, false); else DNB_L(1, false); }
+#undef DNB_L
+  return true;
+}
+
+// ---- weight gradient plans (shared by the scratch-size query and the launcher)
+
+struct WgFastPlan {
+  bool ok;
+  int mtw, ctw, gy, gz, gx;
+  int spi, total_steps, steps_per_wg;  // 1x1
+  int tiles_per_img, nms, PA;          // 3x3
+  size_t lds;
+};
+
+static WgFastPlan plan_wgrad_fast(int n, int cin, int cout, int h, int w, int taps) {
+  WgFastPlan p{};
+  const int hw = h * w, mtiles = (cout + 15) / 16, ctiles = (cin + 15) / 16;
+  p.ok = hw % 4 == 0 && (taps == 1 || (w % 4 == 0 && w >= 4));
+  if (!p.ok) return p;
+  if (taps == 1) {
+    p.mtw = mtiles >= 3 ? 3 : mtiles;
+    p.ctw = ctiles >= 4 ? 4 : ctiles;
+    p.gy = (ctiles + p.ctw - 1) / p.ctw;
+    p.gz = (mtiles + p.mtw - 1) / p.mtw;
+    p.spi = (hw + 15) / 16;
+    p.total_steps = n * p.spi;
+    // about 512 workgroups in all, 1..8 steps per wave
+    int spw = (int)(((int64_t)p.total_steps * p.gy * p.gz + 4 * 512 - 1) / (4 * 512));
+    if (spw < 1) spw = 1;
+    if (spw > 8) spw = 8;
+    p.steps_per_wg = 4 * spw;
+    p.gx = (p.total_steps + p.steps_per_wg - 1) / p.steps_per_wg;
+    p.lds = (size_t)p.mtw * p.ctw * 256 * sizeof(float);
+  } else {
+    p.mtw = mtiles >= 2 ? 2 : 1;
+    p.ctw = p.mtw == 2 ? (ctiles >= 2 ? 2 : 1) : (ctiles >= 3 ? 3 : ctiles);
+    p.gy = (ctiles + p.ctw - 1) / p.ctw;
+    p.gz = (mtiles + p.mtw - 1) / p.mtw;
+    // 64, 128 or 256 pixels per workgroup: the largest that fits LDS and still gives >= 256
+    // workgroups
+    p.nms = 1;
+    for (int nms = 4; nms >= 2; nms >>= 1) {
+      const int tpix = 64 * nms;
+      if (tpix / 2 >= hw) continue;
+      if ((size_t)p.ctw * 16 * pad4mod32(tpix + 2 * w + 8) * sizeof(float) > 64 * 1024) continue;
+      if ((int64_t)((hw + tpix - 1) / tpix) * n * p.gy * p.gz >= 256) { p.nms = nms; break; }
+    }
+    const int tpix = 64 * p.nms;
+    p.tiles_per_img = (hw + tpix - 1) / tpix;
+    p.gx = n * p.tiles_per_img;
+    p.PA = pad4mod32(tpix + 2 * w + 8);
+    size_t tile = (size_t)p.ctw * 16 * p.PA, red = (size_t)p.mtw * p.ctw * 9 * 256;
+    p.lds = (tile > red ? tile : red) * sizeof(float);
+    if (p.lds > 64 * 1024) p.ok = false;
+  }
+  return p;
+}
+
+size_t conv_wgrad_fast_partial_floats(int n, int cin, int cout, int h, int w, int taps) {
+  const WgFastPlan p = plan_wgrad_fast(n, cin, cout, h, w, taps);
+  return p.ok ? (size_t)p.gx * cin * cout * taps : 0;
+}
+
+// Returns false if the fast path does not apply; otherwise launches and reports the number
+// of partials to add in *splits.
+bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
+                       float* partials, int n, int cin, int cout, int h, int w, int taps,
+                       int* splits, hipStream_t st) {
+  if (in_stride % 4 || g_stride % 4 || !aligned16(in) || !aligned16(g)) return false;
+  const WgFastPlan p = plan_wgrad_fast(n, cin, cout, h, w, taps);
+  if (!p.ok) return false;
+  dim3 grid((unsigned)p.gx, (unsigned)p.gy, (unsigned)p.gz);
+  const int hw = h * w;
+  if (taps == 1) {
+#define DNB_L(M, C)                                                                                  \
+  hipLaunchKernelGGL((k_wgrad1x1_fast<M, C>), grid, dim3(256), p.lds, st, in, in_stride, g, g_stride, \
+                     partials, cin, cout, hw, p.spi, p.total_steps, p.steps_per_wg)
+    const int key = p.mtw * 10 + p.ctw;
+    switch (key) {
+      case 34: DNB_L(3, 4); break; case 33: DNB_L(3, 3); break; case 32: DNB_L(3, 2); break; case 31: DNB_L(3, 1); break;
+      case 24: DNB_L(2, 4); break; case 23: DNB_L(2, 3); break; case 22: DNB_L(2, 2); break; case 21: DNB_L(2, 1); break;
+      case 14: DNB_L(1, 4); break; case 13: DNB_L(1, 3); break; case 12: DNB_L(1, 2); break; default: DNB_L(1, 1); break;
+    }
+#undef DNB_L
+  } else {
+#define DNB_L(M, C)                                                                                  \
+  hipLaunchKernelGGL((k_wgrad3x3_fast<M, C>), grid, dim3(256), p.lds, st, in, in_stride, g, g_stride, \
+                     partials, cin, cout, h, w, p.tiles_per_img, p.nms, p.PA)
+    const int key = p.mtw * 10 + p.ctw;
+    switch (key) {
+      case 22: DNB_L(2, 2); break; case 21: DNB_L(2, 1); break;
+      case 13: DNB_L(1, 3); break; case 12: DNB_L(1, 2); break; default: DNB_L(1, 1); break;
+    }
+#undef DNB_L
+  }
+  *splits = p.gx;
+  return true;
+}
+
+}  // namespace dnb

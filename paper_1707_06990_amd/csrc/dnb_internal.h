@@ -48,11 +48,24 @@ struct WeightView {
   int flip;
 };
 
+// Packed weights for the fast kernels: [taps][cout16][cin16], zero padded to multiples of 16,
+// K index permuted inside each 16-chunk (see dnb_conv_f32_fast.hip).
+size_t packed_weight_floats(int cout, int cin, int taps);
+hipError_t launch_pack_weights(WeightView wv, int cout, int cin, int taps, float* packed, hipStream_t st);
+// All layers of a block in one launch.  Layer l (input width c) occupies packed_layer_floats
+// floats: 1x1 forward [B16][c16], 1x1 dgrad [c16][B16], 3x3 forward [9][k16][B16],
+// 3x3 dgrad [9][B16][k16], in that order.
+size_t packed_layer_floats(int c, int k, int B);
+hipError_t launch_pack_block_weights(const float* params, float* packed, int c0, int k, int B, int m,
+                                     hipStream_t st);
+
 // out[n][m][q] = sum_{c,t} W(m,c,t) * in[n][c][q + shift(t)], zero outside the image.
 // taps = 1 or 9.  Used for forward (W = OIHW as is) and data gradient (transposed, flipped).
-hipError_t launch_conv_igemm(const float* in, int64_t in_stride, WeightView wv, float* out,
-                             int64_t out_stride, int n, int cin, int cout, int h, int w, int taps,
-                             hipStream_t st);
+// `packed` (may be null) is the same weight view packed by launch_pack_weights; with it, shapes
+// whose pixel counts and strides are multiples of 4 take the fast kernels.
+hipError_t launch_conv_igemm(const float* in, int64_t in_stride, WeightView wv, const float* packed,
+                             float* out, int64_t out_stride, int n, int cin, int cout, int h, int w,
+                             int taps, hipStream_t st);
 
 // dW[m][c][t] = sum_{n,q} g[n][m][q] * in[n][c][q + shift(t)]  (OIHW result).
 int conv_wgrad_splits(int n, int cin, int cout, int h, int w, int taps);

@@ -123,6 +123,9 @@ CONV_SHAPES = [
     (3, 20, 12, 9, 7, 3), (1, 5, 3, 1, 1, 3), (2, 7, 5, 2, 3, 3), (1, 17, 33, 5, 5, 1),
     (2, 52, 48, 32, 32, 1), (2, 48, 12, 32, 32, 3), (2, 96, 24, 16, 16, 3),
     (1, 70, 100, 6, 6, 1), (2, 9, 200, 5, 4, 1), (1, 12, 48, 11, 13, 3), (4, 30, 64, 7, 7, 3),
+    # aligned shapes (16-byte fast kernels): wide K, many M tiles, tiny and ragged images, channel tails
+    (2, 330, 48, 8, 8, 1), (1, 200, 48, 16, 16, 1), (3, 36, 48, 4, 4, 1), (2, 16, 8, 4, 4, 3),
+    (1, 32, 16, 8, 56, 3), (2, 28, 20, 12, 12, 3), (2, 100, 36, 8, 8, 3), (5, 60, 64, 8, 8, 3), (1, 24, 48, 20, 20, 1),
 ]
 
 
@@ -135,9 +138,11 @@ def test_conv_forward_dgrad_wgrad(dnb, oracle, n, cin, cout, h, w, ks):
     hw = h * w
     d_x, d_w, d_g = dev(x), dev(wgt), dev(g)
     out = torch.full((n, cout, h, w), float("nan"), device="cuda")
-    dnb.dnb_op_conv_forward(d_x, cin * hw, d_w, out, cout * hw, n, cin, cout, h, w, ks)
+    pk = torch.full((dnb.dnb_op_conv_scratch_bytes(cin, cout, ks) // 4,), float("nan"), device="cuda")
+    dnb.dnb_op_conv_forward(d_x, cin * hw, d_w, out, cout * hw, n, cin, cout, h, w, ks, pk)
     din = torch.full((n, cin, h, w), float("nan"), device="cuda")
-    dnb.dnb_op_conv_dgrad(d_g, cout * hw, d_w, din, cin * hw, n, cin, cout, h, w, ks)
+    pk2 = torch.full_like(pk, float("nan"))
+    dnb.dnb_op_conv_dgrad(d_g, cout * hw, d_w, din, cin * hw, n, cin, cout, h, w, ks, pk2)
     dw = torch.full(wgt.shape, float("nan"), device="cuda")
     scratch = torch.empty(max(16, dnb.dnb_op_conv_wgrad_scratch_bytes(n, cin, cout, h, w, ks)), dtype=torch.uint8, device="cuda")
     dnb.dnb_op_conv_wgrad(d_x, cin * hw, d_g, cout * hw, dw, n, cin, cout, h, w, ks, scratch)
@@ -159,7 +164,8 @@ def test_conv_on_channel_slices_of_wider_slabs(dnb, oracle):
     wide_out = torch.full((n, 40, h, w), -3.0, device="cuda")
     x_view = d_in.data_ptr() + 4 * 4 * hw          # channels 4..4+cin
     o_view = wide_out.data_ptr() + 4 * 20 * hw     # channels 20..32
-    dnb.dnb_op_conv_forward(x_view, (cin + 10) * hw, dev(wgt), o_view, 40 * hw, n, cin, cout, h, w, 3)
+    pk = torch.empty(dnb.dnb_op_conv_scratch_bytes(cin, cout, 3), dtype=torch.uint8, device="cuda")
+    dnb.dnb_op_conv_forward(x_view, (cin + 10) * hw, dev(wgt), o_view, 40 * hw, n, cin, cout, h, w, 3, pk)
     torch.cuda.synchronize()
     res = wide_out.cpu().numpy()
     assert_close(res[:, 20:32], oracle.conv_forward(wide_in[:, 4:4 + cin], wgt), TOL, "slice conv")
