@@ -35,6 +35,7 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-compare", action="store_true", help="skip timing the other schedule")
+    ap.add_argument("--only-block", type=int, default=-1, help="time a single dense block of the workload (diagnostic)")
     return ap.parse_args()
 
 
@@ -187,6 +188,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     blocks, wname = workload_blocks(wl, a.workload, a.batch)
+    if a.only_block >= 0:
+        blocks = [blocks[a.only_block]]
+        wname += f" [only dense block {a.only_block}]"
     batch = blocks[0].n
     sched = {"shared": dnb.DNB_SCHED_SHARED, "store_all": dnb.DNB_SCHED_STORE_ALL}
     use_graph = not a.no_graph

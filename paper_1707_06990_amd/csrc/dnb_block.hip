@@ -229,7 +229,11 @@ int dnb_block_forward(dnb_block* b, const void* x0v, const void* paramsv, void* 
   const size_t B16 = (size_t)((B + 15) & ~15), k16 = (size_t)((k + 15) & ~15);
   DNB_TRY(launch_pack_block_weights(params, pack, d.c0, k, B, m, st));
   DNB_TRY(launch_copy_slab(x0, (int64_t)d.c0 * hw, y, ys, n, (int64_t)d.c0 * hw, st));
-  DNB_TRY(launch_bn_stats(y, ys, n, d.c0, hw, d.eps, mean_y, istd_y, part, st));
+  // statistics are reduced to per-split partials by one kernel and merged by the first kernel
+  // that needs them; `fresh` tracks which channels of y still only have partials in `part`
+  int ysplits = 0, bsplits = 0;
+  DNB_TRY(launch_bn_stats_partial(y, ys, n, d.c0, hw, part, &ysplits, st));
+  int fresh_lo = 0, fresh_hi = d.c0;
   for (int l = 1; l <= m; ++l) {
     const int c = c_in(d, l);
     const LayerParams p = layer_ptrs<LayerParams, const float>(b, params, l);
@@ -241,20 +245,22 @@ int dnb_block_forward(dnb_block* b, const void* x0v, const void* paramsv, void* 
     float* istd_b = mean_b + B;
     // concat -> storage 1 and BN+ReLU -> storage 2, one pass over the features
     DNB_TRY(launch_bn_relu(y, ys, S2, (int64_t)c * hw, S1, (int64_t)c * hw, n, c, hw, p.g1, p.b1,
-                           mean_y, istd_y, st));
+                           StatsSrc{mean_y, istd_y, part, ysplits, fresh_lo, fresh_hi, d.eps}, st));
     const size_t c16 = (size_t)((c + 15) & ~15);
     const float* pk1 = pack + b->pk[l];               // 1x1 forward
     const float* pk3 = pk1 + 2 * B16 * c16;           // 3x3 forward
     DNB_TRY(launch_conv_igemm(S2, (int64_t)c * hw, WeightView{p.W1, c, 1, 0}, pk1, bl, (int64_t)B * hw,
                               n, c, B, d.h, d.w, 1, st));
-    DNB_TRY(launch_bn_stats(bl, (int64_t)B * hw, n, B, hw, d.eps, mean_b, istd_b, part, st));
+    DNB_TRY(launch_bn_stats_partial(bl, (int64_t)B * hw, n, B, hw, part, &bsplits, st));
     DNB_TRY(launch_bn_relu(bl, (int64_t)B * hw, S3, (int64_t)B * hw, nullptr, 0, n, B, hw, p.g2, p.b2,
-                           mean_b, istd_b, st));
+                           StatsSrc{mean_b, istd_b, part, bsplits, 0, B, d.eps}, st));
     float* xl = y + (int64_t)c * hw;  // x_l goes straight into its channel range of y
     DNB_TRY(launch_conv_igemm(S3, (int64_t)B * hw, WeightView{p.W3, (int64_t)B * 9, 9, 0}, pk3, xl, ys,
                               n, B, k, d.h, d.w, 9, st));
-    if (l < m)
-      DNB_TRY(launch_bn_stats(xl, ys, n, k, hw, d.eps, mean_y + c, istd_y + c, part, st));
+    if (l < m) {
+      DNB_TRY(launch_bn_stats_partial(xl, ys, n, k, hw, part, &ysplits, st));
+      fresh_lo = c; fresh_hi = c + k;
+    }
   }
   return DNB_OK;
 }
@@ -298,7 +304,7 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
 
     if (recompute)  // re-populate storage 3 from the kept b_l and its cached statistics
       DNB_TRY(launch_bn_relu(bl, (int64_t)B * hw, S3, (int64_t)B * hw, nullptr, 0, n, B, hw, p.g2,
-                             p.b2, mean_b, istd_b, st));
+                             p.b2, StatsSrc{mean_b, istd_b, nullptr, 0, 0, 0, d.eps}, st));
     DNB_TRY(launch_conv_wgrad(S3, (int64_t)B * hw, gl, ys, gp.W3, n, B, k, d.h, d.w, 9, part, st));
     const size_t c16 = (size_t)((c + 15) & ~15);
     const float* pk1t = pack + b->pk[l] + B16 * c16;                    // 1x1 data gradient
@@ -309,7 +315,7 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
                                n, B, hw, p.g2, p.b2, mean_b, istd_b, gp.g2, gp.b2, part, st));
     if (recompute)  // re-populate storage 1 and 2 for this layer
       DNB_TRY(launch_bn_relu(y, ys, S2, (int64_t)c * hw, S1, (int64_t)c * hw, n, c, hw, p.g1, p.b1,
-                             mean_y, istd_y, st));
+                             StatsSrc{mean_y, istd_y, nullptr, 0, 0, 0, d.eps}, st));
     DNB_TRY(launch_conv_wgrad(S2, (int64_t)c * hw, dS3, (int64_t)B * hw, gp.W1, n, c, B, d.h, d.w, 1,
                               part, st));
     DNB_TRY(launch_conv_igemm(dS3, (int64_t)B * hw, WeightView{p.W1, 1, c, 0}, pk1t, dS2, (int64_t)c * hw,
@@ -354,8 +360,8 @@ int dnb_op_bn_relu(const void* x, int64_t x_stride, void* out, int64_t out_strid
   if (!x || !out || !gamma || !beta || !mean || !istd) return DNB_E_NULL;
   if (n < 1 || c < 1 || hw < 1) return DNB_E_RANGE;
   DNB_TRY(launch_bn_relu((const float*)x, x_stride, (float*)out, out_stride, nullptr, 0, (int)n, (int)c,
-                         (int)hw, (const float*)gamma, (const float*)beta, (const float*)mean,
-                         (const float*)istd, (hipStream_t)stream));
+                         (int)hw, (const float*)gamma, (const float*)beta,
+                         StatsSrc{(float*)mean, (float*)istd, nullptr, 0, 0, 0, 0.f}, (hipStream_t)stream));
   return DNB_OK;
 }
 

@@ -85,6 +85,23 @@ __global__ __launch_bounds__(kThreads) void k_copy_slab(const float* __restrict_
   }
 }
 
+// ----------------------------------------------------------------------------- row iteration
+
+// A workgroup of the BN kernels below owns ONE channel and a range of images: its elements are
+// rows of hw contiguous floats, one per image.  RowIter walks (image, vector-in-row) pairs with
+// a stride of blockDim threads without a division per element.
+struct RowIter {
+  int img, q, dimg, dq, hwv;
+  __device__ __forceinline__ RowIter(int hwv_, int tid, int nthr) : hwv(hwv_) {
+    img = tid / hwv_; q = tid - img * hwv_;
+    dimg = nthr / hwv_; dq = nthr - dimg * hwv_;
+  }
+  __device__ __forceinline__ void next() {
+    img += dimg; q += dq;
+    if (q >= hwv) { q -= hwv; ++img; }
+  }
+};
+
 // ----------------------------------------------------------------------------- BN statistics
 
 // grid (c, splits): workgroup (ch, s) reduces images [s*ipb, min(n,(s+1)*ipb)) of channel ch
@@ -95,25 +112,22 @@ __global__ __launch_bounds__(kThreads) void k_bn_stats_partial(const float* __re
                                                                int ipb, float* __restrict__ part) {
   __shared__ float red[kThreads / 64];
   const int ch = blockIdx.x, s = blockIdx.y, splits = gridDim.y;
-  const int n0 = s * ipb, n1 = min(n, n0 + ipb);
+  const int n0 = s * ipb, n1 = min(n, n0 + ipb), ni = n1 - n0;
   const int hwv = hw / V;
-  const int total = (n1 - n0) * hwv;
-  const float* xc = x + (int64_t)ch * hw;
+  const float* xc = x + (int64_t)n0 * stride + (int64_t)ch * hw;
   float acc = 0.f;
-  for (int v = threadIdx.x; v < total; v += blockDim.x) {
-    const int img = v / hwv, q = v - img * hwv;
+  for (RowIter it(hwv, threadIdx.x, blockDim.x); it.img < ni; it.next()) {
     float t[V];
-    Vec<V>::ld(xc + (int64_t)(n0 + img) * stride + (int64_t)q * V, t);
+    Vec<V>::ld(xc + (int64_t)it.img * stride + (int64_t)it.q * V, t);
 #pragma unroll
     for (int e = 0; e < V; ++e) acc += t[e];
   }
-  const float cnt = (float)((n1 - n0) * hw);
+  const float cnt = (float)ni * (float)hw;
   const float mu = block_sum(acc, red) / cnt;
   float m2 = 0.f;
-  for (int v = threadIdx.x; v < total; v += blockDim.x) {
-    const int img = v / hwv, q = v - img * hwv;
+  for (RowIter it(hwv, threadIdx.x, blockDim.x); it.img < ni; it.next()) {
     float t[V];
-    Vec<V>::ld(xc + (int64_t)(n0 + img) * stride + (int64_t)q * V, t);
+    Vec<V>::ld(xc + (int64_t)it.img * stride + (int64_t)it.q * V, t);
 #pragma unroll
     for (int e = 0; e < V; ++e) {
       const float d = t[e] - mu;
@@ -127,47 +141,99 @@ __global__ __launch_bounds__(kThreads) void k_bn_stats_partial(const float* __re
   }
 }
 
-// One thread per channel merges the splits in index order (pairwise update of
-// count/mean/M2), then mean and 1/sqrt(M2/P + eps).
-__global__ void k_bn_stats_finalize(const float* __restrict__ part, int c, int splits, float eps,
-                                    float* __restrict__ mean, float* __restrict__ istd) {
-  const int ch = blockIdx.x * blockDim.x + threadIdx.x;
-  if (ch >= c) return;
-  const float* p = part + (int64_t)ch * splits * 3;
-  float cnt = p[0], mu = p[1], m2 = p[2];
-  for (int s = 1; s < splits; ++s) {
-    const float cb = p[3 * s], mb = p[3 * s + 1], m2b = p[3 * s + 2];
-    const float tot = cnt + cb, d = mb - mu;
-    mu = mu + d * (cb / tot);
-    m2 = m2 + m2b + d * d * (cnt * cb / tot);
-    cnt = tot;
+// Merges the (count, mean, M2) partials of one channel across the lanes of a wave (lane s
+// holds split s, lanes past `splits` hold count 0).  Pairwise-update formula; both lanes of
+// a butterfly pair evaluate the same expression (lower lane's value first), so every lane
+// ends with the same bits and every caller gets the same bits from the same partials.
+__device__ __forceinline__ void merge_stats_wave(float& cnt, float& mu, float& m2) {
+  const int lane = threadIdx.x & 63;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const float oc = __shfl_xor(cnt, off, 64), om = __shfl_xor(mu, off, 64), o2 = __shfl_xor(m2, off, 64);
+    const bool hi = (lane & off) != 0;
+    const float ca = hi ? oc : cnt, ma = hi ? om : mu, m2a = hi ? o2 : m2;
+    const float cb = hi ? cnt : oc, mb = hi ? mu : om, m2b = hi ? m2 : o2;
+    const float tot = __fadd_rn(ca, cb);
+    if (cb == 0.f) { cnt = ca; mu = ma; m2 = m2a; }
+    else if (ca == 0.f) { cnt = cb; mu = mb; m2 = m2b; }
+    else {
+      const float d = __fsub_rn(mb, ma);
+      mu = __fmaf_rn(d, __fdiv_rn(cb, tot), ma);
+      m2 = __fadd_rn(__fadd_rn(m2a, m2b), __fmul_rn(__fmul_rn(d, d), __fdiv_rn(__fmul_rn(ca, cb), tot)));
+      cnt = tot;
+    }
   }
-  mean[ch] = mu;
-  istd[ch] = 1.0f / sqrtf(m2 / cnt + eps);
+}
+
+// Finalised statistics of channel ch for the calling workgroup.  Channels in
+// [fresh_lo, fresh_hi) still only have partials (from the latest k_bn_stats_partial): wave 0
+// merges them; the workgroup with blockIdx.y == 0 also stores mean / inverse std so later
+// kernels read them.  Returns (mean, istd) to every thread.
+__device__ __forceinline__ void channel_stats(int ch, float* mean, float* istd, const float* part,
+                                              int splits, int fresh_lo, int fresh_hi, float eps,
+                                              float* sh, float& mu, float& is) {
+  if (threadIdx.x < 64) {
+    if (ch >= fresh_lo && ch < fresh_hi) {
+      const int lane = threadIdx.x;
+      const float* p = part + ((int64_t)(ch - fresh_lo) * splits + lane) * 3;
+      float cnt = 0.f, m = 0.f, m2 = 0.f;
+      if (lane < splits) { cnt = p[0]; m = p[1]; m2 = p[2]; }
+      merge_stats_wave(cnt, m, m2);
+      const float iv = __fdiv_rn(1.0f, __fsqrt_rn(__fadd_rn(__fdiv_rn(m2, cnt), eps)));
+      if (lane == 0) {
+        sh[0] = m; sh[1] = iv;
+        if (blockIdx.y == 0) { mean[ch] = m; istd[ch] = iv; }
+      }
+    } else if (threadIdx.x == 0) {
+      sh[0] = mean[ch]; sh[1] = istd[ch];
+    }
+  }
+  __syncthreads();
+  mu = sh[0]; is = sh[1];
+}
+
+// One thread per channel merges the splits; used by the stand-alone statistics entry point.
+__global__ __launch_bounds__(64) void k_bn_stats_finalize(const float* __restrict__ part, int c, int splits,
+                                                          float eps, float* __restrict__ mean,
+                                                          float* __restrict__ istd) {
+  const int ch = blockIdx.x, lane = threadIdx.x;
+  const float* p = part + ((int64_t)ch * splits + lane) * 3;
+  float cnt = 0.f, m = 0.f, m2 = 0.f;
+  if (lane < splits) { cnt = p[0]; m = p[1]; m2 = p[2]; }
+  merge_stats_wave(cnt, m, m2);
+  if (lane == 0) {
+    mean[ch] = m;
+    istd[ch] = __fdiv_rn(1.0f, __fsqrt_rn(__fadd_rn(__fdiv_rn(m2, cnt), eps)));
+  }
 }
 
 // ----------------------------------------------------------------------------- BN apply + ReLU
 
+// grid (c, splits).  out = max(0, fma(x, scale, shift)); COPY also writes the raw x (the
+// concatenation into storage 1 and its BN+ReLU into storage 2 in one pass over the features).
 template <int V, bool COPY>
 __global__ __launch_bounds__(kThreads) void k_bn_relu(
     const float* __restrict__ x, int64_t x_stride, float* __restrict__ out, int64_t out_stride,
-    float* __restrict__ copy_out, int64_t copy_stride, int c, int hw, int64_t total /*vectors*/,
-    const float* __restrict__ gamma, const float* __restrict__ beta, const float* __restrict__ mean,
-    const float* __restrict__ istd) {
+    float* __restrict__ copy_out, int64_t copy_stride, int n, int hw, int ipb,
+    const float* __restrict__ gamma, const float* __restrict__ beta, float* mean, float* istd,
+    const float* __restrict__ part, int splits, int fresh_lo, int fresh_hi, float eps) {
+  __shared__ float sh[2];
+  const int ch = blockIdx.x, n0 = blockIdx.y * ipb, ni = min(n, n0 + ipb) - n0;
+  float mu, is, scale, shift;
+  channel_stats(ch, mean, istd, part, splits, fresh_lo, fresh_hi, eps, sh, mu, is);
+  bn_fold(gamma[ch], beta[ch], mu, is, scale, shift);
   const int hwv = hw / V;
-  for (int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x; v < total;
-       v += (int64_t)gridDim.x * kThreads) {
-    const int row = (int)(v / hwv), q = (int)(v - (int64_t)row * hwv);
-    const int img = row / c, ch = row - img * c;
-    float scale, shift;
-    bn_fold(gamma[ch], beta[ch], mean[ch], istd[ch], scale, shift);
-    const int64_t inner = (int64_t)ch * hw + (int64_t)q * V;
+  const int64_t inner = (int64_t)ch * hw;
+  const float* xp = x + (int64_t)n0 * x_stride + inner;
+  float* op = out + (int64_t)n0 * out_stride + inner;
+  float* cp = COPY ? copy_out + (int64_t)n0 * copy_stride + inner : nullptr;
+  for (RowIter it(hwv, threadIdx.x, blockDim.x); it.img < ni; it.next()) {
     float t[V], r[V];
-    Vec<V>::ld(x + (int64_t)img * x_stride + inner, t);
+    Vec<V>::ld(xp + (int64_t)it.img * x_stride + (int64_t)it.q * V, t);
 #pragma unroll
     for (int e = 0; e < V; ++e) r[e] = fmaxf(__fmaf_rn(t[e], scale, shift), 0.f);
-    Vec<V>::st(out + (int64_t)img * out_stride + inner, r);
-    if (COPY) Vec<V>::st(copy_out + (int64_t)img * copy_stride + inner, t);
+    Vec<V>::st(op + (int64_t)it.img * out_stride + (int64_t)it.q * V, r);
+    if (COPY) Vec<V>::st(cp + (int64_t)it.img * copy_stride + (int64_t)it.q * V, t);
   }
 }
 
@@ -182,19 +248,19 @@ __global__ __launch_bounds__(kThreads) void k_bn_bwd_partial(
     float* __restrict__ part) {
   __shared__ float red[kThreads / 64];
   const int ch = blockIdx.x, s = blockIdx.y, splits = gridDim.y;
-  const int n0 = s * ipb, n1 = min(n, n0 + ipb);
+  const int n0 = s * ipb, ni = min(n, n0 + ipb) - n0;
   const int hwv = hw / V;
-  const int total = (n1 - n0) * hwv;
   float scale, shift;
   const float mu = mean[ch], is = istd[ch];
   bn_fold(gamma[ch], beta[ch], mu, is, scale, shift);
+  const int64_t inner = (int64_t)ch * hw;
+  const float* xp = x + (int64_t)n0 * x_stride + inner;
+  const float* gp = dact + (int64_t)n0 * dact_stride + inner;
   float sb = 0.f, sg = 0.f;
-  for (int v = threadIdx.x; v < total; v += blockDim.x) {
-    const int img = v / hwv, q = v - img * hwv;
-    const int64_t inner = (int64_t)ch * hw + (int64_t)q * V;
+  for (RowIter it(hwv, threadIdx.x, blockDim.x); it.img < ni; it.next()) {
     float t[V], g[V];
-    Vec<V>::ld(x + (int64_t)(n0 + img) * x_stride + inner, t);
-    Vec<V>::ld(dact + (int64_t)(n0 + img) * dact_stride + inner, g);
+    Vec<V>::ld(xp + (int64_t)it.img * x_stride + (int64_t)it.q * V, t);
+    Vec<V>::ld(gp + (int64_t)it.img * dact_stride + (int64_t)it.q * V, g);
 #pragma unroll
     for (int e = 0; e < V; ++e) {
       const float dz = __fmaf_rn(t[e], scale, shift) > 0.f ? g[e] : 0.f;
@@ -210,56 +276,79 @@ __global__ __launch_bounds__(kThreads) void k_bn_bwd_partial(
   }
 }
 
-__global__ void k_bn_bwd_finalize(const float* __restrict__ part, int c, int splits,
-                                  float* __restrict__ dgamma, float* __restrict__ dbeta) {
-  const int ch = blockIdx.x * blockDim.x + threadIdx.x;
-  if (ch >= c) return;
-  const float* p = part + (int64_t)ch * splits * 2;
-  float sb = 0.f, sg = 0.f;
-  for (int s = 0; s < splits; ++s) { sb += p[2 * s]; sg += p[2 * s + 1]; }
-  dbeta[ch] = sb;
-  dgamma[ch] = sg;
-}
-
+// grid (c, splits).  Adds up the channel's partial sums (wave butterfly, every workgroup gets
+// the same bits), then du = scale*(dz - dbeta/P - xhat*dgamma/P).  Split 0 stores dgamma/dbeta.
 template <int V, bool ACC>
 __global__ __launch_bounds__(kThreads) void k_bn_bwd_apply(
     const float* __restrict__ x, int64_t x_stride, const float* dact /* may alias du */,
-    int64_t dact_stride, float* du, int64_t du_stride, int c, int hw, int64_t total,
-    float inv_p, const float* __restrict__ gamma, const float* __restrict__ beta,
+    int64_t dact_stride, float* du, int64_t du_stride, int n, int hw, int ipb, float inv_p,
+    const float* __restrict__ gamma, const float* __restrict__ beta,
     const float* __restrict__ mean, const float* __restrict__ istd,
-    const float* __restrict__ dgamma, const float* __restrict__ dbeta) {
+    const float* __restrict__ part, int psplits, float* __restrict__ dgamma, float* __restrict__ dbeta) {
+  __shared__ float sh[2];
+  const int ch = blockIdx.x, n0 = blockIdx.y * ipb, ni = min(n, n0 + ipb) - n0;
+  if (threadIdx.x < 64) {
+    const int lane = threadIdx.x;
+    float sb = 0.f, sg = 0.f;
+    if (lane < psplits) {
+      const float* p = part + ((int64_t)ch * psplits + lane) * 2;
+      sb = p[0]; sg = p[1];
+    }
+    sb = wave_sum(sb);
+    sg = wave_sum(sg);
+    if (lane == 0) {
+      sh[0] = sb; sh[1] = sg;
+      if (blockIdx.y == 0) { dbeta[ch] = sb; dgamma[ch] = sg; }
+    }
+  }
+  __syncthreads();
+  const float mb = sh[0] * inv_p, mg = sh[1] * inv_p;
+  const float mu = mean[ch], is = istd[ch];
+  float scale, shift;
+  bn_fold(gamma[ch], beta[ch], mu, is, scale, shift);
   const int hwv = hw / V;
-  for (int64_t v = (int64_t)blockIdx.x * kThreads + threadIdx.x; v < total;
-       v += (int64_t)gridDim.x * kThreads) {
-    const int row = (int)(v / hwv), q = (int)(v - (int64_t)row * hwv);
-    const int img = row / c, ch = row - img * c;
-    const float mu = mean[ch], is = istd[ch];
-    float scale, shift;
-    bn_fold(gamma[ch], beta[ch], mu, is, scale, shift);
-    const float mb = dbeta[ch] * inv_p, mg = dgamma[ch] * inv_p;
-    const int64_t inner = (int64_t)ch * hw + (int64_t)q * V;
+  const int64_t inner = (int64_t)ch * hw;
+  const float* xp = x + (int64_t)n0 * x_stride + inner;
+  const float* gp = dact + (int64_t)n0 * dact_stride + inner;
+  float* dp = du + (int64_t)n0 * du_stride + inner;
+  for (RowIter it(hwv, threadIdx.x, blockDim.x); it.img < ni; it.next()) {
     float t[V], g[V], r[V];
-    Vec<V>::ld(x + (int64_t)img * x_stride + inner, t);
-    Vec<V>::ld(dact + (int64_t)img * dact_stride + inner, g);
-    float* dp = du + (int64_t)img * du_stride + inner;
-    if (ACC) Vec<V>::ld(dp, r);
+    const int64_t qo = (int64_t)it.q * V;
+    Vec<V>::ld(xp + (int64_t)it.img * x_stride + qo, t);
+    Vec<V>::ld(gp + (int64_t)it.img * dact_stride + qo, g);
+    float* d = dp + (int64_t)it.img * du_stride + qo;
+    if (ACC) Vec<V>::ld(d, r);
 #pragma unroll
     for (int e = 0; e < V; ++e) {
       const float dz = __fmaf_rn(t[e], scale, shift) > 0.f ? g[e] : 0.f;
       const float xh = (t[e] - mu) * is;
-      const float d = scale * (dz - mb - xh * mg);
-      r[e] = ACC ? r[e] + d : d;
+      const float v = scale * (dz - mb - xh * mg);
+      r[e] = ACC ? r[e] + v : v;
     }
-    Vec<V>::st(dp, r);
+    Vec<V>::st(d, r);
   }
 }
 
-int splits_for(int n, int c) {
-  // enough workgroups to cover the chip (256 CUs) a few times over, at least one image each
+// Image splits for a (n, c, hw) slab: enough workgroups to cover the chip a few times over,
+// at least ~4 KB per workgroup, at most 64 (one wave merges a channel's partials).
+int splits_for(int n, int c, int hw) {
   int s = (1024 + c - 1) / c;
+  const int min_ipb = (1024 + hw - 1) / hw;
+  const int cap = (n + min_ipb - 1) / min_ipb;
+  if (s > cap) s = cap;
   if (s > n) s = n;
+  if (s > 64) s = 64;
   if (s < 1) s = 1;
   return s;
+}
+
+struct Split { int ipb, gs; };
+Split split_plan(int n, int c, int hw) {
+  const int s = splits_for(n, c, hw);
+  Split p;
+  p.ipb = (n + s - 1) / s;
+  p.gs = (n + p.ipb - 1) / p.ipb;  // every split non-empty
+  return p;
 }
 
 }  // namespace
@@ -280,46 +369,51 @@ hipError_t launch_copy_slab(const float* src, int64_t src_stride, float* dst, in
   return hipGetLastError();
 }
 
-int bn_stats_splits(int n, int c, int hw) { (void)hw; return splits_for(n, c); }
-size_t bn_stats_partial_floats(int n, int c, int hw) { return (size_t)c * bn_stats_splits(n, c, hw) * 3; }
+size_t bn_stats_partial_floats(int n, int c, int hw) { return (size_t)c * splits_for(n, c, hw) * 3; }
+
+hipError_t launch_bn_stats_partial(const float* x, int64_t stride, int n, int c, int hw,
+                                   float* partials, int* splits, hipStream_t st) {
+  const Split p = split_plan(n, c, hw);
+  *splits = p.gs;
+  if (c <= 0) return hipSuccess;
+  const bool v4 = (hw % 4 == 0) && (stride % 4 == 0) && aligned16(x);
+  dim3 grid((unsigned)c, (unsigned)p.gs);
+  if (v4)
+    hipLaunchKernelGGL(k_bn_stats_partial<4>, grid, dim3(kThreads), 0, st, x, stride, n, hw, p.ipb, partials);
+  else
+    hipLaunchKernelGGL(k_bn_stats_partial<1>, grid, dim3(kThreads), 0, st, x, stride, n, hw, p.ipb, partials);
+  return hipGetLastError();
+}
 
 hipError_t launch_bn_stats(const float* x, int64_t stride, int n, int c, int hw, float eps,
                            float* mean, float* istd, float* partials, hipStream_t st) {
   if (c <= 0) return hipSuccess;
-  const int splits = bn_stats_splits(n, c, hw);
-  const int ipb = (n + splits - 1) / splits;
-  const int gs = (n + ipb - 1) / ipb;  // every split non-empty
-  const bool v4 = (hw % 4 == 0) && (stride % 4 == 0) && aligned16(x);
-  const int work = ipb * (v4 ? hw / 4 : hw);
-  const int threads = work <= 64 ? 64 : (work <= 128 ? 128 : kThreads);
-  dim3 grid((unsigned)c, (unsigned)gs);
-  if (v4)
-    hipLaunchKernelGGL(k_bn_stats_partial<4>, grid, dim3(threads), 0, st, x, stride, n, hw, ipb, partials);
-  else
-    hipLaunchKernelGGL(k_bn_stats_partial<1>, grid, dim3(threads), 0, st, x, stride, n, hw, ipb, partials);
-  hipLaunchKernelGGL(k_bn_stats_finalize, dim3((c + 63) / 64), dim3(64), 0, st, partials, c, gs, eps, mean, istd);
+  int splits = 0;
+  hipError_t e = launch_bn_stats_partial(x, stride, n, c, hw, partials, &splits, st);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(k_bn_stats_finalize, dim3((unsigned)c), dim3(64), 0, st, partials, c, splits, eps, mean, istd);
   return hipGetLastError();
 }
 
 hipError_t launch_bn_relu(const float* x, int64_t x_stride, float* out, int64_t out_stride,
                           float* copy_out, int64_t copy_stride, int n, int c, int hw,
-                          const float* gamma, const float* beta, const float* mean,
-                          const float* istd, hipStream_t st) {
+                          const float* gamma, const float* beta, StatsSrc s, hipStream_t st) {
   if (n <= 0 || c <= 0 || hw <= 0) return hipSuccess;
   const bool v4 = (hw % 4 == 0) && (x_stride % 4 == 0) && (out_stride % 4 == 0) && aligned16(x) &&
                   aligned16(out) && (!copy_out || ((copy_stride % 4 == 0) && aligned16(copy_out)));
-  const int64_t total = (int64_t)n * c * (v4 ? hw / 4 : hw);
-  dim3 grid(grid_for(total, kThreads * 2, 65535 * 4));
+  const Split p = split_plan(n, c, hw);
+  dim3 grid((unsigned)c, (unsigned)p.gs);
 #define DNB_LAUNCH_BNRELU(V, C)                                                                     \
   hipLaunchKernelGGL((k_bn_relu<V, C>), grid, dim3(kThreads), 0, st, x, x_stride, out, out_stride, \
-                     copy_out, copy_stride, c, hw, total, gamma, beta, mean, istd)
+                     copy_out, copy_stride, n, hw, p.ipb, gamma, beta, s.mean, s.istd, s.part,    \
+                     s.splits, s.fresh_lo, s.fresh_hi, s.eps)
   if (v4) { if (copy_out) DNB_LAUNCH_BNRELU(4, true); else DNB_LAUNCH_BNRELU(4, false); }
   else    { if (copy_out) DNB_LAUNCH_BNRELU(1, true); else DNB_LAUNCH_BNRELU(1, false); }
 #undef DNB_LAUNCH_BNRELU
   return hipGetLastError();
 }
 
-size_t bn_bwd_partial_floats(int n, int c, int hw) { (void)hw; return (size_t)c * splits_for(n, c) * 2; }
+size_t bn_bwd_partial_floats(int n, int c, int hw) { return (size_t)c * splits_for(n, c, hw) * 2; }
 
 hipError_t launch_bn_relu_bwd(const float* x, int64_t x_stride, const float* dact,
                               int64_t dact_stride, float* du, int64_t du_stride, bool accumulate,
@@ -327,28 +421,21 @@ hipError_t launch_bn_relu_bwd(const float* x, int64_t x_stride, const float* dac
                               const float* mean, const float* istd, float* dgamma, float* dbeta,
                               float* partials, hipStream_t st) {
   if (n <= 0 || c <= 0 || hw <= 0) return hipSuccess;
-  const int splits = splits_for(n, c);
-  const int ipb = (n + splits - 1) / splits;
-  const int gs = (n + ipb - 1) / ipb;
+  const Split p = split_plan(n, c, hw);
   const bool v4 = (hw % 4 == 0) && (x_stride % 4 == 0) && (dact_stride % 4 == 0) &&
                   (du_stride % 4 == 0) && aligned16(x) && aligned16(dact) && aligned16(du);
-  const int work = ipb * (v4 ? hw / 4 : hw);
-  const int threads = work <= 64 ? 64 : (work <= 128 ? 128 : kThreads);
-  dim3 rgrid((unsigned)c, (unsigned)gs);
+  dim3 grid((unsigned)c, (unsigned)p.gs);
   if (v4)
-    hipLaunchKernelGGL(k_bn_bwd_partial<4>, rgrid, dim3(threads), 0, st, x, x_stride, dact, dact_stride,
-                       n, hw, ipb, gamma, beta, mean, istd, partials);
+    hipLaunchKernelGGL(k_bn_bwd_partial<4>, grid, dim3(kThreads), 0, st, x, x_stride, dact, dact_stride,
+                       n, hw, p.ipb, gamma, beta, mean, istd, partials);
   else
-    hipLaunchKernelGGL(k_bn_bwd_partial<1>, rgrid, dim3(threads), 0, st, x, x_stride, dact, dact_stride,
-                       n, hw, ipb, gamma, beta, mean, istd, partials);
-  hipLaunchKernelGGL(k_bn_bwd_finalize, dim3((c + 63) / 64), dim3(64), 0, st, partials, c, gs, dgamma, dbeta);
-  const int64_t total = (int64_t)n * c * (v4 ? hw / 4 : hw);
+    hipLaunchKernelGGL(k_bn_bwd_partial<1>, grid, dim3(kThreads), 0, st, x, x_stride, dact, dact_stride,
+                       n, hw, p.ipb, gamma, beta, mean, istd, partials);
   const float inv_p = 1.0f / ((float)n * (float)hw);
-  dim3 grid(grid_for(total, kThreads * 2, 65535 * 4));
 #define DNB_LAUNCH_BNBWD(V, A)                                                                      \
   hipLaunchKernelGGL((k_bn_bwd_apply<V, A>), grid, dim3(kThreads), 0, st, x, x_stride, dact,       \
-                     dact_stride, du, du_stride, c, hw, total, inv_p, gamma, beta, mean, istd,     \
-                     dgamma, dbeta)
+                     dact_stride, du, du_stride, n, hw, p.ipb, inv_p, gamma, beta, mean, istd,     \
+                     partials, p.gs, dgamma, dbeta)
   if (v4) { if (accumulate) DNB_LAUNCH_BNBWD(4, true); else DNB_LAUNCH_BNBWD(4, false); }
   else    { if (accumulate) DNB_LAUNCH_BNBWD(1, true); else DNB_LAUNCH_BNBWD(1, false); }
 #undef DNB_LAUNCH_BNBWD

@@ -13,19 +13,32 @@ namespace dnb {
 hipError_t launch_copy_slab(const float* src, int64_t src_stride, float* dst, int64_t dst_stride,
                             int n, int64_t len, hipStream_t st);
 
-// Per-channel batch statistics of x (n, c, hw; image stride `stride`).
-// `partials` needs bn_stats_partial_floats(n, c) floats of scratch.
-int bn_stats_splits(int n, int c, int hw);
+// Per-channel batch statistics of x (n, c, hw; image stride `stride`): mean and
+// 1/sqrt(biased var + eps).  The reduction is split over image ranges: launch_bn_stats_partial
+// writes (count, mean, M2) per (channel, split) -- bn_stats_partial_floats(n, c, hw) floats --
+// and the first kernel that needs the statistics merges them (StatsSrc below), so the forward
+// chain has no separate finalisation launch.  launch_bn_stats = partials + a finalise kernel.
 size_t bn_stats_partial_floats(int n, int c, int hw);
+hipError_t launch_bn_stats_partial(const float* x, int64_t stride, int n, int c, int hw,
+                                   float* partials, int* splits, hipStream_t st);
 hipError_t launch_bn_stats(const float* x, int64_t stride, int n, int c, int hw, float eps,
                            float* mean, float* istd, float* partials, hipStream_t st);
+
+// Where a kernel finds BN statistics: finalised arrays indexed by channel, except channels in
+// [fresh_lo, fresh_hi), whose partials (index ch - fresh_lo) it merges itself and stores back.
+struct StatsSrc {
+  float* mean;
+  float* istd;
+  const float* part;
+  int splits, fresh_lo, fresh_hi;
+  float eps;
+};
 
 // out = max(0, fma(x, gamma*istd, beta - mean*gamma*istd)); if copy_out != nullptr the raw x
 // is also written there (concatenation and BN+ReLU of the same data in one pass).
 hipError_t launch_bn_relu(const float* x, int64_t x_stride, float* out, int64_t out_stride,
                           float* copy_out, int64_t copy_stride, int n, int c, int hw,
-                          const float* gamma, const float* beta, const float* mean,
-                          const float* istd, hipStream_t st);
+                          const float* gamma, const float* beta, StatsSrc s, hipStream_t st);
 
 // BN+ReLU backward.  Pass 1 reduces dbeta = sum dz, dgamma = sum dz*xhat with
 // dz = dact * [fma(x,scale,shift) > 0]; pass 2 writes
