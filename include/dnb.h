@@ -121,6 +121,12 @@ int dnb_block_forward(dnb_block* b, const void* x0, const void* params, void* y,
 int dnb_block_backward(dnb_block* b, const void* params, const void* y, const void* dy, void* dx0,
                        void* dparams, void* workspace, void* stream);
 
+/* The backward pass runs its two weight-gradient chains on helper streams owned by the block
+ * (created at the first backward call, joined to `stream` before the call's last kernel), so
+ * they overlap the data-gradient chain.  enable = 0 puts everything on `stream` in program
+ * order; results are bit-identical either way.  Default: enabled. */
+int dnb_block_set_concurrency(dnb_block* b, int enable);
+
 const char* dnb_status_string(int status);
 
 /* ---- single operations of the path (fp32 NCHW), exported for tests and

@@ -50,6 +50,7 @@ _SIGS = {
     "dnb_block_param_offset": (C.c_int, [_vp, C.c_int, C.c_int, C.POINTER(_sz), C.POINTER(_sz)]),
     "dnb_block_forward": (C.c_int, [_vp] * 6),
     "dnb_block_backward": (C.c_int, [_vp] * 8),
+    "dnb_block_set_concurrency": (C.c_int, [_vp, C.c_int]),
     "dnb_status_string": (C.c_char_p, [C.c_int]),
     "dnb_op_copy_slab": (C.c_int, [_vp, _i64, _vp, _i64, _i64, _i64, _vp]),
     "dnb_op_bn_scratch_bytes": (_sz, [_i64, _i64, _i64]),
@@ -145,6 +146,10 @@ def dnb_block_forward(b, x0, params, y, workspace, stream=None) -> None:
 def dnb_block_backward(b, params, y, dy, dx0, dparams, workspace, stream=None) -> None:
     _check(_lib.dnb_block_backward(b, _ptr(params), _ptr(y), _ptr(dy), _ptr(dx0), _ptr(dparams),
                                    _ptr(workspace), _stream(stream)))
+
+
+def dnb_block_set_concurrency(b, enable: bool) -> None:
+    _check(_lib.dnb_block_set_concurrency(b, int(bool(enable))))
 
 
 def dnb_op_copy_slab(src, src_stride, dst, dst_stride, n, length, stream=None) -> None:

@@ -20,7 +20,15 @@ struct dnb_block {
   size_t off_G, off_dS2, off_dS3;
   size_t off_stat_y;                         // mean[C_out], istd[C_out]
   std::vector<size_t> off_stat_b;            // per layer mean[B], istd[B]
-  size_t off_part;
+  size_t off_part;                           // reduction partials of the main chain (BN)
+  size_t off_partA, off_partB;               // partials of the 3x3 / 1x1 weight gradients
+  // backward runs three chains: the data-gradient chain on the caller's stream and the two
+  // weight-gradient chains on these helper streams (created at the first backward call)
+  int concurrency;
+  bool streams_ready;
+  hipStream_t sA, sB;
+  std::vector<hipEvent_t> ev;                // per layer: main done, db ready, S1/S2 ready, wgrad1 done
+  hipEvent_t ev_start, ev_endA, ev_endB;
   size_t off_pack;                           // packed weights of all layers
   std::vector<size_t> pk;                    // per layer: float offset of its packed weights
   std::vector<size_t> poff;                  // parameter offsets (elements) per layer
@@ -154,7 +162,7 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
   for (int l = 1; l <= m; ++l) b->off_stat_b[l] = carve((size_t)B * 2 * sizeof(float), false);
   mem.stats_bytes = (uint64_t)((size_t)cout * 2 + (size_t)m * B * 2) * sizeof(float);
 
-  size_t part = 0;
+  size_t part = 0, partA = 0, partB = 0;
   auto need = [&](size_t floats) { if (floats > part) part = floats; };
   need(bn_stats_partial_floats(d.n, d.c0, (int)hw));
   need(bn_stats_partial_floats(d.n, k, (int)hw));
@@ -162,21 +170,43 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
   need(bn_bwd_partial_floats(d.n, B, (int)hw));
   for (int l = 1; l <= m; ++l) {
     need(bn_bwd_partial_floats(d.n, c_in(d, l), (int)hw));
-    need(conv_wgrad_partial_floats(d.n, c_in(d, l), B, d.h, d.w, 1));
+    const size_t f = conv_wgrad_partial_floats(d.n, c_in(d, l), B, d.h, d.w, 1);
+    if (f > partB) partB = f;
   }
-  need(conv_wgrad_partial_floats(d.n, B, k, d.h, d.w, 9));
+  partA = conv_wgrad_partial_floats(d.n, B, k, d.h, d.w, 9);
   b->pk.assign(m + 2, 0);
   size_t pack = 0;
   for (int l = 1; l <= m; ++l) { b->pk[l] = pack; pack += packed_layer_floats(c_in(d, l), k, B); }
-  mem.scratch_bytes = (uint64_t)(part + pack) * sizeof(float);
+  mem.scratch_bytes = (uint64_t)(part + partA + partB + pack) * sizeof(float);
   b->off_part = carve(part * sizeof(float), false);
+  b->off_partA = carve(partA * sizeof(float), false);
+  b->off_partB = carve(partB * sizeof(float), false);
   b->off_pack = carve(pack * sizeof(float), false);
+  b->concurrency = 1;
+  b->streams_ready = false;
   mem.workspace_bytes = (uint64_t)off;
   *out = b;
   return DNB_OK;
 }
 
-void dnb_block_destroy(dnb_block* b) { delete b; }
+void dnb_block_destroy(dnb_block* b) {
+  if (!b) return;
+  if (b->streams_ready) {
+    for (hipEvent_t e : b->ev) (void)hipEventDestroy(e);
+    (void)hipEventDestroy(b->ev_start);
+    (void)hipEventDestroy(b->ev_endA);
+    (void)hipEventDestroy(b->ev_endB);
+    (void)hipStreamDestroy(b->sA);
+    (void)hipStreamDestroy(b->sB);
+  }
+  delete b;
+}
+
+int dnb_block_set_concurrency(dnb_block* b, int enable) {
+  if (!b) return DNB_E_NULL;
+  b->concurrency = enable ? 1 : 0;
+  return DNB_OK;
+}
 
 size_t dnb_block_peak_bytes(const dnb_block* b) { return b ? (size_t)b->mem.peak_bytes : 0; }
 size_t dnb_block_workspace_bytes(const dnb_block* b) { return b ? (size_t)b->mem.workspace_bytes : 0; }
@@ -289,7 +319,37 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
 
   const float* pack = (const float*)(ws + b->off_pack);  // packed by the forward pass
   const size_t B16 = (size_t)((B + 15) & ~15), k16 = (size_t)((k + 15) & ~15);
+  float* partA = (float*)(ws + b->off_partA);
+  float* partB = (float*)(ws + b->off_partB);
+
+  // Three chains.  Only the data-gradient chain (dgrad 3x3 -> BN2 bwd -> dgrad 1x1 -> BN1 bwd)
+  // carries the dependence from layer l to layer l-1; the weight gradients, and the
+  // recomputation that feeds only them, hang off it.  With concurrency on they run on two
+  // helper streams, ordered by events exactly where buffers are shared:
+  //   A: [recompute storage 3] -> wgrad 3x3 -> sum        (needs g_l complete)
+  //   B: [recompute storage 1,2] -> wgrad 1x1 -> sum      (needs db_l; storage 1 also feeds BN1 bwd)
+  const bool conc = b->concurrency != 0;
+  if (conc && !b->streams_ready) {
+    if (hipStreamCreateWithFlags(&b->sA, hipStreamNonBlocking) != hipSuccess) return DNB_E_LAUNCH;
+    if (hipStreamCreateWithFlags(&b->sB, hipStreamNonBlocking) != hipSuccess) return DNB_E_LAUNCH;
+    b->ev.resize((size_t)4 * (m + 2));
+    for (auto& e : b->ev)
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
+    if (hipEventCreateWithFlags(&b->ev_start, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
+    if (hipEventCreateWithFlags(&b->ev_endA, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
+    if (hipEventCreateWithFlags(&b->ev_endB, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
+    b->streams_ready = true;
+  }
+  hipStream_t sA = conc ? b->sA : st, sB = conc ? b->sB : st;
+  enum { EV_MAIN = 0, EV_DB = 1, EV_S12 = 2, EV_WG1 = 3 };
+  auto ev = [&](int l, int which) -> hipEvent_t { return conc ? b->ev[(size_t)4 * l + which] : nullptr; };
+  auto record = [&](hipEvent_t e, hipStream_t s) { return conc ? hipEventRecord(e, s) : hipSuccess; };
+  auto wait = [&](hipStream_t s, hipEvent_t e) { return conc ? hipStreamWaitEvent(s, e, 0) : hipSuccess; };
+
   DNB_TRY(launch_copy_slab((const float*)dyv, ys, G, ys, n, ys, st));
+  DNB_TRY(record(conc ? b->ev_start : nullptr, st));
+  DNB_TRY(wait(sA, conc ? b->ev_start : nullptr));
+  DNB_TRY(wait(sB, conc ? b->ev_start : nullptr));
   for (int l = m; l >= 1; --l) {
     const int c = c_in(d, l);
     const LayerParams p = layer_ptrs<LayerParams, const float>(b, params, l);
@@ -301,28 +361,54 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
     float* mean_b = (float*)(ws + b->off_stat_b[l]);
     float* istd_b = mean_b + B;
     float* gl = G + (int64_t)c * hw;  // complete gradient of x_l: all later layers have added theirs
-
-    if (recompute)  // re-populate storage 3 from the kept b_l and its cached statistics
-      DNB_TRY(launch_bn_relu(bl, (int64_t)B * hw, S3, (int64_t)B * hw, nullptr, 0, n, B, hw, p.g2,
-                             p.b2, StatsSrc{mean_b, istd_b, nullptr, 0, 0, 0, d.eps}, st));
-    DNB_TRY(launch_conv_wgrad(S3, (int64_t)B * hw, gl, ys, gp.W3, n, B, k, d.h, d.w, 9, part, st));
     const size_t c16 = (size_t)((c + 15) & ~15);
     const float* pk1t = pack + b->pk[l] + B16 * c16;                    // 1x1 data gradient
     const float* pk3t = pack + b->pk[l] + 2 * B16 * c16 + 9 * k16 * B16;  // 3x3 data gradient
+
+    // ---- chain A: storage 3 and the 3x3 weight gradient.  g_l is complete once layer l+1's
+    // BN1 backward has run; storage 3 is free because the previous wgrad ran on this stream.
+    if (l < m) DNB_TRY(wait(sA, ev(l + 1, EV_MAIN)));
+    if (recompute)  // re-populate storage 3 from the kept b_l and its cached statistics
+      DNB_TRY(launch_bn_relu(bl, (int64_t)B * hw, S3, (int64_t)B * hw, nullptr, 0, n, B, hw, p.g2,
+                             p.b2, StatsSrc{mean_b, istd_b, nullptr, 0, 0, 0, d.eps}, sA));
+    DNB_TRY(launch_conv_wgrad(S3, (int64_t)B * hw, gl, ys, gp.W3, n, B, k, d.h, d.w, 9, partA, sA));
+
+    // ---- chain B, first half: storage 1 and 2.  Storage 1 was last read by layer l+1's BN1
+    // backward on the main chain; storage 2 by the previous wgrad on this stream.
+    if (l < m) DNB_TRY(wait(sB, ev(l + 1, EV_MAIN)));
+    if (recompute)  // re-populate storage 1 and 2 for this layer
+      DNB_TRY(launch_bn_relu(y, ys, S2, (int64_t)c * hw, S1, (int64_t)c * hw, n, c, hw, p.g1, p.b1,
+                             StatsSrc{mean_y, istd_y, nullptr, 0, 0, 0, d.eps}, sB));
+    DNB_TRY(record(ev(l, EV_S12), sB));
+
+    // ---- main chain.  dS3 doubles as db_{l+1}, which chain B's wgrad of layer l+1 still reads.
+    if (l < m) DNB_TRY(wait(st, ev(l + 1, EV_WG1)));
     DNB_TRY(launch_conv_igemm(gl, ys, WeightView{p.W3, 9, (int64_t)B * 9, 1}, pk3t, dS3, (int64_t)B * hw,
                               n, k, B, d.h, d.w, 9, st));
     DNB_TRY(launch_bn_relu_bwd(bl, (int64_t)B * hw, dS3, (int64_t)B * hw, dS3, (int64_t)B * hw, false,
                                n, B, hw, p.g2, p.b2, mean_b, istd_b, gp.g2, gp.b2, part, st));
-    if (recompute)  // re-populate storage 1 and 2 for this layer
-      DNB_TRY(launch_bn_relu(y, ys, S2, (int64_t)c * hw, S1, (int64_t)c * hw, n, c, hw, p.g1, p.b1,
-                             StatsSrc{mean_y, istd_y, nullptr, 0, 0, 0, d.eps}, st));
+    DNB_TRY(record(ev(l, EV_DB), st));
+
+    // ---- chain B, second half: the 1x1 weight gradient from storage 2 and db_l
+    DNB_TRY(wait(sB, ev(l, EV_DB)));
     DNB_TRY(launch_conv_wgrad(S2, (int64_t)c * hw, dS3, (int64_t)B * hw, gp.W1, n, c, B, d.h, d.w, 1,
-                              part, st));
+                              partB, sB));
+    DNB_TRY(record(ev(l, EV_WG1), sB));
+
+    // ---- main chain, continued
     DNB_TRY(launch_conv_igemm(dS3, (int64_t)B * hw, WeightView{p.W1, 1, c, 0}, pk1t, dS2, (int64_t)c * hw,
                               n, B, c, d.h, d.w, 1, st));
+    DNB_TRY(wait(st, ev(l, EV_S12)));
     // BN1+ReLU backward, then concat backward: add the slice gradients into the slab
     DNB_TRY(launch_bn_relu_bwd(S1, (int64_t)c * hw, dS2, (int64_t)c * hw, G, ys, true, n, c, hw, p.g1,
                                p.b1, mean_y, istd_y, gp.g1, gp.b1, part, st));
+    DNB_TRY(record(ev(l, EV_MAIN), st));
+  }
+  if (conc) {  // join: the caller's stream is done only when both helper chains are
+    DNB_TRY(hipEventRecord(b->ev_endA, sA));
+    DNB_TRY(hipEventRecord(b->ev_endB, sB));
+    DNB_TRY(hipStreamWaitEvent(st, b->ev_endA, 0));
+    DNB_TRY(hipStreamWaitEvent(st, b->ev_endB, 0));
   }
   DNB_TRY(launch_copy_slab(G, ys, (float*)dx0v, (int64_t)d.c0 * hw, n, (int64_t)d.c0 * hw, st));
   return DNB_OK;

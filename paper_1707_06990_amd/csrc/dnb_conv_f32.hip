@@ -236,22 +236,49 @@ __global__ __launch_bounds__(256) void k_conv_wgrad(
   }
 }
 
+// out[e] = sum over splits of part[split][e], in a fixed order.  Block = (EPB elements) x
+// (G groups); group g adds splits [g*per, (g+1)*per) with eight independent loads in flight,
+// then the G group sums are added in order 0..G-1 through LDS.
 __global__ __launch_bounds__(256) void k_sum_partials(const float* __restrict__ part, int splits,
-                                                      int64_t count, float* __restrict__ out) {
-  const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (e >= count) return;
-  // fixed summation order (split 0, 1, 2, ...); eight independent loads in flight
+                                                      int64_t count, float* __restrict__ out, int G,
+                                                      int per) {
+  __shared__ float sh[256];
+  const int epb = 256 / G;
+  const int le = threadIdx.x % epb, grp = threadIdx.x / epb;
+  const int64_t e = (int64_t)blockIdx.x * epb + le;
   float s = 0.f;
-  int i = 0;
-  for (; i + 8 <= splits; i += 8) {
-    float v[8];
+  if (e < count) {
+    int i = grp * per;
+    const int end = min(splits, i + per);
+    for (; i + 8 <= end; i += 8) {
+      float v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = part[(int64_t)(i + u) * count + e];
+      for (int u = 0; u < 8; ++u) v[u] = part[(int64_t)(i + u) * count + e];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) s += v[u];
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; i < end; ++i) s += part[(int64_t)i * count + e];
   }
-  for (; i < splits; ++i) s += part[(int64_t)i * count + e];
-  out[e] = s;
+  if (G == 1) {
+    if (e < count) out[e] = s;
+    return;
+  }
+  sh[threadIdx.x] = s;
+  __syncthreads();
+  if (grp == 0 && e < count) {
+    float t = sh[le];
+    for (int g = 1; g < G; ++g) t += sh[g * epb + le];
+    out[e] = t;
+  }
+}
+
+hipError_t launch_sum_partials(const float* partials, int splits, int64_t count, float* out, hipStream_t st) {
+  int G = 1;
+  while (G < 16 && splits / G > 16) G <<= 1;  // about 16 splits per thread, at least 16 elements per row
+  const int per = (splits + G - 1) / G, epb = 256 / G;
+  hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((count + epb - 1) / epb)), dim3(256), 0, st, partials,
+                     splits, count, out, G, per);
+  return hipGetLastError();
 }
 
 struct IgemmPlan {
@@ -391,9 +418,7 @@ hipError_t launch_conv_wgrad(const float* in, int64_t in_stride, const float* g,
                          partials, cin, cout, h, w, p.cpi, p.total, p.cps, p.mtw, p.ctw, p.PA, p.PG);
     splits = p.splits;
   }
-  hipLaunchKernelGGL(k_sum_partials, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, st, partials,
-                     splits, count, dw);
-  return hipGetLastError();
+  return launch_sum_partials(partials, splits, count, dw, st);
 }
 
 }  // namespace dnb

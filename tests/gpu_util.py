@@ -46,11 +46,12 @@ def pack_params_oracle(orc, shape, layer_params):
     return flat
 
 
-def run_block_gpu(dnb, cfg, x0, layer_params, dy, schedule=0, poison=True):
+def run_block_gpu(dnb, cfg, x0, layer_params, dy, schedule=0, poison=True, concurrency=True):
     """Forward + backward of one block through the C ABI.  Returns dict of numpy arrays."""
     h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck,
                              schedule=schedule, eps=cfg.eps)
     try:
+        dnb.dnb_block_set_concurrency(h, concurrency)
         params = dev(pack_params_gpu(dnb, h, layer_params))
         ws_bytes = dnb.dnb_block_workspace_bytes(h)
         ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")

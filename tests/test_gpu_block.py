@@ -68,6 +68,17 @@ def test_schedules_bit_identical(dnb, cfg):
     assert a["peak"] < b["peak"] or cfg.layers == 1
 
 
+@pytest.mark.parametrize("cfg", CFGS, ids=IDS)
+@pytest.mark.parametrize("schedule", [0, 1])
+def test_concurrent_backward_equals_serial_bitwise(dnb, cfg, schedule):
+    """The weight-gradient chains on helper streams change nothing but the timing."""
+    x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
+    a = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=schedule, concurrency=True)
+    b = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=schedule, concurrency=False)
+    for key in ("y", "dx0", "dparams"):
+        assert np.array_equal(a[key], b[key]), key
+
+
 def test_repeated_calls_are_deterministic_and_reuse_workspace(dnb):
     cfg = CFGS[0]
     x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
