@@ -36,6 +36,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-compare", action="store_true", help="skip timing the other schedule")
     ap.add_argument("--only-block", type=int, default=-1, help="time a single dense block of the workload (diagnostic)")
+    ap.add_argument("--forward-only", action="store_true", help="time the forward pass alone (diagnostic, not the metric)")
     return ap.parse_args()
 
 
@@ -67,10 +68,12 @@ class BlockRun:
         self.mem = dnb.dnb_block_memory_breakdown(self.h)
 
 
-def make_step(dnb, runs):
+def make_step(dnb, runs, forward_only=False):
     def step():
         for r in runs:
             dnb.dnb_block_forward(r.h, r.x0, r.params, r.y, r.ws)
+        if forward_only:
+            return
         for r in reversed(runs):
             dnb.dnb_block_backward(r.h, r.params, r.y, r.dy, r.dx0, r.dparams, r.ws)
     return step
@@ -191,13 +194,15 @@ def main():
     if a.only_block >= 0:
         blocks = [blocks[a.only_block]]
         wname += f" [only dense block {a.only_block}]"
+    if a.forward_only:
+        wname += " [FORWARD ONLY]"
     batch = blocks[0].n
     sched = {"shared": dnb.DNB_SCHED_SHARED, "store_all": dnb.DNB_SCHED_STORE_ALL}
     use_graph = not a.no_graph
 
     def measure(schedule):
         runs = [BlockRun(dnb, torch, wl, c, sched[schedule], 10 * i) for i, c in enumerate(blocks)]
-        secs = time_steps(torch, make_step(dnb, runs), a.steps, a.warmup, use_graph)
+        secs = time_steps(torch, make_step(dnb, runs, a.forward_only), a.steps, a.warmup, use_graph)
         return runs, secs
 
     runs, secs = measure(a.schedule)
