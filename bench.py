@@ -31,7 +31,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3"])
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
-    ap.add_argument("--schedule", default="shared", choices=["shared", "store_all"])
+    ap.add_argument("--schedule", default="shared", choices=["shared", "store_all", "fused"])
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-compare", action="store_true", help="skip timing the other schedule")
@@ -197,7 +197,7 @@ def main():
     if a.forward_only:
         wname += " [FORWARD ONLY]"
     batch = blocks[0].n
-    sched = {"shared": dnb.DNB_SCHED_SHARED, "store_all": dnb.DNB_SCHED_STORE_ALL}
+    sched = {"shared": dnb.DNB_SCHED_SHARED, "store_all": dnb.DNB_SCHED_STORE_ALL, "fused": dnb.DNB_SCHED_FUSED}
     use_graph = not a.no_graph
 
     def measure(schedule):

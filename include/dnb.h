@@ -45,7 +45,13 @@ enum { DNB_F32 = 0, DNB_BF16 = 1 };  /* storage type of feature maps; accumulati
 enum { DNB_NCHW = 0, DNB_NHWC = 1 };
 /* Section 5 compares exactly these two ways of running the same arithmetic. */
 enum { DNB_SCHED_SHARED = 0,     /* Section 4: shared storage + recomputation (linear memory)   */
-       DNB_SCHED_STORE_ALL = 1   /* Section 3: every concat / BN output kept (quadratic memory) */ };
+       DNB_SCHED_STORE_ALL = 1,  /* Section 3: every concat / BN output kept (quadratic memory) */
+       /* Section 4 taken one step further: the concatenated and normalised features are
+        * recomputed inside the convolutions' operand loads, in forward and backward, so the
+        * shared storage is never materialised at all (same numbers, linear memory with a
+        * smaller constant).  Needs w % 4 == 0 and B*(2w+72)*4 bytes <= 64 KB of LDS,
+        * else dnb_block_create returns DNB_E_UNSUPPORTED. */
+       DNB_SCHED_FUSED = 2 };
 /* Parameter tensors of one layer, in pack order. */
 enum { DNB_P_G1 = 0, DNB_P_B1 = 1, DNB_P_W1 = 2, DNB_P_G2 = 3, DNB_P_B2 = 4, DNB_P_W3 = 5 };
 
@@ -63,6 +69,7 @@ typedef struct {
 /* Byte accounting of one block.  With P = n*h*w pixels, s = bytes per element,
  * C_l = c0 + (l-1)k, C_m the widest layer input and C_out = c0 + m*k:
  *   shared schedule   : stored = (m*B + m*k) P s        shared = (2 C_m + B) P s
+ *   fused schedule    : stored = (m*B + m*k) P s        shared = 0
  *   store-all schedule: stored = (2 sum_l C_l + m(2B + k)) P s   shared = 0
  *   both              : grad   = (C_out + C_m + B) P s
  *   peak = stored + shared + grad.

@@ -14,7 +14,7 @@ DNB_OK = 0
 DNB_E_BADDESC, DNB_E_NULL, DNB_E_ALIGN, DNB_E_LAUNCH, DNB_E_UNSUPPORTED, DNB_E_RANGE, DNB_E_NOMEM = range(-1, -8, -1)
 DNB_F32, DNB_BF16 = 0, 1
 DNB_NCHW, DNB_NHWC = 0, 1
-DNB_SCHED_SHARED, DNB_SCHED_STORE_ALL = 0, 1
+DNB_SCHED_SHARED, DNB_SCHED_STORE_ALL, DNB_SCHED_FUSED = 0, 1, 2
 DNB_P_G1, DNB_P_B1, DNB_P_W1, DNB_P_G2, DNB_P_B2, DNB_P_W3 = range(6)
 
 

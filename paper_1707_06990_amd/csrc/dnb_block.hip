@@ -20,6 +20,7 @@ struct dnb_block {
   size_t off_G, off_dS2, off_dS3;
   size_t off_stat_y;                         // mean[C_out], istd[C_out]
   std::vector<size_t> off_stat_b;            // per layer mean[B], istd[B]
+  std::vector<size_t> off_fold1, off_fold2;  // fused schedule: per layer folded (scale, shift) of BN1 / BN2
   size_t off_part;                           // reduction partials of the main chain (BN)
   size_t off_partA, off_partB;               // partials of the 3x3 / 1x1 weight gradients
   // backward runs three chains: the data-gradient chain on the caller's stream and the two
@@ -95,8 +96,17 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
   if (!(d.eps >= 0.f)) return DNB_E_BADDESC;
   if (d.dtype != DNB_F32 && d.dtype != DNB_BF16) return DNB_E_BADDESC;
   if (d.layout != DNB_NCHW && d.layout != DNB_NHWC) return DNB_E_BADDESC;
-  if (d.schedule != DNB_SCHED_SHARED && d.schedule != DNB_SCHED_STORE_ALL) return DNB_E_BADDESC;
+  if (d.schedule != DNB_SCHED_SHARED && d.schedule != DNB_SCHED_STORE_ALL && d.schedule != DNB_SCHED_FUSED)
+    return DNB_E_BADDESC;
   if (d.dtype != DNB_F32 || d.layout != DNB_NCHW) return DNB_E_UNSUPPORTED;
+  // the fused schedule exists only in the 16-byte-vector kernels (pixel rows a multiple of 4)
+  if (d.schedule == DNB_SCHED_FUSED) {
+    // ... and its 3x3 stages all B channels of a 64-pixel tile (+ halo) in 64 KB of LDS
+    int pitch = (64 + 2 * d.w + 8 + 31) / 32 * 32 + 4;
+    if (pitch - 32 >= 64 + 2 * d.w + 8) pitch -= 32;
+    if (d.w % 4 != 0 || (size_t)((d.bottleneck + 3) & ~3) * pitch * sizeof(float) > 64 * 1024)
+      return DNB_E_UNSUPPORTED;
+  }
   const int64_t hw = (int64_t)d.h * d.w, P = hw * d.n;
   const int64_t cout = (int64_t)d.c0 + (int64_t)d.layers * d.growth;
   if (cout * P >= (int64_t)1 << 31 || (int64_t)d.bottleneck * P >= (int64_t)1 << 31) return DNB_E_RANGE;
@@ -135,7 +145,11 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
   size_t sigma_c = 0;
   for (int l = 1; l <= m; ++l) sigma_c += (size_t)c_in(d, l);
   for (int l = 1; l <= m; ++l) b->off_b[l] = carve((size_t)B * Ps, true);
-  if (d.schedule == DNB_SCHED_SHARED) {
+  if (d.schedule == DNB_SCHED_FUSED) {
+    // nothing of storage 1/2/3 is materialised: BN+ReLU is applied inside the conv operand loads
+    mem.stored_fwd_bytes = (uint64_t)((size_t)m * B + (size_t)m * k) * Ps;
+    mem.shared_fwd_bytes = 0;
+  } else if (d.schedule == DNB_SCHED_SHARED) {
     const size_t s1 = carve((size_t)b->cm * Ps, true), s2 = carve((size_t)b->cm * Ps, true),
                  s3 = carve((size_t)B * Ps, true);
     for (int l = 1; l <= m; ++l) { b->off_u[l] = s1; b->off_a[l] = s2; b->off_a2[l] = s3; }
@@ -161,6 +175,15 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
   b->off_stat_y = carve((size_t)cout * 2 * sizeof(float), false);
   for (int l = 1; l <= m; ++l) b->off_stat_b[l] = carve((size_t)B * 2 * sizeof(float), false);
   mem.stats_bytes = (uint64_t)((size_t)cout * 2 + (size_t)m * B * 2) * sizeof(float);
+  b->off_fold1.assign(m + 1, 0);
+  b->off_fold2.assign(m + 1, 0);
+  if (d.schedule == DNB_SCHED_FUSED) {
+    for (int l = 1; l <= m; ++l) {
+      b->off_fold1[l] = carve((size_t)c_in(d, l) * 2 * sizeof(float), false);
+      b->off_fold2[l] = carve((size_t)B * 2 * sizeof(float), false);
+      mem.stats_bytes += (uint64_t)((size_t)c_in(d, l) + B) * 2 * sizeof(float);
+    }
+  }
 
   size_t part = 0, partA = 0, partB = 0;
   auto need = [&](size_t floats) { if (floats > part) part = floats; };
@@ -168,6 +191,8 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
   need(bn_stats_partial_floats(d.n, k, (int)hw));
   need(bn_stats_partial_floats(d.n, B, (int)hw));
   need(bn_bwd_partial_floats(d.n, B, (int)hw));
+  need(conv_stats_partial_floats(d.n, B, d.h, d.w));  // epilogue statistics of the two convs
+  need(conv_stats_partial_floats(d.n, k, d.h, d.w));
   for (int l = 1; l <= m; ++l) {
     need(bn_bwd_partial_floats(d.n, c_in(d, l), (int)hw));
     const size_t f = conv_wgrad_partial_floats(d.n, c_in(d, l), B, d.h, d.w, 1);
@@ -259,10 +284,12 @@ int dnb_block_forward(dnb_block* b, const void* x0v, const void* paramsv, void* 
   const size_t B16 = (size_t)((B + 15) & ~15), k16 = (size_t)((k + 15) & ~15);
   DNB_TRY(launch_pack_block_weights(params, pack, d.c0, k, B, m, st));
   DNB_TRY(launch_copy_slab(x0, (int64_t)d.c0 * hw, y, ys, n, (int64_t)d.c0 * hw, st));
-  // statistics are reduced to per-split partials by one kernel and merged by the first kernel
-  // that needs them; `fresh` tracks which channels of y still only have partials in `part`
-  int ysplits = 0, bsplits = 0;
-  DNB_TRY(launch_bn_stats_partial(y, ys, n, d.c0, hw, part, &ysplits, st));
+  // Statistics exist first as partials in `part` -- from the statistics kernel (block input) or
+  // from the epilogue of the convolution that produced the feature -- and are merged by the
+  // first kernel that needs them; `fresh` tracks which channels of y still only have partials.
+  const bool fused = d.schedule == DNB_SCHED_FUSED;
+  int freshT = 0;
+  DNB_TRY(launch_bn_stats_partial(y, ys, n, d.c0, hw, part, &freshT, st));
   int fresh_lo = 0, fresh_hi = d.c0;
   for (int l = 1; l <= m; ++l) {
     const int c = c_in(d, l);
@@ -273,24 +300,42 @@ int dnb_block_forward(dnb_block* b, const void* x0v, const void* paramsv, void* 
     float* bl = (float*)(ws + b->off_b[l]);
     float* mean_b = (float*)(ws + b->off_stat_b[l]);
     float* istd_b = mean_b + B;
-    // concat -> storage 1 and BN+ReLU -> storage 2, one pass over the features
-    DNB_TRY(launch_bn_relu(y, ys, S2, (int64_t)c * hw, S1, (int64_t)c * hw, n, c, hw, p.g1, p.b1,
-                           StatsSrc{mean_y, istd_y, part, ysplits, fresh_lo, fresh_hi, d.eps}, st));
+    float2* fold1 = (float2*)(ws + b->off_fold1[l]);
+    float2* fold2 = (float2*)(ws + b->off_fold2[l]);
     const size_t c16 = (size_t)((c + 15) & ~15);
     const float* pk1 = pack + b->pk[l];               // 1x1 forward
     const float* pk3 = pk1 + 2 * B16 * c16;           // 3x3 forward
-    DNB_TRY(launch_conv_igemm(S2, (int64_t)c * hw, WeightView{p.W1, c, 1, 0}, pk1, bl, (int64_t)B * hw,
-                              n, c, B, d.h, d.w, 1, st));
-    DNB_TRY(launch_bn_stats_partial(bl, (int64_t)B * hw, n, B, hw, part, &bsplits, st));
-    DNB_TRY(launch_bn_relu(bl, (int64_t)B * hw, S3, (int64_t)B * hw, nullptr, 0, n, B, hw, p.g2, p.b2,
-                           StatsSrc{mean_b, istd_b, part, bsplits, 0, B, d.eps}, st));
     float* xl = y + (int64_t)c * hw;  // x_l goes straight into its channel range of y
-    DNB_TRY(launch_conv_igemm(S3, (int64_t)B * hw, WeightView{p.W3, (int64_t)B * 9, 9, 0}, pk3, xl, ys,
-                              n, B, k, d.h, d.w, 9, st));
-    if (l < m) {
-      DNB_TRY(launch_bn_stats_partial(xl, ys, n, k, hw, part, &ysplits, st));
-      fresh_lo = c; fresh_hi = c + k;
+    ConvExtras e1{nullptr, part, 0, false}, e3{nullptr, part, 0, false};
+    if (fused) {
+      // BN1+ReLU is applied in the 1x1's operand load, BN2+ReLU while the 3x3 stages its tile
+      DNB_TRY(launch_bn_fold(p.g1, p.b1, mean_y, istd_y, part, freshT, fresh_lo, fresh_hi, d.eps, c,
+                             fold1, st));
+      e1.fold = fold1;
+      DNB_TRY(launch_conv_igemm(y, ys, WeightView{p.W1, c, 1, 0}, pk1, bl, (int64_t)B * hw, n, c, B,
+                                d.h, d.w, 1, &e1, st));
+      DNB_TRY(launch_bn_fold(p.g2, p.b2, mean_b, istd_b, part, e1.stats_T, 0, B, d.eps, B, fold2, st));
+      e3.fold = fold2;
+      DNB_TRY(launch_conv_igemm(bl, (int64_t)B * hw, WeightView{p.W3, (int64_t)B * 9, 9, 0}, pk3, xl, ys,
+                                n, B, k, d.h, d.w, 9, &e3, st));
+      freshT = e3.stats_T;
+    } else {
+      // concat -> storage 1 and BN+ReLU -> storage 2, one pass over the features
+      DNB_TRY(launch_bn_relu(y, ys, S2, (int64_t)c * hw, S1, (int64_t)c * hw, n, c, hw, p.g1, p.b1,
+                             StatsSrc{mean_y, istd_y, part, freshT, fresh_lo, fresh_hi, d.eps}, st));
+      DNB_TRY(launch_conv_igemm(S2, (int64_t)c * hw, WeightView{p.W1, c, 1, 0}, pk1, bl, (int64_t)B * hw,
+                                n, c, B, d.h, d.w, 1, &e1, st));
+      int bT = e1.stats_T;
+      if (!e1.used_fast) DNB_TRY(launch_bn_stats_partial(bl, (int64_t)B * hw, n, B, hw, part, &bT, st));
+      DNB_TRY(launch_bn_relu(bl, (int64_t)B * hw, S3, (int64_t)B * hw, nullptr, 0, n, B, hw, p.g2, p.b2,
+                             StatsSrc{mean_b, istd_b, part, bT, 0, B, d.eps}, st));
+      if (l == m) e3.stats_part = nullptr;  // nobody normalises x_m inside the block
+      DNB_TRY(launch_conv_igemm(S3, (int64_t)B * hw, WeightView{p.W3, (int64_t)B * 9, 9, 0}, pk3, xl, ys,
+                                n, B, k, d.h, d.w, 9, &e3, st));
+      freshT = e3.stats_T;
+      if (l < m && !e3.used_fast) DNB_TRY(launch_bn_stats_partial(xl, ys, n, k, hw, part, &freshT, st));
     }
+    fresh_lo = c; fresh_hi = c + k;
   }
   return DNB_OK;
 }
@@ -305,6 +350,7 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
   const dnb_block_desc& d = b->d;
   const int n = d.n, m = d.layers, k = d.growth, B = d.bottleneck, hw = (int)b->hw;
   const bool recompute = d.schedule == DNB_SCHED_SHARED;
+  const bool fused = d.schedule == DNB_SCHED_FUSED;
   const float* params = (const float*)paramsv;
   const float* y = (const float*)yv;
   float* dparams = (float*)dparamsv;
@@ -371,7 +417,11 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
     if (recompute)  // re-populate storage 3 from the kept b_l and its cached statistics
       DNB_TRY(launch_bn_relu(bl, (int64_t)B * hw, S3, (int64_t)B * hw, nullptr, 0, n, B, hw, p.g2,
                              p.b2, StatsSrc{mean_b, istd_b, nullptr, 0, 0, 0, d.eps}, sA));
-    DNB_TRY(launch_conv_wgrad(S3, (int64_t)B * hw, gl, ys, gp.W3, n, B, k, d.h, d.w, 9, partA, sA));
+    if (fused)  // BN2+ReLU of b_l is applied while the kernel stages its tile: nothing to re-populate
+      DNB_TRY(launch_conv_wgrad(bl, (int64_t)B * hw, gl, ys, gp.W3, n, B, k, d.h, d.w, 9, partA,
+                                (const float2*)(ws + b->off_fold2[l]), sA));
+    else
+      DNB_TRY(launch_conv_wgrad(S3, (int64_t)B * hw, gl, ys, gp.W3, n, B, k, d.h, d.w, 9, partA, nullptr, sA));
 
     // ---- chain B, first half: storage 1 and 2.  Storage 1 was last read by layer l+1's BN1
     // backward on the main chain; storage 2 by the previous wgrad on this stream.
@@ -384,24 +434,29 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
     // ---- main chain.  dS3 doubles as db_{l+1}, which chain B's wgrad of layer l+1 still reads.
     if (l < m) DNB_TRY(wait(st, ev(l + 1, EV_WG1)));
     DNB_TRY(launch_conv_igemm(gl, ys, WeightView{p.W3, 9, (int64_t)B * 9, 1}, pk3t, dS3, (int64_t)B * hw,
-                              n, k, B, d.h, d.w, 9, st));
+                              n, k, B, d.h, d.w, 9, nullptr, st));
     DNB_TRY(launch_bn_relu_bwd(bl, (int64_t)B * hw, dS3, (int64_t)B * hw, dS3, (int64_t)B * hw, false,
                                n, B, hw, p.g2, p.b2, mean_b, istd_b, gp.g2, gp.b2, part, st));
     DNB_TRY(record(ev(l, EV_DB), st));
 
     // ---- chain B, second half: the 1x1 weight gradient from storage 2 and db_l
     DNB_TRY(wait(sB, ev(l, EV_DB)));
-    DNB_TRY(launch_conv_wgrad(S2, (int64_t)c * hw, dS3, (int64_t)B * hw, gp.W1, n, c, B, d.h, d.w, 1,
-                              partB, sB));
+    if (fused)  // BN1+ReLU of the concatenated features is applied in the operand load
+      DNB_TRY(launch_conv_wgrad(y, ys, dS3, (int64_t)B * hw, gp.W1, n, c, B, d.h, d.w, 1, partB,
+                                (const float2*)(ws + b->off_fold1[l]), sB));
+    else
+      DNB_TRY(launch_conv_wgrad(S2, (int64_t)c * hw, dS3, (int64_t)B * hw, gp.W1, n, c, B, d.h, d.w, 1,
+                                partB, nullptr, sB));
     DNB_TRY(record(ev(l, EV_WG1), sB));
 
     // ---- main chain, continued
     DNB_TRY(launch_conv_igemm(dS3, (int64_t)B * hw, WeightView{p.W1, 1, c, 0}, pk1t, dS2, (int64_t)c * hw,
-                              n, B, c, d.h, d.w, 1, st));
+                              n, B, c, d.h, d.w, 1, nullptr, st));
     DNB_TRY(wait(st, ev(l, EV_S12)));
     // BN1+ReLU backward, then concat backward: add the slice gradients into the slab
-    DNB_TRY(launch_bn_relu_bwd(S1, (int64_t)c * hw, dS2, (int64_t)c * hw, G, ys, true, n, c, hw, p.g1,
-                               p.b1, mean_y, istd_y, gp.g1, gp.b1, part, st));
+    // (the fused schedule reads the concatenated features in place from y)
+    DNB_TRY(launch_bn_relu_bwd(fused ? y : S1, fused ? ys : (int64_t)c * hw, dS2, (int64_t)c * hw, G, ys,
+                               true, n, c, hw, p.g1, p.b1, mean_y, istd_y, gp.g1, gp.b1, part, st));
     DNB_TRY(record(ev(l, EV_MAIN), st));
   }
   if (conc) {  // join: the caller's stream is done only when both helper chains are
@@ -487,7 +542,7 @@ int dnb_op_conv_forward(const void* x, int64_t x_stride, const void* wgt, void* 
   const WeightView wv{(const float*)wgt, cin * taps, taps, 0};
   DNB_TRY(launch_pack_weights(wv, (int)cout, (int)cin, taps, (float*)scratch, (hipStream_t)stream));
   DNB_TRY(launch_conv_igemm((const float*)x, x_stride, wv, (const float*)scratch, (float*)out, out_stride,
-                            (int)n, (int)cin, (int)cout, (int)h, (int)w, taps, (hipStream_t)stream));
+                            (int)n, (int)cin, (int)cout, (int)h, (int)w, taps, nullptr, (hipStream_t)stream));
   return DNB_OK;
 }
 
@@ -502,7 +557,7 @@ int dnb_op_conv_dgrad(const void* dout, int64_t dout_stride, const void* wgt, vo
   const WeightView wv{(const float*)wgt, taps, cin * taps, taps == 9 ? 1 : 0};
   DNB_TRY(launch_pack_weights(wv, (int)cin, (int)cout, taps, (float*)scratch, (hipStream_t)stream));
   DNB_TRY(launch_conv_igemm((const float*)dout, dout_stride, wv, (const float*)scratch, (float*)din,
-                            din_stride, (int)n, (int)cout, (int)cin, (int)h, (int)w, taps,
+                            din_stride, (int)n, (int)cout, (int)cin, (int)h, (int)w, taps, nullptr,
                             (hipStream_t)stream));
   return DNB_OK;
 }
@@ -520,7 +575,7 @@ int dnb_op_conv_wgrad(const void* x, int64_t x_stride, const void* dout, int64_t
   const int rc = conv_args_ok(n, cin, cout, h, w, ks);
   if (rc) return rc;
   DNB_TRY(launch_conv_wgrad((const float*)x, x_stride, (const float*)dout, dout_stride, (float*)dwgt,
-                            (int)n, (int)cin, (int)cout, (int)h, (int)w, ks * ks, (float*)scratch,
+                            (int)n, (int)cin, (int)cout, (int)h, (int)w, ks * ks, (float*)scratch, nullptr,
                             (hipStream_t)stream));
   return DNB_OK;
 }

@@ -19,11 +19,11 @@ bool conv_fast_ok(const float* in, int64_t in_stride, const float* out, int64_t 
                   int w, int taps);
 bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, float* out,
                       int64_t out_stride, int n, int cin, int cout, int h, int w, int taps,
-                      hipStream_t st);
+                      const float2* fold, float* spart, int* sT, hipStream_t st);
 size_t conv_wgrad_fast_partial_floats(int n, int cin, int cout, int h, int w, int taps);
 bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
                        float* partials, int n, int cin, int cout, int h, int w, int taps,
-                       int* splits, hipStream_t st);
+                       const float2* fold, int* splits, hipStream_t st);
 
 namespace {
 
@@ -380,11 +380,17 @@ WgradPlan plan_wgrad(int n, int cin, int cout, int h, int w, int taps) {
 
 hipError_t launch_conv_igemm(const float* in, int64_t in_stride, WeightView wv, const float* packed,
                              float* out, int64_t out_stride, int n, int cin, int cout, int h, int w,
-                             int taps, hipStream_t st) {
+                             int taps, ConvExtras* ex, hipStream_t st) {
   if (n <= 0 || cout <= 0 || h <= 0 || w <= 0) return hipSuccess;
+  if (ex) ex->used_fast = false;
   if (packed && conv_fast_ok(in, in_stride, out, out_stride, h, w, taps) &&
-      launch_conv_fast(in, in_stride, packed, out, out_stride, n, cin, cout, h, w, taps, st))
+      launch_conv_fast(in, in_stride, packed, out, out_stride, n, cin, cout, h, w, taps,
+                       ex ? ex->fold : nullptr, ex ? ex->stats_part : nullptr,
+                       ex ? &ex->stats_T : nullptr, st)) {
+    if (ex) ex->used_fast = true;
     return hipGetLastError();
+  }
+  if (ex && ex->fold) return hipErrorInvalidValue;  // the generic kernels have no BN prologue
   const IgemmPlan p = plan_igemm(n, cout, h, w, taps);
   if (p.lds > 64 * 1024) return hipErrorInvalidValue;
   if (taps == 9) return launch_igemm_mt<9>(p, in, in_stride, wv, out, out_stride, cin, cout, h, w, st);
@@ -403,11 +409,12 @@ size_t conv_wgrad_partial_floats(int n, int cin, int cout, int h, int w, int tap
 
 hipError_t launch_conv_wgrad(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
                              float* dw, int n, int cin, int cout, int h, int w, int taps,
-                             float* partials, hipStream_t st) {
+                             float* partials, const float2* fold, hipStream_t st) {
   if (cin <= 0 || cout <= 0) return hipSuccess;
   const int64_t count = (int64_t)cin * cout * taps;
   int splits = 0;
-  if (!launch_wgrad_fast(in, in_stride, g, g_stride, partials, n, cin, cout, h, w, taps, &splits, st)) {
+  if (!launch_wgrad_fast(in, in_stride, g, g_stride, partials, n, cin, cout, h, w, taps, fold, &splits, st)) {
+    if (fold) return hipErrorInvalidValue;  // the generic kernel has no BN prologue
     const WgradPlan p = plan_wgrad(n, cin, cout, h, w, taps);
     if (p.lds > 64 * 1024) return hipErrorInvalidValue;
     if (taps == 9)

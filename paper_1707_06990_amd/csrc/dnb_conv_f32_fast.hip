@@ -10,6 +10,7 @@
 // {g, 4+g, 8+g, 12+g} of a 16-channel chunk and a channel tail that is a multiple of 4
 // costs no padding.
 #include "dnb_internal.h"
+#include "dnb_stats.cuh"
 
 namespace dnb {
 
@@ -131,10 +132,47 @@ __device__ __forceinline__ void ksplit_reduce(f32x4 (&acc)[MT][NT], float* red, 
 //             e.g. the forward 1x1 over the whole concatenation) and are summed through LDS;
 //   !KSPLIT : its waves take different M-tiles of the same pixels (short K, many output
 //             channels: the data gradient of the 1x1).
-template <int MT, int PPL, bool KSPLIT>
+// Epilogue statistics.  A wave that owns an output tile (16 channels x 16*NT pixels, lane (j,g)
+// holding channels 4g+r and pixels NT*j+t) reduces each channel over the tile's valid pixels to
+// (count, mean, M2) -- two passes in registers, 16-lane butterflies -- and stores it as partial
+// `tile_id` of that channel: part[(m*T + tile_id)*3 ..].  The BN that consumes the conv output
+// merges the T partials, so the output is never re-read for its statistics.
+template <int NT>
+__device__ __forceinline__ void tile_stats(const f32x4 (&acc)[NT], bool pix_ok, float cnt, int mfirst,
+                                           int cout, float* __restrict__ part, int T, int tile_id) {
+  const int lane = threadIdx.x & 63, j = lane & 15, g = lane >> 4;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    float s = 0.f;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) s += pix_ok ? acc[t][r] : 0.f;
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) s += __shfl_xor(s, off, 64);
+    const float mu = s / cnt;
+    float m2 = 0.f;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const float dlt = acc[t][r] - mu;
+      m2 += pix_ok ? dlt * dlt : 0.f;
+    }
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) m2 += __shfl_xor(m2, off, 64);
+    const int m = mfirst + 4 * g + r;
+    if (j == 0 && m < cout) {
+      float* p = part + ((int64_t)m * T + tile_id) * 3;
+      p[0] = cnt; p[1] = mu; p[2] = m2;
+    }
+  }
+}
+
+// PRO  : BN + ReLU of the input is applied on the fly: v = max(0, fma(x, fold[ch].x, fold[ch].y))
+//        (the fused schedule's "BN-apply+ReLU feeding straight into the conv operand").
+// STATS: the epilogue writes the output's per-tile BN statistics (see tile_stats).
+template <int MT, int PPL, bool KSPLIT, bool PRO, bool STATS>
 __global__ __launch_bounds__(256) void k_conv1x1_v3(
     const float* __restrict__ in, int64_t in_stride, const float* __restrict__ Wp, int Kpad,
-    float* __restrict__ out, int64_t out_stride, int cin, int cout, int HW) {
+    float* __restrict__ out, int64_t out_stride, int cin, int cout, int HW,
+    const float2* __restrict__ fold, float* __restrict__ spart, int sT) {
   extern __shared__ float red[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
   const int j = lane & 15, g = lane >> 4;
@@ -143,10 +181,11 @@ __global__ __launch_bounds__(256) void k_conv1x1_v3(
   const bool pix_ok = q < HW;
   const float* inb = in + (int64_t)img * in_stride + q;
   const int mbase = KSPLIT ? blockIdx.y * (MT * 16) : (blockIdx.y * nw + wave) * (MT * 16);
+  const int M16 = (cout + 15) & ~15;
   const int nchunks = Kpad >> 4;
   const int cstart = KSPLIT ? wave : 0, cstep = KSPLIT ? nw : 1;
   const float* wrow = Wp + (int64_t)(mbase + j) * Kpad + 4 * g;
-  const bool m_ok = mbase < ((cout + 15) & ~15);  // this wave's first tile exists in the packed rows
+  const bool m_ok = mbase < M16;  // this wave's first tile exists in the packed rows
 
   f32x4 acc[MT][PPL];
 #pragma unroll
@@ -161,17 +200,23 @@ __global__ __launch_bounds__(256) void k_conv1x1_v3(
     for (int ks = 0; ks < 4; ++ks) {
       const int ch = ch0 + 4 * ks + g;
       const bool ok = pix_ok && ch < cin;
+      float2 f = make_float2(1.f, 0.f);
+      if (PRO && ok) f = fold[ch];
       if (PPL == 4) {
         const float4 t = ok ? ldg4(inb + (int64_t)ch * HW) : zero4();
         v[ks][0] = t.x; v[ks][1 % PPL] = t.y; v[ks][2 % PPL] = t.z; v[ks][3 % PPL] = t.w;
       } else {
         v[ks][0] = ok ? inb[(int64_t)ch * HW] : 0.f;
       }
+      if (PRO) {
+#pragma unroll
+        for (int t = 0; t < PPL; ++t) v[ks][t] = ok ? fmaxf(__fmaf_rn(v[ks][t], f.x, f.y), 0.f) : 0.f;
+      }
     }
 #pragma unroll
     for (int a = 0; a < MT; ++a) {
       // rows of M-tiles past the padded output-channel count do not exist: leave them zero
-      const bool rok = mbase + a * 16 < ((cout + 15) & ~15);
+      const bool rok = mbase + a * 16 < M16;
       w4[a] = rok ? ldg4(wrow + (int64_t)a * 16 * Kpad + ch0) : zero4();
     }
   };
@@ -207,11 +252,16 @@ __global__ __launch_bounds__(256) void k_conv1x1_v3(
 
   if (KSPLIT) ksplit_reduce<MT, PPL>(acc, red, wave, lane, nw);
 
-  if (pix_ok) {
-    float* ob = out + (int64_t)img * out_stride + q;
+  const int tile_px = min(16 * PPL, HW - (int)blockIdx.x * (16 * PPL));
 #pragma unroll
-    for (int a = 0; a < MT; ++a) {
-      if (KSPLIT && a % nw != wave) continue;  // after the reduction M-tile a lives in wave a % nw
+  for (int a = 0; a < MT; ++a) {
+    if (KSPLIT && a % nw != wave) continue;  // after the reduction M-tile a lives in wave a % nw
+    if (mbase + a * 16 >= M16) continue;
+    if (STATS)
+      tile_stats<PPL>(acc[a], pix_ok, (float)tile_px, mbase + a * 16, cout, spart, sT,
+                      img * gridDim.x + blockIdx.x);
+    if (pix_ok) {
+      float* ob = out + (int64_t)img * out_stride + q;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int m = mbase + a * 16 + 4 * g + r;
@@ -238,10 +288,11 @@ __global__ __launch_bounds__(256) void k_conv1x1_v3(
 // (W is a multiple of 4), which are masked.  Waves split K (forward: 9*B long K, k outputs)
 // or M (data gradient: k*9 short K, B outputs) as in the 1x1 kernel; packed weights come
 // from L2, 16 bytes per lane per (tap, chunk).
-template <int MT, bool KSPLIT>
+template <int MT, bool KSPLIT, bool PRO, bool STATS>
 __global__ __launch_bounds__(256) void k_conv3x3_v3(
     const float* __restrict__ in, int64_t in_stride, const float* __restrict__ Wp, int Mpad,
-    int Kpad, float* __restrict__ out, int64_t out_stride, int cin, int cout, int H, int W, int CS) {
+    int Kpad, float* __restrict__ out, int64_t out_stride, int cin, int cout, int H, int W, int CS,
+    const float2* __restrict__ fold, float* __restrict__ spart, int sT) {
   extern __shared__ float lds[];
   const int HW = H * W;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nthr = blockDim.x, nw = nthr >> 6;
@@ -260,9 +311,16 @@ __global__ __launch_bounds__(256) void k_conv3x3_v3(
   const int rows = (cin + 3) & ~3;  // staged channel rows (tail rows zero)
   for (int row = tid >> 4; row < rows; row += nthr >> 4) {
     const float* src = inb + (int64_t)row * HW;
+    float2 f = make_float2(1.f, 0.f);
+    if (PRO && row < cin) f = fold[row];
     for (int c4 = tid & 15; c4 < seg4; c4 += 16) {
       const int qq = origin + 4 * c4;
-      const float4 v = (row < cin && qq >= 0 && qq < HW) ? ldg4(src + qq) : zero4();
+      const bool ok = row < cin && qq >= 0 && qq < HW;
+      float4 v = ok ? ldg4(src + qq) : zero4();
+      if (PRO && ok) {  // BN + ReLU on the way in; the zero padding stays zero
+        v.x = fmaxf(__fmaf_rn(v.x, f.x, f.y), 0.f); v.y = fmaxf(__fmaf_rn(v.y, f.x, f.y), 0.f);
+        v.z = fmaxf(__fmaf_rn(v.z, f.x, f.y), 0.f); v.w = fmaxf(__fmaf_rn(v.w, f.x, f.y), 0.f);
+      }
       *reinterpret_cast<float4*>(&lds[row * CS + 4 * c4]) = v;
     }
   }
@@ -329,11 +387,16 @@ __global__ __launch_bounds__(256) void k_conv3x3_v3(
 
   if (KSPLIT) ksplit_reduce<MT, 4>(acc, lds, wave, lane, nw);  // reuses the tile's LDS (barrier inside)
 
-  if (q < HW) {
-    float* ob = out + (int64_t)img * out_stride + q;
+  const int tile_px = min(64, HW - q0);
 #pragma unroll
-    for (int a = 0; a < MT; ++a) {
-      if (KSPLIT && a % nw != wave) continue;
+  for (int a = 0; a < MT; ++a) {
+    if (KSPLIT && a % nw != wave) continue;
+    if (mbase + a * 16 >= Mpad) continue;
+    if (STATS)
+      tile_stats<4>(acc[a], q < HW, (float)tile_px, mbase + a * 16, cout, spart, sT,
+                    img * gridDim.x + blockIdx.x);
+    if (q < HW) {
+      float* ob = out + (int64_t)img * out_stride + q;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int m = mbase + a * 16 + 4 * g + r;
@@ -372,10 +435,11 @@ __device__ __forceinline__ void reduce_waves(f32x4 (&acc)[NT], float* buf, int w
 // 4kk..4kk+3 of row r of both operands (16 bytes each) and issues 4 K-steps.  The four waves of
 // a workgroup take alternate steps (together 256 contiguous bytes per row), keep all MTW x CTW
 // tiles in registers, and are summed in LDS at the end; the workgroup writes one partial.
-template <int MTW, int CTW>
+template <int MTW, int CTW, bool PRO>
 __global__ __launch_bounds__(256) void k_wgrad1x1_fast(
     const float* __restrict__ a, int64_t a_stride, const float* __restrict__ gout, int64_t g_stride,
-    float* __restrict__ part, int cin, int cout, int HW, int spi, int total_steps, int steps_per_wg) {
+    float* __restrict__ part, int cin, int cout, int HW, int spi, int total_steps, int steps_per_wg,
+    const float2* __restrict__ fold) {
   extern __shared__ float lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, kk = lane >> 4;
@@ -385,6 +449,13 @@ __global__ __launch_bounds__(256) void k_wgrad1x1_fast(
   f32x4 acc[MTW * CTW];
 #pragma unroll
   for (int t = 0; t < MTW * CTW; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  float2 fl[CTW];  // PRO: BN+ReLU of the activation operand, one channel per lane and c-tile
+#pragma unroll
+  for (int y = 0; y < CTW; ++y) {
+    const int c = c0 + y * 16 + r;
+    fl[y] = (PRO && c < cin) ? fold[c] : make_float2(1.f, 0.f);
+  }
 
   for (int s = s_begin + wave; s < s_end; s += 4) {
     const int img = s / spi, q = (s - img * spi) * 16 + 4 * kk;
@@ -399,6 +470,12 @@ __global__ __launch_bounds__(256) void k_wgrad1x1_fast(
     for (int y = 0; y < CTW; ++y) {
       const int c = c0 + y * 16 + r;
       Bv[y] = (ok && c < cin) ? ldg4(a + (int64_t)img * a_stride + (int64_t)c * HW + q) : zero4();
+      if (PRO && ok && c < cin) {
+        Bv[y].x = fmaxf(__fmaf_rn(Bv[y].x, fl[y].x, fl[y].y), 0.f);
+        Bv[y].y = fmaxf(__fmaf_rn(Bv[y].y, fl[y].x, fl[y].y), 0.f);
+        Bv[y].z = fmaxf(__fmaf_rn(Bv[y].z, fl[y].x, fl[y].y), 0.f);
+        Bv[y].w = fmaxf(__fmaf_rn(Bv[y].w, fl[y].x, fl[y].y), 0.f);
+      }
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e)
@@ -431,10 +508,11 @@ __global__ __launch_bounds__(256) void k_wgrad1x1_fast(
 // of a pixel range (plus halo, as in the forward kernel) in LDS; every wave takes its own
 // 16-pixel steps of that range and keeps all MTW x CTW x 9 tiles in registers.  g comes
 // straight from HBM (16 bytes per lane and step).
-template <int MTW, int CTW>
+template <int MTW, int CTW, bool PRO>
 __global__ __launch_bounds__(256) void k_wgrad3x3_fast(
     const float* __restrict__ a, int64_t a_stride, const float* __restrict__ gout, int64_t g_stride,
-    float* __restrict__ part, int cin, int cout, int H, int W, int tiles_per_img, int nms, int PA) {
+    float* __restrict__ part, int cin, int cout, int H, int W, int tiles_per_img, int nms, int PA,
+    const float2* __restrict__ fold) {
   extern __shared__ float lds[];
   const int HW = H * W;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -451,9 +529,16 @@ __global__ __launch_bounds__(256) void k_wgrad3x3_fast(
   for (int row = tid >> 4; row < CB; row += 16) {
     const int ch = c0 + row;
     const float* src = ab + (int64_t)ch * HW;
+    float2 f = make_float2(1.f, 0.f);
+    if (PRO && ch < cin) f = fold[ch];
     for (int c4 = tid & 15; c4 < seg4; c4 += 16) {
       const int qq = origin + 4 * c4;
-      const float4 v = (ch < cin && qq >= 0 && qq < HW) ? ldg4(src + qq) : zero4();
+      const bool ok = ch < cin && qq >= 0 && qq < HW;
+      float4 v = ok ? ldg4(src + qq) : zero4();
+      if (PRO && ok) {
+        v.x = fmaxf(__fmaf_rn(v.x, f.x, f.y), 0.f); v.y = fmaxf(__fmaf_rn(v.y, f.x, f.y), 0.f);
+        v.z = fmaxf(__fmaf_rn(v.z, f.x, f.y), 0.f); v.w = fmaxf(__fmaf_rn(v.w, f.x, f.y), 0.f);
+      }
       *reinterpret_cast<float4*>(&lds[row * PA + 4 * c4]) = v;
     }
   }
@@ -521,6 +606,33 @@ __global__ __launch_bounds__(256) void k_wgrad3x3_fast(
   }
 }
 
+// fold[ch] = (gamma*istd, beta - mean*gamma*istd) for nch channels.  Channels in
+// [fresh_lo, fresh_hi) only have partial statistics ([T][3] each): they are merged here and
+// their mean / inverse std stored for the backward pass.  One workgroup per channel, 256 threads
+// like the BN kernels' own merge, so both give the same bits from the same partials.
+__global__ __launch_bounds__(256) void k_bn_fold(const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                float* mean, float* istd, const float* __restrict__ part,
+                                                int T, int fresh_lo, int fresh_hi, float eps,
+                                                float2* __restrict__ fold) {
+  __shared__ float sh[12];
+  const int ch = blockIdx.x;
+  float mu, is;
+  if (ch >= fresh_lo && ch < fresh_hi) {
+    const Stat3 r = stat_merge_block(part + (int64_t)(ch - fresh_lo) * T * 3, T, sh);
+    mu = r.m;
+    is = bn_istd(r.m2, r.c, eps);
+    if (threadIdx.x == 0) { mean[ch] = mu; istd[ch] = is; }
+  } else {
+    mu = mean[ch];
+    is = istd[ch];
+  }
+  if (threadIdx.x == 0) {
+    float sc, sf;
+    bn_fold(gamma[ch], beta[ch], mu, is, sc, sf);
+    fold[ch] = make_float2(sc, sf);
+  }
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline int pad4mod32(int v) {  // smallest pitch >= v with pitch % 32 == 4
   int p = (v + 31) / 32 * 32 + 4;
@@ -567,12 +679,28 @@ hipError_t launch_pack_block_weights(const float* params, float* packed, int c0,
   return hipGetLastError();
 }
 
+hipError_t launch_bn_fold(const float* gamma, const float* beta, float* mean, float* istd,
+                          const float* part, int T, int fresh_lo, int fresh_hi, float eps, int nch,
+                          float2* fold, hipStream_t st) {
+  if (nch <= 0) return hipSuccess;
+  hipLaunchKernelGGL(k_bn_fold, dim3((unsigned)nch), dim3(256), 0, st, gamma, beta, mean, istd, part, T,
+                     fresh_lo, fresh_hi, eps, fold);
+  return hipGetLastError();
+}
+
+size_t conv_stats_partial_floats(int n, int cout, int h, int w) {
+  return (size_t)cout * n * ((h * w + 15) / 16) * 3;
+}
+
 // Returns false (nothing launched) if the fast path does not cover this shape.
+// fold != null: BN+ReLU prologue.  spart != null: epilogue statistics, *sT = partials per channel.
 bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, float* out,
                       int64_t out_stride, int n, int cin, int cout, int h, int w, int taps,
-                      hipStream_t st) {
+                      const float2* fold, float* spart, int* sT, hipStream_t st) {
   const int hw = h * w, mtiles = (cout + 15) / 16, M16 = mtiles * 16;
   const int K16 = (cin + 15) & ~15, nchunks = K16 / 16;
+  const int mode = fold ? 2 : (spart ? 1 : 0);  // 0 plain, 1 statistics, 2 prologue + statistics
+  if (fold && !spart) return false;
   if (taps == 1) {
     const bool ksplit = nchunks >= 4;
     int nw, mt, gy;
@@ -587,16 +715,25 @@ bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, f
     const int ppl = ((int64_t)((hw + 63) / 64) * gy * n >= 512) ? 4 : 1;
     dim3 grid((unsigned)((hw + 16 * ppl - 1) / (16 * ppl)), (unsigned)gy, (unsigned)n);
     const size_t lds = ksplit ? (size_t)nw * mt * ppl * 256 * sizeof(float) : 0;
-#define DNB_L(MT, PPL, KS)                                                                          \
-  hipLaunchKernelGGL((k_conv1x1_v3<MT, PPL, KS>), grid, dim3(64 * nw), lds, st, in, in_stride, packed, \
-                     K16, out, out_stride, cin, cout, hw)
+    const int T = (int)grid.x * n;
+    if (sT) *sT = T;
+#define DNB_L(MT, PPL, KS, PRO, STATS)                                                                \
+  hipLaunchKernelGGL((k_conv1x1_v3<MT, PPL, KS, PRO, STATS>), grid, dim3(64 * nw), lds, st, in,        \
+                     in_stride, packed, K16, out, out_stride, cin, cout, hw, fold, spart, T)
+#define DNB_L3(MT, PPL, KS)                                                         \
+  do {                                                                              \
+    if (mode == 2) DNB_L(MT, PPL, KS, true, true);                                   \
+    else if (mode == 1) DNB_L(MT, PPL, KS, false, true);                             \
+    else DNB_L(MT, PPL, KS, false, false);                                           \
+  } while (0)
 #define DNB_L2(MT)                                                                   \
   do {                                                                               \
-    if (ksplit) { if (ppl == 4) DNB_L(MT, 4, true); else DNB_L(MT, 1, true); }        \
-    else        { if (ppl == 4) DNB_L(MT, 4, false); else DNB_L(MT, 1, false); }      \
+    if (ksplit) { if (ppl == 4) DNB_L3(MT, 4, true); else DNB_L3(MT, 1, true); }      \
+    else        { if (ppl == 4) DNB_L3(MT, 4, false); else DNB_L3(MT, 1, false); }    \
   } while (0)
     switch (mt) { case 3: DNB_L2(3); break; case 2: DNB_L2(2); break; default: DNB_L2(1); break; }
 #undef DNB_L2
+#undef DNB_L3
 #undef DNB_L
     return true;
   }
@@ -615,11 +752,20 @@ bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, f
   const size_t lds = (tile > red ? tile : red) * sizeof(float);
   if (lds > 64 * 1024) return false;
   dim3 grid((unsigned)((hw + 63) / 64), (unsigned)gy, (unsigned)n);
-#define DNB_L(MT, KS)                                                                                  \
-  hipLaunchKernelGGL((k_conv3x3_v3<MT, KS>), grid, dim3(64 * nw), lds, st, in, in_stride, packed, M16,  \
-                     K16, out, out_stride, cin, cout, h, w, CS)
-  if (ksplit) { if (mt == 2) DNB_L(2, true); else DNB_L(1, true); }
-  else        { if (mt == 2) DNB_L(2, false); else DNB_L(1, false); }
+  const int T = (int)grid.x * n;
+  if (sT) *sT = T;
+#define DNB_L(MT, KS, PRO, STATS)                                                                      \
+  hipLaunchKernelGGL((k_conv3x3_v3<MT, KS, PRO, STATS>), grid, dim3(64 * nw), lds, st, in, in_stride,   \
+                     packed, M16, K16, out, out_stride, cin, cout, h, w, CS, fold, spart, T)
+#define DNB_L3(MT, KS)                                                              \
+  do {                                                                              \
+    if (mode == 2) DNB_L(MT, KS, true, true);                                        \
+    else if (mode == 1) DNB_L(MT, KS, false, true);                                  \
+    else DNB_L(MT, KS, false, false);                                                \
+  } while (0)
+  if (ksplit) { if (mt == 2) DNB_L3(2, true); else DNB_L3(1, true); }
+  else        { if (mt == 2) DNB_L3(2, false); else DNB_L3(1, false); }
+#undef DNB_L3
 #undef DNB_L
   return true;
 }
@@ -687,7 +833,7 @@ size_t conv_wgrad_fast_partial_floats(int n, int cin, int cout, int h, int w, in
 // of partials to add in *splits.
 bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
                        float* partials, int n, int cin, int cout, int h, int w, int taps,
-                       int* splits, hipStream_t st) {
+                       const float2* fold, int* splits, hipStream_t st) {
   if (in_stride % 4 || g_stride % 4 || !aligned16(in) || !aligned16(g)) return false;
   const WgFastPlan p = plan_wgrad_fast(n, cin, cout, h, w, taps);
   if (!p.ok) return false;
@@ -695,8 +841,14 @@ bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64
   const int hw = h * w;
   if (taps == 1) {
 #define DNB_L(M, C)                                                                                  \
-  hipLaunchKernelGGL((k_wgrad1x1_fast<M, C>), grid, dim3(256), p.lds, st, in, in_stride, g, g_stride, \
-                     partials, cin, cout, hw, p.spi, p.total_steps, p.steps_per_wg)
+  do {                                                                                               \
+    if (fold)                                                                                        \
+      hipLaunchKernelGGL((k_wgrad1x1_fast<M, C, true>), grid, dim3(256), p.lds, st, in, in_stride, g, \
+                         g_stride, partials, cin, cout, hw, p.spi, p.total_steps, p.steps_per_wg, fold); \
+    else                                                                                             \
+      hipLaunchKernelGGL((k_wgrad1x1_fast<M, C, false>), grid, dim3(256), p.lds, st, in, in_stride, g, \
+                         g_stride, partials, cin, cout, hw, p.spi, p.total_steps, p.steps_per_wg, fold); \
+  } while (0)
     const int key = p.mtw * 10 + p.ctw;
     switch (key) {
       case 34: DNB_L(3, 4); break; case 33: DNB_L(3, 3); break; case 32: DNB_L(3, 2); break; case 31: DNB_L(3, 1); break;
@@ -706,8 +858,14 @@ bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64
 #undef DNB_L
   } else {
 #define DNB_L(M, C)                                                                                  \
-  hipLaunchKernelGGL((k_wgrad3x3_fast<M, C>), grid, dim3(256), p.lds, st, in, in_stride, g, g_stride, \
-                     partials, cin, cout, h, w, p.tiles_per_img, p.nms, p.PA)
+  do {                                                                                               \
+    if (fold)                                                                                        \
+      hipLaunchKernelGGL((k_wgrad3x3_fast<M, C, true>), grid, dim3(256), p.lds, st, in, in_stride, g, \
+                         g_stride, partials, cin, cout, h, w, p.tiles_per_img, p.nms, p.PA, fold);    \
+    else                                                                                             \
+      hipLaunchKernelGGL((k_wgrad3x3_fast<M, C, false>), grid, dim3(256), p.lds, st, in, in_stride, g, \
+                         g_stride, partials, cin, cout, h, w, p.tiles_per_img, p.nms, p.PA, fold);    \
+  } while (0)
     const int key = p.mtw * 10 + p.ctw;
     switch (key) {
       case 22: DNB_L(2, 2); break; case 21: DNB_L(2, 1); break;

@@ -5,6 +5,7 @@
 // kernel, wave-level butterfly reductions and LDS only to combine the waves of a
 // workgroup.
 #include "dnb_internal.h"
+#include "dnb_stats.cuh"
 
 namespace dnb {
 
@@ -30,14 +31,6 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   float t = 0.f;
   for (int i = 0; i < nw; ++i) t += red[i];
   return t;
-}
-
-// The one place BN's affine map is folded into (scale, shift); forward, recomputation
-// and backward all call it so the ReLU mask is reproduced bit for bit.
-__device__ __forceinline__ void bn_fold(float gamma, float beta, float mean, float istd,
-                                        float& scale, float& shift) {
-  scale = __fmul_rn(gamma, istd);
-  shift = __fmaf_rn(-mean, scale, beta);
 }
 
 template <int V>
@@ -141,69 +134,34 @@ __global__ __launch_bounds__(kThreads) void k_bn_stats_partial(const float* __re
   }
 }
 
-// Merges the (count, mean, M2) partials of one channel across the lanes of a wave (lane s
-// holds split s, lanes past `splits` hold count 0).  Pairwise-update formula; both lanes of
-// a butterfly pair evaluate the same expression (lower lane's value first), so every lane
-// ends with the same bits and every caller gets the same bits from the same partials.
-__device__ __forceinline__ void merge_stats_wave(float& cnt, float& mu, float& m2) {
-  const int lane = threadIdx.x & 63;
-#pragma unroll
-  for (int off = 1; off < 64; off <<= 1) {
-    const float oc = __shfl_xor(cnt, off, 64), om = __shfl_xor(mu, off, 64), o2 = __shfl_xor(m2, off, 64);
-    const bool hi = (lane & off) != 0;
-    const float ca = hi ? oc : cnt, ma = hi ? om : mu, m2a = hi ? o2 : m2;
-    const float cb = hi ? cnt : oc, mb = hi ? mu : om, m2b = hi ? m2 : o2;
-    const float tot = __fadd_rn(ca, cb);
-    if (cb == 0.f) { cnt = ca; mu = ma; m2 = m2a; }
-    else if (ca == 0.f) { cnt = cb; mu = mb; m2 = m2b; }
-    else {
-      const float d = __fsub_rn(mb, ma);
-      mu = __fmaf_rn(d, __fdiv_rn(cb, tot), ma);
-      m2 = __fadd_rn(__fadd_rn(m2a, m2b), __fmul_rn(__fmul_rn(d, d), __fdiv_rn(__fmul_rn(ca, cb), tot)));
-      cnt = tot;
-    }
-  }
-}
-
 // Finalised statistics of channel ch for the calling workgroup.  Channels in
-// [fresh_lo, fresh_hi) still only have partials (from the latest k_bn_stats_partial): wave 0
-// merges them; the workgroup with blockIdx.y == 0 also stores mean / inverse std so later
-// kernels read them.  Returns (mean, istd) to every thread.
+// [fresh_lo, fresh_hi) still only have partials ([splits][3] per channel, from the statistics
+// kernel or a convolution epilogue): the workgroup merges them; the one with blockIdx.y == 0
+// also stores mean / inverse std so later kernels read them.  Returns (mean, istd) to every thread.
 __device__ __forceinline__ void channel_stats(int ch, float* mean, float* istd, const float* part,
                                               int splits, int fresh_lo, int fresh_hi, float eps,
                                               float* sh, float& mu, float& is) {
-  if (threadIdx.x < 64) {
-    if (ch >= fresh_lo && ch < fresh_hi) {
-      const int lane = threadIdx.x;
-      const float* p = part + ((int64_t)(ch - fresh_lo) * splits + lane) * 3;
-      float cnt = 0.f, m = 0.f, m2 = 0.f;
-      if (lane < splits) { cnt = p[0]; m = p[1]; m2 = p[2]; }
-      merge_stats_wave(cnt, m, m2);
-      const float iv = __fdiv_rn(1.0f, __fsqrt_rn(__fadd_rn(__fdiv_rn(m2, cnt), eps)));
-      if (lane == 0) {
-        sh[0] = m; sh[1] = iv;
-        if (blockIdx.y == 0) { mean[ch] = m; istd[ch] = iv; }
-      }
-    } else if (threadIdx.x == 0) {
-      sh[0] = mean[ch]; sh[1] = istd[ch];
-    }
+  if (ch >= fresh_lo && ch < fresh_hi) {  // workgroup-uniform branch
+    const Stat3 r = stat_merge_block(part + (int64_t)(ch - fresh_lo) * splits * 3, splits, sh);
+    mu = r.m;
+    is = bn_istd(r.m2, r.c, eps);
+    if (blockIdx.y == 0 && threadIdx.x == 0) { mean[ch] = mu; istd[ch] = is; }
+  } else {
+    mu = mean[ch];
+    is = istd[ch];
   }
-  __syncthreads();
-  mu = sh[0]; is = sh[1];
 }
 
-// One thread per channel merges the splits; used by the stand-alone statistics entry point.
+// One wave per channel merges the partials; used by the stand-alone statistics entry point.
 __global__ __launch_bounds__(64) void k_bn_stats_finalize(const float* __restrict__ part, int c, int splits,
                                                           float eps, float* __restrict__ mean,
                                                           float* __restrict__ istd) {
-  const int ch = blockIdx.x, lane = threadIdx.x;
-  const float* p = part + ((int64_t)ch * splits + lane) * 3;
-  float cnt = 0.f, m = 0.f, m2 = 0.f;
-  if (lane < splits) { cnt = p[0]; m = p[1]; m2 = p[2]; }
-  merge_stats_wave(cnt, m, m2);
-  if (lane == 0) {
-    mean[ch] = m;
-    istd[ch] = __fdiv_rn(1.0f, __fsqrt_rn(__fadd_rn(__fdiv_rn(m2, cnt), eps)));
+  __shared__ float sh[3];
+  const int ch = blockIdx.x;
+  const Stat3 r = stat_merge_block(part + (int64_t)ch * splits * 3, splits, sh);
+  if (threadIdx.x == 0) {
+    mean[ch] = r.m;
+    istd[ch] = bn_istd(r.m2, r.c, eps);
   }
 }
 
@@ -217,7 +175,7 @@ __global__ __launch_bounds__(kThreads) void k_bn_relu(
     float* __restrict__ copy_out, int64_t copy_stride, int n, int hw, int ipb,
     const float* __restrict__ gamma, const float* __restrict__ beta, float* mean, float* istd,
     const float* __restrict__ part, int splits, int fresh_lo, int fresh_hi, float eps) {
-  __shared__ float sh[2];
+  __shared__ float sh[3 * kThreads / 64];
   const int ch = blockIdx.x, n0 = blockIdx.y * ipb, ni = min(n, n0 + ipb) - n0;
   float mu, is, scale, shift;
   channel_stats(ch, mean, istd, part, splits, fresh_lo, fresh_hi, eps, sh, mu, is);

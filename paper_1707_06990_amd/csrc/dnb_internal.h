@@ -76,15 +76,36 @@ hipError_t launch_pack_block_weights(const float* params, float* packed, int c0,
 // taps = 1 or 9.  Used for forward (W = OIHW as is) and data gradient (transposed, flipped).
 // `packed` (may be null) is the same weight view packed by launch_pack_weights; with it, shapes
 // whose pixel counts and strides are multiples of 4 take the fast kernels.
+// Optional extras of the fast kernels:
+//   fold        BN+ReLU prologue: the input is max(0, fma(x, fold[c].x, fold[c].y)) (fast path only)
+//   stats_part  epilogue statistics of the output: [cout][stats_T][3] partials (count, mean, M2),
+//               conv_stats_partial_floats floats; stats_T is set by the launcher
+//   used_fast   set by the launcher; false = generic kernel ran, no statistics were written
+struct ConvExtras {
+  const float2* fold;
+  float* stats_part;
+  int stats_T;
+  bool used_fast;
+};
+size_t conv_stats_partial_floats(int n, int cout, int h, int w);
 hipError_t launch_conv_igemm(const float* in, int64_t in_stride, WeightView wv, const float* packed,
                              float* out, int64_t out_stride, int n, int cin, int cout, int h, int w,
-                             int taps, hipStream_t st);
+                             int taps, ConvExtras* ex, hipStream_t st);
+bool conv_fast_ok(const float* in, int64_t in_stride, const float* out, int64_t out_stride, int h,
+                  int w, int taps);
+
+// fold[ch] = BN's affine map folded to (scale, shift) for nch channels; channels in
+// [fresh_lo, fresh_hi) are first finalised from their [T][3] partial statistics.
+hipError_t launch_bn_fold(const float* gamma, const float* beta, float* mean, float* istd,
+                          const float* part, int T, int fresh_lo, int fresh_hi, float eps, int nch,
+                          float2* fold, hipStream_t st);
 
 // dW[m][c][t] = sum_{n,q} g[n][m][q] * in[n][c][q + shift(t)]  (OIHW result).
 int conv_wgrad_splits(int n, int cin, int cout, int h, int w, int taps);
 size_t conv_wgrad_partial_floats(int n, int cin, int cout, int h, int w, int taps);
+// fold != null applies the BN+ReLU prologue to `in` (fast path only).
 hipError_t launch_conv_wgrad(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
                              float* dw, int n, int cin, int cout, int h, int w, int taps,
-                             float* partials, hipStream_t st);
+                             float* partials, const float2* fold, hipStream_t st);
 
 }  // namespace dnb

@@ -23,6 +23,9 @@ CFGS = [
 IDS = [f"n{c.n}c{c.c0}h{c.h}w{c.w}m{c.layers}k{c.growth}B{c.bottleneck}" for c in CFGS]
 
 
+FUSED = [i for i, c in enumerate(CFGS) if c.w % 4 == 0]   # the fused schedule needs pixel rows that are multiples of 4
+
+
 def compare(gpu, ores, oslices, cfg, tol=TOL):
     assert_close(gpu["y"], ores.y, tol, "y")
     assert_close(gpu["dx0"], ores.dx0, tol, "dx0")
@@ -44,6 +47,25 @@ def test_block_matches_oracle(dnb, oracle, cfg, schedule):
     gpu = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=schedule)
     ores, osl = run_block_oracle(oracle, cfg, x0, lp, dy)
     compare(gpu, ores, osl, cfg)
+
+
+@pytest.mark.parametrize("i", FUSED, ids=[IDS[i] for i in FUSED])
+def test_fused_schedule_matches_oracle_and_shared_schedule(dnb, oracle, i):
+    """BN+ReLU recomputed inside the conv operand loads (nothing of storage 1/2/3 materialised):
+    same parity bar against the oracle, and the same bits as the shared-storage schedule."""
+    cfg = CFGS[i]
+    x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
+    fused = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=2)
+    ores, osl = run_block_oracle(oracle, cfg, x0, lp, dy)
+    compare(fused, ores, osl, cfg)
+    shared = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=0)
+    for key in ("y", "dx0", "dparams"):
+        assert np.array_equal(fused[key], shared[key]), key
+    P4 = cfg.pixels * 4
+    assert fused["peak"] == shared["peak"] - (2 * cfg.c_in(cfg.layers) + cfg.bottleneck) * P4
+    serial = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=2, concurrency=False)
+    for key in ("y", "dx0", "dparams"):
+        assert np.array_equal(fused[key], serial[key]), key
 
 
 def test_config1_exact_recipe(dnb, oracle):

@@ -41,7 +41,8 @@ def test_status_strings(dnb):
 @pytest.mark.parametrize("kw,code", [
     (dict(n=0), -1), (dict(c0=0), -1), (dict(layers=0), -1), (dict(growth=0), -1), (dict(bottleneck=0), -1),
     (dict(h=-1), -1), (dict(eps=-1.0), -1), (dict(dtype=7), -1), (dict(layout=3), -1), (dict(schedule=9), -1),
-    (dict(dtype=1), -5), (dict(layout=1), -5), (dict(n=4096, h=512, w=512), -6)])
+    (dict(dtype=1), -5), (dict(layout=1), -5), (dict(n=4096, h=512, w=512), -6),
+    (dict(schedule=2, h=7, w=7), -5), (dict(schedule=2, bottleneck=512), -5)])
 def test_descriptor_validation(dnb, kw, code):
     base = dict(n=2, c0=16, h=8, w=8, layers=4, growth=12, bottleneck=48)
     base.update(kw)
@@ -87,6 +88,18 @@ def test_peak_bytes_formula(dnb, cfg):
         lo = mm["peak_bytes"] - m * k * Ps + mm["stats_bytes"] + mm["scratch_bytes"]
         assert lo <= mm["workspace_bytes"] == dnb.dnb_block_workspace_bytes(h) <= lo + 256 * (6 * m + 16)
         dnb.dnb_block_destroy(h)
+
+
+@pytest.mark.parametrize("cfg", [c for c in CFGS if c.w % 4 == 0], ids=lambda c: f"{c.n}x{c.c0}x{c.h}x{c.w}-m{c.layers}k{c.growth}")
+def test_fused_schedule_bytes(dnb, cfg):
+    """No shared storage at all: stored conv outputs + gradient storage only, linear in m."""
+    Ps, m, k, B = cfg.pixels * 4, cfg.layers, cfg.growth, cfg.bottleneck
+    h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, m, k, B, schedule=2)
+    mm = dnb.dnb_block_memory_breakdown(h)
+    assert mm["shared_fwd_bytes"] == 0
+    assert mm["stored_fwd_bytes"] == (m * B + m * k) * Ps
+    assert mm["peak_bytes"] == (m * B + m * k + cfg.c_out + cfg.c_in(m) + B) * Ps == dnb.dnb_block_peak_bytes(h)
+    dnb.dnb_block_destroy(h)
 
 
 def test_config1_bytes_as_stated(dnb):
