@@ -9,6 +9,10 @@
 // K-steps.  The order of the K index inside a sum is free, so lane group g takes channels
 // {g, 4+g, 8+g, 12+g} of a 16-channel chunk and a channel tail that is a multiple of 4
 // costs no padding.
+#ifndef DNB_DBG
+#define DNB_DBG 0  // kernel ablation builds for tuning experiments (1: no MFMA, 2/4: no activation / weight loads)
+#endif
+
 #include "dnb_internal.h"
 #include "dnb_stats.cuh"
 
@@ -94,28 +98,42 @@ __global__ __launch_bounds__(256) void k_pack_block_weights(const float* __restr
   }
 }
 
-// Sums the accumulators of the K-split waves of a workgroup (fixed order 0,1,2,...).  Every
-// wave writes its tiles to LDS; M-tile a is then owned by wave a % nw, which adds the nw copies
-// and keeps the result in its own registers.  red: [nw][MT*NT][64 lanes][4].
+// Sums the accumulators of the K-split waves of a workgroup (fixed order 0,1,2,...).  M-tile a
+// is owned by wave a % nw: every other wave writes its copy of the tile to LDS, the owner adds
+// the copies (its own stays in registers, inserted at its place in the order) and keeps the
+// result.  red: [MT*NT][nw-1 slots][64 lanes][4].
 template <int MT, int NT>
 __device__ __forceinline__ void ksplit_reduce(f32x4 (&acc)[MT][NT], float* red, int wave, int lane, int nw) {
-  __syncthreads();
+  __syncthreads();  // (wave = index inside the K group, nw = waves per K group, red = the group's buffer)
+  if (nw == 1) return;
 #pragma unroll
-  for (int a = 0; a < MT; ++a)
+  for (int a = 0; a < MT; ++a) {
+    const int owner = a % nw;
+    if (wave != owner) {
+      const int slot = (wave - owner - 1 + nw) % nw;
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
-      *reinterpret_cast<float4*>(&red[(((wave * MT + a) * NT + t) * 64 + lane) * 4]) =
-          make_float4(acc[a][t][0], acc[a][t][1], acc[a][t][2], acc[a][t][3]);
+      for (int t = 0; t < NT; ++t)
+        *reinterpret_cast<float4*>(&red[((((a * NT + t) * (nw - 1)) + slot) * 64 + lane) * 4]) =
+            make_float4(acc[a][t][0], acc[a][t][1], acc[a][t][2], acc[a][t][3]);
+    }
+  }
   __syncthreads();
 #pragma unroll
   for (int a = 0; a < MT; ++a) {
-    if (a % nw == wave) {
+    const int owner = a % nw;
+    if (wave == owner) {
 #pragma unroll
       for (int t = 0; t < NT; ++t) {
         f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
         for (int w = 0; w < nw; ++w) {
-          const float4 v = *reinterpret_cast<const float4*>(&red[(((w * MT + a) * NT + t) * 64 + lane) * 4]);
-          s[0] += v.x; s[1] += v.y; s[2] += v.z; s[3] += v.w;
+          if (w == owner) {
+            s[0] += acc[a][t][0]; s[1] += acc[a][t][1]; s[2] += acc[a][t][2]; s[3] += acc[a][t][3];
+          } else {
+            const int slot = (w - owner - 1 + nw) % nw;
+            const float4 v = *reinterpret_cast<const float4*>(
+                &red[((((a * NT + t) * (nw - 1)) + slot) * 64 + lane) * 4]);
+            s[0] += v.x; s[1] += v.y; s[2] += v.z; s[3] += v.w;
+          }
         }
         acc[a][t] = s;
       }
@@ -172,11 +190,16 @@ template <int MT, int PPL, bool KSPLIT, bool PRO, bool STATS>
 __global__ __launch_bounds__(256) void k_conv1x1_v3(
     const float* __restrict__ in, int64_t in_stride, const float* __restrict__ Wp, int Kpad,
     float* __restrict__ out, int64_t out_stride, int cin, int cout, int HW,
-    const float2* __restrict__ fold, float* __restrict__ spart, int sT) {
+    const float2* __restrict__ fold, float* __restrict__ spart, int sT, int wk) {
   extern __shared__ float red[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, nw = blockDim.x >> 6;
+  // KSPLIT: the workgroup's waves form wp pixel groups of wk waves; a group shares one pixel tile
+  // and splits K.  !KSPLIT: all waves share the pixel tile and split M (wk = 1).
+  const int tid = threadIdx.x, lane = tid & 63, wave_all = tid >> 6, nw_all = blockDim.x >> 6;
+  const int wave = KSPLIT ? wave_all % wk : wave_all, nw = KSPLIT ? wk : nw_all;
+  const int wpid = KSPLIT ? wave_all / wk : 0, wp = KSPLIT ? nw_all / wk : 1;
   const int j = lane & 15, g = lane >> 4;
-  const int q = blockIdx.x * (16 * PPL) + PPL * j;
+  const int tile = blockIdx.x * wp + wpid;
+  const int q = tile * (16 * PPL) + PPL * j;
   const int img = blockIdx.z;
   const bool pix_ok = q < HW;
   const float* inb = in + (int64_t)img * in_stride + q;
@@ -193,73 +216,90 @@ __global__ __launch_bounds__(256) void k_conv1x1_v3(
 #pragma unroll
     for (int t = 0; t < PPL; ++t) acc[a][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  float cur[4][PPL], nxt[4][PPL];
-  float4 wcur[MT], wnxt[MT];
-  auto load_chunk = [&](int ch0, float(&v)[4][PPL], float4(&w4)[MT]) {
+  // Ring of D chunks in registers: chunk i+D is requested right after chunk i has been fed to
+  // the MFMAs, so a wave keeps D-1..D chunks (activations + weights) in flight and a single wave
+  // per SIMD can cover the HBM latency.  The loop body is branch free on purpose: every load is
+  // unconditional with a clamped address (out-of-range channels read the last real channel and
+  // meet zero weights; out-of-range pixels read pixel 0 and are never stored; ring slots past
+  // the wave's last chunk get their weights zeroed), so the compiler's wait counters stay exact
+  // and loads overlap the MFMAs.
+  constexpr int D = 3;
+  float buf[D][4][PPL];
+  float4 wbuf[D][MT];
+  float2 fbuf[D][4];  // PRO: folded BN of the slot's four channels, applied when the slot is used
+  float keep[D];      // 0 for ring slots past the wave's last chunk
+  const float* inq = in + (int64_t)img * in_stride + (pix_ok ? q : 0);
+  const int nmy = (m_ok && cstart < nchunks) ? (nchunks - cstart + cstep - 1) / cstep : 0;  // chunks of this wave
+  // nothing in here may consume a loaded value: the loads must stay in flight
+  auto load_chunk = [&](int i, float(&v)[4][PPL], float4(&w4)[MT], float2(&f)[4], float& kp) {
+    const bool valid = i < nmy;
+    kp = valid ? 1.f : 0.f;
+    const int ch0 = (cstart + (valid ? i : 0) * cstep) * 16;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
-      const int ch = ch0 + 4 * ks + g;
-      const bool ok = pix_ok && ch < cin;
-      float2 f = make_float2(1.f, 0.f);
-      if (PRO && ok) f = fold[ch];
-      if (PPL == 4) {
-        const float4 t = ok ? ldg4(inb + (int64_t)ch * HW) : zero4();
+      const int ch = min(ch0 + 4 * ks + g, cin - 1);
+      if (DNB_DBG & 2) {
+#pragma unroll
+        for (int t = 0; t < PPL; ++t) v[ks][t] = 1.f;
+      } else if (PPL == 4) {
+        const float4 t = ldg4(inq + (int64_t)ch * HW);
         v[ks][0] = t.x; v[ks][1 % PPL] = t.y; v[ks][2 % PPL] = t.z; v[ks][3 % PPL] = t.w;
       } else {
-        v[ks][0] = ok ? inb[(int64_t)ch * HW] : 0.f;
+        v[ks][0] = inq[(int64_t)ch * HW];
       }
-      if (PRO) {
-#pragma unroll
-        for (int t = 0; t < PPL; ++t) v[ks][t] = ok ? fmaxf(__fmaf_rn(v[ks][t], f.x, f.y), 0.f) : 0.f;
-      }
+      if (PRO) f[ks] = fold[ch];
     }
 #pragma unroll
     for (int a = 0; a < MT; ++a) {
-      // rows of M-tiles past the padded output-channel count do not exist: leave them zero
-      const bool rok = mbase + a * 16 < M16;
-      w4[a] = rok ? ldg4(wrow + (int64_t)a * 16 * Kpad + ch0) : zero4();
+      // M-tiles past the padded output-channel count read tile 0's rows; they are never stored
+      const int row = (mbase + a * 16 < M16) ? mbase + a * 16 + j : j;
+      w4[a] = (DNB_DBG & 4) ? make_float4(1.f, 1.f, 1.f, 1.f) : ldg4(Wp + (int64_t)row * Kpad + 4 * g + ch0);
     }
   };
 
-  if (m_ok) {
-    if (cstart < nchunks) load_chunk(cstart * 16, cur, wcur);
-    for (int ci = cstart; ci < nchunks; ci += cstep) {
-      const int c0 = ci * 16;
-      const bool more = ci + cstep < nchunks;
-      if (more) load_chunk(c0 + cstep * 16, nxt, wnxt);
-      const int nks = min(4, (cin - c0 + 3) >> 2);
+  if (nmy > 0) {  // uniform per wave
 #pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        if (ks < nks) {
+    for (int d = 0; d < D; ++d) load_chunk(d, buf[d], wbuf[d], fbuf[d], keep[d]);
+    for (int base = 0; base < nmy; base += D) {
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          float bv[PPL];
+#pragma unroll
+          for (int t = 0; t < PPL; ++t)
+            bv[t] = PRO ? fmaxf(__fmaf_rn(buf[d][ks][t], fbuf[d][ks].x, fbuf[d][ks].y), 0.f) : buf[d][ks][t];
 #pragma unroll
           for (int a = 0; a < MT; ++a) {
-            const float wa = elem(wcur[a], ks);
+            const float wa = elem(wbuf[d][a], ks) * keep[d];
 #pragma unroll
-            for (int t = 0; t < PPL; ++t) acc[a][t] = mfma16(wa, cur[ks][t], acc[a][t]);
+            for (int t = 0; t < PPL; ++t) {
+              if (DNB_DBG & 1) acc[a][t][(ks + t) & 3] += wa * bv[t];
+              else acc[a][t] = mfma16(wa, bv[t], acc[a][t]);
+            }
           }
         }
-      }
-      if (more) {
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-          for (int t = 0; t < PPL; ++t) cur[ks][t] = nxt[ks][t];
-#pragma unroll
-        for (int a = 0; a < MT; ++a) wcur[a] = wnxt[a];
+        // keep the refill of this slot here, D chunks ahead of its use (the scheduler would
+        // otherwise sink the loads to just before they are consumed)
+        __builtin_amdgcn_sched_barrier(0);
+        load_chunk(base + d + D, buf[d], wbuf[d], fbuf[d], keep[d]);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
 
-  if (KSPLIT) ksplit_reduce<MT, PPL>(acc, red, wave, lane, nw);
+  if (KSPLIT) ksplit_reduce<MT, PPL>(acc, red + (size_t)wpid * MT * PPL * (nw - 1) * 256, wave, lane, nw);
 
-  const int tile_px = min(16 * PPL, HW - (int)blockIdx.x * (16 * PPL));
+  const int tiles_per_img = (HW + 16 * PPL - 1) / (16 * PPL);
+  const int tile_px = min(16 * PPL, HW - tile * (16 * PPL));
 #pragma unroll
   for (int a = 0; a < MT; ++a) {
     if (KSPLIT && a % nw != wave) continue;  // after the reduction M-tile a lives in wave a % nw
     if (mbase + a * 16 >= M16) continue;
     if (STATS)
-      tile_stats<PPL>(acc[a], pix_ok, (float)tile_px, mbase + a * 16, cout, spart, sT,
-                      img * gridDim.x + blockIdx.x);
+      if (tile_px > 0)
+        tile_stats<PPL>(acc[a], pix_ok, (float)tile_px, mbase + a * 16, cout, spart, sT,
+                        img * tiles_per_img + tile);
     if (pix_ok) {
       float* ob = out + (int64_t)img * out_stride + q;
 #pragma unroll
@@ -713,13 +753,19 @@ bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, f
     }
     // 64-pixel tiles unless that leaves the chip underfilled (fewer than 2 workgroups per CU)
     const int ppl = ((int64_t)((hw + 63) / 64) * gy * n >= 512) ? 4 : 1;
-    dim3 grid((unsigned)((hw + 16 * ppl - 1) / (16 * ppl)), (unsigned)gy, (unsigned)n);
-    const size_t lds = ksplit ? (size_t)nw * mt * ppl * 256 * sizeof(float) : 0;
-    const int T = (int)grid.x * n;
+    const int tiles = (hw + 16 * ppl - 1) / (16 * ppl);
+    // 64-pixel tiles: two waves share a tile's K range and two tiles share the workgroup (longer
+    // contiguous runs per channel row measured faster than four-way K-split); 16-pixel tiles of
+    // small images: four-way K-split for more loads in flight
+    const int wk = ksplit ? (ppl == 4 ? 2 : nw) : 1;
+    const int wp = ksplit ? nw / wk : 1;
+    dim3 grid((unsigned)((tiles + wp - 1) / wp), (unsigned)gy, (unsigned)n);
+    const size_t lds = ksplit ? (size_t)wp * (wk - 1) * mt * ppl * 256 * sizeof(float) : 0;
+    const int T = tiles * n;
     if (sT) *sT = T;
 #define DNB_L(MT, PPL, KS, PRO, STATS)                                                                \
   hipLaunchKernelGGL((k_conv1x1_v3<MT, PPL, KS, PRO, STATS>), grid, dim3(64 * nw), lds, st, in,        \
-                     in_stride, packed, K16, out, out_stride, cin, cout, hw, fold, spart, T)
+                     in_stride, packed, K16, out, out_stride, cin, cout, hw, fold, spart, T, wk)
 #define DNB_L3(MT, PPL, KS)                                                         \
   do {                                                                              \
     if (mode == 2) DNB_L(MT, PPL, KS, true, true);                                   \
@@ -748,7 +794,7 @@ bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, f
     gy = (mtiles + nw * mt - 1) / (nw * mt);
   }
   const int CS = pad4mod32(64 + 2 * w + 8);
-  const size_t tile = (size_t)((cin + 3) & ~3) * CS, red = ksplit ? (size_t)nw * mt * 4 * 256 : 0;
+  const size_t tile = (size_t)((cin + 3) & ~3) * CS, red = ksplit ? (size_t)(nw - 1) * mt * 4 * 256 : 0;
   const size_t lds = (tile > red ? tile : red) * sizeof(float);
   if (lds > 64 * 1024) return false;
   dim3 grid((unsigned)((hw + 63) / 64), (unsigned)gy, (unsigned)n);
