@@ -3,10 +3,11 @@
 
 A step = forward + backward of every dense block of the workload (default: the three
 dense blocks of DenseNet-BC L=100, k=12, batch 64, fp32 -- benchmark configs[1]) through
-the C ABI, shared-storage schedule, inputs resident in HBM.  Prints ONE JSON line with
-training images/s, the roofline of the dominant kernel measured live with events on the
-launch stream, the store-everything schedule's rate (recompute overhead), exact peak
-feature-map bytes, and the CPU oracle timed on the host cores.
+the C ABI, inputs resident in HBM.  Prints ONE JSON line with training images/s of the fastest
+linear-memory schedule (fused), the rates of the paper-literal shared-storage schedule and of
+the store-everything schedule (recompute overhead), exact peak feature-map bytes, the roofline
+of the dominant kernel measured live with events on the launch stream, and the CPU oracle timed
+on the host cores.
 """
 from __future__ import annotations
 
@@ -31,7 +32,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3"])
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
-    ap.add_argument("--schedule", default="shared", choices=["shared", "store_all", "fused"])
+    ap.add_argument("--schedule", default="fused", choices=["shared", "store_all", "fused"],
+                    help="fused: BN+ReLU recomputed inside the conv operand loads (default, fastest linear-memory schedule); "
+                         "shared: storage 1/2/3 materialised as in the paper; store_all: every intermediate kept")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-compare", action="store_true", help="skip timing the other schedule")
@@ -117,40 +120,56 @@ def event_time_ms(torch, fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
-def dominant_kernel_roofline(dnb, torch, runs):
-    """Live measurement of the kernel that takes the largest share of the step (per the
-    committed rocprofv3 summary): the BN+ReLU backward apply pass of the first BN, which reads
-    the layer input, the incoming gradient and the gradient slab and writes the slab
-    (4 * C_l * P * 4 bytes).  Replayed per layer shape of the largest block via the
-    single-op entry point, timed with events on the launch stream."""
-    r = runs[0]
-    cfg = r.cfg
-    hw, n = cfg.h * cfg.w, cfg.n
-    cm = cfg.c_in(cfg.layers)
-    x = torch.randn((n, cm, cfg.h, cfg.w), device="cuda")
-    dact = torch.randn_like(x)
-    G = torch.zeros((n, cfg.c_out, cfg.h, cfg.w), device="cuda")
-    gamma, beta = torch.ones(cm, device="cuda"), torch.zeros(cm, device="cuda")
-    mean, istd = torch.zeros(cm, device="cuda"), torch.ones(cm, device="cuda")
-    dg, db = torch.empty(cm, device="cuda"), torch.empty(cm, device="cuda")
-    scratch = torch.empty(dnb.dnb_op_bn_scratch_bytes(n, cm, hw), dtype=torch.uint8, device="cuda")
-    total_bytes, launches = 0, 0
+DOMINANT_KERNEL = "k_bn_bwd_apply<4, true>"
+# Mean HBM bytes per launch of that kernel on the first dense block's 16 layer shapes, from the two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by the copy kernel of known size)
+# summarised in profiles/bc100_b64_fp32_bn_bwd_apply_hbm_traffic.txt; valid for that workload only.
+MEASURED_TRAFFIC = {"config2:64": 119595721}
 
-    def all_layers():
+
+def dominant_kernel_roofline(dnb, torch, runs, traffic_key):
+    """Live measurement of the kernel with the largest share of the step in the committed
+    rocprofv3 summary (profiles/): the apply pass of the first BN's backward, which also is the
+    concatenation's backward -- per element it reads the layer input x, the incoming gradient and
+    the gradient slab G and writes G: 4 * C_l * P * 4 algorithmic bytes per launch.  Every
+    layer shape of the workload's largest dense block (where three quarters of this kernel's time
+    goes; the small blocks' launches are a few microseconds, below what an event pair resolves)
+    is launched with its real strides through the single-op entry point, each launch stamping its
+    own pair of events at kernel start and end on the launch stream; `achieved` = mean bytes / mean duration."""
+    times, nbytes = [], []
+    for r in runs[:1]:
+        cfg = r.cfg
+        hw, n, cout = cfg.h * cfg.w, cfg.n, cfg.c_out
+        cm = cfg.c_in(cfg.layers)
+        x = torch.randn((n, cout, cfg.h, cfg.w), device="cuda")
+        dact = torch.randn((n, cm, cfg.h, cfg.w), device="cuda")
+        G = torch.zeros((n, cout, cfg.h, cfg.w), device="cuda")
+        gamma, beta = torch.ones(cm, device="cuda"), torch.zeros(cm, device="cuda")
+        mean, istd = torch.zeros(cm, device="cuda"), torch.ones(cm, device="cuda")
+        dg, db = torch.empty(cm, device="cuda"), torch.empty(cm, device="cuda")
+        scratch = torch.empty(dnb.dnb_op_bn_scratch_bytes(n, cm, hw), dtype=torch.uint8, device="cuda")
         for l in range(1, cfg.layers + 1):
             c = cfg.c_in(l)
-            dnb.dnb_op_bn_relu_backward(x, c * hw, dact, c * hw, G, cfg.c_out * hw, 1, n, c, hw, gamma, beta,
-                                        mean, istd, dg, db, scratch)
-    for l in range(1, cfg.layers + 1):
-        # reduce pass: read x and dact (2 C P); apply pass: read x, dact, G and write G (4 C P)
-        total_bytes += 6 * cfg.c_in(l) * n * hw * 4
-        launches += 1
-    ms = event_time_ms(torch, all_layers, 10)
-    achieved = total_bytes / (ms * 1e-3) / 1e9
-    return {"bound": "hbm", "kernel": "bn_relu_backward (reduce + apply, first BN, block 1 layer shapes)",
+            args = (x, cout * hw, dact, c * hw, G, cout * hw, 1, n, c, hw, gamma, beta, mean, istd, dg, db, scratch)
+            dnb.dnb_op_bn_relu_backward(*args)          # leaves this shape's partial sums in scratch
+            dnb.dnb_op_bn_relu_backward_apply(*args)    # warm
+            reps = 5
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+            for e0, e1 in evs:
+                e0.record(); e1.record()   # creates the handles; the launch below re-stamps both
+                dnb.dnb_op_bn_relu_backward_apply(*args, ev_start=e0, ev_stop=e1)
+            torch.cuda.synchronize()
+            times.append(sum(e0.elapsed_time(e1) for e0, e1 in evs) / reps)
+            nbytes.append(4 * c * n * hw * 4)
+    ms = sum(times) / len(times)
+    by = sum(nbytes) / len(nbytes)
+    achieved = by / (ms * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC.get(traffic_key)
+    return {"bound": "hbm", "kernel": DOMINANT_KERNEL + " (BN1 backward apply + concat backward)",
             "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-            "avg_launch_ms": round(ms / launches, 5), "algorithmic_bytes_per_launch": total_bytes // launches}
+            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+            "avg_launch_ms": round(ms, 5), "algorithmic_bytes_per_launch": int(by), "launches_averaged": len(times),
+            "shapes": "the %d layers of the first dense block (P = %d pixels)" % (len(times), runs[0].cfg.pixels)}
 
 
 def cpu_baseline(wl, blocks):
@@ -218,18 +237,24 @@ def main():
                                    "total": sum(r.mem["peak_bytes"] for r in runs),
                                    "workspace_total": sum(r.mem["workspace_bytes"] for r in runs)},
     }
-    out["roofline"] = dominant_kernel_roofline(dnb, torch, runs)
+    out["roofline"] = dominant_kernel_roofline(dnb, torch, runs, f"{a.workload}:{batch}" if a.only_block < 0 else "")
     del runs
     torch.cuda.empty_cache()
     if not a.no_compare:
-        other = "store_all" if a.schedule == "shared" else "shared"
-        oruns, osecs = measure(other)
-        t_shared, t_all = (secs, osecs) if a.schedule == "shared" else (osecs, secs)
-        out["store_all_images_per_s" if other == "store_all" else "shared_images_per_s"] = round(batch * a.steps / osecs, 2)
-        out["recompute_overhead"] = round(t_shared / t_all - 1.0, 4)
-        out["peak_feature_map_bytes"][other + "_total"] = sum(r.mem["peak_bytes"] for r in oruns)
-        del oruns
-        torch.cuda.empty_cache()
+        # the other schedules on the same workload: the paper-literal shared-storage schedule and
+        # the store-everything schedule it is compared with (Section 5)
+        t = {a.schedule: secs}
+        for other in ("shared", "store_all", "fused"):
+            if other in t:
+                continue
+            oruns, osecs = measure(other)
+            t[other] = osecs
+            out[other + "_images_per_s"] = round(batch * a.steps / osecs, 2)
+            out["peak_feature_map_bytes"][other + "_total"] = sum(r.mem["peak_bytes"] for r in oruns)
+            del oruns
+            torch.cuda.empty_cache()
+        out["recompute_overhead"] = round(t["shared"] / t["store_all"] - 1.0, 4)
+        out["fused_vs_store_all_time"] = round(t["fused"] / t["store_all"] - 1.0, 4)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, blocks)
     print(json.dumps(out), flush=True)

@@ -160,6 +160,15 @@ int dnb_op_bn_relu_backward(const void* x, int64_t x_stride, const void* dact, i
                             int64_t hw, const void* gamma, const void* beta, const void* mean,
                             const void* istd, void* dgamma, void* dbeta, void* scratch,
                             void* stream);
+/* Second pass of dnb_op_bn_relu_backward alone (the per-element apply), reusing the partial
+ * sums a previous full call left in `scratch` for the same shape: lets a benchmark time the
+ * apply kernel by itself.  ev_start / ev_stop (hipEvent_t as void*, may be NULL) are stamped
+ * at the kernel's own start and end on `stream`. */
+int dnb_op_bn_relu_backward_apply(const void* x, int64_t x_stride, const void* dact, int64_t dact_stride,
+                                  void* du, int64_t du_stride, int accumulate, int64_t n, int64_t c,
+                                  int64_t hw, const void* gamma, const void* beta, const void* mean,
+                                  const void* istd, void* dgamma, void* dbeta, const void* scratch,
+                                  void* ev_start, void* ev_stop, void* stream);
 /* Convolutions: ks = 1 or 3, stride 1, zero padding (ks-1)/2, no bias,
  * cross-correlation; weights OIHW (cout, cin, ks, ks).  `scratch` holds the re-laid
  * weights (forward, dgrad: dnb_op_conv_scratch_bytes) or the split reduction partials of

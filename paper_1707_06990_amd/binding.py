@@ -58,6 +58,8 @@ _SIGS = {
     "dnb_op_bn_relu": (C.c_int, [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp]),
     "dnb_op_bn_relu_backward": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, C.c_int, _i64, _i64, _i64,
                                           _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "dnb_op_bn_relu_backward_apply": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, C.c_int, _i64, _i64, _i64,
+                                                _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "dnb_op_conv_scratch_bytes": (_sz, [_i64, _i64, C.c_int]),
     "dnb_op_conv_forward": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
     "dnb_op_conv_dgrad": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
@@ -175,6 +177,19 @@ def dnb_op_bn_relu_backward(x, x_stride, dact, dact_stride, du, du_stride, accum
     _check(_lib.dnb_op_bn_relu_backward(_ptr(x), x_stride, _ptr(dact), dact_stride, _ptr(du), du_stride,
                                         int(accumulate), n, c, hw, _ptr(gamma), _ptr(beta), _ptr(mean),
                                         _ptr(istd), _ptr(dgamma), _ptr(dbeta), _ptr(scratch), _stream(stream)))
+
+
+def dnb_op_bn_relu_backward_apply(x, x_stride, dact, dact_stride, du, du_stride, accumulate, n, c, hw, gamma,
+                                  beta, mean, istd, dgamma, dbeta, scratch, ev_start=None, ev_stop=None,
+                                  stream=None) -> None:
+    """ev_start / ev_stop: torch.cuda.Event(enable_timing=True) that have been recorded once (so their
+    handles exist), or None; they are stamped at the kernel's own start and end."""
+    h0 = ev_start.cuda_event if ev_start is not None else None
+    h1 = ev_stop.cuda_event if ev_stop is not None else None
+    _check(_lib.dnb_op_bn_relu_backward_apply(_ptr(x), x_stride, _ptr(dact), dact_stride, _ptr(du), du_stride,
+                                              int(accumulate), n, c, hw, _ptr(gamma), _ptr(beta), _ptr(mean),
+                                              _ptr(istd), _ptr(dgamma), _ptr(dbeta), _ptr(scratch), h0, h1,
+                                              _stream(stream)))
 
 
 def dnb_op_conv_scratch_bytes(cin, cout, ks) -> int:

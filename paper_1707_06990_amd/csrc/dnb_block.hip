@@ -520,6 +520,22 @@ int dnb_op_bn_relu_backward(const void* x, int64_t x_stride, const void* dact, i
   return DNB_OK;
 }
 
+int dnb_op_bn_relu_backward_apply(const void* x, int64_t x_stride, const void* dact, int64_t dact_stride,
+                                  void* du, int64_t du_stride, int accumulate, int64_t n, int64_t c,
+                                  int64_t hw, const void* gamma, const void* beta, const void* mean,
+                                  const void* istd, void* dgamma, void* dbeta, const void* scratch,
+                                  void* ev_start, void* ev_stop, void* stream) {
+  if (!x || !dact || !du || !gamma || !beta || !mean || !istd || !dgamma || !dbeta || !scratch)
+    return DNB_E_NULL;
+  if (n < 1 || c < 1 || hw < 1 || c > 65535) return DNB_E_RANGE;
+  DNB_TRY(launch_bn_relu_bwd((const float*)x, x_stride, (const float*)dact, dact_stride, (float*)du,
+                             du_stride, accumulate != 0, (int)n, (int)c, (int)hw, (const float*)gamma,
+                             (const float*)beta, (const float*)mean, (const float*)istd,
+                             (float*)dgamma, (float*)dbeta, (float*)const_cast<void*>(scratch),
+                             (hipStream_t)stream, 2, (hipEvent_t)ev_start, (hipEvent_t)ev_stop));
+  return DNB_OK;
+}
+
 static int conv_args_ok(int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w, int ks) {
   if (ks != 1 && ks != 3) return DNB_E_UNSUPPORTED;
   if (n < 1 || cin < 1 || cout < 1 || h < 1 || w < 1 || n > 65535) return DNB_E_RANGE;

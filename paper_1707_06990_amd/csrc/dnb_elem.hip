@@ -4,6 +4,8 @@
 // 16-byte accesses along the contiguous pixel axis, one pass over the data per
 // kernel, wave-level butterfly reductions and LDS only to combine the waves of a
 // workgroup.
+#include <hip/hip_ext.h>
+
 #include "dnb_internal.h"
 #include "dnb_stats.cuh"
 
@@ -377,23 +379,28 @@ hipError_t launch_bn_relu_bwd(const float* x, int64_t x_stride, const float* dac
                               int64_t dact_stride, float* du, int64_t du_stride, bool accumulate,
                               int n, int c, int hw, const float* gamma, const float* beta,
                               const float* mean, const float* istd, float* dgamma, float* dbeta,
-                              float* partials, hipStream_t st) {
+                              float* partials, hipStream_t st, int passes, hipEvent_t ev_start,
+                              hipEvent_t ev_stop) {
   if (n <= 0 || c <= 0 || hw <= 0) return hipSuccess;
   const Split p = split_plan(n, c, hw);
   const bool v4 = (hw % 4 == 0) && (x_stride % 4 == 0) && (dact_stride % 4 == 0) &&
                   (du_stride % 4 == 0) && aligned16(x) && aligned16(dact) && aligned16(du);
   dim3 grid((unsigned)c, (unsigned)p.gs);
-  if (v4)
-    hipLaunchKernelGGL(k_bn_bwd_partial<4>, grid, dim3(kThreads), 0, st, x, x_stride, dact, dact_stride,
-                       n, hw, p.ipb, gamma, beta, mean, istd, partials);
-  else
-    hipLaunchKernelGGL(k_bn_bwd_partial<1>, grid, dim3(kThreads), 0, st, x, x_stride, dact, dact_stride,
-                       n, hw, p.ipb, gamma, beta, mean, istd, partials);
+  if (passes & 1) {
+    if (v4)
+      hipLaunchKernelGGL(k_bn_bwd_partial<4>, grid, dim3(kThreads), 0, st, x, x_stride, dact, dact_stride,
+                         n, hw, p.ipb, gamma, beta, mean, istd, partials);
+    else
+      hipLaunchKernelGGL(k_bn_bwd_partial<1>, grid, dim3(kThreads), 0, st, x, x_stride, dact, dact_stride,
+                         n, hw, p.ipb, gamma, beta, mean, istd, partials);
+  }
+  if (!(passes & 2)) return hipGetLastError();
   const float inv_p = 1.0f / ((float)n * (float)hw);
+  // (the Ext launch stamps the two optional events right at the kernel's start and end)
 #define DNB_LAUNCH_BNBWD(V, A)                                                                      \
-  hipLaunchKernelGGL((k_bn_bwd_apply<V, A>), grid, dim3(kThreads), 0, st, x, x_stride, dact,       \
-                     dact_stride, du, du_stride, n, hw, p.ipb, inv_p, gamma, beta, mean, istd,     \
-                     partials, p.gs, dgamma, dbeta)
+  hipExtLaunchKernelGGL((k_bn_bwd_apply<V, A>), grid, dim3(kThreads), 0, st, ev_start, ev_stop, 0, \
+                        x, x_stride, dact, dact_stride, du, du_stride, n, hw, p.ipb, inv_p, gamma, \
+                        beta, mean, istd, (const float*)partials, p.gs, dgamma, dbeta)
   if (v4) { if (accumulate) DNB_LAUNCH_BNBWD(4, true); else DNB_LAUNCH_BNBWD(4, false); }
   else    { if (accumulate) DNB_LAUNCH_BNBWD(1, true); else DNB_LAUNCH_BNBWD(1, false); }
 #undef DNB_LAUNCH_BNBWD

@@ -49,7 +49,8 @@ hipError_t launch_bn_relu_bwd(const float* x, int64_t x_stride, const float* dac
                               int64_t dact_stride, float* du, int64_t du_stride, bool accumulate,
                               int n, int c, int hw, const float* gamma, const float* beta,
                               const float* mean, const float* istd, float* dgamma, float* dbeta,
-                              float* partials, hipStream_t st);
+                              float* partials, hipStream_t st, int passes = 3 /*1 reduce | 2 apply*/,
+                              hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
 // ---- convolutions (MFMA implicit GEMM, fp32) -----------------------------------------------
 
