@@ -23,6 +23,10 @@
  *                        overwrite them; backward re-runs concat and BN to
  *                        re-populate them before ordinary back-propagation.
  *   Both track the peak number of live feature-map elements they allocate.
+ *   dnbo_block_naive_bf16 -- the store-everything schedule with every stored tensor rounded
+ *                        to bfloat16 where it is produced (arithmetic still float64); the
+ *                        reference for the bf16 path's gradients.  Pinned by a library
+ *                        autograd construction with casts at the same points.
  *
  * Readings where the paper is silent (listed in the design notes too):
  *   BN uses train-mode batch statistics over (n,h,w), biased variance, eps
@@ -121,6 +125,33 @@ static double* fm_alloc(dnbo_mem* mem, int64_t elems) {
 static void fm_free(dnbo_mem* mem, double* p, int64_t elems) {
   free(p);
   if (mem) mem->live_elems -= elems;
+}
+
+/* Storage-precision emulation (reading of the bf16 workloads: "bf16 activations/weights with
+ * fp32 accumulation and fp32 BN statistics"): a value that the bf16 path keeps in memory is
+ * rounded to the nearest bfloat16 (8-bit significand, round to nearest even) at the point
+ * where it is stored; all arithmetic stays float64.  Used only by dnbo_block_naive_bf16. */
+double dnbo_round_bf16(double v) {
+  float f = (float)v;
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  if ((u & 0x7F800000u) == 0x7F800000u) return (double)f; /* inf / nan unchanged */
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  u &= 0xFFFF0000u;
+  memcpy(&f, &u, 4);
+  return (double)f;
+}
+
+static void quantize(double* p, int64_t count, int on) {
+  if (!on) return;
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < count; ++i) p[i] = dnbo_round_bf16(p[i]);
+}
+
+static double* rounded_copy(const double* src, int64_t count, int on) {
+  double* q = (double*)malloc((size_t)(count > 0 ? count : 1) * sizeof(double));
+  for (int64_t i = 0; i < count; ++i) q[i] = on ? dnbo_round_bf16(src[i]) : src[i];
+  return q;
 }
 
 /* ------------------------------------------------------------- primitives */
@@ -358,8 +389,8 @@ static void split_dy(const double* dy, double** gx, int m, int64_t n, int64_t c0
  * reverse mode, layers m..1, with one gradient accumulator per feature
  * (dense connectivity: the gradient of x_l is complete once every later
  * layer has been processed). */
-int dnbo_block_naive(const dnbo_desc* d, const double* x0, const double* params, const double* dy,
-                     double* y, double* dx0, double* dparams, dnbo_mem* mem) {
+static int block_naive_impl(const dnbo_desc* d, const double* x0, const double* params, const double* dy,
+                            double* y, double* dx0, double* dparams, dnbo_mem* mem, int q /* bf16 storage */) {
   const int m = d->layers;
   const int64_t n = d->n, c0 = d->c0, k = d->growth, B = d->bottleneck, H = d->h, W = d->w;
   const int64_t hw = H * W, P = n * hw, cout = c0 + m * k;
@@ -373,6 +404,8 @@ int dnbo_block_naive(const dnbo_desc* d, const double* x0, const double* params,
   double** v1 = (double**)calloc((size_t)m + 1, sizeof(double*));
   double** mu2 = (double**)calloc((size_t)m + 1, sizeof(double*));
   double** v2 = (double**)calloc((size_t)m + 1, sizeof(double*));
+  double** W1q = (double**)calloc((size_t)m + 1, sizeof(double*)); /* weights as the convs read them */
+  double** W3q = (double**)calloc((size_t)m + 1, sizeof(double*));
 
   x[0] = (double*)x0; /* the caller's input is not ours to count */
   for (int l = 1; l <= m; ++l) {
@@ -385,20 +418,28 @@ int dnbo_block_naive(const dnbo_desc* d, const double* x0, const double* params,
     dnbo_bn_forward(u[l], n, c, hw, par(d, params, l, DNBO_G1), par(d, params, l, DNBO_B1), d->eps,
                     a[l], mu1[l], v1[l]);
     dnbo_relu_inplace(a[l], c * P);
+    quantize(a[l], c * P, q);
     x[l] = fm_alloc(mem, k * P);
+    int64_t nw3 = 0;
+    dnbo_param_offset(d, l, DNBO_W3, &nw3);
+    W3q[l] = rounded_copy(par(d, params, l, DNBO_W3), nw3, q);
     if (B > 0) {
+      W1q[l] = rounded_copy(par(d, params, l, DNBO_W1), B * c, q);
       b[l] = fm_alloc(mem, B * P);
-      dnbo_conv_forward(a[l], par(d, params, l, DNBO_W1), n, c, B, H, W, 1, b[l]);
+      dnbo_conv_forward(a[l], W1q[l], n, c, B, H, W, 1, b[l]);
+      quantize(b[l], B * P, q);
       a2[l] = fm_alloc(mem, B * P);
       mu2[l] = (double*)calloc((size_t)B, sizeof(double));
       v2[l] = (double*)calloc((size_t)B, sizeof(double));
       dnbo_bn_forward(b[l], n, B, hw, par(d, params, l, DNBO_G2), par(d, params, l, DNBO_B2),
                       d->eps, a2[l], mu2[l], v2[l]);
       dnbo_relu_inplace(a2[l], B * P);
-      dnbo_conv_forward(a2[l], par(d, params, l, DNBO_W3), n, B, k, H, W, 3, x[l]);
+      quantize(a2[l], B * P, q);
+      dnbo_conv_forward(a2[l], W3q[l], n, B, k, H, W, 3, x[l]);
     } else {
-      dnbo_conv_forward(a[l], par(d, params, l, DNBO_W3), n, c, k, H, W, 3, x[l]);
+      dnbo_conv_forward(a[l], W3q[l], n, c, k, H, W, 3, x[l]);
     }
+    quantize(x[l], k * P, q);
   }
   /* block output = concatenation of everything */
   concat_into(y, x, m + 1, n, c0, k, hw);
@@ -416,24 +457,32 @@ int dnbo_block_naive(const dnbo_desc* d, const double* x0, const double* params,
     split_dy(dy, gx, m, n, c0, k, hw);
     for (int l = m; l >= 1; --l) {
       const int64_t c = layer_cin(d, l);
+      /* the convs read the accumulated gradient of x_l as a rounded operand; the
+       * accumulators themselves stay unrounded (they are fp32 on the bf16 path) */
+      double* g = q ? rounded_copy(gx[l], k * P, 1) : gx[l];
       if (B > 0) {
-        dnbo_conv_wgrad(a2[l], gx[l], n, B, k, H, W, 3, dpar(d, dparams, l, DNBO_W3));
-        dnbo_conv_dgrad(gx[l], par(d, params, l, DNBO_W3), n, B, k, H, W, 3, da2);
+        dnbo_conv_wgrad(a2[l], g, n, B, k, H, W, 3, dpar(d, dparams, l, DNBO_W3));
+        dnbo_conv_dgrad(g, W3q[l], n, B, k, H, W, 3, da2);
+        quantize(da2, B * P, q);
         dnbo_relu_backward(a2[l], da2, da2, B * P);
         dnbo_bn_backward(b[l], da2, n, B, hw, par(d, params, l, DNBO_G2), mu2[l], v2[l], d->eps,
                          da2, dpar(d, dparams, l, DNBO_G2), dpar(d, dparams, l, DNBO_B2));
+        quantize(da2, B * P, q);
         dnbo_conv_wgrad(a[l], da2, n, c, B, H, W, 1, dpar(d, dparams, l, DNBO_W1));
-        dnbo_conv_dgrad(da2, par(d, params, l, DNBO_W1), n, c, B, H, W, 1, da);
+        dnbo_conv_dgrad(da2, W1q[l], n, c, B, H, W, 1, da);
       } else {
-        dnbo_conv_wgrad(a[l], gx[l], n, c, k, H, W, 3, dpar(d, dparams, l, DNBO_W3));
-        dnbo_conv_dgrad(gx[l], par(d, params, l, DNBO_W3), n, c, k, H, W, 3, da);
+        dnbo_conv_wgrad(a[l], g, n, c, k, H, W, 3, dpar(d, dparams, l, DNBO_W3));
+        dnbo_conv_dgrad(g, W3q[l], n, c, k, H, W, 3, da);
       }
+      quantize(da, c * P, q);
+      if (q) free(g);
       dnbo_relu_backward(a[l], da, da, c * P);
       dnbo_bn_backward(u[l], da, n, c, hw, par(d, params, l, DNBO_G1), mu1[l], v1[l], d->eps, da,
                        dpar(d, dparams, l, DNBO_G1), dpar(d, dparams, l, DNBO_B1));
       concat_backward_add(da, gx, l, n, c0, k, hw);
     }
     memcpy(dx0, gx[0], (size_t)(c0 * P) * sizeof(double));
+    quantize(dx0, c0 * P, q);
     fm_free(mem, da, cmax * P);
     if (da2) fm_free(mem, da2, B * P);
     fm_free(mem, gx[0], c0 * P);
@@ -453,10 +502,32 @@ int dnbo_block_naive(const dnbo_desc* d, const double* x0, const double* params,
     }
     free(mu1[l]);
     free(v1[l]);
+    free(W1q[l]);
+    free(W3q[l]);
   }
   free(x); free(u); free(a); free(b); free(a2); free(mu1); free(v1); free(mu2); free(v2);
+  free(W1q); free(W3q);
   (void)cout;
   return 0;
+}
+
+int dnbo_block_naive(const dnbo_desc* d, const double* x0, const double* params, const double* dy,
+                     double* y, double* dx0, double* dparams, dnbo_mem* mem) {
+  return block_naive_impl(d, x0, params, dy, y, dx0, dparams, mem, 0);
+}
+
+/* The same block with bf16 storage emulated: every tensor the bf16 path keeps in memory or
+ * feeds to a convolution as an operand is rounded to bfloat16 where it is produced -- the
+ * BN+ReLU outputs, the conv weights as read by forward and data-gradient convs, the conv
+ * outputs b_l and x_l (whose batch statistics are then those of the rounded values), the
+ * gradient of x_l as a conv operand, the data gradients leaving each conv and the bottleneck
+ * BN, and dx0.  Gradient accumulators, statistics and parameter gradients are not rounded.
+ * It separates storage quantisation from algorithmic error: ReLU masks decided on rounded
+ * values can flip, which moves a sum of random-sign gradient terms by far more than the
+ * rounding itself.  x0 and dy should already hold bf16-representable values. */
+int dnbo_block_naive_bf16(const dnbo_desc* d, const double* x0, const double* params, const double* dy,
+                          double* y, double* dx0, double* dparams, dnbo_mem* mem) {
+  return block_naive_impl(d, x0, params, dy, y, dx0, dparams, mem, 1);
 }
 
 /* ------------------------------------------- schedule 0: shared storage */

@@ -52,10 +52,12 @@ def lib():
         _lib.dnbo_param_count.argtypes = [C.POINTER(_Desc)]
         _lib.dnbo_param_offset.restype = C.c_int64
         _lib.dnbo_param_offset.argtypes = [C.POINTER(_Desc), C.c_int, C.c_int, C.POINTER(C.c_int64)]
-        for name in ("dnbo_block_naive", "dnbo_block_shared"):
+        for name in ("dnbo_block_naive", "dnbo_block_shared", "dnbo_block_naive_bf16"):
             f = getattr(_lib, name)
             f.restype = C.c_int
             f.argtypes = [C.POINTER(_Desc), _dp, _dp, _dp, _dp, _dp, _dp, C.POINTER(_Mem)]
+        _lib.dnbo_round_bf16.restype = C.c_double
+        _lib.dnbo_round_bf16.argtypes = [C.c_double]
         _lib.dnbo_block_probe_layer.restype = C.c_int
         _lib.dnbo_block_probe_layer.argtypes = [C.POINTER(_Desc), _dp, _dp, C.c_int, _dp, _dp]
         i64 = C.c_int64
@@ -149,7 +151,8 @@ def block(s: BlockShape, x0, params, dy=None, schedule: str = "naive") -> BlockR
     assert params.size == param_count(s)
     y = np.zeros((s.n, s.c_out, s.h, s.w), dtype=np.float64)
     mem = _Mem()
-    fn = {"naive": lib().dnbo_block_naive, "shared": lib().dnbo_block_shared}[schedule]
+    fn = {"naive": lib().dnbo_block_naive, "shared": lib().dnbo_block_shared,
+          "naive_bf16": lib().dnbo_block_naive_bf16}[schedule]
     if dy is None:
         fn(C.byref(d), _p(x0), _p(params), None, _p(y), None, None, C.byref(mem))
         return BlockResult(y, None, None, int(mem.peak_elems), int(mem.stored_elems))
@@ -158,6 +161,11 @@ def block(s: BlockShape, x0, params, dy=None, schedule: str = "naive") -> BlockR
     dparams = np.zeros_like(params)
     fn(C.byref(d), _p(x0), _p(params), _p(dy), _p(y), _p(dx0), _p(dparams), C.byref(mem))
     return BlockResult(y, dx0, dparams, int(mem.peak_elems), int(mem.stored_elems))
+
+
+def round_bf16(v: float) -> float:
+    """Nearest bfloat16 (ties to even) of a float64, as the storage-emulating block uses it."""
+    return float(lib().dnbo_round_bf16(float(v)))
 
 
 def probe_layer(s: BlockShape, x0, params, layer: int):

@@ -339,3 +339,65 @@ def test_parameter_counts_match_paper(oracle, row):
             c //= 2
     total += 2 * c + c * classes + classes
     assert abs(total / 1e6 - printed_m) <= tol_m, total
+
+
+# --------------------------------------------------- bf16 storage emulation
+
+def test_round_bf16_matches_library_cast(oracle):
+    """The oracle's rounding to bfloat16 against the tensor library's cast: random values over
+    many binades, exact ties (round to even), signs, and values that are already representable."""
+    rng = np.random.default_rng(7)
+    vals = list((rng.standard_normal(2000) * np.exp(rng.uniform(-20, 20, 2000))).astype(np.float32))
+    vals += [1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -(1.0 + 2.0 ** -8), 1.0 + 2.0 ** -8 + 2.0 ** -20, 0.0, -0.0, 1.5, 3.0e38 / 2]
+    ref = torch.tensor(vals, dtype=torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+    got = np.array([oracle.round_bf16(float(v)) for v in vals])
+    assert np.array_equal(got, ref)
+
+
+def _bf16_ste(t):
+    """Value rounded to bf16, gradient passed through unchanged."""
+    return t + (t.detach().to(torch.float32).to(torch.bfloat16).to(torch.float64) - t.detach())
+
+
+def _round_grad(t):
+    t.register_hook(lambda g: g.to(torch.float32).to(torch.bfloat16).to(torch.float64))
+    return t
+
+
+@pytest.mark.parametrize("cfg", [wl.BlockCfg(2, 4, 4, 4, 2, 4, 8), wl.BlockCfg(1, 8, 5, 3, 3, 2, 4)],
+                         ids=["n2c4h4w4m2k4B8", "n1c8h5w3m3k2B4"])
+def test_bf16_storage_block_matches_autograd_with_casts(oracle, cfg):
+    """The storage-emulating block against an independent construction: library float64 batch
+    norm and convolutions under autograd, with a cast to bfloat16 at every point where the bf16
+    path stores a tensor (values: BN+ReLU outputs, conv weights, conv outputs; gradients: of each
+    x_l before its convs use it, of each BN+ReLU output, of the bottleneck output, of x_0).  A
+    rounding point that is missing, misplaced or applied to an accumulator shows up at the 1e-3
+    level; agreement is asked to 1e-9."""
+    s, x0, params, dy, lp = setup(oracle, cfg)
+    r32 = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(torch.float32).to(torch.bfloat16).to(torch.float64)
+    x0q, dyq = r32(x0), r32(dy)
+    res = oracle.block(s, x0q.numpy(), params, dyq.numpy(), schedule="naive_bf16")
+
+    t = lambda a: torch.tensor(np.asarray(a, dtype=np.float64), requires_grad=True)
+    x0t = x0q.clone().requires_grad_(True)
+    tp = [{k: t(v) for k, v in p.items()} for p in lp]
+    feats = [x0t]
+    for p in tp:
+        u = torch.cat(feats, dim=1)
+        a = _round_grad(_bf16_ste(F.relu(F.batch_norm(u, None, None, p["g1"], p["b1"], True, 0.0, cfg.eps))))
+        b = _round_grad(_bf16_ste(F.conv2d(a, _bf16_ste(p["W1"]).reshape(cfg.bottleneck, -1, 1, 1))))
+        a2 = _round_grad(_bf16_ste(F.relu(F.batch_norm(b, None, None, p["g2"], p["b2"], True, 0.0, cfg.eps))))
+        x = _round_grad(_bf16_ste(F.conv2d(a2, _bf16_ste(p["W3"]), padding=1)))
+        feats.append(x)
+    y = torch.cat(feats, dim=1)
+    y.backward(dyq)
+    assert np.allclose(res.y, y.detach().numpy(), rtol=1e-9, atol=1e-12)
+    dx0_ref = x0t.grad.to(torch.float32).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.allclose(res.dx0, dx0_ref, rtol=1e-9, atol=1e-12)
+    for l, p in enumerate(tp, start=1):
+        for name in NAMES:
+            got = res.dparams[oracle.param_slice(s, l, NAMES.index(name))]
+            assert np.allclose(got, p[name].grad.numpy().ravel(), rtol=1e-8, atol=1e-11), (l, name)
+    # and it is a small perturbation of the unrounded block
+    plain = oracle.block(s, x0q.numpy(), params, dyq.numpy(), schedule="naive")
+    assert np.linalg.norm(res.y - plain.y) / np.linalg.norm(plain.y) < 1e-2
