@@ -186,6 +186,27 @@ int dnb_op_conv_wgrad(const void* x, int64_t x_stride, const void* dout, int64_t
                       void* dwgt, int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w, int ks,
                       void* scratch, void* stream);
 
+/* ---- single operations of the bf16 / NHWC path.  Feature maps are bf16 with channels
+ * contiguous; "ld" is the pixel stride in elements, so channel ranges of a wider tensor are
+ * addressed in place; channel counts are multiples of 8.  Weights and weight gradients are fp32
+ * OIHW.  `scratch`: dnb_op_nhwc_scratch_bytes(n, cin, cout, h, w, ks) device bytes. */
+size_t dnb_op_nhwc_scratch_bytes(int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w, int ks);
+int dnb_op_nhwc_conv_forward(const void* x, int64_t x_ld, const void* wgt, void* out, int64_t out_ld, int64_t n,
+                             int64_t cin, int64_t cout, int64_t h, int64_t w, int ks, void* scratch, void* stream);
+/* dout is bf16, or fp32 if dout_is_f32 (the block keeps its gradient slab in fp32). */
+int dnb_op_nhwc_conv_dgrad(const void* dout, int64_t dout_ld, int dout_is_f32, const void* wgt, void* din,
+                           int64_t din_ld, int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w, int ks,
+                           void* scratch, void* stream);
+int dnb_op_nhwc_conv_wgrad(const void* x, int64_t x_ld, const void* dout, int64_t dout_ld, int dout_is_f32, void* dwgt,
+                           int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w, int ks, void* scratch,
+                           void* stream);
+/* BN+ReLU backward over (pixels, c): du is written as bf16 to du_bf16 (may alias dact), or, if
+ * du_accum_f32 != NULL, added into that fp32 tensor instead. */
+int dnb_op_nhwc_bn_relu_backward(const void* x, int64_t x_ld, const void* dact, int64_t dact_ld, void* du_bf16,
+                                 int64_t du_ld, void* du_accum_f32, int64_t acc_ld, int64_t pixels, int64_t c,
+                                 const void* gamma, const void* beta, const void* mean, const void* istd,
+                                 void* dgamma, void* dbeta, void* scratch, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

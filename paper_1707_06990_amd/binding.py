@@ -65,6 +65,12 @@ _SIGS = {
     "dnb_op_conv_dgrad": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
     "dnb_op_conv_wgrad_scratch_bytes": (_sz, [_i64, _i64, _i64, _i64, _i64, C.c_int]),
     "dnb_op_conv_wgrad": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
+    "dnb_op_nhwc_scratch_bytes": (_sz, [_i64, _i64, _i64, _i64, _i64, C.c_int]),
+    "dnb_op_nhwc_conv_forward": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
+    "dnb_op_nhwc_conv_dgrad": (C.c_int, [_vp, _i64, C.c_int, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
+    "dnb_op_nhwc_conv_wgrad": (C.c_int, [_vp, _i64, _vp, _i64, C.c_int, _vp, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
+    "dnb_op_nhwc_bn_relu_backward": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64,
+                                               _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _f = getattr(_lib, _name)
@@ -213,3 +219,32 @@ def dnb_op_conv_wgrad_scratch_bytes(n, cin, cout, h, w, ks) -> int:
 def dnb_op_conv_wgrad(x, x_stride, dout, dout_stride, dwgt, n, cin, cout, h, w, ks, scratch, stream=None) -> None:
     _check(_lib.dnb_op_conv_wgrad(_ptr(x), x_stride, _ptr(dout), dout_stride, _ptr(dwgt), n, cin, cout, h, w,
                                   ks, _ptr(scratch), _stream(stream)))
+
+
+def dnb_op_nhwc_scratch_bytes(n, cin, cout, h, w, ks) -> int:
+    return int(_lib.dnb_op_nhwc_scratch_bytes(n, cin, cout, h, w, ks))
+
+
+def dnb_op_nhwc_conv_forward(x, x_ld, wgt, out, out_ld, n, cin, cout, h, w, ks, scratch, stream=None) -> None:
+    _check(_lib.dnb_op_nhwc_conv_forward(_ptr(x), x_ld, _ptr(wgt), _ptr(out), out_ld, n, cin, cout, h, w, ks,
+                                         _ptr(scratch), _stream(stream)))
+
+
+def dnb_op_nhwc_conv_dgrad(dout, dout_ld, dout_is_f32, wgt, din, din_ld, n, cin, cout, h, w, ks, scratch,
+                           stream=None) -> None:
+    _check(_lib.dnb_op_nhwc_conv_dgrad(_ptr(dout), dout_ld, int(dout_is_f32), _ptr(wgt), _ptr(din), din_ld, n, cin,
+                                       cout, h, w, ks, _ptr(scratch), _stream(stream)))
+
+
+def dnb_op_nhwc_conv_wgrad(x, x_ld, dout, dout_ld, dout_is_f32, dwgt, n, cin, cout, h, w, ks, scratch,
+                           stream=None) -> None:
+    _check(_lib.dnb_op_nhwc_conv_wgrad(_ptr(x), x_ld, _ptr(dout), dout_ld, int(dout_is_f32), _ptr(dwgt), n, cin, cout,
+                                       h, w, ks, _ptr(scratch), _stream(stream)))
+
+
+def dnb_op_nhwc_bn_relu_backward(x, x_ld, dact, dact_ld, du_bf16, du_ld, du_accum_f32, acc_ld, pixels, c, gamma, beta,
+                                 mean, istd, dgamma, dbeta, scratch, stream=None) -> None:
+    _check(_lib.dnb_op_nhwc_bn_relu_backward(_ptr(x), x_ld, _ptr(dact), dact_ld, _ptr(du_bf16), du_ld,
+                                             _ptr(du_accum_f32), acc_ld, pixels, c, _ptr(gamma), _ptr(beta),
+                                             _ptr(mean), _ptr(istd), _ptr(dgamma), _ptr(dbeta), _ptr(scratch),
+                                             _stream(stream)))

@@ -70,6 +70,97 @@ T layer_ptrs(const dnb_block* b, P* base, int l) {
   return r;
 }
 
+
+// ---- bf16 / NHWC, fused schedule.  x0, y, dy, dx0 and the kept b_l are bf16 with channels
+// contiguous; y's pixel stride is C_out, so layer l reads y[..., :C_l] in place and writes its k
+// new channels into y[..., C_l:C_l+k].  The gradient slab G is fp32 (it is accumulated into up to
+// m times); dS2 / dS3 are bf16.  Everything runs on the caller's stream in program order.
+int forward_bf16(dnb_block* b, const void* x0, const float* params, void* yv, char* ws, hipStream_t st) {
+  const dnb_block_desc& d = b->d;
+  const int n = d.n, m = d.layers, k = d.growth, B = d.bottleneck, cout = b->cout;
+  const int64_t P = b->P;
+  unsigned short* y = (unsigned short*)yv;
+  float* mean_y = (float*)(ws + b->off_stat_y);
+  float* istd_y = mean_y + cout;
+  float* part = (float*)(ws + b->off_part);
+  unsigned short* pack = (unsigned short*)(ws + b->off_pack);
+  const size_t B16 = (size_t)((B + 15) & ~15), k16 = (size_t)((k + 15) & ~15), B32 = (size_t)((B + 31) & ~31);
+  DNB_TRY(nhwc::pack_block_weights(params, pack, d.c0, k, B, m, st));
+  DNB_TRY(nhwc::copy_rows(x0, d.c0, y, cout, P, d.c0, st));
+  int freshT = 0;
+  DNB_TRY(nhwc::stats_partial(y, cout, P, d.c0, part, &freshT, st));
+  int fresh_lo = 0, fresh_hi = d.c0;
+  for (int l = 1; l <= m; ++l) {
+    const int c = c_in(d, l);
+    const LayerParams p = layer_ptrs<LayerParams, const float>(b, params, l);
+    unsigned short* bl = (unsigned short*)(ws + b->off_b[l]);
+    float* mean_b = (float*)(ws + b->off_stat_b[l]);
+    float* istd_b = mean_b + B;
+    float2* fold1 = (float2*)(ws + b->off_fold1[l]);
+    float2* fold2 = (float2*)(ws + b->off_fold2[l]);
+    const size_t c16 = (size_t)((c + 15) & ~15), c32 = (size_t)((c + 31) & ~31);
+    const unsigned short* pk1 = pack + b->pk[l];                   // 1x1 forward
+    const unsigned short* pk3 = pk1 + B16 * c32 + c16 * B32;       // 3x3 forward
+    int T1 = 0, T3 = 0;
+    DNB_TRY(launch_bn_fold(p.g1, p.b1, mean_y, istd_y, part, freshT, fresh_lo, fresh_hi, d.eps, c, fold1, st));
+    DNB_TRY(nhwc::conv(y, cout, false, pk1, bl, B, n, c, B, d.h, d.w, 1, fold1, part, &T1, st));
+    DNB_TRY(launch_bn_fold(p.g2, p.b2, mean_b, istd_b, part, T1, 0, B, d.eps, B, fold2, st));
+    DNB_TRY(nhwc::conv(bl, B, false, pk3, y + c, cout, n, B, k, d.h, d.w, 9, fold2, part, &T3, st));
+    freshT = T3; fresh_lo = c; fresh_hi = c + k;
+  }
+  (void)k16;
+  return DNB_OK;
+}
+
+int backward_bf16(dnb_block* b, const float* params, const void* yv, const void* dy, void* dx0, float* dparams,
+                  char* ws, hipStream_t st) {
+  const dnb_block_desc& d = b->d;
+  const int n = d.n, m = d.layers, k = d.growth, B = d.bottleneck, cout = b->cout;
+  const int64_t P = b->P;
+  const unsigned short* y = (const unsigned short*)yv;
+  float* mean_y = (float*)(ws + b->off_stat_y);
+  float* istd_y = mean_y + cout;
+  float* part = (float*)(ws + b->off_part);
+  float* partA = (float*)(ws + b->off_partA);
+  float* partB = (float*)(ws + b->off_partB);
+  float* G = (float*)(ws + b->off_G);
+  unsigned short* dS2 = (unsigned short*)(ws + b->off_dS2);
+  unsigned short* dS3 = (unsigned short*)(ws + b->off_dS3);
+  const unsigned short* pack = (const unsigned short*)(ws + b->off_pack);
+  const size_t B16 = (size_t)((B + 15) & ~15), k16 = (size_t)((k + 15) & ~15), B32 = (size_t)((B + 31) & ~31);
+  DNB_TRY(nhwc::bf16_to_f32(dy, G, P * cout, st));
+  for (int l = m; l >= 1; --l) {
+    const int c = c_in(d, l);
+    const LayerParams p = layer_ptrs<LayerParams, const float>(b, params, l);
+    const LayerGrads gp = layer_ptrs<LayerGrads, float>(b, dparams, l);
+    const unsigned short* bl = (const unsigned short*)(ws + b->off_b[l]);
+    float* mean_b = (float*)(ws + b->off_stat_b[l]);
+    float* istd_b = mean_b + B;
+    const float2* fold1 = (const float2*)(ws + b->off_fold1[l]);
+    const float2* fold2 = (const float2*)(ws + b->off_fold2[l]);
+    const size_t c16 = (size_t)((c + 15) & ~15), c32 = (size_t)((c + 31) & ~31);
+    const unsigned short* pk1t = pack + b->pk[l] + B16 * c32;                         // 1x1 data gradient
+    const unsigned short* pk3t = pack + b->pk[l] + B16 * c32 + c16 * B32 + 9 * k16 * B32;  // 3x3 data gradient
+    const float* gl = G + c;  // gradient of x_l (fp32, pixel stride C_out), complete at this point
+    int splits = 0;
+    // 3x3: weight gradient (BN2+ReLU of b_l recomputed in the operand staging), data gradient
+    DNB_TRY(nhwc::wgrad(bl, B, gl, cout, true, partA, n, B, k, d.h, d.w, 9, fold2, &splits, st));
+    DNB_TRY(launch_sum_partials(partA, splits, (int64_t)k * B * 9, gp.W3, st));
+    DNB_TRY(nhwc::conv(gl, cout, true, pk3t, dS3, B, n, k, B, d.h, d.w, 9, nullptr, nullptr, nullptr, st));
+    DNB_TRY(nhwc::bn_relu_bwd(bl, B, dS3, B, dS3, B, nullptr, 0, P, B, p.g2, p.b2, mean_b, istd_b, gp.g2, gp.b2,
+                              part, st));
+    // 1x1: weight gradient (BN1+ReLU of y[..., :C_l] recomputed in the operand staging), data gradient
+    DNB_TRY(nhwc::wgrad(y, cout, dS3, B, false, partB, n, c, B, d.h, d.w, 1, fold1, &splits, st));
+    DNB_TRY(launch_sum_partials(partB, splits, (int64_t)B * c, gp.W1, st));
+    DNB_TRY(nhwc::conv(dS3, B, false, pk1t, dS2, c, n, B, c, d.h, d.w, 1, nullptr, nullptr, nullptr, st));
+    // BN1+ReLU backward and concat backward: accumulate into the slab
+    DNB_TRY(nhwc::bn_relu_bwd(y, cout, dS2, c, nullptr, 0, G, cout, P, c, p.g1, p.b1, mean_y, istd_y, gp.g1,
+                              gp.b1, part, st));
+  }
+  DNB_TRY(nhwc::f32_rows_to_bf16(G, cout, dx0, P, d.c0, st));
+  return DNB_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -98,9 +189,15 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
   if (d.layout != DNB_NCHW && d.layout != DNB_NHWC) return DNB_E_BADDESC;
   if (d.schedule != DNB_SCHED_SHARED && d.schedule != DNB_SCHED_STORE_ALL && d.schedule != DNB_SCHED_FUSED)
     return DNB_E_BADDESC;
-  if (d.dtype != DNB_F32 || d.layout != DNB_NCHW) return DNB_E_UNSUPPORTED;
-  // the fused schedule exists only in the 16-byte-vector kernels (pixel rows a multiple of 4)
-  if (d.schedule == DNB_SCHED_FUSED) {
+  // built combinations: fp32 + NCHW (all schedules), bf16 + NHWC (fused schedule)
+  const bool bf16 = d.dtype == DNB_BF16;
+  if (bf16 ? (d.layout != DNB_NHWC || d.schedule != DNB_SCHED_FUSED) : (d.layout != DNB_NCHW))
+    return DNB_E_UNSUPPORTED;
+  // bf16 kernels move 8 channels (16 bytes) at a time
+  if (bf16 && (d.c0 % 8 || d.growth % 8 || d.bottleneck % 8)) return DNB_E_UNSUPPORTED;
+  if (bf16 && (size_t)(64 + 2 * (d.w + 1)) * 80 > 64 * 1024) return DNB_E_UNSUPPORTED;
+  // the fp32 fused schedule exists only in the 16-byte-vector kernels (pixel rows a multiple of 4)
+  if (!bf16 && d.schedule == DNB_SCHED_FUSED) {
     // ... and its 3x3 stages all B channels of a 64-pixel tile (+ halo) in 64 KB of LDS
     int pitch = (64 + 2 * d.w + 8 + 31) / 32 * 32 + 4;
     if (pitch - 32 >= 64 + 2 * d.w + 8) pitch -= 32;
@@ -119,8 +216,9 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
   const int m = d.layers, k = d.growth, B = d.bottleneck;
   b->cm = c_in(d, m);
   b->cout = (int)cout;
-  b->esz = 4;
+  b->esz = bf16 ? 2 : 4;
   const size_t Ps = (size_t)P * b->esz;
+  const size_t Pg = (size_t)P * 4;  // the gradient slab G is fp32 for both storage types
 
   b->poff.assign(m + 2, 0);
   size_t po = 0;
@@ -164,10 +262,10 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
     mem.stored_fwd_bytes = (uint64_t)(2 * sigma_c + (size_t)m * (2 * B + k)) * Ps;
     mem.shared_fwd_bytes = 0;
   }
-  b->off_G = carve((size_t)cout * Ps, true);
+  b->off_G = carve((size_t)cout * Pg, true);
   b->off_dS2 = carve((size_t)b->cm * Ps, true);
   b->off_dS3 = carve((size_t)B * Ps, true);
-  mem.grad_bytes = (uint64_t)((size_t)cout + b->cm + B) * Ps;
+  mem.grad_bytes = (uint64_t)((size_t)cout * Pg + ((size_t)b->cm + B) * Ps);
   mem.peak_bytes = mem.stored_fwd_bytes + mem.shared_fwd_bytes + mem.grad_bytes;
   // the x_l part of `stored` lives in the caller's y, everything else was carved above
   if (fm_exact + (size_t)m * k * Ps != mem.peak_bytes) { delete b; return DNB_E_BADDESC; }
@@ -187,21 +285,38 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
 
   size_t part = 0, partA = 0, partB = 0;
   auto need = [&](size_t floats) { if (floats > part) part = floats; };
-  need(bn_stats_partial_floats(d.n, d.c0, (int)hw));
-  need(bn_stats_partial_floats(d.n, k, (int)hw));
-  need(bn_stats_partial_floats(d.n, B, (int)hw));
-  need(bn_bwd_partial_floats(d.n, B, (int)hw));
-  need(conv_stats_partial_floats(d.n, B, d.h, d.w));  // epilogue statistics of the two convs
-  need(conv_stats_partial_floats(d.n, k, d.h, d.w));
-  for (int l = 1; l <= m; ++l) {
-    need(bn_bwd_partial_floats(d.n, c_in(d, l), (int)hw));
-    const size_t f = conv_wgrad_partial_floats(d.n, c_in(d, l), B, d.h, d.w, 1);
-    if (f > partB) partB = f;
-  }
-  partA = conv_wgrad_partial_floats(d.n, B, k, d.h, d.w, 9);
   b->pk.assign(m + 2, 0);
-  size_t pack = 0;
-  for (int l = 1; l <= m; ++l) { b->pk[l] = pack; pack += packed_layer_floats(c_in(d, l), k, B); }
+  size_t pack = 0;  // in floats
+  if (bf16) {
+    need(nhwc::stats_partial_floats(P, d.c0));
+    need(nhwc::conv_stats_partial_floats(d.n, B, d.h, d.w));
+    need(nhwc::conv_stats_partial_floats(d.n, k, d.h, d.w));
+    need(nhwc::bn_bwd_partial_floats(P, B));
+    size_t pe = 0;  // bf16 elements
+    for (int l = 1; l <= m; ++l) {
+      need(nhwc::bn_bwd_partial_floats(P, c_in(d, l)));
+      const size_t f = nhwc::wgrad_partial_floats(d.n, c_in(d, l), B, d.h, d.w, 1);
+      if (f > partB) partB = f;
+      b->pk[l] = pe;
+      pe += nhwc::packed_layer_elems(c_in(d, l), k, B);
+    }
+    partA = nhwc::wgrad_partial_floats(d.n, B, k, d.h, d.w, 9);
+    pack = (pe + 1) / 2;
+  } else {
+    need(bn_stats_partial_floats(d.n, d.c0, (int)hw));
+    need(bn_stats_partial_floats(d.n, k, (int)hw));
+    need(bn_stats_partial_floats(d.n, B, (int)hw));
+    need(bn_bwd_partial_floats(d.n, B, (int)hw));
+    need(conv_stats_partial_floats(d.n, B, d.h, d.w));  // epilogue statistics of the two convs
+    need(conv_stats_partial_floats(d.n, k, d.h, d.w));
+    for (int l = 1; l <= m; ++l) {
+      need(bn_bwd_partial_floats(d.n, c_in(d, l), (int)hw));
+      const size_t f = conv_wgrad_partial_floats(d.n, c_in(d, l), B, d.h, d.w, 1);
+      if (f > partB) partB = f;
+    }
+    partA = conv_wgrad_partial_floats(d.n, B, k, d.h, d.w, 9);
+    for (int l = 1; l <= m; ++l) { b->pk[l] = pack; pack += packed_layer_floats(c_in(d, l), k, B); }
+  }
   mem.scratch_bytes = (uint64_t)(part + partA + partB + pack) * sizeof(float);
   b->off_part = carve(part * sizeof(float), false);
   b->off_partA = carve(partA * sizeof(float), false);
@@ -268,6 +383,7 @@ int dnb_block_forward(dnb_block* b, const void* x0v, const void* paramsv, void* 
   if (misaligned(x0v) || misaligned(paramsv) || misaligned(yv) || misaligned(wsv)) return DNB_E_ALIGN;
   hipStream_t st = (hipStream_t)stream;
   const dnb_block_desc& d = b->d;
+  if (d.dtype == DNB_BF16) return forward_bf16(b, x0v, (const float*)paramsv, yv, (char*)wsv, st);
   const int n = d.n, m = d.layers, k = d.growth, B = d.bottleneck, hw = (int)b->hw;
   const float* x0 = (const float*)x0v;
   const float* params = (const float*)paramsv;
@@ -348,6 +464,8 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
     return DNB_E_ALIGN;
   hipStream_t st = (hipStream_t)stream;
   const dnb_block_desc& d = b->d;
+  if (d.dtype == DNB_BF16)
+    return backward_bf16(b, (const float*)paramsv, yv, dyv, dx0v, (float*)dparamsv, (char*)wsv, st);
   const int n = d.n, m = d.layers, k = d.growth, B = d.bottleneck, hw = (int)b->hw;
   const bool recompute = d.schedule == DNB_SCHED_SHARED;
   const bool fused = d.schedule == DNB_SCHED_FUSED;
@@ -593,6 +711,81 @@ int dnb_op_conv_wgrad(const void* x, int64_t x_stride, const void* dout, int64_t
   DNB_TRY(launch_conv_wgrad((const float*)x, x_stride, (const float*)dout, dout_stride, (float*)dwgt,
                             (int)n, (int)cin, (int)cout, (int)h, (int)w, ks * ks, (float*)scratch, nullptr,
                             (hipStream_t)stream));
+  return DNB_OK;
+}
+
+// ---- single operations of the bf16 / NHWC path
+
+size_t dnb_op_nhwc_scratch_bytes(int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w, int ks) {
+  if ((ks != 1 && ks != 3) || n < 1 || cin < 1 || cout < 1 || h < 1 || w < 1) return 0;
+  const size_t a = nhwc::packed_weight_elems((int)cout, (int)cin, ks * ks) * 2;
+  const size_t b = nhwc::packed_weight_elems((int)cin, (int)cout, ks * ks) * 2;
+  const size_t c = nhwc::wgrad_partial_floats((int)n, (int)cin, (int)cout, (int)h, (int)w, ks * ks) * 4;
+  const size_t d = nhwc::bn_bwd_partial_floats(n * h * w, (int)(cin > cout ? cin : cout)) * 4;
+  size_t m = a > b ? a : b;
+  if (c > m) m = c;
+  if (d > m) m = d;
+  return m + 256;
+}
+
+static int nhwc_args_ok(int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w, int ks) {
+  if (ks != 1 && ks != 3) return DNB_E_UNSUPPORTED;
+  if (n < 1 || cin < 1 || cout < 1 || h < 1 || w < 1 || n > 65535) return DNB_E_RANGE;
+  if (cin % 8 || cout % 8) return DNB_E_UNSUPPORTED;
+  if ((size_t)(64 + 2 * (w + 1)) * 80 > 64 * 1024) return DNB_E_UNSUPPORTED;
+  return DNB_OK;
+}
+
+int dnb_op_nhwc_conv_forward(const void* x, int64_t x_ld, const void* wgt, void* out, int64_t out_ld, int64_t n,
+                             int64_t cin, int64_t cout, int64_t h, int64_t w, int ks, void* scratch, void* stream) {
+  if (!x || !wgt || !out || !scratch) return DNB_E_NULL;
+  const int rc = nhwc_args_ok(n, cin, cout, h, w, ks);
+  if (rc) return rc;
+  const int taps = ks * ks;
+  DNB_TRY(nhwc::pack_weights(WeightView{(const float*)wgt, cin * taps, taps, 0}, (int)cout, (int)cin, taps, scratch,
+                             (hipStream_t)stream));
+  DNB_TRY(nhwc::conv(x, x_ld, false, scratch, out, out_ld, (int)n, (int)cin, (int)cout, (int)h, (int)w, taps, nullptr,
+                     nullptr, nullptr, (hipStream_t)stream));
+  return DNB_OK;
+}
+
+int dnb_op_nhwc_conv_dgrad(const void* dout, int64_t dout_ld, int dout_is_f32, const void* wgt, void* din,
+                           int64_t din_ld, int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w, int ks,
+                           void* scratch, void* stream) {
+  if (!dout || !wgt || !din || !scratch) return DNB_E_NULL;
+  const int rc = nhwc_args_ok(n, cin, cout, h, w, ks);
+  if (rc) return rc;
+  const int taps = ks * ks;
+  DNB_TRY(nhwc::pack_weights(WeightView{(const float*)wgt, taps, cin * taps, taps == 9 ? 1 : 0}, (int)cin, (int)cout,
+                             taps, scratch, (hipStream_t)stream));
+  DNB_TRY(nhwc::conv(dout, dout_ld, dout_is_f32 != 0, scratch, din, din_ld, (int)n, (int)cout, (int)cin, (int)h, (int)w,
+                     taps, nullptr, nullptr, nullptr, (hipStream_t)stream));
+  return DNB_OK;
+}
+
+int dnb_op_nhwc_conv_wgrad(const void* x, int64_t x_ld, const void* dout, int64_t dout_ld, int dout_is_f32, void* dwgt,
+                           int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w, int ks, void* scratch,
+                           void* stream) {
+  if (!x || !dout || !dwgt || !scratch) return DNB_E_NULL;
+  const int rc = nhwc_args_ok(n, cin, cout, h, w, ks);
+  if (rc) return rc;
+  int splits = 0;
+  DNB_TRY(nhwc::wgrad(x, x_ld, dout, dout_ld, dout_is_f32 != 0, (float*)scratch, (int)n, (int)cin, (int)cout, (int)h,
+                      (int)w, ks * ks, nullptr, &splits, (hipStream_t)stream));
+  DNB_TRY(launch_sum_partials((const float*)scratch, splits, cin * cout * ks * ks, (float*)dwgt, (hipStream_t)stream));
+  return DNB_OK;
+}
+
+int dnb_op_nhwc_bn_relu_backward(const void* x, int64_t x_ld, const void* dact, int64_t dact_ld, void* du_bf16,
+                                 int64_t du_ld, void* du_accum_f32, int64_t acc_ld, int64_t pixels, int64_t c,
+                                 const void* gamma, const void* beta, const void* mean, const void* istd,
+                                 void* dgamma, void* dbeta, void* scratch, void* stream) {
+  if (!x || !dact || (!du_bf16 && !du_accum_f32) || !gamma || !beta || !mean || !istd || !dgamma || !dbeta || !scratch)
+    return DNB_E_NULL;
+  if (pixels < 1 || c < 8 || c % 8) return DNB_E_RANGE;
+  DNB_TRY(nhwc::bn_relu_bwd(x, x_ld, dact, dact_ld, du_bf16, du_ld, (float*)du_accum_f32, acc_ld, pixels, (int)c,
+                            (const float*)gamma, (const float*)beta, (const float*)mean, (const float*)istd,
+                            (float*)dgamma, (float*)dbeta, (float*)scratch, (hipStream_t)stream));
   return DNB_OK;
 }
 

@@ -272,6 +272,8 @@ __global__ __launch_bounds__(256) void k_sum_partials(const float* __restrict__ 
   }
 }
 
+}  // namespace
+
 hipError_t launch_sum_partials(const float* partials, int splits, int64_t count, float* out, hipStream_t st) {
   int G = 1;
   while (G < 16 && splits / G > 16) G <<= 1;  // about 16 splits per thread, at least 16 elements per row
@@ -280,6 +282,8 @@ hipError_t launch_sum_partials(const float* partials, int splits, int64_t count,
                      splits, count, out, G, per);
   return hipGetLastError();
 }
+
+namespace {
 
 struct IgemmPlan {
   int mt, nt, wm;

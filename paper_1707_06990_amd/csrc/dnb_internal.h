@@ -109,4 +109,35 @@ hipError_t launch_conv_wgrad(const float* in, int64_t in_stride, const float* g,
                              float* dw, int n, int cin, int cout, int h, int w, int taps,
                              float* partials, const float2* fold, hipStream_t st);
 
+// out[e] = sum over splits of partials[split][e] (fixed order).
+hipError_t launch_sum_partials(const float* partials, int splits, int64_t count, float* out, hipStream_t st);
+
+// ---- bf16 / NHWC path (dnb_nhwc_bf16.hip): feature maps bf16 with channels contiguous, row
+// strides ("ld") in elements; parameters, statistics, gradient slab and partials fp32.
+namespace nhwc {
+hipError_t copy_rows(const void* src, int64_t sld, void* dst, int64_t dld, int64_t P, int c, hipStream_t st);
+hipError_t bf16_to_f32(const void* src, float* dst, int64_t count, hipStream_t st);
+hipError_t f32_rows_to_bf16(const float* src, int64_t sld, void* dst, int64_t P, int c, hipStream_t st);
+size_t stats_partial_floats(int64_t P, int c);
+hipError_t stats_partial(const void* x, int64_t ld, int64_t P, int c, float* part, int* T, hipStream_t st);
+// per layer, in order: 1x1 forward [B16][c32], 1x1 dgrad [c16][B32], 3x3 forward [9][k16][B32],
+// 3x3 dgrad [9][B16][k32]  (bf16 elements; 16 / 32 = rounded up to that multiple)
+size_t packed_layer_elems(int c, int k, int B);
+hipError_t pack_block_weights(const float* params, void* packed, int c0, int k, int B, int m, hipStream_t st);
+size_t packed_weight_elems(int cout, int cin, int taps);
+hipError_t pack_weights(WeightView wv, int cout, int cin, int taps, void* packed, hipStream_t st);
+size_t conv_stats_partial_floats(int n, int cout, int h, int w);
+hipError_t conv(const void* in, int64_t in_ld, bool in_f32, const void* Wp, void* out, int64_t out_ld, int n,
+                int cin, int cout, int h, int w, int taps, const float2* fold, float* spart, int* sT,
+                hipStream_t st);
+size_t wgrad_partial_floats(int n, int cin, int cout, int h, int w, int taps);
+hipError_t wgrad(const void* a, int64_t a_ld, const void* g, int64_t g_ld, bool g_f32, float* part, int n, int cin,
+                 int cout, int h, int w, int taps, const float2* fold, int* splits, hipStream_t st);
+size_t bn_bwd_partial_floats(int64_t P, int c);
+hipError_t bn_relu_bwd(const void* x, int64_t x_ld, const void* dact, int64_t d_ld, void* du_bf, int64_t du_ld,
+                       float* G, int64_t g_ld, int64_t P, int c, const float* gamma, const float* beta,
+                       const float* mean, const float* istd, float* dgamma, float* dbeta, float* part,
+                       hipStream_t st);
+}  // namespace nhwc
+
 }  // namespace dnb

@@ -1,0 +1,708 @@
+// bf16 / NHWC kernels of the dense block (feature maps stored as bf16, channels contiguous;
+// fp32 accumulation, fp32 BN statistics, fp32 parameters and parameter gradients, fp32 gradient
+// slab).  First correct version: every step of the fused schedule, built around
+// v_mfma_f32_16x16x32_bf16 with output channels on M and pixels on N, so a lane's operand is
+// 8 consecutive channels of one pixel (16 bytes of NHWC) and an accumulator holds 4 consecutive
+// channels of one pixel (one 8-byte NHWC store).
+//
+// Convolutions (forward / data gradient): the workgroup stages a 64-pixel tile (+ one image row
+// of halo for 3x3) of a 32-channel chunk in LDS, applying the BN+ReLU prologue once per element;
+// its four waves split the output-channel tiles and read packed bf16 weights straight from L2.
+// Weight gradients contract over pixels, which NHWC keeps on the slow axis, so both operands are
+// transposed on their way into LDS ([channel][pixel]); the 3x3 stages one shifted copy per tap.
+#include "dnb_internal.h"
+#include "dnb_stats.cuh"
+
+namespace dnb {
+namespace nhwc {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned short u16;
+
+__device__ __forceinline__ float bf2f(u16 v) { return __uint_as_float((unsigned)v << 16); }
+// round to nearest even; inputs are finite
+__device__ __forceinline__ u16 f2bf(float f) {
+  unsigned u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (u16)(u >> 16);
+}
+
+union V8 {          // 8 bf16 = 16 bytes
+  uint4 q;
+  u16 h[8];
+  bf16x8 v;
+};
+
+__device__ __forceinline__ f32x4 mfma_bf16(const V8& a, const V8& b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// ----------------------------------------------------------------------------- small kernels
+
+// dst[p][0:c] = src[p][0:c] (bf16, c % 8 == 0), pixel strides in elements
+__global__ __launch_bounds__(256) void k_copy_rows(const u16* __restrict__ src, int64_t sld,
+                                                   u16* __restrict__ dst, int64_t dld, int64_t P, int cv) {
+  const int64_t total = P * cv;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t p = i / cv;
+    const int v = (int)(i - p * cv);
+    *reinterpret_cast<uint4*>(dst + p * dld + 8 * v) = *reinterpret_cast<const uint4*>(src + p * sld + 8 * v);
+  }
+}
+
+// G (fp32, [P][c]) = dy (bf16, [P][c])
+__global__ __launch_bounds__(256) void k_bf16_to_f32(const u16* __restrict__ src, float* __restrict__ dst,
+                                                     int64_t total8) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total8; i += (int64_t)gridDim.x * 256) {
+    V8 s;
+    s.q = *reinterpret_cast<const uint4*>(src + 8 * i);
+    float4 a = make_float4(bf2f(s.h[0]), bf2f(s.h[1]), bf2f(s.h[2]), bf2f(s.h[3]));
+    float4 b = make_float4(bf2f(s.h[4]), bf2f(s.h[5]), bf2f(s.h[6]), bf2f(s.h[7]));
+    *reinterpret_cast<float4*>(dst + 8 * i) = a;
+    *reinterpret_cast<float4*>(dst + 8 * i + 4) = b;
+  }
+}
+
+// dst (bf16, [P][c]) = src (fp32, [P][ld]) first c channels
+__global__ __launch_bounds__(256) void k_f32_rows_to_bf16(const float* __restrict__ src, int64_t sld,
+                                                          u16* __restrict__ dst, int64_t P, int cv) {
+  const int64_t total = P * cv;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t p = i / cv;
+    const int v = (int)(i - p * cv);
+    const float4 a = *reinterpret_cast<const float4*>(src + p * sld + 8 * v);
+    const float4 b = *reinterpret_cast<const float4*>(src + p * sld + 8 * v + 4);
+    V8 o;
+    o.h[0] = f2bf(a.x); o.h[1] = f2bf(a.y); o.h[2] = f2bf(a.z); o.h[3] = f2bf(a.w);
+    o.h[4] = f2bf(b.x); o.h[5] = f2bf(b.y); o.h[6] = f2bf(b.z); o.h[7] = f2bf(b.w);
+    *reinterpret_cast<uint4*>(dst + p * (int64_t)(8 * cv) + 8 * v) = o.q;
+  }
+}
+
+// Statistics partials of c channels over pixel range split s: part[(ch*S + s)*3] = (count, mean, M2).
+// Thread = one channel, consecutive threads = consecutive channels (coalesced rows); two passes.
+__global__ __launch_bounds__(64) void k_stats_partial(const u16* __restrict__ x, int64_t ld, int64_t P,
+                                                      int c, int ppb, float* __restrict__ part) {
+  const int ch = blockIdx.x * 64 + threadIdx.x, s = blockIdx.y, S = gridDim.y;
+  if (ch >= c) return;
+  const int64_t p0 = (int64_t)s * ppb, p1 = min(P, p0 + ppb);
+  float sum = 0.f;
+  for (int64_t p = p0; p < p1; ++p) sum += bf2f(x[p * ld + ch]);
+  const float cnt = (float)(p1 - p0), mu = sum / cnt;
+  float m2 = 0.f;
+  for (int64_t p = p0; p < p1; ++p) {
+    const float d = bf2f(x[p * ld + ch]) - mu;
+    m2 = __fmaf_rn(d, d, m2);
+  }
+  float* o = part + ((int64_t)ch * S + s) * 3;
+  o[0] = cnt; o[1] = mu; o[2] = m2;
+}
+
+// Packed bf16 weights: [taps][M16][K32] (K padded to a multiple of 32, zero filled), K natural order.
+__global__ __launch_bounds__(256) void k_pack_block_weights(const float* __restrict__ params,
+                                                            u16* __restrict__ packed, int c0, int k, int B) {
+  const int l = blockIdx.y + 1;
+  const int B16 = (B + 15) & ~15, k16 = (k + 15) & ~15, B32 = (B + 31) & ~31, k32 = (k + 31) & ~31;
+  int64_t poff = 0, koff = 0;
+  for (int i = 1; i < l; ++i) {
+    const int c = c0 + (i - 1) * k, c16 = (c + 15) & ~15, c32 = (c + 31) & ~31;
+    poff += 2 * (int64_t)c + (int64_t)B * c + 2 * B + 9 * (int64_t)k * B;
+    koff += (int64_t)B16 * c32 + (int64_t)c16 * B32 + 9 * (int64_t)k16 * B32 + 9 * (int64_t)B16 * k32;
+  }
+  const int C = c0 + (l - 1) * k, C16 = (C + 15) & ~15, C32 = (C + 31) & ~31;
+  const float* W1 = params + poff + 2 * C;
+  const float* W3 = W1 + (int64_t)B * C + 2 * B;
+  u16* A = packed + koff;
+  const int64_t n1 = (int64_t)B16 * C32, n2 = (int64_t)C16 * B32, n3 = 9 * (int64_t)k16 * B32,
+                n4 = 9 * (int64_t)B16 * k32, total = n1 + n2 + n3 + n4;
+  for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+    float v = 0.f;
+    if (idx < n1) {                       // 1x1 forward  [B16][C32]
+      const int m = (int)(idx / C32), c = (int)(idx % C32);
+      if (m < B && c < C) v = W1[(int64_t)m * C + c];
+    } else if (idx < n1 + n2) {           // 1x1 dgrad    [C16][B32]
+      const int64_t e = idx - n1;
+      const int cc = (int)(e / B32), o = (int)(e % B32);
+      if (cc < C && o < B) v = W1[(int64_t)o * C + cc];
+    } else if (idx < n1 + n2 + n3) {      // 3x3 forward  [9][k16][B32]
+      const int64_t e = idx - n1 - n2;
+      const int t = (int)(e / (k16 * B32)), rem = (int)(e % (k16 * B32));
+      const int mm = rem / B32, c = rem % B32;
+      if (mm < k && c < B) v = W3[((int64_t)mm * B + c) * 9 + t];
+    } else {                              // 3x3 dgrad    [9][B16][k32], transposed and flipped
+      const int64_t e = idx - n1 - n2 - n3;
+      const int t = (int)(e / (B16 * k32)), rem = (int)(e % (B16 * k32));
+      const int cc = rem / k32, o = rem % k32;
+      if (cc < B && o < k) v = W3[((int64_t)o * B + cc) * 9 + (8 - t)];
+    }
+    A[idx] = f2bf(v);
+  }
+}
+
+// One convolution's weights: [taps][M16][K32] from element (m, c, t) at w[m*sm + c*sc + (flip ? taps-1-t : t)].
+__global__ __launch_bounds__(256) void k_pack_weights(const float* __restrict__ w, int64_t sm, int64_t sc, int flip,
+                                                      int cout, int cin, int taps, u16* __restrict__ outp) {
+  const int M16 = (cout + 15) & ~15, K32 = (cin + 31) & ~31;
+  const int64_t total = (int64_t)taps * M16 * K32;
+  for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
+    const int c = (int)(idx % K32);
+    const int64_t rem = idx / K32;
+    const int m = (int)(rem % M16), t = (int)(rem / M16);
+    const float v = (m < cout && c < cin) ? w[(int64_t)m * sm + (int64_t)c * sc + (flip ? taps - 1 - t : t)] : 0.f;
+    outp[idx] = f2bf(v);
+  }
+}
+
+// ----------------------------------------------------------------------------- conv fwd / dgrad
+
+// out[q][m] = sum_{t,c} W(t,m,c) * act(in[q+shift(t)][c]),  act = BN+ReLU prologue or identity.
+// grid (pixel tiles of 64 per image, M groups, images); 256 threads.  TIN = u16 (bf16) or float
+// (the gradient slab).  STATS: per-tile (count, mean, M2) of the rounded outputs, as in the fp32
+// kernels: spart[(m*T + tile)*3].
+template <int TAPS, int MT, typename TIN, bool PRO, bool STATS>
+__global__ __launch_bounds__(256) void k_conv(
+    const TIN* __restrict__ in, int64_t in_ld, const u16* __restrict__ Wp, int M16, int K32,
+    u16* __restrict__ out, int64_t out_ld, int cin, int cout, int H, int W,
+    const float2* __restrict__ fold, float* __restrict__ spart, int sT) {
+  extern __shared__ u16 lds[];
+  constexpr int KC = 32, PITCH = KC + 8;  // elements per staged pixel (80 bytes: spreads banks)
+  const int HW = H * W;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = lane & 15, g = lane >> 4;
+  const int q0 = blockIdx.x * 64, img = blockIdx.z;
+  const int halo = (TAPS == 9) ? W + 1 : 0;
+  const int seg = 64 + 2 * halo;
+  const TIN* inb = in + (int64_t)img * HW * in_ld;
+  const int mbase = (blockIdx.y * 4 + wave) * (MT * 16);
+  const bool m_ok = mbase < M16;
+
+  f32x4 acc[MT][4];
+#pragma unroll
+  for (int a = 0; a < MT; ++a)
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[a][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  bool lok[4], rok[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const int wc = (q0 + t * 16 + j) % W;
+    lok[t] = wc != 0;
+    rok[t] = wc != W - 1;
+  }
+
+  for (int c0 = 0; c0 < cin; c0 += KC) {
+    __syncthreads();
+    // stage seg pixels x 32 channels; thread = (pixel, 8-channel vector)
+    for (int idx = tid; idx < seg * 4; idx += 256) {
+      const int s = idx >> 2, v = idx & 3;
+      const int q = q0 - halo + s, ch = c0 + 8 * v;
+      V8 o;
+      o.q = make_uint4(0u, 0u, 0u, 0u);
+      if (q >= 0 && q < HW && ch < cin) {  // cin % 8 == 0: a vector is entirely in or out
+        float f[8];
+        if (sizeof(TIN) == 2) {
+          V8 r;
+          r.q = *reinterpret_cast<const uint4*>(reinterpret_cast<const u16*>(inb) + (int64_t)q * in_ld + ch);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) f[e] = bf2f(r.h[e]);
+        } else {
+          const float* pf = reinterpret_cast<const float*>(inb) + (int64_t)q * in_ld + ch;
+          const float4 a = *reinterpret_cast<const float4*>(pf), b = *reinterpret_cast<const float4*>(pf + 4);
+          f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+        }
+        if (PRO) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float2 fl = fold[ch + e];
+            f[e] = fmaxf(__fmaf_rn(f[e], fl.x, fl.y), 0.f);
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o.h[e] = f2bf(f[e]);
+      }
+      *reinterpret_cast<uint4*>(&lds[s * PITCH + 8 * v]) = o.q;
+    }
+    __syncthreads();
+    if (m_ok) {
+#pragma unroll
+      for (int t9 = 0; t9 < TAPS; ++t9) {
+        const int di = (TAPS == 9) ? t9 / 3 - 1 : 0, dj = (TAPS == 9) ? t9 % 3 - 1 : 0;
+        V8 bfrag[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          bfrag[t].q = *reinterpret_cast<const uint4*>(&lds[(t * 16 + j + halo + di * W + dj) * PITCH + 8 * g]);
+          if ((dj < 0 && !lok[t]) || (dj > 0 && !rok[t])) bfrag[t].q = make_uint4(0u, 0u, 0u, 0u);
+        }
+#pragma unroll
+        for (int a = 0; a < MT; ++a) {
+          if (mbase + a * 16 < M16) {
+            V8 w;
+            w.q = *reinterpret_cast<const uint4*>(Wp + ((int64_t)t9 * M16 + mbase + a * 16 + j) * K32 + c0 + 8 * g);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[a][t] = mfma_bf16(w, bfrag[t], acc[a][t]);
+          }
+        }
+      }
+    }
+  }
+
+  if (!m_ok) return;
+  const int tile_px = min(64, HW - q0);
+#pragma unroll
+  for (int a = 0; a < MT; ++a) {
+    if (mbase + a * 16 >= M16) continue;
+    // round to bf16 first: statistics describe exactly what is stored
+    float rv[4][4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) rv[t][r] = bf2f(f2bf(acc[a][t][r]));
+    if (STATS) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float s = 0.f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) s += (q0 + t * 16 + j < HW) ? rv[t][r] : 0.f;
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) s += __shfl_xor(s, off, 64);
+        const float mu = s / (float)tile_px;
+        float m2 = 0.f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const float d = rv[t][r] - mu;
+          m2 += (q0 + t * 16 + j < HW) ? d * d : 0.f;
+        }
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) m2 += __shfl_xor(m2, off, 64);
+        const int m = mbase + a * 16 + 4 * g + r;
+        if (j == 0 && m < cout) {
+          float* p = spart + ((int64_t)m * sT + (int64_t)img * gridDim.x + blockIdx.x) * 3;
+          p[0] = (float)tile_px; p[1] = mu; p[2] = m2;
+        }
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int q = q0 + t * 16 + j, m = mbase + a * 16 + 4 * g;
+      if (q < HW && m < cout) {  // cout % 4 == 0 on this path
+        u16* o = out + ((int64_t)img * HW + q) * out_ld + m;
+        uint2 pk;
+        pk.x = (unsigned)f2bf(acc[a][t][0]) | ((unsigned)f2bf(acc[a][t][1]) << 16);
+        pk.y = (unsigned)f2bf(acc[a][t][2]) | ((unsigned)f2bf(acc[a][t][3]) << 16);
+        *reinterpret_cast<uint2*>(o) = pk;
+      }
+    }
+  }
+}
+
+// ----------------------------------------------------------------------------- weight gradient
+
+// dW[m][c][t] = sum_{img,q} g[q][m] * act(a[q+shift(t)][c]).  grid (pixel splits, c groups of 64,
+// m groups of 64).  Per 64-pixel tile and tap the workgroup stages gT[m][pixel] and aT[c][pixel]
+// (transposed, prologue and edge masks applied) in LDS; wave w owns m-tile w of the group and
+// all four c-tiles.  part[split][m][c][t] fp32.
+template <int TAPS, typename TG, bool PRO>
+__global__ __launch_bounds__(256) void k_wgrad(
+    const u16* __restrict__ a, int64_t a_ld, const TG* __restrict__ gout, int64_t g_ld,
+    float* __restrict__ part, int cin, int cout, int n, int H, int W, int tiles_per_img,
+    int tiles_per_split, const float2* __restrict__ fold) {
+  __shared__ u16 gT[64 * 72];  // [m][pixel], pitch 72 elements (144 bytes)
+  __shared__ u16 aT[64 * 72];  // [c][pixel]
+  constexpr int PT = 72;
+  const int HW = H * W;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = lane & 15, g = lane >> 4;
+  const int c0 = blockIdx.y * 64, m0 = blockIdx.z * 64;
+  const int total_tiles = n * tiles_per_img;
+  const int t_begin = blockIdx.x * tiles_per_split, t_end = min(total_tiles, t_begin + tiles_per_split);
+
+  f32x4 acc[TAPS][4];
+#pragma unroll
+  for (int t = 0; t < TAPS; ++t)
+#pragma unroll
+    for (int y = 0; y < 4; ++y) acc[t][y] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  for (int tile = t_begin; tile < t_end; ++tile) {
+    const int img = tile / tiles_per_img, q0 = (tile - img * tiles_per_img) * 64;
+    const u16* ab = a + (int64_t)img * HW * a_ld;
+    const TG* gb = gout + (int64_t)img * HW * g_ld;
+    __syncthreads();
+    // gT: thread = (pixel s, 8-channel vector v of the 64 m's)
+    for (int idx = tid; idx < 64 * 8; idx += 256) {
+      const int s = idx >> 3, v = idx & 7;
+      const int q = q0 + s, m = m0 + 8 * v;
+      u16 h[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) h[e] = 0;
+      if (q < HW && m < cout) {  // cout % 8 == 0
+        if (sizeof(TG) == 2) {
+          V8 r;
+          r.q = *reinterpret_cast<const uint4*>(reinterpret_cast<const u16*>(gb) + (int64_t)q * g_ld + m);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) h[e] = r.h[e];
+        } else {
+          const float* pf = reinterpret_cast<const float*>(gb) + (int64_t)q * g_ld + m;
+          const float4 x = *reinterpret_cast<const float4*>(pf), y = *reinterpret_cast<const float4*>(pf + 4);
+          h[0] = f2bf(x.x); h[1] = f2bf(x.y); h[2] = f2bf(x.z); h[3] = f2bf(x.w);
+          h[4] = f2bf(y.x); h[5] = f2bf(y.y); h[6] = f2bf(y.z); h[7] = f2bf(y.w);
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) gT[(8 * v + e) * PT + s] = h[e];
+    }
+#pragma unroll
+    for (int t9 = 0; t9 < TAPS; ++t9) {  // unrolled: acc[t9] must stay in registers
+      const int di = (TAPS == 9) ? t9 / 3 - 1 : 0, dj = (TAPS == 9) ? t9 % 3 - 1 : 0;
+      if (t9 > 0) __syncthreads();
+      for (int idx = tid; idx < 64 * 8; idx += 256) {
+        const int s = idx >> 3, v = idx & 7;
+        const int q = q0 + s, ch = c0 + 8 * v;
+        const int wc = q % W, qq = q + di * W + dj;
+        u16 h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = 0;
+        const bool ok = q < HW && ch < cin && qq >= 0 && qq < HW && !(dj < 0 && wc == 0) && !(dj > 0 && wc == W - 1);
+        if (ok) {
+          V8 r;
+          r.q = *reinterpret_cast<const uint4*>(ab + (int64_t)qq * a_ld + ch);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            if (PRO) {
+              const float2 fl = fold[ch + e];
+              h[e] = f2bf(fmaxf(__fmaf_rn(bf2f(r.h[e]), fl.x, fl.y), 0.f));
+            } else {
+              h[e] = r.h[e];
+            }
+          }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) aT[(8 * v + e) * PT + s] = h[e];
+      }
+      __syncthreads();
+      // 64 pixels = 2 K-steps of 32
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks) {
+        V8 af;
+        af.q = *reinterpret_cast<const uint4*>(&gT[(wave * 16 + j) * PT + ks * 32 + 8 * g]);
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+          V8 bf;
+          bf.q = *reinterpret_cast<const uint4*>(&aT[(y * 16 + j) * PT + ks * 32 + 8 * g]);
+          acc[t9][y] = mfma_bf16(af, bf, acc[t9][y]);
+        }
+      }
+    }
+  }
+
+  float* pb = part + (int64_t)blockIdx.x * cout * cin * TAPS;
+#pragma unroll
+  for (int t9 = 0; t9 < TAPS; ++t9)
+#pragma unroll
+    for (int y = 0; y < 4; ++y) {
+      const int c = c0 + y * 16 + j;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int m = m0 + wave * 16 + 4 * g + r;
+        if (m < cout && c < cin) pb[((int64_t)m * cin + c) * TAPS + t9] = acc[t9][y][r];
+      }
+    }
+}
+
+// ----------------------------------------------------------------------------- BN + ReLU backward
+
+// Thread = (pixel row pr, 8-channel vector cv); workgroup = 256 threads covering `rows` pixels per
+// step x CV vectors (CV*rows = 256).  grid (channel-vector groups, pixel splits).
+// part[(ch*S + s)*2] = (sum dz, sum dz*xhat) over the split's pixels.
+__global__ __launch_bounds__(256) void k_bn_bwd_partial(
+    const u16* __restrict__ x, int64_t x_ld, const u16* __restrict__ dact, int64_t d_ld, int64_t P,
+    int c, int ppb, const float* __restrict__ gamma, const float* __restrict__ beta,
+    const float* __restrict__ mean, const float* __restrict__ istd, float* __restrict__ part) {
+  __shared__ float red[2][8][256];
+  const int cvl = threadIdx.x & 31, pr = threadIdx.x >> 5;  // 32 vectors x 8 pixel rows
+  const int ch0 = (blockIdx.x * 32 + cvl) * 8, s = blockIdx.y, S = gridDim.y;
+  const int64_t p0 = (int64_t)s * ppb, p1 = min(P, p0 + ppb);
+  float sb[8], sg[8], sc[8], sf[8], mu[8], is[8];
+  const bool ok = ch0 < c;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    sb[e] = sg[e] = 0.f;
+    if (ok) {
+      mu[e] = mean[ch0 + e]; is[e] = istd[ch0 + e];
+      bn_fold(gamma[ch0 + e], beta[ch0 + e], mu[e], is[e], sc[e], sf[e]);
+    }
+  }
+  if (ok) {
+    for (int64_t p = p0 + pr; p < p1; p += 8) {
+      V8 xv, dv;
+      xv.q = *reinterpret_cast<const uint4*>(x + p * x_ld + ch0);
+      dv.q = *reinterpret_cast<const uint4*>(dact + p * d_ld + ch0);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float xf = bf2f(xv.h[e]);
+        const float dz = __fmaf_rn(xf, sc[e], sf[e]) > 0.f ? bf2f(dv.h[e]) : 0.f;
+        sb[e] += dz;
+        sg[e] = __fmaf_rn(dz, (xf - mu[e]) * is[e], sg[e]);
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { red[0][e][threadIdx.x] = sb[e]; red[1][e][threadIdx.x] = sg[e]; }
+  __syncthreads();
+  if (pr == 0 && ok) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float b = 0.f, gg = 0.f;
+      for (int r = 0; r < 8; ++r) { b += red[0][e][r * 32 + cvl]; gg += red[1][e][r * 32 + cvl]; }
+      float* o = part + ((int64_t)(ch0 + e) * S + s) * 2;
+      o[0] = b; o[1] = gg;
+    }
+  }
+}
+
+// dgamma/dbeta = sum of the S partials (fixed order); one thread per channel.
+__global__ __launch_bounds__(64) void k_bn_bwd_finalize(const float* __restrict__ part, int c, int S,
+                                                        float* __restrict__ dgamma, float* __restrict__ dbeta) {
+  const int ch = blockIdx.x * 64 + threadIdx.x;
+  if (ch >= c) return;
+  float b = 0.f, g = 0.f;
+  for (int s = 0; s < S; ++s) { b += part[((int64_t)ch * S + s) * 2]; g += part[((int64_t)ch * S + s) * 2 + 1]; }
+  dbeta[ch] = b; dgamma[ch] = g;
+}
+
+// du = scale*(dz - dbeta/P - xhat*dgamma/P).  ACC: added into the fp32 slab G (BN1, concat
+// backward); else written as bf16 over dact (BN2: gradient of b_l).
+template <bool ACC>
+__global__ __launch_bounds__(256) void k_bn_bwd_apply(
+    const u16* __restrict__ x, int64_t x_ld, const u16* dact, int64_t d_ld, u16* du_bf, int64_t du_ld,
+    float* __restrict__ G, int64_t g_ld, int64_t P, int cv, float inv_p,
+    const float* __restrict__ gamma, const float* __restrict__ beta, const float* __restrict__ mean,
+    const float* __restrict__ istd, const float* __restrict__ dgamma, const float* __restrict__ dbeta) {
+  const int64_t total = P * cv;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t p = i / cv;
+    const int ch0 = (int)(i - p * cv) * 8;
+    V8 xv, dv, ov;
+    xv.q = *reinterpret_cast<const uint4*>(x + p * x_ld + ch0);
+    dv.q = *reinterpret_cast<const uint4*>(dact + p * d_ld + ch0);
+    float r[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float mu = mean[ch0 + e], is = istd[ch0 + e];
+      float sc, sf;
+      bn_fold(gamma[ch0 + e], beta[ch0 + e], mu, is, sc, sf);
+      const float xf = bf2f(xv.h[e]);
+      const float dz = __fmaf_rn(xf, sc, sf) > 0.f ? bf2f(dv.h[e]) : 0.f;
+      r[e] = sc * (dz - dbeta[ch0 + e] * inv_p - (xf - mu) * is * (dgamma[ch0 + e] * inv_p));
+    }
+    if (ACC) {
+      float* gp = G + p * g_ld + ch0;
+      float4 a = *reinterpret_cast<float4*>(gp), b = *reinterpret_cast<float4*>(gp + 4);
+      a.x += r[0]; a.y += r[1]; a.z += r[2]; a.w += r[3]; b.x += r[4]; b.y += r[5]; b.z += r[6]; b.w += r[7];
+      *reinterpret_cast<float4*>(gp) = a;
+      *reinterpret_cast<float4*>(gp + 4) = b;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ov.h[e] = f2bf(r[e]);
+      *reinterpret_cast<uint4*>(du_bf + p * du_ld + ch0) = ov.q;
+    }
+  }
+}
+
+inline unsigned grid1d(int64_t items, int per, unsigned cap) {
+  int64_t g = (items + per - 1) / per;
+  if (g < 1) g = 1;
+  if (g > (int64_t)cap) g = cap;
+  return (unsigned)g;
+}
+
+}  // namespace
+
+// ============================================================================ launchers
+
+hipError_t copy_rows(const void* src, int64_t sld, void* dst, int64_t dld, int64_t P, int c, hipStream_t st) {
+  hipLaunchKernelGGL(k_copy_rows, dim3(grid1d(P * (c / 8), 512, 16384)), dim3(256), 0, st, (const u16*)src, sld,
+                     (u16*)dst, dld, P, c / 8);
+  return hipGetLastError();
+}
+
+hipError_t bf16_to_f32(const void* src, float* dst, int64_t count, hipStream_t st) {
+  hipLaunchKernelGGL(k_bf16_to_f32, dim3(grid1d(count / 8, 512, 16384)), dim3(256), 0, st, (const u16*)src, dst,
+                     count / 8);
+  return hipGetLastError();
+}
+
+hipError_t f32_rows_to_bf16(const float* src, int64_t sld, void* dst, int64_t P, int c, hipStream_t st) {
+  hipLaunchKernelGGL(k_f32_rows_to_bf16, dim3(grid1d(P * (c / 8), 512, 16384)), dim3(256), 0, st, src, sld,
+                     (u16*)dst, P, c / 8);
+  return hipGetLastError();
+}
+
+int stats_splits(int64_t P, int c) {
+  int s = (2048 + c - 1) / c;
+  if (s > 256) s = 256;
+  const int64_t cap = (P + 63) / 64;
+  if (s > cap) s = (int)cap;
+  return s < 1 ? 1 : s;
+}
+size_t stats_partial_floats(int64_t P, int c) { return (size_t)c * stats_splits(P, c) * 3; }
+
+hipError_t stats_partial(const void* x, int64_t ld, int64_t P, int c, float* part, int* T, hipStream_t st) {
+  const int S = stats_splits(P, c);
+  const int ppb = (int)((P + S - 1) / S);
+  const int gs = (int)((P + ppb - 1) / ppb);
+  *T = gs;
+  hipLaunchKernelGGL(k_stats_partial, dim3((unsigned)((c + 63) / 64), (unsigned)gs), dim3(64), 0, st, (const u16*)x, ld,
+                     P, c, ppb, part);
+  return hipGetLastError();
+}
+
+size_t packed_layer_elems(int c, int k, int B) {
+  const size_t B16 = (B + 15) & ~15, k16 = (k + 15) & ~15, B32 = (B + 31) & ~31, k32 = (k + 31) & ~31;
+  const size_t c16 = (c + 15) & ~15, c32 = (c + 31) & ~31;
+  return B16 * c32 + c16 * B32 + 9 * k16 * B32 + 9 * B16 * k32;
+}
+
+hipError_t pack_block_weights(const float* params, void* packed, int c0, int k, int B, int m, hipStream_t st) {
+  const size_t most = packed_layer_elems(c0 + (m - 1) * k, k, B);
+  unsigned gx = (unsigned)((most + 255) / 256);
+  if (gx > 256) gx = 256;
+  hipLaunchKernelGGL(k_pack_block_weights, dim3(gx, (unsigned)m), dim3(256), 0, st, params, (u16*)packed, c0, k, B);
+  return hipGetLastError();
+}
+
+size_t packed_weight_elems(int cout, int cin, int taps) {
+  return (size_t)taps * ((cout + 15) & ~15) * ((cin + 31) & ~31);
+}
+
+hipError_t pack_weights(WeightView wv, int cout, int cin, int taps, void* packed, hipStream_t st) {
+  const size_t total = packed_weight_elems(cout, cin, taps);
+  unsigned grid = (unsigned)((total + 255) / 256);
+  if (grid > 4096) grid = 4096;
+  hipLaunchKernelGGL(k_pack_weights, dim3(grid), dim3(256), 0, st, wv.w, wv.sm, wv.sc, wv.flip, cout, cin, taps,
+                     (u16*)packed);
+  return hipGetLastError();
+}
+
+size_t conv_stats_partial_floats(int n, int cout, int h, int w) {
+  return (size_t)cout * n * ((h * w + 63) / 64) * 3;
+}
+
+// taps 1 or 9; in_f32: input is the fp32 gradient slab.  fold: BN+ReLU prologue (or null).
+// spart: epilogue statistics (or null), *sT = partials per channel.
+hipError_t conv(const void* in, int64_t in_ld, bool in_f32, const void* Wp, void* out, int64_t out_ld, int n,
+                int cin, int cout, int h, int w, int taps, const float2* fold, float* spart, int* sT,
+                hipStream_t st) {
+  const int hw = h * w, M16 = (cout + 15) & ~15, K32 = (cin + 31) & ~31, mtiles = M16 / 16;
+  int mt = (mtiles + 3) / 4;
+  if (mt > 3) mt = 3;
+  const int gy = (mtiles + 4 * mt - 1) / (4 * mt);
+  dim3 grid((unsigned)((hw + 63) / 64), (unsigned)gy, (unsigned)n);
+  const int T = (int)grid.x * n;
+  if (sT) *sT = T;
+  const int halo = taps == 9 ? w + 1 : 0;
+  const size_t lds = (size_t)(64 + 2 * halo) * 40 * sizeof(u16);
+  if (lds > 64 * 1024) return hipErrorInvalidValue;
+  if ((fold != nullptr) != (spart != nullptr) && fold) return hipErrorInvalidValue;
+#define DNB_K(TAPS, MT, TIN, PRO, STATS)                                                                 \
+  hipLaunchKernelGGL((k_conv<TAPS, MT, TIN, PRO, STATS>), grid, dim3(256), lds, st, (const TIN*)in, in_ld, \
+                     (const u16*)Wp, M16, K32, (u16*)out, out_ld, cin, cout, h, w, fold, spart, T)
+#define DNB_K2(TAPS, MT)                                                              \
+  do {                                                                                \
+    if (in_f32) DNB_K(TAPS, MT, float, false, false);                                 \
+    else if (fold) DNB_K(TAPS, MT, u16, true, true);                                  \
+    else if (spart) DNB_K(TAPS, MT, u16, false, true);                                \
+    else DNB_K(TAPS, MT, u16, false, false);                                          \
+  } while (0)
+#define DNB_K3(TAPS)                                                                  \
+  do {                                                                                \
+    if (mt == 3) DNB_K2(TAPS, 3); else if (mt == 2) DNB_K2(TAPS, 2); else DNB_K2(TAPS, 1); \
+  } while (0)
+  if (taps == 9) DNB_K3(9); else DNB_K3(1);
+#undef DNB_K3
+#undef DNB_K2
+#undef DNB_K
+  return hipGetLastError();
+}
+
+int wgrad_splits(int n, int cin, int cout, int h, int w) {
+  const int tiles = n * ((h * w + 63) / 64);
+  const int gy = (cin + 63) / 64, gz = (cout + 63) / 64;
+  int s = 1024 / (gy * gz);
+  if (s < 1) s = 1;
+  if (s > tiles) s = tiles;
+  if (s > 128) s = 128;
+  const int tps = (tiles + s - 1) / s;
+  return (tiles + tps - 1) / tps;
+}
+size_t wgrad_partial_floats(int n, int cin, int cout, int h, int w, int taps) {
+  return (size_t)wgrad_splits(n, cin, cout, h, w) * cin * cout * taps;
+}
+
+// g_f32: the gradient operand is the fp32 slab (3x3), else bf16 (1x1).  The caller adds the
+// partials (launch_sum_partials) -- *splits says how many.
+hipError_t wgrad(const void* a, int64_t a_ld, const void* g, int64_t g_ld, bool g_f32, float* part, int n, int cin,
+                 int cout, int h, int w, int taps, const float2* fold, int* splits, hipStream_t st) {
+  const int tpi = (h * w + 63) / 64, tiles = n * tpi;
+  const int S = wgrad_splits(n, cin, cout, h, w);
+  const int tps = (tiles + S - 1) / S;
+  *splits = S;
+  dim3 grid((unsigned)S, (unsigned)((cin + 63) / 64), (unsigned)((cout + 63) / 64));
+#define DNB_W(TAPS, TG, PRO)                                                                              \
+  hipLaunchKernelGGL((k_wgrad<TAPS, TG, PRO>), grid, dim3(256), 0, st, (const u16*)a, a_ld, (const TG*)g, \
+                     g_ld, part, cin, cout, n, h, w, tpi, tps, fold)
+  if (taps == 9) {
+    if (g_f32) { if (fold) DNB_W(9, float, true); else DNB_W(9, float, false); }
+    else       { if (fold) DNB_W(9, u16, true); else DNB_W(9, u16, false); }
+  } else {
+    if (g_f32) { if (fold) DNB_W(1, float, true); else DNB_W(1, float, false); }
+    else       { if (fold) DNB_W(1, u16, true); else DNB_W(1, u16, false); }
+  }
+#undef DNB_W
+  return hipGetLastError();
+}
+
+int bn_bwd_splits(int64_t P, int c) {
+  const int groups = (c / 8 + 31) / 32;
+  int s = 1024 / groups;
+  if (s > 256) s = 256;
+  const int64_t cap = (P + 63) / 64;
+  if (s > cap) s = (int)cap;
+  return s < 1 ? 1 : s;
+}
+size_t bn_bwd_partial_floats(int64_t P, int c) { return (size_t)c * bn_bwd_splits(P, c) * 2; }
+
+// BN+ReLU backward.  G != null: du is accumulated into the fp32 slab (row stride g_ld); else du
+// is written as bf16 to du_bf (may alias dact).
+hipError_t bn_relu_bwd(const void* x, int64_t x_ld, const void* dact, int64_t d_ld, void* du_bf, int64_t du_ld,
+                       float* G, int64_t g_ld, int64_t P, int c, const float* gamma, const float* beta,
+                       const float* mean, const float* istd, float* dgamma, float* dbeta, float* part,
+                       hipStream_t st) {
+  const int S = bn_bwd_splits(P, c);
+  const int ppb = (int)((P + S - 1) / S);
+  const int gs = (int)((P + ppb - 1) / ppb);
+  hipLaunchKernelGGL(k_bn_bwd_partial, dim3((unsigned)((c / 8 + 31) / 32), (unsigned)gs), dim3(256), 0, st,
+                     (const u16*)x, x_ld, (const u16*)dact, d_ld, P, c, ppb, gamma, beta, mean, istd, part);
+  hipLaunchKernelGGL(k_bn_bwd_finalize, dim3((unsigned)((c + 63) / 64)), dim3(64), 0, st, part, c, gs, dgamma, dbeta);
+  const float inv_p = 1.0f / (float)P;
+  const unsigned grid = grid1d(P * (c / 8), 256, 65536);
+  if (G)
+    hipLaunchKernelGGL((k_bn_bwd_apply<true>), dim3(grid), dim3(256), 0, st, (const u16*)x, x_ld, (const u16*)dact,
+                       d_ld, (u16*)nullptr, (int64_t)0, G, g_ld, P, c / 8, inv_p, gamma, beta, mean, istd, dgamma, dbeta);
+  else
+    hipLaunchKernelGGL((k_bn_bwd_apply<false>), dim3(grid), dim3(256), 0, st, (const u16*)x, x_ld, (const u16*)dact,
+                       d_ld, (u16*)du_bf, du_ld, (float*)nullptr, (int64_t)0, P, c / 8, inv_p, gamma, beta, mean, istd,
+                       dgamma, dbeta);
+  return hipGetLastError();
+}
+
+}  // namespace nhwc
+}  // namespace dnb

@@ -1,0 +1,181 @@
+"""GPU parity of the bf16 / NHWC path (feature maps bf16, fp32 accumulation and statistics, fused
+schedule) against the float64 oracle evaluated on the same bf16-rounded inputs.
+
+Two oracles are used.  The block output is compared with the plain float64 block.  The gradients
+are compared with the float64 block that rounds to bf16 at the points where the bf16 path stores
+a tensor: a ReLU mask decided on a rounded pre-activation can differ from the unrounded one, and
+with the synthetic N(0,1) loss weights each per-channel gradient sum is a random walk, so a few
+flipped masks (about one element in 700) move those sums by several per cent whatever the
+arithmetic does.  With the storage points emulated the masks agree and the bound is meaningful."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_util import NAMES, assert_close, dev, pack_params_gpu, rel_errors, run_block_oracle
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2  # bf16 storage (the benchmark spec): relative error vs the float64 oracle, L2 and max-abs/max
+# Gradients: the L2 measure keeps TOL.  The worst single element gets a wider bound: where the fp32
+# and the float64 accumulation of the same sum land on different sides of a bf16 rounding boundary
+# the two paths store values one bf16 ulp apart, later layers amplify that, and an occasional ReLU
+# mask then differs, which changes one gradient element (or one small per-channel sum) by its
+# whole size.  Blocks small enough to have no such boundary case agree to 1e-6.
+GRAD_MAX_TOL = 8e-2
+
+
+def assert_grad_close(a, r, what):
+    l2, mx = rel_errors(a, r)
+    assert l2 <= TOL and mx <= GRAD_MAX_TOL, f"{what}: rel L2 {l2:.3e} (> {TOL:g}?), rel max {mx:.3e} (> {GRAD_MAX_TOL:g}?)"
+
+CFGS = [
+    wl.BlockCfg(2, 16, 8, 8, 3, 8, 32),        # small, one 64-pixel tile per image
+    wl.BlockCfg(2, 32, 14, 14, 3, 16, 64),     # 196 pixels: three tiles and a ragged one
+    wl.BlockCfg(1, 24, 7, 7, 2, 8, 32),        # 49 pixels: less than one tile, odd width
+    wl.BlockCfg(2, 96, 28, 28, 2, 48, 192),    # DenseNet-161 widths (k = 48, B = 192)
+    wl.BlockCfg(3, 64, 12, 20, 2, 32, 128),    # DenseNet-264 widths (k = 32, B = 128), non-square
+]
+IDS = [f"n{c.n}c{c.c0}h{c.h}w{c.w}m{c.layers}k{c.growth}B{c.bottleneck}" for c in CFGS]
+
+
+def to_bf16_values(a):
+    """fp32 array rounded to the nearest bf16 value (kept as fp32)."""
+    return torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).to(torch.float32).numpy()
+
+
+def run_block_gpu_bf16(dnb, cfg, x0, layer_params, dy):
+    h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck,
+                             dtype=dnb.DNB_BF16, layout=dnb.DNB_NHWC, schedule=dnb.DNB_SCHED_FUSED, eps=cfg.eps)
+    try:
+        params = dev(pack_params_gpu(dnb, h, layer_params))
+        ws = torch.empty(dnb.dnb_block_workspace_bytes(h), dtype=torch.uint8, device="cuda")
+        ws.fill_(0xFF)
+        nhwc = lambda a: torch.from_numpy(np.ascontiguousarray(a)).permute(0, 2, 3, 1).contiguous().to("cuda", torch.bfloat16)
+        x0d, dyd = nhwc(x0), nhwc(dy)
+        y = torch.full((cfg.n, cfg.h, cfg.w, cfg.c_out), float("nan"), dtype=torch.bfloat16, device="cuda")
+        dx0 = torch.full((cfg.n, cfg.h, cfg.w, cfg.c0), float("nan"), dtype=torch.bfloat16, device="cuda")
+        dparams = torch.full_like(params, float("nan"))
+        dnb.dnb_block_forward(h, x0d, params, y, ws)
+        dnb.dnb_block_backward(h, params, y, dyd, dx0, dparams, ws)
+        torch.cuda.synchronize()
+        back = lambda t: t.float().permute(0, 3, 1, 2).contiguous().cpu().numpy()
+        out = {"y": back(y), "dx0": back(dx0), "dparams": dparams.cpu().numpy(),
+               "mem": dnb.dnb_block_memory_breakdown(h)}
+        out["slices"] = {(l, name): slice(*(lambda o, c: (o, o + c))(*dnb.dnb_block_param_offset(h, l, NAMES.index(name))))
+                         for l in range(1, cfg.layers + 1) for name in NAMES}
+        return out
+    finally:
+        dnb.dnb_block_destroy(h)
+
+
+@pytest.mark.parametrize("cfg", CFGS, ids=IDS)
+def test_bf16_block_matches_oracle(dnb, oracle, cfg):
+    x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
+    x0, dy = to_bf16_values(x0), to_bf16_values(dy)
+    gpu = run_block_gpu_bf16(dnb, cfg, x0, lp, dy)
+    plain, _ = run_block_oracle(oracle, cfg, x0, lp, dy)
+    ores, osl = run_block_oracle(oracle, cfg, x0, lp, dy, schedule="naive_bf16")
+    assert np.array_equal(gpu["y"][:, :cfg.c0], x0)
+    assert_close(gpu["y"], plain.y, TOL, "y vs plain float64")
+    assert_close(gpu["y"], ores.y, TOL, "y")
+    assert_grad_close(gpu["dx0"], ores.dx0, "dx0")
+    for l in range(1, cfg.layers + 1):
+        for name in NAMES:
+            assert_grad_close(gpu["dparams"][gpu["slices"][(l, name)]], ores.dparams[osl[(l, name)]], f"layer {l} d{name}")
+
+
+def test_bf16_bytes_and_unsupported_combinations(dnb):
+    cfg = CFGS[3]
+    h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck,
+                             dtype=dnb.DNB_BF16, layout=dnb.DNB_NHWC, schedule=dnb.DNB_SCHED_FUSED)
+    mm = dnb.dnb_block_memory_breakdown(h)
+    P, m, k, B = cfg.pixels, cfg.layers, cfg.growth, cfg.bottleneck
+    assert mm["stored_fwd_bytes"] == (m * B + m * k) * P * 2 and mm["shared_fwd_bytes"] == 0
+    assert mm["grad_bytes"] == cfg.c_out * P * 4 + (cfg.c_in(m) + B) * P * 2
+    assert mm["peak_bytes"] == mm["stored_fwd_bytes"] + mm["grad_bytes"]
+    dnb.dnb_block_destroy(h)
+    for kw in (dict(layout=dnb.DNB_NCHW), dict(schedule=dnb.DNB_SCHED_SHARED), dict(c0=20)):
+        args = dict(n=2, c0=16, h=8, w=8, layers=2, growth=8, bottleneck=32, dtype=dnb.DNB_BF16,
+                    layout=dnb.DNB_NHWC, schedule=dnb.DNB_SCHED_FUSED)
+        args.update(kw)
+        with pytest.raises(dnb.binding.DnbError) as e:
+            dnb.dnb_block_create(**args)
+        assert e.value.status == dnb.DNB_E_UNSUPPORTED
+
+
+# ------------------------------------------------------------------ single operations
+
+def nhwc_bf16(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).permute(0, 2, 3, 1).contiguous().to("cuda", torch.bfloat16)
+
+
+def nhwc_f32(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).permute(0, 2, 3, 1).contiguous().to("cuda", torch.float32)
+
+
+def back(t):
+    return t.float().permute(0, 3, 1, 2).contiguous().cpu().numpy()
+
+
+OP_SHAPES = [(2, 16, 8, 8, 8, 1), (2, 32, 8, 8, 8, 3), (2, 8, 32, 8, 8, 3), (1, 24, 16, 7, 7, 3), (2, 40, 64, 14, 14, 1),
+             (1, 192, 48, 12, 20, 3), (2, 48, 192, 9, 11, 3), (1, 200, 192, 10, 10, 1)]
+
+
+@pytest.mark.parametrize("n,cin,cout,h,w,ks", OP_SHAPES)
+@pytest.mark.parametrize("g_f32", [0, 1])
+def test_nhwc_conv_ops(dnb, oracle, n, cin, cout, h, w, ks, g_f32):
+    r = np.random.default_rng(5)
+    x = to_bf16_values(r.standard_normal((n, cin, h, w)).astype(np.float32))
+    wgt = to_bf16_values((r.standard_normal((cout, cin, ks, ks)) * np.sqrt(2.0 / (cin * ks * ks))).astype(np.float32))
+    g = to_bf16_values(r.standard_normal((n, cout, h, w)).astype(np.float32))
+    scratch = torch.empty(dnb.dnb_op_nhwc_scratch_bytes(n, cin, cout, h, w, ks), dtype=torch.uint8, device="cuda")
+    d_w = dev(wgt)
+    d_x = nhwc_bf16(x)
+    d_g = nhwc_f32(g) if g_f32 else nhwc_bf16(g)
+    out = torch.full((n, h, w, cout), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dnb.dnb_op_nhwc_conv_forward(d_x, cin, d_w, out, cout, n, cin, cout, h, w, ks, scratch)
+    torch.cuda.synchronize()
+    assert_close(back(out), oracle.conv_forward(x, wgt), 1e-2, "forward")
+    din = torch.full((n, h, w, cin), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dnb.dnb_op_nhwc_conv_dgrad(d_g, cout, g_f32, d_w, din, cin, n, cin, cout, h, w, ks, scratch)
+    torch.cuda.synchronize()
+    assert_close(back(din), oracle.conv_dgrad(g, wgt), 1e-2, "dgrad")
+    dw = torch.full(wgt.shape, float("nan"), device="cuda")
+    dnb.dnb_op_nhwc_conv_wgrad(d_x, cin, d_g, cout, g_f32, dw, n, cin, cout, h, w, ks, scratch)
+    torch.cuda.synchronize()
+    assert_close(dw.cpu().numpy(), oracle.conv_wgrad(x, g, ks), 1e-2, "wgrad")
+
+
+@pytest.mark.parametrize("shape", [(2, 16, 8, 8), (3, 40, 7, 5), (2, 264, 6, 6)])
+@pytest.mark.parametrize("accumulate", [0, 1])
+def test_nhwc_bn_relu_backward(dnb, oracle, shape, accumulate):
+    r = np.random.default_rng(6)
+    n, c, h, w = shape
+    x = to_bf16_values((r.standard_normal(shape) * 1.5 + 0.3).astype(np.float32))
+    dact = to_bf16_values(r.standard_normal(shape).astype(np.float32))
+    base = r.standard_normal(shape).astype(np.float32)
+    gamma = (1 + 0.3 * r.standard_normal(c)).astype(np.float32)
+    beta = (0.3 * r.standard_normal(c)).astype(np.float32)
+    eps = 1e-5
+    z, omean, ovar = oracle.bn_forward(x, gamma, beta, eps)
+    mean, istd = dev(omean.astype(np.float32)), dev((1 / np.sqrt(ovar + eps)).astype(np.float32))
+    scratch = torch.empty(dnb.dnb_op_nhwc_scratch_bytes(n, c, c, h, w, 1), dtype=torch.uint8, device="cuda")
+    dg, db = torch.empty(c, device="cuda"), torch.empty(c, device="cuda")
+    d_x, d_d = nhwc_bf16(x), nhwc_bf16(dact)
+    P = n * h * w
+    if accumulate:
+        acc = nhwc_f32(base)
+        dnb.dnb_op_nhwc_bn_relu_backward(d_x, c, d_d, c, None, 0, acc, c, P, c, dev(gamma), dev(beta), mean, istd, dg, db, scratch)
+        got = back(acc)
+    else:
+        dnb.dnb_op_nhwc_bn_relu_backward(d_x, c, d_d, c, d_d, c, None, 0, P, c, dev(gamma), dev(beta), mean, istd, dg, db, scratch)
+        got = back(d_d)
+    torch.cuda.synchronize()
+    # the mask is taken in fp32 from the same bf16 x: recompute z in fp32 like the kernel
+    dz = oracle.relu_backward(oracle.relu(z), dact)
+    odu, odg, odb = oracle.bn_backward(x, dz, gamma, omean, ovar, eps)
+    if accumulate:
+        odu = odu + base
+    assert_close(got, odu, 1e-2, "du")
+    assert_close(dg.cpu().numpy(), odg, 1e-2, "dgamma")
+    assert_close(db.cpu().numpy(), odb, 1e-2, "dbeta")
