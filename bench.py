@@ -30,7 +30,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3"])
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config4", "config5"],
+                    help="config2 is the metric's workload; config4/5 are the bf16 NHWC ImageNet-shaped block sets (diagnostic)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--schedule", default="fused", choices=["shared", "store_all", "fused"],
                     help="fused: BN+ReLU recomputed inside the conv operand loads (default, fastest linear-memory schedule); "
@@ -49,23 +50,35 @@ def workload_blocks(wl, name, batch):
     if name == "config2":
         b = batch or 64
         return wl.config2(b), f"DenseNet-BC L=100 k=12 batch {b} fp32 NCHW, 3 dense blocks x 16 layers (fwd+bwd)"
-    b = batch or 64
-    return wl.config3(b), f"DenseNet-BC L=250 k=24 batch {b} fp32 NCHW, 3 dense blocks x 41 layers (fwd+bwd)"
+    if name == "config3":
+        b = batch or 64
+        return wl.config3(b), f"DenseNet-BC L=250 k=24 batch {b} fp32 NCHW, 3 dense blocks x 41 layers (fwd+bwd)"
+    if name == "config4":
+        b = batch or 32
+        return wl.config4(b), f"DenseNet-161-shaped k=48 batch {b} bf16 NHWC, dense blocks 6-12-36-24 (fwd+bwd)"
+    b = batch or 32
+    return wl.config5(b), f"DenseNet-264-shaped k=32 batch {b} bf16 NHWC, dense blocks 6-12-64-48 (fwd+bwd)"
 
 
 class BlockRun:
     """Device buffers + handle of one dense block."""
 
-    def __init__(self, dnb, torch, wl, cfg, schedule, seed):
+    def __init__(self, dnb, torch, wl, cfg, schedule, seed, bf16=False):
         from gpu_util import dev, pack_params_gpu
         self.cfg = cfg
+        kw = dict(dtype=dnb.DNB_BF16, layout=dnb.DNB_NHWC) if bf16 else {}
         self.h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck,
-                                      schedule=schedule, eps=cfg.eps)
+                                      schedule=schedule, eps=cfg.eps, **kw)
         x0, lp, dy = wl.make_block_inputs(cfg, seed, seed + 1, seed + 2, affine="ones")
-        self.x0, self.dy = dev(x0), dev(dy)
+        if bf16:
+            nhwc = lambda a: torch.from_numpy(a).permute(0, 2, 3, 1).contiguous().to("cuda", torch.bfloat16)
+            self.x0, self.dy = nhwc(x0), nhwc(dy)
+            self.y = torch.empty((cfg.n, cfg.h, cfg.w, cfg.c_out), dtype=torch.bfloat16, device="cuda")
+        else:
+            self.x0, self.dy = dev(x0), dev(dy)
+            self.y = torch.empty((cfg.n, cfg.c_out, cfg.h, cfg.w), dtype=torch.float32, device="cuda")
         self.params = dev(pack_params_gpu(dnb, self.h, lp))
         self.dparams = torch.empty_like(self.params)
-        self.y = torch.empty((cfg.n, cfg.c_out, cfg.h, cfg.w), dtype=torch.float32, device="cuda")
         self.dx0 = torch.empty_like(self.x0)
         self.ws = torch.empty(dnb.dnb_block_workspace_bytes(self.h), dtype=torch.uint8, device="cuda")
         self.mem = dnb.dnb_block_memory_breakdown(self.h)
@@ -219,8 +232,13 @@ def main():
     sched = {"shared": dnb.DNB_SCHED_SHARED, "store_all": dnb.DNB_SCHED_STORE_ALL, "fused": dnb.DNB_SCHED_FUSED}
     use_graph = not a.no_graph
 
+    bf16 = a.workload in ("config4", "config5")
+    if bf16 and a.schedule != "fused":
+        print("bench.py: the bf16 NHWC path has the fused schedule only", file=sys.stderr)
+        sys.exit(2)
+
     def measure(schedule):
-        runs = [BlockRun(dnb, torch, wl, c, sched[schedule], 10 * i) for i, c in enumerate(blocks)]
+        runs = [BlockRun(dnb, torch, wl, c, sched[schedule], 10 * i, bf16) for i, c in enumerate(blocks)]
         secs = time_steps(torch, make_step(dnb, runs, a.forward_only), a.steps, a.warmup, use_graph)
         return runs, secs
 
@@ -230,17 +248,18 @@ def main():
         "metric": "train images/sec per MI355X (fwd+bwd) + peak feature-map bytes vs depth",
         "value": round(value, 2), "unit": "images/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": round(1e3 * secs / a.steps, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": wname, "schedule": a.schedule, "launch": "hip_graph" if use_graph else "eager",
                    "global_batch": batch},
         "peak_feature_map_bytes": {"per_block": [r.mem["peak_bytes"] for r in runs],
                                    "total": sum(r.mem["peak_bytes"] for r in runs),
                                    "workspace_total": sum(r.mem["workspace_bytes"] for r in runs)},
     }
-    out["roofline"] = dominant_kernel_roofline(dnb, torch, runs, f"{a.workload}:{batch}" if a.only_block < 0 else "")
+    # the roofline entry is that of the fp32 path's dominant kernel; the bf16 block sets are diagnostic
+    out["roofline"] = None if bf16 else dominant_kernel_roofline(dnb, torch, runs, f"{a.workload}:{batch}" if a.only_block < 0 else "")
     del runs
     torch.cuda.empty_cache()
-    if not a.no_compare:
+    if not a.no_compare and not bf16:
         # the other schedules on the same workload: the paper-literal shared-storage schedule and
         # the store-everything schedule it is compared with (Section 5)
         t = {a.schedule: secs}
@@ -255,7 +274,7 @@ def main():
             torch.cuda.empty_cache()
         out["recompute_overhead"] = round(t["shared"] / t["store_all"] - 1.0, 4)
         out["fused_vs_store_all_time"] = round(t["fused"] / t["store_all"] - 1.0, 4)
-    if not a.no_cpu_baseline:
+    if not a.no_cpu_baseline and not bf16:
         out["cpu_baseline"] = cpu_baseline(wl, blocks)
     print(json.dumps(out), flush=True)
 

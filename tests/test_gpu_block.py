@@ -169,3 +169,35 @@ def test_hip_graph_replays_match_eager(dnb):
         assert np.array_equal(dparams.cpu().numpy(), eager["dparams"]), rep
         _ = (torch.randn(1000, device="cuda") * 2).sum().item()  # unrelated eager work between replays
     dnb.dnb_block_destroy(h)
+
+
+def full_size_grad_close(a, r, what, elementwise=False):
+    """Gradient comparison at full size.  With ~10^8 pre-activations per block a few dozen lie within
+    fp32 rounding of zero, so their ReLU masks differ between any fp32 evaluation and the float64
+    one; each such element changes a gradient element (or a per-channel sum) by its whole size.
+    The float64 oracle itself moves by rel L2 9e-4 / rel max 2.7e-2 in dx0 when its input is
+    perturbed by 6e-8 relative noise.  So: rel L2 <= 1e-2, worst element <= 1e-1, and for the
+    feature-map gradient (where a differing mask touches few elements, unlike the per-channel
+    sums) at most 2 % of the elements further than 1e-4 * max|ref|.  Blocks where no mask differs
+    (the 8x8 one) agree to 1e-6, and the small-shape tests keep the strict bound."""
+    l2, mx = rel_errors(a, r)
+    far = float((np.abs(a.astype(np.float64) - r) > TOL * np.abs(r).max()).mean()) if elementwise else 0.0
+    assert l2 <= 1e-2 and mx <= 1e-1 and far <= 0.02, f"{what}: rel L2 {l2:.3e}, rel max {mx:.3e}, fraction beyond {TOL:g}: {far:.4f}"
+
+
+@pytest.mark.parametrize("i", [0, 1, 2])
+def test_full_size_benchmark_blocks_match_oracle(dnb, oracle, i):
+    """The benchmark workload at its full size (DenseNet-BC L=100, k=12, batch 64; the three dense
+    blocks of 16 layers) in the configuration the benchmark times -- fused schedule, weight-gradient
+    chains on helper streams -- against the oracle's memory-efficient schedule: the output to the
+    strict bound, every gradient to the mask-flip-tolerant one, the byte count exactly."""
+    cfg = wl.config2(64)[i]
+    x0, lp, dy = wl.make_block_inputs(cfg, 10 + i, 20 + i, 30 + i, affine="random")
+    gpu = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=2)
+    ores, osl = run_block_oracle(oracle, cfg, x0, lp, dy, schedule="shared")
+    assert_close(gpu["y"], ores.y, TOL, "y")
+    full_size_grad_close(gpu["dx0"], ores.dx0, "dx0", elementwise=True)
+    for l in range(1, cfg.layers + 1):
+        for name in NAMES:
+            full_size_grad_close(gpu["dparams"][gpu["slices"][(l, name)]], ores.dparams[osl[(l, name)]], f"layer {l} d{name}")
+    assert gpu["peak"] == ores.peak_elems * 4 - (2 * cfg.c_in(cfg.layers) + cfg.bottleneck) * cfg.pixels * 4
