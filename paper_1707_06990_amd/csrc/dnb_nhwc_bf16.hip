@@ -89,22 +89,60 @@ __global__ __launch_bounds__(256) void k_f32_rows_to_bf16(const float* __restric
 }
 
 // Statistics partials of c channels over pixel range split s: part[(ch*S + s)*3] = (count, mean, M2).
-// Thread = one channel, consecutive threads = consecutive channels (coalesced rows); two passes.
-__global__ __launch_bounds__(64) void k_stats_partial(const u16* __restrict__ x, int64_t ld, int64_t P,
-                                                      int c, int ppb, float* __restrict__ part) {
-  const int ch = blockIdx.x * 64 + threadIdx.x, s = blockIdx.y, S = gridDim.y;
-  if (ch >= c) return;
+// Thread = (8-channel vector, pixel row): 32 vectors x 8 rows per workgroup, 16-byte loads.  Each
+// thread sums deviations from its first value (no cancellation for |mean| >> std), converts to
+// (count, mean, M2) and the 8 rows are combined in row order.  grid (vector groups, splits).
+__global__ __launch_bounds__(256) void k_stats_partial(const u16* __restrict__ x, int64_t ld, int64_t P,
+                                                       int c, int ppb, float* __restrict__ part) {
+  __shared__ float red[3][8][256];
+  const int cvl = threadIdx.x & 31, pr = threadIdx.x >> 5;
+  const int ch0 = (blockIdx.x * 32 + cvl) * 8, s = blockIdx.y, S = gridDim.y;
   const int64_t p0 = (int64_t)s * ppb, p1 = min(P, p0 + ppb);
-  float sum = 0.f;
-  for (int64_t p = p0; p < p1; ++p) sum += bf2f(x[p * ld + ch]);
-  const float cnt = (float)(p1 - p0), mu = sum / cnt;
-  float m2 = 0.f;
-  for (int64_t p = p0; p < p1; ++p) {
-    const float d = bf2f(x[p * ld + ch]) - mu;
-    m2 = __fmaf_rn(d, d, m2);
+  const bool ok = ch0 < c;
+  float K[8], sd[8], sq[8];
+  float cnt = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) K[e] = sd[e] = sq[e] = 0.f;
+  if (ok) {
+    int64_t p = p0 + pr;
+    if (p < p1) {
+      V8 v;
+      v.q = *reinterpret_cast<const uint4*>(x + p * ld + ch0);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) K[e] = bf2f(v.h[e]);
+      cnt = 1.f;
+      p += 8;
+    }
+    for (; p < p1; p += 8) {
+      V8 v;
+      v.q = *reinterpret_cast<const uint4*>(x + p * ld + ch0);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float d = bf2f(v.h[e]) - K[e];
+        sd[e] += d;
+        sq[e] = __fmaf_rn(d, d, sq[e]);
+      }
+      cnt += 1.f;
+    }
   }
-  float* o = part + ((int64_t)ch * S + s) * 3;
-  o[0] = cnt; o[1] = mu; o[2] = m2;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float md = cnt > 0.f ? sd[e] / cnt : 0.f;
+    red[0][e][threadIdx.x] = cnt;
+    red[1][e][threadIdx.x] = K[e] + md;
+    red[2][e][threadIdx.x] = fmaxf(0.f, __fmaf_rn(-sd[e], md, sq[e]));
+  }
+  __syncthreads();
+  if (pr == 0 && ok) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      Stat3 a{red[0][e][cvl], red[1][e][cvl], red[2][e][cvl]};
+      for (int r = 1; r < 8; ++r)
+        a = stat_combine(a, Stat3{red[0][e][r * 32 + cvl], red[1][e][r * 32 + cvl], red[2][e][r * 32 + cvl]});
+      float* o = part + ((int64_t)(ch0 + e) * S + s) * 3;
+      o[0] = a.c; o[1] = a.m; o[2] = a.m2;
+    }
+  }
 }
 
 // Packed bf16 weights: [taps][M16][K32] (K padded to a multiple of 32, zero filled), K natural order.
@@ -468,14 +506,18 @@ __global__ __launch_bounds__(256) void k_bn_bwd_partial(
   }
 }
 
-// dgamma/dbeta = sum of the S partials (fixed order); one thread per channel.
-__global__ __launch_bounds__(64) void k_bn_bwd_finalize(const float* __restrict__ part, int c, int S,
-                                                        float* __restrict__ dgamma, float* __restrict__ dbeta) {
-  const int ch = blockIdx.x * 64 + threadIdx.x;
+// dgamma/dbeta = sum of the S partials, one wave per channel: lane i adds partials i, i+64, ...
+// in order, then a butterfly over the lanes (fixed order, every lane the same bits).
+__global__ __launch_bounds__(256) void k_bn_bwd_finalize(const float* __restrict__ part, int c, int S,
+                                                         float* __restrict__ dgamma, float* __restrict__ dbeta) {
+  const int ch = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (ch >= c) return;
+  const float2* pp = reinterpret_cast<const float2*>(part) + (int64_t)ch * S;
   float b = 0.f, g = 0.f;
-  for (int s = 0; s < S; ++s) { b += part[((int64_t)ch * S + s) * 2]; g += part[((int64_t)ch * S + s) * 2 + 1]; }
-  dbeta[ch] = b; dgamma[ch] = g;
+  for (int s = lane; s < S; s += 64) { const float2 v = pp[s]; b += v.x; g += v.y; }
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) { b += __shfl_xor(b, off, 64); g += __shfl_xor(g, off, 64); }
+  if (lane == 0) { dbeta[ch] = b; dgamma[ch] = g; }
 }
 
 // du = scale*(dz - dbeta/P - xhat*dgamma/P).  ACC: added into the fp32 slab G (BN1, concat
@@ -547,7 +589,8 @@ hipError_t f32_rows_to_bf16(const float* src, int64_t sld, void* dst, int64_t P,
 }
 
 int stats_splits(int64_t P, int c) {
-  int s = (2048 + c - 1) / c;
+  const int groups = (c / 8 + 31) / 32;
+  int s = 1024 / groups;
   if (s > 256) s = 256;
   const int64_t cap = (P + 63) / 64;
   if (s > cap) s = (int)cap;
@@ -560,8 +603,8 @@ hipError_t stats_partial(const void* x, int64_t ld, int64_t P, int c, float* par
   const int ppb = (int)((P + S - 1) / S);
   const int gs = (int)((P + ppb - 1) / ppb);
   *T = gs;
-  hipLaunchKernelGGL(k_stats_partial, dim3((unsigned)((c + 63) / 64), (unsigned)gs), dim3(64), 0, st, (const u16*)x, ld,
-                     P, c, ppb, part);
+  hipLaunchKernelGGL(k_stats_partial, dim3((unsigned)((c / 8 + 31) / 32), (unsigned)gs), dim3(256), 0, st,
+                     (const u16*)x, ld, P, c, ppb, part);
   return hipGetLastError();
 }
 
@@ -691,7 +734,7 @@ hipError_t bn_relu_bwd(const void* x, int64_t x_ld, const void* dact, int64_t d_
   const int gs = (int)((P + ppb - 1) / ppb);
   hipLaunchKernelGGL(k_bn_bwd_partial, dim3((unsigned)((c / 8 + 31) / 32), (unsigned)gs), dim3(256), 0, st,
                      (const u16*)x, x_ld, (const u16*)dact, d_ld, P, c, ppb, gamma, beta, mean, istd, part);
-  hipLaunchKernelGGL(k_bn_bwd_finalize, dim3((unsigned)((c + 63) / 64)), dim3(64), 0, st, part, c, gs, dgamma, dbeta);
+  hipLaunchKernelGGL(k_bn_bwd_finalize, dim3((unsigned)((c + 3) / 4)), dim3(256), 0, st, part, c, gs, dgamma, dbeta);
   const float inv_p = 1.0f / (float)P;
   const unsigned grid = grid1d(P * (c / 8), 256, 65536);
   if (G)
