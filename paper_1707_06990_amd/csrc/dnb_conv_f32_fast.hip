@@ -10,7 +10,9 @@
 // {g, 4+g, 8+g, 12+g} of a 16-channel chunk and a channel tail that is a multiple of 4
 // costs no padding.
 #ifndef DNB_DBG
-#define DNB_DBG 0  // kernel ablation builds for tuning experiments (1: no MFMA, 2/4: no activation / weight loads)
+#define DNB_DBG 0  // kernel ablation builds for tuning experiments (1x1: 1 no MFMA, 2/4 no activation / weight loads;
+                   // 3x3: 8 no MFMA, 16/32 no activation / weight loads, 64 no statistics epilogue,
+                   // 128 no output stores, 256 no K-split reduction, 512 no LDS operand reads, 1024 no staging)
 #endif
 
 #include "dnb_internal.h"
@@ -348,20 +350,35 @@ __global__ __launch_bounds__(256) void k_conv3x3_v3(
   const int nchunks = Kpad >> 4;
   const int cstart = KSPLIT ? wave : 0, cstep = KSPLIT ? nw : 1;
 
+  // Staging: U independent 16-byte loads per thread are issued back to back (clamped addresses,
+  // no branches, so they are all in flight together), then transformed and stored.
   const int rows = (cin + 3) & ~3;  // staged channel rows (tail rows zero)
-  for (int row = tid >> 4; row < rows; row += nthr >> 4) {
-    const float* src = inb + (int64_t)row * HW;
-    float2 f = make_float2(1.f, 0.f);
-    if (PRO && row < cin) f = fold[row];
-    for (int c4 = tid & 15; c4 < seg4; c4 += 16) {
+  const int total = rows * seg4;
+  constexpr int U = 8;
+  for (int base = 0; base < ((DNB_DBG & 1024) ? 0 : total); base += nthr * U) {
+    float4 v[U];
+    float2 f[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int idx = base + u * nthr + tid;
+      const int row = min(idx / seg4, cin - 1);
+      const int qq = origin + 4 * (idx % seg4);
+      v[u] = (DNB_DBG & 16) ? make_float4(1.f, 1.f, 1.f, 1.f) : ldg4(inb + (int64_t)row * HW + min(max(qq, 0), HW - 4));
+      if (PRO) f[u] = fold[row];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int idx = base + u * nthr + tid;
+      const int row = idx / seg4, c4 = idx - row * seg4;
       const int qq = origin + 4 * c4;
       const bool ok = row < cin && qq >= 0 && qq < HW;
-      float4 v = ok ? ldg4(src + qq) : zero4();
-      if (PRO && ok) {  // BN + ReLU on the way in; the zero padding stays zero
-        v.x = fmaxf(__fmaf_rn(v.x, f.x, f.y), 0.f); v.y = fmaxf(__fmaf_rn(v.y, f.x, f.y), 0.f);
-        v.z = fmaxf(__fmaf_rn(v.z, f.x, f.y), 0.f); v.w = fmaxf(__fmaf_rn(v.w, f.x, f.y), 0.f);
+      float4 x = v[u];
+      if (PRO) {  // BN + ReLU on the way in; the zero padding stays zero
+        x.x = fmaxf(__fmaf_rn(x.x, f[u].x, f[u].y), 0.f); x.y = fmaxf(__fmaf_rn(x.y, f[u].x, f[u].y), 0.f);
+        x.z = fmaxf(__fmaf_rn(x.z, f[u].x, f[u].y), 0.f); x.w = fmaxf(__fmaf_rn(x.w, f[u].x, f[u].y), 0.f);
       }
-      *reinterpret_cast<float4*>(&lds[row * CS + 4 * c4]) = v;
+      if (!ok) x = zero4();
+      if (idx < total) *reinterpret_cast<float4*>(&lds[row * CS + 4 * c4]) = x;
     }
   }
   __syncthreads();
@@ -381,7 +398,8 @@ __global__ __launch_bounds__(256) void k_conv3x3_v3(
       for (int t = 0; t < 9; ++t)
 #pragma unroll
         for (int a = 0; a < MT; ++a)
-          w4[t][a] = (mbase + a * 16 < Mpad)
+          w4[t][a] = (DNB_DBG & 32) ? make_float4(1.f, 1.f, 1.f, 1.f)
+                     : (mbase + a * 16 < Mpad)
                          ? ldg4(Wp + ((int64_t)t * Mpad + mbase + a * 16 + j) * Kpad + c0 + 4 * g)
                          : zero4();
 #pragma unroll
@@ -393,9 +411,13 @@ __global__ __launch_bounds__(256) void k_conv3x3_v3(
         for (int ks = 0; ks < 4; ++ks) {
           if (ks < nks) {
             const float* rowp = &lds[(c0 + 4 * ks + g) * CS + base];
-            V[ks] = *reinterpret_cast<const float4*>(rowp);
-            eL[ks] = maskL ? 0.f : rowp[-1];
-            eR[ks] = maskR ? 0.f : rowp[4];
+            if (DNB_DBG & 512) {
+              V[ks] = make_float4(1.f, 2.f, 3.f, 4.f); eL[ks] = 0.5f; eR[ks] = 1.5f;
+            } else {
+              V[ks] = *reinterpret_cast<const float4*>(rowp);
+              eL[ks] = maskL ? 0.f : rowp[-1];
+              eR[ks] = maskR ? 0.f : rowp[4];
+            }
           } else {
             V[ks] = zero4(); eL[ks] = 0.f; eR[ks] = 0.f;
           }
@@ -413,10 +435,14 @@ __global__ __launch_bounds__(256) void k_conv3x3_v3(
 #pragma unroll
               for (int a = 0; a < MT; ++a) {
                 const float wa = elem(w4[t][a], ks);
-                acc[a][0] = mfma16(wa, b0, acc[a][0]);
-                acc[a][1] = mfma16(wa, b1, acc[a][1]);
-                acc[a][2] = mfma16(wa, b2, acc[a][2]);
-                acc[a][3] = mfma16(wa, b3, acc[a][3]);
+                if (DNB_DBG & 8) {
+                  acc[a][0][ks] += wa * b0; acc[a][1][ks] += wa * b1; acc[a][2][ks] += wa * b2; acc[a][3][ks] += wa * b3;
+                } else {
+                  acc[a][0] = mfma16(wa, b0, acc[a][0]);
+                  acc[a][1] = mfma16(wa, b1, acc[a][1]);
+                  acc[a][2] = mfma16(wa, b2, acc[a][2]);
+                  acc[a][3] = mfma16(wa, b3, acc[a][3]);
+                }
               }
             }
           }
@@ -425,17 +451,17 @@ __global__ __launch_bounds__(256) void k_conv3x3_v3(
     }
   }
 
-  if (KSPLIT) ksplit_reduce<MT, 4>(acc, lds, wave, lane, nw);  // reuses the tile's LDS (barrier inside)
+  if (KSPLIT && !(DNB_DBG & 256)) ksplit_reduce<MT, 4>(acc, lds, wave, lane, nw);  // reuses the tile's LDS (barrier inside)
 
   const int tile_px = min(64, HW - q0);
 #pragma unroll
   for (int a = 0; a < MT; ++a) {
     if (KSPLIT && a % nw != wave) continue;
     if (mbase + a * 16 >= Mpad) continue;
-    if (STATS)
+    if (STATS && !(DNB_DBG & 64))
       tile_stats<4>(acc[a], q < HW, (float)tile_px, mbase + a * 16, cout, spart, sT,
                     img * gridDim.x + blockIdx.x);
-    if (q < HW) {
+    if (q < HW && (!(DNB_DBG & 128) || acc[a][0][0] == 12345.f)) {
       float* ob = out + (int64_t)img * out_stride + q;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
