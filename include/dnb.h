@@ -59,7 +59,9 @@ typedef struct {
   int32_t n, c0, h, w;  /* block input x0 is (n, c0, h, w)                            */
   int32_t layers;       /* m >= 1                                                     */
   int32_t growth;       /* k >= 1, channels added per layer                           */
-  int32_t bottleneck;   /* B >= 1, width of the 1x1 conv output (4k in DenseNet-BC)   */
+  int32_t bottleneck;   /* B >= 1, width of the 1x1 conv output (4k in DenseNet-BC);  *
+                         * 0 = no bottleneck: BN -> ReLU -> 3x3 on the concatenation  *
+                         * (fp32 NCHW, shared and store-all schedules)                */
   int32_t dtype;        /* DNB_F32 | DNB_BF16                                         */
   int32_t layout;       /* DNB_NCHW | DNB_NHWC                                        */
   int32_t schedule;     /* DNB_SCHED_*                                                */

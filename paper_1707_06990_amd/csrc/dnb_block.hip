@@ -42,8 +42,11 @@ namespace {
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 inline int c_in(const dnb_block_desc& d, int l) { return d.c0 + (l - 1) * d.growth; }
 
+// Per layer: g1[C] b1[C] W1[B][C] g2[B] b2[B] W3[k][B][3][3]; without a bottleneck (B = 0) the
+// 3x3 conv reads the concatenation directly: g1[C] b1[C] W3[k][C][3][3].
 size_t layer_params(const dnb_block_desc& d, int l) {
   const size_t c = (size_t)c_in(d, l), B = (size_t)d.bottleneck, k = (size_t)d.growth;
+  if (B == 0) return 2 * c + k * c * 9;
   return 2 * c + B * c + 2 * B + k * B * 9;
 }
 
@@ -67,7 +70,7 @@ T layer_ptrs(const dnb_block* b, P* base, int l) {
   P* p = base + b->poff[l];
   T r;
   r.g1 = p; r.b1 = p + c; r.W1 = p + 2 * c; r.g2 = p + 2 * c + B * c; r.b2 = r.g2 + B; r.W3 = r.b2 + B;
-  return r;
+  return r;  // (B = 0: W1, g2, b2 are empty and W3 starts right after b1)
 }
 
 
@@ -161,6 +164,71 @@ int backward_bf16(dnb_block* b, const float* params, const void* yv, const void*
   return DNB_OK;
 }
 
+// ---- fp32 NCHW without a bottleneck: each layer is BN -> ReLU -> 3x3 conv on the concatenation
+// (the composite function as first defined, Section 2 "Dense connectivity").  Storage 1 and 2 are
+// used exactly as with a bottleneck; there is no storage 3 and no kept b_l.  The generic
+// implicit-GEMM kernels take the wide 3x3 (C_l input channels); everything runs in program order
+// on the caller's stream.
+int forward_plain3x3(dnb_block* b, const float* x0, const float* params, float* y, char* ws, hipStream_t st) {
+  const dnb_block_desc& d = b->d;
+  const int n = d.n, m = d.layers, k = d.growth, hw = (int)b->hw;
+  const int64_t ys = (int64_t)b->cout * hw;
+  float* mean_y = (float*)(ws + b->off_stat_y);
+  float* istd_y = mean_y + b->cout;
+  float* part = (float*)(ws + b->off_part);
+  DNB_TRY(launch_copy_slab(x0, (int64_t)d.c0 * hw, y, ys, n, (int64_t)d.c0 * hw, st));
+  int freshT = 0;
+  DNB_TRY(launch_bn_stats_partial(y, ys, n, d.c0, hw, part, &freshT, st));
+  int fresh_lo = 0, fresh_hi = d.c0;
+  for (int l = 1; l <= m; ++l) {
+    const int c = c_in(d, l);
+    const LayerParams p = layer_ptrs<LayerParams, const float>(b, params, l);
+    float* S1 = (float*)(ws + b->off_u[l]);
+    float* S2 = (float*)(ws + b->off_a[l]);
+    float* xl = y + (int64_t)c * hw;
+    DNB_TRY(launch_bn_relu(y, ys, S2, (int64_t)c * hw, S1, (int64_t)c * hw, n, c, hw, p.g1, p.b1,
+                           StatsSrc{mean_y, istd_y, part, freshT, fresh_lo, fresh_hi, d.eps}, st));
+    DNB_TRY(launch_conv_igemm(S2, (int64_t)c * hw, WeightView{p.W3, (int64_t)c * 9, 9, 0}, nullptr, xl, ys,
+                              n, c, k, d.h, d.w, 9, nullptr, st));
+    if (l < m) DNB_TRY(launch_bn_stats_partial(xl, ys, n, k, hw, part, &freshT, st));
+    fresh_lo = c; fresh_hi = c + k;
+  }
+  return DNB_OK;
+}
+
+int backward_plain3x3(dnb_block* b, const float* params, const float* y, const float* dy, float* dx0,
+                      float* dparams, char* ws, hipStream_t st) {
+  const dnb_block_desc& d = b->d;
+  const int n = d.n, m = d.layers, k = d.growth, hw = (int)b->hw;
+  const bool recompute = d.schedule == DNB_SCHED_SHARED;
+  const int64_t ys = (int64_t)b->cout * hw;
+  float* mean_y = (float*)(ws + b->off_stat_y);
+  float* istd_y = mean_y + b->cout;
+  float* part = (float*)(ws + b->off_part);
+  float* partA = (float*)(ws + b->off_partA);
+  float* G = (float*)(ws + b->off_G);
+  float* dS2 = (float*)(ws + b->off_dS2);
+  DNB_TRY(launch_copy_slab(dy, ys, G, ys, n, ys, st));
+  for (int l = m; l >= 1; --l) {
+    const int c = c_in(d, l);
+    const LayerParams p = layer_ptrs<LayerParams, const float>(b, params, l);
+    const LayerGrads gp = layer_ptrs<LayerGrads, float>(b, dparams, l);
+    float* S1 = (float*)(ws + b->off_u[l]);
+    float* S2 = (float*)(ws + b->off_a[l]);
+    float* gl = G + (int64_t)c * hw;
+    if (recompute)  // re-populate storage 1 and 2 for this layer
+      DNB_TRY(launch_bn_relu(y, ys, S2, (int64_t)c * hw, S1, (int64_t)c * hw, n, c, hw, p.g1, p.b1,
+                             StatsSrc{mean_y, istd_y, nullptr, 0, 0, 0, d.eps}, st));
+    DNB_TRY(launch_conv_wgrad(S2, (int64_t)c * hw, gl, ys, gp.W3, n, c, k, d.h, d.w, 9, partA, nullptr, st));
+    DNB_TRY(launch_conv_igemm(gl, ys, WeightView{p.W3, 9, (int64_t)c * 9, 1}, nullptr, dS2, (int64_t)c * hw,
+                              n, k, c, d.h, d.w, 9, nullptr, st));
+    DNB_TRY(launch_bn_relu_bwd(S1, (int64_t)c * hw, dS2, (int64_t)c * hw, G, ys, true, n, c, hw, p.g1, p.b1,
+                               mean_y, istd_y, gp.g1, gp.b1, part, st));
+  }
+  DNB_TRY(launch_copy_slab(G, ys, dx0, (int64_t)d.c0 * hw, n, (int64_t)d.c0 * hw, st));
+  return DNB_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -182,7 +250,7 @@ const char* dnb_status_string(int status) {
 int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
   if (!desc || !out) return DNB_E_NULL;
   const dnb_block_desc& d = *desc;
-  if (d.n < 1 || d.c0 < 1 || d.h < 1 || d.w < 1 || d.layers < 1 || d.growth < 1 || d.bottleneck < 1)
+  if (d.n < 1 || d.c0 < 1 || d.h < 1 || d.w < 1 || d.layers < 1 || d.growth < 1 || d.bottleneck < 0)
     return DNB_E_BADDESC;
   if (!(d.eps >= 0.f)) return DNB_E_BADDESC;
   if (d.dtype != DNB_F32 && d.dtype != DNB_BF16) return DNB_E_BADDESC;
@@ -193,6 +261,8 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
   const bool bf16 = d.dtype == DNB_BF16;
   if (bf16 ? (d.layout != DNB_NHWC || d.schedule != DNB_SCHED_FUSED) : (d.layout != DNB_NCHW))
     return DNB_E_UNSUPPORTED;
+  // no bottleneck (BN-ReLU-3x3 on the concatenation): fp32, materialised schedules
+  if (d.bottleneck == 0 && (bf16 || d.schedule == DNB_SCHED_FUSED)) return DNB_E_UNSUPPORTED;
   // bf16 kernels move 8 channels (16 bytes) at a time
   if (bf16 && (d.c0 % 8 || d.growth % 8 || d.bottleneck % 8)) return DNB_E_UNSUPPORTED;
   if (bf16 && (size_t)(64 + 2 * (d.w + 1)) * 80 > 64 * 1024) return DNB_E_UNSUPPORTED;
@@ -305,17 +375,26 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
   } else {
     need(bn_stats_partial_floats(d.n, d.c0, (int)hw));
     need(bn_stats_partial_floats(d.n, k, (int)hw));
-    need(bn_stats_partial_floats(d.n, B, (int)hw));
-    need(bn_bwd_partial_floats(d.n, B, (int)hw));
-    need(conv_stats_partial_floats(d.n, B, d.h, d.w));  // epilogue statistics of the two convs
+    if (B > 0) {
+      need(bn_stats_partial_floats(d.n, B, (int)hw));
+      need(bn_bwd_partial_floats(d.n, B, (int)hw));
+      need(conv_stats_partial_floats(d.n, B, d.h, d.w));  // epilogue statistics of the two convs
+    }
     need(conv_stats_partial_floats(d.n, k, d.h, d.w));
     for (int l = 1; l <= m; ++l) {
       need(bn_bwd_partial_floats(d.n, c_in(d, l), (int)hw));
-      const size_t f = conv_wgrad_partial_floats(d.n, c_in(d, l), B, d.h, d.w, 1);
+      const size_t f = B > 0 ? conv_wgrad_partial_floats(d.n, c_in(d, l), B, d.h, d.w, 1) : 0;
       if (f > partB) partB = f;
     }
-    partA = conv_wgrad_partial_floats(d.n, B, k, d.h, d.w, 9);
-    for (int l = 1; l <= m; ++l) { b->pk[l] = pack; pack += packed_layer_floats(c_in(d, l), k, B); }
+    if (B == 0) {
+      for (int l = 1; l <= m; ++l) {
+        const size_t f = conv_wgrad_partial_floats(d.n, c_in(d, l), k, d.h, d.w, 9);
+        if (f > partA) partA = f;
+      }
+    } else {
+      partA = conv_wgrad_partial_floats(d.n, B, k, d.h, d.w, 9);
+      for (int l = 1; l <= m; ++l) { b->pk[l] = pack; pack += packed_layer_floats(c_in(d, l), k, B); }
+    }
   }
   mem.scratch_bytes = (uint64_t)(part + partA + partB + pack) * sizeof(float);
   b->off_part = carve(part * sizeof(float), false);
@@ -370,7 +449,7 @@ int dnb_block_param_offset(const dnb_block* b, int layer, int which, size_t* off
     case DNB_P_W1: o += 2 * c; n = B * c; break;
     case DNB_P_G2: o += 2 * c + B * c; n = B; break;
     case DNB_P_B2: o += 2 * c + B * c + B; n = B; break;
-    default: o += 2 * c + B * c + 2 * B; n = k * B * 9; break;
+    default: o += 2 * c + B * c + 2 * B; n = k * (B ? B : c) * 9; break;
   }
   *offset = o;
   *count = n;
@@ -384,6 +463,8 @@ int dnb_block_forward(dnb_block* b, const void* x0v, const void* paramsv, void* 
   hipStream_t st = (hipStream_t)stream;
   const dnb_block_desc& d = b->d;
   if (d.dtype == DNB_BF16) return forward_bf16(b, x0v, (const float*)paramsv, yv, (char*)wsv, st);
+  if (d.bottleneck == 0)
+    return forward_plain3x3(b, (const float*)x0v, (const float*)paramsv, (float*)yv, (char*)wsv, st);
   const int n = d.n, m = d.layers, k = d.growth, B = d.bottleneck, hw = (int)b->hw;
   const float* x0 = (const float*)x0v;
   const float* params = (const float*)paramsv;
@@ -466,6 +547,9 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
   const dnb_block_desc& d = b->d;
   if (d.dtype == DNB_BF16)
     return backward_bf16(b, (const float*)paramsv, yv, dyv, dx0v, (float*)dparamsv, (char*)wsv, st);
+  if (d.bottleneck == 0)
+    return backward_plain3x3(b, (const float*)paramsv, (const float*)yv, (const float*)dyv, (float*)dx0v,
+                             (float*)dparamsv, (char*)wsv, st);
   const int n = d.n, m = d.layers, k = d.growth, B = d.bottleneck, hw = (int)b->hw;
   const bool recompute = d.schedule == DNB_SCHED_SHARED;
   const bool fused = d.schedule == DNB_SCHED_FUSED;

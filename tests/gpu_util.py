@@ -70,7 +70,7 @@ def run_block_gpu(dnb, cfg, x0, layer_params, dy, schedule=0, poison=True, concu
         out = {"y": y.cpu().numpy(), "dx0": dx0.cpu().numpy(), "dparams": dparams.cpu().numpy(),
                "mem": dnb.dnb_block_memory_breakdown(h), "peak": dnb.dnb_block_peak_bytes(h)}
         out["slices"] = {(l, name): slice(*(lambda o, c: (o, o + c))(*dnb.dnb_block_param_offset(h, l, NAMES.index(name))))
-                         for l in range(1, cfg.layers + 1) for name in NAMES}
+                         for l in range(1, cfg.layers + 1) for name in NAMES if name in layer_params[0]}
         return out
     finally:
         dnb.dnb_block_destroy(h)
@@ -81,5 +81,5 @@ def run_block_oracle(orc, cfg, x0, layer_params, dy, schedule="naive"):
     params = pack_params_oracle(orc, s, layer_params)
     res = orc.block(s, x0.astype(np.float64), params, dy.astype(np.float64), schedule=schedule)
     slices = {(l, name): orc.param_slice(s, l, NAMES.index(name))
-              for l in range(1, cfg.layers + 1) for name in NAMES}
+              for l in range(1, cfg.layers + 1) for name in NAMES if name in layer_params[0]}
     return res, slices

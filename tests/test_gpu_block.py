@@ -201,3 +201,40 @@ def test_full_size_benchmark_blocks_match_oracle(dnb, oracle, i):
         for name in NAMES:
             full_size_grad_close(gpu["dparams"][gpu["slices"][(l, name)]], ores.dparams[osl[(l, name)]], f"layer {l} d{name}")
     assert gpu["peak"] == ores.peak_elems * 4 - (2 * cfg.c_in(cfg.layers) + cfg.bottleneck) * cfg.pixels * 4
+
+
+# ------------------------------------------------------------------ layers without a bottleneck
+
+NOBOTTLE = [
+    wl.BlockCfg(2, 8, 8, 8, 3, 4, 0),
+    wl.BlockCfg(3, 5, 5, 7, 4, 3, 0),          # nothing a multiple of 4
+    wl.BlockCfg(2, 24, 16, 16, 4, 12, 0),      # k = 12 on a wide concatenation
+    wl.BlockCfg(1, 3, 1, 1, 2, 2, 0),          # one pixel
+]
+
+
+@pytest.mark.parametrize("cfg", NOBOTTLE, ids=lambda c: f"n{c.n}c{c.c0}h{c.h}w{c.w}m{c.layers}k{c.growth}B0")
+def test_block_without_bottleneck_matches_oracle(dnb, oracle, cfg):
+    """BN -> ReLU -> 3x3 conv directly on the concatenation (bottleneck = 0): both materialised
+    schedules against the oracle, bit-identical to each other, byte counts as the oracle allocates."""
+    x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
+    ores, osl = run_block_oracle(oracle, cfg, x0, lp, dy)
+    names = [nm for nm in NAMES if nm in lp[0]]
+    outs = []
+    for schedule, oname in ((0, "shared"), (1, "naive")):
+        gpu = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=schedule)
+        assert_close(gpu["y"], ores.y, TOL, "y")
+        assert_close(gpu["dx0"], ores.dx0, TOL, "dx0")
+        for l in range(1, cfg.layers + 1):
+            for name in names:
+                a, r = gpu["dparams"][gpu["slices"][(l, name)]], ores.dparams[osl[(l, name)]]
+                if cfg.pixels == 1:
+                    # one pixel: the variance is 0, xhat is rounding noise amplified by 1/sqrt(eps)
+                    assert np.all(np.abs(a - r) <= 1e-4 * max(1.0, np.abs(r).max())), (l, name)
+                    continue
+                assert_close(a, r, TOL, f"layer {l} d{name}")
+        s = oracle.BlockShape(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, 0, cfg.eps)
+        assert gpu["peak"] == oracle.block(s, x0, np.zeros(oracle.param_count(s)), dy, schedule=oname).peak_elems * 4
+        outs.append(gpu)
+    for key in ("y", "dx0", "dparams"):
+        assert np.array_equal(outs[0][key], outs[1][key]), key

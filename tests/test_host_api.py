@@ -39,10 +39,11 @@ def test_status_strings(dnb):
 
 
 @pytest.mark.parametrize("kw,code", [
-    (dict(n=0), -1), (dict(c0=0), -1), (dict(layers=0), -1), (dict(growth=0), -1), (dict(bottleneck=0), -1),
+    (dict(n=0), -1), (dict(c0=0), -1), (dict(layers=0), -1), (dict(growth=0), -1), (dict(bottleneck=-1), -1),
     (dict(h=-1), -1), (dict(eps=-1.0), -1), (dict(dtype=7), -1), (dict(layout=3), -1), (dict(schedule=9), -1),
     (dict(dtype=1), -5), (dict(layout=1), -5), (dict(n=4096, h=512, w=512), -6),
-    (dict(schedule=2, h=7, w=7), -5), (dict(schedule=2, bottleneck=512), -5)])
+    (dict(schedule=2, h=7, w=7), -5), (dict(schedule=2, bottleneck=512), -5),
+    (dict(bottleneck=0, schedule=2), -5), (dict(bottleneck=0, dtype=1, layout=1, schedule=2), -5)])
 def test_descriptor_validation(dnb, kw, code):
     base = dict(n=2, c0=16, h=8, w=8, layers=4, growth=12, bottleneck=48)
     base.update(kw)
@@ -66,9 +67,10 @@ def sigma_c(cfg):
 
 
 CFGS = [wl.config1(), wl.BlockCfg(3, 5, 5, 7, 3, 4, 6), wl.BlockCfg(1, 7, 3, 3, 5, 3, 6)] + wl.config2() + wl.config3()
+NOBOTTLE = [wl.BlockCfg(2, 8, 8, 8, 3, 4, 0), wl.BlockCfg(3, 5, 5, 7, 4, 3, 0)]   # BN-ReLU-3x3 layers (bottleneck = 0)
 
 
-@pytest.mark.parametrize("cfg", CFGS, ids=lambda c: f"{c.n}x{c.c0}x{c.h}x{c.w}-m{c.layers}k{c.growth}")
+@pytest.mark.parametrize("cfg", CFGS + NOBOTTLE, ids=lambda c: f"{c.n}x{c.c0}x{c.h}x{c.w}-m{c.layers}k{c.growth}B{c.bottleneck}")
 def test_peak_bytes_formula(dnb, cfg):
     """Linear-memory formula (shared) and quadratic one (store-all), in bytes."""
     Ps, m, k, B = cfg.pixels * 4, cfg.layers, cfg.growth, cfg.bottleneck
@@ -109,7 +111,7 @@ def test_config1_bytes_as_stated(dnb):
     assert dnb.dnb_block_peak_bytes(h1) == 444416
 
 
-@pytest.mark.parametrize("cfg", CFGS[:3])
+@pytest.mark.parametrize("cfg", CFGS[:3] + NOBOTTLE)
 def test_peak_bytes_match_oracle_allocation_count(dnb, oracle, cfg):
     """The library's formula against the elements the oracle's two schedules actually
     allocate (counted by its allocator), times the element size."""
@@ -124,7 +126,7 @@ def test_peak_bytes_match_oracle_allocation_count(dnb, oracle, cfg):
         dnb.dnb_block_destroy(h)
 
 
-@pytest.mark.parametrize("cfg", CFGS[:3])
+@pytest.mark.parametrize("cfg", CFGS[:3] + NOBOTTLE)
 def test_param_offsets_match_oracle(dnb, oracle, cfg):
     s = oracle.BlockShape(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck, cfg.eps)
     h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck)
@@ -132,6 +134,9 @@ def test_param_offsets_match_oracle(dnb, oracle, cfg):
     for l in range(1, cfg.layers + 1):
         for which in range(6):
             off, cnt = dnb.dnb_block_param_offset(h, l, which)
+            if cfg.bottleneck == 0 and which in (2, 3, 4):   # W1, g2, b2 do not exist
+                assert cnt == 0
+                continue
             sl = oracle.param_slice(s, l, which)
             assert (off, off + cnt) == (sl.start, sl.stop)
     with pytest.raises(dnb.binding.DnbError):
