@@ -154,3 +154,22 @@ def test_memory_is_linear_in_depth_for_shared_schedule(dnb):
     d2 = lambda v: [v[i + 2] - 2 * v[i + 1] + v[i] for i in range(len(v) - 2)]
     assert all(x == 0 for x in d2(peaks[0]))
     assert all(x > 0 for x in d2(peaks[1]))
+
+
+def test_depth_sweep_closed_form_matches_library(dnb):
+    """The depth study's closed-form byte counts against the library's accounting, and the
+    quadratic / linear growth they are meant to show."""
+    import bench_depth_sweep as ds
+    sched = {"shared": 0, "store_all": 1, "fused": 2}
+    for L in (40, 100, 250):
+        blocks = wl.densenet_bc_blocks(L, 12, 64)
+        for name, code in sched.items():
+            total = 0
+            for c in blocks:
+                h = dnb.dnb_block_create(c.n, c.c0, c.h, c.w, c.layers, c.growth, c.bottleneck, schedule=code)
+                total += dnb.dnb_block_peak_bytes(h)
+                dnb.dnb_block_destroy(h)
+            assert total == ds.feature_map_bytes(blocks, name)
+    f = lambda L, s: ds.feature_map_bytes(wl.densenet_bc_blocks(L, 12, 64), s)
+    assert f(502, "store_all") / f(100, "store_all") > 15 > 6 > f(502, "shared") / f(100, "shared")
+    assert ds.deepest_that_fits(wl, "store_all", 12, 64) < ds.deepest_that_fits(wl, "shared", 12, 64) < ds.deepest_that_fits(wl, "fused", 12, 64)
