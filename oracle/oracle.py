@@ -16,6 +16,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "dnb_oracle.c")
+_SRC_NET = os.path.join(_HERE, "dnb_net_oracle.c")
 _LIB = os.path.join(_HERE, "libdnb_oracle.so")
 
 G1, B1, W1, G2, B2, W3 = range(6)
@@ -24,8 +25,9 @@ PARAM_NAMES = ("g1", "b1", "W1", "g2", "b2", "W3")
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (OpenMP, -O2).  Returns the library path."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-o", _LIB, _SRC, "-lm"]
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_NET))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-o", _LIB, _SRC, _SRC_NET, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -34,6 +36,11 @@ class _Desc(C.Structure):
     _fields_ = [("n", C.c_int32), ("c0", C.c_int32), ("h", C.c_int32), ("w", C.c_int32),
                 ("layers", C.c_int32), ("growth", C.c_int32), ("bottleneck", C.c_int32),
                 ("eps", C.c_double)]
+
+
+class _NetDesc(C.Structure):
+    _fields_ = [("n", C.c_int32), ("image", C.c_int32), ("depth", C.c_int32), ("growth", C.c_int32),
+                ("classes", C.c_int32), ("eps", C.c_double)]
 
 
 class _Mem(C.Structure):
@@ -76,6 +83,28 @@ def lib():
         _lib.dnbo_relu_backward.restype = None
         _lib.dnbo_relu_backward.argtypes = [_dp, _dp, _dp, i64]
         _lib.dnbo_num_threads.restype = C.c_int
+        # whole-network step (dnb_net_oracle.c)
+        nd = C.POINTER(_NetDesc)
+        _lib.dnbo_net_param_count.restype = C.c_int64
+        _lib.dnbo_net_param_count.argtypes = [nd]
+        _lib.dnbo_net_block_param_offset.restype = C.c_int64
+        _lib.dnbo_net_block_param_offset.argtypes = [nd, C.c_int]
+        _lib.dnbo_net_step.restype = C.c_double
+        _lib.dnbo_net_step.argtypes = [nd, _dp, C.POINTER(C.c_int32), _dp, _dp, _dp]
+        _lib.dnbo_avgpool2.restype = None
+        _lib.dnbo_avgpool2.argtypes = [_dp, i64, i64, i64, i64, _dp]
+        _lib.dnbo_avgpool2_backward.restype = None
+        _lib.dnbo_avgpool2_backward.argtypes = [_dp, i64, i64, i64, i64, _dp]
+        _lib.dnbo_global_avgpool.restype = None
+        _lib.dnbo_global_avgpool.argtypes = [_dp, i64, i64, i64, _dp]
+        _lib.dnbo_global_avgpool_backward.restype = None
+        _lib.dnbo_global_avgpool_backward.argtypes = [_dp, i64, i64, i64, _dp]
+        _lib.dnbo_linear.restype = None
+        _lib.dnbo_linear.argtypes = [_dp, _dp, _dp, i64, i64, i64, _dp]
+        _lib.dnbo_linear_backward.restype = None
+        _lib.dnbo_linear_backward.argtypes = [_dp, _dp, _dp, i64, i64, i64, _dp, _dp, _dp]
+        _lib.dnbo_softmax_xent.restype = C.c_double
+        _lib.dnbo_softmax_xent.argtypes = [_dp, C.POINTER(C.c_int32), i64, i64, _dp]
     return _lib
 
 
@@ -248,3 +277,128 @@ def relu_backward(a, da):
 
 def num_threads() -> int:
     return int(lib().dnbo_num_threads())
+
+
+# ---------------------------------------------------------------- whole network (dnb_net_oracle.c)
+
+@dataclass(frozen=True)
+class NetShape:
+    """CIFAR-shaped DenseNet-BC: stem to 2k, three dense blocks of (depth-4)/6 bottleneck layers,
+    transitions with compression 0.5, BN-ReLU-pool-linear tail."""
+    n: int
+    image: int
+    depth: int
+    growth: int
+    classes: int
+    eps: float = 1e-5
+
+    def _c(self) -> _NetDesc:
+        return _NetDesc(self.n, self.image, self.depth, self.growth, self.classes, self.eps)
+
+    def block(self, b: int) -> BlockShape:
+        per = (self.depth - 4) // 6
+        c, s = 2 * self.growth, self.image
+        for _ in range(b):
+            c = (c + per * self.growth) // 2
+            s //= 2
+        return BlockShape(self.n, c, s, s, per, self.growth, 4 * self.growth, self.eps)
+
+
+def net_param_count(s: NetShape) -> int:
+    d = s._c()
+    return int(lib().dnbo_net_param_count(C.byref(d)))
+
+
+def net_param_slices(s: NetShape) -> dict:
+    """Name -> slice of the network pack: 'stem', 'block0..2', 'trans0.g/b/W', 'trans1.*',
+    'tail.g/b/Wl/bl'."""
+    d = s._c()
+    out = {"stem": slice(0, 2 * s.growth * 27)}
+    for b in range(3):
+        bs = s.block(b)
+        o = int(lib().dnbo_net_block_param_offset(C.byref(d), b))
+        n = param_count(bs)
+        out[f"block{b}"] = slice(o, o + n)
+        c = bs.c_out
+        o += n
+        pre = f"trans{b}" if b < 2 else "tail"
+        out[pre + ".g"] = slice(o, o + c)
+        out[pre + ".b"] = slice(o + c, o + 2 * c)
+        if b < 2:
+            out[pre + ".W"] = slice(o + 2 * c, o + 2 * c + (c // 2) * c)
+        else:
+            out[pre + ".Wl"] = slice(o + 2 * c, o + 2 * c + s.classes * c)
+            out[pre + ".bl"] = slice(o + 2 * c + s.classes * c, o + 2 * c + s.classes * c + s.classes)
+    return out
+
+
+def net_step(s: NetShape, x, labels, params, backward: bool = True):
+    """One training step: returns (loss, dparams or None, logits)."""
+    d = s._c()
+    x = _f64(x).reshape(s.n, 3, s.image, s.image)
+    params = _f64(params).reshape(-1)
+    assert params.size == net_param_count(s)
+    lab = np.ascontiguousarray(np.asarray(labels, dtype=np.int32))
+    assert lab.shape == (s.n,) and lab.min() >= 0 and lab.max() < s.classes
+    logits = np.zeros((s.n, s.classes))
+    dparams = np.zeros_like(params) if backward else None
+    loss = lib().dnbo_net_step(C.byref(d), _p(x), lab.ctypes.data_as(C.POINTER(C.c_int32)), _p(params),
+                               _p(dparams) if backward else None, _p(logits))
+    return float(loss), dparams, logits
+
+
+def avgpool2(x):
+    x = _f64(x)
+    n, c, h, w = x.shape
+    out = np.zeros((n, c, h // 2, w // 2))
+    lib().dnbo_avgpool2(_p(x), n, c, h, w, _p(out))
+    return out
+
+
+def avgpool2_backward(dout, h, w):
+    dout = _f64(dout)
+    n, c = dout.shape[:2]
+    din = np.zeros((n, c, h, w))
+    lib().dnbo_avgpool2_backward(_p(dout), n, c, h, w, _p(din))
+    return din
+
+
+def global_avgpool(x):
+    x = _f64(x)
+    n, c, h, w = x.shape
+    out = np.zeros((n, c))
+    lib().dnbo_global_avgpool(_p(x), n, c, h * w, _p(out))
+    return out
+
+
+def global_avgpool_backward(dout, h, w):
+    dout = _f64(dout)
+    n, c = dout.shape
+    din = np.zeros((n, c, h, w))
+    lib().dnbo_global_avgpool_backward(_p(dout), n, c, h * w, _p(din))
+    return din
+
+
+def linear(f, wl, bl):
+    f, wl, bl = _f64(f), _f64(wl), _f64(bl)
+    n, c = f.shape
+    out = np.zeros((n, wl.shape[0]))
+    lib().dnbo_linear(_p(f), _p(wl), _p(bl), n, c, wl.shape[0], _p(out))
+    return out
+
+
+def linear_backward(f, wl, dlogits):
+    f, wl, dlogits = _f64(f), _f64(wl), _f64(dlogits)
+    n, c = f.shape
+    df, dwl, dbl = np.zeros_like(f), np.zeros_like(wl), np.zeros(wl.shape[0])
+    lib().dnbo_linear_backward(_p(f), _p(wl), _p(dlogits), n, c, wl.shape[0], _p(df), _p(dwl), _p(dbl))
+    return df, dwl, dbl
+
+
+def softmax_xent(logits, labels):
+    logits = _f64(logits)
+    n, classes = logits.shape
+    lab = np.ascontiguousarray(np.asarray(labels, dtype=np.int32))
+    d = np.zeros_like(logits)
+    loss = lib().dnbo_softmax_xent(_p(logits), lab.ctypes.data_as(C.POINTER(C.c_int32)), n, classes, _p(d))
+    return float(loss), d

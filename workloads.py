@@ -137,3 +137,65 @@ def config4(batch: int = 32) -> List[BlockCfg]:
 def config5(batch: int = 32) -> List[BlockCfg]:
     """DenseNet-264-shaped (k=32, blocks 6-12-64-48, stem 64), batch 32."""
     return imagenet_blocks((6, 12, 64, 48), 32, 64, batch)
+
+
+# --------------------------------------------------------------- whole CIFAR-shaped networks
+
+@dataclass(frozen=True)
+class NetCfg:
+    """DenseNet-BC on square 3-channel images: stem to 2k channels, three dense blocks of
+    (depth-4)/6 bottleneck layers (B = 4k), transitions with compression 0.5, linear head."""
+    n: int
+    image: int
+    depth: int
+    growth: int
+    classes: int
+    eps: float = 1e-5
+
+    def blocks(self) -> List[BlockCfg]:
+        return [BlockCfg(b.n, b.c0, b.h, b.w, b.layers, b.growth, b.bottleneck, self.eps)
+                for b in densenet_bc_blocks(self.depth, self.growth, self.n, self.image)]
+
+
+def make_net_inputs(cfg: NetCfg, seed_x: int = 0, seed_w: int = 1, seed_t: int = 2, affine: str = "ones"):
+    """Returns (x, labels, params): x (n,3,image,image) float32 ~ N(0,1); labels int32 uniform in
+    [0, classes); params a dict: 'stem' (2k,3,3,3); 'block0..2' lists of per-layer dicts as in
+    make_block_inputs; 'trans0', 'trans1' dicts g, b, W (C/2, C); 'tail' dict g, b, Wl
+    (classes, C), bl (zeros).  Conv and linear weights He-normal, BN affine as in
+    make_block_inputs."""
+    rx = np.random.default_rng(seed_x)
+    rw = np.random.default_rng(seed_w)
+    rt = np.random.default_rng(seed_t)
+    x = rx.standard_normal((cfg.n, 3, cfg.image, cfg.image)).astype(np.float32)
+    labels = rt.integers(0, cfg.classes, size=cfg.n).astype(np.int32)
+
+    def he(shape):
+        return (rw.standard_normal(shape) * np.sqrt(2.0 / int(np.prod(shape[1:])))).astype(np.float32)
+
+    def gam(c):
+        return (1.0 + 0.25 * rw.standard_normal(c)).astype(np.float32) if affine == "random" else np.ones(c, np.float32)
+
+    def bet(c):
+        return (0.25 * rw.standard_normal(c)).astype(np.float32) if affine == "random" else np.zeros(c, np.float32)
+
+    params = {"stem": he((2 * cfg.growth, 3, 3, 3))}
+    for b, bc in enumerate(cfg.blocks()):
+        _, layers, _ = make_block_inputs(bc, seed_x + 100 + b, seed_w + 100 + b, seed_t + 100 + b, affine)
+        params[f"block{b}"] = layers
+        c = bc.c_out
+        if b < 2:
+            params[f"trans{b}"] = {"g": gam(c), "b": bet(c), "W": he((c // 2, c))}
+        else:
+            params["tail"] = {"g": gam(c), "b": bet(c), "Wl": he((cfg.classes, c)),
+                              "bl": np.zeros(cfg.classes, np.float32)}
+    return x, labels, params
+
+
+def net_config2(batch: int = 64) -> NetCfg:
+    """DenseNet-BC L=100 k=12, 32x32 inputs, 10 classes."""
+    return NetCfg(batch, 32, 100, 12, 10)
+
+
+def net_config3(batch: int = 64) -> NetCfg:
+    """DenseNet-BC L=250 k=24, 32x32 inputs, 100 classes."""
+    return NetCfg(batch, 32, 250, 24, 100)
