@@ -1,13 +1,15 @@
 #!/usr/bin/env python3
-"""Benchmark of the dense-block hot path on one MI355X.
+"""Benchmark of the memory-efficient DenseNet training step on one MI355X.
 
-A step = forward + backward of every dense block of the workload (default: the three
-dense blocks of DenseNet-BC L=100, k=12, batch 64, fp32 -- benchmark configs[1]) through
-the C ABI, inputs resident in HBM.  Prints ONE JSON line with training images/s of the fastest
-linear-memory schedule (fused), the rates of the paper-literal shared-storage schedule and of
-the store-everything schedule (recompute overhead), exact peak feature-map bytes, the roofline
-of the dominant kernel measured live with events on the launch stream, and the CPU oracle timed
-on the host cores.
+A step = forward + backward of the workload through the C ABI, inputs resident in HBM.  Default
+workload: DenseNet-BC L=100, k=12, batch 64, fp32 (benchmark configs[1]) as a whole network --
+stem conv, three dense blocks of 16 bottleneck layers, two transitions, BN-ReLU-pool-linear head
+and mean softmax cross-entropy (no optimiser update: the metric is forward + backward).  Prints
+ONE JSON line with training images/s of the fastest linear-memory schedule (fused), the same
+workload's dense blocks alone, the rates of the paper-literal shared-storage schedule and of the
+store-everything schedule (recompute overhead), exact peak feature-map bytes, the roofline of the
+dominant kernel measured live with events on the launch stream, and the CPU oracle timed on the
+host cores.
 """
 from __future__ import annotations
 
@@ -33,6 +35,9 @@ def parse():
     ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config4", "config5"],
                     help="config2 is the metric's workload; config4/5 are the bf16 NHWC ImageNet-shaped block sets (diagnostic)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
+    ap.add_argument("--scope", default="auto", choices=["auto", "net", "blocks"],
+                    help="net: the whole training step (stem, dense blocks, transitions, head, loss; configs 2-3); "
+                         "blocks: the dense blocks alone; auto = net where it is built")
     ap.add_argument("--schedule", default="fused", choices=["shared", "store_all", "fused"],
                     help="fused: BN+ReLU recomputed inside the conv operand loads (default, fastest linear-memory schedule); "
                          "shared: storage 1/2/3 materialised as in the paper; store_all: every intermediate kept")
@@ -83,6 +88,51 @@ class BlockRun:
         self.dx0 = torch.empty_like(self.x0)
         self.ws = torch.empty(dnb.dnb_block_workspace_bytes(self.h), dtype=torch.uint8, device="cuda")
         self.mem = dnb.dnb_block_memory_breakdown(self.h)
+
+
+class NetRun:
+    """Device buffers + handle of one whole network."""
+
+    def __init__(self, dnb, torch, wl, ncfg, schedule):
+        import numpy as np
+        from gpu_util import dev
+        self.cfg = ncfg
+        self.h = dnb.dnb_net_create(ncfg.n, ncfg.image, ncfg.depth, ncfg.growth, ncfg.classes, schedule=schedule,
+                                    eps=ncfg.eps)
+        x, labels, params = wl.make_net_inputs(ncfg)
+        flat = np.zeros(dnb.dnb_net_param_count(self.h), dtype=np.float32)
+
+        def put(part, arr):
+            off, cnt = dnb.dnb_net_param_offset(self.h, part)
+            assert cnt == arr.size
+            flat[off:off + cnt] = np.asarray(arr, dtype=np.float32).ravel()
+
+        put(dnb.DNB_NP_STEM, params["stem"])
+        for b, bc in enumerate(ncfg.blocks()):
+            hb = dnb.dnb_block_create(bc.n, bc.c0, bc.h, bc.w, bc.layers, bc.growth, bc.bottleneck, eps=bc.eps)
+            from gpu_util import pack_params_gpu
+            put(dnb.DNB_NP_BLOCK0 + b, pack_params_gpu(dnb, hb, params[f"block{b}"]))
+            dnb.dnb_block_destroy(hb)
+        for b in (0, 1):
+            for i, name in enumerate(("g", "b", "W")):
+                put(dnb.DNB_NP_TRANS0_G + 3 * b + i, params[f"trans{b}"][name])
+        for i, name in enumerate(("g", "b", "Wl", "bl")):
+            put(dnb.DNB_NP_TAIL_G + i, params["tail"][name])
+        self.x, self.labels = dev(x), torch.from_numpy(labels).to("cuda")
+        self.params = dev(flat)
+        self.dparams = torch.empty_like(self.params)
+        self.loss = torch.zeros(1, device="cuda")
+        self.ws = torch.empty(dnb.dnb_net_workspace_bytes(self.h), dtype=torch.uint8, device="cuda")
+        self.peak = dnb.dnb_net_peak_bytes(self.h)
+        self.workspace = dnb.dnb_net_workspace_bytes(self.h)
+
+
+def make_net_step(dnb, r, forward_only=False):
+    def step():
+        dnb.dnb_net_forward(r.h, r.x, r.labels, r.params, r.loss, None, r.ws)
+        if not forward_only:
+            dnb.dnb_net_backward(r.h, r.x, r.params, r.dparams, r.ws)
+    return step
 
 
 def make_step(dnb, runs, forward_only=False):
@@ -213,6 +263,27 @@ def cpu_baseline(wl, blocks):
                       f"(float64, store-everything schedule, fwd+bwd), {t:.1f} s"}
 
 
+def cpu_baseline_net(wl, ncfg):
+    """The oracle's whole training step on the host cores, on a bounded number of images of the
+    same network (its cost per image does not depend on the batch)."""
+    from oracle import oracle as orc
+    from test_oracle_net import pack_net
+    sample = min(ncfg.n, 16)
+    cs = wl.NetCfg(sample, ncfg.image, ncfg.depth, ncfg.growth, ncfg.classes, ncfg.eps)
+    x, labels, params = wl.make_net_inputs(cs)
+    s = orc.NetShape(cs.n, cs.image, cs.depth, cs.growth, cs.classes, cs.eps)
+    flat = pack_net(orc, s, params)
+    t, passes = 0.0, 0
+    while t < 10.0 and passes < 20:
+        t0 = time.perf_counter()
+        orc.net_step(s, x, labels, flat)
+        t += time.perf_counter() - t0
+        passes += 1
+    return {"value": round(sample * passes / t, 3), "unit": "images/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"{passes} training step(s) of {sample} of {ncfg.n} images through the same network "
+                      f"(float64, store-everything schedule, fwd+bwd), {t:.1f} s"}
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -246,7 +317,28 @@ def main():
         secs = time_steps(torch, make_step(dnb, runs, a.forward_only), a.steps, a.warmup, use_graph)
         return runs, secs
 
-    runs, secs = measure(a.schedule)
+    net_scope = a.scope == "net" or (a.scope == "auto" and a.workload in ("config2", "config3") and a.only_block < 0)
+    if net_scope and a.workload not in ("config2", "config3"):
+        print("bench.py: the whole-network step is built for the CIFAR-shaped fp32 networks (config2, config3)", file=sys.stderr)
+        sys.exit(2)
+    ncfg = None
+    if net_scope:
+        ncfg = wl.net_config2(batch) if a.workload == "config2" else wl.net_config3(batch)
+        wname = wname.replace("3 dense blocks", "whole network: stem, 3 dense blocks").replace(
+            "layers (fwd+bwd)", "layers, 2 transitions, head, softmax cross-entropy (fwd+bwd)")
+
+    def measure_net(schedule):
+        r = NetRun(dnb, torch, wl, ncfg, sched[schedule])
+        if a.serial:
+            dnb.dnb_net_set_concurrency(r.h, False)
+        secs = time_steps(torch, make_net_step(dnb, r, a.forward_only), a.steps, a.warmup, use_graph)
+        return r, secs
+
+    runs, secs = measure(a.schedule)   # dense blocks alone (also feeds the roofline measurement)
+    block_secs = secs
+    netrun = None
+    if net_scope:
+        netrun, secs = measure_net(a.schedule)
     value = batch * a.steps / secs
     out = {
         "metric": "train images/sec per MI355X (fwd+bwd) + peak feature-map bytes vs depth",
@@ -259,6 +351,14 @@ def main():
                                    "total": sum(r.mem["peak_bytes"] for r in runs),
                                    "workspace_total": sum(r.mem["workspace_bytes"] for r in runs)},
     }
+    if net_scope:
+        out["dense_blocks_only"] = {"images_per_s": round(batch * a.steps / block_secs, 2),
+                                    "ms_per_step": round(1e3 * block_secs / a.steps, 4)}
+        out["peak_feature_map_bytes"]["network_total"] = netrun.peak
+        out["peak_feature_map_bytes"]["network_workspace"] = netrun.workspace
+        dnb.dnb_net_destroy(netrun.h)
+        del netrun
+        torch.cuda.empty_cache()
     # the roofline entry is that of the fp32 path's dominant kernel; the bf16 block sets are diagnostic
     out["roofline"] = None if bf16 else dominant_kernel_roofline(dnb, torch, runs, f"{a.workload}:{batch}" if a.only_block < 0 else "")
     del runs
@@ -270,16 +370,28 @@ def main():
         for other in ("shared", "store_all", "fused"):
             if other in t:
                 continue
-            oruns, osecs = measure(other)
+            if net_scope:
+                onet, osecs = measure_net(other)
+                out["peak_feature_map_bytes"][other + "_network_total"] = onet.peak
+                dnb.dnb_net_destroy(onet.h)
+                del onet
+                # the blocks' own exact accounting under this schedule
+                hs = [dnb.dnb_block_create(c.n, c.c0, c.h, c.w, c.layers, c.growth, c.bottleneck, schedule=sched[other])
+                      for c in blocks]
+                out["peak_feature_map_bytes"][other + "_total"] = sum(dnb.dnb_block_peak_bytes(h) for h in hs)
+                for h in hs:
+                    dnb.dnb_block_destroy(h)
+            else:
+                oruns, osecs = measure(other)
+                out["peak_feature_map_bytes"][other + "_total"] = sum(r.mem["peak_bytes"] for r in oruns)
+                del oruns
             t[other] = osecs
             out[other + "_images_per_s"] = round(batch * a.steps / osecs, 2)
-            out["peak_feature_map_bytes"][other + "_total"] = sum(r.mem["peak_bytes"] for r in oruns)
-            del oruns
             torch.cuda.empty_cache()
         out["recompute_overhead"] = round(t["shared"] / t["store_all"] - 1.0, 4)
         out["fused_vs_store_all_time"] = round(t["fused"] / t["store_all"] - 1.0, 4)
     if not a.no_cpu_baseline and not bf16:
-        out["cpu_baseline"] = cpu_baseline(wl, blocks)
+        out["cpu_baseline"] = cpu_baseline_net(wl, ncfg) if net_scope else cpu_baseline(wl, blocks)
     print(json.dumps(out), flush=True)
 
 

@@ -15,7 +15,8 @@
  * Conventions
  *   - Every pointer named x0, params, y, dy, dx0, dparams, workspace is a DEVICE
  *     pointer owned by the caller (e.g. torch.empty(...).data_ptr()), at least
- *     16-byte aligned.  The library never allocates or frees device memory.
+ *     16-byte aligned (params and dparams: 4-byte).  The library never allocates or
+ *     frees device memory.
  *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  Calls
  *     enqueue kernels on it and return without synchronising.  Calls that share
  *     a workspace must be ordered on one stream: the shared buffers are
@@ -216,6 +217,50 @@ int dnb_op_nhwc_bn_relu_backward(const void* x, int64_t x_ld, const void* dact, 
                                  int64_t du_ld, void* du_accum_f32, int64_t acc_ld, int64_t pixels, int64_t c,
                                  const void* gamma, const void* beta, const void* mean, const void* istd,
                                  void* dgamma, void* dbeta, void* scratch, void* stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Whole training step of a CIFAR-shaped DenseNet-BC (fp32, NCHW): the dense blocks above joined
+ * by the network's glue (paper Section 2, "DenseNet Architecture": dense blocks connected by
+ * transition layers; Section 5 measures such networks).
+ *   stem      3x3 conv, pad 1, 3 -> 2k channels, no bias
+ *   3 x       dense block of (depth-4)/6 bottleneck layers (B = 4k), run under `schedule`
+ *   between   transition: BN -> ReLU -> 1x1 conv (C -> C/2) -> 2x2 average pool, stride 2
+ *   tail      BN -> ReLU -> global average pool -> linear (+bias) to `classes`
+ *   loss      mean over the batch of the softmax cross-entropy
+ * BN uses batch statistics as in the blocks.  Parameter pack (fp32; gradients same layout):
+ *   stem W[2k][3][3][3] | block0 | trans0: g[C] b[C] W[C/2][C] | block1 | trans1 | block2 |
+ *   tail: g[C] b[C] Wl[classes][C] bl[classes]
+ * (query the offsets).  x is (n, 3, image, image) fp32, labels n int32 in [0, classes): device
+ * pointers.  loss (1 float) and logits (n*classes floats, may be NULL) are device pointers too.
+ * dnb_net_backward needs the preceding dnb_net_forward on the same workspace and overwrites
+ * dparams.  Errors and ownership as for the block calls. */
+typedef struct dnb_net dnb_net;
+typedef struct {
+  int32_t n, image;   /* batch; input height = width, a multiple of 4 */
+  int32_t depth;      /* L = 6*layers_per_block + 4 */
+  int32_t growth;     /* k */
+  int32_t classes;
+  int32_t schedule;   /* DNB_SCHED_* of the dense blocks */
+  float eps;
+} dnb_net_desc;
+/* parts of the network pack for dnb_net_param_offset */
+enum { DNB_NP_STEM = 0, DNB_NP_BLOCK0 = 1, DNB_NP_BLOCK1 = 2, DNB_NP_BLOCK2 = 3,
+       DNB_NP_TRANS0_G = 4, DNB_NP_TRANS0_B = 5, DNB_NP_TRANS0_W = 6,
+       DNB_NP_TRANS1_G = 7, DNB_NP_TRANS1_B = 8, DNB_NP_TRANS1_W = 9,
+       DNB_NP_TAIL_G = 10, DNB_NP_TAIL_B = 11, DNB_NP_TAIL_WL = 12, DNB_NP_TAIL_BL = 13 };
+
+int dnb_net_create(const dnb_net_desc* desc, dnb_net** out);
+void dnb_net_destroy(dnb_net* net);
+size_t dnb_net_param_count(const dnb_net* net);      /* floats in params / dparams */
+int dnb_net_param_offset(const dnb_net* net, int part /*DNB_NP_* */, size_t* offset, size_t* count);
+size_t dnb_net_workspace_bytes(const dnb_net* net);  /* bytes the caller allocates */
+/* feature-map bytes of the whole step: the blocks' exact accounting plus the glue's feature maps */
+size_t dnb_net_peak_bytes(const dnb_net* net);
+int dnb_net_set_concurrency(dnb_net* net, int enable); /* helper streams in the blocks' backward */
+int dnb_net_forward(dnb_net* net, const void* x, const int32_t* labels, const void* params, float* loss,
+                    float* logits, void* workspace, void* stream);
+int dnb_net_backward(dnb_net* net, const void* x, const void* params, void* dparams, void* workspace,
+                     void* stream);
 
 #ifdef __cplusplus
 }

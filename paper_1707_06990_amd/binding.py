@@ -16,6 +16,9 @@ DNB_F32, DNB_BF16 = 0, 1
 DNB_NCHW, DNB_NHWC = 0, 1
 DNB_SCHED_SHARED, DNB_SCHED_STORE_ALL, DNB_SCHED_FUSED = 0, 1, 2
 DNB_P_G1, DNB_P_B1, DNB_P_W1, DNB_P_G2, DNB_P_B2, DNB_P_W3 = range(6)
+(DNB_NP_STEM, DNB_NP_BLOCK0, DNB_NP_BLOCK1, DNB_NP_BLOCK2, DNB_NP_TRANS0_G, DNB_NP_TRANS0_B, DNB_NP_TRANS0_W,
+ DNB_NP_TRANS1_G, DNB_NP_TRANS1_B, DNB_NP_TRANS1_W, DNB_NP_TAIL_G, DNB_NP_TAIL_B, DNB_NP_TAIL_WL,
+ DNB_NP_TAIL_BL) = range(14)
 
 
 class dnb_block_desc(C.Structure):
@@ -23,6 +26,11 @@ class dnb_block_desc(C.Structure):
                 ("layers", C.c_int32), ("growth", C.c_int32), ("bottleneck", C.c_int32),
                 ("dtype", C.c_int32), ("layout", C.c_int32), ("schedule", C.c_int32),
                 ("eps", C.c_float)]
+
+
+class dnb_net_desc(C.Structure):
+    _fields_ = [("n", C.c_int32), ("image", C.c_int32), ("depth", C.c_int32), ("growth", C.c_int32),
+                ("classes", C.c_int32), ("schedule", C.c_int32), ("eps", C.c_float)]
 
 
 class dnb_block_memory(C.Structure):
@@ -71,6 +79,15 @@ _SIGS = {
     "dnb_op_nhwc_conv_wgrad": (C.c_int, [_vp, _i64, _vp, _i64, C.c_int, _vp, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
     "dnb_op_nhwc_bn_relu_backward": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64,
                                                _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "dnb_net_create": (C.c_int, [C.POINTER(dnb_net_desc), C.POINTER(_vp)]),
+    "dnb_net_destroy": (None, [_vp]),
+    "dnb_net_param_count": (_sz, [_vp]),
+    "dnb_net_param_offset": (C.c_int, [_vp, C.c_int, C.POINTER(_sz), C.POINTER(_sz)]),
+    "dnb_net_workspace_bytes": (_sz, [_vp]),
+    "dnb_net_peak_bytes": (_sz, [_vp]),
+    "dnb_net_set_concurrency": (C.c_int, [_vp, C.c_int]),
+    "dnb_net_forward": (C.c_int, [_vp] * 8),
+    "dnb_net_backward": (C.c_int, [_vp] * 6),
 }
 for _name, (_res, _args) in _SIGS.items():
     _f = getattr(_lib, _name)
@@ -248,3 +265,47 @@ def dnb_op_nhwc_bn_relu_backward(x, x_ld, dact, dact_ld, du_bf16, du_ld, du_accu
                                              _ptr(du_accum_f32), acc_ld, pixels, c, _ptr(gamma), _ptr(beta),
                                              _ptr(mean), _ptr(istd), _ptr(dgamma), _ptr(dbeta), _ptr(scratch),
                                              _stream(stream)))
+
+
+# ---------------------------------------------------------------- whole network step
+
+def dnb_net_create(n, image, depth, growth, classes, schedule=DNB_SCHED_FUSED, eps=1e-5):
+    desc = dnb_net_desc(n, image, depth, growth, classes, schedule, eps)
+    out = _vp()
+    _check(_lib.dnb_net_create(C.byref(desc), C.byref(out)))
+    return out
+
+
+def dnb_net_destroy(net) -> None:
+    _lib.dnb_net_destroy(net)
+
+
+def dnb_net_param_count(net) -> int:
+    return int(_lib.dnb_net_param_count(net))
+
+
+def dnb_net_param_offset(net, part: int):
+    off, cnt = _sz(), _sz()
+    _check(_lib.dnb_net_param_offset(net, part, C.byref(off), C.byref(cnt)))
+    return int(off.value), int(cnt.value)
+
+
+def dnb_net_workspace_bytes(net) -> int:
+    return int(_lib.dnb_net_workspace_bytes(net))
+
+
+def dnb_net_peak_bytes(net) -> int:
+    return int(_lib.dnb_net_peak_bytes(net))
+
+
+def dnb_net_set_concurrency(net, enable: bool) -> None:
+    _check(_lib.dnb_net_set_concurrency(net, 1 if enable else 0))
+
+
+def dnb_net_forward(net, x, labels, params, loss, logits, workspace, stream=None) -> None:
+    _check(_lib.dnb_net_forward(net, _ptr(x), _ptr(labels), _ptr(params), _ptr(loss), _ptr(logits),
+                                _ptr(workspace), _stream(stream)))
+
+
+def dnb_net_backward(net, x, params, dparams, workspace, stream=None) -> None:
+    _check(_lib.dnb_net_backward(net, _ptr(x), _ptr(params), _ptr(dparams), _ptr(workspace), _stream(stream)))

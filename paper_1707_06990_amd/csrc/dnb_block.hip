@@ -51,6 +51,9 @@ size_t layer_params(const dnb_block_desc& d, int l) {
 }
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+// parameter packs are read and written with scalar accesses only (layer offsets inside a pack
+// are not multiples of 16 bytes anyway): float alignment is enough
+inline bool misaligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3u) != 0; }
 
 #define DNB_TRY(expr)                                 \
   do {                                                \
@@ -459,7 +462,7 @@ int dnb_block_param_offset(const dnb_block* b, int layer, int which, size_t* off
 int dnb_block_forward(dnb_block* b, const void* x0v, const void* paramsv, void* yv, void* wsv,
                       void* stream) {
   if (!b || !x0v || !paramsv || !yv || !wsv) return DNB_E_NULL;
-  if (misaligned(x0v) || misaligned(paramsv) || misaligned(yv) || misaligned(wsv)) return DNB_E_ALIGN;
+  if (misaligned(x0v) || misaligned4(paramsv) || misaligned(yv) || misaligned(wsv)) return DNB_E_ALIGN;
   hipStream_t st = (hipStream_t)stream;
   const dnb_block_desc& d = b->d;
   if (d.dtype == DNB_BF16) return forward_bf16(b, x0v, (const float*)paramsv, yv, (char*)wsv, st);
@@ -540,8 +543,8 @@ int dnb_block_forward(dnb_block* b, const void* x0v, const void* paramsv, void* 
 int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const void* dyv,
                        void* dx0v, void* dparamsv, void* wsv, void* stream) {
   if (!b || !paramsv || !yv || !dyv || !dx0v || !dparamsv || !wsv) return DNB_E_NULL;
-  if (misaligned(paramsv) || misaligned(yv) || misaligned(dyv) || misaligned(dx0v) ||
-      misaligned(dparamsv) || misaligned(wsv))
+  if (misaligned4(paramsv) || misaligned(yv) || misaligned(dyv) || misaligned(dx0v) ||
+      misaligned4(dparamsv) || misaligned(wsv))
     return DNB_E_ALIGN;
   hipStream_t st = (hipStream_t)stream;
   const dnb_block_desc& d = b->d;

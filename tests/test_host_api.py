@@ -173,3 +173,40 @@ def test_depth_sweep_closed_form_matches_library(dnb):
     f = lambda L, s: ds.feature_map_bytes(wl.densenet_bc_blocks(L, 12, 64), s)
     assert f(502, "store_all") / f(100, "store_all") > 15 > 6 > f(502, "shared") / f(100, "shared")
     assert ds.deepest_that_fits(wl, "store_all", 12, 64) < ds.deepest_that_fits(wl, "shared", 12, 64) < ds.deepest_that_fits(wl, "fused", 12, 64)
+
+
+# ------------------------------------------------------------------ whole-network entry points
+
+NET_PARTS = {"stem": 0, "block0": 1, "block1": 2, "block2": 3, "trans0.g": 4, "trans0.b": 5, "trans0.W": 6,
+             "trans1.g": 7, "trans1.b": 8, "trans1.W": 9, "tail.g": 10, "tail.b": 11, "tail.Wl": 12, "tail.bl": 13}
+
+
+@pytest.mark.parametrize("cfg", [wl.NetCfg(2, 8, 16, 4, 5), wl.net_config2(), wl.net_config3()],
+                         ids=["tiny", "bc100", "bc250"])
+def test_net_param_layout_matches_oracle(dnb, oracle, cfg):
+    s = oracle.NetShape(cfg.n, cfg.image, cfg.depth, cfg.growth, cfg.classes, cfg.eps)
+    fusable = all(b.w % 4 == 0 for b in cfg.blocks())
+    net = dnb.dnb_net_create(cfg.n, cfg.image, cfg.depth, cfg.growth, cfg.classes, schedule=2 if fusable else 0)
+    assert dnb.dnb_net_param_count(net) == oracle.net_param_count(s)
+    for name, sl in oracle.net_param_slices(s).items():
+        off, cnt = dnb.dnb_net_param_offset(net, NET_PARTS[name])
+        assert (off, off + cnt) == (sl.start, sl.stop), name
+    with pytest.raises(dnb.binding.DnbError):
+        dnb.dnb_net_param_offset(net, 14)
+    blocks = cfg.blocks()
+    glue = sum((b.c0 + 2 * b.c_out) * b.pixels * 4 for b in blocks)           # block inputs, outputs, BN+ReLU of outputs
+    glue += 2 * (blocks[0].c_out // 2) * blocks[0].pixels * 4                    # transition conv output and its gradient
+    glue += 2 * max(b.c_out * b.pixels for b in blocks) * 4 + blocks[0].c0 * blocks[0].pixels * 4  # gradient buffers
+    inner = sum((b.layers * b.bottleneck + b.c_out + b.c_in(b.layers) + b.bottleneck
+                 + (0 if fusable else 2 * b.c_in(b.layers) + b.bottleneck)) * b.pixels * 4 for b in blocks)
+    assert dnb.dnb_net_peak_bytes(net) == glue + inner <= dnb.dnb_net_workspace_bytes(net)
+    dnb.dnb_net_destroy(net)
+
+
+@pytest.mark.parametrize("kw", [dict(n=0), dict(depth=17), dict(depth=4), dict(image=10), dict(classes=0), dict(growth=0)])
+def test_net_descriptor_validation(dnb, kw):
+    base = dict(n=2, image=8, depth=16, growth=4, classes=5)
+    base.update(kw)
+    with pytest.raises(dnb.binding.DnbError) as e:
+        dnb.dnb_net_create(**base)
+    assert e.value.status == dnb.DNB_E_BADDESC
