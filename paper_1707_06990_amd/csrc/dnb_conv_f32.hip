@@ -22,7 +22,7 @@ bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, f
                       const float2* fold, float* spart, int* sT, hipStream_t st);
 size_t conv_wgrad_fast_partial_floats(int n, int cin, int cout, int h, int w, int taps);
 bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
-                       float* partials, int n, int cin, int cout, int h, int w, int taps,
+                       float* partials, float* dw, int n, int cin, int cout, int h, int w, int taps,
                        const float2* fold, int* splits, hipStream_t st);
 
 namespace {
@@ -417,7 +417,7 @@ hipError_t launch_conv_wgrad(const float* in, int64_t in_stride, const float* g,
   if (cin <= 0 || cout <= 0) return hipSuccess;
   const int64_t count = (int64_t)cin * cout * taps;
   int splits = 0;
-  if (!launch_wgrad_fast(in, in_stride, g, g_stride, partials, n, cin, cout, h, w, taps, fold, &splits, st)) {
+  if (!launch_wgrad_fast(in, in_stride, g, g_stride, partials, dw, n, cin, cout, h, w, taps, fold, &splits, st)) {
     if (fold) return hipErrorInvalidValue;  // the generic kernel has no BN prologue
     const WgradPlan p = plan_wgrad(n, cin, cout, h, w, taps);
     if (p.lds > 64 * 1024) return hipErrorInvalidValue;
@@ -429,6 +429,7 @@ hipError_t launch_conv_wgrad(const float* in, int64_t in_stride, const float* g,
                          partials, cin, cout, h, w, p.cpi, p.total, p.cps, p.mtw, p.ctw, p.PA, p.PG);
     splits = p.splits;
   }
+  if (splits == 0) return hipGetLastError();  // the fast 3x3 path has already summed its partials
   return launch_sum_partials(partials, splits, count, dw, st);
 }
 

@@ -12,7 +12,8 @@
 #ifndef DNB_DBG
 #define DNB_DBG 0  // kernel ablation builds for tuning experiments (1x1: 1 no MFMA, 2/4 no activation / weight loads;
                    // 3x3: 8 no MFMA, 16/32 no activation / weight loads, 64 no statistics epilogue,
-                   // 128 no output stores, 256 no K-split reduction, 512 no LDS operand reads, 1024 no staging)
+                   // 128 no output stores, 256 no K-split reduction, 512 no LDS operand reads, 1024 no staging;
+                   // 3x3 wgrad: 2048 no wave reduction, 4096 no partial stores, 8192 no MFMA)
 #endif
 
 #include "dnb_internal.h"
@@ -474,7 +475,8 @@ __global__ __launch_bounds__(256) void k_conv3x3_v3(
   }
 }
 
-// Adds the accumulators of the waves of a workgroup into wave 0, in a fixed order.
+// Adds the accumulators of the waves of a workgroup into wave 0 as a chain 3 -> 2 -> 1 -> 0 through
+// one LDS region (NT * 256 floats).  (A two-region tree (0+2)+(1+3) was measured slower.)
 template <int NT>
 __device__ __forceinline__ void reduce_waves(f32x4 (&acc)[NT], float* buf, int wave, int lane, int nw) {
   for (int w = nw - 1; w >= 1; --w) {
@@ -592,21 +594,36 @@ __global__ __launch_bounds__(256) void k_wgrad3x3_fast(
   const float* ab = a + (int64_t)img * a_stride;
   const float* gb = gout + (int64_t)img * g_stride;
 
+  // The tile is staged progressively: first the columns the first 64-pixel step needs (its pixels
+  // plus the halo on both sides), then 64 more columns per step, loaded into registers before the
+  // MFMAs of the current step are issued and written to LDS after them, so the HBM latency of
+  // step ms+1's activations is covered by step ms's matrix work.
+  auto bnrelu = [&](float4 v, float2 f) {
+    v.x = fmaxf(__fmaf_rn(v.x, f.x, f.y), 0.f); v.y = fmaxf(__fmaf_rn(v.y, f.x, f.y), 0.f);
+    v.z = fmaxf(__fmaf_rn(v.z, f.x, f.y), 0.f); v.w = fmaxf(__fmaf_rn(v.w, f.x, f.y), 0.f);
+    return v;
+  };
+  const int seg0_4 = (64 + 2 * W + 8) >> 2;  // float4 columns of the first chunk
   for (int row = tid >> 4; row < CB; row += 16) {
     const int ch = c0 + row;
     const float* src = ab + (int64_t)ch * HW;
     float2 f = make_float2(1.f, 0.f);
     if (PRO && ch < cin) f = fold[ch];
-    for (int c4 = tid & 15; c4 < seg4; c4 += 16) {
+    for (int c4 = tid & 15; c4 < seg0_4; c4 += 16) {
       const int qq = origin + 4 * c4;
       const bool ok = ch < cin && qq >= 0 && qq < HW;
       float4 v = ok ? ldg4(src + qq) : zero4();
-      if (PRO && ok) {
-        v.x = fmaxf(__fmaf_rn(v.x, f.x, f.y), 0.f); v.y = fmaxf(__fmaf_rn(v.y, f.x, f.y), 0.f);
-        v.z = fmaxf(__fmaf_rn(v.z, f.x, f.y), 0.f); v.w = fmaxf(__fmaf_rn(v.w, f.x, f.y), 0.f);
-      }
+      if (PRO && ok) v = bnrelu(v, f);
       *reinterpret_cast<float4*>(&lds[row * PA + 4 * c4]) = v;
     }
+  }
+  // per-thread constants of the later chunks: thread (row group, float4 column) -> CTW rows
+  const int prow = tid >> 4, pc4 = tid & 15;
+  float2 pf[CTW];
+#pragma unroll
+  for (int u = 0; u < CTW; ++u) {
+    const int ch = c0 + u * 16 + prow;
+    pf[u] = (PRO && ch < cin) ? fold[ch] : make_float2(1.f, 0.f);
   }
   __syncthreads();
 
@@ -614,14 +631,39 @@ __global__ __launch_bounds__(256) void k_wgrad3x3_fast(
 #pragma unroll
   for (int t = 0; t < NT; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  for (int ms = 0; ms < nms; ++ms) {
-    const int pw = (wave * nms + ms) * 16 + 4 * kk, q = q0 + pw;
-    const bool ok = q < HW;
-    float4 A[MTW];
+  float4 An[MTW];  // gradient operand, one step ahead
+  {
+    const int q = q0 + wave * 16 + 4 * kk;
 #pragma unroll
     for (int x = 0; x < MTW; ++x) {
       const int m = m0 + x * 16 + r;
-      A[x] = (ok && m < cout) ? ldg4(gb + (int64_t)m * HW + q) : zero4();
+      An[x] = (q < HW && m < cout) ? ldg4(gb + (int64_t)m * HW + q) : zero4();
+    }
+  }
+  for (int ms = 0; ms < nms; ++ms) {
+    // request the next chunk: columns [64(ms+1) + 2W + 8, +64) of the tile
+    float4 nxt[CTW];
+    const bool more = ms + 1 < nms;
+    const int ncol = 64 * (ms + 1) + 2 * W + 8 + 4 * pc4;  // column of this thread's float4
+    const int nq = origin + ncol;
+    if (more) {
+#pragma unroll
+      for (int u = 0; u < CTW; ++u) {
+        const int ch = min(c0 + u * 16 + prow, cin - 1);
+        nxt[u] = ldg4(ab + (int64_t)ch * HW + min(max(nq, 0), HW - 4));
+      }
+    }
+    const int pw = (ms * 4 + wave) * 16 + 4 * kk, q = q0 + pw;
+    float4 A[MTW];
+#pragma unroll
+    for (int x = 0; x < MTW; ++x) A[x] = An[x];
+    if (more) {  // the gradient operand of the next step, requested before this step's MFMAs
+      const int qn = q + 64;
+#pragma unroll
+      for (int x = 0; x < MTW; ++x) {
+        const int m = m0 + x * 16 + r;
+        An[x] = (qn < HW && m < cout) ? ldg4(gb + (int64_t)m * HW + qn) : zero4();
+      }
     }
     const int wc = q % W;
     const bool maskL = wc == 0, maskR = wc + 3 == W - 1;
@@ -643,32 +685,82 @@ __global__ __launch_bounds__(256) void k_wgrad3x3_fast(
 #pragma unroll
           for (int x = 0; x < MTW; ++x) {
             f32x4& d = acc[(x * CTW + y) * 9 + t];
-            d = mfma16(A[x].x, b0, d);
-            d = mfma16(A[x].y, b1, d);
-            d = mfma16(A[x].z, b2, d);
-            d = mfma16(A[x].w, b3, d);
+            if (DNB_DBG & 8192) {
+              d[0] += A[x].x * b0; d[1] += A[x].y * b1; d[2] += A[x].z * b2; d[3] += A[x].w * b3;
+            } else {
+              d = mfma16(A[x].x, b0, d);
+              d = mfma16(A[x].y, b1, d);
+              d = mfma16(A[x].z, b2, d);
+              d = mfma16(A[x].w, b3, d);
+            }
           }
         }
       }
     }
+    if (more) {
+#pragma unroll
+      for (int u = 0; u < CTW; ++u) {
+        const int ch = c0 + u * 16 + prow;
+        const bool okc = ch < cin && nq >= 0 && nq < HW;
+        float4 v = nxt[u];
+        if (PRO) v = bnrelu(v, pf[u]);
+        if (!okc) v = zero4();
+        *reinterpret_cast<float4*>(&lds[(u * 16 + prow) * PA + ncol]) = v;
+      }
+      __syncthreads();
+    }
   }
 
-  reduce_waves<NT>(acc, lds, wave, lane, 4);  // reuses the activation tile's LDS (barrier inside)
-  if (wave == 0) {
-    float* pb = part + (int64_t)blockIdx.x * cout * cin * 9;
+  if (!(DNB_DBG & 2048)) reduce_waves<NT>(acc, lds, wave, lane, 4);  // reuses the activation tile's LDS (barrier inside)
+  if (wave == 0 && (!(DNB_DBG & 4096) || acc[0][0] == 12345.f)) {
+    // the partial is stored in accumulator order (tile, lane, 4 rows): 16-byte stores, contiguous
+    // across the wave; k_sum_wgrad3x3 adds the partials and puts the sums in OIHW order
+    float* pb = part + (((int64_t)blockIdx.x * gridDim.z + blockIdx.z) * gridDim.y + blockIdx.y) * (NT * 256);
 #pragma unroll
-    for (int x = 0; x < MTW; ++x)
+    for (int t = 0; t < NT; ++t)
+      *reinterpret_cast<float4*>(&pb[(t * 64 + lane) * 4]) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
+  }
+}
+
+// Sum of the 3x3 weight-gradient partials.  A partial is gz*gy blocks of mtw*ctw*9 accumulator
+// tiles in lane order (see k_wgrad3x3_fast); element f of a partial belongs to output
+// (m, c, t) computed below.  256 threads = G groups x 256/G elements: group g adds partials
+// [g*per, (g+1)*per) of its elements in order, the groups are added in order through LDS.
+__global__ __launch_bounds__(256) void k_sum_wgrad3x3(const float* __restrict__ part, int splits, int gy, int gz,
+                                                      int mtw, int ctw, int cin, int cout,
+                                                      float* __restrict__ out, int G, int per) {
+  __shared__ float sh[256];
+  const int NT = mtw * ctw * 9;
+  const int64_t F = (int64_t)gz * gy * NT * 256;
+  const int epb = 256 / G;
+  const int le = threadIdx.x % epb, grp = threadIdx.x / epb;
+  const int64_t f = (int64_t)blockIdx.x * epb + le;
+  float s = 0.f;
+  if (f < F) {
+    int i = grp * per;
+    const int end = min(splits, i + per);
+    for (; i + 8 <= end; i += 8) {
+      float v[8];
 #pragma unroll
-      for (int y = 0; y < CTW; ++y) {
-        const int c = c0 + y * 16 + r;
+      for (int u = 0; u < 8; ++u) v[u] = part[(int64_t)(i + u) * F + f];
 #pragma unroll
-        for (int t = 0; t < 9; ++t)
-#pragma unroll
-          for (int rr = 0; rr < 4; ++rr) {
-            const int m = m0 + x * 16 + 4 * kk + rr;
-            if (m < cout && c < cin) pb[((int64_t)m * cin + c) * 9 + t] = acc[(x * CTW + y) * 9 + t][rr];
-          }
-      }
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; i < end; ++i) s += part[(int64_t)i * F + f];
+  }
+  sh[threadIdx.x] = s;
+  __syncthreads();
+  if (grp == 0 && f < F) {
+    float t = sh[le];
+    for (int g = 1; g < G; ++g) t += sh[g * epb + le];
+    const int rr = (int)(f & 3), lane = (int)((f >> 2) & 63);
+    const int64_t tl = f >> 8;
+    const int tile = (int)(tl % NT), blk = (int)(tl / NT);
+    const int yb = blk % gy, z = blk / gy;
+    const int tap = tile % 9, y = (tile / 9) % ctw, x = tile / (9 * ctw);
+    const int m = z * (mtw * 16) + x * 16 + 4 * (lane >> 4) + rr;
+    const int c = yb * (ctw * 16) + y * 16 + (lane & 15);
+    if (m < cout && c < cin) out[((int64_t)m * cin + c) * 9 + tap] = t;
   }
 }
 
@@ -898,13 +990,15 @@ static WgFastPlan plan_wgrad_fast(int n, int cin, int cout, int h, int w, int ta
 
 size_t conv_wgrad_fast_partial_floats(int n, int cin, int cout, int h, int w, int taps) {
   const WgFastPlan p = plan_wgrad_fast(n, cin, cout, h, w, taps);
-  return p.ok ? (size_t)p.gx * cin * cout * taps : 0;
+  if (!p.ok) return 0;
+  if (taps == 9) return (size_t)p.gx * p.gy * p.gz * p.mtw * p.ctw * 9 * 256;  // accumulator-order partials
+  return (size_t)p.gx * cin * cout;
 }
 
 // Returns false if the fast path does not apply; otherwise launches and reports the number
 // of partials to add in *splits.
 bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
-                       float* partials, int n, int cin, int cout, int h, int w, int taps,
+                       float* partials, float* dw, int n, int cin, int cout, int h, int w, int taps,
                        const float2* fold, int* splits, hipStream_t st) {
   if (in_stride % 4 || g_stride % 4 || !aligned16(in) || !aligned16(g)) return false;
   const WgFastPlan p = plan_wgrad_fast(n, cin, cout, h, w, taps);
@@ -944,6 +1038,17 @@ bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64
       case 13: DNB_L(1, 3); break; case 12: DNB_L(1, 2); break; default: DNB_L(1, 1); break;
     }
 #undef DNB_L
+  }
+  if (taps == 9) {
+    // the 3x3 partials are in accumulator order: summed and reordered here
+    const int64_t F = (int64_t)p.gz * p.gy * p.mtw * p.ctw * 9 * 256;
+    int G = 1;
+    while (G < 16 && p.gx / (G * 2) >= 4) G *= 2;   // at least 4 partials per group
+    const int per = (p.gx + G - 1) / G, epb = 256 / G;
+    hipLaunchKernelGGL(k_sum_wgrad3x3, dim3((unsigned)((F + epb - 1) / epb)), dim3(256), 0, st, partials, p.gx,
+                       p.gy, p.gz, p.mtw, p.ctw, cin, cout, dw, G, per);
+    *splits = 0;  // nothing left for the caller to add
+    return true;
   }
   *splits = p.gx;
   return true;
