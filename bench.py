@@ -184,56 +184,48 @@ def event_time_ms(torch, fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
-DOMINANT_KERNEL = "k_bn_bwd_apply<4, true>"
-# Mean HBM bytes per launch of that kernel on the first dense block's 16 layer shapes, from the two
-# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by the copy kernel of known size)
-# summarised in profiles/bc100_b64_fp32_bn_bwd_apply_hbm_traffic.txt; valid for that workload only.
-MEASURED_TRAFFIC = {"config2:64": 119595721}
+DOMINANT_KERNEL = "k_conv3x3_v3<1, true, true, true>"
+# HBM bytes per launch of that kernel from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each
+# scaled by the copy kernel of known size), summarised in profiles/; valid for that workload only.
+MEASURED_TRAFFIC = {}
 
 
 def dominant_kernel_roofline(dnb, torch, runs, traffic_key):
     """Live measurement of the kernel with the largest share of the step in the committed
-    rocprofv3 summary (profiles/): the apply pass of the first BN's backward, which also is the
-    concatenation's backward -- per element it reads the layer input x, the incoming gradient and
-    the gradient slab G and writes G: 4 * C_l * P * 4 algorithmic bytes per launch.  Every
-    layer shape of the workload's largest dense block (where three quarters of this kernel's time
-    goes; the small blocks' launches are a few microseconds, below what an event pair resolves)
-    is launched with its real strides through the single-op entry point, each launch stamping its
-    own pair of events at kernel start and end on the launch stream; `achieved` = mean bytes / mean duration."""
-    times, nbytes = [], []
-    for r in runs[:1]:
-        cfg = r.cfg
-        hw, n, cout = cfg.h * cfg.w, cfg.n, cfg.c_out
-        cm = cfg.c_in(cfg.layers)
-        x = torch.randn((n, cout, cfg.h, cfg.w), device="cuda")
-        dact = torch.randn((n, cm, cfg.h, cfg.w), device="cuda")
-        G = torch.zeros((n, cout, cfg.h, cfg.w), device="cuda")
-        gamma, beta = torch.ones(cm, device="cuda"), torch.zeros(cm, device="cuda")
-        mean, istd = torch.zeros(cm, device="cuda"), torch.ones(cm, device="cuda")
-        dg, db = torch.empty(cm, device="cuda"), torch.empty(cm, device="cuda")
-        scratch = torch.empty(dnb.dnb_op_bn_scratch_bytes(n, cm, hw), dtype=torch.uint8, device="cuda")
-        for l in range(1, cfg.layers + 1):
-            c = cfg.c_in(l)
-            args = (x, cout * hw, dact, c * hw, G, cout * hw, 1, n, c, hw, gamma, beta, mean, istd, dg, db, scratch)
-            dnb.dnb_op_bn_relu_backward(*args)          # leaves this shape's partial sums in scratch
-            dnb.dnb_op_bn_relu_backward_apply(*args)    # warm
-            reps = 5
-            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-            for e0, e1 in evs:
-                e0.record(); e1.record()   # creates the handles; the launch below re-stamps both
-                dnb.dnb_op_bn_relu_backward_apply(*args, ev_start=e0, ev_stop=e1)
-            torch.cuda.synchronize()
-            times.append(sum(e0.elapsed_time(e1) for e0, e1 in evs) / reps)
-            nbytes.append(4 * c * n * hw * 4)
-    ms = sum(times) / len(times)
-    by = sum(nbytes) / len(nbytes)
-    achieved = by / (ms * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC.get(traffic_key)
-    return {"bound": "hbm", "kernel": DOMINANT_KERNEL + " (BN1 backward apply + concat backward)",
-            "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-            "avg_launch_ms": round(ms, 5), "algorithmic_bytes_per_launch": int(by), "launches_averaged": len(times),
-            "shapes": "the %d layers of the first dense block (P = %d pixels)" % (len(times), runs[0].cfg.pixels)}
+    rocprofv3 summary (profiles/): the fused schedule's forward 3x3 convolution -- BN2+ReLU applied
+    while the tile is staged, fp32 MFMA implicit GEMM (k outputs from 9*B inputs per pixel),
+    statistics of the output in the epilogue.  It is bound by the fp32 matrix pipe: 18*P*B*k
+    algorithmic flops per launch (useful flops: the padding of k = 12 to a 16-row tile is not
+    counted).  The layer shape of the workload's largest dense block (all its layers have the same
+    3x3: B -> k at P pixels) is launched through the single-op entry point, each launch stamping
+    its own pair of events at kernel start and end on the launch stream."""
+    import numpy as np
+    cfg = runs[0].cfg
+    n, B, k, h, w = cfg.n, cfg.bottleneck, cfg.growth, cfg.h, cfg.w
+    hw = h * w
+    x = torch.randn((n, B, h, w), device="cuda")
+    wgt = torch.randn((k, B, 3, 3), device="cuda") * (2.0 / (9 * B)) ** 0.5
+    fold = torch.stack([torch.ones(B, device="cuda"), torch.zeros(B, device="cuda")], dim=1).contiguous()
+    out = torch.empty((n, k, h, w), device="cuda")
+    pk = torch.empty(dnb.dnb_op_conv_scratch_bytes(B, k, 3), dtype=torch.uint8, device="cuda")
+    stats = torch.empty(dnb.dnb_op_conv_stats_bytes(n, k, h, w), dtype=torch.uint8, device="cuda")
+    args = (x, B * hw, wgt, fold, out, k * hw, stats, n, B, k, h, w, 3, pk)
+    dnb.dnb_op_conv_bnrelu_forward(*args)                     # packs the weights, warms up
+    reps = 20
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for e0, e1 in evs:
+        e0.record(); e1.record()   # creates the handles; the launch below re-stamps both
+        dnb.dnb_op_conv_bnrelu_forward(*args, prepacked=True, ev_start=e0, ev_stop=e1)
+    torch.cuda.synchronize()
+    ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
+    flops = 18.0 * n * hw * B * k
+    achieved = flops / (ms * 1e-3) / 1e12
+    return {"bound": "mfma", "kernel": DOMINANT_KERNEL + " (forward 3x3 conv with BN2+ReLU prologue and statistics epilogue)",
+            "achieved": round(achieved, 2), "peak": MFMA_F32_PEAK_TF, "unit": "TFLOP/s",
+            "frac": round(achieved / MFMA_F32_PEAK_TF, 4), "traffic": MEASURED_TRAFFIC.get(traffic_key),
+            "avg_launch_ms": round(ms, 5), "algorithmic_flops_per_launch": int(flops),
+            "algorithmic_bytes_per_launch": int((B + k) * n * hw * 4), "launches_averaged": reps,
+            "shapes": "3x3 conv %d -> %d channels at P = %d pixels (every layer of the first dense block)" % (B, k, n * hw)}
 
 
 def cpu_baseline(wl, blocks):

@@ -188,6 +188,19 @@ size_t dnb_op_conv_scratch_bytes(int64_t cin, int64_t cout, int ks); /* packed w
 int dnb_op_conv_forward(const void* x, int64_t x_stride, const void* wgt, void* out,
                         int64_t out_stride, int64_t n, int64_t cin, int64_t cout, int64_t h,
                         int64_t w, int ks, void* scratch, void* stream);
+/* The fused schedule's forward convolution as one operation (the "BN-apply+ReLU feeding straight
+ * into the conv operand" step plus the statistics its consumer needs):
+ *   out = conv(max(0, x * scale_c + shift_c)),  (scale_c, shift_c) = fold[c] (cin float pairs),
+ * and stats[(m*T + j)*3 ..] = (count, mean, sum of squared deviations) of output channel m over
+ * pixel tile j, *tiles = T (host int).  `stats` needs dnb_op_conv_stats_bytes bytes.  Only for
+ * shapes the 16-byte-vector kernels cover (pixel rows and strides multiples of 4; for ks = 3 the
+ * staged tile must fit LDS), else DNB_E_UNSUPPORTED.  prepacked != 0: `scratch` already holds
+ * the weights packed by an earlier call for the same wgt.  ev_start / ev_stop as above. */
+size_t dnb_op_conv_stats_bytes(int64_t n, int64_t cout, int64_t h, int64_t w);
+int dnb_op_conv_bnrelu_forward(const void* x, int64_t x_stride, const void* wgt, const void* fold, void* out,
+                               int64_t out_stride, void* stats, int* tiles, int64_t n, int64_t cin, int64_t cout,
+                               int64_t h, int64_t w, int ks, void* scratch, int prepacked, void* ev_start,
+                               void* ev_stop, void* stream);
 int dnb_op_conv_dgrad(const void* dout, int64_t dout_stride, const void* wgt, void* din,
                       int64_t din_stride, int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w,
                       int ks, void* scratch, void* stream);

@@ -70,6 +70,9 @@ _SIGS = {
                                                 _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "dnb_op_conv_scratch_bytes": (_sz, [_i64, _i64, C.c_int]),
     "dnb_op_conv_forward": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
+    "dnb_op_conv_stats_bytes": (_sz, [_i64, _i64, _i64, _i64]),
+    "dnb_op_conv_bnrelu_forward": (C.c_int, [_vp, _i64, _vp, _vp, _vp, _i64, _vp, C.POINTER(C.c_int), _i64, _i64, _i64,
+                                             _i64, _i64, C.c_int, _vp, C.c_int, _vp, _vp, _vp]),
     "dnb_op_conv_dgrad": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
     "dnb_op_conv_wgrad_scratch_bytes": (_sz, [_i64, _i64, _i64, _i64, _i64, C.c_int]),
     "dnb_op_conv_wgrad": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
@@ -222,6 +225,23 @@ def dnb_op_conv_scratch_bytes(cin, cout, ks) -> int:
 def dnb_op_conv_forward(x, x_stride, wgt, out, out_stride, n, cin, cout, h, w, ks, scratch, stream=None) -> None:
     _check(_lib.dnb_op_conv_forward(_ptr(x), x_stride, _ptr(wgt), _ptr(out), out_stride, n, cin, cout, h, w,
                                     ks, _ptr(scratch), _stream(stream)))
+
+
+def dnb_op_conv_stats_bytes(n, cout, h, w) -> int:
+    return int(_lib.dnb_op_conv_stats_bytes(n, cout, h, w))
+
+
+def dnb_op_conv_bnrelu_forward(x, x_stride, wgt, fold, out, out_stride, stats, n, cin, cout, h, w, ks, scratch,
+                               prepacked=False, ev_start=None, ev_stop=None, stream=None) -> int:
+    """Returns the number of statistics tiles per output channel.  Events as in
+    dnb_op_bn_relu_backward_apply."""
+    tiles = C.c_int(0)
+    h0 = ev_start.cuda_event if ev_start is not None else None
+    h1 = ev_stop.cuda_event if ev_stop is not None else None
+    _check(_lib.dnb_op_conv_bnrelu_forward(_ptr(x), x_stride, _ptr(wgt), _ptr(fold), _ptr(out), out_stride,
+                                           _ptr(stats), C.byref(tiles), n, cin, cout, h, w, ks, _ptr(scratch),
+                                           int(prepacked), h0, h1, _stream(stream)))
+    return int(tiles.value)
 
 
 def dnb_op_conv_dgrad(dout, dout_stride, wgt, din, din_stride, n, cin, cout, h, w, ks, scratch, stream=None) -> None:

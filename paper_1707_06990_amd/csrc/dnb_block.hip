@@ -767,6 +767,31 @@ int dnb_op_conv_forward(const void* x, int64_t x_stride, const void* wgt, void* 
   return DNB_OK;
 }
 
+size_t dnb_op_conv_stats_bytes(int64_t n, int64_t cout, int64_t h, int64_t w) {
+  if (n < 1 || cout < 1 || h < 1 || w < 1 || n > 65535 || cout > 65535 || h > 4096 || w > 4096) return 0;
+  return conv_stats_partial_floats((int)n, (int)cout, (int)h, (int)w) * sizeof(float);
+}
+
+int dnb_op_conv_bnrelu_forward(const void* x, int64_t x_stride, const void* wgt, const void* fold, void* out,
+                               int64_t out_stride, void* stats, int* tiles, int64_t n, int64_t cin, int64_t cout,
+                               int64_t h, int64_t w, int ks, void* scratch, int prepacked, void* ev_start,
+                               void* ev_stop, void* stream) {
+  if (!x || !wgt || !fold || !out || !stats || !tiles || !scratch) return DNB_E_NULL;
+  const int rc = conv_args_ok(n, cin, cout, h, w, ks);
+  if (rc) return rc;
+  const int taps = ks * ks;
+  const WeightView wv{(const float*)wgt, cin * taps, taps, 0};
+  if (!conv_fast_ok((const float*)x, x_stride, (const float*)out, out_stride, (int)h, (int)w, taps))
+    return DNB_E_UNSUPPORTED;
+  if (!prepacked) DNB_TRY(launch_pack_weights(wv, (int)cout, (int)cin, taps, (float*)scratch, (hipStream_t)stream));
+  ConvExtras ex{(const float2*)fold, (float*)stats, 0, false, (hipEvent_t)ev_start, (hipEvent_t)ev_stop};
+  DNB_TRY(launch_conv_igemm((const float*)x, x_stride, wv, (const float*)scratch, (float*)out, out_stride,
+                            (int)n, (int)cin, (int)cout, (int)h, (int)w, taps, &ex, (hipStream_t)stream));
+  if (!ex.used_fast) return DNB_E_UNSUPPORTED;
+  *tiles = ex.stats_T;
+  return DNB_OK;
+}
+
 int dnb_op_conv_dgrad(const void* dout, int64_t dout_stride, const void* wgt, void* din,
                       int64_t din_stride, int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w,
                       int ks, void* scratch, void* stream) {

@@ -19,7 +19,7 @@ bool conv_fast_ok(const float* in, int64_t in_stride, const float* out, int64_t 
                   int w, int taps);
 bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, float* out,
                       int64_t out_stride, int n, int cin, int cout, int h, int w, int taps,
-                      const float2* fold, float* spart, int* sT, hipStream_t st);
+                      const float2* fold, float* spart, int* sT, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 size_t conv_wgrad_fast_partial_floats(int n, int cin, int cout, int h, int w, int taps);
 bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
                        float* partials, float* dw, int n, int cin, int cout, int h, int w, int taps,
@@ -390,7 +390,8 @@ hipError_t launch_conv_igemm(const float* in, int64_t in_stride, WeightView wv, 
   if (packed && conv_fast_ok(in, in_stride, out, out_stride, h, w, taps) &&
       launch_conv_fast(in, in_stride, packed, out, out_stride, n, cin, cout, h, w, taps,
                        ex ? ex->fold : nullptr, ex ? ex->stats_part : nullptr,
-                       ex ? &ex->stats_T : nullptr, st)) {
+                       ex ? &ex->stats_T : nullptr, st, ex ? ex->ev_start : nullptr,
+                       ex ? ex->ev_stop : nullptr)) {
     if (ex) ex->used_fast = true;
     return hipGetLastError();
   }

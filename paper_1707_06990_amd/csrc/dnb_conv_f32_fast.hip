@@ -17,6 +17,8 @@
 #endif
 
 #include "dnb_internal.h"
+#include <hip/hip_ext.h>
+
 #include "dnb_stats.cuh"
 
 namespace dnb {
@@ -475,6 +477,200 @@ __global__ __launch_bounds__(256) void k_conv3x3_v3(
   }
 }
 
+// ------------------------------------------------------------------------------- 3x3, persistent
+//
+// Second 3x3 kernel, for image widths 8, 16, 32 with a multiple of 64 pixels per image and shapes
+// where all packed weights of a wave fit its registers (MT M-tiles x NCH 16-channel chunks x 9
+// taps: the forward 3x3 with k <= 16 outputs from B <= 48 inputs, and its data gradient).
+// Differences from k_conv3x3_v3:
+//   * a workgroup walks over several 64-pixel tiles (whole image rows); the next tile's rows are
+//     requested from HBM before the current tile's MFMAs are issued and stored to the other LDS
+//     buffer after them, so load latency, BN+ReLU staging and matrix work overlap inside one
+//     workgroup (one barrier per tile);
+//   * the four waves split the tile's pixels (16 each) instead of K or M: all four SIMDs work, no
+//     cross-wave reduction, and the weights are read from L2 once per workgroup, not per tile;
+//   * the image width is a template parameter and every staged image row keeps a 4-float zero gap
+//     in front of it, so a tap is one LDS read at a compile-time offset from a single per-lane
+//     base -- no edge masks and no address arithmetic between the MFMAs;
+//   * two interleaved accumulators per M-tile break the MFMA dependence chain.
+// LDS is addressed through lds[] with integer offsets only (generic pointers to LDS must not be
+// formed here: loads through them become flat instructions).
+// Workgroup b takes tiles of its own contiguous range (consecutive workgroups sit on different
+// XCDs: each XCD's workgroups share halo rows through that XCD's L2).
+template <int MT, int NCH, int W, bool PRO, bool STATS>
+__global__ __launch_bounds__(256) void k_conv3x3_v4(
+    const float* __restrict__ in, int64_t in_stride, const float* __restrict__ Wp, int Mpad,
+    int Kpad, float* __restrict__ out, int64_t out_stride, int cin, int cout, int H,
+    const float2* __restrict__ fold, float* __restrict__ spart, int sT, int tiles_per_img,
+    int total_tiles) {
+  extern __shared__ float lds[];
+  constexpr int ROWS = NCH * 16;             // staged channel planes
+  constexpr int RW = W + 4, TR = 64 / W;     // LDS pitch of an image row; image rows per tile
+  constexpr int NR = TR + 2, W4 = W / 4;     // staged image rows (one of halo above and below)
+  constexpr int CS = 144;                    // plane pitch (>= NR*RW; 144 % 32 == 16: the four planes
+                                             // of a B-operand read fall on disjoint banks)
+  static_assert(NR * RW <= CS, "plane pitch");
+  constexpr int PER_PLANE = NR * W4, TOTAL = ROWS * PER_PLANE, U = (TOTAL + 255) / 256;
+  const int HW = H * W;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = lane & 15, g = lane >> 4;
+  // two tile buffers, then [2][4 waves][MT*16][3].  Each buffer ends with 4 zero floats: the right
+  // neighbour of the last staged row of the last plane (for the other planes it is the next
+  // plane's leading gap).
+  constexpr int BUF = ROWS * CS + 4, SST0 = 2 * BUF;
+
+  // tiles of this workgroup: XCD x = b % 8 owns tiles [x*tpx, (x+1)*tpx), its workgroups stride it
+  const int G = gridDim.x, tpx = (total_tiles + 7) >> 3, wgx = G >> 3;
+  const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+  const int t_lo = xcd * tpx, t_hi = min(total_tiles, t_lo + tpx);
+  int tile = t_lo + slot;
+  if (tile >= t_hi) return;  // uniform for the workgroup
+
+  // packed weights of every tap, chunk and M-tile: 16 bytes per lane each, kept in registers
+  float4 w4[9][NCH][MT];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int ci = 0; ci < NCH; ++ci)
+#pragma unroll
+      for (int a = 0; a < MT; ++a)
+        w4[t][ci][a] = (a * 16 < Mpad && ci * 16 < Kpad)
+                           ? ldg4(Wp + ((int64_t)t * Mpad + a * 16 + j) * Kpad + ci * 16 + 4 * g)
+                           : zero4();
+
+  // the gaps between staged rows (and the pitch padding) stay zero for the whole kernel
+  for (int i = tid; i < 2 * BUF / 4; i += 256) *reinterpret_cast<float4*>(&lds[4 * i]) = zero4();
+
+  // staging slots of this thread: the same (plane, image row, 4-pixel column) in every tile
+  int sch[U], sry[U], sgo[U], slo[U];  // channel, staged row, offset in the image row, LDS offset
+  float2 sfold[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int idx = min(u * 256 + tid, TOTAL - 1);
+    sch[u] = idx / PER_PLANE;
+    const int rem = idx - sch[u] * PER_PLANE;
+    sry[u] = rem / W4;
+    sgo[u] = 4 * (rem - sry[u] * W4);
+    slo[u] = sch[u] * CS + sry[u] * RW + 4 + sgo[u];
+    sfold[u] = (PRO && sch[u] < cin) ? fold[sch[u]] : make_float2(1.f, 0.f);
+  }
+  auto request = [&](int tl, float4(&v)[U]) {
+    const int img = tl / tiles_per_img, y0 = (tl - img * tiles_per_img) * TR;
+    const float* inb = in + (int64_t)img * in_stride;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int y = min(max(y0 - 1 + sry[u], 0), H - 1);
+      v[u] = (DNB_DBG & 16) ? make_float4(1.f, 1.f, 1.f, 1.f)
+                            : ldg4(inb + (int64_t)min(sch[u], cin - 1) * HW + y * W + sgo[u]);
+    }
+  };
+  auto deposit = [&](int tl, const float4(&v)[U], int boff) {
+    const int img = tl / tiles_per_img, y0 = (tl - img * tiles_per_img) * TR;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int y = y0 - 1 + sry[u];
+      float4 x = v[u];
+      if (PRO) {
+        x.x = fmaxf(__fmaf_rn(x.x, sfold[u].x, sfold[u].y), 0.f); x.y = fmaxf(__fmaf_rn(x.y, sfold[u].x, sfold[u].y), 0.f);
+        x.z = fmaxf(__fmaf_rn(x.z, sfold[u].x, sfold[u].y), 0.f); x.w = fmaxf(__fmaf_rn(x.w, sfold[u].x, sfold[u].y), 0.f);
+      }
+      if (!(sch[u] < cin && y >= 0 && y < H)) x = zero4();  // channel tail, rows above / below the image
+      if (u * 256 + tid < TOTAL) *reinterpret_cast<float4*>(&lds[boff + slo[u]]) = x;
+    }
+  };
+
+  __syncthreads();  // zero fill done before the first rows land
+  {
+    float4 v[U];
+    request(tile, v);
+    deposit(tile, v, 0);
+  }
+  __syncthreads();
+
+  // this lane's pixel inside the tile and its LDS base: plane g, staged row 1 + p / W, column 4 + p % W
+  const int p = 16 * wave + j;
+  const int lane_base = g * CS + (p / W + 1) * RW + 4 + (p % W);
+
+  for (int it = 0; tile < t_hi; ++it, tile += wgx) {
+    const int cur = it & 1;
+    const int boff = cur * BUF;
+    const int nxt = tile + wgx;
+    const bool more = nxt < t_hi;
+    float4 vn[U];
+    if (more) request(nxt, vn);
+
+    f32x4 acc[MT][2];
+#pragma unroll
+    for (int a = 0; a < MT; ++a) { acc[a][0] = (f32x4){0.f, 0.f, 0.f, 0.f}; acc[a][1] = (f32x4){0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+    for (int ci = 0; ci < NCH; ++ci) {
+#pragma unroll
+      for (int di = -1; di <= 1; ++di) {
+#pragma unroll
+        for (int dj = -1; dj <= 1; ++dj) {
+          const int t = (di + 1) * 3 + (dj + 1);
+#pragma unroll
+          for (int ks = 0; ks < 4; ++ks) {
+            const float b = (DNB_DBG & 512) ? 1.5f : lds[boff + lane_base + (ci * 16 + 4 * ks) * CS + di * RW + dj];
+#pragma unroll
+            for (int a = 0; a < MT; ++a) {
+              if (DNB_DBG & 8) acc[a][ks & 1][ks] += elem(w4[t][ci][a], ks) * b;
+              else acc[a][ks & 1] = mfma16(elem(w4[t][ci][a], ks), b, acc[a][ks & 1]);
+            }
+          }
+        }
+      }
+    }
+
+    // epilogue of this wave's 16 pixels (all inside the image: HW is a multiple of 64)
+    const int img = tile / tiles_per_img, q = (tile - img * tiles_per_img) * 64 + p;
+#pragma unroll
+    for (int a = 0; a < MT; ++a) {
+      if (a * 16 >= Mpad) continue;
+      float v[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) v[r] = acc[a][0][r] + acc[a][1][r];
+      if (STATS && !(DNB_DBG & 64)) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float s = v[r];
+#pragma unroll
+          for (int off = 1; off < 16; off <<= 1) s += __shfl_xor(s, off, 64);
+          const float mu = s * (1.0f / 16.0f);
+          const float dlt = v[r] - mu;
+          float m2 = dlt * dlt;
+#pragma unroll
+          for (int off = 1; off < 16; off <<= 1) m2 += __shfl_xor(m2, off, 64);
+          if (j == 0) {
+            float* ps = &lds[SST0 + (((cur * 4 + wave) * (MT * 16)) + a * 16 + 4 * g + r) * 3];
+            ps[0] = 16.f; ps[1] = mu; ps[2] = m2;
+          }
+        }
+      }
+      float* ob = out + (int64_t)img * out_stride + q;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int m = a * 16 + 4 * g + r;
+        if (m < cout) ob[(int64_t)m * HW] = v[r];
+      }
+    }
+
+    if (more) deposit(nxt, vn, (cur ^ 1) * BUF);
+    __syncthreads();
+    if (STATS && wave == 0 && lane < MT * 16 && lane < cout) {
+      const float* ps = &lds[SST0 + ((cur * 4) * (MT * 16) + lane) * 3];
+      Stat3 r{ps[0], ps[1], ps[2]};
+#pragma unroll
+      for (int w = 1; w < 4; ++w) {
+        const float* pw = ps + w * (MT * 16) * 3;
+        r = stat_combine(r, Stat3{pw[0], pw[1], pw[2]});
+      }
+      float* o = spart + ((int64_t)lane * sT + tile) * 3;
+      o[0] = r.c; o[1] = r.m; o[2] = r.m2;
+    }
+  }
+}
+
 // Adds the accumulators of the waves of a workgroup into wave 0 as a chain 3 -> 2 -> 1 -> 0 through
 // one LDS region (NT * 256 floats).  (A two-region tree (0+2)+(1+3) was measured slower.)
 template <int NT>
@@ -854,7 +1050,7 @@ size_t conv_stats_partial_floats(int n, int cout, int h, int w) {
 // fold != null: BN+ReLU prologue.  spart != null: epilogue statistics, *sT = partials per channel.
 bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, float* out,
                       int64_t out_stride, int n, int cin, int cout, int h, int w, int taps,
-                      const float2* fold, float* spart, int* sT, hipStream_t st) {
+                      const float2* fold, float* spart, int* sT, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   const int hw = h * w, mtiles = (cout + 15) / 16, M16 = mtiles * 16;
   const int K16 = (cin + 15) & ~15, nchunks = K16 / 16;
   const int mode = fold ? 2 : (spart ? 1 : 0);  // 0 plain, 1 statistics, 2 prologue + statistics
@@ -882,8 +1078,9 @@ bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, f
     const int T = tiles * n;
     if (sT) *sT = T;
 #define DNB_L(MT, PPL, KS, PRO, STATS)                                                                \
-  hipLaunchKernelGGL((k_conv1x1_v3<MT, PPL, KS, PRO, STATS>), grid, dim3(64 * nw), lds, st, in,        \
-                     in_stride, packed, K16, out, out_stride, cin, cout, hw, fold, spart, T, wk)
+  hipExtLaunchKernelGGL((k_conv1x1_v3<MT, PPL, KS, PRO, STATS>), grid, dim3(64 * nw), lds, st, ev0,   \
+                        ev1, 0, in, in_stride, packed, K16, out, out_stride, cin, cout, hw, fold,     \
+                        spart, T, wk)
 #define DNB_L3(MT, PPL, KS)                                                         \
   do {                                                                              \
     if (mode == 2) DNB_L(MT, PPL, KS, true, true);                                   \
@@ -899,6 +1096,29 @@ bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, f
 #undef DNB_L2
 #undef DNB_L3
 #undef DNB_L
+    return true;
+  }
+  const bool fwd13 = mtiles == 1 && nchunks == 3, dg31 = mtiles == 3 && nchunks == 1 && mode == 0;
+  if ((fwd13 || dg31) && (w == 8 || w == 16 || w == 32) && hw % 64 == 0) {
+    // persistent kernel: weights in registers, pixel-split waves, double-buffered tiles
+    const int tpi = hw / 64, total_tiles = tpi * n;
+    int G = total_tiles < 512 ? (total_tiles + 7) / 8 * 8 : 512;
+    const size_t lds = ((size_t)2 * (nchunks * 16 * 144 + 4) + 2 * 4 * mtiles * 16 * 3) * sizeof(float);
+    if (sT) *sT = total_tiles;
+#define DNB_L4(MT, NCH, WW, PRO, STATS)                                                                  \
+  hipExtLaunchKernelGGL((k_conv3x3_v4<MT, NCH, WW, PRO, STATS>), dim3(G), dim3(256), lds, st, ev0, ev1,  \
+                        0, in, in_stride, packed, M16, K16, out, out_stride, cin, cout, h, fold, spart,  \
+                        total_tiles, tpi, total_tiles)
+#define DNB_L4W(WW)                                                                  \
+  do {                                                                               \
+    if (dg31) DNB_L4(3, 1, WW, false, false);                                         \
+    else if (mode == 2) DNB_L4(1, 3, WW, true, true);                                 \
+    else if (mode == 1) DNB_L4(1, 3, WW, false, true);                                \
+    else DNB_L4(1, 3, WW, false, false);                                              \
+  } while (0)
+    if (w == 32) DNB_L4W(32); else if (w == 16) DNB_L4W(16); else DNB_L4W(8);
+#undef DNB_L4W
+#undef DNB_L4
     return true;
   }
   const bool ksplit = nchunks >= 3;
@@ -919,8 +1139,9 @@ bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, f
   const int T = (int)grid.x * n;
   if (sT) *sT = T;
 #define DNB_L(MT, KS, PRO, STATS)                                                                      \
-  hipLaunchKernelGGL((k_conv3x3_v3<MT, KS, PRO, STATS>), grid, dim3(64 * nw), lds, st, in, in_stride,   \
-                     packed, M16, K16, out, out_stride, cin, cout, h, w, CS, fold, spart, T)
+  hipExtLaunchKernelGGL((k_conv3x3_v3<MT, KS, PRO, STATS>), grid, dim3(64 * nw), lds, st, ev0, ev1, 0, \
+                        in, in_stride, packed, M16, K16, out, out_stride, cin, cout, h, w, CS, fold,   \
+                        spart, T)
 #define DNB_L3(MT, KS)                                                              \
   do {                                                                              \
     if (mode == 2) DNB_L(MT, KS, true, true);                                        \

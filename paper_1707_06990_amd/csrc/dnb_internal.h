@@ -82,11 +82,13 @@ hipError_t launch_pack_block_weights(const float* params, float* packed, int c0,
 //   stats_part  epilogue statistics of the output: [cout][stats_T][3] partials (count, mean, M2),
 //               conv_stats_partial_floats floats; stats_T is set by the launcher
 //   used_fast   set by the launcher; false = generic kernel ran, no statistics were written
+//   ev_start / ev_stop  optional events stamped at the fast kernel's own start and end
 struct ConvExtras {
   const float2* fold;
   float* stats_part;
   int stats_T;
   bool used_fast;
+  hipEvent_t ev_start = nullptr, ev_stop = nullptr;
 };
 size_t conv_stats_partial_floats(int n, int cout, int h, int w);
 hipError_t launch_conv_igemm(const float* in, int64_t in_stride, WeightView wv, const float* packed,

@@ -170,3 +170,31 @@ def test_conv_on_channel_slices_of_wider_slabs(dnb, oracle):
     res = wide_out.cpu().numpy()
     assert_close(res[:, 20:32], oracle.conv_forward(wide_in[:, 4:4 + cin], wgt), TOL, "slice conv")
     assert np.all(res[:, :20] == -3.0) and np.all(res[:, 32:] == -3.0)
+
+
+@pytest.mark.parametrize("n,cin,cout,h,w,ks", [(2, 48, 12, 32, 32, 3), (3, 40, 48, 16, 16, 1), (2, 204, 48, 8, 8, 1),
+                                               (2, 24, 12, 8, 12, 3)])
+def test_fused_conv_bnrelu_forward_and_statistics(dnb, oracle, n, cin, cout, h, w, ks):
+    """BN+ReLU applied in the operand load, statistics of the output from the epilogue: against
+    relu(x*scale+shift) -> conv of the oracle, and the merged tile statistics against the output's
+    mean and biased variance."""
+    r = rng(21)
+    x = f32(r.standard_normal((n, cin, h, w)))
+    wgt = f32(r.standard_normal((cout, cin, ks, ks)) * np.sqrt(2.0 / (cin * ks * ks)))
+    fold = f32(np.stack([1.0 + 0.3 * r.standard_normal(cin), 0.3 * r.standard_normal(cin)], axis=1))
+    hw = h * w
+    out = torch.full((n, cout, h, w), float("nan"), device="cuda")
+    pk = torch.empty(dnb.dnb_op_conv_scratch_bytes(cin, cout, ks), dtype=torch.uint8, device="cuda")
+    stats = torch.full((dnb.dnb_op_conv_stats_bytes(n, cout, h, w) // 4,), float("nan"), device="cuda")
+    T = dnb.dnb_op_conv_bnrelu_forward(dev(x), cin * hw, dev(wgt), dev(fold), out, cout * hw, stats, n, cin, cout, h, w, ks, pk)
+    torch.cuda.synchronize()
+    a = np.maximum(x.astype(np.float64) * fold[:, 0].astype(np.float64)[None, :, None, None]
+                   + fold[:, 1].astype(np.float64)[None, :, None, None], 0.0)
+    ref = oracle.conv_forward(a, wgt)
+    assert_close(out.cpu().numpy(), ref, TOL, "fused conv")
+    st = stats.cpu().numpy()[:cout * T * 3].reshape(cout, T, 3).astype(np.float64)
+    assert np.all(st[:, :, 0].sum(axis=1) == n * hw)
+    mean = (st[:, :, 0] * st[:, :, 1]).sum(axis=1) / (n * hw)
+    m2 = (st[:, :, 2] + st[:, :, 0] * (st[:, :, 1] - mean[:, None]) ** 2).sum(axis=1)
+    assert_close(mean, ref.mean(axis=(0, 2, 3)), 1e-4 * max(1.0, float(np.abs(ref).max() / np.abs(ref.mean(axis=(0, 2, 3))).max())), "mean")
+    assert_close(m2 / (n * hw), ref.var(axis=(0, 2, 3)), TOL, "variance")
