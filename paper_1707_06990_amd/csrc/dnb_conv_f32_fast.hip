@@ -9,6 +9,9 @@
 // K-steps.  The order of the K index inside a sum is free, so lane group g takes channels
 // {g, 4+g, 8+g, 12+g} of a 16-channel chunk and a channel tail that is a multiple of 4
 // costs no padding.
+#ifndef DNB_V4_WGS
+#define DNB_V4_WGS 512  // workgroups of the persistent 3x3 kernel (two per CU)
+#endif
 #ifndef DNB_DBG
 #define DNB_DBG 0  // kernel ablation builds for tuning experiments (1x1: 1 no MFMA, 2/4 no activation / weight loads;
                    // 3x3: 8 no MFMA, 16/32 no activation / weight loads, 64 no statistics epilogue,
@@ -526,21 +529,6 @@ __global__ __launch_bounds__(256) void k_conv3x3_v4(
   int tile = t_lo + slot;
   if (tile >= t_hi) return;  // uniform for the workgroup
 
-  // packed weights of every tap, chunk and M-tile: 16 bytes per lane each, kept in registers
-  float4 w4[9][NCH][MT];
-#pragma unroll
-  for (int t = 0; t < 9; ++t)
-#pragma unroll
-    for (int ci = 0; ci < NCH; ++ci)
-#pragma unroll
-      for (int a = 0; a < MT; ++a)
-        w4[t][ci][a] = (a * 16 < Mpad && ci * 16 < Kpad)
-                           ? ldg4(Wp + ((int64_t)t * Mpad + a * 16 + j) * Kpad + ci * 16 + 4 * g)
-                           : zero4();
-
-  // the gaps between staged rows (and the pitch padding) stay zero for the whole kernel
-  for (int i = tid; i < 2 * BUF / 4; i += 256) *reinterpret_cast<float4*>(&lds[4 * i]) = zero4();
-
   // staging slots of this thread: the same (plane, image row, 4-pixel column) in every tile
   int sch[U], sry[U], sgo[U], slo[U];  // channel, staged row, offset in the image row, LDS offset
   float2 sfold[U];
@@ -579,12 +567,27 @@ __global__ __launch_bounds__(256) void k_conv3x3_v4(
     }
   };
 
+  // the first tile's rows are requested first (longest latency); the weights and the zero fill
+  // are issued while they are in flight
+  float4 v0[U];
+  request(tile, v0);
+  // packed weights of every tap, chunk and M-tile: 16 bytes per lane each, kept in registers
+  float4 w4[9][NCH][MT];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int ci = 0; ci < NCH; ++ci)
+#pragma unroll
+      for (int a = 0; a < MT; ++a)
+        w4[t][ci][a] = (a * 16 < Mpad && ci * 16 < Kpad)
+                           ? ldg4(Wp + ((int64_t)t * Mpad + a * 16 + j) * Kpad + ci * 16 + 4 * g)
+                           : zero4();
+
+  // the gaps between staged rows (and the pitch padding) stay zero for the whole kernel
+  for (int i = tid; i < 2 * BUF / 4; i += 256) *reinterpret_cast<float4*>(&lds[4 * i]) = zero4();
+
   __syncthreads();  // zero fill done before the first rows land
-  {
-    float4 v[U];
-    request(tile, v);
-    deposit(tile, v, 0);
-  }
+  deposit(tile, v0, 0);
   __syncthreads();
 
   // this lane's pixel inside the tile and its LDS base: plane g, staged row 1 + p / W, column 4 + p % W
@@ -1102,7 +1105,7 @@ bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, f
   if ((fwd13 || dg31) && (w == 8 || w == 16 || w == 32) && hw % 64 == 0) {
     // persistent kernel: weights in registers, pixel-split waves, double-buffered tiles
     const int tpi = hw / 64, total_tiles = tpi * n;
-    int G = total_tiles < 512 ? (total_tiles + 7) / 8 * 8 : 512;
+    int G = total_tiles < DNB_V4_WGS ? (total_tiles + 7) / 8 * 8 : DNB_V4_WGS;
     const size_t lds = ((size_t)2 * (nchunks * 16 * 144 + 4) + 2 * 4 * mtiles * 16 * 3) * sizeof(float);
     if (sT) *sT = total_tiles;
 #define DNB_L4(MT, NCH, WW, PRO, STATS)                                                                  \
