@@ -184,7 +184,7 @@ def event_time_ms(torch, fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
-DOMINANT_KERNEL = "k_conv3x3_v3<1, true, true, true>"
+DOMINANT_KERNEL = "k_wgrad3x3_fast<1, 3, true>"
 # HBM bytes per launch of that kernel from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each
 # scaled by the copy kernel of known size), summarised in profiles/; valid for that workload only.
 MEASURED_TRAFFIC = {}
@@ -192,40 +192,40 @@ MEASURED_TRAFFIC = {}
 
 def dominant_kernel_roofline(dnb, torch, runs, traffic_key):
     """Live measurement of the kernel with the largest share of the step in the committed
-    rocprofv3 summary (profiles/): the fused schedule's forward 3x3 convolution -- BN2+ReLU applied
-    while the tile is staged, fp32 MFMA implicit GEMM (k outputs from 9*B inputs per pixel),
-    statistics of the output in the epilogue.  It is bound by the fp32 matrix pipe: 18*P*B*k
-    algorithmic flops per launch (useful flops: the padding of k = 12 to a 16-row tile is not
-    counted).  The layer shape of the workload's largest dense block (all its layers have the same
-    3x3: B -> k at P pixels) is launched through the single-op entry point, each launch stamping
-    its own pair of events at kernel start and end on the launch stream."""
+    rocprofv3 summary (profiles/): the fused schedule's 3x3 weight gradient -- BN2+ReLU of b_l
+    recomputed while the activation tile is staged, fp32 MFMA with pixels on the K axis, all
+    k x B x 9 outputs kept in accumulators, partial sums per workgroup.  It is bound by the fp32
+    matrix pipe: 18*P*B*k algorithmic flops per launch (useful flops: the padding of k = 12 to a
+    16-row tile is not counted).  The layer shape of the workload's largest dense block (all its
+    layers have the same 3x3: B x k at P pixels) is launched through the single-op entry point,
+    each launch stamping its own pair of events at the kernel's start and end on the launch
+    stream."""
     import numpy as np
     cfg = runs[0].cfg
     n, B, k, h, w = cfg.n, cfg.bottleneck, cfg.growth, cfg.h, cfg.w
     hw = h * w
     x = torch.randn((n, B, h, w), device="cuda")
-    wgt = torch.randn((k, B, 3, 3), device="cuda") * (2.0 / (9 * B)) ** 0.5
+    g = torch.randn((n, k, h, w), device="cuda")
     fold = torch.stack([torch.ones(B, device="cuda"), torch.zeros(B, device="cuda")], dim=1).contiguous()
-    out = torch.empty((n, k, h, w), device="cuda")
-    pk = torch.empty(dnb.dnb_op_conv_scratch_bytes(B, k, 3), dtype=torch.uint8, device="cuda")
-    stats = torch.empty(dnb.dnb_op_conv_stats_bytes(n, k, h, w), dtype=torch.uint8, device="cuda")
-    args = (x, B * hw, wgt, fold, out, k * hw, stats, n, B, k, h, w, 3, pk)
-    dnb.dnb_op_conv_bnrelu_forward(*args)                     # packs the weights, warms up
+    dw = torch.empty((k, B, 3, 3), device="cuda")
+    scratch = torch.empty(dnb.dnb_op_conv_wgrad_scratch_bytes(n, B, k, h, w, 3), dtype=torch.uint8, device="cuda")
+    args = (x, B * hw, fold, g, k * hw, dw, n, B, k, h, w, 3, scratch)
+    dnb.dnb_op_conv_bnrelu_wgrad(*args)   # warm
     reps = 20
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
     for e0, e1 in evs:
         e0.record(); e1.record()   # creates the handles; the launch below re-stamps both
-        dnb.dnb_op_conv_bnrelu_forward(*args, prepacked=True, ev_start=e0, ev_stop=e1)
+        dnb.dnb_op_conv_bnrelu_wgrad(*args, ev_start=e0, ev_stop=e1)
     torch.cuda.synchronize()
     ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
     flops = 18.0 * n * hw * B * k
     achieved = flops / (ms * 1e-3) / 1e12
-    return {"bound": "mfma", "kernel": DOMINANT_KERNEL + " (forward 3x3 conv with BN2+ReLU prologue and statistics epilogue)",
+    return {"bound": "mfma", "kernel": DOMINANT_KERNEL + " (3x3 weight gradient with BN2+ReLU prologue)",
             "achieved": round(achieved, 2), "peak": MFMA_F32_PEAK_TF, "unit": "TFLOP/s",
             "frac": round(achieved / MFMA_F32_PEAK_TF, 4), "traffic": MEASURED_TRAFFIC.get(traffic_key),
             "avg_launch_ms": round(ms, 5), "algorithmic_flops_per_launch": int(flops),
             "algorithmic_bytes_per_launch": int((B + k) * n * hw * 4), "launches_averaged": reps,
-            "shapes": "3x3 conv %d -> %d channels at P = %d pixels (every layer of the first dense block)" % (B, k, n * hw)}
+            "shapes": "3x3 weight gradient %d x %d x 9 over P = %d pixels (every layer of the first dense block)" % (k, B, n * hw)}
 
 
 def cpu_baseline(wl, blocks):

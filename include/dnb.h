@@ -201,6 +201,14 @@ int dnb_op_conv_bnrelu_forward(const void* x, int64_t x_stride, const void* wgt,
                                int64_t out_stride, void* stats, int* tiles, int64_t n, int64_t cin, int64_t cout,
                                int64_t h, int64_t w, int ks, void* scratch, int prepacked, void* ev_start,
                                void* ev_stop, void* stream);
+/* The fused schedule's weight gradient as one operation: dwgt = wgrad(max(0, x*scale_c + shift_c), dout),
+ * the BN+ReLU of the activation operand recomputed in the operand load (fold as above).
+ * scratch: dnb_op_conv_wgrad_scratch_bytes.  ev_start / ev_stop are stamped around the gradient
+ * kernel itself (the small kernel that adds its partial sums follows it).  Same shape limits as
+ * dnb_op_conv_bnrelu_forward, else DNB_E_UNSUPPORTED. */
+int dnb_op_conv_bnrelu_wgrad(const void* x, int64_t x_stride, const void* fold, const void* dout,
+                             int64_t dout_stride, void* dwgt, int64_t n, int64_t cin, int64_t cout, int64_t h,
+                             int64_t w, int ks, void* scratch, void* ev_start, void* ev_stop, void* stream);
 int dnb_op_conv_dgrad(const void* dout, int64_t dout_stride, const void* wgt, void* din,
                       int64_t din_stride, int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w,
                       int ks, void* scratch, void* stream);

@@ -73,6 +73,8 @@ _SIGS = {
     "dnb_op_conv_stats_bytes": (_sz, [_i64, _i64, _i64, _i64]),
     "dnb_op_conv_bnrelu_forward": (C.c_int, [_vp, _i64, _vp, _vp, _vp, _i64, _vp, C.POINTER(C.c_int), _i64, _i64, _i64,
                                              _i64, _i64, C.c_int, _vp, C.c_int, _vp, _vp, _vp]),
+    "dnb_op_conv_bnrelu_wgrad": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _vp, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp,
+                                           _vp, _vp, _vp]),
     "dnb_op_conv_dgrad": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
     "dnb_op_conv_wgrad_scratch_bytes": (_sz, [_i64, _i64, _i64, _i64, _i64, C.c_int]),
     "dnb_op_conv_wgrad": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
@@ -242,6 +244,14 @@ def dnb_op_conv_bnrelu_forward(x, x_stride, wgt, fold, out, out_stride, stats, n
                                            _ptr(stats), C.byref(tiles), n, cin, cout, h, w, ks, _ptr(scratch),
                                            int(prepacked), h0, h1, _stream(stream)))
     return int(tiles.value)
+
+
+def dnb_op_conv_bnrelu_wgrad(x, x_stride, fold, dout, dout_stride, dwgt, n, cin, cout, h, w, ks, scratch,
+                             ev_start=None, ev_stop=None, stream=None) -> None:
+    h0 = ev_start.cuda_event if ev_start is not None else None
+    h1 = ev_stop.cuda_event if ev_stop is not None else None
+    _check(_lib.dnb_op_conv_bnrelu_wgrad(_ptr(x), x_stride, _ptr(fold), _ptr(dout), dout_stride, _ptr(dwgt), n, cin,
+                                         cout, h, w, ks, _ptr(scratch), h0, h1, _stream(stream)))
 
 
 def dnb_op_conv_dgrad(dout, dout_stride, wgt, din, din_stride, n, cin, cout, h, w, ks, scratch, stream=None) -> None:

@@ -826,6 +826,21 @@ int dnb_op_conv_wgrad(const void* x, int64_t x_stride, const void* dout, int64_t
   return DNB_OK;
 }
 
+int dnb_op_conv_bnrelu_wgrad(const void* x, int64_t x_stride, const void* fold, const void* dout,
+                             int64_t dout_stride, void* dwgt, int64_t n, int64_t cin, int64_t cout, int64_t h,
+                             int64_t w, int ks, void* scratch, void* ev_start, void* ev_stop, void* stream) {
+  if (!x || !fold || !dout || !dwgt || !scratch) return DNB_E_NULL;
+  const int rc = conv_args_ok(n, cin, cout, h, w, ks);
+  if (rc) return rc;
+  bool fast = false;
+  const hipError_t e = launch_conv_wgrad((const float*)x, x_stride, (const float*)dout, dout_stride, (float*)dwgt,
+                                         (int)n, (int)cin, (int)cout, (int)h, (int)w, ks * ks, (float*)scratch,
+                                         (const float2*)fold, (hipStream_t)stream, (hipEvent_t)ev_start,
+                                         (hipEvent_t)ev_stop, &fast);
+  if (!fast) return DNB_E_UNSUPPORTED;  // only the 16-byte-vector kernels have the prologue
+  return e == hipSuccess ? DNB_OK : DNB_E_LAUNCH;
+}
+
 // ---- single operations of the bf16 / NHWC path
 
 size_t dnb_op_nhwc_scratch_bytes(int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w, int ks) {

@@ -23,7 +23,7 @@ bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, f
 size_t conv_wgrad_fast_partial_floats(int n, int cin, int cout, int h, int w, int taps);
 bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
                        float* partials, float* dw, int n, int cin, int cout, int h, int w, int taps,
-                       const float2* fold, int* splits, hipStream_t st);
+                       const float2* fold, int* splits, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 
 namespace {
 
@@ -414,11 +414,15 @@ size_t conv_wgrad_partial_floats(int n, int cin, int cout, int h, int w, int tap
 
 hipError_t launch_conv_wgrad(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
                              float* dw, int n, int cin, int cout, int h, int w, int taps,
-                             float* partials, const float2* fold, hipStream_t st) {
+                             float* partials, const float2* fold, hipStream_t st, hipEvent_t ev0,
+                             hipEvent_t ev1, bool* used_fast) {
   if (cin <= 0 || cout <= 0) return hipSuccess;
+  if (used_fast) *used_fast = true;
   const int64_t count = (int64_t)cin * cout * taps;
   int splits = 0;
-  if (!launch_wgrad_fast(in, in_stride, g, g_stride, partials, dw, n, cin, cout, h, w, taps, fold, &splits, st)) {
+  if (!launch_wgrad_fast(in, in_stride, g, g_stride, partials, dw, n, cin, cout, h, w, taps, fold, &splits, st, ev0,
+                         ev1)) {
+    if (used_fast) *used_fast = false;
     if (fold) return hipErrorInvalidValue;  // the generic kernel has no BN prologue
     const WgradPlan p = plan_wgrad(n, cin, cout, h, w, taps);
     if (p.lds > 64 * 1024) return hipErrorInvalidValue;

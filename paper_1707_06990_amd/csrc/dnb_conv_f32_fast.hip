@@ -1223,7 +1223,7 @@ size_t conv_wgrad_fast_partial_floats(int n, int cin, int cout, int h, int w, in
 // of partials to add in *splits.
 bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
                        float* partials, float* dw, int n, int cin, int cout, int h, int w, int taps,
-                       const float2* fold, int* splits, hipStream_t st) {
+                       const float2* fold, int* splits, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
   if (in_stride % 4 || g_stride % 4 || !aligned16(in) || !aligned16(g)) return false;
   const WgFastPlan p = plan_wgrad_fast(n, cin, cout, h, w, taps);
   if (!p.ok) return false;
@@ -1233,10 +1233,10 @@ bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64
 #define DNB_L(M, C)                                                                                  \
   do {                                                                                               \
     if (fold)                                                                                        \
-      hipLaunchKernelGGL((k_wgrad1x1_fast<M, C, true>), grid, dim3(256), p.lds, st, in, in_stride, g, \
+      hipExtLaunchKernelGGL((k_wgrad1x1_fast<M, C, true>), grid, dim3(256), p.lds, st, ev0, ev1, 0, in, in_stride, g, \
                          g_stride, partials, cin, cout, hw, p.spi, p.total_steps, p.steps_per_wg, fold); \
     else                                                                                             \
-      hipLaunchKernelGGL((k_wgrad1x1_fast<M, C, false>), grid, dim3(256), p.lds, st, in, in_stride, g, \
+      hipExtLaunchKernelGGL((k_wgrad1x1_fast<M, C, false>), grid, dim3(256), p.lds, st, ev0, ev1, 0, in, in_stride, g, \
                          g_stride, partials, cin, cout, hw, p.spi, p.total_steps, p.steps_per_wg, fold); \
   } while (0)
     const int key = p.mtw * 10 + p.ctw;
@@ -1250,10 +1250,10 @@ bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64
 #define DNB_L(M, C)                                                                                  \
   do {                                                                                               \
     if (fold)                                                                                        \
-      hipLaunchKernelGGL((k_wgrad3x3_fast<M, C, true>), grid, dim3(256), p.lds, st, in, in_stride, g, \
+      hipExtLaunchKernelGGL((k_wgrad3x3_fast<M, C, true>), grid, dim3(256), p.lds, st, ev0, ev1, 0, in, in_stride, g, \
                          g_stride, partials, cin, cout, h, w, p.tiles_per_img, p.nms, p.PA, fold);    \
     else                                                                                             \
-      hipLaunchKernelGGL((k_wgrad3x3_fast<M, C, false>), grid, dim3(256), p.lds, st, in, in_stride, g, \
+      hipExtLaunchKernelGGL((k_wgrad3x3_fast<M, C, false>), grid, dim3(256), p.lds, st, ev0, ev1, 0, in, in_stride, g, \
                          g_stride, partials, cin, cout, h, w, p.tiles_per_img, p.nms, p.PA, fold);    \
   } while (0)
     const int key = p.mtw * 10 + p.ctw;

@@ -109,7 +109,9 @@ size_t conv_wgrad_partial_floats(int n, int cin, int cout, int h, int w, int tap
 // fold != null applies the BN+ReLU prologue to `in` (fast path only).
 hipError_t launch_conv_wgrad(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
                              float* dw, int n, int cin, int cout, int h, int w, int taps,
-                             float* partials, const float2* fold, hipStream_t st);
+                             float* partials, const float2* fold, hipStream_t st, hipEvent_t ev_start = nullptr,
+                             hipEvent_t ev_stop = nullptr /*stamped around the fast kernel (not the sum)*/,
+                             bool* used_fast = nullptr);
 
 // out[e] = sum over splits of partials[split][e] (fixed order).
 hipError_t launch_sum_partials(const float* partials, int splits, int64_t count, float* out, hipStream_t st);

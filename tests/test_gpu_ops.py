@@ -198,3 +198,21 @@ def test_fused_conv_bnrelu_forward_and_statistics(dnb, oracle, n, cin, cout, h, 
     m2 = (st[:, :, 2] + st[:, :, 0] * (st[:, :, 1] - mean[:, None]) ** 2).sum(axis=1)
     assert_close(mean, ref.mean(axis=(0, 2, 3)), 1e-4 * max(1.0, float(np.abs(ref).max() / np.abs(ref.mean(axis=(0, 2, 3))).max())), "mean")
     assert_close(m2 / (n * hw), ref.var(axis=(0, 2, 3)), TOL, "variance")
+
+
+@pytest.mark.parametrize("n,cin,cout,h,w,ks", [(2, 48, 12, 32, 32, 3), (3, 40, 48, 16, 16, 1), (2, 204, 48, 8, 8, 1),
+                                               (2, 24, 12, 8, 12, 3)])
+def test_fused_conv_bnrelu_wgrad(dnb, oracle, n, cin, cout, h, w, ks):
+    """Weight gradient with BN+ReLU of the activation recomputed in the operand load."""
+    r = rng(22)
+    x = f32(r.standard_normal((n, cin, h, w)))
+    g = f32(r.standard_normal((n, cout, h, w)))
+    fold = f32(np.stack([1.0 + 0.3 * r.standard_normal(cin), 0.3 * r.standard_normal(cin)], axis=1))
+    hw = h * w
+    dw = torch.full((cout, cin, ks, ks), float("nan"), device="cuda")
+    scratch = torch.empty(max(16, dnb.dnb_op_conv_wgrad_scratch_bytes(n, cin, cout, h, w, ks)), dtype=torch.uint8, device="cuda")
+    dnb.dnb_op_conv_bnrelu_wgrad(dev(x), cin * hw, dev(fold), dev(g), cout * hw, dw, n, cin, cout, h, w, ks, scratch)
+    torch.cuda.synchronize()
+    a = np.maximum(x.astype(np.float64) * fold[:, 0].astype(np.float64)[None, :, None, None]
+                   + fold[:, 1].astype(np.float64)[None, :, None, None], 0.0)
+    assert_close(dw.cpu().numpy(), oracle.conv_wgrad(a, g, ks), TOL, "fused wgrad")
