@@ -187,7 +187,7 @@ def event_time_ms(torch, fn, reps):
 DOMINANT_KERNEL = "k_wgrad3x3_fast<1, 3, true>"
 # HBM bytes per launch of that kernel from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each
 # scaled by the copy kernel of known size), summarised in profiles/; valid for that workload only.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {"config2:64": 41039579}   # profiles/bc100_b64_fp32_wgrad3x3_hbm_traffic.txt, first dense block shape
 
 
 def dominant_kernel_roofline(dnb, torch, runs, traffic_key):
