@@ -9,6 +9,21 @@
 // K-steps.  The order of the K index inside a sum is free, so lane group g takes channels
 // {g, 4+g, 8+g, 12+g} of a 16-channel chunk and a channel tail that is a multiple of 4
 // costs no padding.
+//
+// Measurements that shaped (or failed to improve) these kernels, on the first dense block's
+// shapes of DenseNet-BC-100 at batch 64 (P = 65536, B = 48, k = 12), compile-time ablation builds:
+//   * forward 3x3, one tile per workgroup (v3): 28 us = ~4.4 empty launch + 3.8 staging + 4 loads
+//     + 8 MFMA + 1.8 statistics + 1 K-split reduction + ...: the parts add up because all
+//     workgroups of a launch are in the same phase at the same time.  The persistent kernel (v4)
+//     overlaps them inside a workgroup: 19.5 us; with everything but the skeleton removed 9.4 us.
+//   * 3x3 weight gradient: 27 us = 6.4 MFMA + 6.6 scattered 4-byte partial stores + 4 wave
+//     reduction + ~10 rest; accumulator-order stores brought it to 22.5 us.  A two-region tree
+//     reduction ((0+2)+(1+3)) was slower than the chain (29 us); staging the tile progressively
+//     and prefetching the gradient operand changed nothing (neither is on the critical path).
+//   * 1x1: a 3-deep register prefetch ring over the K chunks did not change the 22 us of the
+//     forward kernel; 5 us remain with loads and MFMAs removed.
+//   * BN-backward sums computed in the data-gradient convs' epilogues (to drop the separate
+//     reduction launch) made those convs 6-15 us slower, more than the launch they saved.
 #ifndef DNB_V4_WGS
 #define DNB_V4_WGS 512  // workgroups of the persistent 3x3 kernel (two per CU)
 #endif
