@@ -268,7 +268,8 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
   if (d.bottleneck == 0 && (bf16 || d.schedule == DNB_SCHED_FUSED)) return DNB_E_UNSUPPORTED;
   // bf16 kernels move 8 channels (16 bytes) at a time
   if (bf16 && (d.c0 % 8 || d.growth % 8 || d.bottleneck % 8)) return DNB_E_UNSUPPORTED;
-  if (bf16 && (size_t)(64 + 2 * (d.w + 1)) * 80 > 64 * 1024) return DNB_E_UNSUPPORTED;
+  // ... and the 3x3 double-buffers 64 pixels + halo x 64 channels in 64 KB of LDS (w <= 80)
+  if (bf16 && (size_t)2 * (64 + 2 * (d.w + 1)) * 72 * 2 > 64 * 1024) return DNB_E_UNSUPPORTED;
   // the fp32 fused schedule exists only in the 16-byte-vector kernels (pixel rows a multiple of 4)
   if (!bf16 && d.schedule == DNB_SCHED_FUSED) {
     // ... and its 3x3 stages all B channels of a 64-pixel tile (+ halo) in 64 KB of LDS

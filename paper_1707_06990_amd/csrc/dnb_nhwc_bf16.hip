@@ -203,22 +203,30 @@ __global__ __launch_bounds__(256) void k_pack_weights(const float* __restrict__ 
 // ----------------------------------------------------------------------------- conv fwd / dgrad
 
 // out[q][m] = sum_{t,c} W(t,m,c) * act(in[q+shift(t)][c]),  act = BN+ReLU prologue or identity.
-// grid (pixel tiles of 64 per image, M groups, images); 256 threads.  TIN = u16 (bf16) or float
-// (the gradient slab).  STATS: per-tile (count, mean, M2) of the rounded outputs, as in the fp32
-// kernels: spart[(m*T + tile)*3].
+// 256 threads; a workgroup owns 64 pixels -- for the 1x1 a flat range of all n*h*w pixels (grid.x
+// tiles, grid.z = 1), for the 3x3 a range of one image (grid.z = images) plus one image row and
+// one pixel of halo on both sides -- and the four waves split the output channels (MT M-tiles
+// each).  Input channels are walked in chunks of 64 through two LDS buffers: the next chunk is
+// requested from HBM before the current chunk's MFMAs are issued and written to the other
+// buffer (BN+ReLU applied, rounded to bf16) after them: one barrier per chunk, load latency
+// under the matrix work.  TIN = u16 (bf16) or float (the gradient slab).  STATS: per-tile
+// (count, mean, M2) of the rounded outputs, as in the fp32 kernels: spart[(m*T + tile)*3].
 template <int TAPS, int MT, typename TIN, bool PRO, bool STATS>
 __global__ __launch_bounds__(256) void k_conv(
     const TIN* __restrict__ in, int64_t in_ld, const u16* __restrict__ Wp, int M16, int K32,
-    u16* __restrict__ out, int64_t out_ld, int cin, int cout, int H, int W,
+    u16* __restrict__ out, int64_t out_ld, int cin, int cout, int H, int W, int64_t Ptot,
     const float2* __restrict__ fold, float* __restrict__ spart, int sT) {
   extern __shared__ u16 lds[];
-  constexpr int KC = 32, PITCH = KC + 8;  // elements per staged pixel (80 bytes: spreads banks)
+  constexpr int KC = 64, PITCH = KC + 8;  // elements per staged pixel (144 bytes: spreads banks)
+  constexpr int U = TAPS == 9 ? 8 : 2;    // 16-byte vectors per thread and chunk (3x3: W <= 95)
   const int HW = H * W;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 15, g = lane >> 4;
-  const int q0 = blockIdx.x * 64, img = blockIdx.z;
+  const int img = TAPS == 9 ? blockIdx.z : 0;
+  const int64_t q0 = (int64_t)blockIdx.x * 64;
+  const int64_t limit = TAPS == 9 ? (int64_t)HW : Ptot;  // pixels of the range q0 indexes
   const int halo = (TAPS == 9) ? W + 1 : 0;
-  const int seg = 64 + 2 * halo;
+  const int seg = 64 + 2 * halo, nvec = seg * 8, BUFE = seg * PITCH;
   const TIN* inb = in + (int64_t)img * HW * in_ld;
   const int mbase = (blockIdx.y * 4 + wave) * (MT * 16);
   const bool m_ok = mbase < M16;
@@ -232,69 +240,156 @@ __global__ __launch_bounds__(256) void k_conv(
   bool lok[4], rok[4];
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
-    const int wc = (q0 + t * 16 + j) % W;
+    const int wc = (int)((q0 + t * 16 + j) % W);
     lok[t] = wc != 0;
     rok[t] = wc != W - 1;
   }
 
-  for (int c0 = 0; c0 < cin; c0 += KC) {
+  // PRO: the folded BN (scale, shift) of all input channels is copied to LDS once, behind the two
+  // tile buffers (the staging reads it for every vector it transforms)
+  float* flds = reinterpret_cast<float*>(lds + 2 * BUFE);  // 2*BUFE*2 bytes is a multiple of 16
+  if (PRO) {
+    for (int i = tid; i < cin; i += 256) {
+      const float2 fl = fold[i];
+      flds[2 * i] = fl.x; flds[2 * i + 1] = fl.y;
+    }
     __syncthreads();
-    // stage seg pixels x 32 channels; thread = (pixel, 8-channel vector)
-    for (int idx = tid; idx < seg * 4; idx += 256) {
-      const int s = idx >> 2, v = idx & 3;
-      const int q = q0 - halo + s, ch = c0 + 8 * v;
-      V8 o;
-      o.q = make_uint4(0u, 0u, 0u, 0u);
-      if (q >= 0 && q < HW && ch < cin) {  // cin % 8 == 0: a vector is entirely in or out
-        float f[8];
+  }
+
+  struct Raw { uint4 a, b; };  // bf16: a only; float: 8 floats
+  auto request = [&](int c0, Raw(&v)[U]) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int idx = u * 256 + tid;
+      if (idx < nvec) {
+        const int s = idx >> 3, ch = min(c0 + 8 * (idx & 7), cin - 8);  // cin % 8 == 0
+        const int64_t q = min(max(q0 - halo + s, (int64_t)0), limit - 1);
         if (sizeof(TIN) == 2) {
-          V8 r;
-          r.q = *reinterpret_cast<const uint4*>(reinterpret_cast<const u16*>(inb) + (int64_t)q * in_ld + ch);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) f[e] = bf2f(r.h[e]);
+          v[u].a = *reinterpret_cast<const uint4*>(reinterpret_cast<const u16*>(inb) + q * in_ld + ch);
         } else {
-          const float* pf = reinterpret_cast<const float*>(inb) + (int64_t)q * in_ld + ch;
-          const float4 a = *reinterpret_cast<const float4*>(pf), b = *reinterpret_cast<const float4*>(pf + 4);
-          f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w; f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+          const float* pf = reinterpret_cast<const float*>(inb) + q * in_ld + ch;
+          v[u].a = *reinterpret_cast<const uint4*>(pf);
+          v[u].b = *reinterpret_cast<const uint4*>(pf + 4);
         }
-        if (PRO) {
+      }
+    }
+  };
+  auto deposit = [&](int c0, const Raw(&v)[U], int boff) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const float2 fl = fold[ch + e];
-            f[e] = fmaxf(__fmaf_rn(f[e], fl.x, fl.y), 0.f);
+    for (int u = 0; u < U; ++u) {
+      const int idx = u * 256 + tid;
+      if (idx < nvec) {
+        const int s = idx >> 3, vv = idx & 7, ch = c0 + 8 * vv;
+        const int64_t q = q0 - halo + s;
+        V8 o;
+        o.q = make_uint4(0u, 0u, 0u, 0u);
+        if (q >= 0 && q < limit && ch < cin) {  // a vector is entirely in or out
+          float f[8];
+          if (sizeof(TIN) == 2) {
+            V8 r;
+            r.q = v[u].a;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) f[e] = bf2f(r.h[e]);
+          } else {
+            f[0] = __uint_as_float(v[u].a.x); f[1] = __uint_as_float(v[u].a.y);
+            f[2] = __uint_as_float(v[u].a.z); f[3] = __uint_as_float(v[u].a.w);
+            f[4] = __uint_as_float(v[u].b.x); f[5] = __uint_as_float(v[u].b.y);
+            f[6] = __uint_as_float(v[u].b.z); f[7] = __uint_as_float(v[u].b.w);
+          }
+          if (PRO) {
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {  // (scale, shift) pairs from their LDS copy, 16 bytes at a time
+              const float4 fl = *reinterpret_cast<const float4*>(&flds[2 * (ch + e)]);
+              f[e] = fmaxf(__fmaf_rn(f[e], fl.x, fl.y), 0.f);
+              f[e + 1] = fmaxf(__fmaf_rn(f[e + 1], fl.z, fl.w), 0.f);
+            }
+          }
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o.h[e] = f2bf(f[e]);
+        }
+        *reinterpret_cast<uint4*>(&lds[boff + s * PITCH + 8 * vv]) = o.q;
+      }
+    }
+  };
+
+  // packed weights of one (chunk, tap): MT M-tiles x 2 K-steps, 16 bytes per lane each; loaded one
+  // (chunk, tap) ahead of their use so the L2 latency is under the previous tap's MFMAs
+  struct WSet { uint4 w[MT][2]; };
+  auto wload = [&](int c0, int t9, WSet& ws) {
+    const int ksteps = min(2, (K32 - c0) >> 5);
+#pragma unroll
+    for (int a = 0; a < MT; ++a)
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk)
+        ws.w[a][kk] = (m_ok && kk < ksteps && mbase + a * 16 < M16)
+                          ? *reinterpret_cast<const uint4*>(Wp + ((int64_t)t9 * M16 + mbase + a * 16 + j) * K32 +
+                                                            c0 + kk * 32 + 8 * g)
+                          : make_uint4(0u, 0u, 0u, 0u);
+  };
+
+  // activations: the 1x1 keeps three chunks requested ahead of the one being multiplied (its
+  // chunks carry little matrix work), the 3x3 one
+  constexpr int AHEAD = TAPS == 1 ? 3 : 1;
+  Raw va[U], vb[U], vc[U];  // chunks i+1, i+2, i+3 (1x1); va only (3x3)
+  {
+    Raw v[U];
+    request(0, v);
+    if (KC < cin) request(KC, va);
+    if (AHEAD >= 2 && 2 * KC < cin) request(2 * KC, vb);
+    deposit(0, v, 0);
+  }
+  WSet wcur, wnext;
+  wload(0, 0, wcur);
+  __syncthreads();
+
+  int it = 0;
+  for (int c0 = 0; c0 < cin; c0 += KC, ++it) {
+    const int boff = (it & 1) * BUFE;
+    const bool more = c0 + KC < cin;
+    if (AHEAD >= 3 && c0 + 3 * KC < cin) request(c0 + 3 * KC, vc);
+    const int ksteps = min(2, (K32 - c0) >> 5);
+#pragma unroll
+    for (int t9 = 0; t9 < TAPS; ++t9) {
+      const int di = (TAPS == 9) ? t9 / 3 - 1 : 0, dj = (TAPS == 9) ? t9 % 3 - 1 : 0;
+      // weights of the next (chunk, tap)
+      if (t9 + 1 < TAPS) wload(c0, t9 + 1, wnext);
+      else if (more) wload(c0 + KC, 0, wnext);
+      if (m_ok) {
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+          if (kk < ksteps) {
+            V8 bfrag[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+              bfrag[t].q = *reinterpret_cast<const uint4*>(
+                  &lds[boff + (t * 16 + j + halo + di * W + dj) * PITCH + kk * 32 + 8 * g]);
+              if ((dj < 0 && !lok[t]) || (dj > 0 && !rok[t])) bfrag[t].q = make_uint4(0u, 0u, 0u, 0u);
+            }
+#pragma unroll
+            for (int a = 0; a < MT; ++a) {
+              V8 w;
+              w.q = wcur.w[a][kk];
+#pragma unroll
+              for (int t = 0; t < 4; ++t) acc[a][t] = mfma_bf16(w, bfrag[t], acc[a][t]);
+            }
           }
         }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o.h[e] = f2bf(f[e]);
       }
-      *reinterpret_cast<uint4*>(&lds[s * PITCH + 8 * v]) = o.q;
+      wcur = wnext;
+    }
+    if (more) deposit(c0 + KC, va, ((it & 1) ^ 1) * BUFE);
+    if (AHEAD >= 3) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) { va[u] = vb[u]; vb[u] = vc[u]; }
+    } else if (c0 + 2 * KC < cin) {
+      request(c0 + 2 * KC, va);  // 3x3: chunk i+2, in flight across the barrier and the next chunk's MFMAs
     }
     __syncthreads();
-    if (m_ok) {
-#pragma unroll
-      for (int t9 = 0; t9 < TAPS; ++t9) {
-        const int di = (TAPS == 9) ? t9 / 3 - 1 : 0, dj = (TAPS == 9) ? t9 % 3 - 1 : 0;
-        V8 bfrag[4];
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          bfrag[t].q = *reinterpret_cast<const uint4*>(&lds[(t * 16 + j + halo + di * W + dj) * PITCH + 8 * g]);
-          if ((dj < 0 && !lok[t]) || (dj > 0 && !rok[t])) bfrag[t].q = make_uint4(0u, 0u, 0u, 0u);
-        }
-#pragma unroll
-        for (int a = 0; a < MT; ++a) {
-          if (mbase + a * 16 < M16) {
-            V8 w;
-            w.q = *reinterpret_cast<const uint4*>(Wp + ((int64_t)t9 * M16 + mbase + a * 16 + j) * K32 + c0 + 8 * g);
-#pragma unroll
-            for (int t = 0; t < 4; ++t) acc[a][t] = mfma_bf16(w, bfrag[t], acc[a][t]);
-          }
-        }
-      }
-    }
   }
 
   if (!m_ok) return;
-  const int tile_px = min(64, HW - q0);
+  const int tile_px = (int)min((int64_t)64, limit - q0);
+  const int tile_id = TAPS == 9 ? img * gridDim.x + blockIdx.x : blockIdx.x;
 #pragma unroll
   for (int a = 0; a < MT; ++a) {
     if (mbase + a * 16 >= M16) continue;
@@ -309,7 +404,7 @@ __global__ __launch_bounds__(256) void k_conv(
       for (int r = 0; r < 4; ++r) {
         float s = 0.f;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) s += (q0 + t * 16 + j < HW) ? rv[t][r] : 0.f;
+        for (int t = 0; t < 4; ++t) s += (q0 + t * 16 + j < limit) ? rv[t][r] : 0.f;
 #pragma unroll
         for (int off = 1; off < 16; off <<= 1) s += __shfl_xor(s, off, 64);
         const float mu = s / (float)tile_px;
@@ -317,21 +412,22 @@ __global__ __launch_bounds__(256) void k_conv(
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
           const float d = rv[t][r] - mu;
-          m2 += (q0 + t * 16 + j < HW) ? d * d : 0.f;
+          m2 += (q0 + t * 16 + j < limit) ? d * d : 0.f;
         }
 #pragma unroll
         for (int off = 1; off < 16; off <<= 1) m2 += __shfl_xor(m2, off, 64);
         const int m = mbase + a * 16 + 4 * g + r;
         if (j == 0 && m < cout) {
-          float* p = spart + ((int64_t)m * sT + (int64_t)img * gridDim.x + blockIdx.x) * 3;
+          float* p = spart + ((int64_t)m * sT + tile_id) * 3;
           p[0] = (float)tile_px; p[1] = mu; p[2] = m2;
         }
       }
     }
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      const int q = q0 + t * 16 + j, m = mbase + a * 16 + 4 * g;
-      if (q < HW && m < cout) {  // cout % 4 == 0 on this path
+      const int64_t q = q0 + t * 16 + j;
+      const int m = mbase + a * 16 + 4 * g;
+      if (q < limit && m < cout) {  // cout % 4 == 0 on this path
         u16* o = out + ((int64_t)img * HW + q) * out_ld + m;
         uint2 pk;
         pk.x = (unsigned)f2bf(acc[a][t][0]) | ((unsigned)f2bf(acc[a][t][1]) << 16);
@@ -648,16 +744,19 @@ hipError_t conv(const void* in, int64_t in_ld, bool in_f32, const void* Wp, void
   int mt = (mtiles + 3) / 4;
   if (mt > 3) mt = 3;
   const int gy = (mtiles + 4 * mt - 1) / (4 * mt);
-  dim3 grid((unsigned)((hw + 63) / 64), (unsigned)gy, (unsigned)n);
-  const int T = (int)grid.x * n;
+  const int64_t P = (int64_t)n * hw;
+  // 1x1: flat 64-pixel tiles over all images; 3x3: tiles of one image
+  dim3 grid(taps == 9 ? (unsigned)((hw + 63) / 64) : (unsigned)((P + 63) / 64), (unsigned)gy,
+            taps == 9 ? (unsigned)n : 1u);
+  const int T = taps == 9 ? (int)grid.x * n : (int)grid.x;
   if (sT) *sT = T;
   const int halo = taps == 9 ? w + 1 : 0;
-  const size_t lds = (size_t)(64 + 2 * halo) * 40 * sizeof(u16);
-  if (lds > 64 * 1024) return hipErrorInvalidValue;
+  const size_t lds = (size_t)2 * (64 + 2 * halo) * 72 * sizeof(u16) + (fold ? (size_t)cin * 8 : 0);
+  if (lds > 64 * 1024 || (taps == 9 && (64 + 2 * halo) * 8 > 8 * 256)) return hipErrorInvalidValue;
   if ((fold != nullptr) != (spart != nullptr) && fold) return hipErrorInvalidValue;
 #define DNB_K(TAPS, MT, TIN, PRO, STATS)                                                                 \
   hipLaunchKernelGGL((k_conv<TAPS, MT, TIN, PRO, STATS>), grid, dim3(256), lds, st, (const TIN*)in, in_ld, \
-                     (const u16*)Wp, M16, K32, (u16*)out, out_ld, cin, cout, h, w, fold, spart, T)
+                     (const u16*)Wp, M16, K32, (u16*)out, out_ld, cin, cout, h, w, P, fold, spart, T)
 #define DNB_K2(TAPS, MT)                                                              \
   do {                                                                                \
     if (in_f32) DNB_K(TAPS, MT, float, false, false);                                 \
