@@ -551,6 +551,188 @@ __global__ __launch_bounds__(256) void k_wgrad(
     }
 }
 
+// 3x3 weight gradient with the activation tile staged once.  A tile is R image rows of one image;
+// aT[c][row][x] holds rows r0-1 .. r0+R of the (prologue-applied) activations, pixel-contiguous
+// per channel with 8 zero pixels on either side of each row, so a tap is the same tile read at a
+// shifted position: the centre column is one aligned 16-byte read, the left and right columns
+// are that read funnel-shifted by one element with the neighbouring dword.  gT[m][row][x] holds
+// the gradient tile.  A K-step is four 8-pixel row fragments (one per lane group).  Rows of both
+// arrays are permuted (channel 8v+e sits in row v+8e) so that the staging stores of one wave
+// spread over all banks.  Everything the staging loops do not write stays zero from the initial
+// fill: the row margins, fragments past the tile, channels past cin / cout.
+constexpr int WG3_AP = 328, WG3_GP = 136;  // row pitches, both = 8 (mod 64) elements
+constexpr int WG3_ROWPIX = 320;            // (R+2) * (8*FR+16) must fit in this
+struct Wg3Geom {
+  bool ok;
+  int R, FR, tpi;
+};
+static Wg3Geom wg3_geom(int h, int w) {
+  Wg3Geom q{};
+  q.FR = (w + 7) / 8;
+  const int XP = q.FR * 8 + 16;
+  if (3 * XP > WG3_ROWPIX) return q;
+  int R = WG3_ROWPIX / XP - 2;
+  if (R > 16 / q.FR) R = 16 / q.FR;
+  if (R > h) R = h;
+  q.R = R;
+  q.tpi = (h + R - 1) / R;
+  q.ok = true;
+  return q;
+}
+
+template <typename TG, bool PRO>
+__global__ __launch_bounds__(256) void k_wgrad3(
+    const u16* __restrict__ a, int64_t a_ld, const TG* __restrict__ gout, int64_t g_ld,
+    float* __restrict__ part, int cin, int cout, int n, int H, int W, int R, int FR, int tiles_per_img,
+    int tiles_per_split, const float2* __restrict__ fold) {
+  constexpr int AP = WG3_AP, GP = WG3_GP;
+  __shared__ __attribute__((aligned(16))) u16 aT[64 * AP];
+  __shared__ __attribute__((aligned(16))) u16 gT[64 * GP];
+  const int RW = FR * 8, XP = RW + 16, F = R * FR, KS = (F + 3) >> 2;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = lane & 15, g = lane >> 4, v = tid & 7;
+  const int c0 = blockIdx.y * 64, m0 = blockIdx.z * 64;
+  const int total_tiles = n * tiles_per_img;
+  const int t_begin = blockIdx.x * tiles_per_split, t_end = min(total_tiles, t_begin + tiles_per_split);
+
+  for (int i = tid; i < 64 * AP / 8; i += 256) reinterpret_cast<uint4*>(aT)[i] = make_uint4(0u, 0u, 0u, 0u);
+  for (int i = tid; i < 64 * GP / 8; i += 256) reinterpret_cast<uint4*>(gT)[i] = make_uint4(0u, 0u, 0u, 0u);
+
+  const int chv = c0 + 8 * v, mv = m0 + 8 * v;
+  const bool ch_ok = chv < cin, m_ok = mv < cout;  // cin % 8 == 0, cout % 8 == 0
+  float fs[8], fb[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    fs[e] = 0.f;
+    fb[e] = 0.f;
+    if (PRO && ch_ok) {
+      const float2 fl = fold[chv + e];
+      fs[e] = fl.x;
+      fb[e] = fl.y;
+    }
+  }
+  int boff[4];  // per K-step: offset of this lane group's fragment inside an aT row block
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const int f = 4 * s + g, fv = f < F ? f : 0;  // fragments past the tile meet zeros in gT
+    const int r = fv / FR;
+    boff[s] = r * XP + (fv - r * FR) * 8;
+  }
+
+  f32x4 acc[9][4];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int y = 0; y < 4; ++y) acc[t][y] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  const int na = (R + 2) * RW * 8, ng = R * RW * 8;
+  for (int tile = t_begin; tile < t_end; ++tile) {
+    const int img = tile / tiles_per_img, r0 = (tile - img * tiles_per_img) * R;
+    const u16* ab = a + (int64_t)img * H * W * a_ld;
+    const TG* gb = gout + (int64_t)img * H * W * g_ld;
+    __syncthreads();
+    if (ch_ok) {
+      for (int i0 = tid; i0 < na; i0 += 1024) {
+        V8 raw[4];
+        int dst[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int idx = i0 + 256 * u, pos = idx >> 3;
+          const int rr = pos / RW, x = pos - rr * RW, ir = r0 - 1 + rr;
+          dst[u] = idx < na ? rr * XP + 8 + x : -1;
+          raw[u].q = make_uint4(0u, 0u, 0u, 0u);
+          if (idx < na && ir >= 0 && ir < H && x < W) {
+            raw[u].q = *reinterpret_cast<const uint4*>(ab + ((int64_t)ir * W + x) * a_ld + chv);
+            if (PRO) {
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                raw[u].h[e] = f2bf(fmaxf(__fmaf_rn(bf2f(raw[u].h[e]), fs[e], fb[e]), 0.f));
+            }
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (dst[u] >= 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) aT[(v + 8 * e) * AP + dst[u]] = raw[u].h[e];
+          }
+      }
+    }
+    if (m_ok) {
+      for (int i0 = tid; i0 < ng; i0 += 1024) {
+        V8 raw[4];
+        int dst[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int idx = i0 + 256 * u, pos = idx >> 3;
+          const int r = pos / RW, x = pos - r * RW, ir = r0 + r;
+          dst[u] = idx < ng ? pos : -1;
+          raw[u].q = make_uint4(0u, 0u, 0u, 0u);
+          if (idx < ng && ir < H && x < W) {
+            const int64_t q = (int64_t)ir * W + x;
+            if (sizeof(TG) == 2) {
+              raw[u].q = *reinterpret_cast<const uint4*>(reinterpret_cast<const u16*>(gb) + q * g_ld + mv);
+            } else {
+              const float* pf = reinterpret_cast<const float*>(gb) + q * g_ld + mv;
+              const float4 lo = *reinterpret_cast<const float4*>(pf), hi = *reinterpret_cast<const float4*>(pf + 4);
+              raw[u].h[0] = f2bf(lo.x); raw[u].h[1] = f2bf(lo.y); raw[u].h[2] = f2bf(lo.z); raw[u].h[3] = f2bf(lo.w);
+              raw[u].h[4] = f2bf(hi.x); raw[u].h[5] = f2bf(hi.y); raw[u].h[6] = f2bf(hi.z); raw[u].h[7] = f2bf(hi.w);
+            }
+          }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (dst[u] >= 0) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) gT[(v + 8 * e) * GP + dst[u]] = raw[u].h[e];
+          }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      if (s < KS) {
+        V8 af;
+        af.q = *reinterpret_cast<const uint4*>(&gT[(wave * 16 + j) * GP + (4 * s + g) * 8]);
+        const int lb = j * AP + boff[s] + 8;
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+#pragma unroll
+          for (int d = 0; d < 3; ++d) {  // image row offset d - 1
+            const int base = lb + y * 16 * AP + d * XP;
+            V8 cur, lf, rf;
+            cur.q = *reinterpret_cast<const uint4*>(&aT[base]);
+            const unsigned prev = *reinterpret_cast<const unsigned*>(&aT[base - 2]);
+            const unsigned next = *reinterpret_cast<const unsigned*>(&aT[base + 8]);
+            const unsigned s0 = __builtin_amdgcn_alignbit(cur.q.y, cur.q.x, 16);
+            const unsigned s1 = __builtin_amdgcn_alignbit(cur.q.z, cur.q.y, 16);
+            const unsigned s2 = __builtin_amdgcn_alignbit(cur.q.w, cur.q.z, 16);
+            lf.q = make_uint4(__builtin_amdgcn_alignbit(cur.q.x, prev, 16), s0, s1, s2);
+            rf.q = make_uint4(s0, s1, s2, __builtin_amdgcn_alignbit(next, cur.q.w, 16));
+            acc[d * 3 + 0][y] = mfma_bf16(af, lf, acc[d * 3 + 0][y]);
+            acc[d * 3 + 1][y] = mfma_bf16(af, cur, acc[d * 3 + 1][y]);
+            acc[d * 3 + 2][y] = mfma_bf16(af, rf, acc[d * 3 + 2][y]);
+          }
+        }
+      }
+    }
+  }
+
+  float* pb = part + (int64_t)blockIdx.x * cout * cin * 9;
+#pragma unroll
+  for (int y = 0; y < 4; ++y) {
+    const int rc = y * 16 + j, c = c0 + 8 * (rc & 7) + (rc >> 3);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int rm = wave * 16 + 4 * g + r, m = m0 + 8 * (rm & 7) + (rm >> 3);
+      if (m < cout && c < cin) {
+#pragma unroll
+        for (int t9 = 0; t9 < 9; ++t9) pb[((int64_t)m * cin + c) * 9 + t9] = acc[t9][y][r];
+      }
+    }
+  }
+}
+
 // ----------------------------------------------------------------------------- BN + ReLU backward
 
 // Thread = (pixel row pr, 8-channel vector cv); workgroup = 256 threads covering `rows` pixels per
@@ -775,8 +957,12 @@ hipError_t conv(const void* in, int64_t in_ld, bool in_f32, const void* Wp, void
   return hipGetLastError();
 }
 
-int wgrad_splits(int n, int cin, int cout, int h, int w) {
-  const int tiles = n * ((h * w + 63) / 64);
+static int wgrad_tiles(int n, int h, int w, int taps) {
+  const Wg3Geom q = wg3_geom(h, w);
+  return (taps == 9 && q.ok) ? n * q.tpi : n * ((h * w + 63) / 64);
+}
+int wgrad_splits(int n, int cin, int cout, int h, int w, int taps) {
+  const int tiles = wgrad_tiles(n, h, w, taps);
   const int gy = (cin + 63) / 64, gz = (cout + 63) / 64;
   int s = 1024 / (gy * gz);
   if (s < 1) s = 1;
@@ -786,18 +972,29 @@ int wgrad_splits(int n, int cin, int cout, int h, int w) {
   return (tiles + tps - 1) / tps;
 }
 size_t wgrad_partial_floats(int n, int cin, int cout, int h, int w, int taps) {
-  return (size_t)wgrad_splits(n, cin, cout, h, w) * cin * cout * taps;
+  return (size_t)wgrad_splits(n, cin, cout, h, w, taps) * cin * cout * taps;
 }
 
 // g_f32: the gradient operand is the fp32 slab (3x3), else bf16 (1x1).  The caller adds the
 // partials (launch_sum_partials) -- *splits says how many.
 hipError_t wgrad(const void* a, int64_t a_ld, const void* g, int64_t g_ld, bool g_f32, float* part, int n, int cin,
                  int cout, int h, int w, int taps, const float2* fold, int* splits, hipStream_t st) {
-  const int tpi = (h * w + 63) / 64, tiles = n * tpi;
-  const int S = wgrad_splits(n, cin, cout, h, w);
+  const Wg3Geom q3 = wg3_geom(h, w);
+  const bool three = taps == 9 && q3.ok;
+  const int tpi = three ? q3.tpi : (h * w + 63) / 64, tiles = n * tpi;
+  const int S = wgrad_splits(n, cin, cout, h, w, taps);
   const int tps = (tiles + S - 1) / S;
   *splits = S;
   dim3 grid((unsigned)S, (unsigned)((cin + 63) / 64), (unsigned)((cout + 63) / 64));
+  if (three) {
+#define DNB_W3(TG, PRO)                                                                                \
+  hipLaunchKernelGGL((k_wgrad3<TG, PRO>), grid, dim3(256), 0, st, (const u16*)a, a_ld, (const TG*)g, \
+                     g_ld, part, cin, cout, n, h, w, q3.R, q3.FR, tpi, tps, fold)
+    if (g_f32) { if (fold) DNB_W3(float, true); else DNB_W3(float, false); }
+    else       { if (fold) DNB_W3(u16, true); else DNB_W3(u16, false); }
+#undef DNB_W3
+    return hipGetLastError();
+  }
 #define DNB_W(TAPS, TG, PRO)                                                                              \
   hipLaunchKernelGGL((k_wgrad<TAPS, TG, PRO>), grid, dim3(256), 0, st, (const u16*)a, a_ld, (const TG*)g, \
                      g_ld, part, cin, cout, n, h, w, tpi, tps, fold)
