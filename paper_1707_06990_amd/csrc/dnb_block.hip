@@ -148,16 +148,13 @@ int backward_bf16(dnb_block* b, const float* params, const void* yv, const void*
     const unsigned short* pk1t = pack + b->pk[l] + B16 * c32;                         // 1x1 data gradient
     const unsigned short* pk3t = pack + b->pk[l] + B16 * c32 + c16 * B32 + 9 * k16 * B32;  // 3x3 data gradient
     const float* gl = G + c;  // gradient of x_l (fp32, pixel stride C_out), complete at this point
-    int splits = 0;
     // 3x3: weight gradient (BN2+ReLU of b_l recomputed in the operand staging), data gradient
-    DNB_TRY(nhwc::wgrad(bl, B, gl, cout, true, partA, n, B, k, d.h, d.w, 9, fold2, &splits, st));
-    DNB_TRY(launch_sum_partials(partA, splits, (int64_t)k * B * 9, gp.W3, st));
+    DNB_TRY(nhwc::wgrad(bl, B, gl, cout, true, partA, gp.W3, n, B, k, d.h, d.w, 9, fold2, st));
     DNB_TRY(nhwc::conv(gl, cout, true, pk3t, dS3, B, n, k, B, d.h, d.w, 9, nullptr, nullptr, nullptr, st));
     DNB_TRY(nhwc::bn_relu_bwd(bl, B, dS3, B, dS3, B, nullptr, 0, P, B, p.g2, p.b2, mean_b, istd_b, gp.g2, gp.b2,
                               part, st));
     // 1x1: weight gradient (BN1+ReLU of y[..., :C_l] recomputed in the operand staging), data gradient
-    DNB_TRY(nhwc::wgrad(y, cout, dS3, B, false, partB, n, c, B, d.h, d.w, 1, fold1, &splits, st));
-    DNB_TRY(launch_sum_partials(partB, splits, (int64_t)B * c, gp.W1, st));
+    DNB_TRY(nhwc::wgrad(y, cout, dS3, B, false, partB, gp.W1, n, c, B, d.h, d.w, 1, fold1, st));
     DNB_TRY(nhwc::conv(dS3, B, false, pk1t, dS2, c, n, B, c, d.h, d.w, 1, nullptr, nullptr, nullptr, st));
     // BN1+ReLU backward and concat backward: accumulate into the slab
     DNB_TRY(nhwc::bn_relu_bwd(y, cout, dS2, c, nullptr, 0, G, cout, P, c, p.g1, p.b1, mean_y, istd_y, gp.g1,
@@ -897,10 +894,8 @@ int dnb_op_nhwc_conv_wgrad(const void* x, int64_t x_ld, const void* dout, int64_
   if (!x || !dout || !dwgt || !scratch) return DNB_E_NULL;
   const int rc = nhwc_args_ok(n, cin, cout, h, w, ks);
   if (rc) return rc;
-  int splits = 0;
-  DNB_TRY(nhwc::wgrad(x, x_ld, dout, dout_ld, dout_is_f32 != 0, (float*)scratch, (int)n, (int)cin, (int)cout, (int)h,
-                      (int)w, ks * ks, nullptr, &splits, (hipStream_t)stream));
-  DNB_TRY(launch_sum_partials((const float*)scratch, splits, cin * cout * ks * ks, (float*)dwgt, (hipStream_t)stream));
+  DNB_TRY(nhwc::wgrad(x, x_ld, dout, dout_ld, dout_is_f32 != 0, (float*)scratch, (float*)dwgt, (int)n, (int)cin,
+                      (int)cout, (int)h, (int)w, ks * ks, nullptr, (hipStream_t)stream));
   return DNB_OK;
 }
 

@@ -135,8 +135,9 @@ hipError_t conv(const void* in, int64_t in_ld, bool in_f32, const void* Wp, void
                 int cin, int cout, int h, int w, int taps, const float2* fold, float* spart, int* sT,
                 hipStream_t st);
 size_t wgrad_partial_floats(int n, int cin, int cout, int h, int w, int taps);
-hipError_t wgrad(const void* a, int64_t a_ld, const void* g, int64_t g_ld, bool g_f32, float* part, int n, int cin,
-                 int cout, int h, int w, int taps, const float2* fold, int* splits, hipStream_t st);
+// writes per-split partials to `part` and their sum to dw ([cout][cin][taps])
+hipError_t wgrad(const void* a, int64_t a_ld, const void* g, int64_t g_ld, bool g_f32, float* part, float* dw, int n,
+                 int cin, int cout, int h, int w, int taps, const float2* fold, hipStream_t st);
 size_t bn_bwd_partial_floats(int64_t P, int c);
 hipError_t bn_relu_bwd(const void* x, int64_t x_ld, const void* dact, int64_t d_ld, void* du_bf, int64_t du_ld,
                        float* G, int64_t g_ld, int64_t P, int c, const float* gamma, const float* beta,

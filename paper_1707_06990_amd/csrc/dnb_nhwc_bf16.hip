@@ -23,11 +23,10 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16;
 
 __device__ __forceinline__ float bf2f(u16 v) { return __uint_as_float((unsigned)v << 16); }
-// round to nearest even; inputs are finite
+// round to nearest even (the hardware conversion of gfx950)
 __device__ __forceinline__ u16 f2bf(float f) {
-  unsigned u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (u16)(u >> 16);
+  const __bf16 b = (__bf16)f;
+  return __builtin_bit_cast(u16, b);
 }
 
 union V8 {          // 8 bf16 = 16 bytes
@@ -562,6 +561,7 @@ __global__ __launch_bounds__(256) void k_wgrad(
 // fill: the row margins, fragments past the tile, channels past cin / cout.
 constexpr int WG3_AP = 328, WG3_GP = 136;  // row pitches, both = 8 (mod 64) elements
 constexpr int WG3_ROWPIX = 320;            // (R+2) * (8*FR+16) must fit in this
+constexpr int WG3_BLOCK = 64 * 64 * 9;     // partial floats per (split, c group, m group)
 struct Wg3Geom {
   bool ok;
   int R, FR, tpi;
@@ -581,7 +581,7 @@ static Wg3Geom wg3_geom(int h, int w) {
 }
 
 template <typename TG, bool PRO>
-__global__ __launch_bounds__(256) void k_wgrad3(
+__global__ __launch_bounds__(512) void k_wgrad3(
     const u16* __restrict__ a, int64_t a_ld, const TG* __restrict__ gout, int64_t g_ld,
     float* __restrict__ part, int cin, int cout, int n, int H, int W, int R, int FR, int tiles_per_img,
     int tiles_per_split, const float2* __restrict__ fold) {
@@ -589,24 +589,26 @@ __global__ __launch_bounds__(256) void k_wgrad3(
   __shared__ __attribute__((aligned(16))) u16 aT[64 * AP];
   __shared__ __attribute__((aligned(16))) u16 gT[64 * GP];
   const int RW = FR * 8, XP = RW + 16, F = R * FR, KS = (F + 3) >> 2;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // eight waves: wave & 3 = m-tile of the group, wave >> 2 = which pair of the four c-tiles
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, mw = wave & 3, yh = wave >> 2;
   const int j = lane & 15, g = lane >> 4, v = tid & 7;
   const int c0 = blockIdx.y * 64, m0 = blockIdx.z * 64;
   const int total_tiles = n * tiles_per_img;
   const int t_begin = blockIdx.x * tiles_per_split, t_end = min(total_tiles, t_begin + tiles_per_split);
 
-  for (int i = tid; i < 64 * AP / 8; i += 256) reinterpret_cast<uint4*>(aT)[i] = make_uint4(0u, 0u, 0u, 0u);
-  for (int i = tid; i < 64 * GP / 8; i += 256) reinterpret_cast<uint4*>(gT)[i] = make_uint4(0u, 0u, 0u, 0u);
+  for (int i = tid; i < 64 * AP / 8; i += 512) reinterpret_cast<uint4*>(aT)[i] = make_uint4(0u, 0u, 0u, 0u);
+  for (int i = tid; i < 64 * GP / 8; i += 512) reinterpret_cast<uint4*>(gT)[i] = make_uint4(0u, 0u, 0u, 0u);
 
   const int chv = c0 + 8 * v, mv = m0 + 8 * v;
   const bool ch_ok = chv < cin, m_ok = mv < cout;  // cin % 8 == 0, cout % 8 == 0
+  const int chl = ch_ok ? chv : 0, ml = m_ok ? mv : 0;  // load addresses stay inside the tensors
   float fs[8], fb[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     fs[e] = 0.f;
     fb[e] = 0.f;
-    if (PRO && ch_ok) {
-      const float2 fl = fold[chv + e];
+    if (PRO) {
+      const float2 fl = fold[chl + e];
       fs[e] = fl.x;
       fb[e] = fl.y;
     }
@@ -619,117 +621,176 @@ __global__ __launch_bounds__(256) void k_wgrad3(
     boff[s] = r * XP + (fv - r * FR) * 8;
   }
 
-  f32x4 acc[9][4];
+  f32x4 acc[9][2];
 #pragma unroll
   for (int t = 0; t < 9; ++t)
 #pragma unroll
-    for (int y = 0; y < 4; ++y) acc[t][y] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int y = 0; y < 2; ++y) acc[t][y] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  const int na = (R + 2) * RW * 8, ng = R * RW * 8;
-  for (int tile = t_begin; tile < t_end; ++tile) {
+  // Software pipeline: the global loads of tile i+1 are issued before the MFMA phase of tile i
+  // and deposited (prologue, bf16 rounding, transposing 2-byte stores) after it.  Every load is
+  // unconditional at a clamped in-range address, so none of them waits for another; what lies
+  // outside the image or the tile is replaced by zero when it is deposited.
+  const int na = (R + 2) * RW * 8, ng = R * RW * 8;  // at most 5 and 2 vectors per thread
+  uint4 ra[5], rg[2];  // kept as whole vectors across the MFMA phase; taken apart only in deposit
+  float4 rgl[2], rgh[2];
+  auto issue = [&](int tile) {
     const int img = tile / tiles_per_img, r0 = (tile - img * tiles_per_img) * R;
-    const u16* ab = a + (int64_t)img * H * W * a_ld;
-    const TG* gb = gout + (int64_t)img * H * W * g_ld;
-    __syncthreads();
-    if (ch_ok) {
-      for (int i0 = tid; i0 < na; i0 += 1024) {
-        V8 raw[4];
-        int dst[4];
+    const u16* ab = a + (int64_t)img * H * W * a_ld + chl;
+    const TG* gb = gout + (int64_t)img * H * W * g_ld + ml;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int idx = i0 + 256 * u, pos = idx >> 3;
-          const int rr = pos / RW, x = pos - rr * RW, ir = r0 - 1 + rr;
-          dst[u] = idx < na ? rr * XP + 8 + x : -1;
-          raw[u].q = make_uint4(0u, 0u, 0u, 0u);
-          if (idx < na && ir >= 0 && ir < H && x < W) {
-            raw[u].q = *reinterpret_cast<const uint4*>(ab + ((int64_t)ir * W + x) * a_ld + chv);
-            if (PRO) {
+    for (int u = 0; u < 5; ++u) {
+      const int pos = (tid + 512 * u) >> 3;
+      const int rr = pos / RW, x = min(pos - rr * RW, W - 1), ir = min(max(r0 - 1 + rr, 0), H - 1);
+      ra[u] = *reinterpret_cast<const uint4*>(ab + ((int64_t)ir * W + x) * a_ld);
+    }
 #pragma unroll
-              for (int e = 0; e < 8; ++e)
-                raw[u].h[e] = f2bf(fmaxf(__fmaf_rn(bf2f(raw[u].h[e]), fs[e], fb[e]), 0.f));
-            }
-          }
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-          if (dst[u] >= 0) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) aT[(v + 8 * e) * AP + dst[u]] = raw[u].h[e];
-          }
+    for (int u = 0; u < 2; ++u) {
+      const int pos = (tid + 512 * u) >> 3;
+      const int r = pos / RW, x = min(pos - r * RW, W - 1), ir = min(r0 + r, H - 1);
+      const int64_t q = (int64_t)ir * W + x;
+      if (sizeof(TG) == 2) {
+        rg[u] = *reinterpret_cast<const uint4*>(reinterpret_cast<const u16*>(gb) + q * g_ld);
+      } else {
+        const float* pf = reinterpret_cast<const float*>(gb) + q * g_ld;
+        rgl[u] = *reinterpret_cast<const float4*>(pf);
+        rgh[u] = *reinterpret_cast<const float4*>(pf + 4);
       }
     }
-    if (m_ok) {
-      for (int i0 = tid; i0 < ng; i0 += 1024) {
-        V8 raw[4];
-        int dst[4];
+  };
+  auto deposit = [&](int tile) {
+    const int img = tile / tiles_per_img, r0 = (tile - img * tiles_per_img) * R;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int idx = i0 + 256 * u, pos = idx >> 3;
-          const int r = pos / RW, x = pos - r * RW, ir = r0 + r;
-          dst[u] = idx < ng ? pos : -1;
-          raw[u].q = make_uint4(0u, 0u, 0u, 0u);
-          if (idx < ng && ir < H && x < W) {
-            const int64_t q = (int64_t)ir * W + x;
-            if (sizeof(TG) == 2) {
-              raw[u].q = *reinterpret_cast<const uint4*>(reinterpret_cast<const u16*>(gb) + q * g_ld + mv);
-            } else {
-              const float* pf = reinterpret_cast<const float*>(gb) + q * g_ld + mv;
-              const float4 lo = *reinterpret_cast<const float4*>(pf), hi = *reinterpret_cast<const float4*>(pf + 4);
-              raw[u].h[0] = f2bf(lo.x); raw[u].h[1] = f2bf(lo.y); raw[u].h[2] = f2bf(lo.z); raw[u].h[3] = f2bf(lo.w);
-              raw[u].h[4] = f2bf(hi.x); raw[u].h[5] = f2bf(hi.y); raw[u].h[6] = f2bf(hi.z); raw[u].h[7] = f2bf(hi.w);
-            }
-          }
+    for (int u = 0; u < 5; ++u) {
+      const int idx = tid + 512 * u, pos = idx >> 3;
+      const int rr = pos / RW, x = pos - rr * RW, ir = r0 - 1 + rr;
+      if (ch_ok && idx < na) {
+        const bool in = ir >= 0 && ir < H && x < W;
+        const int dst = rr * XP + 8 + x;
+        V8 t;
+        t.q = ra[u];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          u16 hv = t.h[e];
+          if (PRO) hv = f2bf(fmaxf(__fmaf_rn(bf2f(hv), fs[e], fb[e]), 0.f));
+          aT[(v + 8 * e) * AP + dst] = in ? hv : (u16)0;
         }
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-          if (dst[u] >= 0) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) gT[(v + 8 * e) * GP + dst[u]] = raw[u].h[e];
-          }
       }
     }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int idx = tid + 512 * u, pos = idx >> 3;
+      const int r = pos / RW, x = pos - r * RW, ir = r0 + r;
+      if (m_ok && idx < ng) {
+        const bool in = ir < H && x < W;
+        V8 t;
+        if (sizeof(TG) == 2) {
+          t.q = rg[u];
+        } else {
+          t.h[0] = f2bf(rgl[u].x); t.h[1] = f2bf(rgl[u].y); t.h[2] = f2bf(rgl[u].z); t.h[3] = f2bf(rgl[u].w);
+          t.h[4] = f2bf(rgh[u].x); t.h[5] = f2bf(rgh[u].y); t.h[6] = f2bf(rgh[u].z); t.h[7] = f2bf(rgh[u].w);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) gT[(v + 8 * e) * GP + pos] = in ? t.h[e] : (u16)0;
+      }
+    }
+  };
+
+  if (t_begin < t_end) issue(t_begin);
+  for (int tile = t_begin; tile < t_end; ++tile) {
+    __syncthreads();  // the previous tile's fragment reads (first pass: the zero fill) are done
+    deposit(tile);
     __syncthreads();
+    if (tile + 1 < t_end) issue(tile + 1);
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       if (s < KS) {
         V8 af;
-        af.q = *reinterpret_cast<const uint4*>(&gT[(wave * 16 + j) * GP + (4 * s + g) * 8]);
-        const int lb = j * AP + boff[s] + 8;
+        af.q = *reinterpret_cast<const uint4*>(&gT[(mw * 16 + j) * GP + (4 * s + g) * 8]);
+        const int lb = (yh * 32 + j) * AP + boff[s] + 8;
+        uint4 cq[6];
+        unsigned pv[6], nx[6];
 #pragma unroll
-        for (int y = 0; y < 4; ++y) {
+        for (int i = 0; i < 6; ++i) {  // i = c-tile of the pair * 3 + image row offset + 1
+          const int base = lb + (i / 3) * 16 * AP + (i % 3) * XP;
+          cq[i] = *reinterpret_cast<const uint4*>(&aT[base]);
+          pv[i] = *reinterpret_cast<const unsigned*>(&aT[base - 2]);
+          nx[i] = *reinterpret_cast<const unsigned*>(&aT[base + 8]);
+        }
 #pragma unroll
-          for (int d = 0; d < 3; ++d) {  // image row offset d - 1
-            const int base = lb + y * 16 * AP + d * XP;
-            V8 cur, lf, rf;
-            cur.q = *reinterpret_cast<const uint4*>(&aT[base]);
-            const unsigned prev = *reinterpret_cast<const unsigned*>(&aT[base - 2]);
-            const unsigned next = *reinterpret_cast<const unsigned*>(&aT[base + 8]);
-            const unsigned s0 = __builtin_amdgcn_alignbit(cur.q.y, cur.q.x, 16);
-            const unsigned s1 = __builtin_amdgcn_alignbit(cur.q.z, cur.q.y, 16);
-            const unsigned s2 = __builtin_amdgcn_alignbit(cur.q.w, cur.q.z, 16);
-            lf.q = make_uint4(__builtin_amdgcn_alignbit(cur.q.x, prev, 16), s0, s1, s2);
-            rf.q = make_uint4(s0, s1, s2, __builtin_amdgcn_alignbit(next, cur.q.w, 16));
-            acc[d * 3 + 0][y] = mfma_bf16(af, lf, acc[d * 3 + 0][y]);
-            acc[d * 3 + 1][y] = mfma_bf16(af, cur, acc[d * 3 + 1][y]);
-            acc[d * 3 + 2][y] = mfma_bf16(af, rf, acc[d * 3 + 2][y]);
-          }
+        for (int i = 0; i < 6; ++i) {
+          const int y = i / 3, d = i % 3;
+          V8 cur, lf, rf;
+          cur.q = cq[i];
+          const unsigned s0 = __builtin_amdgcn_alignbit(cur.q.y, cur.q.x, 16);
+          const unsigned s1 = __builtin_amdgcn_alignbit(cur.q.z, cur.q.y, 16);
+          const unsigned s2 = __builtin_amdgcn_alignbit(cur.q.w, cur.q.z, 16);
+          lf.q = make_uint4(__builtin_amdgcn_alignbit(cur.q.x, pv[i], 16), s0, s1, s2);
+          rf.q = make_uint4(s0, s1, s2, __builtin_amdgcn_alignbit(nx[i], cur.q.w, 16));
+          acc[d * 3 + 0][y] = mfma_bf16(af, lf, acc[d * 3 + 0][y]);
+          acc[d * 3 + 1][y] = mfma_bf16(af, cur, acc[d * 3 + 1][y]);
+          acc[d * 3 + 2][y] = mfma_bf16(af, rf, acc[d * 3 + 2][y]);
         }
       }
     }
   }
 
-  float* pb = part + (int64_t)blockIdx.x * cout * cin * 9;
+  // partials in accumulator order: [split][c group][m group][wave][tap][c-tile of the pair][lane][4]
+  float* pb = part + (((int64_t)blockIdx.x * gridDim.y + blockIdx.y) * gridDim.z + blockIdx.z) * WG3_BLOCK +
+              (int64_t)wave * 18 * 256 + lane * 4;
 #pragma unroll
-  for (int y = 0; y < 4; ++y) {
-    const int rc = y * 16 + j, c = c0 + 8 * (rc & 7) + (rc >> 3);
+  for (int t9 = 0; t9 < 9; ++t9)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int rm = wave * 16 + 4 * g + r, m = m0 + 8 * (rm & 7) + (rm >> 3);
-      if (m < cout && c < cin) {
+    for (int y = 0; y < 2; ++y)
+      *reinterpret_cast<float4*>(pb + (t9 * 2 + y) * 256) = make_float4(acc[t9][y][0], acc[t9][y][1], acc[t9][y][2], acc[t9][y][3]);
+}
+
+// Sums the splits of k_wgrad3's partials and writes dW[m][c][tap].  A workgroup covers 64
+// accumulator quads; its four 64-thread groups each sum every fourth split (loads batched four
+// deep), and the four results are added in group order.
+__global__ __launch_bounds__(256) void k_sum_wgrad3(const float* __restrict__ part, int S, int gy, int gz, int cin,
+                                                    int cout, float* __restrict__ dw) {
+  __shared__ float4 red[3][64];
+  const int64_t per_split = (int64_t)gy * gz * WG3_BLOCK;
+  const int t = threadIdx.x & 63, sg = threadIdx.x >> 6;
+  const int64_t i = ((int64_t)blockIdx.x * 64 + t) * 4;  // per_split is a multiple of 256
+  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+  const float* p = part + i;
+  int s = sg;
+  for (; s + 12 < S; s += 16) {
+    const float4 a0 = *reinterpret_cast<const float4*>(p + (int64_t)s * per_split);
+    const float4 a1 = *reinterpret_cast<const float4*>(p + (int64_t)(s + 4) * per_split);
+    const float4 a2 = *reinterpret_cast<const float4*>(p + (int64_t)(s + 8) * per_split);
+    const float4 a3 = *reinterpret_cast<const float4*>(p + (int64_t)(s + 12) * per_split);
+    sum.x += a0.x; sum.y += a0.y; sum.z += a0.z; sum.w += a0.w;
+    sum.x += a1.x; sum.y += a1.y; sum.z += a1.z; sum.w += a1.w;
+    sum.x += a2.x; sum.y += a2.y; sum.z += a2.z; sum.w += a2.w;
+    sum.x += a3.x; sum.y += a3.y; sum.z += a3.z; sum.w += a3.w;
+  }
+  for (; s < S; s += 4) {
+    const float4 a0 = *reinterpret_cast<const float4*>(p + (int64_t)s * per_split);
+    sum.x += a0.x; sum.y += a0.y; sum.z += a0.z; sum.w += a0.w;
+  }
+  if (sg > 0) red[sg - 1][t] = sum;
+  __syncthreads();
+  if (sg > 0) return;
 #pragma unroll
-        for (int t9 = 0; t9 < 9; ++t9) pb[((int64_t)m * cin + c) * 9 + t9] = acc[t9][y][r];
-      }
-    }
+  for (int q = 0; q < 3; ++q) {
+    const float4 o = red[q][t];
+    sum.x += o.x; sum.y += o.y; sum.z += o.z; sum.w += o.w;
+  }
+  const int blk = (int)(i / WG3_BLOCK), rem = (int)(i - (int64_t)blk * WG3_BLOCK);
+  const int by = blk / gz, bz = blk - by * gz;
+  const int lane = (rem >> 2) & 63, ty = rem >> 8;  // ty = (wave*9 + tap)*2 + c-tile of the pair
+  const int wave = ty / 18, t9 = (ty - wave * 18) >> 1, y = 2 * (wave >> 2) + (ty & 1);
+  const int j = lane & 15, g = lane >> 4;
+  const int rc = y * 16 + j, c = by * 64 + 8 * (rc & 7) + (rc >> 3);
+  if (c >= cin) return;
+  const float o4[4] = {sum.x, sum.y, sum.z, sum.w};
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int rm = (wave & 3) * 16 + 4 * g + r, m = bz * 64 + 8 * (rm & 7) + (rm >> 3);
+    if (m < cout) dw[((int64_t)m * cin + c) * 9 + t9] = o4[r];
   }
 }
 
@@ -964,7 +1025,8 @@ static int wgrad_tiles(int n, int h, int w, int taps) {
 int wgrad_splits(int n, int cin, int cout, int h, int w, int taps) {
   const int tiles = wgrad_tiles(n, h, w, taps);
   const int gy = (cin + 63) / 64, gz = (cout + 63) / 64;
-  int s = 1024 / (gy * gz);
+  // k_wgrad3 runs one workgroup per compute unit: one round of workgroups, evenly loaded
+  int s = ((taps == 9 && wg3_geom(h, w).ok) ? 256 : 1024) / (gy * gz);
   if (s < 1) s = 1;
   if (s > tiles) s = tiles;
   if (s > 128) s = 128;
@@ -972,27 +1034,31 @@ int wgrad_splits(int n, int cin, int cout, int h, int w, int taps) {
   return (tiles + tps - 1) / tps;
 }
 size_t wgrad_partial_floats(int n, int cin, int cout, int h, int w, int taps) {
-  return (size_t)wgrad_splits(n, cin, cout, h, w, taps) * cin * cout * taps;
+  const size_t S = (size_t)wgrad_splits(n, cin, cout, h, w, taps);
+  if (taps == 9 && wg3_geom(h, w).ok) return S * ((cin + 63) / 64) * ((cout + 63) / 64) * WG3_BLOCK;
+  return S * cin * cout * taps;
 }
 
 // g_f32: the gradient operand is the fp32 slab (3x3), else bf16 (1x1).  The caller adds the
 // partials (launch_sum_partials) -- *splits says how many.
-hipError_t wgrad(const void* a, int64_t a_ld, const void* g, int64_t g_ld, bool g_f32, float* part, int n, int cin,
-                 int cout, int h, int w, int taps, const float2* fold, int* splits, hipStream_t st) {
+hipError_t wgrad(const void* a, int64_t a_ld, const void* g, int64_t g_ld, bool g_f32, float* part, float* dw, int n,
+                 int cin, int cout, int h, int w, int taps, const float2* fold, hipStream_t st) {
   const Wg3Geom q3 = wg3_geom(h, w);
   const bool three = taps == 9 && q3.ok;
   const int tpi = three ? q3.tpi : (h * w + 63) / 64, tiles = n * tpi;
   const int S = wgrad_splits(n, cin, cout, h, w, taps);
   const int tps = (tiles + S - 1) / S;
-  *splits = S;
   dim3 grid((unsigned)S, (unsigned)((cin + 63) / 64), (unsigned)((cout + 63) / 64));
   if (three) {
 #define DNB_W3(TG, PRO)                                                                                \
-  hipLaunchKernelGGL((k_wgrad3<TG, PRO>), grid, dim3(256), 0, st, (const u16*)a, a_ld, (const TG*)g, \
+  hipLaunchKernelGGL((k_wgrad3<TG, PRO>), grid, dim3(512), 0, st, (const u16*)a, a_ld, (const TG*)g, \
                      g_ld, part, cin, cout, n, h, w, q3.R, q3.FR, tpi, tps, fold)
     if (g_f32) { if (fold) DNB_W3(float, true); else DNB_W3(float, false); }
     else       { if (fold) DNB_W3(u16, true); else DNB_W3(u16, false); }
 #undef DNB_W3
+    const int64_t per_split = (int64_t)grid.y * grid.z * WG3_BLOCK;
+    hipLaunchKernelGGL(k_sum_wgrad3, dim3((unsigned)(per_split / 256)), dim3(256), 0, st, part, S,
+                       (int)grid.y, (int)grid.z, cin, cout, dw);
     return hipGetLastError();
   }
 #define DNB_W(TAPS, TG, PRO)                                                                              \
@@ -1006,7 +1072,9 @@ hipError_t wgrad(const void* a, int64_t a_ld, const void* g, int64_t g_ld, bool 
     else       { if (fold) DNB_W(1, u16, true); else DNB_W(1, u16, false); }
   }
 #undef DNB_W
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_sum_partials(part, S, (int64_t)cin * cout * taps, dw, st);
 }
 
 int bn_bwd_splits(int64_t P, int c) {
