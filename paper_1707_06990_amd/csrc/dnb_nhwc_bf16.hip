@@ -794,6 +794,184 @@ __global__ __launch_bounds__(256) void k_sum_wgrad3(const float* __restrict__ pa
   }
 }
 
+// 1x1 weight gradient, bf16 gradient operand.  A workgroup (eight waves) owns up to 256 input
+// channels and up to 192 output channels, so the activations are read once when cout <= 192 and
+// the gradient once per 256 input channels.  A tile is 32 pixels of the flattened pixel axis (one
+// K-step); both operands are staged transposed, rows permuted inside each block of 64 channels
+// (channel 8v+e in row v+8e) so that the 2-byte staging stores of a wave spread over all banks.
+// Wave (mh, cq) accumulates m-tiles mh, mh+2, .. and c-tiles cq, cq+4, ...  The next tile's loads
+// are issued, unconditionally at clamped addresses, before the MFMA phase.
+constexpr int WG1_PT = 40, WG1_CG = 256, WG1_MG = 192, WG1_BLOCK = WG1_CG * WG1_MG;
+
+template <bool PRO>
+__global__ __launch_bounds__(512) void k_wgrad1(
+    const u16* __restrict__ a, int64_t a_ld, const u16* __restrict__ gout, int64_t g_ld,
+    float* __restrict__ part, int cin, int cout, int64_t P, int tiles_per_split, const float2* __restrict__ fold) {
+  constexpr int PT = WG1_PT;
+  __shared__ __attribute__((aligned(16))) u16 aT[WG1_CG * PT];
+  __shared__ __attribute__((aligned(16))) u16 gT[WG1_MG * PT];
+  __shared__ __attribute__((aligned(16))) float2 fl[WG1_CG];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, mh = wave & 1, cq = wave >> 1;
+  const int j = lane & 15, g = lane >> 4, v = lane & 7, pl = lane >> 3;
+  const int c0 = blockIdx.y * WG1_CG, m0 = blockIdx.z * WG1_MG;
+  const int64_t tiles = (P + 31) / 32;
+  const int64_t t_begin = (int64_t)blockIdx.x * tiles_per_split;
+  const int64_t t_end = min(tiles, t_begin + tiles_per_split);
+  if (PRO) {
+    for (int i = tid; i < WG1_CG; i += 512) fl[i] = c0 + i < cin ? fold[c0 + i] : make_float2(0.f, 0.f);
+  }
+
+  // staging units of 64 lanes = (8 pixels) x (8 channel vectors): 16 for the activations, 12 for
+  // the gradient; wave w takes units w and w + 8
+  int a_row[2], a_px[2], g_row[2], g_px[2];
+  bool a_ok[2], g_ok[2], g_unit[2];
+  const u16* a_src[2];
+  const u16* g_src[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int unit = wave + 8 * u, blk = unit >> 2, pg = unit & 3;
+    const int ch = c0 + blk * 64 + 8 * v, m = m0 + blk * 64 + 8 * v;
+    a_ok[u] = ch < cin;  // cin % 8 == 0, cout % 8 == 0
+    a_row[u] = blk * 64 + v;
+    a_px[u] = pg * 8 + pl;
+    a_src[u] = a + (a_ok[u] ? ch : 0);
+    g_unit[u] = unit < 12;
+    g_ok[u] = g_unit[u] && m < cout;
+    g_row[u] = blk * 64 + v;
+    g_px[u] = pg * 8 + pl;
+    g_src[u] = gout + (g_ok[u] ? m : 0);
+  }
+
+  f32x4 acc[6][4];
+#pragma unroll
+  for (int i = 0; i < 6; ++i)
+#pragma unroll
+    for (int k = 0; k < 4; ++k) acc[i][k] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  uint4 ra[2], rg[2];
+  auto issue = [&](int64_t tile) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int64_t pa = min(tile * 32 + a_px[u], P - 1), pg = min(tile * 32 + g_px[u], P - 1);
+      ra[u] = *reinterpret_cast<const uint4*>(a_src[u] + pa * a_ld);
+      rg[u] = *reinterpret_cast<const uint4*>(g_src[u] + pg * g_ld);
+    }
+  };
+  auto deposit = [&](int64_t tile) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const bool in = a_ok[u] && tile * 32 + a_px[u] < P;
+      V8 t;
+      t.q = ra[u];
+      float2 f8[8];
+      if (PRO) {
+        const float4* fp = reinterpret_cast<const float4*>(&fl[(a_row[u] & ~63) + 8 * v]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float4 q = fp[e];
+          f8[2 * e] = make_float2(q.x, q.y);
+          f8[2 * e + 1] = make_float2(q.z, q.w);
+        }
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        u16 hv = t.h[e];
+        if (PRO) hv = f2bf(fmaxf(__fmaf_rn(bf2f(hv), f8[e].x, f8[e].y), 0.f));
+        aT[(a_row[u] + 8 * e) * PT + a_px[u]] = in ? hv : (u16)0;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      if (g_unit[u]) {
+        const bool in = g_ok[u] && tile * 32 + g_px[u] < P;
+        V8 t;
+        t.q = rg[u];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) gT[(g_row[u] + 8 * e) * PT + g_px[u]] = in ? t.h[e] : (u16)0;
+      }
+    }
+  };
+
+  if (t_begin < t_end) issue(t_begin);
+  __syncthreads();  // fold parameters are in LDS
+  for (int64_t tile = t_begin; tile < t_end; ++tile) {
+    deposit(tile);
+    __syncthreads();
+    if (tile + 1 < t_end) issue(tile + 1);
+    // every row of both arrays is deposited each tile (zeros past cin / cout), so all 24 products
+    // are formed unguarded
+    V8 af[6], bf[4];
+#pragma unroll
+    for (int i = 0; i < 6; ++i) af[i].q = *reinterpret_cast<const uint4*>(&gT[((mh + 2 * i) * 16 + j) * PT + 8 * g]);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) bf[k].q = *reinterpret_cast<const uint4*>(&aT[((cq + 4 * k) * 16 + j) * PT + 8 * g]);
+#pragma unroll
+    for (int i = 0; i < 6; ++i)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) acc[i][k] = mfma_bf16(af[i], bf[k], acc[i][k]);
+    __syncthreads();  // fragment reads done before the next tile is deposited
+  }
+
+  // partials in accumulator order: [split][c group][m group][wave][m-tile i][c-tile k][lane][4]
+  float* pb = part + (((int64_t)blockIdx.x * gridDim.y + blockIdx.y) * gridDim.z + blockIdx.z) * WG1_BLOCK +
+              (int64_t)wave * 24 * 256 + lane * 4;
+#pragma unroll
+  for (int i = 0; i < 6; ++i)
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      *reinterpret_cast<float4*>(pb + (i * 4 + k) * 256) = make_float4(acc[i][k][0], acc[i][k][1], acc[i][k][2], acc[i][k][3]);
+}
+
+// Sums the splits of k_wgrad1's partials (same scheme as k_sum_wgrad3) and writes dW[m][c].
+__global__ __launch_bounds__(256) void k_sum_wgrad1(const float* __restrict__ part, int S, int gy, int gz, int cin,
+                                                    int cout, float* __restrict__ dw) {
+  __shared__ float4 red[3][64];
+  const int64_t per_split = (int64_t)gy * gz * WG1_BLOCK;
+  const int t = threadIdx.x & 63, sg = threadIdx.x >> 6;
+  const int64_t i = ((int64_t)blockIdx.x * 64 + t) * 4;
+  const int blk = (int)(i / WG1_BLOCK), rem = (int)(i - (int64_t)blk * WG1_BLOCK);
+  const int by = blk / gz, bz = blk - by * gz;
+  const int lane = (rem >> 2) & 63, ty = rem >> 8;  // ty = wave*24 + i*4 + k
+  const int wave = ty / 24, ik = ty - wave * 24, mt = (wave & 1) + 2 * (ik >> 2), ct = (wave >> 1) + 4 * (ik & 3);
+  // the 64 quads of a workgroup share (wave, m-tile, c-tile): uniform early exit for tiles whose
+  // whole block of 64 (the unit of the row permutation) lies past the tensor
+  if (bz * WG1_MG + (mt >> 2) * 64 >= cout || by * WG1_CG + (ct >> 2) * 64 >= cin) return;
+  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+  const float* p = part + i;
+  int s = sg;
+  for (; s + 12 < S; s += 16) {
+    const float4 a0 = *reinterpret_cast<const float4*>(p + (int64_t)s * per_split);
+    const float4 a1 = *reinterpret_cast<const float4*>(p + (int64_t)(s + 4) * per_split);
+    const float4 a2 = *reinterpret_cast<const float4*>(p + (int64_t)(s + 8) * per_split);
+    const float4 a3 = *reinterpret_cast<const float4*>(p + (int64_t)(s + 12) * per_split);
+    sum.x += a0.x; sum.y += a0.y; sum.z += a0.z; sum.w += a0.w;
+    sum.x += a1.x; sum.y += a1.y; sum.z += a1.z; sum.w += a1.w;
+    sum.x += a2.x; sum.y += a2.y; sum.z += a2.z; sum.w += a2.w;
+    sum.x += a3.x; sum.y += a3.y; sum.z += a3.z; sum.w += a3.w;
+  }
+  for (; s < S; s += 4) {
+    const float4 a0 = *reinterpret_cast<const float4*>(p + (int64_t)s * per_split);
+    sum.x += a0.x; sum.y += a0.y; sum.z += a0.z; sum.w += a0.w;
+  }
+  if (sg > 0) red[sg - 1][t] = sum;
+  __syncthreads();
+  if (sg > 0) return;
+#pragma unroll
+  for (int q = 0; q < 3; ++q) {
+    const float4 o = red[q][t];
+    sum.x += o.x; sum.y += o.y; sum.z += o.z; sum.w += o.w;
+  }
+  const int j = lane & 15, g = lane >> 4;
+  const int rc = ct * 16 + j, c = by * WG1_CG + (rc & ~63) + 8 * (rc & 7) + ((rc & 63) >> 3);
+  if (c >= cin) return;
+  const float o4[4] = {sum.x, sum.y, sum.z, sum.w};
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int rm = mt * 16 + 4 * g + r, m = bz * WG1_MG + (rm & ~63) + 8 * (rm & 7) + ((rm & 63) >> 3);
+    if (m < cout) dw[(int64_t)m * cin + c] = o4[r];
+  }
+}
+
 // ----------------------------------------------------------------------------- BN + ReLU backward
 
 // Thread = (pixel row pr, 8-channel vector cv); workgroup = 256 threads covering `rows` pixels per
@@ -1033,16 +1211,49 @@ int wgrad_splits(int n, int cin, int cout, int h, int w, int taps) {
   const int tps = (tiles + s - 1) / s;
   return (tiles + tps - 1) / tps;
 }
+// k_wgrad1: 32-pixel tiles of the flattened pixel axis, one round of workgroups
+static int wgrad1_splits(int64_t P, int cin, int cout) {
+  const int64_t tiles = (P + 31) / 32;
+  const int gy = (cin + WG1_CG - 1) / WG1_CG, gz = (cout + WG1_MG - 1) / WG1_MG;
+  int64_t s = 256 / (gy * gz);
+  if (s < 1) s = 1;
+  if (s > tiles) s = tiles;
+  if (s > 128) s = 128;
+  const int64_t tps = (tiles + s - 1) / s;
+  return (int)((tiles + tps - 1) / tps);
+}
 size_t wgrad_partial_floats(int n, int cin, int cout, int h, int w, int taps) {
   const size_t S = (size_t)wgrad_splits(n, cin, cout, h, w, taps);
   if (taps == 9 && wg3_geom(h, w).ok) return S * ((cin + 63) / 64) * ((cout + 63) / 64) * WG3_BLOCK;
-  return S * cin * cout * taps;
+  size_t f = S * cin * cout * taps;
+  if (taps == 1) {  // either 1x1 kernel may run, depending on the gradient operand's type
+    const size_t f1 = (size_t)wgrad1_splits((int64_t)n * h * w, cin, cout) * ((cin + WG1_CG - 1) / WG1_CG) *
+                      ((cout + WG1_MG - 1) / WG1_MG) * WG1_BLOCK;
+    if (f1 > f) f = f1;
+  }
+  return f;
 }
 
 // g_f32: the gradient operand is the fp32 slab (3x3), else bf16 (1x1).  The caller adds the
 // partials (launch_sum_partials) -- *splits says how many.
 hipError_t wgrad(const void* a, int64_t a_ld, const void* g, int64_t g_ld, bool g_f32, float* part, float* dw, int n,
                  int cin, int cout, int h, int w, int taps, const float2* fold, hipStream_t st) {
+  if (taps == 1 && !g_f32) {
+    const int64_t P = (int64_t)n * h * w, tiles = (P + 31) / 32;
+    const int S = wgrad1_splits(P, cin, cout);
+    const int tps = (int)((tiles + S - 1) / S);
+    dim3 grid((unsigned)S, (unsigned)((cin + WG1_CG - 1) / WG1_CG), (unsigned)((cout + WG1_MG - 1) / WG1_MG));
+    if (fold)
+      hipLaunchKernelGGL((k_wgrad1<true>), grid, dim3(512), 0, st, (const u16*)a, a_ld, (const u16*)g, g_ld, part,
+                         cin, cout, P, tps, fold);
+    else
+      hipLaunchKernelGGL((k_wgrad1<false>), grid, dim3(512), 0, st, (const u16*)a, a_ld, (const u16*)g, g_ld, part,
+                         cin, cout, P, tps, fold);
+    const int64_t per_split = (int64_t)grid.y * grid.z * WG1_BLOCK;
+    hipLaunchKernelGGL(k_sum_wgrad1, dim3((unsigned)(per_split / 256)), dim3(256), 0, st, part, S, (int)grid.y,
+                       (int)grid.z, cin, cout, dw);
+    return hipGetLastError();
+  }
   const Wg3Geom q3 = wg3_geom(h, w);
   const bool three = taps == 9 && q3.ok;
   const int tpi = three ? q3.tpi : (h * w + 63) / 64, tiles = n * tpi;
