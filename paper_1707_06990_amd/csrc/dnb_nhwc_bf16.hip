@@ -18,6 +18,11 @@ namespace nhwc {
 
 namespace {
 
+#ifndef DNB_DBG
+#define DNB_DBG 0  // kernel ablation builds for tuning experiments (1x1 conv loop: 0x10000 no MFMA, 0x20000 no deposit,
+                   // 0x40000 no weight loads, 0x80000 no activation loads)
+#endif
+
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16;
@@ -210,7 +215,7 @@ __global__ __launch_bounds__(256) void k_pack_weights(const float* __restrict__ 
 // buffer (BN+ReLU applied, rounded to bf16) after them: one barrier per chunk, load latency
 // under the matrix work.  TIN = u16 (bf16) or float (the gradient slab).  STATS: per-tile
 // (count, mean, M2) of the rounded outputs, as in the fp32 kernels: spart[(m*T + tile)*3].
-template <int TAPS, int MT, typename TIN, bool PRO, bool STATS>
+template <int TAPS, int MT, typename TIN, bool PRO, bool STATS, bool RING>
 __global__ __launch_bounds__(256) void k_conv(
     const TIN* __restrict__ in, int64_t in_ld, const u16* __restrict__ Wp, int M16, int K32,
     u16* __restrict__ out, int64_t out_ld, int cin, int cout, int H, int W, int64_t Ptot,
@@ -256,20 +261,21 @@ __global__ __launch_bounds__(256) void k_conv(
   }
 
   struct Raw { uint4 a, b; };  // bf16: a only; float: 8 floats
+  // Every load of the main loop is unconditional, at an address clamped into the tensor: the
+  // number of loads in flight at each point is then the same on every path, and a use waits only
+  // for its own load instead of for all of them.
   auto request = [&](int c0, Raw(&v)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int idx = u * 256 + tid;
-      if (idx < nvec) {
-        const int s = idx >> 3, ch = min(c0 + 8 * (idx & 7), cin - 8);  // cin % 8 == 0
-        const int64_t q = min(max(q0 - halo + s, (int64_t)0), limit - 1);
-        if (sizeof(TIN) == 2) {
-          v[u].a = *reinterpret_cast<const uint4*>(reinterpret_cast<const u16*>(inb) + q * in_ld + ch);
-        } else {
-          const float* pf = reinterpret_cast<const float*>(inb) + q * in_ld + ch;
-          v[u].a = *reinterpret_cast<const uint4*>(pf);
-          v[u].b = *reinterpret_cast<const uint4*>(pf + 4);
-        }
+      const int idx = min(u * 256 + tid, nvec - 1);
+      const int s = idx >> 3, ch = min(c0 + 8 * (idx & 7), cin - 8);  // cin % 8 == 0
+      const int64_t q = min(max(q0 - halo + s, (int64_t)0), limit - 1);
+      if (sizeof(TIN) == 2) {
+        v[u].a = *reinterpret_cast<const uint4*>(reinterpret_cast<const u16*>(inb) + q * in_ld + ch);
+      } else {
+        const float* pf = reinterpret_cast<const float*>(inb) + q * in_ld + ch;
+        v[u].a = *reinterpret_cast<const uint4*>(pf);
+        v[u].b = *reinterpret_cast<const uint4*>(pf + 4);
       }
     }
   };
@@ -311,79 +317,103 @@ __global__ __launch_bounds__(256) void k_conv(
     }
   };
 
-  // packed weights of one (chunk, tap): MT M-tiles x 2 K-steps, 16 bytes per lane each; loaded one
-  // (chunk, tap) ahead of their use so the L2 latency is under the previous tap's MFMAs
+  // packed weights of one (chunk, tap): MT M-tiles x 2 K-steps, 16 bytes per lane each.  They
+  // come from L2 at best and, early in a launch, from HBM, so they are requested several steps
+  // before their use, into a ring of register sets indexed statically: the 1x1 keeps four chunks
+  // in flight (chunk loop unrolled by four), the 3x3 nine taps (MT == 1) or three.  Rows past M16
+  // and K-steps past K32 are clamped: their products are never formed or never stored.
   struct WSet { uint4 w[MT][2]; };
   auto wload = [&](int c0, int t9, WSet& ws) {
-    const int ksteps = min(2, (K32 - c0) >> 5);
 #pragma unroll
     for (int a = 0; a < MT; ++a)
 #pragma unroll
       for (int kk = 0; kk < 2; ++kk)
-        ws.w[a][kk] = (m_ok && kk < ksteps && mbase + a * 16 < M16)
-                          ? *reinterpret_cast<const uint4*>(Wp + ((int64_t)t9 * M16 + mbase + a * 16 + j) * K32 +
-                                                            c0 + kk * 32 + 8 * g)
-                          : make_uint4(0u, 0u, 0u, 0u);
+        ws.w[a][kk] = *reinterpret_cast<const uint4*>(Wp + ((int64_t)t9 * M16 + min(mbase + a * 16 + j, M16 - 1)) * K32 +
+                                                      min(c0 + kk * 32, K32 - 32) + 8 * g);
   };
-
-  // activations: the 1x1 keeps three chunks requested ahead of the one being multiplied (its
-  // chunks carry little matrix work), the 3x3 one
-  constexpr int AHEAD = TAPS == 1 ? 3 : 1;
-  Raw va[U], vb[U], vc[U];  // chunks i+1, i+2, i+3 (1x1); va only (3x3)
-  {
-    Raw v[U];
-    request(0, v);
-    if (KC < cin) request(KC, va);
-    if (AHEAD >= 2 && 2 * KC < cin) request(2 * KC, vb);
-    deposit(0, v, 0);
-  }
-  WSet wcur, wnext;
-  wload(0, 0, wcur);
-  __syncthreads();
-
-  int it = 0;
-  for (int c0 = 0; c0 < cin; c0 += KC, ++it) {
-    const int boff = (it & 1) * BUFE;
-    const bool more = c0 + KC < cin;
-    if (AHEAD >= 3 && c0 + 3 * KC < cin) request(c0 + 3 * KC, vc);
+  // the MFMAs of one (chunk, tap) on the tile staged at boff
+  auto mm = [&](int c0, int t9, int boff, const WSet& ws) {
+    const int di = (TAPS == 9) ? t9 / 3 - 1 : 0, dj = (TAPS == 9) ? t9 % 3 - 1 : 0;
     const int ksteps = min(2, (K32 - c0) >> 5);
+    if (m_ok) {
 #pragma unroll
-    for (int t9 = 0; t9 < TAPS; ++t9) {
-      const int di = (TAPS == 9) ? t9 / 3 - 1 : 0, dj = (TAPS == 9) ? t9 % 3 - 1 : 0;
-      // weights of the next (chunk, tap)
-      if (t9 + 1 < TAPS) wload(c0, t9 + 1, wnext);
-      else if (more) wload(c0 + KC, 0, wnext);
-      if (m_ok) {
+      for (int kk = 0; kk < 2; ++kk) {
+        if (kk < ksteps) {
+          V8 bfrag[4];
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-          if (kk < ksteps) {
-            V8 bfrag[4];
+          for (int t = 0; t < 4; ++t) {
+            bfrag[t].q = *reinterpret_cast<const uint4*>(
+                &lds[boff + (t * 16 + j + halo + di * W + dj) * PITCH + kk * 32 + 8 * g]);
+            if ((dj < 0 && !lok[t]) || (dj > 0 && !rok[t])) bfrag[t].q = make_uint4(0u, 0u, 0u, 0u);
+          }
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-              bfrag[t].q = *reinterpret_cast<const uint4*>(
-                  &lds[boff + (t * 16 + j + halo + di * W + dj) * PITCH + kk * 32 + 8 * g]);
-              if ((dj < 0 && !lok[t]) || (dj > 0 && !rok[t])) bfrag[t].q = make_uint4(0u, 0u, 0u, 0u);
-            }
+          for (int a = 0; a < MT; ++a) {
+            V8 w;
+            w.q = ws.w[a][kk];
 #pragma unroll
-            for (int a = 0; a < MT; ++a) {
-              V8 w;
-              w.q = wcur.w[a][kk];
-#pragma unroll
-              for (int t = 0; t < 4; ++t) acc[a][t] = mfma_bf16(w, bfrag[t], acc[a][t]);
-            }
+            for (int t = 0; t < 4; ++t) acc[a][t] = mfma_bf16(w, bfrag[t], acc[a][t]);
           }
         }
       }
-      wcur = wnext;
     }
-    if (more) deposit(c0 + KC, va, ((it & 1) ^ 1) * BUFE);
-    if (AHEAD >= 3) {
+  };
+
+  const int clast = ((cin - 1) / KC) * KC;  // start of the last chunk
+  if (RING) {  // 1x1 with many chunks
+    // chunk x lives in ring slot x % 4 (activations and weights alike): step s multiplies chunk
+    // c, requests chunk c+4 into the slots it has just freed and deposits chunk c+1
+    Raw r[4][U];
+    WSet wt[4];
+    request(0, r[0]);
+    wload(0, 0, wt[0]);
 #pragma unroll
-      for (int u = 0; u < U; ++u) { va[u] = vb[u]; vb[u] = vc[u]; }
-    } else if (c0 + 2 * KC < cin) {
-      request(c0 + 2 * KC, va);  // 3x3: chunk i+2, in flight across the barrier and the next chunk's MFMAs
+    for (int x = 1; x < 4; ++x) {
+      wload(min(x * KC, clast), 0, wt[x]);
+      request(min(x * KC, clast), r[x]);
     }
+    deposit(0, r[0], 0);
     __syncthreads();
+    // The loop always runs whole groups of four steps: steps past the last chunk load (clamped),
+    // deposit and synchronise like the others and only skip the MFMAs, so the sequence of loads
+    // and of waits for them is the same on every path.
+    for (int cb = 0; cb < cin; cb += 4 * KC) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        const int c0 = cb + s * KC, cn = min(c0 + 4 * KC, clast);
+        if (c0 < cin && !(DNB_DBG & 0x10000)) mm(c0, 0, (s & 1) * BUFE, wt[s]);
+        if (!(DNB_DBG & 0x40000)) wload(cn, 0, wt[s]);
+        if (!(DNB_DBG & 0x80000)) request(cn, r[s]);
+        if (!(DNB_DBG & 0x20000)) deposit(min(c0 + KC, clast), r[(s + 1) & 3], ((s & 1) ^ 1) * BUFE);
+        __syncthreads();
+      }
+    }
+  } else {
+    constexpr int WD = TAPS == 1 ? 1 : (MT == 1 ? 9 : 3);
+    Raw va[U];
+    {
+      Raw v[U];
+      request(0, v);
+      request(min(KC, clast), va);
+      deposit(0, v, 0);
+    }
+    WSet wt[WD];
+#pragma unroll
+    for (int s = 0; s < WD; ++s) wload(0, s, wt[s]);
+    __syncthreads();
+    int it = 0;
+    for (int c0 = 0; c0 < cin; c0 += KC, ++it) {
+      const int boff = (it & 1) * BUFE;
+      const int cn = min(c0 + KC, clast);
+#pragma unroll
+      for (int t9 = 0; t9 < TAPS; ++t9) {
+        mm(c0, t9, boff, wt[t9 % WD]);
+        if (t9 + WD < TAPS) wload(c0, t9 + WD, wt[t9 % WD]);
+        else wload(cn, t9 + WD - TAPS, wt[t9 % WD]);
+      }
+      if (c0 + KC < cin) deposit(c0 + KC, va, ((it & 1) ^ 1) * BUFE);
+      request(min(c0 + 2 * KC, clast), va);  // in flight across the barrier and the next chunk's MFMAs
+      __syncthreads();
+    }
   }
 
   if (!m_ok) return;
@@ -1162,34 +1192,42 @@ hipError_t conv(const void* in, int64_t in_ld, bool in_f32, const void* Wp, void
                 int cin, int cout, int h, int w, int taps, const float2* fold, float* spart, int* sT,
                 hipStream_t st) {
   const int hw = h * w, M16 = (cout + 15) & ~15, K32 = (cin + 31) & ~31, mtiles = M16 / 16;
-  int mt = (mtiles + 3) / 4;
-  if (mt > 3) mt = 3;
-  const int gy = (mtiles + 4 * mt - 1) / (4 * mt);
   const int64_t P = (int64_t)n * hw;
   // 1x1: flat 64-pixel tiles over all images; 3x3: tiles of one image
-  dim3 grid(taps == 9 ? (unsigned)((hw + 63) / 64) : (unsigned)((P + 63) / 64), (unsigned)gy,
-            taps == 9 ? (unsigned)n : 1u);
-  const int T = taps == 9 ? (int)grid.x * n : (int)grid.x;
+  const int64_t ptiles = taps == 9 ? (int64_t)((hw + 63) / 64) * n : (P + 63) / 64;
+  int mt = (mtiles + 3) / 4;
+  if (mt > 3) mt = 3;
+  // few pixel tiles: split the output channels over more workgroups (each repeats the staging,
+  // on compute units that would otherwise idle) so that a chunk costs each of them less
+  while (mt > 1 && ptiles * ((mtiles + 4 * mt - 1) / (4 * mt)) < 256) --mt;
+  const int gy = (mtiles + 4 * mt - 1) / (4 * mt);
+  dim3 grid(taps == 9 ? (unsigned)((hw + 63) / 64) : (unsigned)ptiles, (unsigned)gy, taps == 9 ? (unsigned)n : 1u);
+  const int T = (int)ptiles;
   if (sT) *sT = T;
   const int halo = taps == 9 ? w + 1 : 0;
   const size_t lds = (size_t)2 * (64 + 2 * halo) * 72 * sizeof(u16) + (fold ? (size_t)cin * 8 : 0);
   if (lds > 64 * 1024 || (taps == 9 && (64 + 2 * halo) * 8 > 8 * 256)) return hipErrorInvalidValue;
   if ((fold != nullptr) != (spart != nullptr) && fold) return hipErrorInvalidValue;
-#define DNB_K(TAPS, MT, TIN, PRO, STATS)                                                                 \
-  hipLaunchKernelGGL((k_conv<TAPS, MT, TIN, PRO, STATS>), grid, dim3(256), lds, st, (const TIN*)in, in_ld, \
+  // eight chunks or more, and about one workgroup per compute unit (with several, their phases
+  // already cover one another's latencies and the ring's extra loads only cost)
+  const bool ring = taps == 1 && cin >= 512 && ptiles * gy <= 320;
+#define DNB_K(TAPS, MT, TIN, PRO, STATS, RING)                                                                  \
+  hipLaunchKernelGGL((k_conv<TAPS, MT, TIN, PRO, STATS, RING>), grid, dim3(256), lds, st, (const TIN*)in, in_ld, \
                      (const u16*)Wp, M16, K32, (u16*)out, out_ld, cin, cout, h, w, P, fold, spart, T)
-#define DNB_K2(TAPS, MT)                                                              \
+#define DNB_K2(TAPS, MT, RING)                                                        \
   do {                                                                                \
-    if (in_f32) DNB_K(TAPS, MT, float, false, false);                                 \
-    else if (fold) DNB_K(TAPS, MT, u16, true, true);                                  \
-    else if (spart) DNB_K(TAPS, MT, u16, false, true);                                \
-    else DNB_K(TAPS, MT, u16, false, false);                                          \
+    if (in_f32) DNB_K(TAPS, MT, float, false, false, RING);                           \
+    else if (fold) DNB_K(TAPS, MT, u16, true, true, RING);                            \
+    else if (spart) DNB_K(TAPS, MT, u16, false, true, RING);                          \
+    else DNB_K(TAPS, MT, u16, false, false, RING);                                    \
   } while (0)
-#define DNB_K3(TAPS)                                                                  \
+#define DNB_K3(TAPS, RING)                                                            \
   do {                                                                                \
-    if (mt == 3) DNB_K2(TAPS, 3); else if (mt == 2) DNB_K2(TAPS, 2); else DNB_K2(TAPS, 1); \
+    if (mt == 3) DNB_K2(TAPS, 3, RING); else if (mt == 2) DNB_K2(TAPS, 2, RING); else DNB_K2(TAPS, 1, RING); \
   } while (0)
-  if (taps == 9) DNB_K3(9); else DNB_K3(1);
+  if (taps == 9) DNB_K3(9, false);
+  else if (ring) DNB_K3(1, true);
+  else DNB_K3(1, false);
 #undef DNB_K3
 #undef DNB_K2
 #undef DNB_K
