@@ -1009,11 +1009,13 @@ __global__ __launch_bounds__(256) void k_sum_wgrad1(const float* __restrict__ pa
 // part[(ch*S + s)*2] = (sum dz, sum dz*xhat) over the split's pixels.
 __global__ __launch_bounds__(256) void k_bn_bwd_partial(
     const u16* __restrict__ x, int64_t x_ld, const u16* __restrict__ dact, int64_t d_ld, int64_t P,
-    int c, int ppb, const float* __restrict__ gamma, const float* __restrict__ beta,
+    int c, int ppb, int lsh, const float* __restrict__ gamma, const float* __restrict__ beta,
     const float* __restrict__ mean, const float* __restrict__ istd, float* __restrict__ part) {
   __shared__ float red[2][8][256];
-  const int cvl = threadIdx.x & 31, pr = threadIdx.x >> 5;  // 32 vectors x 8 pixel rows
-  const int ch0 = (blockIdx.x * 32 + cvl) * 8, s = blockIdx.y, S = gridDim.y;
+  // L = 1 << lsh channel vectors x 256/L pixel rows; four pixels per thread in flight
+  const int L = 1 << lsh, rows = 256 >> lsh;
+  const int cvl = threadIdx.x & (L - 1), pr = threadIdx.x >> lsh;
+  const int ch0 = (blockIdx.x * L + cvl) * 8, s = blockIdx.y, S = gridDim.y;
   const int64_t p0 = (int64_t)s * ppb, p1 = min(P, p0 + ppb);
   float sb[8], sg[8], sc[8], sf[8], mu[8], is[8];
   const bool ok = ch0 < c;
@@ -1026,29 +1028,41 @@ __global__ __launch_bounds__(256) void k_bn_bwd_partial(
     }
   }
   if (ok) {
-    for (int64_t p = p0 + pr; p < p1; p += 8) {
-      V8 xv, dv;
-      xv.q = *reinterpret_cast<const uint4*>(x + p * x_ld + ch0);
-      dv.q = *reinterpret_cast<const uint4*>(dact + p * d_ld + ch0);
+    const u16* xp = x + ch0;
+    const u16* dp = dact + ch0;
+    for (int64_t pb = p0 + pr; pb < p1; pb += 4 * rows) {
+      V8 xv[4], dv[4];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float xf = bf2f(xv.h[e]);
-        const float dz = __fmaf_rn(xf, sc[e], sf[e]) > 0.f ? bf2f(dv.h[e]) : 0.f;
-        sb[e] += dz;
-        sg[e] = __fmaf_rn(dz, (xf - mu[e]) * is[e], sg[e]);
+      for (int u = 0; u < 4; ++u) {  // rows past the split are clamped here and skipped below
+        const int64_t p = min(pb + u * rows, p1 - 1);
+        xv[u].q = *reinterpret_cast<const uint4*>(xp + p * x_ld);
+        dv[u].q = *reinterpret_cast<const uint4*>(dp + p * d_ld);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (pb + u * rows < p1) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float xf = bf2f(xv[u].h[e]);
+            const float dz = __fmaf_rn(xf, sc[e], sf[e]) > 0.f ? bf2f(dv[u].h[e]) : 0.f;
+            sb[e] += dz;
+            sg[e] = __fmaf_rn(dz, (xf - mu[e]) * is[e], sg[e]);
+          }
+        }
       }
     }
   }
 #pragma unroll
   for (int e = 0; e < 8; ++e) { red[0][e][threadIdx.x] = sb[e]; red[1][e][threadIdx.x] = sg[e]; }
   __syncthreads();
-  if (pr == 0 && ok) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float b = 0.f, gg = 0.f;
-      for (int r = 0; r < 8; ++r) { b += red[0][e][r * 32 + cvl]; gg += red[1][e][r * 32 + cvl]; }
-      float* o = part + ((int64_t)(ch0 + e) * S + s) * 2;
-      o[0] = b; o[1] = gg;
+  // one thread per (sum, channel of the vector, vector): adds its 256/L pixel rows in order
+  for (int q = threadIdx.x; q < 16 * L; q += 256) {
+    const int cv = q & (L - 1), e = (q >> lsh) & 7, which = q >> (lsh + 3);
+    const int ch = (blockIdx.x * L + cv) * 8 + e;
+    if (ch < c) {
+      float acc = 0.f;
+      for (int r = 0; r < rows; ++r) acc += red[which][e][r * L + cv];
+      part[((int64_t)ch * S + s) * 2 + which] = acc;
     }
   }
 }
@@ -1072,36 +1086,64 @@ __global__ __launch_bounds__(256) void k_bn_bwd_finalize(const float* __restrict
 template <bool ACC>
 __global__ __launch_bounds__(256) void k_bn_bwd_apply(
     const u16* __restrict__ x, int64_t x_ld, const u16* dact, int64_t d_ld, u16* du_bf, int64_t du_ld,
-    float* __restrict__ G, int64_t g_ld, int64_t P, int cv, float inv_p,
+    float* __restrict__ G, int64_t g_ld, int64_t P, int c, int ppb, int lsh, float inv_p,
     const float* __restrict__ gamma, const float* __restrict__ beta, const float* __restrict__ mean,
     const float* __restrict__ istd, const float* __restrict__ dgamma, const float* __restrict__ dbeta) {
-  const int64_t total = P * cv;
-  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-    const int64_t p = i / cv;
-    const int ch0 = (int)(i - p * cv) * 8;
-    V8 xv, dv, ov;
-    xv.q = *reinterpret_cast<const uint4*>(x + p * x_ld + ch0);
-    dv.q = *reinterpret_cast<const uint4*>(dact + p * d_ld + ch0);
-    float r[8];
+  // same thread map as k_bn_bwd_partial: a thread keeps its eight channels' coefficients in
+  // registers and walks pixels, four in flight
+  const int L = 1 << lsh, rows = 256 >> lsh;
+  const int cvl = threadIdx.x & (L - 1), pr = threadIdx.x >> lsh;
+  const int ch0 = (blockIdx.x * L + cvl) * 8;
+  if (ch0 >= c) return;
+  const int64_t p0 = (int64_t)blockIdx.y * ppb, p1 = min(P, p0 + ppb);
+  float sc[8], sf[8], mu[8], is[8], db[8], dg[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float mu = mean[ch0 + e], is = istd[ch0 + e];
-      float sc, sf;
-      bn_fold(gamma[ch0 + e], beta[ch0 + e], mu, is, sc, sf);
-      const float xf = bf2f(xv.h[e]);
-      const float dz = __fmaf_rn(xf, sc, sf) > 0.f ? bf2f(dv.h[e]) : 0.f;
-      r[e] = sc * (dz - dbeta[ch0 + e] * inv_p - (xf - mu) * is * (dgamma[ch0 + e] * inv_p));
+  for (int e = 0; e < 8; ++e) {
+    mu[e] = mean[ch0 + e]; is[e] = istd[ch0 + e];
+    bn_fold(gamma[ch0 + e], beta[ch0 + e], mu[e], is[e], sc[e], sf[e]);
+    db[e] = dbeta[ch0 + e] * inv_p;
+    dg[e] = dgamma[ch0 + e] * inv_p;
+  }
+  const u16* xp = x + ch0;
+  const u16* dp = dact + ch0;
+  for (int64_t pb = p0 + pr; pb < p1; pb += 4 * rows) {
+    V8 xv[4], dv[4];
+    float4 ga[4], gb[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {  // rows past the split are clamped here and skipped below
+      const int64_t p = min(pb + u * rows, p1 - 1);
+      xv[u].q = *reinterpret_cast<const uint4*>(xp + p * x_ld);
+      dv[u].q = *reinterpret_cast<const uint4*>(dp + p * d_ld);
+      if (ACC) {
+        const float* gp = G + p * g_ld + ch0;
+        ga[u] = *reinterpret_cast<const float4*>(gp);
+        gb[u] = *reinterpret_cast<const float4*>(gp + 4);
+      }
     }
-    if (ACC) {
-      float* gp = G + p * g_ld + ch0;
-      float4 a = *reinterpret_cast<float4*>(gp), b = *reinterpret_cast<float4*>(gp + 4);
-      a.x += r[0]; a.y += r[1]; a.z += r[2]; a.w += r[3]; b.x += r[4]; b.y += r[5]; b.z += r[6]; b.w += r[7];
-      *reinterpret_cast<float4*>(gp) = a;
-      *reinterpret_cast<float4*>(gp + 4) = b;
-    } else {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) ov.h[e] = f2bf(r[e]);
-      *reinterpret_cast<uint4*>(du_bf + p * du_ld + ch0) = ov.q;
+    for (int u = 0; u < 4; ++u) {
+      const int64_t p = pb + u * rows;
+      if (p < p1) {
+        float r[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float xf = bf2f(xv[u].h[e]);
+          const float dz = __fmaf_rn(xf, sc[e], sf[e]) > 0.f ? bf2f(dv[u].h[e]) : 0.f;
+          r[e] = sc[e] * (dz - db[e] - (xf - mu[e]) * is[e] * dg[e]);
+        }
+        if (ACC) {
+          float* gp = G + p * g_ld + ch0;
+          float4 a = ga[u], b = gb[u];
+          a.x += r[0]; a.y += r[1]; a.z += r[2]; a.w += r[3]; b.x += r[4]; b.y += r[5]; b.z += r[6]; b.w += r[7];
+          *reinterpret_cast<float4*>(gp) = a;
+          *reinterpret_cast<float4*>(gp + 4) = b;
+        } else {
+          V8 ov;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) ov.h[e] = f2bf(r[e]);
+          *reinterpret_cast<uint4*>(du_bf + p * du_ld + ch0) = ov.q;
+        }
+      }
     }
   }
 }
@@ -1326,11 +1368,24 @@ hipError_t wgrad(const void* a, int64_t a_ld, const void* g, int64_t g_ld, bool 
   return launch_sum_partials(part, S, (int64_t)cin * cout * taps, dw, st);
 }
 
+// channel vectors side by side in a workgroup of the BN backward kernels: 4, 8, 16 or 32
+// (the count among 8, 16, 32 that leaves the fewest lanes without a vector; 4 for tiny c)
+static int bn_bwd_lsh(int c) {
+  const int cv = c / 8;
+  if (cv <= 4) return 2;
+  int best = 5, waste = ((cv + 31) / 32) * 32 - cv;
+  for (int lsh = 4; lsh >= 3; --lsh) {
+    const int L = 1 << lsh, w = ((cv + L - 1) / L) * L - cv;
+    if (w < waste) { waste = w; best = lsh; }
+  }
+  return best;
+}
 int bn_bwd_splits(int64_t P, int c) {
-  const int groups = (c / 8 + 31) / 32;
+  const int lsh = bn_bwd_lsh(c), L = 1 << lsh, rows = 256 >> lsh;
+  const int groups = (c / 8 + L - 1) / L;
   int s = 1024 / groups;
   if (s > 256) s = 256;
-  const int64_t cap = (P + 63) / 64;
+  const int64_t cap = (P + 8 * rows - 1) / (8 * rows);  // at least two batches of four pixels per thread
   if (s > cap) s = (int)cap;
   return s < 1 ? 1 : s;
 }
@@ -1342,20 +1397,23 @@ hipError_t bn_relu_bwd(const void* x, int64_t x_ld, const void* dact, int64_t d_
                        float* G, int64_t g_ld, int64_t P, int c, const float* gamma, const float* beta,
                        const float* mean, const float* istd, float* dgamma, float* dbeta, float* part,
                        hipStream_t st) {
-  const int S = bn_bwd_splits(P, c);
+  const int S = bn_bwd_splits(P, c), lsh = bn_bwd_lsh(c), L = 1 << lsh;
   const int ppb = (int)((P + S - 1) / S);
   const int gs = (int)((P + ppb - 1) / ppb);
-  hipLaunchKernelGGL(k_bn_bwd_partial, dim3((unsigned)((c / 8 + 31) / 32), (unsigned)gs), dim3(256), 0, st,
-                     (const u16*)x, x_ld, (const u16*)dact, d_ld, P, c, ppb, gamma, beta, mean, istd, part);
+  const dim3 grid((unsigned)((c / 8 + L - 1) / L), (unsigned)gs);
+  hipLaunchKernelGGL(k_bn_bwd_partial, grid, dim3(256), 0, st, (const u16*)x, x_ld, (const u16*)dact, d_ld, P, c, ppb,
+                     lsh, gamma, beta, mean, istd, part);
   hipLaunchKernelGGL(k_bn_bwd_finalize, dim3((unsigned)((c + 3) / 4)), dim3(256), 0, st, part, c, gs, dgamma, dbeta);
   const float inv_p = 1.0f / (float)P;
-  const unsigned grid = grid1d(P * (c / 8), 256, 65536);
+  // the element-wise pass wants more, shorter workgroups than the reduction
+  const int ppa = (int)min((int64_t)ppb, (int64_t)(256 >> lsh) * 16);
+  const dim3 grida(grid.x, (unsigned)((P + ppa - 1) / ppa));
   if (G)
-    hipLaunchKernelGGL((k_bn_bwd_apply<true>), dim3(grid), dim3(256), 0, st, (const u16*)x, x_ld, (const u16*)dact,
-                       d_ld, (u16*)nullptr, (int64_t)0, G, g_ld, P, c / 8, inv_p, gamma, beta, mean, istd, dgamma, dbeta);
+    hipLaunchKernelGGL((k_bn_bwd_apply<true>), grida, dim3(256), 0, st, (const u16*)x, x_ld, (const u16*)dact, d_ld,
+                       (u16*)nullptr, (int64_t)0, G, g_ld, P, c, ppa, lsh, inv_p, gamma, beta, mean, istd, dgamma, dbeta);
   else
-    hipLaunchKernelGGL((k_bn_bwd_apply<false>), dim3(grid), dim3(256), 0, st, (const u16*)x, x_ld, (const u16*)dact,
-                       d_ld, (u16*)du_bf, du_ld, (float*)nullptr, (int64_t)0, P, c / 8, inv_p, gamma, beta, mean, istd,
+    hipLaunchKernelGGL((k_bn_bwd_apply<false>), grida, dim3(256), 0, st, (const u16*)x, x_ld, (const u16*)dact, d_ld,
+                       (u16*)du_bf, du_ld, (float*)nullptr, (int64_t)0, P, c, ppa, lsh, inv_p, gamma, beta, mean, istd,
                        dgamma, dbeta);
   return hipGetLastError();
 }
