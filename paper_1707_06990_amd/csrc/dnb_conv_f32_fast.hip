@@ -739,32 +739,58 @@ __global__ __launch_bounds__(256) void k_wgrad1x1_fast(
     fl[y] = (PRO && c < cin) ? fold[c] : make_float2(1.f, 0.f);
   }
 
-  for (int s = s_begin + wave; s < s_end; s += 4) {
-    const int img = s / spi, q = (s - img * spi) * 16 + 4 * kk;
-    const bool ok = q < HW;
-    float4 A[MTW], Bv[CTW];
+  // Operands are requested two steps ahead into two register stages (loop unrolled by two so
+  // the stages are indexed statically).  Every load is unconditional at an address clamped into
+  // the tensors, so a step waits for its own operands only; what a clamped load stands in for
+  // (a step past the range, pixels past the image) is zeroed when the stage is consumed, and
+  // rows past cout / cin are computed on repeated data and never stored.
+  const float* grow[MTW];
+  const float* arow[CTW];
 #pragma unroll
-    for (int x = 0; x < MTW; ++x) {
-      const int m = m0 + x * 16 + r;
-      A[x] = (ok && m < cout) ? ldg4(gout + (int64_t)img * g_stride + (int64_t)m * HW + q) : zero4();
-    }
+  for (int x = 0; x < MTW; ++x) grow[x] = gout + (int64_t)min(m0 + x * 16 + r, cout - 1) * HW;
+#pragma unroll
+  for (int y = 0; y < CTW; ++y) arow[y] = a + (int64_t)min(c0 + y * 16 + r, cin - 1) * HW;
+  auto request = [&](int s, float4(&A)[MTW], float4(&Bv)[CTW]) {
+    const int sc = min(s, total_steps - 1);
+    const int img = sc / spi, q = min((sc - img * spi) * 16 + 4 * kk, HW - 4);  // HW % 4 == 0
+#pragma unroll
+    for (int x = 0; x < MTW; ++x) A[x] = ldg4(grow[x] + (int64_t)img * g_stride + q);
+#pragma unroll
+    for (int y = 0; y < CTW; ++y) Bv[y] = ldg4(arow[y] + (int64_t)img * a_stride + q);
+  };
+  auto step = [&](int s, float4(&A)[MTW], float4(&Bv)[CTW]) {
+    const int img = s / spi, q = (s - img * spi) * 16 + 4 * kk;
+    const bool ok = s < s_end && q < HW;
+    float4 Au[MTW], Bu[CTW];
+#pragma unroll
+    for (int x = 0; x < MTW; ++x) Au[x] = ok ? A[x] : zero4();
 #pragma unroll
     for (int y = 0; y < CTW; ++y) {
-      const int c = c0 + y * 16 + r;
-      Bv[y] = (ok && c < cin) ? ldg4(a + (int64_t)img * a_stride + (int64_t)c * HW + q) : zero4();
-      if (PRO && ok && c < cin) {
-        Bv[y].x = fmaxf(__fmaf_rn(Bv[y].x, fl[y].x, fl[y].y), 0.f);
-        Bv[y].y = fmaxf(__fmaf_rn(Bv[y].y, fl[y].x, fl[y].y), 0.f);
-        Bv[y].z = fmaxf(__fmaf_rn(Bv[y].z, fl[y].x, fl[y].y), 0.f);
-        Bv[y].w = fmaxf(__fmaf_rn(Bv[y].w, fl[y].x, fl[y].y), 0.f);
+      Bu[y] = Bv[y];
+      if (PRO) {
+        Bu[y].x = fmaxf(__fmaf_rn(Bu[y].x, fl[y].x, fl[y].y), 0.f);
+        Bu[y].y = fmaxf(__fmaf_rn(Bu[y].y, fl[y].x, fl[y].y), 0.f);
+        Bu[y].z = fmaxf(__fmaf_rn(Bu[y].z, fl[y].x, fl[y].y), 0.f);
+        Bu[y].w = fmaxf(__fmaf_rn(Bu[y].w, fl[y].x, fl[y].y), 0.f);
       }
     }
+    request(s + 8, A, Bv);  // this stage's next use
 #pragma unroll
     for (int e = 0; e < 4; ++e)
 #pragma unroll
       for (int x = 0; x < MTW; ++x)
 #pragma unroll
-        for (int y = 0; y < CTW; ++y) acc[x * CTW + y] = mfma16(elem(A[x], e), elem(Bv[y], e), acc[x * CTW + y]);
+        for (int y = 0; y < CTW; ++y) acc[x * CTW + y] = mfma16(elem(Au[x], e), elem(Bu[y], e), acc[x * CTW + y]);
+  };
+  {
+    float4 A0[MTW], B0[CTW], A1[MTW], B1[CTW];
+    const int s0 = s_begin + wave;
+    request(s0, A0, B0);
+    request(s0 + 4, A1, B1);
+    for (int s = s0; s < s_end; s += 8) {
+      step(s, A0, B0);
+      step(s + 4, A1, B1);
+    }
   }
 
   reduce_waves<MTW * CTW>(acc, lds, wave, lane, 4);
@@ -817,27 +843,54 @@ __global__ __launch_bounds__(256) void k_wgrad3x3_fast(
     v.z = fmaxf(__fmaf_rn(v.z, f.x, f.y), 0.f); v.w = fmaxf(__fmaf_rn(v.w, f.x, f.y), 0.f);
     return v;
   };
-  const int seg0_4 = (64 + 2 * W + 8) >> 2;  // float4 columns of the first chunk
-  for (int row = tid >> 4; row < CB; row += 16) {
-    const int ch = c0 + row;
-    const float* src = ab + (int64_t)ch * HW;
-    float2 f = make_float2(1.f, 0.f);
-    if (PRO && ch < cin) f = fold[ch];
-    for (int c4 = tid & 15; c4 < seg0_4; c4 += 16) {
-      const int qq = origin + 4 * c4;
-      const bool ok = ch < cin && qq >= 0 && qq < HW;
-      float4 v = ok ? ldg4(src + qq) : zero4();
-      if (PRO && ok) v = bnrelu(v, f);
-      *reinterpret_cast<float4*>(&lds[row * PA + 4 * c4]) = v;
-    }
-  }
-  // per-thread constants of the later chunks: thread (row group, float4 column) -> CTW rows
+  // per-thread constants: thread (row group, float4 column) -> CTW rows, in every chunk
   const int prow = tid >> 4, pc4 = tid & 15;
   float2 pf[CTW];
 #pragma unroll
   for (int u = 0; u < CTW; ++u) {
-    const int ch = c0 + u * 16 + prow;
-    pf[u] = (PRO && ch < cin) ? fold[ch] : make_float2(1.f, 0.f);
+    pf[u] = make_float2(1.f, 0.f);
+    if (PRO) pf[u] = fold[min(c0 + u * 16 + prow, cin - 1)];
+  }
+  const int seg0_4 = (64 + 2 * W + 8) >> 2;  // float4 columns of the first chunk
+  if (seg0_4 <= 48) {
+    // all of the first chunk's loads at once, unconditional at clamped addresses (conditional
+    // loads are waited for one by one); what lies outside the image or the tensor is zeroed
+    // when it is written to LDS
+    // (threads past the chunk's last column repeat that column: same load, same store)
+    float4 v0[CTW][3];
+#pragma unroll
+    for (int u = 0; u < CTW; ++u) {
+      const float* src = ab + (int64_t)min(c0 + u * 16 + prow, cin - 1) * HW;
+#pragma unroll
+      for (int i = 0; i < 3; ++i)
+        v0[u][i] = ldg4(src + min(max(origin + 4 * min(pc4 + 16 * i, seg0_4 - 1), 0), HW - 4));
+    }
+#pragma unroll
+    for (int u = 0; u < CTW; ++u) {
+      const int row = u * 16 + prow, ch = c0 + row;
+#pragma unroll
+      for (int i = 0; i < 3; ++i) {
+        const int c4 = min(pc4 + 16 * i, seg0_4 - 1), qq = origin + 4 * c4;
+        float4 v = v0[u][i];
+        if (PRO) v = bnrelu(v, pf[u]);
+        if (!(ch < cin && qq >= 0 && qq < HW)) v = zero4();
+        *reinterpret_cast<float4*>(&lds[row * PA + 4 * c4]) = v;
+      }
+    }
+  } else {
+    for (int row = tid >> 4; row < CB; row += 16) {
+      const int ch = c0 + row;
+      const float* src = ab + (int64_t)ch * HW;
+      float2 f = make_float2(1.f, 0.f);
+      if (PRO && ch < cin) f = fold[ch];
+      for (int c4 = tid & 15; c4 < seg0_4; c4 += 16) {
+        const int qq = origin + 4 * c4;
+        const bool ok = ch < cin && qq >= 0 && qq < HW;
+        float4 v = ok ? ldg4(src + qq) : zero4();
+        if (PRO && ok) v = bnrelu(v, f);
+        *reinterpret_cast<float4*>(&lds[row * PA + 4 * c4]) = v;
+      }
+    }
   }
   __syncthreads();
 
@@ -845,14 +898,14 @@ __global__ __launch_bounds__(256) void k_wgrad3x3_fast(
 #pragma unroll
   for (int t = 0; t < NT; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  float4 An[MTW];  // gradient operand, one step ahead
-  {
-    const int q = q0 + wave * 16 + 4 * kk;
+  // gradient operand, one step ahead; loaded unconditionally at clamped addresses (pixels past
+  // the image are zeroed when the step consumes it, rows past cout are never stored)
+  float4 An[MTW];
+  const float* grow[MTW];
 #pragma unroll
-    for (int x = 0; x < MTW; ++x) {
-      const int m = m0 + x * 16 + r;
-      An[x] = (q < HW && m < cout) ? ldg4(gb + (int64_t)m * HW + q) : zero4();
-    }
+  for (int x = 0; x < MTW; ++x) {
+    grow[x] = gb + (int64_t)min(m0 + x * 16 + r, cout - 1) * HW;
+    An[x] = ldg4(grow[x] + min(q0 + wave * 16 + 4 * kk, HW - 4));
   }
   for (int ms = 0; ms < nms; ++ms) {
     // request the next chunk: columns [64(ms+1) + 2W + 8, +64) of the tile
@@ -870,15 +923,10 @@ __global__ __launch_bounds__(256) void k_wgrad3x3_fast(
     const int pw = (ms * 4 + wave) * 16 + 4 * kk, q = q0 + pw;
     float4 A[MTW];
 #pragma unroll
-    for (int x = 0; x < MTW; ++x) A[x] = An[x];
-    if (more) {  // the gradient operand of the next step, requested before this step's MFMAs
-      const int qn = q + 64;
+    for (int x = 0; x < MTW; ++x) A[x] = q < HW ? An[x] : zero4();
+    // the gradient operand of the next step, requested before this step's MFMAs
 #pragma unroll
-      for (int x = 0; x < MTW; ++x) {
-        const int m = m0 + x * 16 + r;
-        An[x] = (qn < HW && m < cout) ? ldg4(gb + (int64_t)m * HW + qn) : zero4();
-      }
-    }
+    for (int x = 0; x < MTW; ++x) An[x] = ldg4(grow[x] + min(q + 64, HW - 4));
     const int wc = q % W;
     const bool maskL = wc == 0, maskR = wc + 3 == W - 1;
 #pragma unroll
