@@ -217,15 +217,29 @@ __global__ __launch_bounds__(kThreads) void k_bn_bwd_partial(
   const float* xp = x + (int64_t)n0 * x_stride + inner;
   const float* gp = dact + (int64_t)n0 * dact_stride + inner;
   float sb = 0.f, sg = 0.f;
-  for (RowIter it(hwv, threadIdx.x, blockDim.x); it.img < ni; it.next()) {
-    float t[V], g[V];
-    Vec<V>::ld(xp + (int64_t)it.img * x_stride + (int64_t)it.q * V, t);
-    Vec<V>::ld(gp + (int64_t)it.img * dact_stride + (int64_t)it.q * V, g);
+  // four positions per pass: all eight loads are issued (unconditionally; a position past the
+  // range repeats the last image's) before the first is consumed
+  for (RowIter it(hwv, threadIdx.x, blockDim.x); it.img < ni;) {
+    float t[4][V], g[4][V];
+    bool ok[4];
 #pragma unroll
-    for (int e = 0; e < V; ++e) {
-      const float dz = __fmaf_rn(t[e], scale, shift) > 0.f ? g[e] : 0.f;
-      sb += dz;
-      sg = __fmaf_rn(dz, (t[e] - mu) * is, sg);
+    for (int u = 0; u < 4; ++u) {
+      ok[u] = it.img < ni;
+      const int im = ok[u] ? it.img : ni - 1;
+      Vec<V>::ld(xp + (int64_t)im * x_stride + (int64_t)it.q * V, t[u]);
+      Vec<V>::ld(gp + (int64_t)im * dact_stride + (int64_t)it.q * V, g[u]);
+      it.next();
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (ok[u]) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          const float dz = __fmaf_rn(t[u][e], scale, shift) > 0.f ? g[u][e] : 0.f;
+          sb += dz;
+          sg = __fmaf_rn(dz, (t[u][e] - mu) * is, sg);
+        }
+      }
     }
   }
   sb = block_sum(sb, red);
@@ -271,21 +285,36 @@ __global__ __launch_bounds__(kThreads) void k_bn_bwd_apply(
   const float* xp = x + (int64_t)n0 * x_stride + inner;
   const float* gp = dact + (int64_t)n0 * dact_stride + inner;
   float* dp = du + (int64_t)n0 * du_stride + inner;
-  for (RowIter it(hwv, threadIdx.x, blockDim.x); it.img < ni; it.next()) {
-    float t[V], g[V], r[V];
-    const int64_t qo = (int64_t)it.q * V;
-    Vec<V>::ld(xp + (int64_t)it.img * x_stride + qo, t);
-    Vec<V>::ld(gp + (int64_t)it.img * dact_stride + qo, g);
-    float* d = dp + (int64_t)it.img * du_stride + qo;
-    if (ACC) Vec<V>::ld(d, r);
+  // four positions per pass, all loads issued before the first is consumed (as in the partial
+  // kernel); dact may alias du: a thread reads its four positions before it writes them
+  for (RowIter it(hwv, threadIdx.x, blockDim.x); it.img < ni;) {
+    float t[4][V], g[4][V], r[4][V];
+    float* d[4];
+    bool ok[4];
 #pragma unroll
-    for (int e = 0; e < V; ++e) {
-      const float dz = __fmaf_rn(t[e], scale, shift) > 0.f ? g[e] : 0.f;
-      const float xh = (t[e] - mu) * is;
-      const float v = scale * (dz - mb - xh * mg);
-      r[e] = ACC ? r[e] + v : v;
+    for (int u = 0; u < 4; ++u) {
+      ok[u] = it.img < ni;
+      const int im = ok[u] ? it.img : ni - 1;
+      const int64_t qo = (int64_t)it.q * V;
+      Vec<V>::ld(xp + (int64_t)im * x_stride + qo, t[u]);
+      Vec<V>::ld(gp + (int64_t)im * dact_stride + qo, g[u]);
+      d[u] = dp + (int64_t)im * du_stride + qo;
+      if (ACC) Vec<V>::ld(d[u], r[u]);
+      it.next();
     }
-    Vec<V>::st(d, r);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (ok[u]) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+          const float dz = __fmaf_rn(t[u][e], scale, shift) > 0.f ? g[u][e] : 0.f;
+          const float xh = (t[u][e] - mu) * is;
+          const float v = scale * (dz - mb - xh * mg);
+          r[u][e] = ACC ? r[u][e] + v : v;
+        }
+        Vec<V>::st(d[u], r[u]);
+      }
+    }
   }
 }
 

@@ -118,7 +118,15 @@ def back(t):
 
 
 OP_SHAPES = [(2, 16, 8, 8, 8, 1), (2, 32, 8, 8, 8, 3), (2, 8, 32, 8, 8, 3), (1, 24, 16, 7, 7, 3), (2, 40, 64, 14, 14, 1),
-             (1, 192, 48, 12, 20, 3), (2, 48, 192, 9, 11, 3), (1, 200, 192, 10, 10, 1)]
+             (1, 192, 48, 12, 20, 3), (2, 48, 192, 9, 11, 3), (1, 200, 192, 10, 10, 1),
+             # 1x1 with nine input chunks, the last one 8 channels wide (forward takes the four-chunk ring);
+             # weight gradient over 3 x 2 channel groups with a ragged last pixel tile
+             (2, 520, 200, 9, 7, 1),
+             # 1x1 whose data gradient reduces over nine chunks; output channels over three workgroup rows
+             (1, 64, 576, 6, 6, 1),
+             # 3x3 weight gradient: two row tiles per image and two channel groups; then more tiles than
+             # splits (two tiles per workgroup)
+             (5, 72, 16, 14, 14, 3), (130, 8, 8, 4, 4, 3)]
 
 
 @pytest.mark.parametrize("n,cin,cout,h,w,ks", OP_SHAPES)
@@ -146,7 +154,7 @@ def test_nhwc_conv_ops(dnb, oracle, n, cin, cout, h, w, ks, g_f32):
     assert_close(dw.cpu().numpy(), oracle.conv_wgrad(x, g, ks), 1e-2, "wgrad")
 
 
-@pytest.mark.parametrize("shape", [(2, 16, 8, 8), (3, 40, 7, 5), (2, 264, 6, 6)])
+@pytest.mark.parametrize("shape", [(2, 16, 8, 8), (3, 40, 7, 5), (2, 264, 6, 6), (4, 24, 40, 40), (2, 192, 28, 28)])
 @pytest.mark.parametrize("accumulate", [0, 1])
 def test_nhwc_bn_relu_backward(dnb, oracle, shape, accumulate):
     r = np.random.default_rng(6)
