@@ -37,6 +37,8 @@
 #include "dnb_internal.h"
 #include <hip/hip_ext.h>
 
+#include <type_traits>
+
 #include "dnb_stats.cuh"
 
 namespace dnb {
@@ -894,70 +896,87 @@ __global__ __launch_bounds__(256) void k_wgrad3x3_fast(
   }
   __syncthreads();
 
-  f32x4 acc[NT];
+  // The four waves split the NT accumulator tiles (contiguous ranges of (m-tile, c-tile, tap)), not
+  // the pixels: every wave walks all 16-pixel steps of the tile and there is nothing to add
+  // across waves at the end.  A tile's three horizontal taps share one LDS row read (16 bytes
+  // plus the two edge elements).  The code of a wave's range is instantiated per wave so that
+  // every tile index is static.
+  constexpr int TPW = (NT + 3) / 4;
+  f32x4 acc[TPW];
 #pragma unroll
-  for (int t = 0; t < NT; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int t = 0; t < TPW; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  // gradient operand, one step ahead; loaded unconditionally at clamped addresses (pixels past
-  // the image are zeroed when the step consumes it, rows past cout are never stored)
-  float4 An[MTW];
+  // gradient operand of the four steps of a pass (every wave loads all of them), one pass ahead;
+  // loaded unconditionally at clamped addresses: pixels past the image are zeroed when the step
+  // consumes them, rows past cout are never stored
   const float* grow[MTW];
 #pragma unroll
-  for (int x = 0; x < MTW; ++x) {
-    grow[x] = gb + (int64_t)min(m0 + x * 16 + r, cout - 1) * HW;
-    An[x] = ldg4(grow[x] + min(q0 + wave * 16 + 4 * kk, HW - 4));
-  }
+  for (int x = 0; x < MTW; ++x) grow[x] = gb + (int64_t)min(m0 + x * 16 + r, cout - 1) * HW;
+  float4 An[4][MTW];
+#pragma unroll
+  for (int sub = 0; sub < 4; ++sub)
+#pragma unroll
+    for (int x = 0; x < MTW; ++x) An[sub][x] = ldg4(grow[x] + min(q0 + sub * 16 + 4 * kk, HW - 4));
+
   for (int ms = 0; ms < nms; ++ms) {
     // request the next chunk: columns [64(ms+1) + 2W + 8, +64) of the tile
     float4 nxt[CTW];
     const bool more = ms + 1 < nms;
     const int ncol = 64 * (ms + 1) + 2 * W + 8 + 4 * pc4;  // column of this thread's float4
     const int nq = origin + ncol;
-    if (more) {
 #pragma unroll
-      for (int u = 0; u < CTW; ++u) {
-        const int ch = min(c0 + u * 16 + prow, cin - 1);
-        nxt[u] = ldg4(ab + (int64_t)ch * HW + min(max(nq, 0), HW - 4));
-      }
+    for (int u = 0; u < CTW; ++u) {
+      const int ch = min(c0 + u * 16 + prow, cin - 1);
+      nxt[u] = ldg4(ab + (int64_t)ch * HW + min(max(nq, 0), HW - 4));
     }
-    const int pw = (ms * 4 + wave) * 16 + 4 * kk, q = q0 + pw;
-    float4 A[MTW];
+    float4 A[4][MTW];
 #pragma unroll
-    for (int x = 0; x < MTW; ++x) A[x] = q < HW ? An[x] : zero4();
-    // the gradient operand of the next step, requested before this step's MFMAs
+    for (int sub = 0; sub < 4; ++sub) {
+      const bool in = q0 + (ms * 4 + sub) * 16 + 4 * kk < HW;
 #pragma unroll
-    for (int x = 0; x < MTW; ++x) An[x] = ldg4(grow[x] + min(q + 64, HW - 4));
-    const int wc = q % W;
-    const bool maskL = wc == 0, maskR = wc + 3 == W - 1;
+      for (int x = 0; x < MTW; ++x) A[sub][x] = in ? An[sub][x] : zero4();
+    }
 #pragma unroll
-    for (int y = 0; y < CTW; ++y) {
+    for (int sub = 0; sub < 4; ++sub)
 #pragma unroll
-      for (int di = -1; di <= 1; ++di) {
-        const float* rowp = &lds[(y * 16 + r) * PA + pw + 4 + W + di * W];
-        const float4 V = *reinterpret_cast<const float4*>(rowp);
-        const float eL = maskL ? 0.f : rowp[-1];
-        const float eR = maskR ? 0.f : rowp[4];
+      for (int x = 0; x < MTW; ++x)
+        An[sub][x] = ldg4(grow[x] + min(q0 + ((ms + 1) * 4 + sub) * 16 + 4 * kk, HW - 4));
+
+    auto steps = [&](auto wv) {
+      constexpr int WV = decltype(wv)::value;
+      constexpr int T0 = WV * TPW, T1 = (T0 + TPW < NT) ? T0 + TPW : NT;
 #pragma unroll
-        for (int dj = -1; dj <= 1; ++dj) {
-          const int t = (di + 1) * 3 + (dj + 1);
+      for (int sub = 0; sub < 4; ++sub) {
+        const int pw = (ms * 4 + sub) * 16 + 4 * kk, wc = (q0 + pw) % W;
+        const bool maskL = wc == 0, maskR = wc + 3 == W - 1;
+        float4 V = zero4();
+        float eL = 0.f, eR = 0.f;
+#pragma unroll
+        for (int T = T0; T < T1; ++T) {
+          const int x = T / (CTW * 9), y = (T / 9) % CTW, t = T % 9, di = t / 3 - 1, dj = t % 3 - 1;
+          if (T == T0 || t % 3 == 0) {  // first tap of this row in the wave's range
+            const int o = (y * 16 + r) * PA + pw + 4 + W + di * W;
+            V = *reinterpret_cast<const float4*>(&lds[o]);
+            eL = maskL ? 0.f : lds[o - 1];
+            eR = maskR ? 0.f : lds[o + 4];
+          }
           const float b0 = dj < 0 ? eL : (dj == 0 ? V.x : V.y);
           const float b1 = dj < 0 ? V.x : (dj == 0 ? V.y : V.z);
           const float b2 = dj < 0 ? V.y : (dj == 0 ? V.z : V.w);
           const float b3 = dj < 0 ? V.z : (dj == 0 ? V.w : eR);
-#pragma unroll
-          for (int x = 0; x < MTW; ++x) {
-            f32x4& d = acc[(x * CTW + y) * 9 + t];
-            if (DNB_DBG & 8192) {
-              d[0] += A[x].x * b0; d[1] += A[x].y * b1; d[2] += A[x].z * b2; d[3] += A[x].w * b3;
-            } else {
-              d = mfma16(A[x].x, b0, d);
-              d = mfma16(A[x].y, b1, d);
-              d = mfma16(A[x].z, b2, d);
-              d = mfma16(A[x].w, b3, d);
-            }
-          }
+          f32x4& d = acc[T - T0];
+          d = mfma16(A[sub][x].x, b0, d);
+          d = mfma16(A[sub][x].y, b1, d);
+          d = mfma16(A[sub][x].z, b2, d);
+          d = mfma16(A[sub][x].w, b3, d);
         }
       }
+    };
+    switch (wave) {
+      case 0: steps(std::integral_constant<int, 0>{}); break;
+      case 1: steps(std::integral_constant<int, 1>{}); break;
+      case 2: steps(std::integral_constant<int, 2>{}); break;
+      default: steps(std::integral_constant<int, 3>{}); break;
     }
     if (more) {
 #pragma unroll
@@ -973,14 +992,14 @@ __global__ __launch_bounds__(256) void k_wgrad3x3_fast(
     }
   }
 
-  if (!(DNB_DBG & 2048)) reduce_waves<NT>(acc, lds, wave, lane, 4);  // reuses the activation tile's LDS (barrier inside)
-  if (wave == 0 && (!(DNB_DBG & 4096) || acc[0][0] == 12345.f)) {
-    // the partial is stored in accumulator order (tile, lane, 4 rows): 16-byte stores, contiguous
-    // across the wave; k_sum_wgrad3x3 adds the partials and puts the sums in OIHW order
-    float* pb = part + (((int64_t)blockIdx.x * gridDim.z + blockIdx.z) * gridDim.y + blockIdx.y) * (NT * 256);
+  // the partial is stored in accumulator order (tile, lane, 4 rows): 16-byte stores, contiguous
+  // across the wave; k_sum_wgrad3x3 adds the partials and puts the sums in OIHW order
+  float* pb = part + (((int64_t)blockIdx.x * gridDim.z + blockIdx.z) * gridDim.y + blockIdx.y) * (NT * 256);
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
-      *reinterpret_cast<float4*>(&pb[(t * 64 + lane) * 4]) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
+  for (int t = 0; t < TPW; ++t) {
+    const int T = wave * TPW + t;
+    if (T < NT)
+      *reinterpret_cast<float4*>(&pb[(T * 64 + lane) * 4]) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
   }
 }
 
