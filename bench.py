@@ -184,48 +184,65 @@ def event_time_ms(torch, fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
-DOMINANT_KERNEL = "k_wgrad3x3_fast<1, 3, true>"
-# HBM bytes per launch of that kernel from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each
-# scaled by the copy kernel of known size), summarised in profiles/; valid for that workload only.
-MEASURED_TRAFFIC = {"config2:64": 41039579}   # profiles/bc100_b64_fp32_wgrad3x3_hbm_traffic.txt, first dense block shape
+DOMINANT_KERNEL = "k_wgrad1x1_fast<3, 4, true>"
+# HBM bytes per launch of that kernel (average over the launches timed below) from the two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by the copy kernel of known size),
+# summarised in profiles/; valid for that workload only.
+MEASURED_TRAFFIC = {}   # filled from profiles/bc100_b64_fp32_wgrad1x1_hbm_traffic.txt
+HBM_PEAK_GBS = 8000.0
 
 
 def dominant_kernel_roofline(dnb, torch, runs, traffic_key):
     """Live measurement of the kernel with the largest share of the step in the committed
-    rocprofv3 summary (profiles/): the fused schedule's 3x3 weight gradient -- BN2+ReLU of b_l
-    recomputed while the activation tile is staged, fp32 MFMA with pixels on the K axis, all
-    k x B x 9 outputs kept in accumulators, partial sums per workgroup.  It is bound by the fp32
-    matrix pipe: 18*P*B*k algorithmic flops per launch (useful flops: the padding of k = 12 to a
-    16-row tile is not counted).  The layer shape of the workload's largest dense block (all its
-    layers have the same 3x3: B x k at P pixels) is launched through the single-op entry point,
-    each launch stamping its own pair of events at the kernel's start and end on the launch
-    stream."""
+    rocprofv3 summary (profiles/): the fused schedule's 1x1 weight gradient -- BN1+ReLU of the
+    concatenated features recomputed in the operand load, fp32 MFMA with pixels on the K axis,
+    operands straight from HBM, one partial per workgroup.  Per launch it reads P*(C_l + B)*4
+    bytes and writes C_l*B*4 (algorithmic bytes) for 2*P*C_l*B flops: at these widths the HBM
+    roof (8 TB/s) binds a little before the fp32 matrix pipe does, and the roof whose time over
+    the launches below is the larger is reported.  The launches are the layers of the workload's
+    largest dense block that take this instantiation (C_l >= 49: four or more 16-channel
+    tiles), with the block's own slab stride, through the single-op entry point, each launch
+    stamping its own pair of events at the kernel's start and end on the launch stream."""
     import numpy as np
     cfg = runs[0].cfg
-    n, B, k, h, w = cfg.n, cfg.bottleneck, cfg.growth, cfg.h, cfg.w
+    n, B, k, h, w, m = cfg.n, cfg.bottleneck, cfg.growth, cfg.h, cfg.w, cfg.layers
     hw = h * w
-    x = torch.randn((n, B, h, w), device="cuda")
-    g = torch.randn((n, k, h, w), device="cuda")
-    fold = torch.stack([torch.ones(B, device="cuda"), torch.zeros(B, device="cuda")], dim=1).contiguous()
-    dw = torch.empty((k, B, 3, 3), device="cuda")
-    scratch = torch.empty(dnb.dnb_op_conv_wgrad_scratch_bytes(n, B, k, h, w, 3), dtype=torch.uint8, device="cuda")
-    args = (x, B * hw, fold, g, k * hw, dw, n, B, k, h, w, 3, scratch)
-    dnb.dnb_op_conv_bnrelu_wgrad(*args)   # warm
-    reps = 20
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
-    for e0, e1 in evs:
-        e0.record(); e1.record()   # creates the handles; the launch below re-stamps both
-        dnb.dnb_op_conv_bnrelu_wgrad(*args, ev_start=e0, ev_stop=e1)
-    torch.cuda.synchronize()
-    ms = float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
-    flops = 18.0 * n * hw * B * k
-    achieved = flops / (ms * 1e-3) / 1e12
-    return {"bound": "mfma", "kernel": DOMINANT_KERNEL + " (3x3 weight gradient with BN2+ReLU prologue)",
-            "achieved": round(achieved, 2), "peak": MFMA_F32_PEAK_TF, "unit": "TFLOP/s",
-            "frac": round(achieved / MFMA_F32_PEAK_TF, 4), "traffic": MEASURED_TRAFFIC.get(traffic_key),
-            "avg_launch_ms": round(ms, 5), "algorithmic_flops_per_launch": int(flops),
-            "algorithmic_bytes_per_launch": int((B + k) * n * hw * 4), "launches_averaged": reps,
-            "shapes": "3x3 weight gradient %d x %d x 9 over P = %d pixels (every layer of the first dense block)" % (k, B, n * hw)}
+    c_out = cfg.c0 + m * k
+    y = torch.randn((n, c_out, h, w), device="cuda")
+    g = torch.randn((n, B, h, w), device="cuda")
+    cs = [cfg.c0 + (l - 1) * k for l in range(1, m + 1) if cfg.c0 + (l - 1) * k >= 49]
+    reps = 3
+    ms_sum, flops, nbytes, launches = 0.0, 0.0, 0.0, 0
+    for c in cs:
+        fold = torch.stack([torch.ones(c, device="cuda"), torch.zeros(c, device="cuda")], dim=1).contiguous()
+        dw = torch.empty((B, c, 1, 1), device="cuda")
+        scratch = torch.empty(dnb.dnb_op_conv_wgrad_scratch_bytes(n, c, B, h, w, 1), dtype=torch.uint8, device="cuda")
+        args = (y, c_out * hw, fold, g, B * hw, dw, n, c, B, h, w, 1, scratch)
+        dnb.dnb_op_conv_bnrelu_wgrad(*args)   # warm
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for e0, e1 in evs:
+            e0.record(); e1.record()   # creates the handles; the launch below re-stamps both
+            dnb.dnb_op_conv_bnrelu_wgrad(*args, ev_start=e0, ev_stop=e1)
+        torch.cuda.synchronize()
+        ms_sum += float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
+        flops += 2.0 * n * hw * c * B
+        nbytes += 4.0 * (n * hw * (c + B) + c * B)
+        launches += 1
+    ms = ms_sum / launches
+    t_hbm, t_mfma = nbytes / (HBM_PEAK_GBS * 1e9), flops / (MFMA_F32_PEAK_TF * 1e12)
+    common = {"kernel": DOMINANT_KERNEL + " (1x1 weight gradient with BN1+ReLU prologue)",
+              "traffic": MEASURED_TRAFFIC.get(traffic_key), "avg_launch_ms": round(ms, 5),
+              "algorithmic_flops_per_launch": int(flops / launches),
+              "algorithmic_bytes_per_launch": int(nbytes / launches), "launches_averaged": launches * reps,
+              "shapes": "1x1 weight gradient %d x C_l over P = %d pixels, C_l = %d..%d (the %d layers of the first dense "
+                        "block with C_l >= 49)" % (B, n * hw, cs[0], cs[-1], launches)}
+    if t_hbm >= t_mfma:
+        achieved = nbytes / (ms_sum * 1e-3) / 1e9
+        return dict({"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4)}, **common)
+    achieved = flops / (ms_sum * 1e-3) / 1e12
+    return dict({"bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_F32_PEAK_TF, "unit": "TFLOP/s",
+                 "frac": round(achieved / MFMA_F32_PEAK_TF, 4)}, **common)
 
 
 def cpu_baseline(wl, blocks):
