@@ -188,7 +188,7 @@ DOMINANT_KERNEL = "k_wgrad1x1_fast<3, 4, true>"
 # HBM bytes per launch of that kernel (average over the launches timed below) from the two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by the copy kernel of known size),
 # summarised in profiles/; valid for that workload only.
-MEASURED_TRAFFIC = {}   # filled from profiles/bc100_b64_fp32_wgrad1x1_hbm_traffic.txt
+MEASURED_TRAFFIC = {"config2:64": 74636145}   # profiles/bc100_b64_fp32_wgrad1x1_hbm_traffic.txt, average over the launches timed below
 HBM_PEAK_GBS = 8000.0
 
 

@@ -20,6 +20,7 @@
 //     reduction + ~10 rest; accumulator-order stores brought it to 22.5 us.  A two-region tree
 //     reduction ((0+2)+(1+3)) was slower than the chain (29 us); staging the tile progressively
 //     and prefetching the gradient operand changed nothing (neither is on the critical path).
+//     Splitting the tiles instead of the pixels over the waves removed the reduction: 17.6 us.
 //   * 1x1: a 3-deep register prefetch ring over the K chunks did not change the 22 us of the
 //     forward kernel; 5 us remain with loads and MFMAs removed.
 //   * BN-backward sums computed in the data-gradient convs' epilogues (to drop the separate
@@ -31,7 +32,7 @@
 #define DNB_DBG 0  // kernel ablation builds for tuning experiments (1x1: 1 no MFMA, 2/4 no activation / weight loads;
                    // 3x3: 8 no MFMA, 16/32 no activation / weight loads, 64 no statistics epilogue,
                    // 128 no output stores, 256 no K-split reduction, 512 no LDS operand reads, 1024 no staging;
-                   // 3x3 wgrad: 2048 no wave reduction, 4096 no partial stores, 8192 no MFMA)
+                   // (the 3x3 wgrad hooks 2048 / 4096 / 8192 went with its pixel-split version))
 #endif
 
 #include "dnb_internal.h"
@@ -815,9 +816,9 @@ __global__ __launch_bounds__(256) void k_wgrad1x1_fast(
 // ------------------------------------------------------------------------------- 3x3 wgrad
 //
 // dW[m][c][t] = sum_{n,q} g[n][m][q] a[n][c][q+shift(t)].  The workgroup stages CTW*16 channels
-// of a pixel range (plus halo, as in the forward kernel) in LDS; every wave takes its own
-// 16-pixel steps of that range and keeps all MTW x CTW x 9 tiles in registers.  g comes
-// straight from HBM (16 bytes per lane and step).
+// of a pixel range (plus halo, as in the forward kernel) in LDS; the MTW x CTW x 9 accumulator
+// tiles are split over the four waves and every wave takes all 16-pixel steps of the range.
+// g comes straight from HBM (16 bytes per lane and step).
 template <int MTW, int CTW, bool PRO>
 __global__ __launch_bounds__(256) void k_wgrad3x3_fast(
     const float* __restrict__ a, int64_t a_stride, const float* __restrict__ gout, int64_t g_stride,
