@@ -118,6 +118,23 @@ int forward_bf16(dnb_block* b, const void* x0, const float* params, void* yv, ch
   return DNB_OK;
 }
 
+// The two helper streams and the events of the concurrent backward pass, created on first use
+// (default priority; four events per layer: main chain done, db_l ready, storage 1/2 ready,
+// 1x1 weight gradient done).
+int ensure_helper_streams(dnb_block* b) {
+  if (b->streams_ready) return DNB_OK;
+  if (hipStreamCreateWithFlags(&b->sA, hipStreamNonBlocking) != hipSuccess) return DNB_E_LAUNCH;
+  if (hipStreamCreateWithFlags(&b->sB, hipStreamNonBlocking) != hipSuccess) return DNB_E_LAUNCH;
+  b->ev.resize((size_t)4 * (b->d.layers + 2));
+  for (auto& e : b->ev)
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
+  if (hipEventCreateWithFlags(&b->ev_start, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
+  if (hipEventCreateWithFlags(&b->ev_endA, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
+  if (hipEventCreateWithFlags(&b->ev_endB, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
+  b->streams_ready = true;
+  return DNB_OK;
+}
+
 int backward_bf16(dnb_block* b, const float* params, const void* yv, const void* dy, void* dx0, float* dparams,
                   char* ws, hipStream_t st) {
   const dnb_block_desc& d = b->d;
@@ -134,7 +151,27 @@ int backward_bf16(dnb_block* b, const float* params, const void* yv, const void*
   unsigned short* dS3 = (unsigned short*)(ws + b->off_dS3);
   const unsigned short* pack = (const unsigned short*)(ws + b->off_pack);
   const size_t B16 = (size_t)((B + 15) & ~15), k16 = (size_t)((k + 15) & ~15), B32 = (size_t)((B + 31) & ~31);
+  // Three chains, as in the fp32 backward: only the data-gradient chain (dgrad 3x3 -> BN2 bwd ->
+  // dgrad 1x1 -> BN1 bwd) carries the dependence from layer l to layer l-1.  With concurrency on,
+  // the two weight gradients (with their sums) run on helper streams, ordered by events where
+  // buffers are shared: the 3x3 needs the slab's slice g_l complete (layer l+1's BN1 backward),
+  // the 1x1 needs db_l in dS3, which the next layer's 3x3 data gradient overwrites.  The slices
+  // of the fp32 slab that the chains touch at the same time are disjoint channel ranges.
+  const bool conc = b->concurrency != 0;
+  if (conc) {
+    const int rc = ensure_helper_streams(b);
+    if (rc != DNB_OK) return rc;
+  }
+  hipStream_t sA = conc ? b->sA : st, sB = conc ? b->sB : st;
+  enum { EV_MAIN = 0, EV_DB = 1, EV_WG1 = 3 };
+  auto ev = [&](int l, int which) -> hipEvent_t { return conc ? b->ev[(size_t)4 * l + which] : nullptr; };
+  auto record = [&](hipEvent_t e, hipStream_t s) { return conc ? hipEventRecord(e, s) : hipSuccess; };
+  auto wait = [&](hipStream_t s, hipEvent_t e) { return conc ? hipStreamWaitEvent(s, e, 0) : hipSuccess; };
+
   DNB_TRY(nhwc::bf16_to_f32(dy, G, P * cout, st));
+  DNB_TRY(record(conc ? b->ev_start : nullptr, st));
+  DNB_TRY(wait(sA, conc ? b->ev_start : nullptr));
+  DNB_TRY(wait(sB, conc ? b->ev_start : nullptr));
   for (int l = m; l >= 1; --l) {
     const int c = c_in(d, l);
     const LayerParams p = layer_ptrs<LayerParams, const float>(b, params, l);
@@ -148,17 +185,36 @@ int backward_bf16(dnb_block* b, const float* params, const void* yv, const void*
     const unsigned short* pk1t = pack + b->pk[l] + B16 * c32;                         // 1x1 data gradient
     const unsigned short* pk3t = pack + b->pk[l] + B16 * c32 + c16 * B32 + 9 * k16 * B32;  // 3x3 data gradient
     const float* gl = G + c;  // gradient of x_l (fp32, pixel stride C_out), complete at this point
-    // 3x3: weight gradient (BN2+ReLU of b_l recomputed in the operand staging), data gradient
-    DNB_TRY(nhwc::wgrad(bl, B, gl, cout, true, partA, gp.W3, n, B, k, d.h, d.w, 9, fold2, st));
+
+    // ---- chain A: 3x3 weight gradient (BN2+ReLU of b_l recomputed in the operand staging)
+    if (l < m) DNB_TRY(wait(sA, ev(l + 1, EV_MAIN)));
+    DNB_TRY(nhwc::wgrad(bl, B, gl, cout, true, partA, gp.W3, n, B, k, d.h, d.w, 9, fold2, sA));
+
+    // ---- main chain: 3x3 data gradient and BN2 backward; dS3 is still read by layer l+1's 1x1
+    // weight gradient
+    if (l < m) DNB_TRY(wait(st, ev(l + 1, EV_WG1)));
     DNB_TRY(nhwc::conv(gl, cout, true, pk3t, dS3, B, n, k, B, d.h, d.w, 9, nullptr, nullptr, nullptr, st));
     DNB_TRY(nhwc::bn_relu_bwd(bl, B, dS3, B, dS3, B, nullptr, 0, P, B, p.g2, p.b2, mean_b, istd_b, gp.g2, gp.b2,
                               part, st));
-    // 1x1: weight gradient (BN1+ReLU of y[..., :C_l] recomputed in the operand staging), data gradient
-    DNB_TRY(nhwc::wgrad(y, cout, dS3, B, false, partB, gp.W1, n, c, B, d.h, d.w, 1, fold1, st));
+    DNB_TRY(record(ev(l, EV_DB), st));
+
+    // ---- chain B: 1x1 weight gradient (BN1+ReLU of y[..., :C_l] recomputed in the operand staging)
+    DNB_TRY(wait(sB, ev(l, EV_DB)));
+    DNB_TRY(nhwc::wgrad(y, cout, dS3, B, false, partB, gp.W1, n, c, B, d.h, d.w, 1, fold1, sB));
+    DNB_TRY(record(ev(l, EV_WG1), sB));
+
+    // ---- main chain, continued: 1x1 data gradient, BN1+ReLU backward and concat backward
+    // (accumulate into the slab)
     DNB_TRY(nhwc::conv(dS3, B, false, pk1t, dS2, c, n, B, c, d.h, d.w, 1, nullptr, nullptr, nullptr, st));
-    // BN1+ReLU backward and concat backward: accumulate into the slab
     DNB_TRY(nhwc::bn_relu_bwd(y, cout, dS2, c, nullptr, 0, G, cout, P, c, p.g1, p.b1, mean_y, istd_y, gp.g1,
                               gp.b1, part, st));
+    DNB_TRY(record(ev(l, EV_MAIN), st));
+  }
+  if (conc) {  // join: the caller's stream is done only when both helper chains are
+    DNB_TRY(hipEventRecord(b->ev_endA, sA));
+    DNB_TRY(hipEventRecord(b->ev_endB, sB));
+    DNB_TRY(hipStreamWaitEvent(st, b->ev_endA, 0));
+    DNB_TRY(hipStreamWaitEvent(st, b->ev_endB, 0));
   }
   DNB_TRY(nhwc::f32_rows_to_bf16(G, cout, dx0, P, d.c0, st));
   return DNB_OK;
@@ -578,16 +634,9 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
   //   A: [recompute storage 3] -> wgrad 3x3 -> sum        (needs g_l complete)
   //   B: [recompute storage 1,2] -> wgrad 1x1 -> sum      (needs db_l; storage 1 also feeds BN1 bwd)
   const bool conc = b->concurrency != 0;
-  if (conc && !b->streams_ready) {
-    if (hipStreamCreateWithFlags(&b->sA, hipStreamNonBlocking) != hipSuccess) return DNB_E_LAUNCH;
-    if (hipStreamCreateWithFlags(&b->sB, hipStreamNonBlocking) != hipSuccess) return DNB_E_LAUNCH;
-    b->ev.resize((size_t)4 * (m + 2));
-    for (auto& e : b->ev)
-      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
-    if (hipEventCreateWithFlags(&b->ev_start, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
-    if (hipEventCreateWithFlags(&b->ev_endA, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
-    if (hipEventCreateWithFlags(&b->ev_endB, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
-    b->streams_ready = true;
+  if (conc) {
+    const int rc = ensure_helper_streams(b);
+    if (rc != DNB_OK) return rc;
   }
   hipStream_t sA = conc ? b->sA : st, sB = conc ? b->sB : st;
   enum { EV_MAIN = 0, EV_DB = 1, EV_S12 = 2, EV_WG1 = 3 };

@@ -43,10 +43,11 @@ def to_bf16_values(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).to(torch.float32).numpy()
 
 
-def run_block_gpu_bf16(dnb, cfg, x0, layer_params, dy):
+def run_block_gpu_bf16(dnb, cfg, x0, layer_params, dy, concurrency=True):
     h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck,
                              dtype=dnb.DNB_BF16, layout=dnb.DNB_NHWC, schedule=dnb.DNB_SCHED_FUSED, eps=cfg.eps)
     try:
+        dnb.dnb_block_set_concurrency(h, concurrency)
         params = dev(pack_params_gpu(dnb, h, layer_params))
         ws = torch.empty(dnb.dnb_block_workspace_bytes(h), dtype=torch.uint8, device="cuda")
         ws.fill_(0xFF)
@@ -82,6 +83,18 @@ def test_bf16_block_matches_oracle(dnb, oracle, cfg):
     for l in range(1, cfg.layers + 1):
         for name in NAMES:
             assert_grad_close(gpu["dparams"][gpu["slices"][(l, name)]], ores.dparams[osl[(l, name)]], f"layer {l} d{name}")
+
+
+@pytest.mark.parametrize("cfg", [CFGS[1], CFGS[3]], ids=[IDS[1], IDS[3]])
+def test_bf16_backward_chains_on_helper_streams_give_the_same_bits(dnb, cfg):
+    """The weight gradients run on two helper streams beside the data-gradient chain; with
+    concurrency off everything runs in program order on one stream.  Same kernels, same sums."""
+    x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
+    x0, dy = to_bf16_values(x0), to_bf16_values(dy)
+    a = run_block_gpu_bf16(dnb, cfg, x0, lp, dy, concurrency=True)
+    b = run_block_gpu_bf16(dnb, cfg, x0, lp, dy, concurrency=False)
+    for key in ("y", "dx0", "dparams"):
+        assert np.array_equal(a[key], b[key]), key
 
 
 def test_bf16_bytes_and_unsupported_combinations(dnb):
