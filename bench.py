@@ -45,7 +45,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-compare", action="store_true", help="skip timing the other schedule")
     ap.add_argument("--only-block", type=int, default=-1, help="time a single dense block of the workload (diagnostic)")
-    ap.add_argument("--serial", action="store_true", help="no helper streams in backward (diagnostic: undistorted per-kernel durations)")
+    ap.add_argument("--serial", action="store_true", help="no helper streams in backward (the library's default for fp32)")
+    ap.add_argument("--concurrent", action="store_true", help="weight gradients on helper streams in backward (the library's default for bf16)")
     ap.add_argument("--forward-only", action="store_true", help="time the forward pass alone (diagnostic, not the metric)")
     return ap.parse_args()
 
@@ -320,9 +321,9 @@ def main():
 
     def measure(schedule):
         runs = [BlockRun(dnb, torch, wl, c, sched[schedule], 10 * i, bf16) for i, c in enumerate(blocks)]
-        if a.serial:
+        if a.serial or a.concurrent:
             for r in runs:
-                dnb.dnb_block_set_concurrency(r.h, False)
+                dnb.dnb_block_set_concurrency(r.h, a.concurrent)
         secs = time_steps(torch, make_step(dnb, runs, a.forward_only), a.steps, a.warmup, use_graph)
         return runs, secs
 
@@ -338,8 +339,8 @@ def main():
 
     def measure_net(schedule):
         r = NetRun(dnb, torch, wl, ncfg, sched[schedule])
-        if a.serial:
-            dnb.dnb_net_set_concurrency(r.h, False)
+        if a.serial or a.concurrent:
+            dnb.dnb_net_set_concurrency(r.h, a.concurrent)
         secs = time_steps(torch, make_net_step(dnb, r, a.forward_only), a.steps, a.warmup, use_graph)
         return r, secs
 

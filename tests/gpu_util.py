@@ -46,12 +46,14 @@ def pack_params_oracle(orc, shape, layer_params):
     return flat
 
 
-def run_block_gpu(dnb, cfg, x0, layer_params, dy, schedule=0, poison=True, concurrency=True):
-    """Forward + backward of one block through the C ABI.  Returns dict of numpy arrays."""
+def run_block_gpu(dnb, cfg, x0, layer_params, dy, schedule=0, poison=True, concurrency=None):
+    """Forward + backward of one block through the C ABI.  Returns dict of numpy arrays.
+    concurrency=None keeps the library's default (what bench.py times)."""
     h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck,
                              schedule=schedule, eps=cfg.eps)
     try:
-        dnb.dnb_block_set_concurrency(h, concurrency)
+        if concurrency is not None:
+            dnb.dnb_block_set_concurrency(h, concurrency)
         params = dev(pack_params_gpu(dnb, h, layer_params))
         ws_bytes = dnb.dnb_block_workspace_bytes(h)
         ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")

@@ -43,11 +43,12 @@ def to_bf16_values(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).to(torch.float32).numpy()
 
 
-def run_block_gpu_bf16(dnb, cfg, x0, layer_params, dy, concurrency=True):
+def run_block_gpu_bf16(dnb, cfg, x0, layer_params, dy, concurrency=None):
     h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck,
                              dtype=dnb.DNB_BF16, layout=dnb.DNB_NHWC, schedule=dnb.DNB_SCHED_FUSED, eps=cfg.eps)
     try:
-        dnb.dnb_block_set_concurrency(h, concurrency)
+        if concurrency is not None:   # None: the library's default, what bench.py times
+            dnb.dnb_block_set_concurrency(h, concurrency)
         params = dev(pack_params_gpu(dnb, h, layer_params))
         ws = torch.empty(dnb.dnb_block_workspace_bytes(h), dtype=torch.uint8, device="cuda")
         ws.fill_(0xFF)
