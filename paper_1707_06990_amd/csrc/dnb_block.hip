@@ -22,6 +22,7 @@ struct dnb_block {
   std::vector<size_t> off_stat_b;            // per layer mean[B], istd[B]
   std::vector<size_t> off_fold1, off_fold2;  // fused schedule: per layer folded (scale, shift) of BN1 / BN2
   size_t off_part;                           // reduction partials of the main chain (BN)
+  size_t partA_floats, partB_floats;         // size of one weight-gradient partial buffer
   size_t off_partA, off_partB;               // partials of the 3x3 / 1x1 weight gradients
   // backward runs three chains: the data-gradient chain on the caller's stream and the two
   // weight-gradient chains on these helper streams (created at the first backward call)
@@ -453,10 +454,15 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
       for (int l = 1; l <= m; ++l) { b->pk[l] = pack; pack += packed_layer_floats(c_in(d, l), k, B); }
     }
   }
-  mem.scratch_bytes = (uint64_t)(part + partA + partB + pack) * sizeof(float);
+  mem.scratch_bytes = (uint64_t)(part + (bf16 ? 1 : 2) * (partA + partB) + pack) * sizeof(float);
   b->off_part = carve(part * sizeof(float), false);
-  b->off_partA = carve(partA * sizeof(float), false);
-  b->off_partB = carve(partB * sizeof(float), false);
+  // fp32: two buffers each, used alternately by consecutive layers (a layer's partials are
+  // summed by extra workgroups of the next layer's weight-gradient launch)
+  b->partA_floats = partA;
+  b->partB_floats = partB;
+  const size_t nbuf = bf16 ? 1 : 2;
+  b->off_partA = carve(nbuf * partA * sizeof(float), false);
+  b->off_partB = carve(nbuf * partB * sizeof(float), false);
   b->off_pack = carve(pack * sizeof(float), false);
   // measured on MI355X: with the weight gradients on helper streams the fp32 step is 4 % slower
   // (idle time between dependent launches of different streams outweighs the overlap), the
@@ -647,6 +653,7 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
   auto record = [&](hipEvent_t e, hipStream_t s) { return conc ? hipEventRecord(e, s) : hipSuccess; };
   auto wait = [&](hipStream_t s, hipEvent_t e) { return conc ? hipStreamWaitEvent(s, e, 0) : hipSuccess; };
 
+  PendingSum pendA, pendB, nextA, nextB;
   DNB_TRY(launch_copy_slab((const float*)dyv, ys, G, ys, n, ys, st));
   DNB_TRY(record(conc ? b->ev_start : nullptr, st));
   DNB_TRY(wait(sA, conc ? b->ev_start : nullptr));
@@ -672,11 +679,15 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
     if (recompute)  // re-populate storage 3 from the kept b_l and its cached statistics
       DNB_TRY(launch_bn_relu(bl, (int64_t)B * hw, S3, (int64_t)B * hw, nullptr, 0, n, B, hw, p.g2,
                              p.b2, StatsSrc{mean_b, istd_b, nullptr, 0, 0, 0, d.eps}, sA));
+    // (the sum of this launch's partials is left to the next layer's launch on this chain)
+    float* pA = partA + (size_t)(l & 1) * b->partA_floats;
     if (fused)  // BN2+ReLU of b_l is applied while the kernel stages its tile: nothing to re-populate
-      DNB_TRY(launch_conv_wgrad(bl, (int64_t)B * hw, gl, ys, gp.W3, n, B, k, d.h, d.w, 9, partA,
-                                (const float2*)(ws + b->off_fold2[l]), sA));
+      DNB_TRY(launch_conv_wgrad(bl, (int64_t)B * hw, gl, ys, gp.W3, n, B, k, d.h, d.w, 9, pA,
+                                (const float2*)(ws + b->off_fold2[l]), sA, nullptr, nullptr, nullptr, &pendA, &nextA));
     else
-      DNB_TRY(launch_conv_wgrad(S3, (int64_t)B * hw, gl, ys, gp.W3, n, B, k, d.h, d.w, 9, partA, nullptr, sA));
+      DNB_TRY(launch_conv_wgrad(S3, (int64_t)B * hw, gl, ys, gp.W3, n, B, k, d.h, d.w, 9, pA, nullptr, sA, nullptr,
+                                nullptr, nullptr, &pendA, &nextA));
+    pendA = nextA;
 
     // ---- chain B, first half: storage 1 and 2.  Storage 1 was last read by layer l+1's BN1
     // backward on the main chain; storage 2 by the previous wgrad on this stream.
@@ -696,12 +707,14 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
 
     // ---- chain B, second half: the 1x1 weight gradient from storage 2 and db_l
     DNB_TRY(wait(sB, ev(l, EV_DB)));
+    float* pB = partB + (size_t)(l & 1) * b->partB_floats;
     if (fused)  // BN1+ReLU of the concatenated features is applied in the operand load
-      DNB_TRY(launch_conv_wgrad(y, ys, dS3, (int64_t)B * hw, gp.W1, n, c, B, d.h, d.w, 1, partB,
-                                (const float2*)(ws + b->off_fold1[l]), sB));
+      DNB_TRY(launch_conv_wgrad(y, ys, dS3, (int64_t)B * hw, gp.W1, n, c, B, d.h, d.w, 1, pB,
+                                (const float2*)(ws + b->off_fold1[l]), sB, nullptr, nullptr, nullptr, &pendB, &nextB));
     else
       DNB_TRY(launch_conv_wgrad(S2, (int64_t)c * hw, dS3, (int64_t)B * hw, gp.W1, n, c, B, d.h, d.w, 1,
-                                partB, nullptr, sB));
+                                pB, nullptr, sB, nullptr, nullptr, nullptr, &pendB, &nextB));
+    pendB = nextB;
     DNB_TRY(record(ev(l, EV_WG1), sB));
 
     // ---- main chain, continued
@@ -714,6 +727,9 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
                                true, n, c, hw, p.g1, p.b1, mean_y, istd_y, gp.g1, gp.b1, part, st));
     DNB_TRY(record(ev(l, EV_MAIN), st));
   }
+  // the first layer's weight-gradient partials have no later launch to ride on
+  DNB_TRY(launch_pending_sum(&pendA, sA));
+  DNB_TRY(launch_pending_sum(&pendB, sB));
   if (conc) {  // join: the caller's stream is done only when both helper chains are
     DNB_TRY(hipEventRecord(b->ev_endA, sA));
     DNB_TRY(hipEventRecord(b->ev_endB, sB));

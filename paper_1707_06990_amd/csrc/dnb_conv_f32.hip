@@ -21,9 +21,14 @@ bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, f
                       int64_t out_stride, int n, int cin, int cout, int h, int w, int taps,
                       const float2* fold, float* spart, int* sT, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
 size_t conv_wgrad_fast_partial_floats(int n, int cin, int cout, int h, int w, int taps);
+// Launches the fast weight-gradient kernel if it applies (returns false otherwise).  *own
+// describes the sum of its partials, which is left to the caller; *absorb (may be null or of kind
+// 0) is carried out by extra workgroups of the same launch and cleared.
 bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
                        float* partials, float* dw, int n, int cin, int cout, int h, int w, int taps,
-                       const float2* fold, int* splits, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1);
+                       const float2* fold, PendingSum* own, PendingSum* absorb, hipStream_t st, hipEvent_t ev0,
+                       hipEvent_t ev1);
+hipError_t launch_sum_wgrad3x3(const PendingSum& p, hipStream_t st);
 
 namespace {
 
@@ -412,30 +417,42 @@ size_t conv_wgrad_partial_floats(int n, int cin, int cout, int h, int w, int tap
   return a > b ? a : b;
 }
 
+hipError_t launch_pending_sum(PendingSum* p, hipStream_t st) {
+  hipError_t e = hipSuccess;
+  if (p->kind == 1) e = launch_sum_partials(p->part, p->splits, p->count, p->out, st);
+  else if (p->kind == 2) e = launch_sum_wgrad3x3(*p, st);
+  p->kind = 0;
+  return e;
+}
+
 hipError_t launch_conv_wgrad(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
                              float* dw, int n, int cin, int cout, int h, int w, int taps,
                              float* partials, const float2* fold, hipStream_t st, hipEvent_t ev0,
-                             hipEvent_t ev1, bool* used_fast) {
-  if (cin <= 0 || cout <= 0) return hipSuccess;
+                             hipEvent_t ev1, bool* used_fast, PendingSum* absorb, PendingSum* defer) {
+  if (defer) defer->kind = 0;
+  if (cin <= 0 || cout <= 0) return absorb ? launch_pending_sum(absorb, st) : hipSuccess;
   if (used_fast) *used_fast = true;
-  const int64_t count = (int64_t)cin * cout * taps;
-  int splits = 0;
-  if (!launch_wgrad_fast(in, in_stride, g, g_stride, partials, dw, n, cin, cout, h, w, taps, fold, &splits, st, ev0,
-                         ev1)) {
-    if (used_fast) *used_fast = false;
-    if (fold) return hipErrorInvalidValue;  // the generic kernel has no BN prologue
-    const WgradPlan p = plan_wgrad(n, cin, cout, h, w, taps);
-    if (p.lds > 64 * 1024) return hipErrorInvalidValue;
-    if (taps == 9)
-      hipLaunchKernelGGL((k_conv_wgrad<9, 7>), p.grid, dim3(256), p.lds, st, in, in_stride, g, g_stride,
-                         partials, cin, cout, h, w, p.cpi, p.total, p.cps, p.mtw, p.ctw, p.PA, p.PG);
-    else
-      hipLaunchKernelGGL((k_conv_wgrad<1, 3>), p.grid, dim3(256), p.lds, st, in, in_stride, g, g_stride,
-                         partials, cin, cout, h, w, p.cpi, p.total, p.cps, p.mtw, p.ctw, p.PA, p.PG);
-    splits = p.splits;
+  PendingSum own;
+  if (launch_wgrad_fast(in, in_stride, g, g_stride, partials, dw, n, cin, cout, h, w, taps, fold, &own, absorb, st,
+                        ev0, ev1)) {
+    if (defer) { *defer = own; return hipGetLastError(); }
+    return launch_pending_sum(&own, st);
   }
-  if (splits == 0) return hipGetLastError();  // the fast 3x3 path has already summed its partials
-  return launch_sum_partials(partials, splits, count, dw, st);
+  if (used_fast) *used_fast = false;
+  if (absorb) {
+    const hipError_t e = launch_pending_sum(absorb, st);
+    if (e != hipSuccess) return e;
+  }
+  if (fold) return hipErrorInvalidValue;  // the generic kernel has no BN prologue
+  const WgradPlan p = plan_wgrad(n, cin, cout, h, w, taps);
+  if (p.lds > 64 * 1024) return hipErrorInvalidValue;
+  if (taps == 9)
+    hipLaunchKernelGGL((k_conv_wgrad<9, 7>), p.grid, dim3(256), p.lds, st, in, in_stride, g, g_stride,
+                       partials, cin, cout, h, w, p.cpi, p.total, p.cps, p.mtw, p.ctw, p.PA, p.PG);
+  else
+    hipLaunchKernelGGL((k_conv_wgrad<1, 3>), p.grid, dim3(256), p.lds, st, in, in_stride, g, g_stride,
+                       partials, cin, cout, h, w, p.cpi, p.total, p.cps, p.mtw, p.ctw, p.PA, p.PG);
+  return launch_sum_partials(partials, p.splits, (int64_t)cin * cout * taps, dw, st);
 }
 
 }  // namespace dnb

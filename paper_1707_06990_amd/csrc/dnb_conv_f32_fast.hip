@@ -695,6 +695,57 @@ __global__ __launch_bounds__(256) void k_conv3x3_v4(
   }
 }
 
+// A pending sum of partials carried out by extra workgroups of a weight-gradient launch (the
+// workgroups with blockIdx.x >= gx_main): kind 1 is k_sum_partials' job, kind 2 k_sum_wgrad3x3's,
+// with the same grouping and order of additions, so the sums have the same bits either way.
+struct SumRole {
+  int kind, wgs;  // kind 0: none; wgs: workgroups the sum needs
+  const float* part;
+  float* out;
+  int splits, G, per;
+  long long count;  // elements of one partial
+  int gy, gz, mtw, ctw, cin, cout;
+};
+
+__device__ __forceinline__ void sum_role(const SumRole& sr, int wg) {
+  extern __shared__ float sh[];  // the launch's dynamic LDS (every weight-gradient launch has >= 1 KB)
+  const int epb = 256 / sr.G;
+  const int le = threadIdx.x % epb, grp = threadIdx.x / epb;
+  const long long f = (long long)wg * epb + le;
+  float s = 0.f;
+  if (f < sr.count) {
+    int i = grp * sr.per;
+    const int end = min(sr.splits, i + sr.per);
+    for (; i + 8 <= end; i += 8) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = sr.part[(long long)(i + u) * sr.count + f];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; i < end; ++i) s += sr.part[(long long)i * sr.count + f];
+  }
+  sh[threadIdx.x] = s;
+  __syncthreads();
+  if (grp == 0 && f < sr.count) {
+    float t = sh[le];
+    for (int g = 1; g < sr.G; ++g) t += sh[g * epb + le];
+    if (sr.kind == 1) {
+      sr.out[f] = t;
+    } else {
+      const int NT = sr.mtw * sr.ctw * 9;
+      const int rr = (int)(f & 3), lane = (int)((f >> 2) & 63);
+      const long long tl = f >> 8;
+      const int tile = (int)(tl % NT), blk = (int)(tl / NT);
+      const int yb = blk % sr.gy, z = blk / sr.gy;
+      const int tap = tile % 9, y = (tile / 9) % sr.ctw, x = tile / (9 * sr.ctw);
+      const int m = z * (sr.mtw * 16) + x * 16 + 4 * (lane >> 4) + rr;
+      const int c = yb * (sr.ctw * 16) + y * 16 + (lane & 15);
+      if (m < sr.cout && c < sr.cin) sr.out[((long long)m * sr.cin + c) * 9 + tap] = t;
+    }
+  }
+}
+
 // Adds the accumulators of the waves of a workgroup into wave 0 as a chain 3 -> 2 -> 1 -> 0 through
 // one LDS region (NT * 256 floats).  (A two-region tree (0+2)+(1+3) was measured slower.)
 template <int NT>
@@ -727,8 +778,13 @@ template <int MTW, int CTW, bool PRO>
 __global__ __launch_bounds__(256) void k_wgrad1x1_fast(
     const float* __restrict__ a, int64_t a_stride, const float* __restrict__ gout, int64_t g_stride,
     float* __restrict__ part, int cin, int cout, int HW, int spi, int total_steps, int steps_per_wg,
-    const float2* __restrict__ fold) {
+    const float2* __restrict__ fold, SumRole sr, int gx_main) {
   extern __shared__ float lds[];
+  if ((int)blockIdx.x >= gx_main) {  // extra workgroups: a pending sum of another partial buffer
+    const int wg = (((int)blockIdx.x - gx_main) * gridDim.y + blockIdx.y) * gridDim.z + blockIdx.z;
+    if (wg < sr.wgs) sum_role(sr, wg);
+    return;
+  }
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, kk = lane >> 4;
   const int c0 = blockIdx.y * (CTW * 16), m0 = blockIdx.z * (MTW * 16);
@@ -826,8 +882,13 @@ template <int MTW, int CTW, bool PRO>
 __global__ __launch_bounds__(256) void k_wgrad3x3_fast(
     const float* __restrict__ a, int64_t a_stride, const float* __restrict__ gout, int64_t g_stride,
     float* __restrict__ part, int cin, int cout, int H, int W, int tiles_per_img, int nms, int PA,
-    const float2* __restrict__ fold) {
+    const float2* __restrict__ fold, SumRole sr, int gx_main) {
   extern __shared__ float lds[];
+  if ((int)blockIdx.x >= gx_main) {  // extra workgroups: a pending sum of another partial buffer
+    const int wg = (((int)blockIdx.x - gx_main) * gridDim.y + blockIdx.y) * gridDim.z + blockIdx.z;
+    if (wg < sr.wgs) sum_role(sr, wg);
+    return;
+  }
   const int HW = H * W;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, kk = lane >> 4;
@@ -1305,25 +1366,57 @@ size_t conv_wgrad_fast_partial_floats(int n, int cin, int cout, int h, int w, in
   return (size_t)p.gx * cin * cout;
 }
 
-// Returns false if the fast path does not apply; otherwise launches and reports the number
-// of partials to add in *splits.
+// Grouping of a sum of `splits` partials (the same rule the stand-alone sum kernels use).
+static void sum_grouping(int kind, int splits, int* G, int* per) {
+  int g = 1;
+  if (kind == 2) { while (g < 16 && splits / (g * 2) >= 4) g *= 2; }   // at least 4 partials per group
+  else           { while (g < 16 && splits / g > 16) g <<= 1; }         // about 16 splits per thread
+  *G = g;
+  *per = (splits + g - 1) / g;
+}
+
+hipError_t launch_sum_wgrad3x3(const PendingSum& p, hipStream_t st) {
+  int G, per;
+  sum_grouping(2, p.splits, &G, &per);
+  const int epb = 256 / G;
+  hipLaunchKernelGGL(k_sum_wgrad3x3, dim3((unsigned)((p.count + epb - 1) / epb)), dim3(256), 0, st, p.part, p.splits,
+                     p.gy, p.gz, p.mtw, p.ctw, p.cin, p.cout, p.out, G, per);
+  return hipGetLastError();
+}
+
+// Returns false if the fast path does not apply; otherwise launches the kernel, describes the sum
+// of its partials in *own (left to the caller) and has *absorb carried out by extra workgroups.
 bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
                        float* partials, float* dw, int n, int cin, int cout, int h, int w, int taps,
-                       const float2* fold, int* splits, hipStream_t st, hipEvent_t ev0, hipEvent_t ev1) {
+                       const float2* fold, PendingSum* own, PendingSum* absorb, hipStream_t st, hipEvent_t ev0,
+                       hipEvent_t ev1) {
   if (in_stride % 4 || g_stride % 4 || !aligned16(in) || !aligned16(g)) return false;
   const WgFastPlan p = plan_wgrad_fast(n, cin, cout, h, w, taps);
   if (!p.ok) return false;
-  dim3 grid((unsigned)p.gx, (unsigned)p.gy, (unsigned)p.gz);
+  SumRole sr{};
+  unsigned sx = 0;
+  if (absorb && absorb->kind != 0) {
+    sr.kind = absorb->kind;
+    sr.part = absorb->part; sr.out = absorb->out; sr.splits = absorb->splits; sr.count = absorb->count;
+    sr.gy = absorb->gy; sr.gz = absorb->gz; sr.mtw = absorb->mtw; sr.ctw = absorb->ctw;
+    sr.cin = absorb->cin; sr.cout = absorb->cout;
+    sum_grouping(sr.kind, sr.splits, &sr.G, &sr.per);
+    const int epb = 256 / sr.G;
+    sr.wgs = (int)((sr.count + epb - 1) / epb);
+    sx = (unsigned)((sr.wgs + p.gy * p.gz - 1) / (p.gy * p.gz));
+    absorb->kind = 0;
+  }
+  dim3 grid((unsigned)p.gx + sx, (unsigned)p.gy, (unsigned)p.gz);
   const int hw = h * w;
   if (taps == 1) {
 #define DNB_L(M, C)                                                                                  \
   do {                                                                                               \
     if (fold)                                                                                        \
       hipExtLaunchKernelGGL((k_wgrad1x1_fast<M, C, true>), grid, dim3(256), p.lds, st, ev0, ev1, 0, in, in_stride, g, \
-                         g_stride, partials, cin, cout, hw, p.spi, p.total_steps, p.steps_per_wg, fold); \
+                         g_stride, partials, cin, cout, hw, p.spi, p.total_steps, p.steps_per_wg, fold, sr, p.gx); \
     else                                                                                             \
       hipExtLaunchKernelGGL((k_wgrad1x1_fast<M, C, false>), grid, dim3(256), p.lds, st, ev0, ev1, 0, in, in_stride, g, \
-                         g_stride, partials, cin, cout, hw, p.spi, p.total_steps, p.steps_per_wg, fold); \
+                         g_stride, partials, cin, cout, hw, p.spi, p.total_steps, p.steps_per_wg, fold, sr, p.gx); \
   } while (0)
     const int key = p.mtw * 10 + p.ctw;
     switch (key) {
@@ -1332,15 +1425,17 @@ bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64
       case 14: DNB_L(1, 4); break; case 13: DNB_L(1, 3); break; case 12: DNB_L(1, 2); break; default: DNB_L(1, 1); break;
     }
 #undef DNB_L
+    own->kind = 1;
+    own->part = partials; own->out = dw; own->splits = p.gx; own->count = (int64_t)cin * cout;
   } else {
 #define DNB_L(M, C)                                                                                  \
   do {                                                                                               \
     if (fold)                                                                                        \
       hipExtLaunchKernelGGL((k_wgrad3x3_fast<M, C, true>), grid, dim3(256), p.lds, st, ev0, ev1, 0, in, in_stride, g, \
-                         g_stride, partials, cin, cout, h, w, p.tiles_per_img, p.nms, p.PA, fold);    \
+                         g_stride, partials, cin, cout, h, w, p.tiles_per_img, p.nms, p.PA, fold, sr, p.gx); \
     else                                                                                             \
       hipExtLaunchKernelGGL((k_wgrad3x3_fast<M, C, false>), grid, dim3(256), p.lds, st, ev0, ev1, 0, in, in_stride, g, \
-                         g_stride, partials, cin, cout, h, w, p.tiles_per_img, p.nms, p.PA, fold);    \
+                         g_stride, partials, cin, cout, h, w, p.tiles_per_img, p.nms, p.PA, fold, sr, p.gx); \
   } while (0)
     const int key = p.mtw * 10 + p.ctw;
     switch (key) {
@@ -1348,19 +1443,12 @@ bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64
       case 13: DNB_L(1, 3); break; case 12: DNB_L(1, 2); break; default: DNB_L(1, 1); break;
     }
 #undef DNB_L
+    // the 3x3 partials are in accumulator order: their sum also reorders them
+    own->kind = 2;
+    own->part = partials; own->out = dw; own->splits = p.gx;
+    own->count = (int64_t)p.gz * p.gy * p.mtw * p.ctw * 9 * 256;
+    own->gy = p.gy; own->gz = p.gz; own->mtw = p.mtw; own->ctw = p.ctw; own->cin = cin; own->cout = cout;
   }
-  if (taps == 9) {
-    // the 3x3 partials are in accumulator order: summed and reordered here
-    const int64_t F = (int64_t)p.gz * p.gy * p.mtw * p.ctw * 9 * 256;
-    int G = 1;
-    while (G < 16 && p.gx / (G * 2) >= 4) G *= 2;   // at least 4 partials per group
-    const int per = (p.gx + G - 1) / G, epb = 256 / G;
-    hipLaunchKernelGGL(k_sum_wgrad3x3, dim3((unsigned)((F + epb - 1) / epb)), dim3(256), 0, st, partials, p.gx,
-                       p.gy, p.gz, p.mtw, p.ctw, cin, cout, dw, G, per);
-    *splits = 0;  // nothing left for the caller to add
-    return true;
-  }
-  *splits = p.gx;
   return true;
 }
 

@@ -106,12 +106,28 @@ hipError_t launch_bn_fold(const float* gamma, const float* beta, float* mean, fl
 // dW[m][c][t] = sum_{n,q} g[n][m][q] * in[n][c][q + shift(t)]  (OIHW result).
 int conv_wgrad_splits(int n, int cin, int cout, int h, int w, int taps);
 size_t conv_wgrad_partial_floats(int n, int cin, int cout, int h, int w, int taps);
+// A sum of weight-gradient partials that a launch has left for later.  In a chain of weight
+// gradients on one stream the next weight-gradient launch carries it out with extra workgroups
+// (the partials are complete when that launch starts), which saves a launch per layer; what is
+// left at the end of the chain is summed by launch_pending_sum.
+struct PendingSum {
+  int kind = 0;  // 0 nothing pending; 1 out[e] = sum_s part[s][e]; 2 the 3x3 fast kernel's accumulator-order partials
+  const float* part = nullptr;
+  float* out = nullptr;
+  int splits = 0;
+  int64_t count = 0;                                      // elements of one partial
+  int gy = 0, gz = 0, mtw = 0, ctw = 0, cin = 0, cout = 0;  // kind 2: how a partial maps to OIHW
+};
+hipError_t launch_pending_sum(PendingSum* p, hipStream_t st);  // no-op for kind 0; clears *p
 // fold != null applies the BN+ReLU prologue to `in` (fast path only).
+// absorb: a pending sum (of another partial buffer) to carry out in this launch, or before it
+// when the fast path does not apply; cleared.  defer: if given, this call's own sum is not
+// launched when it can be deferred and is described there instead (kind 0 if it was launched).
 hipError_t launch_conv_wgrad(const float* in, int64_t in_stride, const float* g, int64_t g_stride,
                              float* dw, int n, int cin, int cout, int h, int w, int taps,
                              float* partials, const float2* fold, hipStream_t st, hipEvent_t ev_start = nullptr,
                              hipEvent_t ev_stop = nullptr /*stamped around the fast kernel (not the sum)*/,
-                             bool* used_fast = nullptr);
+                             bool* used_fast = nullptr, PendingSum* absorb = nullptr, PendingSum* defer = nullptr);
 
 // out[e] = sum over splits of partials[split][e] (fixed order).
 hipError_t launch_sum_partials(const float* partials, int splits, int64_t count, float* out, hipStream_t st);
