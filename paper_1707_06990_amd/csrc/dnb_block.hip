@@ -679,15 +679,16 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
     if (recompute)  // re-populate storage 3 from the kept b_l and its cached statistics
       DNB_TRY(launch_bn_relu(bl, (int64_t)B * hw, S3, (int64_t)B * hw, nullptr, 0, n, B, hw, p.g2,
                              p.b2, StatsSrc{mean_b, istd_b, nullptr, 0, 0, 0, d.eps}, sA));
-    // (the sum of this launch's partials is left to the next layer's launch on this chain)
+    // (the sum of this launch's partials is left to the next layer's launch on this chain).
+    // On one stream the 3x3 weight gradient waits for the 1x1's launch below and shares it.
     float* pA = partA + (size_t)(l & 1) * b->partA_floats;
-    if (fused)  // BN2+ReLU of b_l is applied while the kernel stages its tile: nothing to re-populate
-      DNB_TRY(launch_conv_wgrad(bl, (int64_t)B * hw, gl, ys, gp.W3, n, B, k, d.h, d.w, 9, pA,
-                                (const float2*)(ws + b->off_fold2[l]), sA, nullptr, nullptr, nullptr, &pendA, &nextA));
-    else
-      DNB_TRY(launch_conv_wgrad(S3, (int64_t)B * hw, gl, ys, gp.W3, n, B, k, d.h, d.w, 9, pA, nullptr, sA, nullptr,
-                                nullptr, nullptr, &pendA, &nextA));
-    pendA = nextA;
+    const float* in3 = fused ? bl : S3;
+    const float2* f3 = fused ? (const float2*)(ws + b->off_fold2[l]) : nullptr;
+    if (conc) {  // (fused: BN2+ReLU of b_l is applied while the kernel stages its tile)
+      DNB_TRY(launch_conv_wgrad(in3, (int64_t)B * hw, gl, ys, gp.W3, n, B, k, d.h, d.w, 9, pA, f3, sA, nullptr, nullptr,
+                                nullptr, &pendA, &nextA));
+      pendA = nextA;
+    }
 
     // ---- chain B, first half: storage 1 and 2.  Storage 1 was last read by layer l+1's BN1
     // backward on the main chain; storage 2 by the previous wgrad on this stream.
@@ -708,13 +709,16 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
     // ---- chain B, second half: the 1x1 weight gradient from storage 2 and db_l
     DNB_TRY(wait(sB, ev(l, EV_DB)));
     float* pB = partB + (size_t)(l & 1) * b->partB_floats;
-    if (fused)  // BN1+ReLU of the concatenated features is applied in the operand load
-      DNB_TRY(launch_conv_wgrad(y, ys, dS3, (int64_t)B * hw, gp.W1, n, c, B, d.h, d.w, 1, pB,
-                                (const float2*)(ws + b->off_fold1[l]), sB, nullptr, nullptr, nullptr, &pendB, &nextB));
-    else
-      DNB_TRY(launch_conv_wgrad(S2, (int64_t)c * hw, dS3, (int64_t)B * hw, gp.W1, n, c, B, d.h, d.w, 1,
-                                pB, nullptr, sB, nullptr, nullptr, nullptr, &pendB, &nextB));
-    pendB = nextB;
+    if (!conc) {  // both weight gradients of the layer in one launch
+      DNB_TRY(launch_conv_wgrad_pair(fused ? y : S2, fused ? ys : (int64_t)c * hw, dS3, (int64_t)B * hw, gp.W1, c, pB,
+                                     fused ? (const float2*)(ws + b->off_fold1[l]) : nullptr, in3, (int64_t)B * hw, gl,
+                                     ys, gp.W3, k, pA, f3, n, B, d.h, d.w, st, &pendB, &pendA));
+    } else {  // (fused: BN1+ReLU of the concatenated features is applied in the operand load)
+      DNB_TRY(launch_conv_wgrad(fused ? y : S2, fused ? ys : (int64_t)c * hw, dS3, (int64_t)B * hw, gp.W1, n, c, B, d.h,
+                                d.w, 1, pB, fused ? (const float2*)(ws + b->off_fold1[l]) : nullptr, sB, nullptr,
+                                nullptr, nullptr, &pendB, &nextB));
+      pendB = nextB;
+    }
     DNB_TRY(record(ev(l, EV_WG1), sB));
 
     // ---- main chain, continued

@@ -29,6 +29,11 @@ bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64
                        const float2* fold, PendingSum* own, PendingSum* absorb, hipStream_t st, hipEvent_t ev0,
                        hipEvent_t ev1);
 hipError_t launch_sum_wgrad3x3(const PendingSum& p, hipStream_t st);
+bool launch_wgrad_pair_fast(const float* in1, int64_t in1_stride, const float* g1, int64_t g1_stride, float* part1,
+                            float* dw1, int cin1, const float2* fold1, const float* in3, int64_t in3_stride,
+                            const float* g3, int64_t g3_stride, float* part3, float* dw3, int cout3,
+                            const float2* fold3, int n, int B, int h, int w, PendingSum* own1, PendingSum* own3,
+                            PendingSum* absorb1, PendingSum* absorb3, hipStream_t st);
 
 namespace {
 
@@ -453,6 +458,29 @@ hipError_t launch_conv_wgrad(const float* in, int64_t in_stride, const float* g,
     hipLaunchKernelGGL((k_conv_wgrad<1, 3>), p.grid, dim3(256), p.lds, st, in, in_stride, g, g_stride,
                        partials, cin, cout, h, w, p.cpi, p.total, p.cps, p.mtw, p.ctw, p.PA, p.PG);
   return launch_sum_partials(partials, p.splits, (int64_t)cin * cout * taps, dw, st);
+}
+
+hipError_t launch_conv_wgrad_pair(const float* in1, int64_t in1_stride, const float* g1, int64_t g1_stride,
+                                  float* dw1, int cin1, float* part1, const float2* fold1, const float* in3,
+                                  int64_t in3_stride, const float* g3, int64_t g3_stride, float* dw3, int cout3,
+                                  float* part3, const float2* fold3, int n, int B, int h, int w, hipStream_t st,
+                                  PendingSum* pend1, PendingSum* pend3) {
+  PendingSum own1, own3;
+  if (cin1 > 0 && B > 0 && cout3 > 0 &&
+      launch_wgrad_pair_fast(in1, in1_stride, g1, g1_stride, part1, dw1, cin1, fold1, in3, in3_stride, g3, g3_stride,
+                             part3, dw3, cout3, fold3, n, B, h, w, &own1, &own3, pend1, pend3, st)) {
+    *pend1 = own1;
+    *pend3 = own3;
+    return hipGetLastError();
+  }
+  hipError_t e = launch_conv_wgrad(in3, in3_stride, g3, g3_stride, dw3, n, B, cout3, h, w, 9, part3, fold3, st, nullptr,
+                                   nullptr, nullptr, pend3, &own3);
+  if (e != hipSuccess) return e;
+  *pend3 = own3;
+  e = launch_conv_wgrad(in1, in1_stride, g1, g1_stride, dw1, n, cin1, B, h, w, 1, part1, fold1, st, nullptr, nullptr,
+                        nullptr, pend1, &own1);
+  *pend1 = own1;
+  return e;
 }
 
 }  // namespace dnb

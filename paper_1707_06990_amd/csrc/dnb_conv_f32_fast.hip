@@ -774,21 +774,26 @@ __device__ __forceinline__ void reduce_waves(f32x4 (&acc)[NT], float* buf, int w
 // 4kk..4kk+3 of row r of both operands (16 bytes each) and issues 4 K-steps.  The four waves of
 // a workgroup take alternate steps (together 256 contiguous bytes per row), keep all MTW x CTW
 // tiles in registers, and are summed in LDS at the end; the workgroup writes one partial.
+struct Wg1Args {
+  const float* a; int64_t a_stride; const float* g; int64_t g_stride; float* part;
+  int cin, cout, HW, spi, total_steps, steps_per_wg;
+  const float2* fold;
+};
+
+// the work of workgroup (bx, by, bz) of the 1x1 weight gradient's grid
 template <int MTW, int CTW, bool PRO>
-__global__ __launch_bounds__(256) void k_wgrad1x1_fast(
-    const float* __restrict__ a, int64_t a_stride, const float* __restrict__ gout, int64_t g_stride,
-    float* __restrict__ part, int cin, int cout, int HW, int spi, int total_steps, int steps_per_wg,
-    const float2* __restrict__ fold, SumRole sr, int gx_main) {
+__device__ __forceinline__ void wgrad1x1_body(const Wg1Args& A, int bx, int by, int bz) {
   extern __shared__ float lds[];
-  if ((int)blockIdx.x >= gx_main) {  // extra workgroups: a pending sum of another partial buffer
-    const int wg = (((int)blockIdx.x - gx_main) * gridDim.y + blockIdx.y) * gridDim.z + blockIdx.z;
-    if (wg < sr.wgs) sum_role(sr, wg);
-    return;
-  }
+  const float* __restrict__ a = A.a;
+  const float* __restrict__ gout = A.g;
+  float* __restrict__ part = A.part;
+  const float2* __restrict__ fold = A.fold;
+  const int64_t a_stride = A.a_stride, g_stride = A.g_stride;
+  const int cin = A.cin, cout = A.cout, HW = A.HW, spi = A.spi, total_steps = A.total_steps, steps_per_wg = A.steps_per_wg;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, kk = lane >> 4;
-  const int c0 = blockIdx.y * (CTW * 16), m0 = blockIdx.z * (MTW * 16);
-  const int s_begin = blockIdx.x * steps_per_wg, s_end = min(total_steps, s_begin + steps_per_wg);
+  const int c0 = by * (CTW * 16), m0 = bz * (MTW * 16);
+  const int s_begin = bx * steps_per_wg, s_end = min(total_steps, s_begin + steps_per_wg);
 
   f32x4 acc[MTW * CTW];
 #pragma unroll
@@ -857,7 +862,7 @@ __global__ __launch_bounds__(256) void k_wgrad1x1_fast(
 
   reduce_waves<MTW * CTW>(acc, lds, wave, lane, 4);
   if (wave == 0) {
-    float* pb = part + (int64_t)blockIdx.x * cout * cin;
+    float* pb = part + (int64_t)bx * cout * cin;
 #pragma unroll
     for (int x = 0; x < MTW; ++x)
 #pragma unroll
@@ -872,30 +877,45 @@ __global__ __launch_bounds__(256) void k_wgrad1x1_fast(
   }
 }
 
+template <int MTW, int CTW, bool PRO>
+__global__ __launch_bounds__(256) void k_wgrad1x1_fast(Wg1Args A, SumRole sr, int gx_main) {
+  if ((int)blockIdx.x >= gx_main) {  // extra workgroups: a pending sum of another partial buffer
+    const int wg = (((int)blockIdx.x - gx_main) * gridDim.y + blockIdx.y) * gridDim.z + blockIdx.z;
+    if (wg < sr.wgs) sum_role(sr, wg);
+    return;
+  }
+  wgrad1x1_body<MTW, CTW, PRO>(A, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
 // ------------------------------------------------------------------------------- 3x3 wgrad
 //
 // dW[m][c][t] = sum_{n,q} g[n][m][q] a[n][c][q+shift(t)].  The workgroup stages CTW*16 channels
 // of a pixel range (plus halo, as in the forward kernel) in LDS; the MTW x CTW x 9 accumulator
 // tiles are split over the four waves and every wave takes all 16-pixel steps of the range.
 // g comes straight from HBM (16 bytes per lane and step).
+struct Wg3Args {
+  const float* a; int64_t a_stride; const float* g; int64_t g_stride; float* part;
+  int cin, cout, H, W, tiles_per_img, nms, PA;
+  const float2* fold;
+};
+
+// the work of workgroup (bx, by, bz) of the 3x3 weight gradient's grid (gy x gz channel groups)
 template <int MTW, int CTW, bool PRO>
-__global__ __launch_bounds__(256) void k_wgrad3x3_fast(
-    const float* __restrict__ a, int64_t a_stride, const float* __restrict__ gout, int64_t g_stride,
-    float* __restrict__ part, int cin, int cout, int H, int W, int tiles_per_img, int nms, int PA,
-    const float2* __restrict__ fold, SumRole sr, int gx_main) {
+__device__ __forceinline__ void wgrad3x3_body(const Wg3Args& A3, int bx, int by, int bz, int gy, int gz) {
   extern __shared__ float lds[];
-  if ((int)blockIdx.x >= gx_main) {  // extra workgroups: a pending sum of another partial buffer
-    const int wg = (((int)blockIdx.x - gx_main) * gridDim.y + blockIdx.y) * gridDim.z + blockIdx.z;
-    if (wg < sr.wgs) sum_role(sr, wg);
-    return;
-  }
+  const float* __restrict__ a = A3.a;
+  const float* __restrict__ gout = A3.g;
+  float* __restrict__ part = A3.part;
+  const float2* __restrict__ fold = A3.fold;
+  const int64_t a_stride = A3.a_stride, g_stride = A3.g_stride;
+  const int cin = A3.cin, cout = A3.cout, H = A3.H, W = A3.W, tiles_per_img = A3.tiles_per_img, nms = A3.nms, PA = A3.PA;
   const int HW = H * W;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 15, kk = lane >> 4;
   constexpr int CB = CTW * 16, NT = MTW * CTW * 9;
   const int TPIX = 4 * nms * 16;
-  const int img = blockIdx.x / tiles_per_img, q0 = (blockIdx.x - img * tiles_per_img) * TPIX;
-  const int c0 = blockIdx.y * CB, m0 = blockIdx.z * (MTW * 16);
+  const int img = bx / tiles_per_img, q0 = (bx - img * tiles_per_img) * TPIX;
+  const int c0 = by * CB, m0 = bz * (MTW * 16);
   const int origin = q0 - W - 4;
   const int seg4 = (TPIX + 2 * W + 8) >> 2;
   const float* ab = a + (int64_t)img * a_stride;
@@ -1059,13 +1079,47 @@ __global__ __launch_bounds__(256) void k_wgrad3x3_fast(
 
   // the partial is stored in accumulator order (tile, lane, 4 rows): 16-byte stores, contiguous
   // across the wave; k_sum_wgrad3x3 adds the partials and puts the sums in OIHW order
-  float* pb = part + (((int64_t)blockIdx.x * gridDim.z + blockIdx.z) * gridDim.y + blockIdx.y) * (NT * 256);
+  float* pb = part + (((int64_t)bx * gz + bz) * gy + by) * (NT * 256);
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
     const int T = wave * TPW + t;
     if (T < NT)
       *reinterpret_cast<float4*>(&pb[(T * 64 + lane) * 4]) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
   }
+}
+
+template <int MTW, int CTW, bool PRO>
+__global__ __launch_bounds__(256) void k_wgrad3x3_fast(Wg3Args A, SumRole sr, int gx_main) {
+  if ((int)blockIdx.x >= gx_main) {  // extra workgroups: a pending sum of another partial buffer
+    const int wg = (((int)blockIdx.x - gx_main) * gridDim.y + blockIdx.y) * gridDim.z + blockIdx.z;
+    if (wg < sr.wgs) sum_role(sr, wg);
+    return;
+  }
+  wgrad3x3_body<MTW, CTW, PRO>(A, blockIdx.x, blockIdx.y, blockIdx.z, gridDim.y, gridDim.z);
+}
+
+// One launch for the two weight gradients of a layer (they are independent of each other and of
+// everything that follows them): a 1-D grid whose first n3 workgroups are the 3x3's, the next n1
+// the 1x1's, the rest the two pending sums.
+template <int M1, int C1, int M3, int C3, bool PRO>
+__global__ __launch_bounds__(256) void k_wgrad_pair(Wg1Args A1, int gy1, int gz1, int n1, Wg3Args A3, int gy3, int gz3,
+                                                    int n3, SumRole s1, SumRole s3) {
+  int id = blockIdx.x;
+  if (id < n3) {
+    const int bz = id % gz3, by = (id / gz3) % gy3, bx = id / (gz3 * gy3);
+    wgrad3x3_body<M3, C3, PRO>(A3, bx, by, bz, gy3, gz3);
+    return;
+  }
+  id -= n3;
+  if (id < n1) {
+    const int bz = id % gz1, by = (id / gz1) % gy1, bx = id / (gz1 * gy1);
+    wgrad1x1_body<M1, C1, PRO>(A1, bx, by, bz);
+    return;
+  }
+  id -= n1;
+  if (id < s1.wgs) { sum_role(s1, id); return; }
+  id -= s1.wgs;
+  if (id < s3.wgs) sum_role(s3, id);
 }
 
 // Sum of the 3x3 weight-gradient partials.  A partial is gz*gy blocks of mtw*ctw*9 accumulator
@@ -1409,14 +1463,11 @@ bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64
   dim3 grid((unsigned)p.gx + sx, (unsigned)p.gy, (unsigned)p.gz);
   const int hw = h * w;
   if (taps == 1) {
-#define DNB_L(M, C)                                                                                  \
-  do {                                                                                               \
-    if (fold)                                                                                        \
-      hipExtLaunchKernelGGL((k_wgrad1x1_fast<M, C, true>), grid, dim3(256), p.lds, st, ev0, ev1, 0, in, in_stride, g, \
-                         g_stride, partials, cin, cout, hw, p.spi, p.total_steps, p.steps_per_wg, fold, sr, p.gx); \
-    else                                                                                             \
-      hipExtLaunchKernelGGL((k_wgrad1x1_fast<M, C, false>), grid, dim3(256), p.lds, st, ev0, ev1, 0, in, in_stride, g, \
-                         g_stride, partials, cin, cout, hw, p.spi, p.total_steps, p.steps_per_wg, fold, sr, p.gx); \
+    const Wg1Args A{in, in_stride, g, g_stride, partials, cin, cout, hw, p.spi, p.total_steps, p.steps_per_wg, fold};
+#define DNB_L(M, C)                                                                                                  \
+  do {                                                                                                               \
+    if (fold) hipExtLaunchKernelGGL((k_wgrad1x1_fast<M, C, true>), grid, dim3(256), p.lds, st, ev0, ev1, 0, A, sr, p.gx); \
+    else hipExtLaunchKernelGGL((k_wgrad1x1_fast<M, C, false>), grid, dim3(256), p.lds, st, ev0, ev1, 0, A, sr, p.gx);  \
   } while (0)
     const int key = p.mtw * 10 + p.ctw;
     switch (key) {
@@ -1428,14 +1479,11 @@ bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64
     own->kind = 1;
     own->part = partials; own->out = dw; own->splits = p.gx; own->count = (int64_t)cin * cout;
   } else {
-#define DNB_L(M, C)                                                                                  \
-  do {                                                                                               \
-    if (fold)                                                                                        \
-      hipExtLaunchKernelGGL((k_wgrad3x3_fast<M, C, true>), grid, dim3(256), p.lds, st, ev0, ev1, 0, in, in_stride, g, \
-                         g_stride, partials, cin, cout, h, w, p.tiles_per_img, p.nms, p.PA, fold, sr, p.gx); \
-    else                                                                                             \
-      hipExtLaunchKernelGGL((k_wgrad3x3_fast<M, C, false>), grid, dim3(256), p.lds, st, ev0, ev1, 0, in, in_stride, g, \
-                         g_stride, partials, cin, cout, h, w, p.tiles_per_img, p.nms, p.PA, fold, sr, p.gx); \
+    const Wg3Args A{in, in_stride, g, g_stride, partials, cin, cout, h, w, p.tiles_per_img, p.nms, p.PA, fold};
+#define DNB_L(M, C)                                                                                                  \
+  do {                                                                                                               \
+    if (fold) hipExtLaunchKernelGGL((k_wgrad3x3_fast<M, C, true>), grid, dim3(256), p.lds, st, ev0, ev1, 0, A, sr, p.gx); \
+    else hipExtLaunchKernelGGL((k_wgrad3x3_fast<M, C, false>), grid, dim3(256), p.lds, st, ev0, ev1, 0, A, sr, p.gx);  \
   } while (0)
     const int key = p.mtw * 10 + p.ctw;
     switch (key) {
@@ -1449,6 +1497,70 @@ bool launch_wgrad_fast(const float* in, int64_t in_stride, const float* g, int64
     own->count = (int64_t)p.gz * p.gy * p.mtw * p.ctw * 9 * 256;
     own->gy = p.gy; own->gz = p.gz; own->mtw = p.mtw; own->ctw = p.ctw; own->cin = cin; own->cout = cout;
   }
+  return true;
+}
+
+static SumRole make_sum_role(PendingSum* absorb) {
+  SumRole sr{};
+  if (absorb && absorb->kind != 0) {
+    sr.kind = absorb->kind;
+    sr.part = absorb->part; sr.out = absorb->out; sr.splits = absorb->splits; sr.count = absorb->count;
+    sr.gy = absorb->gy; sr.gz = absorb->gz; sr.mtw = absorb->mtw; sr.ctw = absorb->ctw;
+    sr.cin = absorb->cin; sr.cout = absorb->cout;
+    sum_grouping(sr.kind, sr.splits, &sr.G, &sr.per);
+    const int epb = 256 / sr.G;
+    sr.wgs = (int)((sr.count + epb - 1) / epb);
+    absorb->kind = 0;
+  }
+  return sr;
+}
+
+// Both weight gradients of a bottleneck layer in one launch: the 3x3 (in3: the bottleneck
+// activations, cin3 = B channels; g3: the gradient of x_l, cout3 = k) and the 1x1 (in1: the
+// concatenated features, cin1 = C_l; g1: the gradient of b_l, cout1 = B = cin3), same image
+// size, both with or both without the BN+ReLU prologue.  Returns false (nothing launched,
+// nothing absorbed) when the pair is not one of the instantiated combinations.
+bool launch_wgrad_pair_fast(const float* in1, int64_t in1_stride, const float* g1, int64_t g1_stride, float* part1,
+                            float* dw1, int cin1, const float2* fold1, const float* in3, int64_t in3_stride,
+                            const float* g3, int64_t g3_stride, float* part3, float* dw3, int cout3,
+                            const float2* fold3, int n, int B, int h, int w, PendingSum* own1, PendingSum* own3,
+                            PendingSum* absorb1, PendingSum* absorb3, hipStream_t st) {
+  if ((fold1 != nullptr) != (fold3 != nullptr)) return false;
+  if (in1_stride % 4 || g1_stride % 4 || in3_stride % 4 || g3_stride % 4 || !aligned16(in1) || !aligned16(g1) ||
+      !aligned16(in3) || !aligned16(g3))
+    return false;
+  const WgFastPlan p1 = plan_wgrad_fast(n, cin1, B, h, w, 1), p3 = plan_wgrad_fast(n, B, cout3, h, w, 9);
+  if (!p1.ok || !p3.ok || p1.mtw != 3) return false;
+  const int key3 = p3.mtw * 10 + p3.ctw;
+  if (key3 != 13 && key3 != 22) return false;
+  const SumRole s1 = make_sum_role(absorb1), s3 = make_sum_role(absorb3);
+  const int hw = h * w;
+  const Wg1Args A1{in1, in1_stride, g1, g1_stride, part1, cin1, B, hw, p1.spi, p1.total_steps, p1.steps_per_wg, fold1};
+  const Wg3Args A3{in3, in3_stride, g3, g3_stride, part3, B, cout3, h, w, p3.tiles_per_img, p3.nms, p3.PA, fold3};
+  const int n1 = p1.gx * p1.gy * p1.gz, n3 = p3.gx * p3.gy * p3.gz;
+  const dim3 grid((unsigned)(n1 + n3 + s1.wgs + s3.wgs));
+  const size_t lds = p1.lds > p3.lds ? p1.lds : p3.lds;
+#define DNB_P(C1, M3, C3)                                                                                             \
+  do {                                                                                                                \
+    if (fold1) hipLaunchKernelGGL((k_wgrad_pair<3, C1, M3, C3, true>), grid, dim3(256), lds, st, A1, p1.gy, p1.gz, n1, \
+                                  A3, p3.gy, p3.gz, n3, s1, s3);                                                      \
+    else hipLaunchKernelGGL((k_wgrad_pair<3, C1, M3, C3, false>), grid, dim3(256), lds, st, A1, p1.gy, p1.gz, n1, A3,  \
+                            p3.gy, p3.gz, n3, s1, s3);                                                                \
+  } while (0)
+#define DNB_P1(M3, C3)                                                                          \
+  switch (p1.ctw) {                                                                             \
+    case 4: DNB_P(4, M3, C3); break; case 3: DNB_P(3, M3, C3); break; case 2: DNB_P(2, M3, C3); break; \
+    default: DNB_P(1, M3, C3); break;                                                           \
+  }
+  if (key3 == 13) { DNB_P1(1, 3) } else { DNB_P1(2, 2) }
+#undef DNB_P1
+#undef DNB_P
+  own1->kind = 1;
+  own1->part = part1; own1->out = dw1; own1->splits = p1.gx; own1->count = (int64_t)cin1 * B;
+  own3->kind = 2;
+  own3->part = part3; own3->out = dw3; own3->splits = p3.gx;
+  own3->count = (int64_t)p3.gz * p3.gy * p3.mtw * p3.ctw * 9 * 256;
+  own3->gy = p3.gy; own3->gz = p3.gz; own3->mtw = p3.mtw; own3->ctw = p3.ctw; own3->cin = B; own3->cout = cout3;
   return true;
 }
 

@@ -129,6 +129,16 @@ hipError_t launch_conv_wgrad(const float* in, int64_t in_stride, const float* g,
                              hipEvent_t ev_stop = nullptr /*stamped around the fast kernel (not the sum)*/,
                              bool* used_fast = nullptr, PendingSum* absorb = nullptr, PendingSum* defer = nullptr);
 
+// Both weight gradients of a bottleneck layer on one stream: the 1x1 (in1: C_l channels, g1: the
+// gradient of b_l, B channels) and the 3x3 (in3: B channels, g3: the gradient of x_l, k
+// channels).  One launch when the fast pair applies, else two launch_conv_wgrad calls.  *pend1 /
+// *pend3: in, the previous layer's pending sums (carried out here); out, this layer's.
+hipError_t launch_conv_wgrad_pair(const float* in1, int64_t in1_stride, const float* g1, int64_t g1_stride,
+                                  float* dw1, int cin1, float* part1, const float2* fold1, const float* in3,
+                                  int64_t in3_stride, const float* g3, int64_t g3_stride, float* dw3, int cout3,
+                                  float* part3, const float2* fold3, int n, int B, int h, int w, hipStream_t st,
+                                  PendingSum* pend1, PendingSum* pend3);
+
 // out[e] = sum over splits of partials[split][e] (fixed order).
 hipError_t launch_sum_partials(const float* partials, int splits, int64_t count, float* out, hipStream_t st);
 
