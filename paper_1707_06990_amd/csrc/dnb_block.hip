@@ -6,6 +6,7 @@
 
 #include "../../include/dnb.h"
 #include "dnb_internal.h"
+#include "dnb_stats.cuh"
 
 using namespace dnb;
 
@@ -709,13 +710,11 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
     // ---- chain B, second half: the 1x1 weight gradient from storage 2 and db_l
     DNB_TRY(wait(sB, ev(l, EV_DB)));
     float* pB = partB + (size_t)(l & 1) * b->partB_floats;
-    if (!conc) {  // both weight gradients of the layer in one launch
-      DNB_TRY(launch_conv_wgrad_pair(fused ? y : S2, fused ? ys : (int64_t)c * hw, dS3, (int64_t)B * hw, gp.W1, c, pB,
-                                     fused ? (const float2*)(ws + b->off_fold1[l]) : nullptr, in3, (int64_t)B * hw, gl,
-                                     ys, gp.W3, k, pA, f3, n, B, d.h, d.w, st, &pendB, &pendA));
-    } else {  // (fused: BN1+ReLU of the concatenated features is applied in the operand load)
-      DNB_TRY(launch_conv_wgrad(fused ? y : S2, fused ? ys : (int64_t)c * hw, dS3, (int64_t)B * hw, gp.W1, n, c, B, d.h,
-                                d.w, 1, pB, fused ? (const float2*)(ws + b->off_fold1[l]) : nullptr, sB, nullptr,
+    const float* in1 = fused ? y : S2;
+    const int64_t in1s = fused ? ys : (int64_t)c * hw;
+    const float2* f1 = fused ? (const float2*)(ws + b->off_fold1[l]) : nullptr;
+    if (conc) {  // (fused: BN1+ReLU of the concatenated features is applied in the operand load)
+      DNB_TRY(launch_conv_wgrad(in1, in1s, dS3, (int64_t)B * hw, gp.W1, n, c, B, d.h, d.w, 1, pB, f1, sB, nullptr,
                                 nullptr, nullptr, &pendB, &nextB));
       pendB = nextB;
     }
@@ -727,8 +726,23 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
     DNB_TRY(wait(st, ev(l, EV_S12)));
     // BN1+ReLU backward, then concat backward: add the slice gradients into the slab
     // (the fused schedule reads the concatenated features in place from y)
-    DNB_TRY(launch_bn_relu_bwd(fused ? y : S1, fused ? ys : (int64_t)c * hw, dS2, (int64_t)c * hw, G, ys,
-                               true, n, c, hw, p.g1, p.b1, mean_y, istd_y, gp.g1, gp.b1, part, st));
+    const float* x1 = fused ? y : S1;
+    const int64_t x1s = fused ? ys : (int64_t)c * hw;
+    int passes = 3;
+    if (!conc) {
+      // one stream: the layer's two weight gradients (leaves of the dependence graph: db_l in dS3
+      // and g_l stay untouched until the next layer), the previous layer's partial sums and the
+      // reduction pass of this BN backward share one launch
+      BnBwdPartialArgs bn;
+      const bool has_bn = bn_bwd_partial_plan(x1, x1s, dS2, (int64_t)c * hw, n, c, hw, p.g1, p.b1, mean_y, istd_y, part, &bn);
+      bool bn_done = false;
+      DNB_TRY(launch_conv_wgrad_pair(in1, in1s, dS3, (int64_t)B * hw, gp.W1, c, pB, f1, in3, (int64_t)B * hw, gl, ys,
+                                     gp.W3, k, pA, f3, n, B, d.h, d.w, st, &pendB, &pendA, has_bn ? &bn : nullptr,
+                                     &bn_done));
+      if (bn_done) passes = 2;
+    }
+    DNB_TRY(launch_bn_relu_bwd(x1, x1s, dS2, (int64_t)c * hw, G, ys, true, n, c, hw, p.g1, p.b1, mean_y, istd_y, gp.g1,
+                               gp.b1, part, st, passes));
     DNB_TRY(record(ev(l, EV_MAIN), st));
   }
   // the first layer's weight-gradient partials have no later launch to ride on

@@ -1103,7 +1103,7 @@ __global__ __launch_bounds__(256) void k_wgrad3x3_fast(Wg3Args A, SumRole sr, in
 // the 1x1's, the rest the two pending sums.
 template <int M1, int C1, int M3, int C3, bool PRO>
 __global__ __launch_bounds__(256) void k_wgrad_pair(Wg1Args A1, int gy1, int gz1, int n1, Wg3Args A3, int gy3, int gz3,
-                                                    int n3, SumRole s1, SumRole s3) {
+                                                    int n3, SumRole s1, SumRole s3, BnBwdPartialArgs bn, int nbn) {
   int id = blockIdx.x;
   if (id < n3) {
     const int bz = id % gz3, by = (id / gz3) % gy3, bx = id / (gz3 * gy3);
@@ -1117,6 +1117,11 @@ __global__ __launch_bounds__(256) void k_wgrad_pair(Wg1Args A1, int gy1, int gz1
     return;
   }
   id -= n1;
+  if (id < nbn) {  // a BN+ReLU backward reduction of the main chain carried along
+    bn_bwd_partial_body4(bn, id / bn.splits, id % bn.splits);
+    return;
+  }
+  id -= nbn;
   if (id < s1.wgs) { sum_role(s1, id); return; }
   id -= s1.wgs;
   if (id < s3.wgs) sum_role(s3, id);
@@ -1524,7 +1529,7 @@ bool launch_wgrad_pair_fast(const float* in1, int64_t in1_stride, const float* g
                             float* dw1, int cin1, const float2* fold1, const float* in3, int64_t in3_stride,
                             const float* g3, int64_t g3_stride, float* part3, float* dw3, int cout3,
                             const float2* fold3, int n, int B, int h, int w, PendingSum* own1, PendingSum* own3,
-                            PendingSum* absorb1, PendingSum* absorb3, hipStream_t st) {
+                            PendingSum* absorb1, PendingSum* absorb3, const BnBwdPartialArgs* bn, hipStream_t st) {
   if ((fold1 != nullptr) != (fold3 != nullptr)) return false;
   if (in1_stride % 4 || g1_stride % 4 || in3_stride % 4 || g3_stride % 4 || !aligned16(in1) || !aligned16(g1) ||
       !aligned16(in3) || !aligned16(g3))
@@ -1538,14 +1543,16 @@ bool launch_wgrad_pair_fast(const float* in1, int64_t in1_stride, const float* g
   const Wg1Args A1{in1, in1_stride, g1, g1_stride, part1, cin1, B, hw, p1.spi, p1.total_steps, p1.steps_per_wg, fold1};
   const Wg3Args A3{in3, in3_stride, g3, g3_stride, part3, B, cout3, h, w, p3.tiles_per_img, p3.nms, p3.PA, fold3};
   const int n1 = p1.gx * p1.gy * p1.gz, n3 = p3.gx * p3.gy * p3.gz;
-  const dim3 grid((unsigned)(n1 + n3 + s1.wgs + s3.wgs));
+  const BnBwdPartialArgs bna = bn ? *bn : BnBwdPartialArgs{};
+  const int nbn = bn ? bn->c * bn->splits : 0;
+  const dim3 grid((unsigned)(n1 + n3 + nbn + s1.wgs + s3.wgs));
   const size_t lds = p1.lds > p3.lds ? p1.lds : p3.lds;
 #define DNB_P(C1, M3, C3)                                                                                             \
   do {                                                                                                                \
     if (fold1) hipLaunchKernelGGL((k_wgrad_pair<3, C1, M3, C3, true>), grid, dim3(256), lds, st, A1, p1.gy, p1.gz, n1, \
-                                  A3, p3.gy, p3.gz, n3, s1, s3);                                                      \
+                                  A3, p3.gy, p3.gz, n3, s1, s3, bna, nbn);                                            \
     else hipLaunchKernelGGL((k_wgrad_pair<3, C1, M3, C3, false>), grid, dim3(256), lds, st, A1, p1.gy, p1.gz, n1, A3,  \
-                            p3.gy, p3.gz, n3, s1, s3);                                                                \
+                            p3.gy, p3.gz, n3, s1, s3, bna, nbn);                                                      \
   } while (0)
 #define DNB_P1(M3, C3)                                                                          \
   switch (p1.ctw) {                                                                             \

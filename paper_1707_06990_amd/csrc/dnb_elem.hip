@@ -15,25 +15,8 @@ namespace {
 
 constexpr int kThreads = 256;
 
-__device__ __forceinline__ float wave_sum(float v) {
-  // butterfly over the 64 lanes of a wavefront: every lane ends with the same total
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
-
-// Sum over the workgroup; the result is returned to every thread.  `red` holds one
-// float per wave.  Safe to call repeatedly (barrier before reuse).
-__device__ __forceinline__ float block_sum(float v, float* red) {
-  v = wave_sum(v);
-  const int wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) red[wave] = v;
-  __syncthreads();
-  float t = 0.f;
-  for (int i = 0; i < nw; ++i) t += red[i];
-  return t;
-}
+__device__ __forceinline__ float wave_sum(float v) { return bnb_wave_sum(v); }
+__device__ __forceinline__ float block_sum(float v, float* red) { return bnb_block_sum(v, red); }
 
 template <int V>
 struct Vec;
@@ -83,19 +66,7 @@ __global__ __launch_bounds__(kThreads) void k_copy_slab(const float* __restrict_
 // ----------------------------------------------------------------------------- row iteration
 
 // A workgroup of the BN kernels below owns ONE channel and a range of images: its elements are
-// rows of hw contiguous floats, one per image.  RowIter walks (image, vector-in-row) pairs with
-// a stride of blockDim threads without a division per element.
-struct RowIter {
-  int img, q, dimg, dq, hwv;
-  __device__ __forceinline__ RowIter(int hwv_, int tid, int nthr) : hwv(hwv_) {
-    img = tid / hwv_; q = tid - img * hwv_;
-    dimg = nthr / hwv_; dq = nthr - dimg * hwv_;
-  }
-  __device__ __forceinline__ void next() {
-    img += dimg; q += dq;
-    if (q >= hwv) { q -= hwv; ++img; }
-  }
-};
+// (RowIter, which walks rows of hw contiguous floats, one per image, is in dnb_stats.cuh)
 
 // ----------------------------------------------------------------------------- BN statistics
 
@@ -206,10 +177,15 @@ __global__ __launch_bounds__(kThreads) void k_bn_bwd_partial(
     int64_t dact_stride, int n, int hw, int ipb, const float* __restrict__ gamma,
     const float* __restrict__ beta, const float* __restrict__ mean, const float* __restrict__ istd,
     float* __restrict__ part) {
+  if (V == 4) {  // the vector form lives in dnb_stats.cuh: the weight-gradient launch can carry it too
+    const BnBwdPartialArgs A{x, x_stride, dact, dact_stride, n, hw, ipb, gamma, beta, mean, istd, part,
+                             (int)gridDim.x, (int)gridDim.y};
+    bn_bwd_partial_body4(A, blockIdx.x, blockIdx.y);
+    return;
+  }
   __shared__ float red[kThreads / 64];
   const int ch = blockIdx.x, s = blockIdx.y, splits = gridDim.y;
   const int n0 = s * ipb, ni = min(n, n0 + ipb) - n0;
-  const int hwv = hw / V;
   float scale, shift;
   const float mu = mean[ch], is = istd[ch];
   bn_fold(gamma[ch], beta[ch], mu, is, scale, shift);
@@ -217,30 +193,11 @@ __global__ __launch_bounds__(kThreads) void k_bn_bwd_partial(
   const float* xp = x + (int64_t)n0 * x_stride + inner;
   const float* gp = dact + (int64_t)n0 * dact_stride + inner;
   float sb = 0.f, sg = 0.f;
-  // four positions per pass: all eight loads are issued (unconditionally; a position past the
-  // range repeats the last image's) before the first is consumed
-  for (RowIter it(hwv, threadIdx.x, blockDim.x); it.img < ni;) {
-    float t[4][V], g[4][V];
-    bool ok[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      ok[u] = it.img < ni;
-      const int im = ok[u] ? it.img : ni - 1;
-      Vec<V>::ld(xp + (int64_t)im * x_stride + (int64_t)it.q * V, t[u]);
-      Vec<V>::ld(gp + (int64_t)im * dact_stride + (int64_t)it.q * V, g[u]);
-      it.next();
-    }
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (ok[u]) {
-#pragma unroll
-        for (int e = 0; e < V; ++e) {
-          const float dz = __fmaf_rn(t[u][e], scale, shift) > 0.f ? g[u][e] : 0.f;
-          sb += dz;
-          sg = __fmaf_rn(dz, (t[u][e] - mu) * is, sg);
-        }
-      }
-    }
+  for (RowIter it(hw, threadIdx.x, blockDim.x); it.img < ni; it.next()) {
+    const float t = xp[(int64_t)it.img * x_stride + it.q], g = gp[(int64_t)it.img * dact_stride + it.q];
+    const float dz = __fmaf_rn(t, scale, shift) > 0.f ? g : 0.f;
+    sb += dz;
+    sg = __fmaf_rn(dz, (t - mu) * is, sg);
   }
   sb = block_sum(sb, red);
   sg = block_sum(sg, red);
@@ -403,6 +360,16 @@ hipError_t launch_bn_relu(const float* x, int64_t x_stride, float* out, int64_t 
 }
 
 size_t bn_bwd_partial_floats(int n, int c, int hw) { return (size_t)c * splits_for(n, c, hw) * 2; }
+
+bool bn_bwd_partial_plan(const float* x, int64_t x_stride, const float* dact, int64_t dact_stride, int n, int c,
+                         int hw, const float* gamma, const float* beta, const float* mean, const float* istd,
+                         float* partials, BnBwdPartialArgs* out) {
+  if (n <= 0 || c <= 0 || hw <= 0) return false;
+  if (hw % 4 || x_stride % 4 || dact_stride % 4 || !aligned16(x) || !aligned16(dact)) return false;
+  const Split p = split_plan(n, c, hw);
+  *out = BnBwdPartialArgs{x, x_stride, dact, dact_stride, n, hw, p.ipb, gamma, beta, mean, istd, partials, c, p.gs};
+  return true;
+}
 
 hipError_t launch_bn_relu_bwd(const float* x, int64_t x_stride, const float* dact,
                               int64_t dact_stride, float* du, int64_t du_stride, bool accumulate,

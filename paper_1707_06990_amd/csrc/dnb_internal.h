@@ -45,6 +45,12 @@ hipError_t launch_bn_relu(const float* x, int64_t x_stride, float* out, int64_t 
 // du = gamma*istd*(dz - dbeta/P - xhat*dgamma/P), overwriting or accumulating.
 // `partials` needs bn_bwd_partial_floats(n, c, hw) floats.
 size_t bn_bwd_partial_floats(int n, int c, int hw);
+// Describes the reduction pass (passes & 1) of launch_bn_relu_bwd for another launch to carry
+// (launch_conv_wgrad_pair); false when the 16-byte form does not apply to these operands.
+struct BnBwdPartialArgs;
+bool bn_bwd_partial_plan(const float* x, int64_t x_stride, const float* dact, int64_t dact_stride, int n, int c,
+                         int hw, const float* gamma, const float* beta, const float* mean, const float* istd,
+                         float* partials, BnBwdPartialArgs* out);
 hipError_t launch_bn_relu_bwd(const float* x, int64_t x_stride, const float* dact,
                               int64_t dact_stride, float* du, int64_t du_stride, bool accumulate,
                               int n, int c, int hw, const float* gamma, const float* beta,
@@ -137,7 +143,9 @@ hipError_t launch_conv_wgrad_pair(const float* in1, int64_t in1_stride, const fl
                                   float* dw1, int cin1, float* part1, const float2* fold1, const float* in3,
                                   int64_t in3_stride, const float* g3, int64_t g3_stride, float* dw3, int cout3,
                                   float* part3, const float2* fold3, int n, int B, int h, int w, hipStream_t st,
-                                  PendingSum* pend1, PendingSum* pend3);
+                                  PendingSum* pend1, PendingSum* pend3, const BnBwdPartialArgs* bn = nullptr,
+                                  bool* bn_done = nullptr);
+// (bn: a BN backward reduction to carry in the same launch; *bn_done says whether it was)
 
 // out[e] = sum over splits of partials[split][e] (fixed order).
 hipError_t launch_sum_partials(const float* partials, int splits, int64_t count, float* out, hipStream_t st);

@@ -66,4 +66,97 @@ __device__ __forceinline__ Stat3 stat_merge_block(const float* __restrict__ p, i
   return r;
 }
 
+
+// ---- pieces of the fp32 BN+ReLU backward reduction shared by its own kernel and by the launch
+// that carries it beside the weight gradients (same code, same bits)
+
+__device__ __forceinline__ float bnb_wave_sum(float v) {
+  // butterfly over the 64 lanes of a wavefront: every lane ends with the same total
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+  return v;
+}
+
+// Sum over the workgroup; the result is returned to every thread.  `red` holds one
+// float per wave.  Safe to call repeatedly (barrier before reuse).
+__device__ __forceinline__ float bnb_block_sum(float v, float* red) {
+  v = bnb_wave_sum(v);
+  const int wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[wave] = v;
+  __syncthreads();
+  float t = 0.f;
+  for (int i = 0; i < nw; ++i) t += red[i];
+  return t;
+}
+
+// rows of hw contiguous floats, one per image: walks (image, vector-in-row) pairs with a stride
+// of blockDim threads without a division per element
+struct RowIter {
+  int img, q, dimg, dq, hwv;
+  __device__ __forceinline__ RowIter(int hwv_, int tid, int nthr) : hwv(hwv_) {
+    img = tid / hwv_; q = tid - img * hwv_;
+    dimg = nthr / hwv_; dq = nthr - dimg * hwv_;
+  }
+  __device__ __forceinline__ void next() {
+    img += dimg; q += dq;
+    if (q >= hwv) { q -= hwv; ++img; }
+  }
+};
+
+struct BnBwdPartialArgs {
+  const float* x; int64_t x_stride; const float* dact; int64_t dact_stride;
+  int n, hw, ipb;
+  const float *gamma, *beta, *mean, *istd;
+  float* part;
+  int c, splits;  // grid of the reduction: channels x image splits
+};
+
+// Workgroup (ch, s): partial sums of dz and dz*xhat over images [s*ipb, (s+1)*ipb) of channel ch,
+// 16-byte accesses (hw and the strides multiples of 4, 16-byte aligned), 256 threads.
+__device__ __forceinline__ void bn_bwd_partial_body4(const BnBwdPartialArgs& A, int ch, int s) {
+  __shared__ float red[4];
+  const int n0 = s * A.ipb, ni = min(A.n, n0 + A.ipb) - n0;
+  const int hwv = A.hw / 4;
+  float scale, shift;
+  const float mu = A.mean[ch], is = A.istd[ch];
+  bn_fold(A.gamma[ch], A.beta[ch], mu, is, scale, shift);
+  const int64_t inner = (int64_t)ch * A.hw;
+  const float* xp = A.x + (int64_t)n0 * A.x_stride + inner;
+  const float* gp = A.dact + (int64_t)n0 * A.dact_stride + inner;
+  float sb = 0.f, sg = 0.f;
+  // four positions per pass: all eight loads are issued (unconditionally; a position past the
+  // range repeats the last image's) before the first is consumed
+  for (RowIter it(hwv, threadIdx.x, blockDim.x); it.img < ni;) {
+    float4 t[4], g[4];
+    bool ok[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      ok[u] = it.img < ni;
+      const int im = ok[u] ? it.img : ni - 1;
+      t[u] = *reinterpret_cast<const float4*>(xp + (int64_t)im * A.x_stride + (int64_t)it.q * 4);
+      g[u] = *reinterpret_cast<const float4*>(gp + (int64_t)im * A.dact_stride + (int64_t)it.q * 4);
+      it.next();
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (ok[u]) {
+        const float tv[4] = {t[u].x, t[u].y, t[u].z, t[u].w}, gv[4] = {g[u].x, g[u].y, g[u].z, g[u].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const float dz = __fmaf_rn(tv[e], scale, shift) > 0.f ? gv[e] : 0.f;
+          sb += dz;
+          sg = __fmaf_rn(dz, (tv[e] - mu) * is, sg);
+        }
+      }
+    }
+  }
+  sb = bnb_block_sum(sb, red);
+  sg = bnb_block_sum(sg, red);
+  if (threadIdx.x == 0) {
+    float* p = A.part + ((int64_t)ch * A.splits + s) * 2;
+    p[0] = sb; p[1] = sg;
+  }
+}
+
 }  // namespace dnb
