@@ -185,58 +185,69 @@ def event_time_ms(torch, fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
-DOMINANT_KERNEL = "k_wgrad1x1_fast<3, 4, true>"
+DOMINANT_KERNEL = "k_wgrad_pair<3, 4, 1, 3, true>"
 # HBM bytes per launch of that kernel (average over the launches timed below) from the two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by the copy kernel of known size),
 # summarised in profiles/; valid for that workload only.
-MEASURED_TRAFFIC = {"config2:64": 74636145}   # profiles/bc100_b64_fp32_wgrad1x1_hbm_traffic.txt, average over the launches timed below
+MEASURED_TRAFFIC = {}   # profiles/bc100_b64_fp32_wgrad_pair_hbm_traffic.txt
 HBM_PEAK_GBS = 8000.0
 
 
 def dominant_kernel_roofline(dnb, torch, runs, traffic_key):
     """Live measurement of the kernel with the largest share of the step in the committed
-    rocprofv3 summary (profiles/): the fused schedule's 1x1 weight gradient -- BN1+ReLU of the
-    concatenated features recomputed in the operand load, fp32 MFMA with pixels on the K axis,
-    operands straight from HBM, one partial per workgroup.  Per launch it reads P*(C_l + B)*4
-    bytes and writes C_l*B*4 (algorithmic bytes) for 2*P*C_l*B flops: at these widths the HBM
-    roof (8 TB/s) binds a little before the fp32 matrix pipe does, and the roof whose time over
-    the launches below is the larger is reported.  The launches are the layers of the workload's
-    largest dense block that take this instantiation (C_l >= 49: four or more 16-channel
-    tiles), with the block's own slab stride, through the single-op entry point, each launch
-    stamping its own pair of events at the kernel's start and end on the launch stream."""
+    rocprofv3 summary (profiles/): the launch that holds a bottleneck layer's two weight
+    gradients (1x1 and 3x3, BN+ReLU of their activation operands recomputed in the operand
+    loads, fp32 MFMA with pixels on the K axis) and the reduction pass of the layer's first BN
+    backward.  Algorithmic work per launch: 2*P*C_l*B + 18*P*B*k flops; 4*(P*(C_l + B) + C_l*B)
+    + 4*(P*(B + k) + 9*B*k) + 8*P*C_l bytes (the BN reduction reads the features and their
+    gradient once more).  The roof whose time over the launches below is the larger is reported:
+    at these widths HBM (8 TB/s).  The launches are the layers of the workload's largest dense
+    block that take this instantiation (C_l >= 49), with the block's own slab strides, through
+    the single-op entry point, each launch stamping its own pair of events at the kernel's start
+    and end on the launch stream.  (Inside the step the launch also adds up the previous layer's
+    weight-gradient partial sums: about 20 MB more.)"""
     import numpy as np
     cfg = runs[0].cfg
     n, B, k, h, w, m = cfg.n, cfg.bottleneck, cfg.growth, cfg.h, cfg.w, cfg.layers
     hw = h * w
     c_out = cfg.c0 + m * k
-    y = torch.randn((n, c_out, h, w), device="cuda")
-    g = torch.randn((n, B, h, w), device="cuda")
+    dev = "cuda"
+    y = torch.randn((n, c_out, h, w), device=dev)
+    G = torch.randn((n, c_out, h, w), device=dev)
+    db = torch.randn((n, B, h, w), device=dev)
+    bact = torch.randn((n, B, h, w), device=dev)
+    fold2 = torch.stack([torch.ones(B, device=dev), torch.zeros(B, device=dev)], dim=1).contiguous()
+    dw3 = torch.empty((k, B, 3, 3), device=dev)
     cs = [cfg.c0 + (l - 1) * k for l in range(1, m + 1) if cfg.c0 + (l - 1) * k >= 49]
     reps = 3
     ms_sum, flops, nbytes, launches = 0.0, 0.0, 0.0, 0
     for c in cs:
-        fold = torch.stack([torch.ones(c, device="cuda"), torch.zeros(c, device="cuda")], dim=1).contiguous()
-        dw = torch.empty((B, c, 1, 1), device="cuda")
-        scratch = torch.empty(dnb.dnb_op_conv_wgrad_scratch_bytes(n, c, B, h, w, 1), dtype=torch.uint8, device="cuda")
-        args = (y, c_out * hw, fold, g, B * hw, dw, n, c, B, h, w, 1, scratch)
-        dnb.dnb_op_conv_bnrelu_wgrad(*args)   # warm
+        fold1 = torch.stack([torch.ones(c, device=dev), torch.zeros(c, device=dev)], dim=1).contiguous()
+        dw1 = torch.empty((B, c, 1, 1), device=dev)
+        dact = torch.randn((n, c, h, w), device=dev)
+        ones, zeros = torch.ones(c, device=dev), torch.zeros(c, device=dev)
+        scratch = torch.empty(dnb.dnb_op_layer_wgrads_scratch_bytes(n, c, B, k, h, w), dtype=torch.uint8, device=dev)
+        g = G[:, c:c + k]     # the slab's slice of this layer, image stride c_out*hw
+        args = (y, c_out * hw, fold1, db, dw1, c, bact, fold2, g, c_out * hw, dw3, n, B, k, h, w, scratch)
+        kw = dict(bn_dact=dact, bn_gamma=ones, bn_beta=zeros, bn_mean=zeros, bn_istd=ones)
+        dnb.dnb_op_layer_wgrads(*args, **kw)   # warm
         evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
         for e0, e1 in evs:
             e0.record(); e1.record()   # creates the handles; the launch below re-stamps both
-            dnb.dnb_op_conv_bnrelu_wgrad(*args, ev_start=e0, ev_stop=e1)
+            dnb.dnb_op_layer_wgrads(*args, ev_start=e0, ev_stop=e1, **kw)
         torch.cuda.synchronize()
         ms_sum += float(np.mean([e0.elapsed_time(e1) for e0, e1 in evs]))
-        flops += 2.0 * n * hw * c * B
-        nbytes += 4.0 * (n * hw * (c + B) + c * B)
+        flops += 2.0 * n * hw * c * B + 18.0 * n * hw * B * k
+        nbytes += 4.0 * (n * hw * (c + B) + c * B) + 4.0 * (n * hw * (B + k) + 9 * B * k) + 8.0 * n * hw * c
         launches += 1
     ms = ms_sum / launches
     t_hbm, t_mfma = nbytes / (HBM_PEAK_GBS * 1e9), flops / (MFMA_F32_PEAK_TF * 1e12)
-    common = {"kernel": DOMINANT_KERNEL + " (1x1 weight gradient with BN1+ReLU prologue)",
+    common = {"kernel": DOMINANT_KERNEL + " (a layer's 1x1 and 3x3 weight gradients and its BN1 backward reduction in one launch)",
               "traffic": MEASURED_TRAFFIC.get(traffic_key), "avg_launch_ms": round(ms, 5),
               "algorithmic_flops_per_launch": int(flops / launches),
               "algorithmic_bytes_per_launch": int(nbytes / launches), "launches_averaged": launches * reps,
-              "shapes": "1x1 weight gradient %d x C_l over P = %d pixels, C_l = %d..%d (the %d layers of the first dense "
-                        "block with C_l >= 49)" % (B, n * hw, cs[0], cs[-1], launches)}
+              "shapes": "B = %d, k = %d over P = %d pixels, C_l = %d..%d (the %d layers of the first dense block with "
+                        "C_l >= 49)" % (B, k, n * hw, cs[0], cs[-1], launches)}
     if t_hbm >= t_mfma:
         achieved = nbytes / (ms_sum * 1e-3) / 1e9
         return dict({"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",

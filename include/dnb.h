@@ -210,6 +210,27 @@ int dnb_op_conv_bnrelu_forward(const void* x, int64_t x_stride, const void* wgt,
 int dnb_op_conv_bnrelu_wgrad(const void* x, int64_t x_stride, const void* fold, const void* dout,
                              int64_t dout_stride, void* dwgt, int64_t n, int64_t cin, int64_t cout, int64_t h,
                              int64_t w, int ks, void* scratch, void* ev_start, void* ev_stop, void* stream);
+/* Both weight gradients of a bottleneck layer in the fused schedule, as the one launch the
+ * backward pass issues for them when it runs on one stream (Section 4's recomputation folded
+ * into the operand loads):
+ *   dW1 (B, cin)       = 1x1 weight gradient of max(0, x1[:, :cin]*s1 + t1) and db
+ *   dW3 (k, B, 3, 3)   = 3x3 weight gradient of max(0, b*s2 + t2) and g
+ * x1: (n, >= cin, h, w) with image stride x1_stride; db, b: (n, B, h, w) contiguous; g: (n, k,
+ * h, w) with image stride g_stride; fold1 (cin pairs), fold2 (B pairs) as above.  If bn_dact is
+ * not null the launch also carries the reduction pass of the layer's first BN backward over
+ * x1[:, :cin] and bn_dact (n, cin, h, w) (bn_gamma, bn_beta, bn_mean, bn_istd: cin floats each;
+ * its partial sums stay in scratch).  The two small kernels that add the weight gradients'
+ * partial sums follow the launch; ev_start / ev_stop are stamped around the launch itself.
+ * scratch: dnb_op_layer_wgrads_scratch_bytes.  DNB_E_UNSUPPORTED unless B >= 48, the image is
+ * 16-byte friendly (h*w % 4 == 0, w % 4 == 0) and (B, k) is a combination the paired kernel
+ * is built for ((48, <=16) or (>=32 with two 16-channel tiles each way)). */
+size_t dnb_op_layer_wgrads_scratch_bytes(int64_t n, int64_t cin, int64_t bottleneck, int64_t growth, int64_t h,
+                                         int64_t w);
+int dnb_op_layer_wgrads(const void* x1, int64_t x1_stride, const void* fold1, const void* db, void* dw1, int64_t cin,
+                        const void* b, const void* fold2, const void* g, int64_t g_stride, void* dw3, int64_t n,
+                        int64_t bottleneck, int64_t growth, int64_t h, int64_t w, const void* bn_dact,
+                        const void* bn_gamma, const void* bn_beta, const void* bn_mean, const void* bn_istd,
+                        void* scratch, void* ev_start, void* ev_stop, void* stream);
 int dnb_op_conv_dgrad(const void* dout, int64_t dout_stride, const void* wgt, void* din,
                       int64_t din_stride, int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w,
                       int ks, void* scratch, void* stream);

@@ -75,6 +75,9 @@ _SIGS = {
                                              _i64, _i64, C.c_int, _vp, C.c_int, _vp, _vp, _vp]),
     "dnb_op_conv_bnrelu_wgrad": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _vp, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp,
                                            _vp, _vp, _vp]),
+    "dnb_op_layer_wgrads_scratch_bytes": (_sz, [_i64, _i64, _i64, _i64, _i64, _i64]),
+    "dnb_op_layer_wgrads": (C.c_int, [_vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _i64, _i64, _i64, _i64,
+                                      _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "dnb_op_conv_dgrad": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
     "dnb_op_conv_wgrad_scratch_bytes": (_sz, [_i64, _i64, _i64, _i64, _i64, C.c_int]),
     "dnb_op_conv_wgrad": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
@@ -257,6 +260,22 @@ def dnb_op_conv_bnrelu_wgrad(x, x_stride, fold, dout, dout_stride, dwgt, n, cin,
 def dnb_op_conv_dgrad(dout, dout_stride, wgt, din, din_stride, n, cin, cout, h, w, ks, scratch, stream=None) -> None:
     _check(_lib.dnb_op_conv_dgrad(_ptr(dout), dout_stride, _ptr(wgt), _ptr(din), din_stride, n, cin, cout, h,
                                   w, ks, _ptr(scratch), _stream(stream)))
+
+
+def dnb_op_layer_wgrads_scratch_bytes(n, cin, bottleneck, growth, h, w) -> int:
+    return int(_lib.dnb_op_layer_wgrads_scratch_bytes(n, cin, bottleneck, growth, h, w))
+
+
+def dnb_op_layer_wgrads(x1, x1_stride, fold1, db, dw1, cin, b, fold2, g, g_stride, dw3, n, bottleneck, growth, h, w,
+                        scratch, bn_dact=None, bn_gamma=None, bn_beta=None, bn_mean=None, bn_istd=None,
+                        ev_start=None, ev_stop=None, stream=None) -> None:
+    h0 = ev_start.cuda_event if ev_start is not None else None
+    h1 = ev_stop.cuda_event if ev_stop is not None else None
+    opt = lambda t: _ptr(t) if t is not None else None
+    _check(_lib.dnb_op_layer_wgrads(_ptr(x1), x1_stride, _ptr(fold1), _ptr(db), _ptr(dw1), cin, _ptr(b), _ptr(fold2),
+                                    _ptr(g), g_stride, _ptr(dw3), n, bottleneck, growth, h, w, opt(bn_dact),
+                                    opt(bn_gamma), opt(bn_beta), opt(bn_mean), opt(bn_istd), _ptr(scratch), h0, h1,
+                                    _stream(stream)))
 
 
 def dnb_op_conv_wgrad_scratch_bytes(n, cin, cout, h, w, ks) -> int:

@@ -925,6 +925,51 @@ int dnb_op_conv_bnrelu_wgrad(const void* x, int64_t x_stride, const void* fold, 
   return e == hipSuccess ? DNB_OK : DNB_E_LAUNCH;
 }
 
+size_t dnb_op_layer_wgrads_scratch_bytes(int64_t n, int64_t cin, int64_t B, int64_t k, int64_t h, int64_t w) {
+  if (n < 1 || cin < 1 || B < 1 || k < 1 || h < 1 || w < 1) return 0;
+  const size_t f = conv_wgrad_partial_floats((int)n, (int)cin, (int)B, (int)h, (int)w, 1) +
+                   conv_wgrad_partial_floats((int)n, (int)B, (int)k, (int)h, (int)w, 9) +
+                   bn_bwd_partial_floats((int)n, (int)cin, (int)(h * w)) + 16;
+  return f * sizeof(float);
+}
+
+int dnb_op_layer_wgrads(const void* x1, int64_t x1_stride, const void* fold1, const void* db, void* dw1, int64_t cin,
+                        const void* bact, const void* fold2, const void* g, int64_t g_stride, void* dw3, int64_t n,
+                        int64_t B, int64_t k, int64_t h, int64_t w, const void* bn_dact, const void* bn_gamma,
+                        const void* bn_beta, const void* bn_mean, const void* bn_istd, void* scratch, void* ev_start,
+                        void* ev_stop, void* stream) {
+  if (!x1 || !fold1 || !db || !dw1 || !bact || !fold2 || !g || !dw3 || !scratch) return DNB_E_NULL;
+  if (bn_dact && (!bn_gamma || !bn_beta || !bn_mean || !bn_istd)) return DNB_E_NULL;
+  int rc = conv_args_ok(n, cin, B, h, w, 1);
+  if (rc) return rc;
+  rc = conv_args_ok(n, B, k, h, w, 3);
+  if (rc) return rc;
+  const int hw = (int)(h * w);
+  float* part1 = (float*)scratch;
+  float* part3 = part1 + ((conv_wgrad_partial_floats((int)n, (int)cin, (int)B, (int)h, (int)w, 1) + 3) & ~(size_t)3);
+  float* partbn = part3 + ((conv_wgrad_partial_floats((int)n, (int)B, (int)k, (int)h, (int)w, 9) + 3) & ~(size_t)3);
+  BnBwdPartialArgs bn;
+  bool has_bn = false;
+  if (bn_dact) {
+    has_bn = bn_bwd_partial_plan((const float*)x1, x1_stride, (const float*)bn_dact, cin * hw, (int)n, (int)cin, hw,
+                                 (const float*)bn_gamma, (const float*)bn_beta, (const float*)bn_mean,
+                                 (const float*)bn_istd, partbn, &bn);
+    if (!has_bn) return DNB_E_UNSUPPORTED;
+  }
+  PendingSum p1, p3;
+  bool paired = false, bn_done = false;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = launch_conv_wgrad_pair((const float*)x1, x1_stride, (const float*)db, B * hw, (float*)dw1, (int)cin,
+                                        part1, (const float2*)fold1, (const float*)bact, B * hw, (const float*)g,
+                                        g_stride, (float*)dw3, (int)k, part3, (const float2*)fold2, (int)n, (int)B,
+                                        (int)h, (int)w, st, &p1, &p3, has_bn ? &bn : nullptr, &bn_done,
+                                        (hipEvent_t)ev_start, (hipEvent_t)ev_stop, &paired);
+  if (e == hipSuccess) e = launch_pending_sum(&p1, st);
+  if (e == hipSuccess) e = launch_pending_sum(&p3, st);
+  if (e != hipSuccess) return DNB_E_LAUNCH;
+  return paired ? DNB_OK : DNB_E_UNSUPPORTED;  // (the two gradients are complete either way)
+}
+
 // ---- single operations of the bf16 / NHWC path
 
 size_t dnb_op_nhwc_scratch_bytes(int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w, int ks) {

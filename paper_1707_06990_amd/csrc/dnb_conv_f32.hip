@@ -34,7 +34,8 @@ bool launch_wgrad_pair_fast(const float* in1, int64_t in1_stride, const float* g
                             float* dw1, int cin1, const float2* fold1, const float* in3, int64_t in3_stride,
                             const float* g3, int64_t g3_stride, float* part3, float* dw3, int cout3,
                             const float2* fold3, int n, int B, int h, int w, PendingSum* own1, PendingSum* own3,
-                            PendingSum* absorb1, PendingSum* absorb3, const BnBwdPartialArgs* bn, hipStream_t st);
+                            PendingSum* absorb1, PendingSum* absorb3, const BnBwdPartialArgs* bn, hipStream_t st,
+                            hipEvent_t ev0, hipEvent_t ev1);
 
 namespace {
 
@@ -465,15 +466,18 @@ hipError_t launch_conv_wgrad_pair(const float* in1, int64_t in1_stride, const fl
                                   float* dw1, int cin1, float* part1, const float2* fold1, const float* in3,
                                   int64_t in3_stride, const float* g3, int64_t g3_stride, float* dw3, int cout3,
                                   float* part3, const float2* fold3, int n, int B, int h, int w, hipStream_t st,
-                                  PendingSum* pend1, PendingSum* pend3, const BnBwdPartialArgs* bn, bool* bn_done) {
+                                  PendingSum* pend1, PendingSum* pend3, const BnBwdPartialArgs* bn, bool* bn_done,
+                                  hipEvent_t ev0, hipEvent_t ev1, bool* paired) {
   PendingSum own1, own3;
+  if (paired) *paired = false;
   if (bn_done) *bn_done = false;
   if (cin1 > 0 && B > 0 && cout3 > 0 &&
       launch_wgrad_pair_fast(in1, in1_stride, g1, g1_stride, part1, dw1, cin1, fold1, in3, in3_stride, g3, g3_stride,
-                             part3, dw3, cout3, fold3, n, B, h, w, &own1, &own3, pend1, pend3, bn, st)) {
+                             part3, dw3, cout3, fold3, n, B, h, w, &own1, &own3, pend1, pend3, bn, st, ev0, ev1)) {
     *pend1 = own1;
     *pend3 = own3;
     if (bn_done) *bn_done = bn != nullptr;
+    if (paired) *paired = true;
     return hipGetLastError();
   }
   hipError_t e = launch_conv_wgrad(in3, in3_stride, g3, g3_stride, dw3, n, B, cout3, h, w, 9, part3, fold3, st, nullptr,

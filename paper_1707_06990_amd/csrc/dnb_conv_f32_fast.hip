@@ -1529,7 +1529,8 @@ bool launch_wgrad_pair_fast(const float* in1, int64_t in1_stride, const float* g
                             float* dw1, int cin1, const float2* fold1, const float* in3, int64_t in3_stride,
                             const float* g3, int64_t g3_stride, float* part3, float* dw3, int cout3,
                             const float2* fold3, int n, int B, int h, int w, PendingSum* own1, PendingSum* own3,
-                            PendingSum* absorb1, PendingSum* absorb3, const BnBwdPartialArgs* bn, hipStream_t st) {
+                            PendingSum* absorb1, PendingSum* absorb3, const BnBwdPartialArgs* bn, hipStream_t st,
+                            hipEvent_t ev0, hipEvent_t ev1) {
   if ((fold1 != nullptr) != (fold3 != nullptr)) return false;
   if (in1_stride % 4 || g1_stride % 4 || in3_stride % 4 || g3_stride % 4 || !aligned16(in1) || !aligned16(g1) ||
       !aligned16(in3) || !aligned16(g3))
@@ -1549,10 +1550,10 @@ bool launch_wgrad_pair_fast(const float* in1, int64_t in1_stride, const float* g
   const size_t lds = p1.lds > p3.lds ? p1.lds : p3.lds;
 #define DNB_P(C1, M3, C3)                                                                                             \
   do {                                                                                                                \
-    if (fold1) hipLaunchKernelGGL((k_wgrad_pair<3, C1, M3, C3, true>), grid, dim3(256), lds, st, A1, p1.gy, p1.gz, n1, \
-                                  A3, p3.gy, p3.gz, n3, s1, s3, bna, nbn);                                            \
-    else hipLaunchKernelGGL((k_wgrad_pair<3, C1, M3, C3, false>), grid, dim3(256), lds, st, A1, p1.gy, p1.gz, n1, A3,  \
-                            p3.gy, p3.gz, n3, s1, s3, bna, nbn);                                                      \
+    if (fold1) hipExtLaunchKernelGGL((k_wgrad_pair<3, C1, M3, C3, true>), grid, dim3(256), lds, st, ev0, ev1, 0, A1,  \
+                                     p1.gy, p1.gz, n1, A3, p3.gy, p3.gz, n3, s1, s3, bna, nbn);                       \
+    else hipExtLaunchKernelGGL((k_wgrad_pair<3, C1, M3, C3, false>), grid, dim3(256), lds, st, ev0, ev1, 0, A1, p1.gy, \
+                               p1.gz, n1, A3, p3.gy, p3.gz, n3, s1, s3, bna, nbn);                                    \
   } while (0)
 #define DNB_P1(M3, C3)                                                                          \
   switch (p1.ctw) {                                                                             \

@@ -144,8 +144,10 @@ hipError_t launch_conv_wgrad_pair(const float* in1, int64_t in1_stride, const fl
                                   int64_t in3_stride, const float* g3, int64_t g3_stride, float* dw3, int cout3,
                                   float* part3, const float2* fold3, int n, int B, int h, int w, hipStream_t st,
                                   PendingSum* pend1, PendingSum* pend3, const BnBwdPartialArgs* bn = nullptr,
-                                  bool* bn_done = nullptr);
-// (bn: a BN backward reduction to carry in the same launch; *bn_done says whether it was)
+                                  bool* bn_done = nullptr, hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr,
+                                  bool* paired = nullptr);
+// (bn: a BN backward reduction to carry in the same launch, *bn_done says whether it was;
+//  ev_start / ev_stop are stamped around the shared launch, *paired says whether there was one)
 
 // out[e] = sum over splits of partials[split][e] (fixed order).
 hipError_t launch_sum_partials(const float* partials, int splits, int64_t count, float* out, hipStream_t st);

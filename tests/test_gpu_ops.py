@@ -216,3 +216,48 @@ def test_fused_conv_bnrelu_wgrad(dnb, oracle, n, cin, cout, h, w, ks):
     a = np.maximum(x.astype(np.float64) * fold[:, 0].astype(np.float64)[None, :, None, None]
                    + fold[:, 1].astype(np.float64)[None, :, None, None], 0.0)
     assert_close(dw.cpu().numpy(), oracle.conv_wgrad(a, g, ks), TOL, "fused wgrad")
+
+
+@pytest.mark.parametrize("n,cin,B,k,h,w,with_bn", [(4, 72, 48, 12, 16, 16, True), (2, 40, 96, 24, 8, 8, False),
+                                                   (3, 24, 48, 12, 8, 12, True)])
+def test_layer_weight_gradients_in_one_launch(dnb, oracle, n, cin, B, k, h, w, with_bn):
+    """Both weight gradients of a bottleneck layer (BN+ReLU of their activation operands recomputed
+    in the operand loads) from the launch the one-stream backward pass uses, with and without the
+    BN backward reduction riding along; each against the oracle's weight gradient."""
+    r = rng(31)
+    c_tot = cin + 8                                  # the slab is wider than the layer's input
+    y = f32(r.standard_normal((n, c_tot, h, w)))
+    db = f32(r.standard_normal((n, B, h, w)))
+    b = f32(r.standard_normal((n, B, h, w)))
+    g_slab = f32(r.standard_normal((n, k + 4, h, w)))  # g is a channel slice of a wider slab
+    fold1 = f32(np.stack([1.0 + 0.3 * r.standard_normal(cin), 0.3 * r.standard_normal(cin)], axis=1))
+    fold2 = f32(np.stack([1.0 + 0.3 * r.standard_normal(B), 0.3 * r.standard_normal(B)], axis=1))
+    hw = h * w
+    dw1 = torch.full((B, cin, 1, 1), float("nan"), device="cuda")
+    dw3 = torch.full((k, B, 3, 3), float("nan"), device="cuda")
+    scratch = torch.empty(dnb.dnb_op_layer_wgrads_scratch_bytes(n, cin, B, k, h, w), dtype=torch.uint8, device="cuda")
+    d_g = dev(g_slab)
+    g_view = d_g[:, 4:]                              # channels 4.., image stride (k + 4) * hw
+    bn = {}
+    if with_bn:
+        bn = dict(bn_dact=dev(f32(r.standard_normal((n, cin, h, w)))), bn_gamma=dev(f32(1.0 + 0.1 * r.standard_normal(cin))),
+                  bn_beta=dev(f32(0.1 * r.standard_normal(cin))), bn_mean=dev(f32(0.1 * r.standard_normal(cin))),
+                  bn_istd=dev(f32(1.0 + 0.1 * r.random(cin))))
+    dnb.dnb_op_layer_wgrads(dev(y), c_tot * hw, dev(fold1), dev(db), dw1, cin, dev(b), dev(fold2), g_view, (k + 4) * hw,
+                            dw3, n, B, k, h, w, scratch, **bn)
+    torch.cuda.synchronize()
+    act = lambda x, f: np.maximum(x.astype(np.float64) * f[:, 0].astype(np.float64)[None, :, None, None]
+                                  + f[:, 1].astype(np.float64)[None, :, None, None], 0.0)
+    assert_close(dw1.cpu().numpy(), oracle.conv_wgrad(act(y[:, :cin], fold1), db, 1), TOL, "1x1 weight gradient")
+    assert_close(dw3.cpu().numpy(), oracle.conv_wgrad(act(b, fold2), g_slab[:, 4:], 3), TOL, "3x3 weight gradient")
+
+
+def test_layer_weight_gradients_reports_unbuilt_pairs(dnb):
+    n, cin, B, k, h, w = 2, 16, 32, 8, 8, 8          # B = 32: two 16-channel tiles, not a built pair
+    z = lambda *s: torch.zeros(s, device="cuda")
+    scratch = torch.empty(dnb.dnb_op_layer_wgrads_scratch_bytes(n, cin, B, k, h, w), dtype=torch.uint8, device="cuda")
+    with pytest.raises(dnb.binding.DnbError) as e:
+        dnb.dnb_op_layer_wgrads(z(n, cin, h, w), cin * h * w, z(cin, 2), z(n, B, h, w), z(B, cin, 1, 1), cin, z(n, B, h, w),
+                                z(B, 2), z(n, k, h, w), k * h * w, z(k, B, 3, 3), n, B, k, h, w, scratch)
+    assert e.value.status == dnb.DNB_E_UNSUPPORTED
+
