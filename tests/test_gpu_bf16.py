@@ -168,6 +168,22 @@ def test_nhwc_conv_ops(dnb, oracle, n, cin, cout, h, w, ks, g_f32):
     assert_close(dw.cpu().numpy(), oracle.conv_wgrad(x, g, ks), 1e-2, "wgrad")
 
 
+@pytest.mark.parametrize("g_f32", [0, 1])
+def test_nhwc_wgrad_rows_wider_than_the_row_tiled_kernel_takes(dnb, oracle, g_f32):
+    """96-pixel rows: the 3x3 weight gradient falls back to the kernel that stages 64-pixel tiles
+    once per tap (forward and data gradient do not take such rows at all)."""
+    n, cin, cout, h, w = 1, 8, 8, 2, 96
+    r = np.random.default_rng(9)
+    x = to_bf16_values(r.standard_normal((n, cin, h, w)).astype(np.float32))
+    g = to_bf16_values(r.standard_normal((n, cout, h, w)).astype(np.float32))
+    scratch = torch.empty(dnb.dnb_op_nhwc_scratch_bytes(n, cin, cout, h, w, 3), dtype=torch.uint8, device="cuda")
+    dw = torch.full((cout, cin, 3, 3), float("nan"), device="cuda")
+    dnb.dnb_op_nhwc_conv_wgrad(nhwc_bf16(x), cin, nhwc_f32(g) if g_f32 else nhwc_bf16(g), cout, g_f32, dw, n, cin, cout, h, w, 3,
+                               scratch)
+    torch.cuda.synchronize()
+    assert_close(dw.cpu().numpy(), oracle.conv_wgrad(x, g, 3), 1e-2, "wgrad")
+
+
 @pytest.mark.parametrize("shape", [(2, 16, 8, 8), (3, 40, 7, 5), (2, 264, 6, 6), (4, 24, 40, 40), (2, 192, 28, 28)])
 @pytest.mark.parametrize("accumulate", [0, 1])
 def test_nhwc_bn_relu_backward(dnb, oracle, shape, accumulate):

@@ -126,6 +126,7 @@ CONV_SHAPES = [
     # aligned shapes (16-byte fast kernels): wide K, many M tiles, tiny and ragged images, channel tails
     (2, 330, 48, 8, 8, 1), (1, 200, 48, 16, 16, 1), (3, 36, 48, 4, 4, 1), (2, 16, 8, 4, 4, 3),
     (1, 32, 16, 8, 56, 3), (2, 28, 20, 12, 12, 3), (2, 100, 36, 8, 8, 3), (5, 60, 64, 8, 8, 3), (1, 24, 48, 20, 20, 1),
+    (1, 16, 16, 4, 64, 3),   # rows too wide for the 3x3 weight gradient's one-batch first chunk
 ]
 
 
@@ -201,7 +202,7 @@ def test_fused_conv_bnrelu_forward_and_statistics(dnb, oracle, n, cin, cout, h, 
 
 
 @pytest.mark.parametrize("n,cin,cout,h,w,ks", [(2, 48, 12, 32, 32, 3), (3, 40, 48, 16, 16, 1), (2, 204, 48, 8, 8, 1),
-                                               (2, 24, 12, 8, 12, 3)])
+                                               (2, 24, 12, 8, 12, 3), (1, 16, 12, 4, 64, 3)])
 def test_fused_conv_bnrelu_wgrad(dnb, oracle, n, cin, cout, h, w, ks):
     """Weight gradient with BN+ReLU of the activation recomputed in the operand load."""
     r = rng(22)
