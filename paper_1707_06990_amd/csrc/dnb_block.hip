@@ -25,8 +25,9 @@ struct dnb_block {
   size_t off_part;                           // reduction partials of the main chain (BN)
   size_t partA_floats, partB_floats;         // size of one weight-gradient partial buffer
   size_t off_partA, off_partB;               // partials of the 3x3 / 1x1 weight gradients
-  // backward runs three chains: the data-gradient chain on the caller's stream and the two
-  // weight-gradient chains on these helper streams (created at the first backward call)
+  // with concurrency on, backward runs three chains: the data-gradient chain on the caller's
+  // stream and the two weight-gradient chains on these helper streams (created at the first
+  // such backward call); off, everything runs on the caller's stream
   int concurrency;
   bool streams_ready;
   hipStream_t sA, sB;
@@ -643,6 +644,9 @@ int dnb_block_backward(dnb_block* b, const void* paramsv, const void* yv, const 
   // helper streams, ordered by events exactly where buffers are shared:
   //   A: [recompute storage 3] -> wgrad 3x3 -> sum        (needs g_l complete)
   //   B: [recompute storage 1,2] -> wgrad 1x1 -> sum      (needs db_l; storage 1 also feeds BN1 bwd)
+  // With concurrency off (the fp32 default) the same kernels run on the caller's stream, and the
+  // leaves are gathered: a layer's two weight gradients, the previous layer's partial sums and
+  // the reduction pass of BN1's backward go out as one launch just before BN1's apply pass.
   const bool conc = b->concurrency != 0;
   if (conc) {
     const int rc = ensure_helper_streams(b);

@@ -1,15 +1,16 @@
 // bf16 / NHWC kernels of the dense block (feature maps stored as bf16, channels contiguous;
 // fp32 accumulation, fp32 BN statistics, fp32 parameters and parameter gradients, fp32 gradient
-// slab).  First correct version: every step of the fused schedule, built around
-// v_mfma_f32_16x16x32_bf16 with output channels on M and pixels on N, so a lane's operand is
-// 8 consecutive channels of one pixel (16 bytes of NHWC) and an accumulator holds 4 consecutive
-// channels of one pixel (one 8-byte NHWC store).
+// slab).  Every step of the fused schedule, built around v_mfma_f32_16x16x32_bf16 with output
+// channels on M and pixels on N, so a lane's operand is 8 consecutive channels of one pixel
+// (16 bytes of NHWC) and an accumulator holds 4 consecutive channels of one pixel (one 8-byte
+// NHWC store).
 //
 // Convolutions (forward / data gradient): the workgroup stages a 64-pixel tile (+ one image row
-// of halo for 3x3) of a 32-channel chunk in LDS, applying the BN+ReLU prologue once per element;
-// its four waves split the output-channel tiles and read packed bf16 weights straight from L2.
-// Weight gradients contract over pixels, which NHWC keeps on the slow axis, so both operands are
-// transposed on their way into LDS ([channel][pixel]); the 3x3 stages one shifted copy per tap.
+// of halo for 3x3) of a 64-channel chunk in LDS, double-buffered, applying the BN+ReLU prologue
+// once per element; its four waves split the output-channel tiles and take packed bf16 weights
+// from L2 through register rings.  Weight gradients contract over pixels, which NHWC keeps on
+// the slow axis, so both operands are transposed on their way into LDS ([channel][pixel]); the
+// 3x3 stages a row tile once and reads its nine taps as shifted fragments.
 #include "dnb_internal.h"
 #include "dnb_stats.cuh"
 
