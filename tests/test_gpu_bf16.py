@@ -98,6 +98,41 @@ def test_bf16_backward_chains_on_helper_streams_give_the_same_bits(dnb, cfg):
         assert np.array_equal(a[key], b[key]), key
 
 
+@pytest.mark.parametrize("which", ["config4", "config5"])
+def test_bf16_full_size_last_block(dnb, oracle, which):
+    """The last dense block of the DenseNet-161- and -264-shaped workloads exactly as bench.py
+    times them (batch 32, 7x7; 24 layers, 1056 -> 2208 channels, k = 48, B = 192, and 48 layers,
+    k = 32, B = 128: the ring 1x1 conv, up to nine channel groups in the 1x1 weight gradient, one
+    7-row tile per image in the 3x3's).  y meets the
+    2e-2 bar outright.  At this depth the bf16 block is ill-conditioned in its gradients: a
+    rounding that falls on the other side of a bf16 boundary changes ReLU masks in all later
+    layers.  The emulating oracle shows by how much: re-run with one layer's 1x1 weights perturbed
+    by one part in 1e7 (a thousandth of an fp32 ulp of the activations' bf16 spacing), its own
+    gradients move by 6-9 %.  The HIP path has to be as close to the oracle as the oracle is to
+    that twin: within twice the twin's distance, tensor by tensor."""
+    cfg = (wl.config4() if which == "config4" else wl.config5())[3]
+    x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
+    x0, dy = to_bf16_values(x0), to_bf16_values(dy)
+    gpu = run_block_gpu_bf16(dnb, cfg, x0, lp, dy)
+    ores, osl = run_block_oracle(oracle, cfg, x0, lp, dy, schedule="naive_bf16")
+    lp2 = [dict(p) for p in lp]
+    r = np.random.default_rng(0)
+    lp2[0]["W1"] = (lp2[0]["W1"].astype(np.float64) * (1 + 1e-7 * r.standard_normal(lp2[0]["W1"].shape))).astype(lp2[0]["W1"].dtype)
+    twin, _ = run_block_oracle(oracle, cfg, x0, lp2, dy, schedule="naive_bf16")
+    assert np.array_equal(gpu["y"][:, :cfg.c0], x0)
+    assert_close(gpu["y"], ores.y, TOL, "y")
+
+    def check(a, ref, tw, what):
+        (l2, mx), (tl2, tmx) = rel_errors(a, ref), rel_errors(tw, ref)
+        assert l2 <= max(TOL, 2 * tl2) and mx <= max(GRAD_MAX_TOL, 2 * tmx), \
+            f"{what}: rel L2 {l2:.3e} (twin {tl2:.3e}), rel max {mx:.3e} (twin {tmx:.3e})"
+    check(gpu["dx0"], ores.dx0, twin.dx0, "dx0")
+    for l in range(1, cfg.layers + 1):
+        for name in NAMES:
+            check(gpu["dparams"][gpu["slices"][(l, name)]], ores.dparams[osl[(l, name)]], twin.dparams[osl[(l, name)]],
+                  f"layer {l} d{name}")
+
+
 def test_bf16_bytes_and_unsupported_combinations(dnb):
     cfg = CFGS[3]
     h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck,
