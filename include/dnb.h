@@ -243,7 +243,9 @@ int dnb_op_conv_wgrad(const void* x, int64_t x_stride, const void* dout, int64_t
 /* ---- single operations of the bf16 / NHWC path.  Feature maps are bf16 with channels
  * contiguous; "ld" is the pixel stride in elements, so channel ranges of a wider tensor are
  * addressed in place; channel counts are multiples of 8.  Weights and weight gradients are fp32
- * OIHW.  `scratch`: dnb_op_nhwc_scratch_bytes(n, cin, cout, h, w, ks) device bytes. */
+ * OIHW.  `scratch`: dnb_op_nhwc_scratch_bytes(n, cin, cout, h, w, ks) device bytes.  Feature-map
+ * pointers and `scratch` are 16-byte aligned (else DNB_E_ALIGN); an "ld" is at least the channel
+ * count and a multiple of 8 (of 4 for an fp32 tensor), else DNB_E_RANGE. */
 size_t dnb_op_nhwc_scratch_bytes(int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t w, int ks);
 int dnb_op_nhwc_conv_forward(const void* x, int64_t x_ld, const void* wgt, void* out, int64_t out_ld, int64_t n,
                              int64_t cin, int64_t cout, int64_t h, int64_t w, int ks, void* scratch, void* stream);

@@ -996,11 +996,27 @@ static int nhwc_args_ok(int64_t n, int64_t cin, int64_t cout, int64_t h, int64_t
   return DNB_OK;
 }
 
+// The NHWC kernels move 16 bytes per lane: tensors start on 16-byte boundaries and a pixel
+// stride is a whole number of such vectors that covers the channels used (8 bf16 or 4 fp32 each).
+static int nhwc_tensor_ok(const void* p, int64_t ld, int64_t c, bool f32) {
+  if (misaligned(p)) return DNB_E_ALIGN;
+  if (ld < c || ld % (f32 ? 4 : 8)) return DNB_E_RANGE;
+  return DNB_OK;
+}
+#define DNB_NHWC_CHECK(p, ld, c, f32)                       \
+  do {                                                      \
+    const int rc_ = nhwc_tensor_ok((p), (ld), (c), (f32));  \
+    if (rc_) return rc_;                                    \
+  } while (0)
+
 int dnb_op_nhwc_conv_forward(const void* x, int64_t x_ld, const void* wgt, void* out, int64_t out_ld, int64_t n,
                              int64_t cin, int64_t cout, int64_t h, int64_t w, int ks, void* scratch, void* stream) {
   if (!x || !wgt || !out || !scratch) return DNB_E_NULL;
   const int rc = nhwc_args_ok(n, cin, cout, h, w, ks);
   if (rc) return rc;
+  DNB_NHWC_CHECK(x, x_ld, cin, false);
+  DNB_NHWC_CHECK(out, out_ld, cout, false);
+  if (misaligned4(wgt) || misaligned(scratch)) return DNB_E_ALIGN;
   const int taps = ks * ks;
   DNB_TRY(nhwc::pack_weights(WeightView{(const float*)wgt, cin * taps, taps, 0}, (int)cout, (int)cin, taps, scratch,
                              (hipStream_t)stream));
@@ -1015,6 +1031,9 @@ int dnb_op_nhwc_conv_dgrad(const void* dout, int64_t dout_ld, int dout_is_f32, c
   if (!dout || !wgt || !din || !scratch) return DNB_E_NULL;
   const int rc = nhwc_args_ok(n, cin, cout, h, w, ks);
   if (rc) return rc;
+  DNB_NHWC_CHECK(dout, dout_ld, cout, dout_is_f32 != 0);
+  DNB_NHWC_CHECK(din, din_ld, cin, false);
+  if (misaligned4(wgt) || misaligned(scratch)) return DNB_E_ALIGN;
   const int taps = ks * ks;
   DNB_TRY(nhwc::pack_weights(WeightView{(const float*)wgt, taps, cin * taps, taps == 9 ? 1 : 0}, (int)cin, (int)cout,
                              taps, scratch, (hipStream_t)stream));
@@ -1029,6 +1048,9 @@ int dnb_op_nhwc_conv_wgrad(const void* x, int64_t x_ld, const void* dout, int64_
   if (!x || !dout || !dwgt || !scratch) return DNB_E_NULL;
   const int rc = nhwc_args_ok(n, cin, cout, h, w, ks);
   if (rc) return rc;
+  DNB_NHWC_CHECK(x, x_ld, cin, false);
+  DNB_NHWC_CHECK(dout, dout_ld, cout, dout_is_f32 != 0);
+  if (misaligned4(dwgt) || misaligned(scratch)) return DNB_E_ALIGN;
   DNB_TRY(nhwc::wgrad(x, x_ld, dout, dout_ld, dout_is_f32 != 0, (float*)scratch, (float*)dwgt, (int)n, (int)cin,
                       (int)cout, (int)h, (int)w, ks * ks, nullptr, (hipStream_t)stream));
   return DNB_OK;
@@ -1041,6 +1063,15 @@ int dnb_op_nhwc_bn_relu_backward(const void* x, int64_t x_ld, const void* dact, 
   if (!x || !dact || (!du_bf16 && !du_accum_f32) || !gamma || !beta || !mean || !istd || !dgamma || !dbeta || !scratch)
     return DNB_E_NULL;
   if (pixels < 1 || c < 8 || c % 8) return DNB_E_RANGE;
+  DNB_NHWC_CHECK(x, x_ld, c, false);
+  DNB_NHWC_CHECK(dact, dact_ld, c, false);
+  if (du_accum_f32)
+    DNB_NHWC_CHECK(du_accum_f32, acc_ld, c, true);
+  else
+    DNB_NHWC_CHECK(du_bf16, du_ld, c, false);
+  if (misaligned4(gamma) || misaligned4(beta) || misaligned4(mean) || misaligned4(istd) || misaligned4(dgamma) ||
+      misaligned4(dbeta) || misaligned(scratch))
+    return DNB_E_ALIGN;
   DNB_TRY(nhwc::bn_relu_bwd(x, x_ld, dact, dact_ld, du_bf16, du_ld, (float*)du_accum_f32, acc_ld, pixels, (int)c,
                             (const float*)gamma, (const float*)beta, (const float*)mean, (const float*)istd,
                             (float*)dgamma, (float*)dbeta, (float*)scratch, (hipStream_t)stream));

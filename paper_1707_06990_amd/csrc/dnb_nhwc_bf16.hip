@@ -1070,6 +1070,11 @@ __global__ __launch_bounds__(256) void k_bn_bwd_partial(
 
 // dgamma/dbeta = sum of the S partials, one wave per channel: lane i adds partials i, i+64, ...
 // in order, then a butterfly over the lanes (fixed order, every lane the same bits).
+// (Measured alternative: with at most 32 partials per channel, every workgroup of the
+// element-wise pass added them itself and this launch was left out for slabs of up to 8192
+// pixels.  The reduction pass with fewer splits and the element-wise pass with that prologue
+// each took 3-5 us longer, more than the 3 us launch they replaced: config 4 went from 15.0
+// to 15.2 ms.)
 __global__ __launch_bounds__(256) void k_bn_bwd_finalize(const float* __restrict__ part, int c, int S,
                                                          float* __restrict__ dgamma, float* __restrict__ dbeta) {
   const int ch = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;

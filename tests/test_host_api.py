@@ -62,6 +62,34 @@ def test_null_arguments_are_errors(dnb):
     dnb.dnb_block_destroy(h)
 
 
+def test_nhwc_ops_reject_misaligned_tensors_and_short_strides(dnb):
+    """The bf16 / NHWC single operations move 16 bytes per lane: a feature-map pointer off a
+    16-byte boundary is DNB_E_ALIGN (-3), a pixel stride shorter than the channel count or not a
+    whole number of 16-byte vectors is DNB_E_RANGE (-6); both are found before anything is launched."""
+    lib = ctypes.CDLL(dnb.binding.LIB_PATH)
+    vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    fwd = lib.dnb_op_nhwc_conv_forward
+    fwd.argtypes = [vp, i64, vp, vp, i64, i64, i64, i64, i64, i64, ci, vp, vp]
+    shape = (2, 16, 24, 6, 6, 1)   # n, cin, cout, h, w, ks
+    assert fwd(4096 + 8, 16, 4096, 8192, 24, *shape, 12288, None) == -3       # x off by 8 bytes
+    assert fwd(4096, 16, 4096, 8192 + 2, 24, *shape, 12288, None) == -3       # out off by 2 bytes
+    assert fwd(4096, 16, 4096, 8192, 24, *shape, 12288 + 4, None) == -3       # scratch
+    assert fwd(4096, 8, 4096, 8192, 24, *shape, 12288, None) == -6            # x stride < cin
+    assert fwd(4096, 20, 4096, 8192, 24, *shape, 12288, None) == -6           # x stride not a multiple of 8
+    assert fwd(4096, 16, 4096, 8192, 28, *shape, 12288, None) == -6           # out stride not a multiple of 8
+    dgrad = lib.dnb_op_nhwc_conv_dgrad
+    dgrad.argtypes = [vp, i64, ci, vp, vp, i64, i64, i64, i64, i64, i64, ci, vp, vp]
+    assert dgrad(4096, 26, 1, 4096, 8192, 16, *shape, 12288, None) == -6      # fp32 dout stride not a multiple of 4
+    assert dgrad(4096, 28, 0, 4096, 8192, 16, *shape, 12288, None) == -6      # the same stride for bf16 dout
+    assert dgrad(4096, 24, 0, 4096, 8192 + 8, 16, *shape, 12288, None) == -3  # din
+    bn = lib.dnb_op_nhwc_bn_relu_backward
+    bn.argtypes = [vp, i64, vp, i64, vp, i64, vp, i64, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp]
+    par = [256, 512, 768, 1024, 1280, 1536]
+    assert bn(4096, 16, 8192, 16, None, 0, 12288 + 4, 16, 72, 16, *par, 16384, None) == -3   # fp32 accumulator
+    assert bn(4096, 16, 8192, 16, None, 0, 12288, 18, 72, 16, *par, 16384, None) == -6       # its stride
+    assert bn(4096, 16, 8192, 16, 8192, 12, None, 0, 72, 16, *par, 16384, None) == -6        # bf16 output stride
+
+
 def sigma_c(cfg):
     return sum(cfg.c_in(l) for l in range(1, cfg.layers + 1))
 
