@@ -1274,13 +1274,18 @@ bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, f
       mt = (mtiles + nw - 1) / nw; if (mt > 3) mt = 3;
       gy = (mtiles + nw * mt - 1) / (nw * mt);
     }
-    // 64-pixel tiles unless that leaves the chip underfilled (fewer than 2 workgroups per CU)
-    const int ppl = ((int64_t)((hw + 63) / 64) * gy * n >= 512) ? 4 : 1;
+    // 64-pixel tiles (a lane loads 16 bytes per channel row, and the weights are read once per 64
+    // pixels instead of once per 16) as long as they give one workgroup per CU.  With two per CU or
+    // more, two waves share a tile's K range and two tiles share the workgroup (longer contiguous
+    // runs per channel row measured faster than a four-way K-split); between one and two per CU
+    // (K-split shapes), one tile per workgroup and a four-way K-split: the 16x16 block of
+    // DenseNet-BC-100 at batch 64 went from 18.9 to ~13 us per launch against 16-pixel tiles.
+    // Smaller launches take 16-pixel tiles with a four-way K-split for more loads in flight.
+    const int64_t tiles64 = (int64_t)((hw + 63) / 64) * gy * n;
+    const bool one_tile = ksplit && tiles64 >= 256 && tiles64 < 512;
+    const int ppl = (tiles64 >= 512 || one_tile) ? 4 : 1;
     const int tiles = (hw + 16 * ppl - 1) / (16 * ppl);
-    // 64-pixel tiles: two waves share a tile's K range and two tiles share the workgroup (longer
-    // contiguous runs per channel row measured faster than four-way K-split); 16-pixel tiles of
-    // small images: four-way K-split for more loads in flight
-    const int wk = ksplit ? (ppl == 4 ? 2 : nw) : 1;
+    const int wk = ksplit ? ((ppl == 4 && !one_tile) ? 2 : nw) : 1;
     const int wp = ksplit ? nw / wk : 1;
     dim3 grid((unsigned)((tiles + wp - 1) / wp), (unsigned)gy, (unsigned)n);
     const size_t lds = ksplit ? (size_t)wp * (wk - 1) * mt * ppl * 256 * sizeof(float) : 0;
