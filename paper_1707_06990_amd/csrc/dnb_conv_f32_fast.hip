@@ -746,25 +746,26 @@ __device__ __forceinline__ void sum_role(const SumRole& sr, int wg) {
   }
 }
 
-// Adds the accumulators of the waves of a workgroup into wave 0 as a chain 3 -> 2 -> 1 -> 0 through
-// one LDS region (NT * 256 floats).  (A two-region tree (0+2)+(1+3) was measured slower.)
+// Adds the accumulators of the four waves of a workgroup, a0 + (a1 + (a2 + a3)) element by
+// element: every wave writes its NT tiles to its own LDS region (4 * NT * 256 floats in all),
+// then wave w adds up the tiles t with t % 4 == w, which it alone holds afterwards.
 template <int NT>
-__device__ __forceinline__ void reduce_waves(f32x4 (&acc)[NT], float* buf, int wave, int lane, int nw) {
-  for (int w = nw - 1; w >= 1; --w) {
-    __syncthreads();
-    if (wave == w) {
+__device__ __forceinline__ void reduce_waves_split(f32x4 (&acc)[NT], float* buf, int wave, int lane) {
 #pragma unroll
-      for (int t = 0; t < NT; ++t)
-        *reinterpret_cast<float4*>(&buf[(t * 64 + lane) * 4]) = make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
-    }
-    __syncthreads();
-    if (wave == w - 1) {
+  for (int t = 0; t < NT; ++t)
+    *reinterpret_cast<float4*>(&buf[((wave * NT + t) * 64 + lane) * 4]) =
+        make_float4(acc[t][0], acc[t][1], acc[t][2], acc[t][3]);
+  __syncthreads();
 #pragma unroll
-      for (int t = 0; t < NT; ++t) {
-        const float4 v = *reinterpret_cast<const float4*>(&buf[(t * 64 + lane) * 4]);
-        acc[t][0] += v.x; acc[t][1] += v.y; acc[t][2] += v.z; acc[t][3] += v.w;
-      }
+  for (int t = 0; t < NT; ++t) {
+    if ((t & 3) != wave) continue;
+    float4 s = *reinterpret_cast<const float4*>(&buf[((3 * NT + t) * 64 + lane) * 4]);
+#pragma unroll
+    for (int w = 2; w >= 0; --w) {
+      const float4 v = *reinterpret_cast<const float4*>(&buf[((w * NT + t) * 64 + lane) * 4]);
+      s.x = v.x + s.x; s.y = v.y + s.y; s.z = v.z + s.z; s.w = v.w + s.w;
     }
+    acc[t] = (f32x4){s.x, s.y, s.z, s.w};
   }
 }
 
@@ -773,7 +774,8 @@ __device__ __forceinline__ void reduce_waves(f32x4 (&acc)[NT], float* buf, int w
 // dW[m][c] = sum_{n,q} g[n][m][q] a[n][c][q].  A "step" is 16 pixels: lane (r, kk) loads pixels
 // 4kk..4kk+3 of row r of both operands (16 bytes each) and issues 4 K-steps.  The four waves of
 // a workgroup take alternate steps (together 256 contiguous bytes per row), keep all MTW x CTW
-// tiles in registers, and are summed in LDS at the end; the workgroup writes one partial.
+// tiles in registers, and are summed in LDS at the end (each wave a quarter of the tiles, which
+// it then stores); the workgroup writes one partial.
 struct Wg1Args {
   const float* a; int64_t a_stride; const float* g; int64_t g_stride; float* part;
   int cin, cout, HW, spi, total_steps, steps_per_wg;
@@ -860,21 +862,20 @@ __device__ __forceinline__ void wgrad1x1_body(const Wg1Args& A, int bx, int by, 
     }
   }
 
-  reduce_waves<MTW * CTW>(acc, lds, wave, lane, 4);
-  if (wave == 0) {
-    float* pb = part + (int64_t)bx * cout * cin;
+  reduce_waves_split<MTW * CTW>(acc, lds, wave, lane);
+  float* pb = part + (int64_t)bx * cout * cin;
 #pragma unroll
-    for (int x = 0; x < MTW; ++x)
+  for (int x = 0; x < MTW; ++x)
 #pragma unroll
-      for (int y = 0; y < CTW; ++y) {
-        const int c = c0 + y * 16 + r;
+    for (int y = 0; y < CTW; ++y) {
+      if (((x * CTW + y) & 3) != wave) continue;  // the wave that holds this tile's sum stores it
+      const int c = c0 + y * 16 + r;
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-          const int m = m0 + x * 16 + 4 * kk + rr;
-          if (m < cout && c < cin) pb[(int64_t)m * cin + c] = acc[x * CTW + y][rr];
-        }
+      for (int rr = 0; rr < 4; ++rr) {
+        const int m = m0 + x * 16 + 4 * kk + rr;
+        if (m < cout && c < cin) pb[(int64_t)m * cin + c] = acc[x * CTW + y][rr];
       }
-  }
+    }
 }
 
 template <int MTW, int CTW, bool PRO>
@@ -1391,26 +1392,31 @@ static WgFastPlan plan_wgrad_fast(int n, int cin, int cout, int h, int w, int ta
     p.gz = (mtiles + p.mtw - 1) / p.mtw;
     p.spi = (hw + 15) / 16;
     p.total_steps = n * p.spi;
-    // about 512 workgroups in all, 1..8 steps per wave
-    int spw = (int)(((int64_t)p.total_steps * p.gy * p.gz + 4 * 512 - 1) / (4 * 512));
+    // About 128 workgroups in all, 1..16 steps per wave.  A workgroup ends with a cross-wave sum
+    // and a partial of mtw*ctw tiles to store, and every partial is read again by the sum that
+    // follows, so few long workgroups beat many short ones even when they leave CUs to the other
+    // roles of the launch: a target of 512 workgroups (1..8 steps) took 3.3 % more time per
+    // DenseNet-BC-100 step than 128; 96 and 192 were within 0.5 % of 128.
+    int spw = (int)(((int64_t)p.total_steps * p.gy * p.gz + 4 * 128 - 1) / (4 * 128));
     if (spw < 1) spw = 1;
-    if (spw > 8) spw = 8;
+    if (spw > 16) spw = 16;
     p.steps_per_wg = 4 * spw;
     p.gx = (p.total_steps + p.steps_per_wg - 1) / p.steps_per_wg;
-    p.lds = (size_t)p.mtw * p.ctw * 256 * sizeof(float);
+    p.lds = (size_t)4 * p.mtw * p.ctw * 256 * sizeof(float);
   } else {
     p.mtw = mtiles >= 2 ? 2 : 1;
     p.ctw = p.mtw == 2 ? (ctiles >= 2 ? 2 : 1) : (ctiles >= 3 ? 3 : ctiles);
     p.gy = (ctiles + p.ctw - 1) / p.ctw;
     p.gz = (mtiles + p.mtw - 1) / p.mtw;
-    // 64, 128 or 256 pixels per workgroup: the largest that fits LDS and still gives >= 256
-    // workgroups
+    // 64, 128 or 256 pixels per workgroup: the largest that fits LDS and still gives >= 128
+    // workgroups (each ends with a 27 KB partial; 256 and 64 as the bound measured 0.3-0.5 % slower
+    // per DenseNet-BC-100 step)
     p.nms = 1;
     for (int nms = 4; nms >= 2; nms >>= 1) {
       const int tpix = 64 * nms;
       if (tpix / 2 >= hw) continue;
       if ((size_t)p.ctw * 16 * pad4mod32(tpix + 2 * w + 8) * sizeof(float) > 64 * 1024) continue;
-      if ((int64_t)((hw + tpix - 1) / tpix) * n * p.gy * p.gz >= 256) { p.nms = nms; break; }
+      if ((int64_t)((hw + tpix - 1) / tpix) * n * p.gy * p.gz >= 128) { p.nms = nms; break; }
     }
     const int tpix = 64 * p.nms;
     p.tiles_per_img = (hw + tpix - 1) / tpix;
