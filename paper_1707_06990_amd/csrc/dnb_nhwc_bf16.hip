@@ -1282,6 +1282,13 @@ hipError_t conv(const void* in, int64_t in_ld, bool in_f32, const void* Wp, void
   return hipGetLastError();
 }
 
+// Workgroups of the row-tiled weight-gradient kernels (k_wgrad3, k_wgrad1).  Each ends with a
+// partial of 147 / 196 KB that the sum kernel reads again, and both run beside the data-gradient
+// chain on their own streams, so a quarter of the CUs serves better than all of them: targets of
+// 256 / 128 / 64 / 32 workgroups gave 15.06 / 14.71 / 14.56 / 15.50 ms per step of the
+// DenseNet-161-shaped blocks, and the same order in each block taken alone (56x56 to 7x7).
+constexpr int WG_TARGET = 64;
+
 static int wgrad_tiles(int n, int h, int w, int taps) {
   const Wg3Geom q = wg3_geom(h, w);
   return (taps == 9 && q.ok) ? n * q.tpi : n * ((h * w + 63) / 64);
@@ -1289,19 +1296,19 @@ static int wgrad_tiles(int n, int h, int w, int taps) {
 int wgrad_splits(int n, int cin, int cout, int h, int w, int taps) {
   const int tiles = wgrad_tiles(n, h, w, taps);
   const int gy = (cin + 63) / 64, gz = (cout + 63) / 64;
-  // k_wgrad3 runs one workgroup per compute unit: one round of workgroups, evenly loaded
-  int s = ((taps == 9 && wg3_geom(h, w).ok) ? 256 : 1024) / (gy * gz);
+  // k_wgrad3: about WG_TARGET workgroups in all, evenly loaded
+  int s = ((taps == 9 && wg3_geom(h, w).ok) ? WG_TARGET : 1024) / (gy * gz);
   if (s < 1) s = 1;
   if (s > tiles) s = tiles;
   if (s > 128) s = 128;
   const int tps = (tiles + s - 1) / s;
   return (tiles + tps - 1) / tps;
 }
-// k_wgrad1: 32-pixel tiles of the flattened pixel axis, one round of workgroups
+// k_wgrad1: 32-pixel tiles of the flattened pixel axis, about WG_TARGET workgroups in all
 static int wgrad1_splits(int64_t P, int cin, int cout) {
   const int64_t tiles = (P + 31) / 32;
   const int gy = (cin + WG1_CG - 1) / WG1_CG, gz = (cout + WG1_MG - 1) / WG1_MG;
-  int64_t s = 256 / (gy * gz);
+  int64_t s = WG_TARGET / (gy * gz);
   if (s < 1) s = 1;
   if (s > tiles) s = tiles;
   if (s > 128) s = 128;
