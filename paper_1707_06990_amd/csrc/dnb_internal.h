@@ -179,6 +179,14 @@ hipError_t bn_relu_bwd(const void* x, int64_t x_ld, const void* dact, int64_t d_
                        float* G, int64_t g_ld, int64_t P, int c, const float* gamma, const float* beta,
                        const float* mean, const float* istd, float* dgamma, float* dbeta, float* part,
                        hipStream_t st);
+// its two passes on their own (the element-wise pass also over a channel sub-range)
+hipError_t bn_relu_bwd_reduce(const void* x, int64_t x_ld, const void* dact, int64_t d_ld, int64_t P, int c,
+                              const float* gamma, const float* beta, const float* mean, const float* istd,
+                              float* dgamma, float* dbeta, float* part, hipStream_t st);
+hipError_t bn_relu_bwd_apply(const void* x, int64_t x_ld, const void* dact, int64_t d_ld, void* du_bf, int64_t du_ld,
+                             float* G, int64_t g_ld, int64_t P, int c, const float* gamma, const float* beta,
+                             const float* mean, const float* istd, const float* dgamma, const float* dbeta,
+                             hipStream_t st);
 }  // namespace nhwc
 
 }  // namespace dnb

@@ -1404,12 +1404,10 @@ int bn_bwd_splits(int64_t P, int c) {
 }
 size_t bn_bwd_partial_floats(int64_t P, int c) { return (size_t)c * bn_bwd_splits(P, c) * 2; }
 
-// BN+ReLU backward.  G != null: du is accumulated into the fp32 slab (row stride g_ld); else du
-// is written as bf16 to du_bf (may alias dact).
-hipError_t bn_relu_bwd(const void* x, int64_t x_ld, const void* dact, int64_t d_ld, void* du_bf, int64_t du_ld,
-                       float* G, int64_t g_ld, int64_t P, int c, const float* gamma, const float* beta,
-                       const float* mean, const float* istd, float* dgamma, float* dbeta, float* part,
-                       hipStream_t st) {
+// BN+ReLU backward, reduction pass: dgamma / dbeta over (P, c).
+hipError_t bn_relu_bwd_reduce(const void* x, int64_t x_ld, const void* dact, int64_t d_ld, int64_t P, int c,
+                              const float* gamma, const float* beta, const float* mean, const float* istd,
+                              float* dgamma, float* dbeta, float* part, hipStream_t st) {
   const int S = bn_bwd_splits(P, c), lsh = bn_bwd_lsh(c), L = 1 << lsh;
   const int ppb = (int)((P + S - 1) / S);
   const int gs = (int)((P + ppb - 1) / ppb);
@@ -1417,10 +1415,24 @@ hipError_t bn_relu_bwd(const void* x, int64_t x_ld, const void* dact, int64_t d_
   hipLaunchKernelGGL(k_bn_bwd_partial, grid, dim3(256), 0, st, (const u16*)x, x_ld, (const u16*)dact, d_ld, P, c, ppb,
                      lsh, gamma, beta, mean, istd, part);
   hipLaunchKernelGGL(k_bn_bwd_finalize, dim3((unsigned)((c + 3) / 4)), dim3(256), 0, st, part, c, gs, dgamma, dbeta);
+  return hipGetLastError();
+}
+
+// BN+ReLU backward, element-wise pass over (P, c) with dgamma / dbeta given.  G != null: du is
+// accumulated into the fp32 slab (row stride g_ld); else du is written as bf16 to du_bf (may
+// alias dact).  A channel sub-range of a wider BN is this call with every pointer moved to the
+// range's first channel (a multiple of 8) and `c` its length; `P` is the BN's pixel count.
+hipError_t bn_relu_bwd_apply(const void* x, int64_t x_ld, const void* dact, int64_t d_ld, void* du_bf, int64_t du_ld,
+                             float* G, int64_t g_ld, int64_t P, int c, const float* gamma, const float* beta,
+                             const float* mean, const float* istd, const float* dgamma, const float* dbeta,
+                             hipStream_t st) {
+  if (c <= 0) return hipSuccess;
+  const int S = bn_bwd_splits(P, c), lsh = bn_bwd_lsh(c), L = 1 << lsh;
+  const int ppb = (int)((P + S - 1) / S);
   const float inv_p = 1.0f / (float)P;
   // the element-wise pass wants more, shorter workgroups than the reduction
   const int ppa = (int)min((int64_t)ppb, (int64_t)(256 >> lsh) * 16);
-  const dim3 grida(grid.x, (unsigned)((P + ppa - 1) / ppa));
+  const dim3 grida((unsigned)((c / 8 + L - 1) / L), (unsigned)((P + ppa - 1) / ppa));
   if (G)
     hipLaunchKernelGGL((k_bn_bwd_apply<true>), grida, dim3(256), 0, st, (const u16*)x, x_ld, (const u16*)dact, d_ld,
                        (u16*)nullptr, (int64_t)0, G, g_ld, P, c, ppa, lsh, inv_p, gamma, beta, mean, istd, dgamma, dbeta);
@@ -1429,6 +1441,16 @@ hipError_t bn_relu_bwd(const void* x, int64_t x_ld, const void* dact, int64_t d_
                        (u16*)du_bf, du_ld, (float*)nullptr, (int64_t)0, P, c, ppa, lsh, inv_p, gamma, beta, mean, istd,
                        dgamma, dbeta);
   return hipGetLastError();
+}
+
+// Both passes over the same (P, c).
+hipError_t bn_relu_bwd(const void* x, int64_t x_ld, const void* dact, int64_t d_ld, void* du_bf, int64_t du_ld,
+                       float* G, int64_t g_ld, int64_t P, int c, const float* gamma, const float* beta,
+                       const float* mean, const float* istd, float* dgamma, float* dbeta, float* part,
+                       hipStream_t st) {
+  hipError_t e = bn_relu_bwd_reduce(x, x_ld, dact, d_ld, P, c, gamma, beta, mean, istd, dgamma, dbeta, part, st);
+  if (e != hipSuccess) return e;
+  return bn_relu_bwd_apply(x, x_ld, dact, d_ld, du_bf, du_ld, G, g_ld, P, c, gamma, beta, mean, istd, dgamma, dbeta, st);
 }
 
 }  // namespace nhwc
