@@ -30,9 +30,9 @@ struct dnb_block {
   // such backward call); off, everything runs on the caller's stream
   int concurrency;
   bool streams_ready;
-  hipStream_t sA, sB, sC;
+  hipStream_t sA, sB;
   std::vector<hipEvent_t> ev;                // per layer: main done, db ready, S1/S2 ready, wgrad1 done
-  hipEvent_t ev_start, ev_endA, ev_endB, ev_endC;
+  hipEvent_t ev_start, ev_endA, ev_endB;
   std::vector<hipEvent_t> evc;  // bf16: two more events per layer (BN1 reduction done, slab share done)
   size_t off_pack;                           // packed weights of all layers
   std::vector<size_t> pk;                    // per layer: float offset of its packed weights
@@ -124,19 +124,18 @@ int forward_bf16(dnb_block* b, const void* x0, const float* params, void* yv, ch
 
 // The helper streams and the events of the concurrent backward pass, created on first use
 // (default priority; four events per layer: main chain done, db_l ready, storage 1/2 ready,
-// 1x1 weight gradient done; the bf16 path has a third helper stream and two more events per layer).
+// 1x1 weight gradient done; the bf16 path has two more events per layer and uses one helper stream).
 int ensure_helper_streams(dnb_block* b) {
   if (b->streams_ready) return DNB_OK;
   if (hipStreamCreateWithFlags(&b->sA, hipStreamNonBlocking) != hipSuccess) return DNB_E_LAUNCH;
   if (hipStreamCreateWithFlags(&b->sB, hipStreamNonBlocking) != hipSuccess) return DNB_E_LAUNCH;
-  if (hipStreamCreateWithFlags(&b->sC, hipStreamNonBlocking) != hipSuccess) return DNB_E_LAUNCH;
   b->ev.resize((size_t)4 * (b->d.layers + 2));
   for (auto& e : b->ev)
     if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
   b->evc.resize((size_t)2 * (b->d.layers + 2));
   for (auto& e : b->evc)
     if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
-  if (hipEventCreateWithFlags(&b->ev_endC, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
+
   if (hipEventCreateWithFlags(&b->ev_start, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
   if (hipEventCreateWithFlags(&b->ev_endA, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
   if (hipEventCreateWithFlags(&b->ev_endB, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
@@ -160,24 +159,31 @@ int backward_bf16(dnb_block* b, const float* params, const void* yv, const void*
   unsigned short* dS3 = (unsigned short*)(ws + b->off_dS3);
   const unsigned short* pack = (const unsigned short*)(ws + b->off_pack);
   const size_t B16 = (size_t)((B + 15) & ~15), k16 = (size_t)((k + 15) & ~15), B32 = (size_t)((B + 31) & ~31);
-  // Four chains.  Only the data-gradient chain (dgrad 3x3 -> BN2 bwd -> dgrad 1x1 -> BN1 reduction
+  // Two chains.  Only the data-gradient chain (dgrad 3x3 -> BN2 bwd -> dgrad 1x1 -> BN1 reduction
   // -> BN1 element-wise pass on the k channels of x_{l-1}) carries the dependence from layer l to
   // layer l-1: the next layer down reads nothing of the slab but that slice.  With concurrency on,
-  // the two weight gradients (with their sums) run on helper streams A and B, and the rest of
-  // BN1's element-wise pass (channels below x_{l-1}, the bulk of its traffic) on helper stream C,
-  // ordered by events where buffers are shared: the 3x3 weight gradient needs the slab's slice
-  // g_l complete (layer l+1's share on the main chain), the 1x1 needs db_l in dS3, which the next
-  // layer's 3x3 data gradient overwrites, and chain C reads dS2, which the next layer's 1x1 data
-  // gradient overwrites.  Every slab element still receives its layers' contributions in the
-  // order m, m-1, ...: chain C adds them in stream order and the main chain's share of layer l
-  // waits for chain C's share of layer l+1, so serial and concurrent runs give the same bits.
-  // The slices of the fp32 slab that the chains touch at the same time are disjoint channel ranges.
+  // the two weight gradients (with their sums) and the rest of BN1's element-wise pass (channels
+  // below x_{l-1}, the bulk of its traffic) run on a helper stream, ordered by events where buffers
+  // are shared: the 3x3 weight gradient needs the slab's slice g_l complete (layer l+1's share on
+  // the main chain), the 1x1 needs db_l in dS3, which the next layer's 3x3 data gradient
+  // overwrites, and the helper's share of BN1 reads dS2, which the next layer's 1x1 data gradient
+  // overwrites.  Every slab element still receives its layers' contributions in the order m, m-1,
+  // ...: the helper adds them in stream order and the main chain's share of layer l waits for the
+  // helper's share of layer l+1, so serial and concurrent runs give the same bits.  The slices of
+  // the fp32 slab that the two chains touch at the same time are disjoint channel ranges.
+  //
+  // One helper stream, and at every fork the main chain's launch issued first: a captured graph
+  // keeps the first successor of a node on the node's hardware queue, and a change of queue costs
+  // the main chain about 10 us.  Measured per step of the DenseNet-161-shaped blocks: this order
+  // 13.9 ms; three helper streams with the helpers' launches first 14.4 ms (the main chain then
+  // changes queue twice per layer); three helper streams with the main chain's launches first
+  // 19.9 ms (the graph puts all helpers on one queue in an order that makes the main chain wait).
   const bool conc = b->concurrency != 0;
   if (conc) {
     const int rc = ensure_helper_streams(b);
     if (rc != DNB_OK) return rc;
   }
-  hipStream_t sA = conc ? b->sA : st, sB = conc ? b->sB : st, sC = conc ? b->sC : st;
+  hipStream_t sH = conc ? b->sA : st;
   enum { EV_MAIN = 0, EV_DB = 1, EV_WG1 = 3, EV_RED = 0, EV_REST = 1 };
   auto ev = [&](int l, int which) -> hipEvent_t { return conc ? b->ev[(size_t)4 * l + which] : nullptr; };
   auto evc = [&](int l, int which) -> hipEvent_t { return conc ? b->evc[(size_t)2 * l + which] : nullptr; };
@@ -186,8 +192,7 @@ int backward_bf16(dnb_block* b, const float* params, const void* yv, const void*
 
   DNB_TRY(nhwc::bf16_to_f32(dy, G, P * cout, st));
   DNB_TRY(record(conc ? b->ev_start : nullptr, st));
-  DNB_TRY(wait(sA, conc ? b->ev_start : nullptr));
-  DNB_TRY(wait(sB, conc ? b->ev_start : nullptr));
+  DNB_TRY(wait(sH, conc ? b->ev_start : nullptr));
   for (int l = m; l >= 1; --l) {
     const int c = c_in(d, l);
     const LayerParams p = layer_ptrs<LayerParams, const float>(b, params, l);
@@ -202,55 +207,48 @@ int backward_bf16(dnb_block* b, const float* params, const void* yv, const void*
     const unsigned short* pk3t = pack + b->pk[l] + B16 * c32 + c16 * B32 + 9 * k16 * B32;  // 3x3 data gradient
     const float* gl = G + c;  // gradient of x_l (fp32, pixel stride C_out), complete at this point
 
-    // At each fork the helper chain's launch is issued before the main chain's, and chain C's
-    // after: the order of capture decides which queues a captured graph puts the chains on, and
-    // of the eight orders this one measured fastest (14.3 ms per step of the DenseNet-161-shaped
-    // blocks; the others 14.9 .. 19.9 ms).
-    // ---- chain A: 3x3 weight gradient (BN2+ReLU of b_l recomputed in the operand staging)
-    if (l < m) DNB_TRY(wait(sA, ev(l + 1, EV_MAIN)));
-    DNB_TRY(nhwc::wgrad(bl, B, gl, cout, true, partA, gp.W3, n, B, k, d.h, d.w, 9, fold2, sA));
-
-    // ---- main chain: 3x3 data gradient and BN2 backward; dS3 is still read by layer l+1's 1x1
-    // weight gradient
+    // ---- main chain: 3x3 data gradient; dS3 is still read by layer l+1's 1x1 weight gradient
     if (l < m) DNB_TRY(wait(st, ev(l + 1, EV_WG1)));
     DNB_TRY(nhwc::conv(gl, cout, true, pk3t, dS3, B, n, k, B, d.h, d.w, 9, nullptr, nullptr, nullptr, st));
+
+    // ---- helper: 3x3 weight gradient (BN2+ReLU of b_l recomputed in the operand staging)
+    if (l < m) DNB_TRY(wait(sH, ev(l + 1, EV_MAIN)));
+    DNB_TRY(nhwc::wgrad(bl, B, gl, cout, true, partA, gp.W3, n, B, k, d.h, d.w, 9, fold2, sH));
+
+    // ---- main chain, continued: BN2 backward, then the 1x1 data gradient (dS2 and the slab's
+    // lower channels are the helper's until its share of layer l+1 is done)
     DNB_TRY(nhwc::bn_relu_bwd(bl, B, dS3, B, dS3, B, nullptr, 0, P, B, p.g2, p.b2, mean_b, istd_b, gp.g2, gp.b2,
                               part, st));
     DNB_TRY(record(ev(l, EV_DB), st));
-
-    // ---- chain B: 1x1 weight gradient (BN1+ReLU of y[..., :C_l] recomputed in the operand staging)
-    DNB_TRY(wait(sB, ev(l, EV_DB)));
-    DNB_TRY(nhwc::wgrad(y, cout, dS3, B, false, partB, gp.W1, n, c, B, d.h, d.w, 1, fold1, sB));
-    DNB_TRY(record(ev(l, EV_WG1), sB));
-
-    // ---- main chain, continued: 1x1 data gradient (dS2 and the slab's lower channels are chain
-    // C's until its share of layer l+1 is done), BN1's reduction, and BN1's element-wise pass with
-    // the concat backward (accumulate into the slab) on the k channels of x_{l-1}
     if (l < m) DNB_TRY(wait(st, evc(l + 1, EV_REST)));
     DNB_TRY(nhwc::conv(dS3, B, false, pk1t, dS2, c, n, B, c, d.h, d.w, 1, nullptr, nullptr, nullptr, st));
+
+    // ---- helper: 1x1 weight gradient (BN1+ReLU of y[..., :C_l] recomputed in the operand staging)
+    DNB_TRY(wait(sH, ev(l, EV_DB)));
+    DNB_TRY(nhwc::wgrad(y, cout, dS3, B, false, partB, gp.W1, n, c, B, d.h, d.w, 1, fold1, sH));
+    DNB_TRY(record(ev(l, EV_WG1), sH));
+
+    // ---- main chain, continued: BN1's reduction, and BN1's element-wise pass with the concat
+    // backward (accumulate into the slab) on the k channels of x_{l-1}.  The channels below go to
+    // the helper; layer 1 has only those (x_0); on one stream the pass is one launch.
     DNB_TRY(nhwc::bn_relu_bwd_reduce(y, cout, dS2, c, P, c, p.g1, p.b1, mean_y, istd_y, gp.g1, gp.b1, part, st));
     DNB_TRY(record(evc(l, EV_RED), st));
-    // channels below x_{l-1} go to chain C; layer 1 has only those (x_0); on one stream the pass is one launch
     const int lo = !conc ? 0 : (l >= 2 ? c - k : c);
     if (lo < c)
       DNB_TRY(nhwc::bn_relu_bwd_apply(y + lo, cout, dS2 + lo, c, nullptr, 0, G + lo, cout, P, c - lo, p.g1 + lo,
                                       p.b1 + lo, mean_y + lo, istd_y + lo, gp.g1 + lo, gp.b1 + lo, st));
     DNB_TRY(record(ev(l, EV_MAIN), st));
 
-    // ---- chain C: the same pass on the channels below
-    DNB_TRY(wait(sC, evc(l, EV_RED)));
+    // ---- helper: the same pass on the channels below
+    DNB_TRY(wait(sH, evc(l, EV_RED)));
     if (lo > 0)
       DNB_TRY(nhwc::bn_relu_bwd_apply(y, cout, dS2, c, nullptr, 0, G, cout, P, lo, p.g1, p.b1, mean_y, istd_y, gp.g1,
-                                      gp.b1, sC));
-    DNB_TRY(record(evc(l, EV_REST), sC));
+                                      gp.b1, sH));
+    DNB_TRY(record(evc(l, EV_REST), sH));
   }
-  if (conc) {  // join: the caller's stream is done only when the helper chains are
-    DNB_TRY(hipEventRecord(b->ev_endA, sA));
-    DNB_TRY(hipEventRecord(b->ev_endB, sB));
-    DNB_TRY(hipEventRecord(b->ev_endC, sC));
+  if (conc) {  // join: the caller's stream is done only when the helper chain is
+    DNB_TRY(hipEventRecord(b->ev_endA, sH));
     DNB_TRY(hipStreamWaitEvent(st, b->ev_endA, 0));
-    DNB_TRY(hipStreamWaitEvent(st, b->ev_endB, 0));
-    DNB_TRY(hipStreamWaitEvent(st, b->ev_endC, 0));
   }
   DNB_TRY(nhwc::f32_rows_to_bf16(G, cout, dx0, P, d.c0, st));
   return DNB_OK;
@@ -517,10 +515,8 @@ void dnb_block_destroy(dnb_block* b) {
     (void)hipEventDestroy(b->ev_start);
     (void)hipEventDestroy(b->ev_endA);
     (void)hipEventDestroy(b->ev_endB);
-    (void)hipEventDestroy(b->ev_endC);
     (void)hipStreamDestroy(b->sA);
     (void)hipStreamDestroy(b->sB);
-    (void)hipStreamDestroy(b->sC);
   }
   delete b;
 }

@@ -1284,10 +1284,12 @@ hipError_t conv(const void* in, int64_t in_ld, bool in_f32, const void* Wp, void
 
 // Workgroups of the row-tiled weight-gradient kernels (k_wgrad3, k_wgrad1).  Each ends with a
 // partial of 147 / 196 KB that the sum kernel reads again, and both run beside the data-gradient
-// chain on their own streams, so a quarter of the CUs serves better than all of them: targets of
-// 256 / 128 / 64 / 32 workgroups gave 15.06 / 14.71 / 14.56 / 15.50 ms per step of the
-// DenseNet-161-shaped blocks, and the same order in each block taken alone (56x56 to 7x7).
-constexpr int WG_TARGET = 64;
+// chain on a helper stream, so a part of the CUs serves better than all of them.  Per step of
+// the DenseNet-161-shaped blocks, with three helper streams: targets of 256 / 128 / 64 / 32
+// workgroups gave 15.06 / 14.71 / 14.56 / 15.50 ms (the same order in each block taken alone,
+// 56x56 to 7x7); with the one helper stream now used: 64 / 96 / 128 / 192 / 256 gave 14.83 /
+// 13.87 / 13.90 / 14.19 / 14.40 ms.
+constexpr int WG_TARGET = 96;
 
 static int wgrad_tiles(int n, int h, int w, int taps) {
   const Wg3Geom q = wg3_geom(h, w);
