@@ -1257,7 +1257,9 @@ hipError_t conv(const void* in, int64_t in_ld, bool in_f32, const void* Wp, void
   if (lds > 64 * 1024 || (taps == 9 && (64 + 2 * halo) * 8 > 8 * 256)) return hipErrorInvalidValue;
   if ((fold != nullptr) != (spart != nullptr) && fold) return hipErrorInvalidValue;
   // eight chunks or more, and about one workgroup per compute unit (with several, their phases
-  // already cover one another's latencies and the ring's extra loads only cost)
+  // already cover one another's latencies and the ring's extra loads only cost).  (Chunks of 128
+  // channels instead of 64 in this form -- half the barriers, 171-218 registers -- were slower:
+  // 13.9 -> 14.3 ms per step of the DenseNet-161-shaped blocks.)
   const bool ring = taps == 1 && cin >= 512 && ptiles * gy <= 320;
 #define DNB_K(TAPS, MT, TIN, PRO, STATS, RING)                                                                  \
   hipLaunchKernelGGL((k_conv<TAPS, MT, TIN, PRO, STATS, RING>), grid, dim3(256), lds, st, (const TIN*)in, in_ld, \
