@@ -1100,24 +1100,26 @@ __global__ __launch_bounds__(256) void k_wgrad3x3_fast(Wg3Args A, SumRole sr, in
 }
 
 // One launch for the two weight gradients of a layer (they are independent of each other and of
-// everything that follows them): a 1-D grid whose first n3 workgroups are the 3x3's, the next n1
-// the 1x1's, the rest the two pending sums.
+// everything that follows them): a 1-D grid whose first n1 workgroups are the 1x1's (few and long,
+// so they start first: 41.9 -> 38.4 us per launch on the first dense block of DenseNet-BC-100
+// against the 3x3's first), the next n3 the 3x3's, then the BN backward reduction carried along
+// (before the 3x3's it measured slower, after the sums the same), then the two pending sums.
 template <int M1, int C1, int M3, int C3, bool PRO>
 __global__ __launch_bounds__(256) void k_wgrad_pair(Wg1Args A1, int gy1, int gz1, int n1, Wg3Args A3, int gy3, int gz3,
                                                     int n3, SumRole s1, SumRole s3, BnBwdPartialArgs bn, int nbn) {
   int id = blockIdx.x;
-  if (id < n3) {
-    const int bz = id % gz3, by = (id / gz3) % gy3, bx = id / (gz3 * gy3);
-    wgrad3x3_body<M3, C3, PRO>(A3, bx, by, bz, gy3, gz3);
-    return;
-  }
-  id -= n3;
   if (id < n1) {
     const int bz = id % gz1, by = (id / gz1) % gy1, bx = id / (gz1 * gy1);
     wgrad1x1_body<M1, C1, PRO>(A1, bx, by, bz);
     return;
   }
   id -= n1;
+  if (id < n3) {
+    const int bz = id % gz3, by = (id / gz3) % gy3, bx = id / (gz3 * gy3);
+    wgrad3x3_body<M3, C3, PRO>(A3, bx, by, bz, gy3, gz3);
+    return;
+  }
+  id -= n3;
   if (id < nbn) {  // a BN+ReLU backward reduction of the main chain carried along
     bn_bwd_partial_body4(bn, id / bn.splits, id % bn.splits);
     return;
