@@ -189,7 +189,7 @@ DOMINANT_KERNEL = "k_wgrad_pair<3, 4, 1, 3, true>"
 # HBM bytes per launch of that kernel (average over the launches timed below) from the two
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by the copy kernel of known size),
 # summarised in profiles/; valid for that workload only.
-MEASURED_TRAFFIC = {"config2:64": 188200000}   # profiles/bc100_b64_fp32_wgrad_pair_hbm_traffic.txt
+MEASURED_TRAFFIC = {"config2:64": 190400000}   # profiles/bc100_b64_fp32_wgrad_pair_hbm_traffic.txt
 HBM_PEAK_GBS = 8000.0
 
 
