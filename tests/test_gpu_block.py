@@ -190,8 +190,8 @@ def full_size_grad_close(a, r, what, elementwise=False):
 @pytest.mark.parametrize("i", [0, 1, 2])
 def test_full_size_benchmark_blocks_match_oracle(dnb, oracle, i):
     """The benchmark workload at its full size (DenseNet-BC L=100, k=12, batch 64; the three dense
-    blocks of 16 layers) in the configuration the benchmark times -- fused schedule, weight-gradient
-    chains on helper streams -- against the oracle's memory-efficient schedule: the output to the
+    blocks of 16 layers) in the configuration the benchmark times -- fused schedule, the library's
+    default stream order -- against the oracle's memory-efficient schedule: the output to the
     strict bound, every gradient to the mask-flip-tolerant one, the byte count exactly."""
     cfg = wl.config2(64)[i]
     x0, lp, dy = wl.make_block_inputs(cfg, 10 + i, 20 + i, 30 + i, affine="random")
@@ -199,6 +199,28 @@ def test_full_size_benchmark_blocks_match_oracle(dnb, oracle, i):
     ores, osl = run_block_oracle(oracle, cfg, x0, lp, dy, schedule="shared")
     assert_close(gpu["y"], ores.y, TOL, "y")
     full_size_grad_close(gpu["dx0"], ores.dx0, "dx0", elementwise=True)
+    for l in range(1, cfg.layers + 1):
+        for name in NAMES:
+            full_size_grad_close(gpu["dparams"][gpu["slices"][(l, name)]], ores.dparams[osl[(l, name)]], f"layer {l} d{name}")
+    assert gpu["peak"] == ores.peak_elems * 4 - (2 * cfg.c_in(cfg.layers) + cfg.bottleneck) * cfg.pixels * 4
+
+
+@pytest.mark.parametrize("i", [0, 1, 2])
+def test_bc250_blocks_at_reduced_batch_match_oracle(dnb, oracle, i):
+    """The dense blocks of DenseNet-BC L=250, k=24 (41 layers each, 48 -> 1032, 516 -> 1500 and
+    750 -> 1734 channels, B = 96) with every kernel shape of the full workload except the pixel
+    count: batch 4 instead of 64, which the oracle finishes in seconds.  Fused schedule, default
+    stream order; the output to the strict bound, gradients to the mask-flip-tolerant L2 / worst
+    element bounds of the full-size DenseNet-BC-100 blocks.  Their third criterion (at most 2 % of
+    dx0's elements further than 1e-4 of the largest) does not carry over to 41 layers: the float64
+    oracle itself moves 2.4 % of them that far (rel L2 4.6e-4) when its input is perturbed by 6e-8
+    relative noise once, and fp32 rounds in every layer."""
+    cfg = wl.config3(4)[i]
+    x0, lp, dy = wl.make_block_inputs(cfg, 40 + i, 50 + i, 60 + i, affine="random")
+    gpu = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=2)
+    ores, osl = run_block_oracle(oracle, cfg, x0, lp, dy, schedule="shared")
+    assert_close(gpu["y"], ores.y, TOL, "y")
+    full_size_grad_close(gpu["dx0"], ores.dx0, "dx0")
     for l in range(1, cfg.layers + 1):
         for name in NAMES:
             full_size_grad_close(gpu["dparams"][gpu["slices"][(l, name)]], ores.dparams[osl[(l, name)]], f"layer {l} d{name}")
