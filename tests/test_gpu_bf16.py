@@ -34,6 +34,7 @@ CFGS = [
     wl.BlockCfg(1, 24, 7, 7, 2, 8, 32),        # 49 pixels: less than one tile, odd width
     wl.BlockCfg(2, 96, 28, 28, 2, 48, 192),    # DenseNet-161 widths (k = 48, B = 192)
     wl.BlockCfg(3, 64, 12, 20, 2, 32, 128),    # DenseNet-264 widths (k = 32, B = 128), non-square
+    wl.BlockCfg(1, 96, 56, 56, 2, 48, 192),    # the first DenseNet-161 block's image size (row tiles of 5 rows, the last ragged)
 ]
 IDS = [f"n{c.n}c{c.c0}h{c.h}w{c.w}m{c.layers}k{c.growth}B{c.bottleneck}" for c in CFGS]
 
@@ -175,7 +176,10 @@ OP_SHAPES = [(2, 16, 8, 8, 8, 1), (2, 32, 8, 8, 8, 3), (2, 8, 32, 8, 8, 3), (1, 
              (1, 64, 576, 6, 6, 1),
              # 3x3 weight gradient: two row tiles per image and two channel groups; then more tiles than
              # splits (two tiles per workgroup)
-             (5, 72, 16, 14, 14, 3), (130, 8, 8, 4, 4, 3)]
+             (5, 72, 16, 14, 14, 3), (130, 8, 8, 4, 4, 3),
+             # 56-pixel rows as in the first ImageNet-shaped block: the 3x3's halo is 57 pixels a side, the weight
+             # gradient's row tiles hold 5 rows and the last one 1
+             (1, 64, 48, 56, 56, 3), (1, 32, 128, 56, 56, 3)]
 
 
 @pytest.mark.parametrize("n,cin,cout,h,w,ks", OP_SHAPES)
