@@ -99,6 +99,50 @@ def test_bf16_backward_chains_on_helper_streams_give_the_same_bits(dnb, cfg):
         assert np.array_equal(a[key], b[key]), key
 
 
+def test_bf16_hip_graph_replays_match_eager(dnb):
+    """The bf16 block's forward and backward captured in a HIP graph with the library's default
+    stream order (the backward forks onto its helper stream and joins again), as bench.py times
+    it: every replay, with eager work and synchronisation in between, reproduces the eager bits."""
+    cfg = CFGS[3]
+    x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
+    x0, dy = to_bf16_values(x0), to_bf16_values(dy)
+    eager = run_block_gpu_bf16(dnb, cfg, x0, lp, dy)
+    h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck,
+                             dtype=dnb.DNB_BF16, layout=dnb.DNB_NHWC, schedule=dnb.DNB_SCHED_FUSED, eps=cfg.eps)
+    params = dev(pack_params_gpu(dnb, h, lp))
+    ws = torch.zeros(dnb.dnb_block_workspace_bytes(h), dtype=torch.uint8, device="cuda")
+    nhwc = lambda a: torch.from_numpy(np.ascontiguousarray(a)).permute(0, 2, 3, 1).contiguous().to("cuda", torch.bfloat16)
+    back = lambda t: t.float().permute(0, 3, 1, 2).contiguous().cpu().numpy()
+    x0d, dyd = nhwc(x0), nhwc(dy)
+    y = torch.zeros((cfg.n, cfg.h, cfg.w, cfg.c_out), dtype=torch.bfloat16, device="cuda")
+    dx0 = torch.zeros((cfg.n, cfg.h, cfg.w, cfg.c0), dtype=torch.bfloat16, device="cuda")
+    dparams = torch.zeros_like(params)
+
+    def step():
+        dnb.dnb_block_forward(h, x0d, params, y, ws)
+        dnb.dnb_block_backward(h, params, y, dyd, dx0, dparams, ws)
+
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        step()
+    torch.cuda.current_stream().wait_stream(s)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep in range(4):
+        y.fill_(float("nan")); dx0.fill_(float("nan")); dparams.fill_(float("nan")); ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(back(y), eager["y"]), rep
+        assert np.array_equal(back(dx0), eager["dx0"]), rep
+        assert np.array_equal(dparams.cpu().numpy(), eager["dparams"]), rep
+        _ = (torch.randn(1000, device="cuda") * 2).sum().item()  # unrelated eager work between replays
+    dnb.dnb_block_destroy(h)
+
+
 @pytest.mark.parametrize("which", ["config4", "config5"])
 def test_bf16_full_size_last_block(dnb, oracle, which):
     """The last dense block of the DenseNet-161- and -264-shaped workloads exactly as bench.py

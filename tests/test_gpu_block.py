@@ -133,14 +133,19 @@ def test_output_starts_with_input_and_first_bn_is_normalised(dnb):
     np.testing.assert_allclose(xhat.var(axis=(0, 2, 3)), v / (v + cfg.eps), rtol=1e-4)
 
 
-def test_hip_graph_replays_match_eager(dnb):
-    """The block's launch sequence captured in a HIP graph (as the benchmark does): every
-    replay, with eager work and synchronisation in between, reproduces the eager bits."""
+@pytest.mark.parametrize("schedule,concurrency", [(0, None), (2, None), (2, True), (0, True)],
+                         ids=["shared", "fused", "fused-helper-stream", "shared-helper-streams"])
+def test_hip_graph_replays_match_eager(dnb, schedule, concurrency):
+    """The block's launch sequence captured in a HIP graph (as the benchmark does; with the helper
+    streams on the capture forks and joins): every replay, with eager work and synchronisation
+    in between, reproduces the eager bits."""
     from gpu_util import dev, pack_params_gpu
     cfg = CFGS[4]
     x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
-    eager = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=0)
-    h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck, schedule=0)
+    eager = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=schedule)
+    h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck, schedule=schedule)
+    if concurrency is not None:
+        dnb.dnb_block_set_concurrency(h, concurrency)
     params = dev(pack_params_gpu(dnb, h, lp))
     ws = torch.zeros(dnb.dnb_block_workspace_bytes(h), dtype=torch.uint8, device="cuda")
     y = torch.zeros((cfg.n, cfg.c_out, cfg.h, cfg.w), device="cuda")
