@@ -125,20 +125,37 @@ int forward_bf16(dnb_block* b, const void* x0, const float* params, void* yv, ch
 // The helper streams and the events of the concurrent backward pass, created on first use
 // (default priority; four events per layer: main chain done, db_l ready, storage 1/2 ready,
 // 1x1 weight gradient done; the bf16 path has two more events per layer and uses one helper stream).
+// Destroys whatever of the helper streams and events exists (handles are null until created).
+void release_helper_streams(dnb_block* b) {
+  for (hipEvent_t e : b->ev) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : b->evc) if (e) (void)hipEventDestroy(e);
+  b->ev.clear();
+  b->evc.clear();
+  for (hipEvent_t* e : {&b->ev_start, &b->ev_endA, &b->ev_endB}) {
+    if (*e) (void)hipEventDestroy(*e);
+    *e = nullptr;
+  }
+  for (hipStream_t* s : {&b->sA, &b->sB}) {
+    if (*s) (void)hipStreamDestroy(*s);
+    *s = nullptr;
+  }
+  b->streams_ready = false;
+}
+
 int ensure_helper_streams(dnb_block* b) {
   if (b->streams_ready) return DNB_OK;
-  if (hipStreamCreateWithFlags(&b->sA, hipStreamNonBlocking) != hipSuccess) return DNB_E_LAUNCH;
-  if (hipStreamCreateWithFlags(&b->sB, hipStreamNonBlocking) != hipSuccess) return DNB_E_LAUNCH;
-  b->ev.resize((size_t)4 * (b->d.layers + 2));
-  for (auto& e : b->ev)
-    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
-  b->evc.resize((size_t)2 * (b->d.layers + 2));
-  for (auto& e : b->evc)
-    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
-
-  if (hipEventCreateWithFlags(&b->ev_start, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
-  if (hipEventCreateWithFlags(&b->ev_endA, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
-  if (hipEventCreateWithFlags(&b->ev_endB, hipEventDisableTiming) != hipSuccess) return DNB_E_LAUNCH;
+  bool ok = hipStreamCreateWithFlags(&b->sA, hipStreamNonBlocking) == hipSuccess &&
+            hipStreamCreateWithFlags(&b->sB, hipStreamNonBlocking) == hipSuccess;
+  b->ev.assign((size_t)4 * (b->d.layers + 2), nullptr);
+  b->evc.assign((size_t)2 * (b->d.layers + 2), nullptr);
+  for (auto& e : b->ev) ok = ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
+  for (auto& e : b->evc) ok = ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
+  for (hipEvent_t* e : {&b->ev_start, &b->ev_endA, &b->ev_endB})
+    ok = ok && hipEventCreateWithFlags(e, hipEventDisableTiming) == hipSuccess;
+  if (!ok) {  // nothing half-made is kept: the next call starts over
+    release_helper_streams(b);
+    return DNB_E_LAUNCH;
+  }
   b->streams_ready = true;
   return DNB_OK;
 }
@@ -502,6 +519,8 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
   // bf16 step, whose helper chains carry long kernels, a fifth faster
   b->concurrency = d.dtype == DNB_BF16 ? 1 : 0;
   b->streams_ready = false;
+  b->sA = b->sB = nullptr;
+  b->ev_start = b->ev_endA = b->ev_endB = nullptr;
   mem.workspace_bytes = (uint64_t)off;
   *out = b;
   return DNB_OK;
@@ -509,15 +528,7 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
 
 void dnb_block_destroy(dnb_block* b) {
   if (!b) return;
-  if (b->streams_ready) {
-    for (hipEvent_t e : b->ev) (void)hipEventDestroy(e);
-    for (hipEvent_t e : b->evc) (void)hipEventDestroy(e);
-    (void)hipEventDestroy(b->ev_start);
-    (void)hipEventDestroy(b->ev_endA);
-    (void)hipEventDestroy(b->ev_endB);
-    (void)hipStreamDestroy(b->sA);
-    (void)hipStreamDestroy(b->sB);
-  }
+  release_helper_streams(b);
   delete b;
 }
 
