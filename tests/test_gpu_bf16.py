@@ -251,6 +251,42 @@ def test_nhwc_conv_ops(dnb, oracle, n, cin, cout, h, w, ks, g_f32):
     assert_close(dw.cpu().numpy(), oracle.conv_wgrad(x, g, ks), 1e-2, "wgrad")
 
 
+@pytest.mark.parametrize("ks", [1, 3])
+def test_nhwc_conv_ops_on_channel_slices_of_wider_slabs(dnb, oracle, ks):
+    """Pixel strides wider than the channel ranges, as the block addresses its slabs in place: the
+    input is channels 16..47 of a 64-channel tensor, the output channels 8..31 of a 40-channel one
+    (an fp32 one for the data gradient's operand); everything outside the output range stays
+    untouched."""
+    n, cin, cout, h, w = 2, 32, 24, 9, 8
+    r = np.random.default_rng(11)
+    xs = to_bf16_values(r.standard_normal((n, 64, h, w)).astype(np.float32))
+    gs = to_bf16_values(r.standard_normal((n, 40, h, w)).astype(np.float32))
+    wgt = to_bf16_values((r.standard_normal((cout, cin, ks, ks)) * np.sqrt(2.0 / (cin * ks * ks))).astype(np.float32))
+    x, g = xs[:, 16:48], gs[:, 8:32]
+    scratch = torch.empty(dnb.dnb_op_nhwc_scratch_bytes(n, cin, cout, h, w, ks), dtype=torch.uint8, device="cuda")
+    d_w, d_xs, d_gs, d_gs32 = dev(wgt), nhwc_bf16(xs), nhwc_bf16(gs), nhwc_f32(gs)
+    sentinel = 7.0
+    out = torch.full((n, h, w, 40), sentinel, dtype=torch.bfloat16, device="cuda")
+    dnb.dnb_op_nhwc_conv_forward(d_xs.data_ptr() + 16 * 2, 64, d_w, out.data_ptr() + 8 * 2, 40, n, cin, cout, h, w, ks, scratch)
+    torch.cuda.synchronize()
+    o = back(out)
+    assert_close(o[:, 8:32], oracle.conv_forward(x, wgt), 1e-2, "forward")
+    assert np.all(o[:, :8] == sentinel) and np.all(o[:, 32:] == sentinel)
+    for g_f32, d_g, esz in ((0, d_gs, 2), (1, d_gs32, 4)):
+        din = torch.full((n, h, w, 64), sentinel, dtype=torch.bfloat16, device="cuda")
+        dnb.dnb_op_nhwc_conv_dgrad(d_g.data_ptr() + 8 * esz, 40, g_f32, d_w, din.data_ptr() + 16 * 2, 64, n, cin, cout, h, w, ks,
+                                   scratch)
+        torch.cuda.synchronize()
+        di = back(din)
+        assert_close(di[:, 16:48], oracle.conv_dgrad(g, wgt), 1e-2, "dgrad")
+        assert np.all(di[:, :16] == sentinel) and np.all(di[:, 48:] == sentinel)
+        dw = torch.full(wgt.shape, float("nan"), device="cuda")
+        dnb.dnb_op_nhwc_conv_wgrad(d_xs.data_ptr() + 16 * 2, 64, d_g.data_ptr() + 8 * esz, 40, g_f32, dw, n, cin, cout, h, w, ks,
+                                   scratch)
+        torch.cuda.synchronize()
+        assert_close(dw.cpu().numpy(), oracle.conv_wgrad(x, g, ks), 1e-2, "wgrad")
+
+
 @pytest.mark.parametrize("g_f32", [0, 1])
 def test_nhwc_wgrad_rows_wider_than_the_row_tiled_kernel_takes(dnb, oracle, g_f32):
     """96-pixel rows: the 3x3 weight gradient falls back to the kernel that stages 64-pixel tiles
