@@ -143,6 +143,23 @@ def test_bf16_hip_graph_replays_match_eager(dnb):
     dnb.dnb_block_destroy(h)
 
 
+@pytest.mark.parametrize("which,i", [("config4", 0), ("config4", 2), ("config5", 1)])
+def test_bf16_backward_is_exactly_linear_in_dy_at_full_size(dnb, which, i):
+    """Doubling dy doubles dx0 and every parameter gradient bit for bit (each step of the backward
+    pass is linear in dy, and a factor of 2 commutes with every rounding, bf16 included).  Needs no
+    oracle, so it runs at the full size bench.py times: the 56x56 and 14x14 blocks of the
+    DenseNet-161 shape and the 28x28 block of the DenseNet-264 shape, batch 32."""
+    cfg = (wl.config4() if which == "config4" else wl.config5())[i]
+    x0, lp, dy = wl.make_block_inputs(cfg, 80, 81, 82, affine="random")
+    x0, dy = to_bf16_values(x0), to_bf16_values(dy)
+    a = run_block_gpu_bf16(dnb, cfg, x0, lp, dy)
+    b = run_block_gpu_bf16(dnb, cfg, x0, lp, 2.0 * dy)
+    assert np.array_equal(a["y"], b["y"])
+    assert np.isfinite(a["dx0"]).all() and np.isfinite(a["dparams"]).all()
+    assert np.array_equal(2.0 * a["dx0"], b["dx0"])
+    assert np.array_equal(2.0 * a["dparams"], b["dparams"])
+
+
 @pytest.mark.parametrize("which", ["config4", "config5"])
 def test_bf16_full_size_last_block(dnb, oracle, which):
     """The last dense block of the DenseNet-161- and -264-shaped workloads exactly as bench.py

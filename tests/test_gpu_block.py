@@ -232,6 +232,23 @@ def test_bc250_blocks_at_reduced_batch_match_oracle(dnb, oracle, i):
     assert gpu["peak"] == ores.peak_elems * 4 - (2 * cfg.c_in(cfg.layers) + cfg.bottleneck) * cfg.pixels * 4
 
 
+@pytest.mark.parametrize("which", ["config2", "config3"])
+def test_backward_is_exactly_linear_in_dy_at_full_size(dnb, which):
+    """A property that needs no oracle and holds at any size: every step of the backward pass is
+    linear in dy and a factor of 2 is exact in floating point, so doubling dy doubles dx0 and every
+    parameter gradient bit for bit.  Checked on the first dense block of the two CIFAR-shaped
+    workloads at their full batch of 64 (16 layers at k = 12, 41 layers at k = 24), in the
+    configuration bench.py times; the forward output must not move."""
+    cfg = (wl.config2(64) if which == "config2" else wl.config3(64))[0]
+    x0, lp, dy = wl.make_block_inputs(cfg, 70, 71, 72, affine="random")
+    a = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=2)
+    b = run_block_gpu(dnb, cfg, x0, lp, 2.0 * dy, schedule=2)
+    assert np.array_equal(a["y"], b["y"])
+    assert np.isfinite(a["dx0"]).all() and np.isfinite(a["dparams"]).all()
+    assert np.array_equal(2.0 * a["dx0"], b["dx0"])
+    assert np.array_equal(2.0 * a["dparams"], b["dparams"])
+
+
 # ------------------------------------------------------------------ layers without a bottleneck
 
 NOBOTTLE = [
