@@ -1394,14 +1394,17 @@ static WgFastPlan plan_wgrad_fast(int n, int cin, int cout, int h, int w, int ta
     p.gz = (mtiles + p.mtw - 1) / p.mtw;
     p.spi = (hw + 15) / 16;
     p.total_steps = n * p.spi;
-    // About 128 workgroups in all, 1..16 steps per wave.  A workgroup ends with a cross-wave sum
+    // About 128 workgroups in all, 1..16 (or 64) steps per wave.  A workgroup ends with a cross-wave sum
     // and a partial of mtw*ctw tiles to store, and every partial is read again by the sum that
     // follows, so few long workgroups beat many short ones even when they leave CUs to the other
     // roles of the launch: a target of 512 workgroups (1..8 steps) took 3.3 % more time per
     // DenseNet-BC-100 step than 128; 96 and 192 were within 0.5 % of 128.
+    // With many (m, c) tile columns (wide layers, k = 24 nets) the columns alone fill the chip and the
+    // pixel ranges can be longer still: a cap of 64 steps there took 1.2 % off the DenseNet-BC-250 step.
     int spw = (int)(((int64_t)p.total_steps * p.gy * p.gz + 4 * 128 - 1) / (4 * 128));
+    const int cap = p.gy * p.gz > 8 ? 64 : 16;
     if (spw < 1) spw = 1;
-    if (spw > 16) spw = 16;
+    if (spw > cap) spw = cap;
     p.steps_per_wg = 4 * spw;
     p.gx = (p.total_steps + p.steps_per_wg - 1) / p.steps_per_wg;
     p.lds = (size_t)4 * p.mtw * p.ctw * 256 * sizeof(float);
