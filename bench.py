@@ -21,7 +21,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 MFMA_F32_PEAK_TF = 157.3    # MI355X dense fp32 matrix
@@ -71,7 +70,7 @@ class BlockRun:
     """Device buffers + handle of one dense block."""
 
     def __init__(self, dnb, torch, wl, cfg, schedule, seed, bf16=False):
-        from gpu_util import dev, pack_params_gpu
+        from harness import dev, pack_params_gpu
         self.cfg = cfg
         kw = dict(dtype=dnb.DNB_BF16, layout=dnb.DNB_NHWC) if bf16 else {}
         self.h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck,
@@ -96,7 +95,7 @@ class NetRun:
 
     def __init__(self, dnb, torch, wl, ncfg, schedule):
         import numpy as np
-        from gpu_util import dev
+        from harness import dev
         self.cfg = ncfg
         self.h = dnb.dnb_net_create(ncfg.n, ncfg.image, ncfg.depth, ncfg.growth, ncfg.classes, schedule=schedule,
                                     eps=ncfg.eps)
@@ -111,7 +110,7 @@ class NetRun:
         put(dnb.DNB_NP_STEM, params["stem"])
         for b, bc in enumerate(ncfg.blocks()):
             hb = dnb.dnb_block_create(bc.n, bc.c0, bc.h, bc.w, bc.layers, bc.growth, bc.bottleneck, eps=bc.eps)
-            from gpu_util import pack_params_gpu
+            from harness import pack_params_gpu
             put(dnb.DNB_NP_BLOCK0 + b, pack_params_gpu(dnb, hb, params[f"block{b}"]))
             dnb.dnb_block_destroy(hb)
         for b in (0, 1):
@@ -261,7 +260,7 @@ def cpu_baseline(wl, blocks):
     """The oracle as it stands, on the host cores, same workload shapes (full batch when it
     finishes in tens of seconds, else a bounded number of images: cost per image is
     batch independent for its naive loops)."""
-    from gpu_util import run_block_oracle
+    from harness import run_block_oracle
     from oracle import oracle as orc
     batch = blocks[0].n
     flops_per_img = sum(6 * c.h * c.w * sum(c.c_in(l) * c.bottleneck + 9 * c.bottleneck * c.growth
@@ -288,7 +287,7 @@ def cpu_baseline_net(wl, ncfg):
     """The oracle's whole training step on the host cores, on a bounded number of images of the
     same network (its cost per image does not depend on the batch)."""
     from oracle import oracle as orc
-    from test_oracle_net import pack_net
+    from harness import pack_net
     sample = min(ncfg.n, 16)
     cs = wl.NetCfg(sample, ncfg.image, ncfg.depth, ncfg.growth, ncfg.classes, ncfg.eps)
     x, labels, params = wl.make_net_inputs(cs)

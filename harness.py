@@ -1,0 +1,129 @@
+"""Harness helpers shared by the tests, bench.py and the smoke check: marshal numpy inputs to device
+tensors, pack named parameter tensors into the flat packs of the library and of the oracle, call
+the C ABI through the binding, bring results back, compare.  No arithmetic of the method here."""
+import numpy as np
+import torch
+
+import workloads as wl
+
+NAMES = wl.PARAM_NAMES
+
+
+def rel_errors(a, r):
+    """(L2 relative error, max-abs error relative to max |r|) of a against reference r."""
+    a = np.asarray(a, dtype=np.float64).ravel()
+    r = np.asarray(r, dtype=np.float64).ravel()
+    den2 = np.linalg.norm(r)
+    denm = np.max(np.abs(r)) if r.size else 0.0
+    l2 = np.linalg.norm(a - r) / den2 if den2 > 0 else np.linalg.norm(a - r)
+    mx = np.max(np.abs(a - r)) / denm if denm > 0 else (np.max(np.abs(a - r)) if r.size else 0.0)
+    return float(l2), float(mx)
+
+
+def assert_close(a, r, tol, what=""):
+    l2, mx = rel_errors(a, r)
+    assert l2 <= tol and mx <= tol, f"{what}: rel L2 {l2:.3e}, rel max {mx:.3e} > {tol:g}"
+
+
+def dev(a, dtype=torch.float32):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(device="cuda", dtype=dtype)
+
+
+def pack_params_gpu(dnb, handle, layer_params):
+    flat = np.zeros(dnb.dnb_block_param_count(handle), dtype=np.float32)
+    for l, p in enumerate(layer_params, start=1):
+        for name, arr in p.items():
+            off, cnt = dnb.dnb_block_param_offset(handle, l, NAMES.index(name))
+            assert cnt == arr.size
+            flat[off:off + cnt] = arr.ravel()
+    return flat
+
+
+def pack_params_oracle(orc, shape, layer_params):
+    flat = np.zeros(orc.param_count(shape))
+    for l, p in enumerate(layer_params, start=1):
+        for name, arr in p.items():
+            flat[orc.param_slice(shape, l, NAMES.index(name))] = np.asarray(arr, dtype=np.float64).ravel()
+    return flat
+
+
+def run_block_gpu(dnb, cfg, x0, layer_params, dy, schedule=0, poison=True, concurrency=None):
+    """Forward + backward of one block through the C ABI.  Returns dict of numpy arrays.
+    concurrency=None keeps the library's default (what bench.py times)."""
+    h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck,
+                             schedule=schedule, eps=cfg.eps)
+    try:
+        if concurrency is not None:
+            dnb.dnb_block_set_concurrency(h, concurrency)
+        params = dev(pack_params_gpu(dnb, h, layer_params))
+        ws_bytes = dnb.dnb_block_workspace_bytes(h)
+        ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+        y = torch.empty((cfg.n, cfg.c_out, cfg.h, cfg.w), dtype=torch.float32, device="cuda")
+        dx0 = torch.empty((cfg.n, cfg.c0, cfg.h, cfg.w), dtype=torch.float32, device="cuda")
+        dparams = torch.empty_like(params)
+        if poison:  # stale contents must never leak into results
+            ws.fill_(0xFF)
+            y.fill_(float("nan"))
+            dx0.fill_(float("nan"))
+            dparams.fill_(float("nan"))
+        x0d, dyd = dev(x0), dev(dy)
+        dnb.dnb_block_forward(h, x0d, params, y, ws)
+        dnb.dnb_block_backward(h, params, y, dyd, dx0, dparams, ws)
+        torch.cuda.synchronize()
+        out = {"y": y.cpu().numpy(), "dx0": dx0.cpu().numpy(), "dparams": dparams.cpu().numpy(),
+               "mem": dnb.dnb_block_memory_breakdown(h), "peak": dnb.dnb_block_peak_bytes(h)}
+        out["slices"] = {(l, name): slice(*(lambda o, c: (o, o + c))(*dnb.dnb_block_param_offset(h, l, NAMES.index(name))))
+                         for l in range(1, cfg.layers + 1) for name in NAMES if name in layer_params[0]}
+        return out
+    finally:
+        dnb.dnb_block_destroy(h)
+
+
+def run_block_oracle(orc, cfg, x0, layer_params, dy, schedule="naive"):
+    s = orc.BlockShape(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck, cfg.eps)
+    params = pack_params_oracle(orc, s, layer_params)
+    res = orc.block(s, x0.astype(np.float64), params, dy.astype(np.float64), schedule=schedule)
+    slices = {(l, name): orc.param_slice(s, l, NAMES.index(name))
+              for l in range(1, cfg.layers + 1) for name in NAMES if name in layer_params[0]}
+    return res, slices
+
+
+def pack_net(orc, s, params):
+    """Named tensors of workloads.make_net_inputs -> the oracle's flat network pack."""
+    flat = np.zeros(orc.net_param_count(s))
+    sl = orc.net_param_slices(s)
+    flat[sl["stem"]] = params["stem"].ravel()
+    for b in range(3):
+        bs = s.block(b)
+        blk = np.zeros(orc.param_count(bs))
+        for l, p in enumerate(params[f"block{b}"], start=1):
+            for name, arr in p.items():
+                blk[orc.param_slice(bs, l, NAMES.index(name))] = arr.ravel()
+        flat[sl[f"block{b}"]] = blk
+        pre = f"trans{b}" if b < 2 else "tail"
+        for name, arr in params[pre].items():
+            flat[sl[f"{pre}.{name}"]] = arr.ravel()
+    return flat
+
+
+def run_net_gpu(dnb, oracle, cfg, x, labels, params, schedule, concurrency=None):
+    s = oracle.NetShape(cfg.n, cfg.image, cfg.depth, cfg.growth, cfg.classes, cfg.eps)
+    flat = pack_net(oracle, s, params)   # the two packs have the same layout (checked by the host tests)
+    net = dnb.dnb_net_create(cfg.n, cfg.image, cfg.depth, cfg.growth, cfg.classes, schedule=schedule, eps=cfg.eps)
+    try:
+        if concurrency is not None:   # None: the library's default, what bench.py times
+            dnb.dnb_net_set_concurrency(net, concurrency)
+        p = dev(flat.astype(np.float32))
+        dp = torch.full_like(p, float("nan"))
+        ws = torch.empty(dnb.dnb_net_workspace_bytes(net), dtype=torch.uint8, device="cuda")
+        ws.fill_(0xFF)
+        xd = dev(x)
+        lab = torch.from_numpy(labels).to("cuda")
+        loss = torch.full((1,), float("nan"), device="cuda")
+        logits = torch.full((cfg.n, cfg.classes), float("nan"), device="cuda")
+        dnb.dnb_net_forward(net, xd, lab, p, loss, logits, ws)
+        dnb.dnb_net_backward(net, xd, p, dp, ws)
+        torch.cuda.synchronize()
+        return s, flat, float(loss.item()), logits.cpu().numpy(), dp.cpu().numpy()
+    finally:
+        dnb.dnb_net_destroy(net)

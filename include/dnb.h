@@ -97,23 +97,37 @@ typedef struct {
                                  the workspace, plus alignment padding                          */
 } dnb_block_memory;
 
-/* Validates the descriptor and builds the host-side plan (buffer offsets, launch
- * shapes).  Host memory only.  *out is set on success. */
+/* A dense block as Section 4 sets it up: one object owns the plan of the block-wide shared
+ * storages (storage 1 for the concatenated features, storage 2 for their BN+ReLU output, the
+ * third one for the bottleneck's BN+ReLU output, the shared gradient storage) and of the
+ * convolution outputs that persist, for the layer shapes of Section 2 (m layers, growth k,
+ * optional bottleneck B).  dnb_block_create validates the descriptor and builds that plan
+ * (buffer offsets inside the caller's workspace, launch shapes) in host memory only; shapes
+ * whose LDS tiles or launch plans are not built fail here (DNB_E_UNSUPPORTED), not at launch.
+ * *out is set on success.  dnb_block_destroy frees the host object (and the helper streams a
+ * concurrent backward created); the workspace stays the caller's. */
 int dnb_block_create(const dnb_block_desc* desc, dnb_block** out);
 void dnb_block_destroy(dnb_block* b);
 
 /* Feature-map bytes the block needs at its peak (formula above; Section 4/5:
  * linear in m for DNB_SCHED_SHARED, quadratic for DNB_SCHED_STORE_ALL). */
 size_t dnb_block_peak_bytes(const dnb_block* b);
-/* Size of the single device workspace the caller passes to forward/backward. */
+/* Size of the single device workspace the caller passes to forward/backward: the feature maps
+ * of dnb_block_peak_bytes that do not live in y, plus cached BN statistics (Section 4: only the
+ * apply is recomputed) and reduction scratch. */
 size_t dnb_block_workspace_bytes(const dnb_block* b);
+/* The terms of the byte formula above one by one (Section 5 compares exactly these: what is
+ * stored against what is shared). */
 int dnb_block_memory_breakdown(const dnb_block* b, dnb_block_memory* out);
 
-/* Parameter pack: fp32, per layer l = 1..m in order
+/* Parameter pack (the parameters of the composite function H_l, Section 2: BN scale and bias,
+ * the 1x1 bottleneck weights, second BN, the 3x3 weights): fp32 for both storage types, per
+ * layer l = 1..m in order
  *   g1[C_l] b1[C_l] W1[B][C_l] g2[B] b2[B] W3[k][B][3][3]
- * (first BN scale/bias, 1x1 weights, second BN scale/bias, 3x3 weights, OIHW).
- * `dparams` has the identical layout.  Offsets and counts are in elements. */
+ * (OIHW).  `dparams` has the identical layout.  Offsets and counts are in elements;
+ * dnb_block_param_bytes = 4 * dnb_block_param_count is what the caller allocates for each. */
 size_t dnb_block_param_count(const dnb_block* b);
+size_t dnb_block_param_bytes(const dnb_block* b);
 int dnb_block_param_offset(const dnb_block* b, int layer /*1-based*/, int which /*DNB_P_* */,
                            size_t* offset, size_t* count);
 
@@ -139,7 +153,8 @@ int dnb_block_forward(dnb_block* b, const void* x0, const void* params, void* y,
 int dnb_block_backward(dnb_block* b, const void* params, const void* y, const void* dy, void* dx0,
                        void* dparams, void* workspace, void* stream);
 
-/* The backward pass can run its two weight-gradient chains on helper streams owned by the block
+/* Section 4's "regular back-propagation" after re-population leaves the order of independent
+ * kernels open: the backward pass can run its two weight-gradient chains on helper streams owned by the block
  * (created at the first such backward call, joined to `stream` before the call's last kernel),
  * so that they overlap the data-gradient chain.  enable = 0 puts everything on `stream` in
  * program order; results are bit-identical either way.  Default: disabled for fp32 (measured
@@ -276,7 +291,8 @@ int dnb_op_nhwc_bn_relu_backward(const void* x, int64_t x_ld, const void* dact, 
  *   stem W[2k][3][3][3] | block0 | trans0: g[C] b[C] W[C/2][C] | block1 | trans1 | block2 |
  *   tail: g[C] b[C] Wl[classes][C] bl[classes]
  * (query the offsets).  x is (n, 3, image, image) fp32, labels n int32 in [0, classes): device
- * pointers.  loss (1 float) and logits (n*classes floats, may be NULL) are device pointers too.
+ * pointers (a sample whose label is out of range adds nothing to the loss or the gradients).
+ * loss (1 float) and logits (n*classes floats, may be NULL) are device pointers too.
  * dnb_net_backward needs the preceding dnb_net_forward on the same workspace and overwrites
  * dparams.  Errors and ownership as for the block calls. */
 typedef struct dnb_net dnb_net;
@@ -301,6 +317,11 @@ int dnb_net_param_offset(const dnb_net* net, int part /*DNB_NP_* */, size_t* off
 size_t dnb_net_workspace_bytes(const dnb_net* net);  /* bytes the caller allocates */
 /* feature-map bytes of the whole step: the blocks' exact accounting plus the glue's feature maps */
 size_t dnb_net_peak_bytes(const dnb_net* net);
+/* The i-th piece carved from the workspace (i = 0, 1, ... until DNB_E_RANGE): its name ("feat",
+ * "y", "block_ws", "tz", "mean", "istd", "pack": one per block `index`; "tconv", "gy", "dtz",
+ * "dconv", "dfeat", "part", "pooled", "dpooled", "logits", "dlogits", "terms": shared by all
+ * blocks), byte offset and size.  Host only; lets a caller or a test check the plan. */
+int dnb_net_workspace_piece(const dnb_net* net, int i, const char** name, int* index, size_t* offset, size_t* bytes);
 int dnb_net_set_concurrency(dnb_net* net, int enable); /* helper streams in the blocks' backward */
 int dnb_net_forward(dnb_net* net, const void* x, const int32_t* labels, const void* params, float* loss,
                     float* logits, void* workspace, void* stream);

@@ -55,6 +55,7 @@ _SIGS = {
     "dnb_block_workspace_bytes": (_sz, [_vp]),
     "dnb_block_memory_breakdown": (C.c_int, [_vp, C.POINTER(dnb_block_memory)]),
     "dnb_block_param_count": (_sz, [_vp]),
+    "dnb_block_param_bytes": (_sz, [_vp]),
     "dnb_block_param_offset": (C.c_int, [_vp, C.c_int, C.c_int, C.POINTER(_sz), C.POINTER(_sz)]),
     "dnb_block_forward": (C.c_int, [_vp] * 6),
     "dnb_block_backward": (C.c_int, [_vp] * 8),
@@ -92,6 +93,8 @@ _SIGS = {
     "dnb_net_param_count": (_sz, [_vp]),
     "dnb_net_param_offset": (C.c_int, [_vp, C.c_int, C.POINTER(_sz), C.POINTER(_sz)]),
     "dnb_net_workspace_bytes": (_sz, [_vp]),
+    "dnb_net_workspace_piece": (C.c_int, [_vp, C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_int), C.POINTER(_sz),
+                                          C.POINTER(_sz)]),
     "dnb_net_peak_bytes": (_sz, [_vp]),
     "dnb_net_set_concurrency": (C.c_int, [_vp, C.c_int]),
     "dnb_net_forward": (C.c_int, [_vp] * 8),
@@ -164,6 +167,10 @@ def dnb_block_memory_breakdown(b) -> dict:
 
 def dnb_block_param_count(b) -> int:
     return int(_lib.dnb_block_param_count(b))
+
+
+def dnb_block_param_bytes(b) -> int:
+    return int(_lib.dnb_block_param_bytes(b))
 
 
 def dnb_block_param_offset(b, layer: int, which: int):
@@ -341,6 +348,16 @@ def dnb_net_param_offset(net, part: int):
 
 def dnb_net_workspace_bytes(net) -> int:
     return int(_lib.dnb_net_workspace_bytes(net))
+
+
+def dnb_net_workspace_piece(net, i: int):
+    """(name, block index, byte offset, bytes) of the i-th carved piece, or None past the last."""
+    name, idx, off, nb = C.c_char_p(), C.c_int(), _sz(), _sz()
+    rc = _lib.dnb_net_workspace_piece(net, i, C.byref(name), C.byref(idx), C.byref(off), C.byref(nb))
+    if rc == DNB_E_RANGE:
+        return None
+    _check(rc)
+    return name.value.decode(), int(idx.value), int(off.value), int(nb.value)
 
 
 def dnb_net_peak_bytes(net) -> int:

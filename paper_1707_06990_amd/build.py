@@ -13,10 +13,6 @@ SOURCES = ["dnb_elem.hip", "dnb_conv_f32.hip", "dnb_conv_f32_fast.hip", "dnb_nhw
 # Packed-fp32 instruction selection is switched off for all device code on this target.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
-if os.environ.get("DNB_V4_WGS"):
-    FLAGS.append("-DDNB_V4_WGS=" + os.environ["DNB_V4_WGS"])
-if os.environ.get("DNB_DBG"):  # kernel ablation builds for tuning experiments
-    FLAGS.append("-DDNB_DBG=" + os.environ["DNB_DBG"])
 
 
 def build(verbose: bool = False) -> str:

@@ -6,7 +6,7 @@
 
 #include "../../include/dnb.h"
 #include "dnb_internal.h"
-#include "dnb_stats.cuh"
+#include "dnb_stats.h"
 
 using namespace dnb;
 
@@ -548,6 +548,7 @@ int dnb_block_memory_breakdown(const dnb_block* b, dnb_block_memory* out) {
 }
 
 size_t dnb_block_param_count(const dnb_block* b) { return b ? b->pcount : 0; }
+size_t dnb_block_param_bytes(const dnb_block* b) { return b ? b->pcount * sizeof(float) : 0; }
 
 int dnb_block_param_offset(const dnb_block* b, int layer, int which, size_t* offset, size_t* count) {
   if (!b || !offset || !count) return DNB_E_NULL;

@@ -11,7 +11,7 @@
 // split over pixel ranges across workgroups; partial results go to scratch and a second kernel
 // adds them in a fixed order (no float atomics: results are reproducible run to run).
 #include "dnb_internal.h"
-#include "dnb_stats.cuh"
+#include "dnb_stats.h"
 
 namespace dnb {
 

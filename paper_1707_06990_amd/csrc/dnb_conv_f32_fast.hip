@@ -28,22 +28,15 @@
 //     operand, 236 registers) changed nothing.
 //   * BN-backward sums computed in the data-gradient convs' epilogues (to drop the separate
 //     reduction launch) made those convs 6-15 us slower, more than the launch they saved.
-#ifndef DNB_V4_WGS
-#define DNB_V4_WGS 512  // workgroups of the persistent 3x3 kernel (two per CU)
-#endif
-#ifndef DNB_DBG
-#define DNB_DBG 0  // kernel ablation builds for tuning experiments (1x1: 1 no MFMA, 2/4 no activation / weight loads;
-                   // 3x3: 8 no MFMA, 16/32 no activation / weight loads, 64 no statistics epilogue,
-                   // 128 no output stores, 256 no K-split reduction, 512 no LDS operand reads, 1024 no staging;
-                   // (the 3x3 wgrad hooks 2048 / 4096 / 8192 went with its pixel-split version))
-#endif
+constexpr int kV4Workgroups = 512;  // workgroups of the persistent 3x3 kernel (two per CU)
+static_assert(kV4Workgroups % 8 == 0, "tiles are dealt to workgroups per XCD (8 of them)");
 
 #include "dnb_internal.h"
 #include <hip/hip_ext.h>
 
 #include <type_traits>
 
-#include "dnb_stats.cuh"
+#include "dnb_stats.h"
 
 namespace dnb {
 
@@ -267,10 +260,7 @@ __global__ __launch_bounds__(256) void k_conv1x1_v3(
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int ch = min(ch0 + 4 * ks + g, cin - 1);
-      if (DNB_DBG & 2) {
-#pragma unroll
-        for (int t = 0; t < PPL; ++t) v[ks][t] = 1.f;
-      } else if (PPL == 4) {
+      if (PPL == 4) {
         const float4 t = ldg4(inq + (int64_t)ch * HW);
         v[ks][0] = t.x; v[ks][1 % PPL] = t.y; v[ks][2 % PPL] = t.z; v[ks][3 % PPL] = t.w;
       } else {
@@ -282,7 +272,7 @@ __global__ __launch_bounds__(256) void k_conv1x1_v3(
     for (int a = 0; a < MT; ++a) {
       // M-tiles past the padded output-channel count read tile 0's rows; they are never stored
       const int row = (mbase + a * 16 < M16) ? mbase + a * 16 + j : j;
-      w4[a] = (DNB_DBG & 4) ? make_float4(1.f, 1.f, 1.f, 1.f) : ldg4(Wp + (int64_t)row * Kpad + 4 * g + ch0);
+      w4[a] = ldg4(Wp + (int64_t)row * Kpad + 4 * g + ch0);
     }
   };
 
@@ -303,8 +293,7 @@ __global__ __launch_bounds__(256) void k_conv1x1_v3(
             const float wa = elem(wbuf[d][a], ks) * keep[d];
 #pragma unroll
             for (int t = 0; t < PPL; ++t) {
-              if (DNB_DBG & 1) acc[a][t][(ks + t) & 3] += wa * bv[t];
-              else acc[a][t] = mfma16(wa, bv[t], acc[a][t]);
+              acc[a][t] = mfma16(wa, bv[t], acc[a][t]);
             }
           }
         }
@@ -382,7 +371,7 @@ __global__ __launch_bounds__(256) void k_conv3x3_v3(
   const int rows = (cin + 3) & ~3;  // staged channel rows (tail rows zero)
   const int total = rows * seg4;
   constexpr int U = 8;
-  for (int base = 0; base < ((DNB_DBG & 1024) ? 0 : total); base += nthr * U) {
+  for (int base = 0; base < total; base += nthr * U) {
     float4 v[U];
     float2 f[U];
 #pragma unroll
@@ -390,7 +379,7 @@ __global__ __launch_bounds__(256) void k_conv3x3_v3(
       const int idx = base + u * nthr + tid;
       const int row = min(idx / seg4, cin - 1);
       const int qq = origin + 4 * (idx % seg4);
-      v[u] = (DNB_DBG & 16) ? make_float4(1.f, 1.f, 1.f, 1.f) : ldg4(inb + (int64_t)row * HW + min(max(qq, 0), HW - 4));
+      v[u] = ldg4(inb + (int64_t)row * HW + min(max(qq, 0), HW - 4));
       if (PRO) f[u] = fold[row];
     }
 #pragma unroll
@@ -425,8 +414,7 @@ __global__ __launch_bounds__(256) void k_conv3x3_v3(
       for (int t = 0; t < 9; ++t)
 #pragma unroll
         for (int a = 0; a < MT; ++a)
-          w4[t][a] = (DNB_DBG & 32) ? make_float4(1.f, 1.f, 1.f, 1.f)
-                     : (mbase + a * 16 < Mpad)
+          w4[t][a] = (mbase + a * 16 < Mpad)
                          ? ldg4(Wp + ((int64_t)t * Mpad + mbase + a * 16 + j) * Kpad + c0 + 4 * g)
                          : zero4();
 #pragma unroll
@@ -438,13 +426,9 @@ __global__ __launch_bounds__(256) void k_conv3x3_v3(
         for (int ks = 0; ks < 4; ++ks) {
           if (ks < nks) {
             const float* rowp = &lds[(c0 + 4 * ks + g) * CS + base];
-            if (DNB_DBG & 512) {
-              V[ks] = make_float4(1.f, 2.f, 3.f, 4.f); eL[ks] = 0.5f; eR[ks] = 1.5f;
-            } else {
-              V[ks] = *reinterpret_cast<const float4*>(rowp);
-              eL[ks] = maskL ? 0.f : rowp[-1];
-              eR[ks] = maskR ? 0.f : rowp[4];
-            }
+            V[ks] = *reinterpret_cast<const float4*>(rowp);
+            eL[ks] = maskL ? 0.f : rowp[-1];
+            eR[ks] = maskR ? 0.f : rowp[4];
           } else {
             V[ks] = zero4(); eL[ks] = 0.f; eR[ks] = 0.f;
           }
@@ -462,14 +446,10 @@ __global__ __launch_bounds__(256) void k_conv3x3_v3(
 #pragma unroll
               for (int a = 0; a < MT; ++a) {
                 const float wa = elem(w4[t][a], ks);
-                if (DNB_DBG & 8) {
-                  acc[a][0][ks] += wa * b0; acc[a][1][ks] += wa * b1; acc[a][2][ks] += wa * b2; acc[a][3][ks] += wa * b3;
-                } else {
-                  acc[a][0] = mfma16(wa, b0, acc[a][0]);
-                  acc[a][1] = mfma16(wa, b1, acc[a][1]);
-                  acc[a][2] = mfma16(wa, b2, acc[a][2]);
-                  acc[a][3] = mfma16(wa, b3, acc[a][3]);
-                }
+                acc[a][0] = mfma16(wa, b0, acc[a][0]);
+                acc[a][1] = mfma16(wa, b1, acc[a][1]);
+                acc[a][2] = mfma16(wa, b2, acc[a][2]);
+                acc[a][3] = mfma16(wa, b3, acc[a][3]);
               }
             }
           }
@@ -478,17 +458,17 @@ __global__ __launch_bounds__(256) void k_conv3x3_v3(
     }
   }
 
-  if (KSPLIT && !(DNB_DBG & 256)) ksplit_reduce<MT, 4>(acc, lds, wave, lane, nw);  // reuses the tile's LDS (barrier inside)
+  if (KSPLIT) ksplit_reduce<MT, 4>(acc, lds, wave, lane, nw);  // reuses the tile's LDS (barrier inside)
 
   const int tile_px = min(64, HW - q0);
 #pragma unroll
   for (int a = 0; a < MT; ++a) {
     if (KSPLIT && a % nw != wave) continue;
     if (mbase + a * 16 >= Mpad) continue;
-    if (STATS && !(DNB_DBG & 64))
+    if (STATS)
       tile_stats<4>(acc[a], q < HW, (float)tile_px, mbase + a * 16, cout, spart, sT,
                     img * gridDim.x + blockIdx.x);
-    if (q < HW && (!(DNB_DBG & 128) || acc[a][0][0] == 12345.f)) {
+    if (q < HW) {
       float* ob = out + (int64_t)img * out_stride + q;
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
@@ -569,8 +549,7 @@ __global__ __launch_bounds__(256) void k_conv3x3_v4(
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int y = min(max(y0 - 1 + sry[u], 0), H - 1);
-      v[u] = (DNB_DBG & 16) ? make_float4(1.f, 1.f, 1.f, 1.f)
-                            : ldg4(inb + (int64_t)min(sch[u], cin - 1) * HW + y * W + sgo[u]);
+      v[u] = ldg4(inb + (int64_t)min(sch[u], cin - 1) * HW + y * W + sgo[u]);
     }
   };
   auto deposit = [&](int tl, const float4(&v)[U], int boff) {
@@ -635,11 +614,10 @@ __global__ __launch_bounds__(256) void k_conv3x3_v4(
           const int t = (di + 1) * 3 + (dj + 1);
 #pragma unroll
           for (int ks = 0; ks < 4; ++ks) {
-            const float b = (DNB_DBG & 512) ? 1.5f : lds[boff + lane_base + (ci * 16 + 4 * ks) * CS + di * RW + dj];
+            const float b = lds[boff + lane_base + (ci * 16 + 4 * ks) * CS + di * RW + dj];
 #pragma unroll
             for (int a = 0; a < MT; ++a) {
-              if (DNB_DBG & 8) acc[a][ks & 1][ks] += elem(w4[t][ci][a], ks) * b;
-              else acc[a][ks & 1] = mfma16(elem(w4[t][ci][a], ks), b, acc[a][ks & 1]);
+              acc[a][ks & 1] = mfma16(elem(w4[t][ci][a], ks), b, acc[a][ks & 1]);
             }
           }
         }
@@ -654,7 +632,7 @@ __global__ __launch_bounds__(256) void k_conv3x3_v4(
       float v[4];
 #pragma unroll
       for (int r = 0; r < 4; ++r) v[r] = acc[a][0][r] + acc[a][1][r];
-      if (STATS && !(DNB_DBG & 64)) {
+      if (STATS) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           float s = v[r];
@@ -1322,7 +1300,7 @@ bool launch_conv_fast(const float* in, int64_t in_stride, const float* packed, f
   if ((fwd13 || dg31) && (w == 8 || w == 16 || w == 32) && hw % 64 == 0) {
     // persistent kernel: weights in registers, pixel-split waves, double-buffered tiles
     const int tpi = hw / 64, total_tiles = tpi * n;
-    int G = total_tiles < DNB_V4_WGS ? (total_tiles + 7) / 8 * 8 : DNB_V4_WGS;
+    int G = total_tiles < kV4Workgroups ? (total_tiles + 7) / 8 * 8 : kV4Workgroups;
     const size_t lds = ((size_t)2 * (nchunks * 16 * 144 + 4) + 2 * 4 * mtiles * 16 * 3) * sizeof(float);
     if (sT) *sT = total_tiles;
 #define DNB_L4(MT, NCH, WW, PRO, STATS)                                                                  \

@@ -7,7 +7,7 @@
 #include <hip/hip_ext.h>
 
 #include "dnb_internal.h"
-#include "dnb_stats.cuh"
+#include "dnb_stats.h"
 
 namespace dnb {
 
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(kThreads) void k_copy_slab(const float* __restrict_
 // ----------------------------------------------------------------------------- row iteration
 
 // A workgroup of the BN kernels below owns ONE channel and a range of images: its elements are
-// (RowIter, which walks rows of hw contiguous floats, one per image, is in dnb_stats.cuh)
+// (RowIter, which walks rows of hw contiguous floats, one per image, is in dnb_stats.h)
 
 // ----------------------------------------------------------------------------- BN statistics
 
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kThreads) void k_bn_bwd_partial(
     int64_t dact_stride, int n, int hw, int ipb, const float* __restrict__ gamma,
     const float* __restrict__ beta, const float* __restrict__ mean, const float* __restrict__ istd,
     float* __restrict__ part) {
-  if (V == 4) {  // the vector form lives in dnb_stats.cuh: the weight-gradient launch can carry it too
+  if (V == 4) {  // the vector form lives in dnb_stats.h: the weight-gradient launch can carry it too
     const BnBwdPartialArgs A{x, x_stride, dact, dact_stride, n, hw, ipb, gamma, beta, mean, istd, part,
                              (int)gridDim.x, (int)gridDim.y};
     bn_bwd_partial_body4(A, blockIdx.x, blockIdx.y);

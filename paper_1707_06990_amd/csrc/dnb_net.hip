@@ -97,9 +97,10 @@ __global__ __launch_bounds__(kT) void k_softmax_xent(const float* __restrict__ l
     for (int o = 0; o < classes; ++o) se += expf(z[o] - mx);
     const float lse = mx + logf(se);
     const int lab = labels[i];
-    terms[i] = lse - z[lab];
+    const bool valid = lab >= 0 && lab < classes;  // a sample with a label out of range adds nothing
+    terms[i] = valid ? lse - z[lab] : 0.f;
     for (int o = 0; o < classes; ++o)
-      dlogits[(int64_t)i * classes + o] = (expf(z[o] - lse) - (o == lab ? 1.f : 0.f)) / (float)n;
+      dlogits[(int64_t)i * classes + o] = valid ? (expf(z[o] - lse) - (o == lab ? 1.f : 0.f)) / (float)n : 0.f;
   }
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -174,6 +175,8 @@ struct dnb_net {
   size_t o_tconv, o_gy, o_dtz, o_dconv, o_dfeat, o_part, o_pack[2];
   size_t o_pooled, o_logits, o_dlogits, o_terms, o_dpooled;
   size_t ws_bytes, glue_feature_bytes;
+  struct Piece { const char* name; int index; size_t offset, bytes; };
+  std::vector<Piece> layout;  // every carved piece of the workspace, in carve order
 };
 
 extern "C" {
@@ -218,29 +221,30 @@ int dnb_net_create(const dnb_net_desc* desc, dnb_net** out) {
 
   // ---- workspace plan
   size_t off = 0, glue = 0;
-  auto carve = [&](size_t bytes, bool feature_map) {
+  auto carve = [&](size_t bytes, bool feature_map, const char* name, int index = 0) {
     const size_t o = off;
     off = align_up(off + bytes, 256);
     if (feature_map) glue += bytes;
+    net->layout.push_back(dnb_net::Piece{name, index, o, bytes});
     return o;
   };
   size_t part = 0, pmax = 0;
   for (int b = 0; b < 3; ++b) {
     const dnb_block_desc& bd = net->bd[b];
     const size_t hw = (size_t)bd.h * bd.w, P = hw * d.n, co = (size_t)net->cout[b];
-    net->o_feat[b] = carve((size_t)bd.c0 * P * 4, true);
-    net->o_y[b] = carve(co * P * 4, true);
-    net->o_ws[b] = carve(dnb_block_workspace_bytes(net->blk[b]), false);
-    net->o_tz[b] = carve(co * P * 4, true);
-    net->o_mean[b] = carve(co * 4, false);
-    net->o_istd[b] = carve(co * 4, false);
+    net->o_feat[b] = carve((size_t)bd.c0 * P * 4, true, "feat", b);
+    net->o_y[b] = carve(co * P * 4, true, "y", b);
+    net->o_ws[b] = carve(dnb_block_workspace_bytes(net->blk[b]), false, "block_ws", b);
+    net->o_tz[b] = carve(co * P * 4, true, "tz", b);
+    net->o_mean[b] = carve(co * 4, false, "mean", b);
+    net->o_istd[b] = carve(co * 4, false, "istd", b);
     if (co * P > pmax) pmax = co * P;
     auto need = [&](size_t f) { if (f > part) part = f; };
     need(bn_stats_partial_floats(d.n, (int)co, (int)hw));
     need(bn_bwd_partial_floats(d.n, (int)co, (int)hw));
     if (b < 2) {
       need(conv_wgrad_partial_floats(d.n, (int)co, (int)(co / 2), bd.h, bd.w, 1));
-      net->o_pack[b] = carve(packed_weight_floats((int)(co / 2), (int)co, 1) * 4 * 2, false);  // forward + transposed
+      net->o_pack[b] = carve(packed_weight_floats((int)(co / 2), (int)co, 1) * 4 * 2, false, "pack", b);  // forward + transposed
     }
   }
   {
@@ -248,19 +252,27 @@ int dnb_net_create(const dnb_net_desc* desc, dnb_net** out) {
     size_t f = conv_wgrad_partial_floats(d.n, 3, 2 * k, (int)S, (int)S, 9);
     if (f > part) part = f;
   }
-  const size_t P0 = (size_t)d.n * d.image * d.image;
-  net->o_tconv = carve((size_t)(net->cout[0] / 2) * P0 * 4, true);  // 1x1 output before pooling (largest: transition 0)
-  net->o_gy = carve(pmax * 4, true);                                // gradient of a block output
-  net->o_dtz = carve(pmax * 4, true);                               // gradient of a transition's BN+ReLU output
-  net->o_dconv = carve((size_t)(net->cout[0] / 2) * P0 * 4, true);  // gradient of a transition's conv output
-  net->o_dfeat = carve((size_t)net->bd[0].c0 * P0 * 4, true);       // gradient of a block input (largest: block 0)
-  net->o_part = carve(part * 4, false);
+  // Buffers reused by every block / transition are sized for their largest user, computed (not
+  // assumed): with more than 14 layers per block the input of block 1 is larger than that of block 0.
+  size_t conv_max = 0, feat_max = 0;
+  for (int b = 0; b < 3; ++b) {
+    const dnb_block_desc& bd = net->bd[b];
+    const size_t P = (size_t)d.n * bd.h * bd.w;
+    if ((size_t)bd.c0 * P > feat_max) feat_max = (size_t)bd.c0 * P;
+    if (b < 2 && (size_t)(net->cout[b] / 2) * P > conv_max) conv_max = (size_t)(net->cout[b] / 2) * P;
+  }
+  net->o_tconv = carve(conv_max * 4, true, "tconv");  // a transition's 1x1 output before pooling
+  net->o_gy = carve(pmax * 4, true, "gy");         // gradient of a block output
+  net->o_dtz = carve(pmax * 4, true, "dtz");        // gradient of a transition's BN+ReLU output
+  net->o_dconv = carve(conv_max * 4, true, "dconv");  // gradient of a transition's conv output
+  net->o_dfeat = carve(feat_max * 4, true, "dfeat");  // gradient of a block input
+  net->o_part = carve(part * 4, false, "part");
   const size_t C = (size_t)net->cout[2];
-  net->o_pooled = carve((size_t)d.n * C * 4, false);
-  net->o_dpooled = carve((size_t)d.n * C * 4, false);
-  net->o_logits = carve((size_t)d.n * d.classes * 4, false);
-  net->o_dlogits = carve((size_t)d.n * d.classes * 4, false);
-  net->o_terms = carve((size_t)d.n * 4, false);
+  net->o_pooled = carve((size_t)d.n * C * 4, false, "pooled");
+  net->o_dpooled = carve((size_t)d.n * C * 4, false, "dpooled");
+  net->o_logits = carve((size_t)d.n * d.classes * 4, false, "logits");
+  net->o_dlogits = carve((size_t)d.n * d.classes * 4, false, "dlogits");
+  net->o_terms = carve((size_t)d.n * 4, false, "terms");
   net->ws_bytes = off;
   net->glue_feature_bytes = glue;
   *out = net;
@@ -275,6 +287,14 @@ void dnb_net_destroy(dnb_net* net) {
 }
 
 size_t dnb_net_param_count(const dnb_net* net) { return net ? net->p_count : 0; }
+
+int dnb_net_workspace_piece(const dnb_net* net, int i, const char** name, int* index, size_t* offset, size_t* bytes) {
+  if (!net || !name || !index || !offset || !bytes) return DNB_E_NULL;
+  if (i < 0 || (size_t)i >= net->layout.size()) return DNB_E_RANGE;
+  const dnb_net::Piece& p = net->layout[(size_t)i];
+  *name = p.name; *index = p.index; *offset = p.offset; *bytes = p.bytes;
+  return DNB_OK;
+}
 size_t dnb_net_workspace_bytes(const dnb_net* net) { return net ? net->ws_bytes : 0; }
 
 size_t dnb_net_peak_bytes(const dnb_net* net) {

@@ -12,17 +12,12 @@
 // the slow axis, so both operands are transposed on their way into LDS ([channel][pixel]); the
 // 3x3 stages a row tile once and reads its nine taps as shifted fragments.
 #include "dnb_internal.h"
-#include "dnb_stats.cuh"
+#include "dnb_stats.h"
 
 namespace dnb {
 namespace nhwc {
 
 namespace {
-
-#ifndef DNB_DBG
-#define DNB_DBG 0  // kernel ablation builds for tuning experiments (1x1 conv loop: 0x10000 no MFMA, 0x20000 no deposit,
-                   // 0x40000 no weight loads, 0x80000 no activation loads)
-#endif
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -381,10 +376,10 @@ __global__ __launch_bounds__(256) void k_conv(
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
         const int c0 = cb + s * KC, cn = min(c0 + 4 * KC, clast);
-        if (c0 < cin && !(DNB_DBG & 0x10000)) mm(c0, 0, (s & 1) * BUFE, wt[s]);
-        if (!(DNB_DBG & 0x40000)) wload(cn, 0, wt[s]);
-        if (!(DNB_DBG & 0x80000)) request(cn, r[s]);
-        if (!(DNB_DBG & 0x20000)) deposit(min(c0 + KC, clast), r[(s + 1) & 3], ((s & 1) ^ 1) * BUFE);
+        if (c0 < cin) mm(c0, 0, (s & 1) * BUFE, wt[s]);
+        wload(cn, 0, wt[s]);
+        request(cn, r[s]);
+        deposit(min(c0 + KC, clast), r[(s + 1) & 3], ((s & 1) ^ 1) * BUFE);
         __syncthreads();
       }
     }

@@ -7,33 +7,10 @@ import torch
 import workloads as wl
 from gpu_util import assert_close, dev, rel_errors
 from test_host_api import NET_PARTS
-from test_oracle_net import pack_net
+from harness import pack_net, run_net_gpu  # noqa: F401
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-4
-
-
-def run_net_gpu(dnb, oracle, cfg, x, labels, params, schedule, concurrency=None):
-    s = oracle.NetShape(cfg.n, cfg.image, cfg.depth, cfg.growth, cfg.classes, cfg.eps)
-    flat = pack_net(oracle, s, params)   # the two packs have the same layout (checked by the host tests)
-    net = dnb.dnb_net_create(cfg.n, cfg.image, cfg.depth, cfg.growth, cfg.classes, schedule=schedule, eps=cfg.eps)
-    try:
-        if concurrency is not None:   # None: the library's default, what bench.py times
-            dnb.dnb_net_set_concurrency(net, concurrency)
-        p = dev(flat.astype(np.float32))
-        dp = torch.full_like(p, float("nan"))
-        ws = torch.empty(dnb.dnb_net_workspace_bytes(net), dtype=torch.uint8, device="cuda")
-        ws.fill_(0xFF)
-        xd = dev(x)
-        lab = torch.from_numpy(labels).to("cuda")
-        loss = torch.full((1,), float("nan"), device="cuda")
-        logits = torch.full((cfg.n, cfg.classes), float("nan"), device="cuda")
-        dnb.dnb_net_forward(net, xd, lab, p, loss, logits, ws)
-        dnb.dnb_net_backward(net, xd, p, dp, ws)
-        torch.cuda.synchronize()
-        return s, flat, float(loss.item()), logits.cpu().numpy(), dp.cpu().numpy()
-    finally:
-        dnb.dnb_net_destroy(net)
 
 
 CFGS = [wl.NetCfg(2, 8, 16, 4, 5), wl.NetCfg(3, 12, 10, 2, 3), wl.NetCfg(4, 16, 22, 12, 10)]

@@ -25,6 +25,10 @@ def test_library_exports_every_declared_symbol(dnb):
     names = declared_functions()
     assert "dnb_block_create" in names and "dnb_block_forward" in names
     assert "dnb_block_backward" in names and "dnb_block_peak_bytes" in names
+    # the boundary's named calls
+    for required in ("dnb_block_create", "dnb_block_destroy", "dnb_block_peak_bytes", "dnb_block_param_bytes",
+                     "dnb_block_param_offset", "dnb_block_forward", "dnb_block_backward", "dnb_status_string"):
+        assert required in names, required
     lib = ctypes.CDLL(dnb.binding.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -159,6 +163,7 @@ def test_param_offsets_match_oracle(dnb, oracle, cfg):
     s = oracle.BlockShape(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck, cfg.eps)
     h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck)
     assert dnb.dnb_block_param_count(h) == oracle.param_count(s)
+    assert dnb.dnb_block_param_bytes(h) == 4 * oracle.param_count(s)
     for l in range(1, cfg.layers + 1):
         for which in range(6):
             off, cnt = dnb.dnb_block_param_offset(h, l, which)
@@ -223,8 +228,8 @@ def test_net_param_layout_matches_oracle(dnb, oracle, cfg):
         dnb.dnb_net_param_offset(net, 14)
     blocks = cfg.blocks()
     glue = sum((b.c0 + 2 * b.c_out) * b.pixels * 4 for b in blocks)           # block inputs, outputs, BN+ReLU of outputs
-    glue += 2 * (blocks[0].c_out // 2) * blocks[0].pixels * 4                    # transition conv output and its gradient
-    glue += 2 * max(b.c_out * b.pixels for b in blocks) * 4 + blocks[0].c0 * blocks[0].pixels * 4  # gradient buffers
+    glue += 2 * max((b.c_out // 2) * b.pixels for b in blocks[:2]) * 4        # transition conv output and its gradient
+    glue += 2 * max(b.c_out * b.pixels for b in blocks) * 4 + max(b.c0 * b.pixels for b in blocks) * 4  # gradient buffers
     inner = sum((b.layers * b.bottleneck + b.c_out + b.c_in(b.layers) + b.bottleneck
                  + (0 if fusable else 2 * b.c_in(b.layers) + b.bottleneck)) * b.pixels * 4 for b in blocks)
     assert dnb.dnb_net_peak_bytes(net) == glue + inner <= dnb.dnb_net_workspace_bytes(net)
@@ -238,3 +243,58 @@ def test_net_descriptor_validation(dnb, kw):
     with pytest.raises(dnb.binding.DnbError) as e:
         dnb.dnb_net_create(**base)
     assert e.value.status == dnb.DNB_E_BADDESC
+
+
+def net_pieces(dnb, net):
+    out, i = [], 0
+    while True:
+        p = dnb.dnb_net_workspace_piece(net, i)
+        if p is None:
+            return out
+        out.append(p)
+        i += 1
+
+
+@pytest.mark.parametrize("depth", [10, 16, 22, 88, 94, 100, 130, 190, 250])
+@pytest.mark.parametrize("growth,n", [(12, 64), (24, 64), (4, 3)])
+def test_net_workspace_pieces_hold_their_largest_writer(dnb, depth, growth, n):
+    """Every piece of the network workspace against the largest tensor any step writes into it
+    (with more than 14 layers per block the input of block 1 is larger than that of block 0), no
+    two pieces overlap, and everything lies inside dnb_net_workspace_bytes."""
+    cfg = wl.NetCfg(n, 32, depth, growth, 10)
+    blocks = cfg.blocks()
+    net = dnb.dnb_net_create(cfg.n, cfg.image, cfg.depth, cfg.growth, cfg.classes, schedule=2)
+    pieces = net_pieces(dnb, net)
+    total = dnb.dnb_net_workspace_bytes(net)
+    spans = sorted((off, off + nb) for _, _, off, nb in pieces)
+    for (a0, a1), (b0, b1) in zip(spans, spans[1:]):
+        assert a1 <= b0
+    assert spans[-1][1] <= total
+    size = {(name, idx): nb for name, idx, _, nb in pieces}
+    need = {}
+    def want(key, nbytes):
+        need[key] = max(need.get(key, 0), nbytes)
+    for b, blk in enumerate(blocks):
+        P, co = blk.pixels, blk.c_out
+        want(("feat", b), blk.c0 * P * 4)        # stem / pooled transition output = block input
+        want(("y", b), co * P * 4)
+        want(("tz", b), co * P * 4)
+        want(("mean", b), co * 4)
+        want(("istd", b), co * 4)
+        want(("gy", 0), co * P * 4)              # BN+ReLU backward of the block output
+        want(("dfeat", 0), blk.c0 * P * 4)       # dnb_block_backward's dx0
+        if b < 2:
+            want(("tconv", 0), (co // 2) * P * 4)
+            want(("dconv", 0), (co // 2) * P * 4)   # pooling backward of block b+1's input gradient
+            want(("dtz", 0), co * P * 4)            # the transition conv's data gradient
+            assert blocks[b + 1].c0 == co // 2 and blocks[b + 1].pixels * 4 == P
+        else:
+            want(("dtz", 0), co * P * 4)            # global pooling backward
+            for key in ("pooled", "dpooled"):
+                want((key, 0), n * co * 4)
+    want(("logits", 0), n * cfg.classes * 4)
+    want(("dlogits", 0), n * cfg.classes * 4)
+    want(("terms", 0), n * 4)
+    for key, nbytes in need.items():
+        assert size[key] >= nbytes, (key, size[key], nbytes)
+    dnb.dnb_net_destroy(net)

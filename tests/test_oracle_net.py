@@ -8,24 +8,7 @@ import torch.nn.functional as F
 import workloads as wl
 
 NAMES = wl.PARAM_NAMES
-
-
-def pack_net(orc, s, params):
-    """Named tensors of workloads.make_net_inputs -> the oracle's flat network pack."""
-    flat = np.zeros(orc.net_param_count(s))
-    sl = orc.net_param_slices(s)
-    flat[sl["stem"]] = params["stem"].ravel()
-    for b in range(3):
-        bs = s.block(b)
-        blk = np.zeros(orc.param_count(bs))
-        for l, p in enumerate(params[f"block{b}"], start=1):
-            for name, arr in p.items():
-                blk[orc.param_slice(bs, l, NAMES.index(name))] = arr.ravel()
-        flat[sl[f"block{b}"]] = blk
-        pre = f"trans{b}" if b < 2 else "tail"
-        for name, arr in params[pre].items():
-            flat[sl[f"{pre}.{name}"]] = arr.ravel()
-    return flat
+from harness import pack_net  # noqa: E402
 
 
 def test_avgpool_and_global_pool_match_library_and_are_adjoint(oracle):
