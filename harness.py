@@ -47,9 +47,10 @@ def pack_params_oracle(orc, shape, layer_params):
     return flat
 
 
-def run_block_gpu(dnb, cfg, x0, layer_params, dy, schedule=0, poison=True, concurrency=None):
+def run_block_gpu(dnb, cfg, x0, layer_params, dy, schedule=0, poison=True, concurrency=None, decisions=False):
     """Forward + backward of one block through the C ABI.  Returns dict of numpy arrays.
-    concurrency=None keeps the library's default (what bench.py times)."""
+    concurrency=None keeps the library's default (what bench.py times).  decisions=True also
+    brings back the ReLU decisions the kernels took ("d1", "d2": bytes, the block's own layout)."""
     h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck,
                              schedule=schedule, eps=cfg.eps)
     try:
@@ -68,10 +69,18 @@ def run_block_gpu(dnb, cfg, x0, layer_params, dy, schedule=0, poison=True, concu
             dparams.fill_(float("nan"))
         x0d, dyd = dev(x0), dev(dy)
         dnb.dnb_block_forward(h, x0d, params, y, ws)
+        dec = None
+        if decisions:   # between forward and backward, as a caller checking a step would take them
+            dec = [torch.full((max(dnb.dnb_block_relu_decision_bytes(h, w), 1),), 7, dtype=torch.uint8, device="cuda")
+                   for w in (1, 2)]
+            dnb.dnb_block_relu_decisions(h, params, y, ws, dec[0], dec[1])
         dnb.dnb_block_backward(h, params, y, dyd, dx0, dparams, ws)
         torch.cuda.synchronize()
         out = {"y": y.cpu().numpy(), "dx0": dx0.cpu().numpy(), "dparams": dparams.cpu().numpy(),
                "mem": dnb.dnb_block_memory_breakdown(h), "peak": dnb.dnb_block_peak_bytes(h)}
+        if decisions:
+            out["d1"] = dec[0].cpu().numpy()[:dnb.dnb_block_relu_decision_bytes(h, 1)]
+            out["d2"] = dec[1].cpu().numpy()[:dnb.dnb_block_relu_decision_bytes(h, 2)]
         out["slices"] = {(l, name): slice(*(lambda o, c: (o, o + c))(*dnb.dnb_block_param_offset(h, l, NAMES.index(name))))
                          for l in range(1, cfg.layers + 1) for name in NAMES if name in layer_params[0]}
         return out
@@ -79,9 +88,17 @@ def run_block_gpu(dnb, cfg, x0, layer_params, dy, schedule=0, poison=True, concu
         dnb.dnb_block_destroy(h)
 
 
-def run_block_oracle(orc, cfg, x0, layer_params, dy, schedule="naive"):
+def run_block_oracle(orc, cfg, x0, layer_params, dy, schedule="naive", decisions=None, bf16_storage=False):
+    """The oracle's block on the same inputs.  decisions=(d1, d2): the float64 block evaluated with
+    these ReLU decisions instead of its own; returns (result, slices, stats) then."""
     s = orc.BlockShape(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck, cfg.eps)
     params = pack_params_oracle(orc, s, layer_params)
+    if decisions is not None:
+        res, stats = orc.block_with_decisions(s, x0.astype(np.float64), params, dy.astype(np.float64), decisions,
+                                              bf16_storage=bf16_storage)
+        slices = {(l, name): orc.param_slice(s, l, NAMES.index(name))
+                  for l in range(1, cfg.layers + 1) for name in NAMES if name in layer_params[0]}
+        return res, slices, stats
     res = orc.block(s, x0.astype(np.float64), params, dy.astype(np.float64), schedule=schedule)
     slices = {(l, name): orc.param_slice(s, l, NAMES.index(name))
               for l in range(1, cfg.layers + 1) for name in NAMES if name in layer_params[0]}
@@ -106,7 +123,7 @@ def pack_net(orc, s, params):
     return flat
 
 
-def run_net_gpu(dnb, oracle, cfg, x, labels, params, schedule, concurrency=None):
+def run_net_gpu(dnb, oracle, cfg, x, labels, params, schedule, concurrency=None, decisions=False):
     s = oracle.NetShape(cfg.n, cfg.image, cfg.depth, cfg.growth, cfg.classes, cfg.eps)
     flat = pack_net(oracle, s, params)   # the two packs have the same layout (checked by the host tests)
     net = dnb.dnb_net_create(cfg.n, cfg.image, cfg.depth, cfg.growth, cfg.classes, schedule=schedule, eps=cfg.eps)
@@ -115,15 +132,24 @@ def run_net_gpu(dnb, oracle, cfg, x, labels, params, schedule, concurrency=None)
             dnb.dnb_net_set_concurrency(net, concurrency)
         p = dev(flat.astype(np.float32))
         dp = torch.full_like(p, float("nan"))
-        ws = torch.empty(dnb.dnb_net_workspace_bytes(net), dtype=torch.uint8, device="cuda")
+        guard = 1 << 20   # a band behind the workspace that must come back untouched
+        nbytes = dnb.dnb_net_workspace_bytes(net)
+        ws = torch.empty(nbytes + guard, dtype=torch.uint8, device="cuda")
         ws.fill_(0xFF)
         xd = dev(x)
         lab = torch.from_numpy(labels).to("cuda")
         loss = torch.full((1,), float("nan"), device="cuda")
         logits = torch.full((cfg.n, cfg.classes), float("nan"), device="cuda")
         dnb.dnb_net_forward(net, xd, lab, p, loss, logits, ws)
+        dec = None
+        if decisions:   # the ReLU decisions the kernels take, between forward and backward
+            dec = torch.full((dnb.dnb_net_relu_decision_bytes(net),), 7, dtype=torch.uint8, device="cuda")
+            dnb.dnb_net_relu_decisions(net, p, ws, dec)
         dnb.dnb_net_backward(net, xd, p, dp, ws)
         torch.cuda.synchronize()
+        assert bool((ws[nbytes:] == 0xFF).all()), "the step wrote behind its workspace"
+        if decisions:
+            return s, flat, float(loss.item()), logits.cpu().numpy(), dp.cpu().numpy(), dec.cpu().numpy()
         return s, flat, float(loss.item()), logits.cpu().numpy(), dp.cpu().numpy()
     finally:
         dnb.dnb_net_destroy(net)

@@ -153,6 +153,19 @@ int dnb_block_forward(dnb_block* b, const void* x0, const void* params, void* y,
 int dnb_block_backward(dnb_block* b, const void* params, const void* y, const void* dy, void* dx0,
                        void* dparams, void* workspace, void* stream);
 
+/* The ReLU decisions of the block (Section 3: the non-linearity is applied in place, so only its
+ * sign decisions are ever needed again) exactly as its kernels take them, for checking results
+ * against an evaluation in another precision: one byte (1: pre-activation > 0) per element.
+ *   d1  first BN of every layer: the layers' (n, C_l, h, w) arrays [NHWC: (n, h, w, C_l)] one after
+ *       the other, l = 1..m; dnb_block_relu_decision_bytes(b, 1) bytes
+ *   d2  second BN: m arrays of (n, B, h, w) [NHWC: (n, h, w, B)]; ..._bytes(b, 2); unused (may be
+ *       NULL) without a bottleneck
+ * Call after dnb_block_forward on the same y and workspace (it reads the cached statistics and
+ * the kept b_l), on the same stream.  d1, d2 are device pointers owned by the caller. */
+size_t dnb_block_relu_decision_bytes(const dnb_block* b, int which);
+int dnb_block_relu_decisions(dnb_block* b, const void* params, const void* y, const void* workspace, void* d1,
+                             void* d2, void* stream);
+
 /* Section 4's "regular back-propagation" after re-population leaves the order of independent
  * kernels open: the backward pass can run its two weight-gradient chains on helper streams owned by the block
  * (created at the first such backward call, joined to `stream` before the call's last kernel),
@@ -322,6 +335,12 @@ size_t dnb_net_peak_bytes(const dnb_net* net);
  * "dconv", "dfeat", "part", "pooled", "dpooled", "logits", "dlogits", "terms": shared by all
  * blocks), byte offset and size.  Host only; lets a caller or a test check the plan. */
 int dnb_net_workspace_piece(const dnb_net* net, int i, const char** name, int* index, size_t* offset, size_t* bytes);
+/* Every ReLU decision of the step as the kernels take it (see dnb_block_relu_decisions), one byte
+ * each: for block b = 0, 1, 2 the block's d1, its d2, then the decisions of the BN+ReLU that
+ * follows the block (transition b or the tail), (n, C_out_b, h_b, w_b).  Call after
+ * dnb_net_forward on the same workspace and stream; `out` is a device pointer. */
+size_t dnb_net_relu_decision_bytes(const dnb_net* net);
+int dnb_net_relu_decisions(dnb_net* net, const void* params, const void* workspace, void* out, void* stream);
 int dnb_net_set_concurrency(dnb_net* net, int enable); /* helper streams in the blocks' backward */
 int dnb_net_forward(dnb_net* net, const void* x, const int32_t* labels, const void* params, float* loss,
                     float* logits, void* workspace, void* stream);

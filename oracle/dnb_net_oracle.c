@@ -51,6 +51,14 @@ void dnbo_conv_wgrad(const double* in, const double* dout, int64_t n, int64_t ci
 int64_t dnbo_param_count(const dnbo_desc* d);
 int dnbo_block_naive(const dnbo_desc* d, const double* x0, const double* params, const double* dy,
                      double* y, double* dx0, double* dparams, dnbo_mem* mem);
+/* the block with its ReLU decisions written out (mode 0) or imposed (mode 1), and the two
+ * element-wise routines it uses for that */
+int dnbo_block_naive_masks(const dnbo_desc* d, const double* x0, const double* params, const double* dy,
+                           double* y, double* dx0, double* dparams, dnbo_mem* mem, int mode, uint8_t* m1,
+                           uint8_t* m2, double* stats, int bf16_storage);
+void dnbo_relu_with_decisions(double* z, int64_t n, int64_t c, int64_t hw, const double* gamma,
+                              const double* beta, uint8_t* mask, int mode, double* stat);
+void dnbo_relu_backward_decisions(const uint8_t* mask, const double* da, double* dz, int64_t count);
 
 typedef struct {
   int32_t n, image;   /* batch, input height = width (3 channels) */
@@ -182,10 +190,45 @@ int64_t dnbo_net_block_param_offset(const dnbo_net_desc* d, int b) {
   return t;
 }
 
+/* Bytes of the network's ReLU decisions, in the order they are laid out: for block b = 0, 1, 2
+ * the block's first-BN decisions (all layers), its second-BN decisions (all layers), then the
+ * decisions of the BN+ReLU that follows the block (transition b or the tail), (n, C_out_b, hw). */
+int64_t dnbo_net_decision_count(const dnbo_net_desc* d) {
+  int64_t t = 0;
+  for (int b = 0; b < 3; ++b) {
+    int64_t cout;
+    dnbo_desc bd = block_desc(d, b, &cout);
+    const int64_t P = (int64_t)bd.n * bd.h * bd.w;
+    int64_t sigma = 0;
+    for (int l = 1; l <= bd.layers; ++l) sigma += bd.c0 + (int64_t)(l - 1) * bd.growth;
+    t += (sigma + (int64_t)bd.layers * bd.bottleneck + cout) * P;
+  }
+  return t;
+}
+
+static double net_step_impl(const dnbo_net_desc* d, const double* x, const int32_t* labels, const double* params,
+                            double* dparams, double* logits_out, int use_masks, int mode, uint8_t* masks, double* stats);
+
 /* One training step.  x (n,3,image,image), labels (n).  Returns the loss; writes dparams (whole
  * pack) and, if logits_out != NULL, the logits (n,classes). */
 double dnbo_net_step(const dnbo_net_desc* d, const double* x, const int32_t* labels, const double* params,
                      double* dparams, double* logits_out) {
+  return net_step_impl(d, x, labels, params, dparams, logits_out, 0, 0, NULL, NULL);
+}
+
+/* The same step with every ReLU decision written to `masks` (mode 0) or taken from it (mode 1);
+ * layout as for dnbo_net_decision_count.  stats (mode 1, 2 doubles): how many of the given
+ * decisions differ from the step's own, and the largest margin |z| / sqrt(gamma^2 + beta^2) among
+ * those (see dnb_oracle.c). */
+double dnbo_net_step_masks(const dnbo_net_desc* d, const double* x, const int32_t* labels, const double* params,
+                           double* dparams, double* logits_out, int mode, uint8_t* masks, double* stats) {
+  return net_step_impl(d, x, labels, params, dparams, logits_out, 1, mode, masks, stats);
+}
+
+static double net_step_impl(const dnbo_net_desc* d, const double* x, const int32_t* labels, const double* params,
+                            double* dparams, double* logits_out, int use_masks, int mode, uint8_t* masks, double* stats) {
+  uint8_t *mb1[3], *mb2[3], *mg[3]; /* where block b's and its following BN's decisions sit */
+  double st_acc[2] = {0.0, 0.0};
   const int64_t n = d->n, k = d->growth, S = d->image;
   const double* stemW = params;
   double* dstemW = dparams;
@@ -200,18 +243,42 @@ double dnbo_net_step(const dnbo_net_desc* d, const double* x, const int32_t* lab
   int64_t cout[3];
   feat[0] = (double*)malloc((size_t)(n * 2 * k * S * S) * sizeof(double));
   dnbo_conv_forward(x, stemW, n, 3, 2 * k, S, S, 3, feat[0]);
+  {
+    uint8_t* mp = masks;
+    for (int b = 0; b < 3; ++b) {
+      bd[b] = block_desc(d, b, &cout[b]);
+      const int64_t P = n * bd[b].h * bd[b].w;
+      int64_t sigma = 0;
+      for (int l = 1; l <= bd[b].layers; ++l) sigma += bd[b].c0 + (int64_t)(l - 1) * bd[b].growth;
+      mb1[b] = mp; mp += use_masks ? sigma * P : 0;
+      mb2[b] = mp; mp += use_masks ? (int64_t)bd[b].layers * bd[b].bottleneck * P : 0;
+      mg[b] = mp;  mp += use_masks ? cout[b] * P : 0;
+    }
+  }
   for (int b = 0; b < 3; ++b) {
-    bd[b] = block_desc(d, b, &cout[b]);
     const int64_t hw = (int64_t)bd[b].h * bd[b].w;
     const double* bp = params + dnbo_net_block_param_offset(d, b);
     yb[b] = (double*)malloc((size_t)(n * cout[b] * hw) * sizeof(double));
-    dnbo_block_naive(&bd[b], feat[b], bp, NULL, yb[b], NULL, NULL, NULL);
+    if (use_masks) {
+      double bst[4];
+      dnbo_block_naive_masks(&bd[b], feat[b], bp, NULL, yb[b], NULL, NULL, NULL, mode, mb1[b], mb2[b], bst, 0);
+      if (mode == 1) {
+        st_acc[0] += bst[0] + bst[2];
+        if (bst[1] > st_acc[1]) st_acc[1] = bst[1];
+        if (bst[3] > st_acc[1]) st_acc[1] = bst[3];
+      }
+    } else {
+      dnbo_block_naive(&bd[b], feat[b], bp, NULL, yb[b], NULL, NULL, NULL);
+    }
     const double* tp = bp + dnbo_param_count(&bd[b]);  /* g, b, then W or Wl, bl */
     tz[b] = (double*)malloc((size_t)(n * cout[b] * hw) * sizeof(double));
     tmu[b] = (double*)malloc((size_t)cout[b] * sizeof(double));
     tvar[b] = (double*)malloc((size_t)cout[b] * sizeof(double));
     dnbo_bn_forward(yb[b], n, cout[b], hw, tp, tp + cout[b], d->eps, tz[b], tmu[b], tvar[b]);
-    dnbo_relu_inplace(tz[b], n * cout[b] * hw);
+    if (use_masks)
+      dnbo_relu_with_decisions(tz[b], n, cout[b], hw, tp, tp + cout[b], mg[b], mode, st_acc);
+    else
+      dnbo_relu_inplace(tz[b], n * cout[b] * hw);
     if (b < 2) {
       const int64_t ch = cout[b] / 2;
       tconv[b] = (double*)malloc((size_t)(n * ch * hw) * sizeof(double));
@@ -247,13 +314,21 @@ double dnbo_net_step(const dnbo_net_desc* d, const double* x, const int32_t* lab
       const double* tp = params + boff + dnbo_param_count(&bd[b]);
       double* dtp = dparams + boff + dnbo_param_count(&bd[b]);
       /* g = gradient of the BN+ReLU output of this block's transition / tail */
-      dnbo_relu_backward(tz[b], g, g, n * cout[b] * hw);
+      if (use_masks && mode == 1)
+        dnbo_relu_backward_decisions(mg[b], g, g, n * cout[b] * hw);
+      else
+        dnbo_relu_backward(tz[b], g, g, n * cout[b] * hw);
       dnbo_bn_backward(yb[b], g, n, cout[b], hw, tp, tmu[b], tvar[b], d->eps, g, dtp, dtp + cout[b]);
       /* g = gradient of the block output */
       const int64_t cin = bd[b].c0;
       double* dfeat = (double*)malloc((size_t)(n * cin * hw) * sizeof(double));
       double* ydummy = (double*)malloc((size_t)(n * cout[b] * hw) * sizeof(double));
-      dnbo_block_naive(&bd[b], feat[b], params + boff, g, ydummy, dfeat, dparams + boff, NULL);
+      if (use_masks && mode == 1) {
+        double bst[4];  /* (the forward pass above has already counted this block's disagreements) */
+        dnbo_block_naive_masks(&bd[b], feat[b], params + boff, g, ydummy, dfeat, dparams + boff, NULL, 1, mb1[b], mb2[b], bst, 0);
+      } else {
+        dnbo_block_naive(&bd[b], feat[b], params + boff, g, ydummy, dfeat, dparams + boff, NULL);
+      }
       free(ydummy);
       free(g);
       if (b == 0) {
@@ -276,5 +351,6 @@ double dnbo_net_step(const dnbo_net_desc* d, const double* x, const int32_t* lab
   }
   for (int b = 0; b < 3; ++b) { free(feat[b]); free(yb[b]); free(tz[b]); free(tmu[b]); free(tvar[b]); }
   free(tconv[0]); free(tconv[1]); free(pooled); free(logits); free(dlogits);
+  if (use_masks && mode == 1 && stats) { stats[0] = st_acc[0]; stats[1] = st_acc[1]; }
   return loss;
 }

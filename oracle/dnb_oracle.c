@@ -23,6 +23,18 @@
  *                        overwrite them; backward re-runs concat and BN to
  *                        re-populate them before ordinary back-propagation.
  *   Both track the peak number of live feature-map elements they allocate.
+ *   dnbo_block_naive_masks -- the store-everything schedule with the ReLU decisions (z > 0, one
+ *                        bit per pre-activation) either written out or taken from the caller.
+ *                        A ReLU decision is an integer decided by floating point: a pre-activation
+ *                        within rounding of zero falls on either side depending on the precision
+ *                        of the arithmetic, and the gradient element behind it then changes by
+ *                        its whole size.  A parity test therefore lets both sides take the
+ *                        decision in the same precision (the kernel's): the block is evaluated in
+ *                        float64 with the kernel's decisions, and every decision that differs
+ *                        from the block's own is reported with its margin |z| / sqrt(gamma^2 +
+ *                        beta^2) (the pre-activation in units of its channel's root mean square:
+ *                        xhat has unit variance), so the test can check that only ties within
+ *                        rounding differ.
  *   dnbo_block_naive_bf16 -- the store-everything schedule with every stored tensor rounded
  *                        to bfloat16 where it is produced (arithmetic still float64); the
  *                        reference for the bf16 path's gradients.  Pinned by a library
@@ -381,6 +393,58 @@ static void split_dy(const double* dy, double** gx, int m, int64_t n, int64_t c0
   }
 }
 
+/* ReLU decisions of a block: mode 0 writes the block's own (z > 0), mode 1 reads the caller's
+ * and uses them in forward (a = z where the decision is 1, else 0) and backward.
+ * m1: first BN of every layer, the layers' (n, C_l, hw) byte arrays one after the other;
+ * m2: second BN (bottleneck only), m arrays of (n, B, hw).
+ * stats (mode 1): [0] decisions of m1 that differ from the block's own, [1] the largest margin
+ * |z| / sqrt(gamma^2 + beta^2) among them (z = gamma xhat + beta with xhat of unit variance, so
+ * this is the distance from the decision boundary in units of the channel's root mean square
+ * pre-activation), [2], [3] the same for m2. */
+typedef struct {
+  int mode;
+  uint8_t* m1;
+  uint8_t* m2;
+  double* stats;
+} dnbo_masks;
+
+/* In-place ReLU of z = BN(u) under `mk` (see dnbo_masks); mask points at this tensor's bytes. */
+void dnbo_relu_with_decisions(double* z, int64_t n, int64_t c, int64_t hw, const double* gamma,
+                                const double* beta, uint8_t* mask, int mode, double* stat /* count, worst margin */) {
+  double cnt = 0.0, worst = 0.0;
+#pragma omp parallel for schedule(static) reduction(+ : cnt) reduction(max : worst)
+  for (int64_t ch = 0; ch < c; ++ch) {
+    const double rms = sqrt(gamma[ch] * gamma[ch] + beta[ch] * beta[ch]) + 1e-300;
+    for (int64_t i = 0; i < n; ++i) {
+      const int64_t base = (i * c + ch) * hw;
+      for (int64_t q = 0; q < hw; ++q) {
+        const int own = z[base + q] > 0.0;
+        if (mode == 0) {
+          mask[base + q] = (uint8_t)own;
+          z[base + q] = own ? z[base + q] : 0.0;
+        } else {
+          const int use = mask[base + q] != 0;
+          if (use != own) {
+            const double margin = fabs(z[base + q]) / rms;
+            cnt += 1.0;
+            if (margin > worst) worst = margin;
+          }
+          z[base + q] = use ? z[base + q] : 0.0;
+        }
+      }
+    }
+  }
+  if (stat && mode == 1) {
+    stat[0] += cnt;
+    if (worst > stat[1]) stat[1] = worst;
+  }
+}
+
+void dnbo_relu_backward_decisions(const uint8_t* mask, const double* da, double* dz, int64_t count) {
+#pragma omp parallel for schedule(static)
+  for (int64_t i = 0; i < count; ++i) dz[i] = mask[i] ? da[i] : 0.0;
+}
+
 /* ------------------------------------------------- schedule 1: store all */
 
 /* Section 3.  Forward keeps, per layer: the concat output u_l, the BN+ReLU
@@ -390,7 +454,8 @@ static void split_dy(const double* dy, double** gx, int m, int64_t n, int64_t c0
  * (dense connectivity: the gradient of x_l is complete once every later
  * layer has been processed). */
 static int block_naive_impl(const dnbo_desc* d, const double* x0, const double* params, const double* dy,
-                            double* y, double* dx0, double* dparams, dnbo_mem* mem, int q /* bf16 storage */) {
+                            double* y, double* dx0, double* dparams, dnbo_mem* mem, int q /* bf16 storage */,
+                            const dnbo_masks* mk /* may be NULL */) {
   const int m = d->layers;
   const int64_t n = d->n, c0 = d->c0, k = d->growth, B = d->bottleneck, H = d->h, W = d->w;
   const int64_t hw = H * W, P = n * hw, cout = c0 + m * k;
@@ -407,6 +472,11 @@ static int block_naive_impl(const dnbo_desc* d, const double* x0, const double* 
   double** W1q = (double**)calloc((size_t)m + 1, sizeof(double*)); /* weights as the convs read them */
   double** W3q = (double**)calloc((size_t)m + 1, sizeof(double*));
 
+  /* where layer l's ReLU decisions sit inside mk->m1 / mk->m2 */
+  int64_t* mo1 = (int64_t*)calloc((size_t)m + 2, sizeof(int64_t));
+  for (int l = 1; l <= m; ++l) mo1[l + 1] = mo1[l] + layer_cin(d, l) * P;
+  if (mk && mk->mode == 1 && mk->stats) memset(mk->stats, 0, 4 * sizeof(double));
+
   x[0] = (double*)x0; /* the caller's input is not ours to count */
   for (int l = 1; l <= m; ++l) {
     const int64_t c = layer_cin(d, l);
@@ -417,7 +487,11 @@ static int block_naive_impl(const dnbo_desc* d, const double* x0, const double* 
     v1[l] = (double*)calloc((size_t)c, sizeof(double));
     dnbo_bn_forward(u[l], n, c, hw, par(d, params, l, DNBO_G1), par(d, params, l, DNBO_B1), d->eps,
                     a[l], mu1[l], v1[l]);
-    dnbo_relu_inplace(a[l], c * P);
+    if (mk)
+      dnbo_relu_with_decisions(a[l], n, c, hw, par(d, params, l, DNBO_G1), par(d, params, l, DNBO_B1), mk->m1 + mo1[l],
+                          mk->mode, mk->stats);
+    else
+      dnbo_relu_inplace(a[l], c * P);
     quantize(a[l], c * P, q);
     x[l] = fm_alloc(mem, k * P);
     int64_t nw3 = 0;
@@ -433,7 +507,11 @@ static int block_naive_impl(const dnbo_desc* d, const double* x0, const double* 
       v2[l] = (double*)calloc((size_t)B, sizeof(double));
       dnbo_bn_forward(b[l], n, B, hw, par(d, params, l, DNBO_G2), par(d, params, l, DNBO_B2),
                       d->eps, a2[l], mu2[l], v2[l]);
-      dnbo_relu_inplace(a2[l], B * P);
+      if (mk)
+        dnbo_relu_with_decisions(a2[l], n, B, hw, par(d, params, l, DNBO_G2), par(d, params, l, DNBO_B2),
+                            mk->m2 + (int64_t)(l - 1) * B * P, mk->mode, mk->stats ? mk->stats + 2 : NULL);
+      else
+        dnbo_relu_inplace(a2[l], B * P);
       quantize(a2[l], B * P, q);
       dnbo_conv_forward(a2[l], W3q[l], n, B, k, H, W, 3, x[l]);
     } else {
@@ -464,7 +542,10 @@ static int block_naive_impl(const dnbo_desc* d, const double* x0, const double* 
         dnbo_conv_wgrad(a2[l], g, n, B, k, H, W, 3, dpar(d, dparams, l, DNBO_W3));
         dnbo_conv_dgrad(g, W3q[l], n, B, k, H, W, 3, da2);
         quantize(da2, B * P, q);
-        dnbo_relu_backward(a2[l], da2, da2, B * P);
+        if (mk && mk->mode == 1)
+          dnbo_relu_backward_decisions(mk->m2 + (int64_t)(l - 1) * B * P, da2, da2, B * P);
+        else
+          dnbo_relu_backward(a2[l], da2, da2, B * P);
         dnbo_bn_backward(b[l], da2, n, B, hw, par(d, params, l, DNBO_G2), mu2[l], v2[l], d->eps,
                          da2, dpar(d, dparams, l, DNBO_G2), dpar(d, dparams, l, DNBO_B2));
         quantize(da2, B * P, q);
@@ -476,7 +557,10 @@ static int block_naive_impl(const dnbo_desc* d, const double* x0, const double* 
       }
       quantize(da, c * P, q);
       if (q) free(g);
-      dnbo_relu_backward(a[l], da, da, c * P);
+      if (mk && mk->mode == 1)
+        dnbo_relu_backward_decisions(mk->m1 + mo1[l], da, da, c * P);
+      else
+        dnbo_relu_backward(a[l], da, da, c * P);
       dnbo_bn_backward(u[l], da, n, c, hw, par(d, params, l, DNBO_G1), mu1[l], v1[l], d->eps, da,
                        dpar(d, dparams, l, DNBO_G1), dpar(d, dparams, l, DNBO_B1));
       concat_backward_add(da, gx, l, n, c0, k, hw);
@@ -506,14 +590,25 @@ static int block_naive_impl(const dnbo_desc* d, const double* x0, const double* 
     free(W3q[l]);
   }
   free(x); free(u); free(a); free(b); free(a2); free(mu1); free(v1); free(mu2); free(v2);
-  free(W1q); free(W3q);
+  free(W1q); free(W3q); free(mo1);
   (void)cout;
   return 0;
 }
 
 int dnbo_block_naive(const dnbo_desc* d, const double* x0, const double* params, const double* dy,
                      double* y, double* dx0, double* dparams, dnbo_mem* mem) {
-  return block_naive_impl(d, x0, params, dy, y, dx0, dparams, mem, 0);
+  return block_naive_impl(d, x0, params, dy, y, dx0, dparams, mem, 0, NULL);
+}
+
+/* The store-everything block with its ReLU decisions written to m1 / m2 (mode 0) or taken from
+ * them (mode 1); layout and stats as described at dnbo_masks.  m2 may be NULL without a bottleneck.
+ * bf16_storage != 0: with the storage rounding of dnbo_block_naive_bf16 on top (its distance from
+ * the unrounded block under the same decisions is what bf16 storage costs by itself). */
+int dnbo_block_naive_masks(const dnbo_desc* d, const double* x0, const double* params, const double* dy,
+                           double* y, double* dx0, double* dparams, dnbo_mem* mem, int mode, uint8_t* m1,
+                           uint8_t* m2, double* stats, int bf16_storage) {
+  dnbo_masks mk = {mode, m1, m2, stats};
+  return block_naive_impl(d, x0, params, dy, y, dx0, dparams, mem, bf16_storage ? 1 : 0, &mk);
 }
 
 /* The same block with bf16 storage emulated: every tensor the bf16 path keeps in memory or
@@ -527,7 +622,7 @@ int dnbo_block_naive(const dnbo_desc* d, const double* x0, const double* params,
  * rounding itself.  x0 and dy should already hold bf16-representable values. */
 int dnbo_block_naive_bf16(const dnbo_desc* d, const double* x0, const double* params, const double* dy,
                           double* y, double* dx0, double* dparams, dnbo_mem* mem) {
-  return block_naive_impl(d, x0, params, dy, y, dx0, dparams, mem, 1);
+  return block_naive_impl(d, x0, params, dy, y, dx0, dparams, mem, 1, NULL);
 }
 
 /* ------------------------------------------- schedule 0: shared storage */

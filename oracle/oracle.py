@@ -63,6 +63,9 @@ def lib():
             f = getattr(_lib, name)
             f.restype = C.c_int
             f.argtypes = [C.POINTER(_Desc), _dp, _dp, _dp, _dp, _dp, _dp, C.POINTER(_Mem)]
+        _lib.dnbo_block_naive_masks.restype = C.c_int
+        _lib.dnbo_block_naive_masks.argtypes = [C.POINTER(_Desc), _dp, _dp, _dp, _dp, _dp, _dp, C.POINTER(_Mem), C.c_int,
+                                                C.c_void_p, C.c_void_p, _dp, C.c_int]
         _lib.dnbo_round_bf16.restype = C.c_double
         _lib.dnbo_round_bf16.argtypes = [C.c_double]
         _lib.dnbo_block_probe_layer.restype = C.c_int
@@ -91,6 +94,10 @@ def lib():
         _lib.dnbo_net_block_param_offset.argtypes = [nd, C.c_int]
         _lib.dnbo_net_step.restype = C.c_double
         _lib.dnbo_net_step.argtypes = [nd, _dp, C.POINTER(C.c_int32), _dp, _dp, _dp]
+        _lib.dnbo_net_decision_count.restype = C.c_int64
+        _lib.dnbo_net_decision_count.argtypes = [nd]
+        _lib.dnbo_net_step_masks.restype = C.c_double
+        _lib.dnbo_net_step_masks.argtypes = [nd, _dp, C.POINTER(C.c_int32), _dp, _dp, _dp, C.c_int, C.c_void_p, _dp]
         _lib.dnbo_avgpool2.restype = None
         _lib.dnbo_avgpool2.argtypes = [_dp, i64, i64, i64, i64, _dp]
         _lib.dnbo_avgpool2_backward.restype = None
@@ -190,6 +197,48 @@ def block(s: BlockShape, x0, params, dy=None, schedule: str = "naive") -> BlockR
     dparams = np.zeros_like(params)
     fn(C.byref(d), _p(x0), _p(params), _p(dy), _p(y), _p(dx0), _p(dparams), C.byref(mem))
     return BlockResult(y, dx0, dparams, int(mem.peak_elems), int(mem.stored_elems))
+
+
+def relu_decision_counts(s: BlockShape):
+    """Elements of the two ReLU-decision arrays of a block: the first BN of every layer (the layers'
+    (n, C_l, h, w) arrays one after the other) and the second BN (layers x (n, B, h, w))."""
+    P = s.n * s.h * s.w
+    return sum(s.c_in(l) for l in range(1, s.layers + 1)) * P, s.layers * s.bottleneck * P
+
+
+def block_with_decisions(s: BlockShape, x0, params, dy, decisions=None, bf16_storage: bool = False):
+    """The store-everything block with its ReLU decisions (z > 0, one byte each) written out
+    (decisions=None: returns (result, (m1, m2))) or taken from the caller (decisions=(m1, m2):
+    returns (result, stats) with stats = dict(count1, margin1, count2, margin2): how many of the
+    caller's decisions differ from the block's own and the largest margin |z| / sqrt(gamma^2 +
+    beta^2) among those: the pre-activation in units of its channel's root mean square).
+    bf16_storage: with the storage rounding of schedule "naive_bf16" on top."""
+    d = s._c()
+    x0 = _f64(x0).reshape(s.n, s.c0, s.h, s.w)
+    params = _f64(params).reshape(-1)
+    assert params.size == param_count(s)
+    y = np.zeros((s.n, s.c_out, s.h, s.w), dtype=np.float64)
+    dy = _f64(dy).reshape(y.shape)
+    dx0 = np.zeros_like(x0)
+    dparams = np.zeros_like(params)
+    mem = _Mem()
+    n1, n2 = relu_decision_counts(s)
+    if decisions is None:
+        m1, m2 = np.zeros(n1, dtype=np.uint8), np.zeros(max(n2, 1), dtype=np.uint8)
+        mode = 0
+    else:
+        m1 = np.ascontiguousarray(np.asarray(decisions[0], dtype=np.uint8).reshape(-1))
+        m2 = np.ascontiguousarray(np.asarray(decisions[1], dtype=np.uint8).reshape(-1)) if n2 else np.zeros(1, dtype=np.uint8)
+        assert m1.size == n1 and (n2 == 0 or m2.size == n2)
+        mode = 1
+    stats = np.zeros(4)
+    lib().dnbo_block_naive_masks(C.byref(d), _p(x0), _p(params), _p(dy), _p(y), _p(dx0), _p(dparams), C.byref(mem), mode,
+                                 m1.ctypes.data_as(C.c_void_p), m2.ctypes.data_as(C.c_void_p), _p(stats),
+                                 1 if bf16_storage else 0)
+    res = BlockResult(y, dx0, dparams, int(mem.peak_elems), int(mem.stored_elems))
+    if decisions is None:
+        return res, (m1, m2[:n2])
+    return res, dict(count1=int(stats[0]), margin1=float(stats[1]), count2=int(stats[2]), margin2=float(stats[3]))
 
 
 def round_bf16(v: float) -> float:
@@ -345,6 +394,38 @@ def net_step(s: NetShape, x, labels, params, backward: bool = True):
     loss = lib().dnbo_net_step(C.byref(d), _p(x), lab.ctypes.data_as(C.POINTER(C.c_int32)), _p(params),
                                _p(dparams) if backward else None, _p(logits))
     return float(loss), dparams, logits
+
+
+def net_decision_count(s: NetShape) -> int:
+    """Number of ReLU decisions of one step: per block its first-BN decisions (all layers), its
+    second-BN decisions, then those of the BN+ReLU that follows the block."""
+    d = s._c()
+    return int(lib().dnbo_net_decision_count(C.byref(d)))
+
+
+def net_step_with_decisions(s: NetShape, x, labels, params, decisions=None):
+    """One training step with every ReLU decision written out (decisions=None: returns (loss,
+    dparams, logits, decisions)) or imposed (returns (loss, dparams, logits, stats) with stats =
+    dict(count, margin): decisions that differ from the step's own and their largest margin)."""
+    d = s._c()
+    x = _f64(x).reshape(s.n, 3, s.image, s.image)
+    params = _f64(params).reshape(-1)
+    assert params.size == net_param_count(s)
+    lab = np.ascontiguousarray(np.asarray(labels, dtype=np.int32))
+    logits = np.zeros((s.n, s.classes))
+    dparams = np.zeros_like(params)
+    cnt = net_decision_count(s)
+    if decisions is None:
+        m, mode = np.zeros(cnt, dtype=np.uint8), 0
+    else:
+        m, mode = np.ascontiguousarray(np.asarray(decisions, dtype=np.uint8).reshape(-1)), 1
+        assert m.size == cnt
+    stats = np.zeros(2)
+    loss = lib().dnbo_net_step_masks(C.byref(d), _p(x), lab.ctypes.data_as(C.POINTER(C.c_int32)), _p(params), _p(dparams),
+                                     _p(logits), mode, m.ctypes.data_as(C.c_void_p), _p(stats))
+    if decisions is None:
+        return float(loss), dparams, logits, m
+    return float(loss), dparams, logits, dict(count=int(stats[0]), margin=float(stats[1]))
 
 
 def avgpool2(x):

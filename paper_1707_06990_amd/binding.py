@@ -56,6 +56,8 @@ _SIGS = {
     "dnb_block_memory_breakdown": (C.c_int, [_vp, C.POINTER(dnb_block_memory)]),
     "dnb_block_param_count": (_sz, [_vp]),
     "dnb_block_param_bytes": (_sz, [_vp]),
+    "dnb_block_relu_decision_bytes": (_sz, [_vp, C.c_int]),
+    "dnb_block_relu_decisions": (C.c_int, [_vp] * 7),
     "dnb_block_param_offset": (C.c_int, [_vp, C.c_int, C.c_int, C.POINTER(_sz), C.POINTER(_sz)]),
     "dnb_block_forward": (C.c_int, [_vp] * 6),
     "dnb_block_backward": (C.c_int, [_vp] * 8),
@@ -96,6 +98,8 @@ _SIGS = {
     "dnb_net_workspace_piece": (C.c_int, [_vp, C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_int), C.POINTER(_sz),
                                           C.POINTER(_sz)]),
     "dnb_net_peak_bytes": (_sz, [_vp]),
+    "dnb_net_relu_decision_bytes": (_sz, [_vp]),
+    "dnb_net_relu_decisions": (C.c_int, [_vp] * 5),
     "dnb_net_set_concurrency": (C.c_int, [_vp, C.c_int]),
     "dnb_net_forward": (C.c_int, [_vp] * 8),
     "dnb_net_backward": (C.c_int, [_vp] * 6),
@@ -186,6 +190,14 @@ def dnb_block_forward(b, x0, params, y, workspace, stream=None) -> None:
 def dnb_block_backward(b, params, y, dy, dx0, dparams, workspace, stream=None) -> None:
     _check(_lib.dnb_block_backward(b, _ptr(params), _ptr(y), _ptr(dy), _ptr(dx0), _ptr(dparams),
                                    _ptr(workspace), _stream(stream)))
+
+
+def dnb_block_relu_decision_bytes(b, which: int) -> int:
+    return int(_lib.dnb_block_relu_decision_bytes(b, which))
+
+
+def dnb_block_relu_decisions(b, params, y, workspace, d1, d2, stream=None) -> None:
+    _check(_lib.dnb_block_relu_decisions(b, _ptr(params), _ptr(y), _ptr(workspace), _ptr(d1), _ptr(d2), _stream(stream)))
 
 
 def dnb_block_set_concurrency(b, enable: bool) -> None:
@@ -362,6 +374,14 @@ def dnb_net_workspace_piece(net, i: int):
 
 def dnb_net_peak_bytes(net) -> int:
     return int(_lib.dnb_net_peak_bytes(net))
+
+
+def dnb_net_relu_decision_bytes(net) -> int:
+    return int(_lib.dnb_net_relu_decision_bytes(net))
+
+
+def dnb_net_relu_decisions(net, params, workspace, out, stream=None) -> None:
+    _check(_lib.dnb_net_relu_decisions(net, _ptr(params), _ptr(workspace), _ptr(out), _stream(stream)))
 
 
 def dnb_net_set_concurrency(net, enable: bool) -> None:

@@ -81,6 +81,49 @@ T layer_ptrs(const dnb_block* b, P* base, int l) {
 }
 
 
+// ReLU decisions as the kernels take them: fma(u, scale, shift) > 0 with (scale, shift) folded by
+// bn_fold from the cached statistics -- the one expression every forward, recomputing and backward
+// kernel evaluates.  One byte per pre-activation, in the tensor's own layout: element (img, ch, q)
+// of u sits at u[img*s_img + ch*s_ch + q*s_px]; `nhwc` picks the order of the compact output.
+template <typename T>
+__global__ __launch_bounds__(256) void k_relu_decisions(const T* __restrict__ u, int64_t s_img, int64_t s_ch,
+                                                        int64_t s_px, int n, int c, int hw, int nhwc,
+                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                        const float* __restrict__ mean, const float* __restrict__ istd,
+                                                        unsigned char* __restrict__ out) {
+  const int64_t total = (int64_t)n * c * hw;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    int img, ch, q;
+    if (nhwc) { ch = (int)(i % c); const int64_t r = i / c; q = (int)(r % hw); img = (int)(r / hw); }
+    else      { q = (int)(i % hw); const int64_t r = i / hw; ch = (int)(r % c); img = (int)(r / c); }
+    float scale, shift;
+    bn_fold(gamma[ch], beta[ch], mean[ch], istd[ch], scale, shift);
+    const T raw = u[(int64_t)img * s_img + (int64_t)ch * s_ch + (int64_t)q * s_px];
+    float v;
+    if (sizeof(T) == 2) v = __uint_as_float((unsigned)raw << 16);  // bf16 bits
+    else v = (float)raw;
+    out[i] = __fmaf_rn(v, scale, shift) > 0.f ? 1 : 0;
+  }
+}
+
+}  // namespace
+
+namespace dnb {
+hipError_t launch_relu_decisions(const float* u, int64_t stride, int n, int c, int hw, const float* gamma,
+                                 const float* beta, const float* mean, const float* istd, unsigned char* out,
+                                 hipStream_t st) {
+  const int64_t total = (int64_t)n * c * hw;
+  int64_t g = (total + 256 * 8 - 1) / (256 * 8);
+  if (g < 1) g = 1;
+  if (g > 65535) g = 65535;
+  hipLaunchKernelGGL(k_relu_decisions<float>, dim3((unsigned)g), dim3(256), 0, st, u, stride, (int64_t)hw, (int64_t)1, n,
+                     c, hw, 0, gamma, beta, mean, istd, out);
+  return hipGetLastError();
+}
+}  // namespace dnb
+
+namespace {
+
 // ---- bf16 / NHWC, fused schedule.  x0, y, dy, dx0 and the kept b_l are bf16 with channels
 // contiguous; y's pixel stride is C_out, so layer l reads y[..., :C_l] in place and writes its k
 // new channels into y[..., C_l:C_l+k].  The gradient slab G is fp32 (it is accumulated into up to
@@ -549,6 +592,59 @@ int dnb_block_memory_breakdown(const dnb_block* b, dnb_block_memory* out) {
 
 size_t dnb_block_param_count(const dnb_block* b) { return b ? b->pcount : 0; }
 size_t dnb_block_param_bytes(const dnb_block* b) { return b ? b->pcount * sizeof(float) : 0; }
+
+size_t dnb_block_relu_decision_bytes(const dnb_block* b, int which) {
+  if (!b) return 0;
+  size_t sigma_c = 0;
+  for (int l = 1; l <= b->d.layers; ++l) sigma_c += (size_t)c_in(b->d, l);
+  if (which == 1) return sigma_c * (size_t)b->P;
+  if (which == 2) return (size_t)b->d.layers * (size_t)b->d.bottleneck * (size_t)b->P;
+  return 0;
+}
+
+int dnb_block_relu_decisions(dnb_block* b, const void* paramsv, const void* yv, const void* wsv, void* d1v, void* d2v,
+                             void* stream) {
+  if (!b || !paramsv || !yv || !wsv || !d1v || (b->d.bottleneck > 0 && !d2v)) return DNB_E_NULL;
+  if (misaligned4(paramsv) || misaligned(yv) || misaligned(wsv)) return DNB_E_ALIGN;
+  const dnb_block_desc& d = b->d;
+  hipStream_t st = (hipStream_t)stream;
+  const bool nhwc = d.layout == DNB_NHWC;
+  const int n = d.n, m = d.layers, B = d.bottleneck, hw = (int)b->hw, cout = b->cout;
+  const float* params = (const float*)paramsv;
+  const char* ws = (const char*)wsv;
+  const float* mean_y = (const float*)(ws + b->off_stat_y);
+  const float* istd_y = mean_y + cout;
+  unsigned char* d1 = (unsigned char*)d1v;
+  unsigned char* d2 = (unsigned char*)d2v;
+  auto launch = [&](const void* u, int64_t s_img, int64_t s_ch, int64_t s_px, int c, const float* g, const float* be,
+                    const float* mu, const float* is, unsigned char* out) {
+    const int64_t total = (int64_t)n * c * hw;
+    const unsigned grid = (unsigned)((total + 256 * 8 - 1) / (256 * 8) < 1 ? 1 : (total + 256 * 8 - 1) / (256 * 8) > 65535 ? 65535 : (total + 256 * 8 - 1) / (256 * 8));
+    if (d.dtype == DNB_BF16)
+      hipLaunchKernelGGL(k_relu_decisions<unsigned short>, dim3(grid), dim3(256), 0, st, (const unsigned short*)u, s_img,
+                         s_ch, s_px, n, c, hw, nhwc ? 1 : 0, g, be, mu, is, out);
+    else
+      hipLaunchKernelGGL(k_relu_decisions<float>, dim3(grid), dim3(256), 0, st, (const float*)u, s_img, s_ch, s_px, n,
+                         c, hw, nhwc ? 1 : 0, g, be, mu, is, out);
+    return hipGetLastError();
+  };
+  size_t o1 = 0;
+  for (int l = 1; l <= m; ++l) {
+    const int c = c_in(d, l);
+    const LayerParams p = layer_ptrs<LayerParams, const float>(b, params, l);
+    // the layer's concatenated input is y[:, :C_l] in place
+    if (nhwc) DNB_TRY(launch(yv, (int64_t)hw * cout, 1, cout, c, p.g1, p.b1, mean_y, istd_y, d1 + o1));
+    else      DNB_TRY(launch(yv, (int64_t)cout * hw, hw, 1, c, p.g1, p.b1, mean_y, istd_y, d1 + o1));
+    o1 += (size_t)c * (size_t)b->P;
+    if (B > 0) {
+      const void* bl = ws + b->off_b[l];
+      const float* mean_b = (const float*)(ws + b->off_stat_b[l]);
+      if (nhwc) DNB_TRY(launch(bl, (int64_t)hw * B, 1, B, B, p.g2, p.b2, mean_b, mean_b + B, d2 + (size_t)(l - 1) * B * b->P));
+      else      DNB_TRY(launch(bl, (int64_t)B * hw, hw, 1, B, p.g2, p.b2, mean_b, mean_b + B, d2 + (size_t)(l - 1) * B * b->P));
+    }
+  }
+  return DNB_OK;
+}
 
 int dnb_block_param_offset(const dnb_block* b, int layer, int which, size_t* offset, size_t* count) {
   if (!b || !offset || !count) return DNB_E_NULL;

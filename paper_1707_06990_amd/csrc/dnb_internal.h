@@ -58,6 +58,12 @@ hipError_t launch_bn_relu_bwd(const float* x, int64_t x_stride, const float* dac
                               float* partials, hipStream_t st, int passes = 3 /*1 reduce | 2 apply*/,
                               hipEvent_t ev_start = nullptr, hipEvent_t ev_stop = nullptr);
 
+// out[(img*c + ch)*hw + q] = 1 if fma(u[img*stride + ch*hw + q], scale, shift) > 0 else 0, with
+// (scale, shift) = bn_fold(gamma, beta, mean, istd): the ReLU decision exactly as every kernel takes it.
+hipError_t launch_relu_decisions(const float* u, int64_t stride, int n, int c, int hw, const float* gamma,
+                                 const float* beta, const float* mean, const float* istd, unsigned char* out,
+                                 hipStream_t st);
+
 // ---- convolutions (MFMA implicit GEMM, fp32) -----------------------------------------------
 
 // Weight addressing for the implicit-GEMM kernel: element (m = output channel, c = input

@@ -331,6 +331,37 @@ int dnb_net_param_offset(const dnb_net* net, int part, size_t* offset, size_t* c
   return DNB_OK;
 }
 
+size_t dnb_net_relu_decision_bytes(const dnb_net* net) {
+  if (!net) return 0;
+  size_t t = 0;
+  for (int b = 0; b < 3; ++b) {
+    const dnb_block_desc& bd = net->bd[b];
+    t += dnb_block_relu_decision_bytes(net->blk[b], 1) + dnb_block_relu_decision_bytes(net->blk[b], 2) +
+         (size_t)net->cout[b] * bd.n * bd.h * bd.w;
+  }
+  return t;
+}
+
+int dnb_net_relu_decisions(dnb_net* net, const void* paramsv, const void* wsv, void* outv, void* stream) {
+  if (!net || !paramsv || !wsv || !outv) return DNB_E_NULL;
+  const float* params = (const float*)paramsv;
+  const char* ws = (const char*)wsv;
+  unsigned char* out = (unsigned char*)outv;
+  for (int b = 0; b < 3; ++b) {
+    const dnb_block_desc& bd = net->bd[b];
+    const int hw = bd.h * bd.w, co = net->cout[b];
+    const size_t n1 = dnb_block_relu_decision_bytes(net->blk[b], 1), n2 = dnb_block_relu_decision_bytes(net->blk[b], 2);
+    const float* y = (const float*)(ws + net->o_y[b]);
+    DNB_TRYS(dnb_block_relu_decisions(net->blk[b], params + net->p_block[b], y, ws + net->o_ws[b], out, out + n1, stream));
+    out += n1 + n2;
+    DNB_TRYH(launch_relu_decisions(y, (int64_t)co * hw, bd.n, co, hw, params + net->p_g[b], params + net->p_b[b],
+                                   (const float*)(ws + net->o_mean[b]), (const float*)(ws + net->o_istd[b]), out,
+                                   (hipStream_t)stream));
+    out += (size_t)co * bd.n * hw;
+  }
+  return DNB_OK;
+}
+
 int dnb_net_set_concurrency(dnb_net* net, int enable) {
   if (!net) return DNB_E_NULL;
   for (int b = 0; b < 3; ++b) DNB_TRYS(dnb_block_set_concurrency(net->blk[b], enable));

@@ -1,12 +1,18 @@
 """GPU parity of the bf16 / NHWC path (feature maps bf16, fp32 accumulation and statistics, fused
-schedule) against the float64 oracle evaluated on the same bf16-rounded inputs.
+schedule) against the plain float64 oracle evaluated on the same bf16-rounded inputs, at the 2e-2
+bound on both measures, for the output, dx0 and every parameter gradient (at full size with an
+allowance, measured in the test, for what bf16 storage costs by itself).
 
-Two oracles are used.  The block output is compared with the plain float64 block.  The gradients
-are compared with the float64 block that rounds to bf16 at the points where the bf16 path stores
-a tensor: a ReLU mask decided on a rounded pre-activation can differ from the unrounded one, and
-with the synthetic N(0,1) loss weights each per-channel gradient sum is a random walk, so a few
-flipped masks (about one element in 700) move those sums by several per cent whatever the
-arithmetic does.  With the storage points emulated the masks agree and the bound is meaningful."""
+A ReLU decision (pre-activation > 0) is an integer decided by floating point, and a feature map
+stored in bf16 carries a relative error of 2^-9: about one decision in several hundred falls on the
+other side of zero than in float64, and each such element changes a gradient element by its whole
+size (tests/test_oracle_bf16_reading.py measures this on the CPU: several per cent in every
+gradient tensor, whatever arithmetic computes the block).  Both sides therefore take the decisions
+in the same precision, the kernel's: the library reports the decisions its kernels took
+(dnb_block_relu_decisions) and the float64 oracle evaluates the block with them.  What is compared
+is then unique, and the rest is checked to be valid: every decision that differs from the oracle's
+own must be a tie within bf16 rounding (margin |z| / sqrt(gamma^2 + beta^2) <= MARGIN, at most
+SHARE of all decisions)."""
 import numpy as np
 import pytest
 import torch
@@ -16,17 +22,13 @@ from gpu_util import NAMES, assert_close, dev, pack_params_gpu, rel_errors, run_
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-2  # bf16 storage (the benchmark spec): relative error vs the float64 oracle, L2 and max-abs/max
-# Gradients: the L2 measure keeps TOL.  The worst single element gets a wider bound: where the fp32
-# and the float64 accumulation of the same sum land on different sides of a bf16 rounding boundary
-# the two paths store values one bf16 ulp apart, later layers amplify that, and an occasional ReLU
-# mask then differs, which changes one gradient element (or one small per-channel sum) by its
-# whole size.  Blocks small enough to have no such boundary case agree to 1e-6.
-GRAD_MAX_TOL = 8e-2
-
-
-def assert_grad_close(a, r, what):
-    l2, mx = rel_errors(a, r)
-    assert l2 <= TOL and mx <= GRAD_MAX_TOL, f"{what}: rel L2 {l2:.3e} (> {TOL:g}?), rel max {mx:.3e} (> {GRAD_MAX_TOL:g}?)"
+# A stored conv output u carries half a bf16 ulp, 2^-9 |u|, and |u| reaches about six standard
+# deviations of its channel: 0.012 of the channel's rms pre-activation from the store alone; the
+# conv's bf16 operands (activations and weights, 2^-9 each) add as much again, and the features of
+# earlier layers arrive with the error accumulated so far (the 2e-2 the output itself is allowed).
+# Decisions with margin below m are a share of about 2 m pdf(0) <= m of all.
+MARGIN = 0.1
+SHARE = 0.02
 
 CFGS = [
     wl.BlockCfg(2, 16, 8, 8, 3, 8, 32),        # small, one 64-pixel tile per image
@@ -44,7 +46,7 @@ def to_bf16_values(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).to(torch.float32).numpy()
 
 
-def run_block_gpu_bf16(dnb, cfg, x0, layer_params, dy, concurrency=None):
+def run_block_gpu_bf16(dnb, cfg, x0, layer_params, dy, concurrency=None, decisions=False):
     h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck,
                              dtype=dnb.DNB_BF16, layout=dnb.DNB_NHWC, schedule=dnb.DNB_SCHED_FUSED, eps=cfg.eps)
     try:
@@ -59,11 +61,17 @@ def run_block_gpu_bf16(dnb, cfg, x0, layer_params, dy, concurrency=None):
         dx0 = torch.full((cfg.n, cfg.h, cfg.w, cfg.c0), float("nan"), dtype=torch.bfloat16, device="cuda")
         dparams = torch.full_like(params, float("nan"))
         dnb.dnb_block_forward(h, x0d, params, y, ws)
+        dec = None
+        if decisions:   # the ReLU decisions the kernels take, in the block's own (NHWC) layout
+            dec = [torch.full((dnb.dnb_block_relu_decision_bytes(h, w),), 7, dtype=torch.uint8, device="cuda") for w in (1, 2)]
+            dnb.dnb_block_relu_decisions(h, params, y, ws, dec[0], dec[1])
         dnb.dnb_block_backward(h, params, y, dyd, dx0, dparams, ws)
         torch.cuda.synchronize()
         back = lambda t: t.float().permute(0, 3, 1, 2).contiguous().cpu().numpy()
         out = {"y": back(y), "dx0": back(dx0), "dparams": dparams.cpu().numpy(),
                "mem": dnb.dnb_block_memory_breakdown(h)}
+        if decisions:
+            out["d1"], out["d2"] = dec[0].cpu().numpy(), dec[1].cpu().numpy()
         out["slices"] = {(l, name): slice(*(lambda o, c: (o, o + c))(*dnb.dnb_block_param_offset(h, l, NAMES.index(name))))
                          for l in range(1, cfg.layers + 1) for name in NAMES}
         return out
@@ -71,20 +79,60 @@ def run_block_gpu_bf16(dnb, cfg, x0, layer_params, dy, concurrency=None):
         dnb.dnb_block_destroy(h)
 
 
+def decisions_nchw(flat, cfg, widths):
+    """The library's decision bytes ((n, h, w, c) per tensor, tensors one after the other) in the
+    oracle's (n, c, h, w) order."""
+    out, o = [], 0
+    for c in widths:
+        cnt = cfg.pixels * c
+        out.append(flat[o:o + cnt].reshape(cfg.n, cfg.h, cfg.w, c).transpose(0, 3, 1, 2).ravel())
+        o += cnt
+    assert o == flat.size
+    return np.concatenate(out)
+
+
+def check_bf16_block(dnb, oracle, cfg, x0, lp, dy, storage_allowance=False):
+    """GPU block against the plain float64 block evaluated with the kernels' ReLU decisions.
+    storage_allowance=False: every tensor within TOL.  True (the full-size blocks: dozens of layers,
+    10^5 pixels): bf16 storage by itself moves single gradient tensors by more than TOL even with
+    identical decisions, so the oracle's storage-rounding variant, under the same decisions,
+    measures that cost tensor by tensor (err_s = its distance from the plain block), and the GPU
+    tensor must lie within err_s + TOL of the plain block on both measures, and within
+    max(TOL, 1.5 err_s) in L2, max(TOL, 2.5 err_s) in the worst element: as close to the plain
+    block as the storage format lets anything be.  The output y keeps TOL outright."""
+    gpu = run_block_gpu_bf16(dnb, cfg, x0, lp, dy, decisions=True)
+    assert set(np.unique(gpu["d1"])) <= {0, 1} and set(np.unique(gpu["d2"])) <= {0, 1}
+    d1 = decisions_nchw(gpu["d1"], cfg, [cfg.c_in(l) for l in range(1, cfg.layers + 1)])
+    d2 = decisions_nchw(gpu["d2"], cfg, [cfg.bottleneck] * cfg.layers)
+    ores, osl, st = run_block_oracle(oracle, cfg, x0, lp, dy, decisions=(d1, d2))
+    stor = run_block_oracle(oracle, cfg, x0, lp, dy, decisions=(d1, d2), bf16_storage=True)[0] if storage_allowance else None
+    assert np.array_equal(gpu["y"][:, :cfg.c0], x0)
+    assert_close(gpu["y"], ores.y, TOL, "y")
+
+    def check(a, r, s_, what):
+        if s_ is None:
+            return assert_close(a, r, TOL, what)
+        (l2, mx), (sl2, smx) = rel_errors(a, r), rel_errors(s_, r)
+        ok = l2 <= sl2 + TOL and mx <= smx + TOL and l2 <= max(TOL, 1.5 * sl2) and mx <= max(TOL, 2.5 * smx)
+        assert ok, f"{what}: rel L2 {l2:.3e} (storage alone {sl2:.3e}), rel max {mx:.3e} (storage alone {smx:.3e})"
+    check(gpu["dx0"], ores.dx0, stor.dx0 if stor else None, "dx0")
+    for l in range(1, cfg.layers + 1):
+        for name in NAMES:
+            sl = osl[(l, name)]
+            check(gpu["dparams"][gpu["slices"][(l, name)]], ores.dparams[sl], stor.dparams[sl] if stor else None,
+                  f"layer {l} d{name}")
+    assert st["margin1"] <= MARGIN and st["margin2"] <= MARGIN, st
+    assert st["count1"] <= SHARE * d1.size and st["count2"] <= SHARE * d2.size, st
+    return gpu
+
+
 @pytest.mark.parametrize("cfg", CFGS, ids=IDS)
 def test_bf16_block_matches_oracle(dnb, oracle, cfg):
     x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
     x0, dy = to_bf16_values(x0), to_bf16_values(dy)
-    gpu = run_block_gpu_bf16(dnb, cfg, x0, lp, dy)
-    plain, _ = run_block_oracle(oracle, cfg, x0, lp, dy)
-    ores, osl = run_block_oracle(oracle, cfg, x0, lp, dy, schedule="naive_bf16")
-    assert np.array_equal(gpu["y"][:, :cfg.c0], x0)
-    assert_close(gpu["y"], plain.y, TOL, "y vs plain float64")
-    assert_close(gpu["y"], ores.y, TOL, "y")
-    assert_grad_close(gpu["dx0"], ores.dx0, "dx0")
-    for l in range(1, cfg.layers + 1):
-        for name in NAMES:
-            assert_grad_close(gpu["dparams"][gpu["slices"][(l, name)]], ores.dparams[osl[(l, name)]], f"layer {l} d{name}")
+    gpu = check_bf16_block(dnb, oracle, cfg, x0, lp, dy)
+    plain, _ = run_block_oracle(oracle, cfg, x0, lp, dy)   # the output also with no decision imposed
+    assert_close(gpu["y"], plain.y, TOL, "y vs the oracle's own decisions")
 
 
 @pytest.mark.parametrize("cfg", [CFGS[1], CFGS[3]], ids=[IDS[1], IDS[3]])
@@ -160,39 +208,17 @@ def test_bf16_backward_is_exactly_linear_in_dy_at_full_size(dnb, which, i):
     assert np.array_equal(2.0 * a["dparams"], b["dparams"])
 
 
-@pytest.mark.parametrize("which", ["config4", "config5"])
-def test_bf16_full_size_last_block(dnb, oracle, which):
-    """The last dense block of the DenseNet-161- and -264-shaped workloads exactly as bench.py
-    times them (batch 32, 7x7; 24 layers, 1056 -> 2208 channels, k = 48, B = 192, and 48 layers,
-    k = 32, B = 128: the ring 1x1 conv, up to nine channel groups in the 1x1 weight gradient, one
-    7-row tile per image in the 3x3's).  y meets the
-    2e-2 bar outright.  At this depth the bf16 block is ill-conditioned in its gradients: a
-    rounding that falls on the other side of a bf16 boundary changes ReLU masks in all later
-    layers.  The emulating oracle shows by how much: re-run with one layer's 1x1 weights perturbed
-    by one part in 1e7 (a thousandth of an fp32 ulp of the activations' bf16 spacing), its own
-    gradients move by 6-9 %.  The HIP path has to be as close to the oracle as the oracle is to
-    that twin: within twice the twin's distance, tensor by tensor."""
-    cfg = (wl.config4() if which == "config4" else wl.config5())[3]
-    x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
+@pytest.mark.parametrize("which,i", [("config4", 0), ("config4", 1), ("config4", 2), ("config4", 3),
+                                     ("config5", 0), ("config5", 1), ("config5", 2), ("config5", 3)])
+def test_bf16_full_size_blocks_match_oracle(dnb, oracle, which, i):
+    """Every dense block of the DenseNet-161- and -264-shaped workloads exactly as bench.py times
+    them (batch 32; 56x56, 28x28, 14x14 and 7x7 images; up to 64 layers, 2688 channels) against the
+    plain float64 oracle, decisions as described at the top, with the allowance for what bf16
+    storage costs by itself (see check_bf16_block)."""
+    cfg = (wl.config4() if which == "config4" else wl.config5())[i]
+    x0, lp, dy = wl.make_block_inputs(cfg, 90 + i, 91 + i, 92 + i, affine="random")
     x0, dy = to_bf16_values(x0), to_bf16_values(dy)
-    gpu = run_block_gpu_bf16(dnb, cfg, x0, lp, dy)
-    ores, osl = run_block_oracle(oracle, cfg, x0, lp, dy, schedule="naive_bf16")
-    lp2 = [dict(p) for p in lp]
-    r = np.random.default_rng(0)
-    lp2[0]["W1"] = (lp2[0]["W1"].astype(np.float64) * (1 + 1e-7 * r.standard_normal(lp2[0]["W1"].shape))).astype(lp2[0]["W1"].dtype)
-    twin, _ = run_block_oracle(oracle, cfg, x0, lp2, dy, schedule="naive_bf16")
-    assert np.array_equal(gpu["y"][:, :cfg.c0], x0)
-    assert_close(gpu["y"], ores.y, TOL, "y")
-
-    def check(a, ref, tw, what):
-        (l2, mx), (tl2, tmx) = rel_errors(a, ref), rel_errors(tw, ref)
-        assert l2 <= max(TOL, 2 * tl2) and mx <= max(GRAD_MAX_TOL, 2 * tmx), \
-            f"{what}: rel L2 {l2:.3e} (twin {tl2:.3e}), rel max {mx:.3e} (twin {tmx:.3e})"
-    check(gpu["dx0"], ores.dx0, twin.dx0, "dx0")
-    for l in range(1, cfg.layers + 1):
-        for name in NAMES:
-            check(gpu["dparams"][gpu["slices"][(l, name)]], ores.dparams[osl[(l, name)]], twin.dparams[osl[(l, name)]],
-                  f"layer {l} d{name}")
+    check_bf16_block(dnb, oracle, cfg, x0, lp, dy, storage_allowance=True)
 
 
 def test_bf16_bytes_and_unsupported_combinations(dnb):

@@ -178,58 +178,62 @@ def test_hip_graph_replays_match_eager(dnb, schedule, concurrency):
     dnb.dnb_block_destroy(h)
 
 
-def full_size_grad_close(a, r, what, elementwise=False):
-    """Gradient comparison at full size.  With ~10^8 pre-activations per block a few dozen lie within
-    fp32 rounding of zero, so their ReLU masks differ between any fp32 evaluation and the float64
-    one; each such element changes a gradient element (or a per-channel sum) by its whole size.
-    The float64 oracle itself moves by rel L2 9e-4 / rel max 2.7e-2 in dx0 when its input is
-    perturbed by 6e-8 relative noise.  So: rel L2 <= 1e-2, worst element <= 1e-1, and for the
-    feature-map gradient (where a differing mask touches few elements, unlike the per-channel
-    sums) at most 2 % of the elements further than 1e-4 * max|ref|.  Blocks where no mask differs
-    (the 8x8 one) agree to 1e-6, and the small-shape tests keep the strict bound."""
-    l2, mx = rel_errors(a, r)
-    far = float((np.abs(a.astype(np.float64) - r) > TOL * np.abs(r).max()).mean()) if elementwise else 0.0
-    assert l2 <= 1e-2 and mx <= 1e-1 and far <= 0.02, f"{what}: rel L2 {l2:.3e}, rel max {mx:.3e}, fraction beyond {TOL:g}: {far:.4f}"
+# A ReLU decision (pre-activation > 0) is an integer decided by floating point.  With ~10^8
+# pre-activations per block a few dozen lie within fp32 rounding of zero; their decisions differ
+# between any fp32 evaluation and the float64 one, and each such element changes a gradient element
+# (or a per-channel sum) by its whole size.  At full size both sides therefore take the decisions in
+# the same precision, the kernel's: the library reports the decisions its kernels took
+# (dnb_block_relu_decisions), the float64 oracle evaluates the block with them, and
+#   (1) every output and gradient tensor meets the strict 1e-4 bound, and
+#   (2) the decisions that differ from the oracle's own are ties within rounding: their margin
+#       |z| / sqrt(gamma^2 + beta^2) (distance from zero in units of the channel's rms
+#       pre-activation) is at most MARGIN, and there are at most SHARE of them.
+# MARGIN: an fp32 pre-activation carries the conv's accumulation error, sqrt(K) 2^-24 with K <= 1710
+# terms = 2.5e-6, plus the statistics' ~1e-6; four times that.  SHARE: decisions with margin below
+# m are a share of about 2 m pdf(0) <= m of all, so at most MARGIN of them can differ.
+MARGIN = 1e-5
+SHARE = 1e-5
+
+
+def compare_with_kernel_decisions(dnb, oracle, cfg, x0, lp, dy, schedule=2):
+    gpu = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=schedule, decisions=True)
+    assert set(np.unique(gpu["d1"])) <= {0, 1} and set(np.unique(gpu["d2"])) <= {0, 1}
+    ores, osl, st = run_block_oracle(oracle, cfg, x0, lp, dy, decisions=(gpu["d1"], gpu["d2"]))
+    compare(gpu, ores, osl, cfg)
+    assert st["margin1"] <= MARGIN and st["margin2"] <= MARGIN, st
+    assert st["count1"] <= SHARE * gpu["d1"].size + 2 and st["count2"] <= SHARE * gpu["d2"].size + 2, st
+    return gpu, ores, st
 
 
 @pytest.mark.parametrize("i", [0, 1, 2])
 def test_full_size_benchmark_blocks_match_oracle(dnb, oracle, i):
     """The benchmark workload at its full size (DenseNet-BC L=100, k=12, batch 64; the three dense
     blocks of 16 layers) in the configuration the benchmark times -- fused schedule, the library's
-    default stream order -- against the oracle's memory-efficient schedule: the output to the
-    strict bound, every gradient to the mask-flip-tolerant one, the byte count exactly."""
+    default stream order -- against the float64 oracle: output, dx0 and every parameter gradient to
+    the strict 1e-4 bound with the ReLU decisions taken in the kernel's precision (and those
+    decisions checked as above); the output also against the oracle's own memory-efficient
+    schedule with no decision imposed; the byte count exactly."""
     cfg = wl.config2(64)[i]
     x0, lp, dy = wl.make_block_inputs(cfg, 10 + i, 20 + i, 30 + i, affine="random")
-    gpu = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=2)
-    ores, osl = run_block_oracle(oracle, cfg, x0, lp, dy, schedule="shared")
-    assert_close(gpu["y"], ores.y, TOL, "y")
-    full_size_grad_close(gpu["dx0"], ores.dx0, "dx0", elementwise=True)
-    for l in range(1, cfg.layers + 1):
-        for name in NAMES:
-            full_size_grad_close(gpu["dparams"][gpu["slices"][(l, name)]], ores.dparams[osl[(l, name)]], f"layer {l} d{name}")
-    assert gpu["peak"] == ores.peak_elems * 4 - (2 * cfg.c_in(cfg.layers) + cfg.bottleneck) * cfg.pixels * 4
+    gpu, _, _ = compare_with_kernel_decisions(dnb, oracle, cfg, x0, lp, dy)
+    plain, _ = run_block_oracle(oracle, cfg, x0, lp, dy, schedule="shared")
+    assert_close(gpu["y"], plain.y, TOL, "y")
+    assert gpu["peak"] == plain.peak_elems * 4 - (2 * cfg.c_in(cfg.layers) + cfg.bottleneck) * cfg.pixels * 4
 
 
-@pytest.mark.parametrize("i", [0, 1, 2])
-def test_bc250_blocks_at_reduced_batch_match_oracle(dnb, oracle, i):
+@pytest.mark.parametrize("i,batch", [(0, 16), (1, 64), (2, 64)])
+def test_bc250_blocks_match_oracle(dnb, oracle, i, batch):
     """The dense blocks of DenseNet-BC L=250, k=24 (41 layers each, 48 -> 1032, 516 -> 1500 and
-    750 -> 1734 channels, B = 96) with every kernel shape of the full workload except the pixel
-    count: batch 4 instead of 64, which the oracle finishes in seconds.  Fused schedule, default
-    stream order; the output to the strict bound, gradients to the mask-flip-tolerant L2 / worst
-    element bounds of the full-size DenseNet-BC-100 blocks.  Their third criterion (at most 2 % of
-    dx0's elements further than 1e-4 of the largest) does not carry over to 41 layers: the float64
-    oracle itself moves 2.4 % of them that far (rel L2 4.6e-4) when its input is perturbed by 6e-8
-    relative noise once, and fp32 rounds in every layer."""
-    cfg = wl.config3(4)[i]
+    750 -> 1734 channels, B = 96), fused schedule, default stream order, to the strict 1e-4 bound
+    with the ReLU decisions taken in the kernel's precision.  The second and third block at the
+    workload's full batch of 64; the first (32x32 images) at batch 16, which the oracle finishes
+    in under a minute -- its kernels at the full pixel count are covered one by one in
+    test_gpu_ops.py."""
+    cfg = wl.config3(batch)[i]
     x0, lp, dy = wl.make_block_inputs(cfg, 40 + i, 50 + i, 60 + i, affine="random")
-    gpu = run_block_gpu(dnb, cfg, x0, lp, dy, schedule=2)
-    ores, osl = run_block_oracle(oracle, cfg, x0, lp, dy, schedule="shared")
-    assert_close(gpu["y"], ores.y, TOL, "y")
-    full_size_grad_close(gpu["dx0"], ores.dx0, "dx0")
-    for l in range(1, cfg.layers + 1):
-        for name in NAMES:
-            full_size_grad_close(gpu["dparams"][gpu["slices"][(l, name)]], ores.dparams[osl[(l, name)]], f"layer {l} d{name}")
-    assert gpu["peak"] == ores.peak_elems * 4 - (2 * cfg.c_in(cfg.layers) + cfg.bottleneck) * cfg.pixels * 4
+    gpu, ores, _ = compare_with_kernel_decisions(dnb, oracle, cfg, x0, lp, dy)
+    m, k, B = cfg.layers, cfg.growth, cfg.bottleneck
+    assert gpu["peak"] == (m * B + m * k + cfg.c_out + cfg.c_in(m) + B) * cfg.pixels * 4
 
 
 @pytest.mark.parametrize("which", ["config2", "config3"])

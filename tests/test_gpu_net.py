@@ -41,15 +41,40 @@ def test_net_schedules_agree_and_replays_are_deterministic(dnb, oracle):
     assert np.array_equal(a[3], b[3]) and np.array_equal(a[4], b[4]) and np.array_equal(a[4], c[4])
 
 
-def test_full_size_bc100_step_matches_oracle(dnb, oracle):
-    """DenseNet-BC L=100 k=12 at batch 64 in the benchmarked configuration (fused schedule): loss
-    and logits to the strict bound; gradients to the mask-flip-tolerant bound used for the
-    full-size blocks (a few ReLU masks within fp32 rounding of zero differ from float64)."""
-    cfg = wl.net_config2(64)
+def test_net_with_sixteen_layers_per_block_at_small_batch(dnb, oracle):
+    """Depth 100 (16 layers per block): the input of the second block (108 channels at 16x16) is
+    larger than that of the first (24 channels at 32x32), so the buffers the blocks share for their
+    input gradients must be sized for it (tests/test_host_api.py checks every piece of the plan).
+    Strict parity of the whole step at batch 2; the harness also checks that nothing is written
+    behind the workspace."""
+    cfg = wl.NetCfg(2, 32, 100, 12, 10)
     x, labels, params = wl.make_net_inputs(cfg, affine="random")
     s, flat, loss, logits, dp = run_net_gpu(dnb, oracle, cfg, x, labels, params, 2)
     oloss, odp, ologits = oracle.net_step(s, x, labels, flat)
     assert abs(loss - oloss) <= TOL * abs(oloss)
     assert_close(logits, ologits, TOL, "logits")
-    l2, mx = rel_errors(dp, odp)
-    assert l2 <= 1e-2 and mx <= 1e-1, (l2, mx)
+    for name, sl in oracle.net_param_slices(s).items():
+        assert_close(dp[sl], odp[sl], TOL, f"d{name}")
+
+
+def test_full_size_bc100_step_matches_oracle(dnb, oracle):
+    """DenseNet-BC L=100 k=12 at batch 64 in the benchmarked configuration (fused schedule): loss,
+    logits and the gradient of every parameter tensor to the strict 1e-4 bound, with the ReLU
+    decisions taken in the kernel's precision (the library reports the decisions its kernels took,
+    the float64 oracle evaluates the step with them; see test_gpu_block.py), and the decisions that
+    differ from the oracle's own checked to be ties within fp32 rounding.  Loss and logits also
+    against the oracle's step with no decision imposed."""
+    from test_gpu_block import MARGIN, SHARE
+    cfg = wl.net_config2()
+    x, labels, params = wl.make_net_inputs(cfg, affine="random")
+    s, flat, loss, logits, dp, dec = run_net_gpu(dnb, oracle, cfg, x, labels, params, 2, decisions=True)
+    assert dec.size == oracle.net_decision_count(s) and set(np.unique(dec)) <= {0, 1}
+    oloss, odp, ologits, st = oracle.net_step_with_decisions(s, x, labels, flat, dec)
+    assert abs(loss - oloss) <= TOL * abs(oloss)
+    assert_close(logits, ologits, TOL, "logits")
+    for name, sl in oracle.net_param_slices(s).items():
+        assert_close(dp[sl], odp[sl], TOL, f"d{name}")
+    assert st["margin"] <= MARGIN and st["count"] <= SHARE * dec.size + 2, st
+    ploss, _, plogits = oracle.net_step(s, x, labels, flat, backward=False)
+    assert abs(loss - ploss) <= TOL * abs(ploss)
+    assert_close(logits, plogits, TOL, "logits vs the oracle's own decisions")

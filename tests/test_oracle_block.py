@@ -401,3 +401,81 @@ def test_bf16_storage_block_matches_autograd_with_casts(oracle, cfg):
     # and it is a small perturbation of the unrounded block
     plain = oracle.block(s, x0q.numpy(), params, dyq.numpy(), schedule="naive")
     assert np.linalg.norm(res.y - plain.y) / np.linalg.norm(plain.y) < 1e-2
+
+
+# --------------------------------------------------- ReLU decisions written out / taken from the caller
+
+def torch_block_with_decisions(x0, lp, cfg, dy, m1, m2):
+    """The block under autograd with each ReLU replaced by a multiplication with a given 0/1
+    tensor (forward a = z * decision, hence backward dz = da * decision)."""
+    x0t = torch.tensor(x0, dtype=torch.float64, requires_grad=True)
+    tp = [{k: torch.tensor(np.asarray(v, dtype=np.float64), requires_grad=True) for k, v in p.items()} for p in lp]
+    feats = [x0t]
+    o1 = 0
+    P = cfg.n * cfg.h * cfg.w
+    for l, p in enumerate(tp, start=1):
+        u = torch.cat(feats, dim=1)
+        c = u.shape[1]
+        d1 = torch.tensor(m1[o1:o1 + c * P].reshape(cfg.n, c, cfg.h, cfg.w).astype(np.float64))
+        o1 += c * P
+        a = F.batch_norm(u, None, None, p["g1"], p["b1"], True, 0.0, cfg.eps) * d1
+        if cfg.bottleneck:
+            B = cfg.bottleneck
+            b = F.conv2d(a, p["W1"][:, :, None, None])
+            d2 = torch.tensor(m2[(l - 1) * B * P:l * B * P].reshape(cfg.n, B, cfg.h, cfg.w).astype(np.float64))
+            a = F.batch_norm(b, None, None, p["g2"], p["b2"], True, 0.0, cfg.eps) * d2
+        feats.append(F.conv2d(a, p["W3"], padding=1))
+    y = torch.cat(feats, dim=1)
+    (y * torch.tensor(dy, dtype=torch.float64)).sum().backward()
+    return y.detach().numpy(), x0t.grad.numpy(), tp
+
+
+@pytest.mark.parametrize("cfg", [wl.config1(), wl.BlockCfg(3, 5, 5, 7, 3, 4, 0), wl.BlockCfg(2, 3, 6, 4, 3, 5, 7)])
+def test_block_with_given_relu_decisions(oracle, cfg):
+    """(1) The decisions the block writes out are its own z > 0, and feeding them back reproduces
+    the plain block bit for bit with no disagreement reported.  (2) With arbitrary decisions (a
+    twentieth of them inverted) the block equals float64 autograd of the same network with every
+    ReLU replaced by a multiplication with the given 0/1 tensor, and the number of disagreements
+    reported is the number inverted.  (3) The reported margin |z| / sqrt(gamma^2 + beta^2) of the
+    worst disagreement, recomputed here for the first layer's first BN from library batch norm."""
+    s, x0, params, dy, lp = setup(oracle, cfg)
+    plain = oracle.block(s, x0, params, dy)
+    own, (m1, m2) = oracle.block_with_decisions(s, x0, params, dy)
+    n1, n2 = oracle.relu_decision_counts(s)
+    assert m1.size == n1 and m2.size == n2 and set(np.unique(m1)) <= {0, 1}
+    for a, b in ((own.y, plain.y), (own.dx0, plain.dx0), (own.dparams, plain.dparams)):
+        assert np.array_equal(a, b)
+    # first layer's decisions against library batch norm
+    z1 = F.batch_norm(torch.tensor(x0), None, None, torch.tensor(lp[0]["g1"].astype(np.float64)),
+                      torch.tensor(lp[0]["b1"].astype(np.float64)), True, 0.0, cfg.eps).numpy()
+    assert np.array_equal(m1[:x0.size].reshape(x0.shape), (z1 > 0).astype(np.uint8))
+    back, st = oracle.block_with_decisions(s, x0, params, dy, (m1, m2))
+    assert st == dict(count1=0, margin1=0.0, count2=0, margin2=0.0)
+    for a, b in ((back.y, plain.y), (back.dx0, plain.dx0), (back.dparams, plain.dparams)):
+        assert np.array_equal(a, b)
+
+    r = np.random.default_rng(5)
+    f1, f2 = r.random(n1) < 0.05, r.random(n2) < 0.05
+    g1, g2 = m1 ^ f1.astype(np.uint8), m2 ^ f2.astype(np.uint8)
+    res, st = oracle.block_with_decisions(s, x0, params, dy, (g1, g2))
+    y, dx0, tp = torch_block_with_decisions(x0, lp, cfg, dy, g1, g2)
+    np.testing.assert_allclose(res.y, y, atol=1e-11)
+    np.testing.assert_allclose(res.dx0, dx0, atol=1e-10)
+    for l, p in enumerate(tp, start=1):
+        for name, t in p.items():
+            got = res.dparams[oracle.param_slice(s, l, NAMES.index(name))]
+            np.testing.assert_allclose(got, t.grad.numpy().ravel(), atol=1e-9, err_msg=f"layer {l} {name}")
+    assert not np.allclose(res.dx0, plain.dx0, atol=1e-6)   # the inverted decisions do matter
+    # With decisions imposed, every later pre-activation moves, so only a one-layer block's first BN
+    # has a count known beforehand; its worst margin is recomputed here.
+    cfg1 = wl.BlockCfg(cfg.n, cfg.c0, cfg.h, cfg.w, 1, cfg.growth, cfg.bottleneck, cfg.eps)
+    s1, x0, params1, dy1, lp1 = setup(oracle, cfg1)
+    _, (q1, q2) = oracle.block_with_decisions(s1, x0, params1, dy1)
+    flip = r.random(q1.size) < 0.05
+    _, st1 = oracle.block_with_decisions(s1, x0, params1, dy1, (q1 ^ flip.astype(np.uint8), q2))
+    assert st1["count1"] == int(flip.sum())
+    z1 = F.batch_norm(torch.tensor(x0), None, None, torch.tensor(lp1[0]["g1"].astype(np.float64)),
+                      torch.tensor(lp1[0]["b1"].astype(np.float64)), True, 0.0, cfg.eps).numpy()
+    rms = np.sqrt(lp1[0]["g1"].astype(np.float64) ** 2 + lp1[0]["b1"].astype(np.float64) ** 2)
+    margin = (np.abs(z1) / rms[None, :, None, None])[flip.reshape(x0.shape)].max()
+    assert abs(st1["margin1"] - margin) <= 1e-9 * margin
