@@ -189,6 +189,17 @@ size_t dnb_op_bn_scratch_bytes(int64_t n, int64_t c, int64_t hw);
 /* BN batch statistics per channel: mean and 1/sqrt(biased var + eps). */
 int dnb_op_bn_stats(const void* x, int64_t stride, int64_t n, int64_t c, int64_t hw, float eps,
                     void* mean, void* istd, void* scratch, void* stream);
+/* dnb_op_bn_stats for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same kernels and results, but the
+ * split-reduction partials live in a 256 KiB device array inside the library instead of a
+ * caller's scratch buffer.  The call allocates and frees nothing.  DNB_E_RANGE if the shape needs
+ * more than 256 KiB of partials (12 bytes per channel and image split: every shape up to 1024
+ * channels fits, and up to 21845 channels with one split).
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ * streams) race and must be ordered by the caller.  The array's device address is looked up on
+ * the first call on each device (not while that call's stream is being captured). */
+int dnb_op_bn_stats_static(const void* x, int64_t stride, int64_t n, int64_t c, int64_t hw, float eps,
+                           void* mean, void* istd, void* stream);
 /* out = max(0, gamma*(x-mean)*istd + beta) (BN apply with in-place ReLU, Section 3). */
 int dnb_op_bn_relu(const void* x, int64_t x_stride, void* out, int64_t out_stride, int64_t n,
                    int64_t c, int64_t hw, const void* gamma, const void* beta, const void* mean,

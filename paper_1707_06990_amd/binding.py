@@ -66,6 +66,7 @@ _SIGS = {
     "dnb_op_copy_slab": (C.c_int, [_vp, _i64, _vp, _i64, _i64, _i64, _vp]),
     "dnb_op_bn_scratch_bytes": (_sz, [_i64, _i64, _i64]),
     "dnb_op_bn_stats": (C.c_int, [_vp, _i64, _i64, _i64, _i64, C.c_float, _vp, _vp, _vp, _vp]),
+    "dnb_op_bn_stats_static": (C.c_int, [_vp, _i64, _i64, _i64, _i64, C.c_float, _vp, _vp, _vp]),
     "dnb_op_bn_relu": (C.c_int, [_vp, _i64, _vp, _i64, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _vp]),
     "dnb_op_bn_relu_backward": (C.c_int, [_vp, _i64, _vp, _i64, _vp, _i64, C.c_int, _i64, _i64, _i64,
                                           _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
@@ -215,6 +216,10 @@ def dnb_op_bn_scratch_bytes(n, c, hw) -> int:
 def dnb_op_bn_stats(x, stride, n, c, hw, eps, mean, istd, scratch, stream=None) -> None:
     _check(_lib.dnb_op_bn_stats(_ptr(x), stride, n, c, hw, eps, _ptr(mean), _ptr(istd), _ptr(scratch),
                                 _stream(stream)))
+
+
+def dnb_op_bn_stats_static(x, stride, n, c, hw, eps, mean, istd, stream=None) -> None:
+    _check(_lib.dnb_op_bn_stats_static(_ptr(x), stride, n, c, hw, eps, _ptr(mean), _ptr(istd), _stream(stream)))
 
 
 def dnb_op_bn_relu(x, x_stride, out, out_stride, n, c, hw, gamma, beta, mean, istd, stream=None) -> None:

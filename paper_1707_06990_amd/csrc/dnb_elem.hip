@@ -6,6 +6,9 @@
 // workgroup.
 #include <hip/hip_ext.h>
 
+#include <mutex>
+
+#include "../../include/dnb.h"
 #include "dnb_internal.h"
 #include "dnb_stats.h"
 
@@ -404,3 +407,46 @@ hipError_t launch_bn_relu_bwd(const float* x, int64_t x_stride, const float* dac
 }
 
 }  // namespace dnb
+
+// ---- BN statistics for callers that cannot allocate device memory (code under HIP graph
+// capture, serving loops, harnesses that forbid it): same kernels as dnb_op_bn_stats, with the
+// split-reduction partials in a file-scope device array instead of a caller's buffer.  Every GPU
+// the library runs on holds its own copy of the array (at its own address) until the process ends.
+namespace {
+constexpr size_t kStaticScratchFloats = (size_t)1 << 16;  // 256 KiB
+__device__ __align__(256) float scratch[kStaticScratchFloats];
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices];  // device address of `scratch` per device; null until looked up
+std::mutex g_scratch_mutex;
+
+// The array's name is only a host-side stand-in: its device address is looked up once per device,
+// with that device current, and that pointer is what kernels and copies get.
+int static_scratch(float** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return DNB_E_LAUNCH;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return DNB_E_LAUNCH;
+    g_scratch_ptr[dev] = (float*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return DNB_OK;
+}
+}  // namespace
+
+extern "C" int dnb_op_bn_stats_static(const void* x, int64_t stride, int64_t n, int64_t c, int64_t hw, float eps,
+                                      void* mean, void* istd, void* stream) {
+  if (!x || !mean || !istd) return DNB_E_NULL;
+  if (n < 1 || c < 1 || hw < 1 || c > 65535 || n > 65535 || hw > ((int64_t)1 << 30)) return DNB_E_RANGE;
+  if (dnb::bn_stats_partial_floats((int)n, (int)c, (int)hw) > kStaticScratchFloats) return DNB_E_RANGE;
+  float* part = nullptr;
+  const int rc = static_scratch(&part);
+  if (rc != DNB_OK) return rc;
+  // every (channel, split) slot the finalisation reads is written by the partial kernel of this
+  // call, so nothing of an earlier call's contents has to be cleared
+  if (dnb::launch_bn_stats((const float*)x, stride, (int)n, (int)c, (int)hw, eps, (float*)mean, (float*)istd, part,
+                           (hipStream_t)stream) != hipSuccess)
+    return DNB_E_LAUNCH;
+  return DNB_OK;
+}
