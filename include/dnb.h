@@ -258,13 +258,16 @@ int dnb_op_conv_bnrelu_wgrad(const void* x, int64_t x_stride, const void* fold, 
  * h, w) with image stride g_stride; fold1 (cin pairs), fold2 (B pairs) as above.  If bn_dact is
  * not null the launch also carries the reduction pass of the layer's first BN backward over
  * x1[:, :cin] and bn_dact (n, cin, h, w) (bn_gamma, bn_beta, bn_mean, bn_istd: cin floats each;
- * its partial sums stay in scratch).  The two small kernels that add the weight gradients'
+ * its partial sums stay in scratch, at byte offset dnb_op_layer_wgrads_bn_partials_offset, where
+ * dnb_op_bn_relu_backward_apply finds them when given scratch + that offset).  The two small kernels that add the weight gradients'
  * partial sums follow the launch; ev_start / ev_stop are stamped around the launch itself.
  * scratch: dnb_op_layer_wgrads_scratch_bytes.  DNB_E_UNSUPPORTED unless B >= 48, the image is
  * 16-byte friendly (h*w % 4 == 0, w % 4 == 0) and (B, k) is a combination the paired kernel
  * is built for ((48, <=16) or (>=32 with two 16-channel tiles each way)). */
 size_t dnb_op_layer_wgrads_scratch_bytes(int64_t n, int64_t cin, int64_t bottleneck, int64_t growth, int64_t h,
                                          int64_t w);
+size_t dnb_op_layer_wgrads_bn_partials_offset(int64_t n, int64_t cin, int64_t bottleneck, int64_t growth, int64_t h,
+                                              int64_t w);
 int dnb_op_layer_wgrads(const void* x1, int64_t x1_stride, const void* fold1, const void* db, void* dw1, int64_t cin,
                         const void* b, const void* fold2, const void* g, int64_t g_stride, void* dw3, int64_t n,
                         int64_t bottleneck, int64_t growth, int64_t h, int64_t w, const void* bn_dact,

@@ -80,6 +80,7 @@ _SIGS = {
     "dnb_op_conv_bnrelu_wgrad": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _vp, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp,
                                            _vp, _vp, _vp]),
     "dnb_op_layer_wgrads_scratch_bytes": (_sz, [_i64, _i64, _i64, _i64, _i64, _i64]),
+    "dnb_op_layer_wgrads_bn_partials_offset": (_sz, [_i64, _i64, _i64, _i64, _i64, _i64]),
     "dnb_op_layer_wgrads": (C.c_int, [_vp, _i64, _vp, _vp, _vp, _i64, _vp, _vp, _vp, _i64, _vp, _i64, _i64, _i64, _i64,
                                       _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "dnb_op_conv_dgrad": (C.c_int, [_vp, _i64, _vp, _vp, _i64, _i64, _i64, _i64, _i64, _i64, C.c_int, _vp, _vp]),
@@ -288,6 +289,10 @@ def dnb_op_conv_dgrad(dout, dout_stride, wgt, din, din_stride, n, cin, cout, h, 
 
 def dnb_op_layer_wgrads_scratch_bytes(n, cin, bottleneck, growth, h, w) -> int:
     return int(_lib.dnb_op_layer_wgrads_scratch_bytes(n, cin, bottleneck, growth, h, w))
+
+
+def dnb_op_layer_wgrads_bn_partials_offset(n, cin, bottleneck, growth, h, w) -> int:
+    return int(_lib.dnb_op_layer_wgrads_bn_partials_offset(n, cin, bottleneck, growth, h, w))
 
 
 def dnb_op_layer_wgrads(x1, x1_stride, fold1, db, dw1, cin, b, fold2, g, g_stride, dw3, n, bottleneck, growth, h, w,

@@ -1091,6 +1091,13 @@ size_t dnb_op_layer_wgrads_scratch_bytes(int64_t n, int64_t cin, int64_t B, int6
   return f * sizeof(float);
 }
 
+size_t dnb_op_layer_wgrads_bn_partials_offset(int64_t n, int64_t cin, int64_t B, int64_t k, int64_t h, int64_t w) {
+  if (n < 1 || cin < 1 || B < 1 || k < 1 || h < 1 || w < 1) return 0;
+  const size_t f = ((conv_wgrad_partial_floats((int)n, (int)cin, (int)B, (int)h, (int)w, 1) + 3) & ~(size_t)3) +
+                   ((conv_wgrad_partial_floats((int)n, (int)B, (int)k, (int)h, (int)w, 9) + 3) & ~(size_t)3);
+  return f * sizeof(float);
+}
+
 int dnb_op_layer_wgrads(const void* x1, int64_t x1_stride, const void* fold1, const void* db, void* dw1, int64_t cin,
                         const void* bact, const void* fold2, const void* g, int64_t g_stride, void* dw3, int64_t n,
                         int64_t B, int64_t k, int64_t h, int64_t w, const void* bn_dact, const void* bn_gamma,

@@ -219,38 +219,97 @@ def test_fused_conv_bnrelu_wgrad(dnb, oracle, n, cin, cout, h, w, ks):
     assert_close(dw.cpu().numpy(), oracle.conv_wgrad(a, g, ks), TOL, "fused wgrad")
 
 
-@pytest.mark.parametrize("n,cin,B,k,h,w,with_bn", [(4, 72, 48, 12, 16, 16, True), (2, 40, 96, 24, 8, 8, False),
-                                                   (3, 24, 48, 12, 8, 12, True)])
-def test_layer_weight_gradients_in_one_launch(dnb, oracle, n, cin, B, k, h, w, with_bn):
-    """Both weight gradients of a bottleneck layer (BN+ReLU of their activation operands recomputed
-    in the operand loads) from the launch the one-stream backward pass uses, with and without the
-    BN backward reduction riding along; each against the oracle's weight gradient."""
-    r = rng(31)
+def away_from_zero(x, scale, shift, margin=1e-3):
+    """x (n, c, h, w) with every element whose pre-activation x*scale_c + shift_c lies within
+    `margin` of zero moved so that it lies 2*margin away: the ReLU decisions of such inputs are the
+    same in any precision, so an element-wise comparison needs no allowance for ties."""
+    x = x.astype(np.float64)
+    sc, sh = scale.astype(np.float64)[None, :, None, None], shift.astype(np.float64)[None, :, None, None]
+    z = x * sc + sh
+    near = np.abs(z) < margin
+    target = np.where(z >= 0, 2 * margin, -2 * margin)
+    x = np.where(near, (target - sh) / sc, x)
+    return x.astype(np.float32)
+
+
+def layer_wgrads_case(dnb, oracle, n, cin, B, k, h, w, with_bn, seed=31):
+    r = rng(seed)
     c_tot = cin + 8                                  # the slab is wider than the layer's input
+    hw = h * w
+    fold1 = f32(np.stack([1.0 + 0.3 * r.standard_normal(cin), 0.3 * r.standard_normal(cin)], axis=1))
+    fold2 = f32(np.stack([1.0 + 0.3 * r.standard_normal(B), 0.3 * r.standard_normal(B)], axis=1))
+    gamma, beta = f32(1.0 + 0.1 * r.standard_normal(cin)), f32(0.1 * r.standard_normal(cin))
+    mean, istd = f32(0.1 * r.standard_normal(cin)), f32(1.0 + 0.1 * r.random(cin))
     y = f32(r.standard_normal((n, c_tot, h, w)))
+    if with_bn:   # the BN reduction decides dz = dact * [z > 0] per element: keep every z away from zero
+        scale = gamma.astype(np.float64) * istd
+        y[:, :cin] = away_from_zero(y[:, :cin], scale, beta - mean * scale)
     db = f32(r.standard_normal((n, B, h, w)))
     b = f32(r.standard_normal((n, B, h, w)))
     g_slab = f32(r.standard_normal((n, k + 4, h, w)))  # g is a channel slice of a wider slab
-    fold1 = f32(np.stack([1.0 + 0.3 * r.standard_normal(cin), 0.3 * r.standard_normal(cin)], axis=1))
-    fold2 = f32(np.stack([1.0 + 0.3 * r.standard_normal(B), 0.3 * r.standard_normal(B)], axis=1))
-    hw = h * w
     dw1 = torch.full((B, cin, 1, 1), float("nan"), device="cuda")
     dw3 = torch.full((k, B, 3, 3), float("nan"), device="cuda")
     scratch = torch.empty(dnb.dnb_op_layer_wgrads_scratch_bytes(n, cin, B, k, h, w), dtype=torch.uint8, device="cuda")
-    d_g = dev(g_slab)
+    scratch.fill_(0xFF)
+    d_g, d_y = dev(g_slab), dev(y)
     g_view = d_g[:, 4:]                              # channels 4.., image stride (k + 4) * hw
     bn = {}
     if with_bn:
-        bn = dict(bn_dact=dev(f32(r.standard_normal((n, cin, h, w)))), bn_gamma=dev(f32(1.0 + 0.1 * r.standard_normal(cin))),
-                  bn_beta=dev(f32(0.1 * r.standard_normal(cin))), bn_mean=dev(f32(0.1 * r.standard_normal(cin))),
-                  bn_istd=dev(f32(1.0 + 0.1 * r.random(cin))))
-    dnb.dnb_op_layer_wgrads(dev(y), c_tot * hw, dev(fold1), dev(db), dw1, cin, dev(b), dev(fold2), g_view, (k + 4) * hw,
+        dact = f32(r.standard_normal((n, cin, h, w)))
+        bn = dict(bn_dact=dev(dact), bn_gamma=dev(gamma), bn_beta=dev(beta), bn_mean=dev(mean), bn_istd=dev(istd))
+    dnb.dnb_op_layer_wgrads(d_y, c_tot * hw, dev(fold1), dev(db), dw1, cin, dev(b), dev(fold2), g_view, (k + 4) * hw,
                             dw3, n, B, k, h, w, scratch, **bn)
     torch.cuda.synchronize()
     act = lambda x, f: np.maximum(x.astype(np.float64) * f[:, 0].astype(np.float64)[None, :, None, None]
                                   + f[:, 1].astype(np.float64)[None, :, None, None], 0.0)
     assert_close(dw1.cpu().numpy(), oracle.conv_wgrad(act(y[:, :cin], fold1), db, 1), TOL, "1x1 weight gradient")
     assert_close(dw3.cpu().numpy(), oracle.conv_wgrad(act(b, fold2), g_slab[:, 4:], 3), TOL, "3x3 weight gradient")
+    if with_bn:
+        # the third output of the launch: the partial sums of the BN backward reduction, finished by
+        # the element-wise pass (which reads them where the launch left them)
+        off = dnb.dnb_op_layer_wgrads_bn_partials_offset(n, cin, B, k, h, w)
+        du = torch.full((n, cin, h, w), float("nan"), device="cuda")
+        dg, dbt = torch.full((cin,), float("nan"), device="cuda"), torch.full((cin,), float("nan"), device="cuda")
+        dnb.dnb_op_bn_relu_backward_apply(d_y, c_tot * hw, bn["bn_dact"], cin * hw, du, cin * hw, 0, n, cin, hw, bn["bn_gamma"],
+                                          bn["bn_beta"], bn["bn_mean"], bn["bn_istd"], dg, dbt, scratch.data_ptr() + off)
+        torch.cuda.synchronize()
+        # the oracle's BN backward takes (mean, var): the given 1/sqrt(var + eps) with eps = 0
+        var = 1.0 / istd.astype(np.float64) ** 2
+        x1 = y[:, :cin].astype(np.float64)
+        z = gamma.astype(np.float64)[None, :, None, None] * (x1 - mean.astype(np.float64)[None, :, None, None]) \
+            * istd.astype(np.float64)[None, :, None, None] + beta.astype(np.float64)[None, :, None, None]
+        dz = oracle.relu_backward(oracle.relu(z), dact)
+        odu, odg, odb = oracle.bn_backward(x1, dz, gamma, mean, var, 0.0)
+        assert_close(dg.cpu().numpy(), odg, TOL, "BN dgamma from the launch's partial sums")
+        assert_close(dbt.cpu().numpy(), odb, TOL, "BN dbeta from the launch's partial sums")
+        assert_close(du.cpu().numpy(), odu, TOL, "BN du")
+
+
+@pytest.mark.parametrize("n,cin,B,k,h,w,with_bn", [(4, 72, 48, 12, 16, 16, True), (2, 40, 96, 24, 8, 8, False),
+                                                   (3, 24, 48, 12, 8, 12, True)])
+def test_layer_weight_gradients_in_one_launch(dnb, oracle, n, cin, B, k, h, w, with_bn):
+    """All outputs of the launch the one-stream backward pass uses for a bottleneck layer: both
+    weight gradients (BN+ReLU of their activation operands recomputed in the operand loads) against
+    the oracle's weight gradient, and, when the BN backward reduction rides along, its partial
+    sums -- finished by the element-wise pass -- against the oracle's BN backward (dgamma, dbeta, du)."""
+    layer_wgrads_case(dnb, oracle, n, cin, B, k, h, w, with_bn)
+
+
+@pytest.mark.parametrize("cin,B,k", [(60, 48, 12), (204, 48, 12), (264, 96, 24), (1008, 96, 24)])
+def test_layer_weight_gradients_at_benchmark_pixel_counts(dnb, oracle, cin, B, k):
+    """The same launch at the pixel count the benchmarks run it at (batch 64, 32x32 images: the
+    first dense block of DenseNet-BC-100 and -250, narrowest and widest layers): long pixel ranges
+    per workgroup, all its roles, strict bound on every output."""
+    layer_wgrads_case(dnb, oracle, 64, cin, B, k, 32, 32, True, seed=41)
+
+
+@pytest.mark.parametrize("n,cin,cout,h,w,ks", [(64, 60, 48, 32, 32, 1), (64, 204, 48, 32, 32, 1), (64, 264, 96, 32, 32, 1),
+                                               (64, 1008, 96, 32, 32, 1), (64, 48, 12, 32, 32, 3), (64, 96, 24, 32, 32, 3),
+                                               (64, 1476, 96, 16, 16, 1), (64, 516, 1032, 16, 16, 1)])
+def test_conv_ops_at_benchmark_pixel_counts(dnb, oracle, n, cin, cout, h, w, ks):
+    """Forward, data gradient and weight gradient of the block's convolutions (and the widest
+    transition conv) at the benchmarks' full pixel counts, strict bound."""
+    test_conv_forward_dgrad_wgrad(dnb, oracle, n, cin, cout, h, w, ks)
 
 
 def test_layer_weight_gradients_reports_unbuilt_pairs(dnb):
