@@ -26,10 +26,9 @@
  *     synchronously.
  *   - Tensors are dense, row-major, in the layout named by the descriptor:
  *     NCHW (n, c, h, w) or NHWC (n, h, w, c).
- *   - Built combinations: DNB_F32 + DNB_NCHW with every schedule (and bottleneck = 0
- *     with the shared and store-all schedules); DNB_BF16 + DNB_NHWC with
- *     DNB_SCHED_FUSED (c0, growth, bottleneck multiples of 8).  Others return
- *     DNB_E_UNSUPPORTED from dnb_block_create.
+ *   - Built combinations: DNB_F32 + DNB_NCHW and DNB_BF16 + DNB_NHWC, each with every schedule
+ *     (bf16: c0, growth, bottleneck multiples of 8); bottleneck = 0 with DNB_F32 and the shared
+ *     and store-all schedules.  Others return DNB_E_UNSUPPORTED from dnb_block_create.
  *   - DNB_BF16: x0, y, dy, dx0 are bfloat16 (2 bytes per element).  params and dparams
  *     stay fp32 in the same pack layout (conv weights are rounded to bf16 when the
  *     forward packs them; parameter gradients are fp32 sums); BN statistics and all

@@ -124,10 +124,13 @@ hipError_t launch_relu_decisions(const float* u, int64_t stride, int n, int c, i
 
 namespace {
 
-// ---- bf16 / NHWC, fused schedule.  x0, y, dy, dx0 and the kept b_l are bf16 with channels
-// contiguous; y's pixel stride is C_out, so layer l reads y[..., :C_l] in place and writes its k
-// new channels into y[..., C_l:C_l+k].  The gradient slab G is fp32 (it is accumulated into up to
-// m times); dS2 / dS3 are bf16.  Everything runs on the caller's stream in program order.
+// ---- bf16 / NHWC.  x0, y, dy, dx0 and the kept b_l are bf16 with channels contiguous; y's pixel
+// stride is C_out, so layer l reads y[..., :C_l] in place and writes its k new channels into
+// y[..., C_l:C_l+k].  The gradient slab G is fp32 (it is accumulated into up to m times); dS2 /
+// dS3 are bf16.  Fused schedule: BN+ReLU inside the convolutions' operand loads.  Shared and
+// store-everything schedules (Sections 4 and 3): the concatenation is copied to storage 1, its
+// BN+ReLU written to storage 2, the bottleneck's to storage 3, and the convolutions read those;
+// the values are the ones the fused schedule forms on the fly, so all three give the same bits.
 int forward_bf16(dnb_block* b, const void* x0, const float* params, void* yv, char* ws, hipStream_t st) {
   const dnb_block_desc& d = b->d;
   const int n = d.n, m = d.layers, k = d.growth, B = d.bottleneck, cout = b->cout;
@@ -156,9 +159,20 @@ int forward_bf16(dnb_block* b, const void* x0, const float* params, void* yv, ch
     const unsigned short* pk3 = pk1 + B16 * c32 + c16 * B32;       // 3x3 forward
     int T1 = 0, T3 = 0;
     DNB_TRY(launch_bn_fold(p.g1, p.b1, mean_y, istd_y, part, freshT, fresh_lo, fresh_hi, d.eps, c, fold1, st));
-    DNB_TRY(nhwc::conv(y, cout, false, pk1, bl, B, n, c, B, d.h, d.w, 1, fold1, part, &T1, st));
-    DNB_TRY(launch_bn_fold(p.g2, p.b2, mean_b, istd_b, part, T1, 0, B, d.eps, B, fold2, st));
-    DNB_TRY(nhwc::conv(bl, B, false, pk3, y + c, cout, n, B, k, d.h, d.w, 9, fold2, part, &T3, st));
+    if (d.schedule == DNB_SCHED_FUSED) {
+      DNB_TRY(nhwc::conv(y, cout, false, pk1, bl, B, n, c, B, d.h, d.w, 1, fold1, part, &T1, st));
+      DNB_TRY(launch_bn_fold(p.g2, p.b2, mean_b, istd_b, part, T1, 0, B, d.eps, B, fold2, st));
+      DNB_TRY(nhwc::conv(bl, B, false, pk3, y + c, cout, n, B, k, d.h, d.w, 9, fold2, part, &T3, st));
+    } else {
+      void* S1 = ws + b->off_u[l];
+      void* S2 = ws + b->off_a[l];
+      void* S3 = ws + b->off_a2[l];
+      DNB_TRY(nhwc::bn_relu_rows(y, cout, fold1, S2, c, S1, c, P, c, st));  // concat -> storage 1, BN+ReLU -> storage 2
+      DNB_TRY(nhwc::conv(S2, c, false, pk1, bl, B, n, c, B, d.h, d.w, 1, nullptr, part, &T1, st));
+      DNB_TRY(launch_bn_fold(p.g2, p.b2, mean_b, istd_b, part, T1, 0, B, d.eps, B, fold2, st));
+      DNB_TRY(nhwc::bn_relu_rows(bl, B, fold2, S3, B, nullptr, 0, P, B, st));
+      DNB_TRY(nhwc::conv(S3, B, false, pk3, y + c, cout, n, B, k, d.h, d.w, 9, nullptr, part, &T3, st));
+    }
     freshT = T3; fresh_lo = c; fresh_hi = c + k;
   }
   (void)k16;
@@ -238,6 +252,44 @@ int backward_bf16(dnb_block* b, const float* params, const void* yv, const void*
   // 13.9 ms; three helper streams with the helpers' launches first 14.4 ms (the main chain then
   // changes queue twice per layer); three helper streams with the main chain's launches first
   // 19.9 ms (the graph puts all helpers on one queue in an order that makes the main chain wait).
+  if (d.schedule != DNB_SCHED_FUSED) {
+    // Materialised schedules, in program order on the caller's stream.  Shared (Section 4): before
+    // a layer's back-propagation its storage 3, then storage 1 and 2, are re-populated from the
+    // kept conv outputs and the cached folded statistics; store-everything keeps them per layer.
+    const bool recompute = d.schedule == DNB_SCHED_SHARED;
+    DNB_TRY(nhwc::bf16_to_f32(dy, G, P * cout, st));
+    for (int l = m; l >= 1; --l) {
+      const int c = c_in(d, l);
+      const LayerParams p = layer_ptrs<LayerParams, const float>(b, params, l);
+      const LayerGrads gp = layer_ptrs<LayerGrads, float>(b, dparams, l);
+      const unsigned short* bl = (const unsigned short*)(ws + b->off_b[l]);
+      float* mean_b = (float*)(ws + b->off_stat_b[l]);
+      float* istd_b = mean_b + B;
+      const float2* fold1 = (const float2*)(ws + b->off_fold1[l]);
+      const float2* fold2 = (const float2*)(ws + b->off_fold2[l]);
+      unsigned short* S1 = (unsigned short*)(ws + b->off_u[l]);
+      unsigned short* S2 = (unsigned short*)(ws + b->off_a[l]);
+      unsigned short* S3 = (unsigned short*)(ws + b->off_a2[l]);
+      const size_t c16 = (size_t)((c + 15) & ~15), c32 = (size_t)((c + 31) & ~31);
+      const unsigned short* pk1t = pack + b->pk[l] + B16 * c32;
+      const unsigned short* pk3t = pack + b->pk[l] + B16 * c32 + c16 * B32 + 9 * k16 * B32;
+      const float* gl = G + c;
+      if (recompute) DNB_TRY(nhwc::bn_relu_rows(bl, B, fold2, S3, B, nullptr, 0, P, B, st));
+      DNB_TRY(nhwc::wgrad(S3, B, gl, cout, true, partA, gp.W3, n, B, k, d.h, d.w, 9, nullptr, st));
+      DNB_TRY(nhwc::conv(gl, cout, true, pk3t, dS3, B, n, k, B, d.h, d.w, 9, nullptr, nullptr, nullptr, st));
+      DNB_TRY(nhwc::bn_relu_bwd(bl, B, dS3, B, dS3, B, nullptr, 0, P, B, p.g2, p.b2, mean_b, istd_b, gp.g2, gp.b2,
+                                part, st));
+      if (recompute) DNB_TRY(nhwc::bn_relu_rows(y, cout, fold1, S2, c, S1, c, P, c, st));
+      DNB_TRY(nhwc::wgrad(S2, c, dS3, B, false, partB, gp.W1, n, c, B, d.h, d.w, 1, nullptr, st));
+      DNB_TRY(nhwc::conv(dS3, B, false, pk1t, dS2, c, n, B, c, d.h, d.w, 1, nullptr, nullptr, nullptr, st));
+      // BN1+ReLU backward reads the concatenated features from storage 1; concat backward adds into the slab
+      DNB_TRY(nhwc::bn_relu_bwd_reduce(S1, c, dS2, c, P, c, p.g1, p.b1, mean_y, istd_y, gp.g1, gp.b1, part, st));
+      DNB_TRY(nhwc::bn_relu_bwd_apply(S1, c, dS2, c, nullptr, 0, G, cout, P, c, p.g1, p.b1, mean_y, istd_y, gp.g1, gp.b1,
+                                      st));
+    }
+    DNB_TRY(nhwc::f32_rows_to_bf16(G, cout, dx0, P, d.c0, st));
+    return DNB_OK;
+  }
   const bool conc = b->concurrency != 0;
   if (conc) {
     const int rc = ensure_helper_streams(b);
@@ -407,10 +459,9 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
   if (d.layout != DNB_NCHW && d.layout != DNB_NHWC) return DNB_E_BADDESC;
   if (d.schedule != DNB_SCHED_SHARED && d.schedule != DNB_SCHED_STORE_ALL && d.schedule != DNB_SCHED_FUSED)
     return DNB_E_BADDESC;
-  // built combinations: fp32 + NCHW (all schedules), bf16 + NHWC (fused schedule)
+  // built combinations: fp32 + NCHW, bf16 + NHWC (all schedules each)
   const bool bf16 = d.dtype == DNB_BF16;
-  if (bf16 ? (d.layout != DNB_NHWC || d.schedule != DNB_SCHED_FUSED) : (d.layout != DNB_NCHW))
-    return DNB_E_UNSUPPORTED;
+  if (bf16 ? (d.layout != DNB_NHWC) : (d.layout != DNB_NCHW)) return DNB_E_UNSUPPORTED;
   // no bottleneck (BN-ReLU-3x3 on the concatenation): fp32, materialised schedules
   if (d.bottleneck == 0 && (bf16 || d.schedule == DNB_SCHED_FUSED)) return DNB_E_UNSUPPORTED;
   // bf16 kernels move 8 channels (16 bytes) at a time
@@ -496,7 +547,7 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
   mem.stats_bytes = (uint64_t)((size_t)cout * 2 + (size_t)m * B * 2) * sizeof(float);
   b->off_fold1.assign(m + 1, 0);
   b->off_fold2.assign(m + 1, 0);
-  if (d.schedule == DNB_SCHED_FUSED) {
+  if (d.schedule == DNB_SCHED_FUSED || bf16) {  // (bf16 keeps the folded statistics in every schedule)
     for (int l = 1; l <= m; ++l) {
       b->off_fold1[l] = carve((size_t)c_in(d, l) * 2 * sizeof(float), false);
       b->off_fold2[l] = carve((size_t)B * 2 * sizeof(float), false);

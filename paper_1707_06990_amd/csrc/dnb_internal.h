@@ -162,6 +162,9 @@ hipError_t launch_sum_partials(const float* partials, int splits, int64_t count,
 // strides ("ld") in elements; parameters, statistics, gradient slab and partials fp32.
 namespace nhwc {
 hipError_t copy_rows(const void* src, int64_t sld, void* dst, int64_t dld, int64_t P, int c, hipStream_t st);
+// out = bf16(max(0, fma(x, fold.x, fold.y))) per channel; copy (may be null) = x  (storage 2 / storage 1)
+hipError_t bn_relu_rows(const void* x, int64_t ld, const float2* fold, void* out, int64_t old, void* copy, int64_t cld,
+                        int64_t P, int c, hipStream_t st);
 hipError_t bf16_to_f32(const void* src, float* dst, int64_t count, hipStream_t st);
 hipError_t f32_rows_to_bf16(const float* src, int64_t sld, void* dst, int64_t P, int c, hipStream_t st);
 size_t stats_partial_floats(int64_t P, int c);

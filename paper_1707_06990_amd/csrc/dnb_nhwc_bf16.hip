@@ -59,6 +59,31 @@ __global__ __launch_bounds__(256) void k_copy_rows(const u16* __restrict__ src, 
   }
 }
 
+// out[p][0:c] = bf16(max(0, fma(x[p][ch], scale_ch, shift_ch))) with (scale, shift) = fold[ch]: BN+ReLU
+// into shared storage 2 exactly as the fused schedule's convolutions apply it in their operand
+// loads; copy (may be null) receives the raw features (the concatenation into shared storage 1).
+__global__ __launch_bounds__(256) void k_bn_relu_rows(const u16* __restrict__ x, int64_t ld,
+                                                      const float2* __restrict__ fold, u16* __restrict__ out,
+                                                      int64_t old, u16* __restrict__ copy, int64_t cld, int64_t P,
+                                                      int cv) {
+  const int64_t total = P * cv;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t p = i / cv;
+    const int v = (int)(i - p * cv);
+    V8 r, o;
+    r.q = *reinterpret_cast<const uint4*>(x + p * ld + 8 * v);
+    const float4* f4 = reinterpret_cast<const float4*>(fold + 8 * v);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float4 f = f4[e];  // two channels' (scale, shift)
+      o.h[2 * e] = f2bf(fmaxf(__fmaf_rn(bf2f(r.h[2 * e]), f.x, f.y), 0.f));
+      o.h[2 * e + 1] = f2bf(fmaxf(__fmaf_rn(bf2f(r.h[2 * e + 1]), f.z, f.w), 0.f));
+    }
+    *reinterpret_cast<uint4*>(out + p * old + 8 * v) = o.q;
+    if (copy) *reinterpret_cast<uint4*>(copy + p * cld + 8 * v) = r.q;
+  }
+}
+
 // G (fp32, [P][c]) = dy (bf16, [P][c])
 __global__ __launch_bounds__(256) void k_bf16_to_f32(const u16* __restrict__ src, float* __restrict__ dst,
                                                      int64_t total8) {
@@ -1163,6 +1188,13 @@ inline unsigned grid1d(int64_t items, int per, unsigned cap) {
 hipError_t copy_rows(const void* src, int64_t sld, void* dst, int64_t dld, int64_t P, int c, hipStream_t st) {
   hipLaunchKernelGGL(k_copy_rows, dim3(grid1d(P * (c / 8), 512, 16384)), dim3(256), 0, st, (const u16*)src, sld,
                      (u16*)dst, dld, P, c / 8);
+  return hipGetLastError();
+}
+
+hipError_t bn_relu_rows(const void* x, int64_t ld, const float2* fold, void* out, int64_t old, void* copy, int64_t cld,
+                        int64_t P, int c, hipStream_t st) {
+  hipLaunchKernelGGL(k_bn_relu_rows, dim3(grid1d(P * (c / 8), 512, 16384)), dim3(256), 0, st, (const u16*)x, ld, fold,
+                     (u16*)out, old, (u16*)copy, cld, P, c / 8);
   return hipGetLastError();
 }
 

@@ -46,9 +46,9 @@ def to_bf16_values(a):
     return torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).to(torch.float32).numpy()
 
 
-def run_block_gpu_bf16(dnb, cfg, x0, layer_params, dy, concurrency=None, decisions=False):
+def run_block_gpu_bf16(dnb, cfg, x0, layer_params, dy, concurrency=None, decisions=False, schedule=2):
     h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck,
-                             dtype=dnb.DNB_BF16, layout=dnb.DNB_NHWC, schedule=dnb.DNB_SCHED_FUSED, eps=cfg.eps)
+                             dtype=dnb.DNB_BF16, layout=dnb.DNB_NHWC, schedule=schedule, eps=cfg.eps)
     try:
         if concurrency is not None:   # None: the library's default, what bench.py times
             dnb.dnb_block_set_concurrency(h, concurrency)
@@ -133,6 +133,28 @@ def test_bf16_block_matches_oracle(dnb, oracle, cfg):
     gpu = check_bf16_block(dnb, oracle, cfg, x0, lp, dy)
     plain, _ = run_block_oracle(oracle, cfg, x0, lp, dy)   # the output also with no decision imposed
     assert_close(gpu["y"], plain.y, TOL, "y vs the oracle's own decisions")
+
+
+@pytest.mark.parametrize("cfg", CFGS, ids=IDS)
+def test_bf16_schedules_bit_identical_and_their_bytes(dnb, cfg):
+    """The shared-storage schedule (storage 1, 2, 3 re-populated in the backward pass), the
+    store-everything schedule and the fused schedule (nothing materialised) compute the same
+    numbers bit for bit; their feature-map bytes are the linear / quadratic / linear formulas."""
+    x0, lp, dy = wl.make_block_inputs(cfg, affine="random")
+    x0, dy = to_bf16_values(x0), to_bf16_values(dy)
+    fused = run_block_gpu_bf16(dnb, cfg, x0, lp, dy, schedule=2)
+    shared = run_block_gpu_bf16(dnb, cfg, x0, lp, dy, schedule=0)
+    store = run_block_gpu_bf16(dnb, cfg, x0, lp, dy, schedule=1)
+    for key in ("y", "dx0", "dparams"):
+        assert np.array_equal(fused[key], shared[key]), key
+        assert np.array_equal(fused[key], store[key]), key
+    P, m, k, B = cfg.pixels, cfg.layers, cfg.growth, cfg.bottleneck
+    cm, sigma = cfg.c_in(m), sum(cfg.c_in(l) for l in range(1, m + 1))
+    grad = cfg.c_out * P * 4 + (cm + B) * P * 2
+    assert fused["mem"]["peak_bytes"] == (m * B + m * k) * P * 2 + grad
+    assert shared["mem"]["stored_fwd_bytes"] == (m * B + m * k) * P * 2 and shared["mem"]["shared_fwd_bytes"] == (2 * cm + B) * P * 2
+    assert shared["mem"]["peak_bytes"] == (m * B + m * k + 2 * cm + B) * P * 2 + grad
+    assert store["mem"]["peak_bytes"] == (2 * sigma + m * (2 * B + k)) * P * 2 + grad and store["mem"]["shared_fwd_bytes"] == 0
 
 
 @pytest.mark.parametrize("cfg", [CFGS[1], CFGS[3]], ids=[IDS[1], IDS[3]])
@@ -231,7 +253,7 @@ def test_bf16_bytes_and_unsupported_combinations(dnb):
     assert mm["grad_bytes"] == cfg.c_out * P * 4 + (cfg.c_in(m) + B) * P * 2
     assert mm["peak_bytes"] == mm["stored_fwd_bytes"] + mm["grad_bytes"]
     dnb.dnb_block_destroy(h)
-    for kw in (dict(layout=dnb.DNB_NCHW), dict(schedule=dnb.DNB_SCHED_SHARED), dict(c0=20)):
+    for kw in (dict(layout=dnb.DNB_NCHW), dict(bottleneck=0), dict(c0=20)):
         args = dict(n=2, c0=16, h=8, w=8, layers=2, growth=8, bottleneck=32, dtype=dnb.DNB_BF16,
                     layout=dnb.DNB_NHWC, schedule=dnb.DNB_SCHED_FUSED)
         args.update(kw)
