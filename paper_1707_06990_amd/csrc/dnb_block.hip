@@ -466,14 +466,25 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
   if (d.bottleneck == 0 && (bf16 || d.schedule == DNB_SCHED_FUSED)) return DNB_E_UNSUPPORTED;
   // bf16 kernels move 8 channels (16 bytes) at a time
   if (bf16 && (d.c0 % 8 || d.growth % 8 || d.bottleneck % 8)) return DNB_E_UNSUPPORTED;
-  // ... and the 3x3 double-buffers 64 pixels + halo x 64 channels in 64 KB of LDS (w <= 80)
-  if (bf16 && (size_t)2 * (64 + 2 * (d.w + 1)) * 72 * 2 > 64 * 1024) return DNB_E_UNSUPPORTED;
+  // ... and the 3x3 double-buffers 64 pixels + halo x 64 channels in 64 KB of LDS, with the folded
+  // BN parameters of its input channels behind them in the fused schedule (the 1x1 likewise, with
+  // no halo and the widest layer's channels): shapes beyond that are refused here, not at launch
+  if (bf16) {
+    const size_t fold3 = d.schedule == DNB_SCHED_FUSED ? (size_t)d.bottleneck * 8 : 0;
+    const size_t fold1 = d.schedule == DNB_SCHED_FUSED ? (size_t)(d.c0 + (d.layers - 1) * d.growth) * 8 : 0;
+    if ((size_t)2 * (64 + 2 * (d.w + 1)) * 72 * 2 + fold3 > 64 * 1024 || 64 + 2 * (d.w + 1) > 256) return DNB_E_UNSUPPORTED;
+    if ((size_t)2 * 64 * 72 * 2 + fold1 > 64 * 1024) return DNB_E_UNSUPPORTED;
+  }
   // the fp32 fused schedule exists only in the 16-byte-vector kernels (pixel rows a multiple of 4)
   if (!bf16 && d.schedule == DNB_SCHED_FUSED) {
     // ... and its 3x3 stages all B channels of a 64-pixel tile (+ halo) in 64 KB of LDS
     int pitch = (64 + 2 * d.w + 8 + 31) / 32 * 32 + 4;
     if (pitch - 32 >= 64 + 2 * d.w + 8) pitch -= 32;
     if (d.w % 4 != 0 || (size_t)((d.bottleneck + 3) & ~3) * pitch * sizeof(float) > 64 * 1024)
+      return DNB_E_UNSUPPORTED;
+    // ... and its weight gradients (BN+ReLU in their operand loads) need the fast kernels' tile plans
+    if (d.h * d.w % 4 != 0 || conv_wgrad_fast_partial_floats(d.n, d.bottleneck, d.growth, d.h, d.w, 9) == 0 ||
+        conv_wgrad_fast_partial_floats(d.n, d.c0, d.bottleneck, d.h, d.w, 1) == 0)
       return DNB_E_UNSUPPORTED;
   }
   const int64_t hw = (int64_t)d.h * d.w, P = hw * d.n;

@@ -118,6 +118,8 @@ hipError_t launch_bn_fold(const float* gamma, const float* beta, float* mean, fl
 // dW[m][c][t] = sum_{n,q} g[n][m][q] * in[n][c][q + shift(t)]  (OIHW result).
 int conv_wgrad_splits(int n, int cin, int cout, int h, int w, int taps);
 size_t conv_wgrad_partial_floats(int n, int cin, int cout, int h, int w, int taps);
+// partial floats of the fast (16-byte-vector) weight-gradient kernel for this shape, 0 if its tile plan does not fit
+size_t conv_wgrad_fast_partial_floats(int n, int cin, int cout, int h, int w, int taps);
 // A sum of weight-gradient partials that a launch has left for later.  In a chain of weight
 // gradients on one stream the next weight-gradient launch carries it out with extra workgroups
 // (the partials are complete when that launch starts), which saves a launch per layer; what is

@@ -56,6 +56,30 @@ def test_descriptor_validation(dnb, kw, code):
     assert e.value.status == code
 
 
+def test_shapes_whose_tiles_do_not_fit_are_refused_at_create(dnb):
+    """Kernels whose LDS tiles or launch plans do not fit a shape are found by dnb_block_create
+    (DNB_E_UNSUPPORTED), not by a failing launch in the middle of a backward pass: the fp32 fused
+    schedule's 3x3 weight gradient with rows of 256 pixels; the bf16 3x3 with rows of 80 pixels
+    once the fused schedule's folded BN parameters share its LDS (the materialised schedules still
+    take them), and rows of 84 pixels in any schedule."""
+    def status(**kw):
+        base = dict(n=2, c0=16, h=4, w=8, layers=2, growth=8, bottleneck=32)
+        base.update(kw)
+        try:
+            dnb.dnb_block_destroy(dnb.dnb_block_create(**base))
+            return 0
+        except dnb.binding.DnbError as e:
+            return e.status
+    assert status(schedule=2, bottleneck=24, w=128) == 0
+    assert status(schedule=2, bottleneck=24, w=256) == dnb.DNB_E_UNSUPPORTED
+    assert status(schedule=0, bottleneck=24, w=256) == 0        # the materialised schedules have generic kernels
+    bf = dict(dtype=dnb.DNB_BF16, layout=dnb.DNB_NHWC, c0=96, growth=48, bottleneck=192)
+    assert status(schedule=2, w=76, **bf) == 0
+    assert status(schedule=2, w=80, **bf) == dnb.DNB_E_UNSUPPORTED
+    assert status(schedule=0, w=80, **bf) == 0
+    assert status(schedule=0, w=84, **bf) == dnb.DNB_E_UNSUPPORTED
+
+
 def test_null_arguments_are_errors(dnb):
     lib = ctypes.CDLL(dnb.binding.LIB_PATH)
     assert lib.dnb_block_create(None, None) == -2
