@@ -414,6 +414,11 @@ hipError_t launch_conv_igemm(const float* in, int64_t in_stride, WeightView wv, 
   return launch_igemm_mt<1>(p, in, in_stride, wv, out, out_stride, cin, cout, h, w, st);
 }
 
+bool conv_generic_fits(int n, int cin, int cout, int h, int w, int taps) {
+  return plan_igemm(n, cout, h, w, taps).lds <= 64 * 1024 && plan_igemm(n, cin, h, w, taps).lds <= 64 * 1024 &&
+         plan_wgrad(n, cin, cout, h, w, taps).lds <= 64 * 1024;
+}
+
 int conv_wgrad_splits(int n, int cin, int cout, int h, int w, int taps) {
   return plan_wgrad(n, cin, cout, h, w, taps).splits;
 }

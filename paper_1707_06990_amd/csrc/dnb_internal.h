@@ -106,6 +106,9 @@ size_t conv_stats_partial_floats(int n, int cout, int h, int w);
 hipError_t launch_conv_igemm(const float* in, int64_t in_stride, WeightView wv, const float* packed,
                              float* out, int64_t out_stride, int n, int cin, int cout, int h, int w,
                              int taps, ConvExtras* ex, hipStream_t st);
+// whether the any-shape kernels (forward, data gradient, weight gradient) have LDS for this shape: they
+// are the fallback wherever an operand is not 16-byte friendly, so a plan must not count on the fast ones
+bool conv_generic_fits(int n, int cin, int cout, int h, int w, int taps);
 bool conv_fast_ok(const float* in, int64_t in_stride, const float* out, int64_t out_stride, int h,
                   int w, int taps);
 

@@ -59,7 +59,8 @@ def test_descriptor_validation(dnb, kw, code):
 def test_shapes_whose_tiles_do_not_fit_are_refused_at_create(dnb):
     """Kernels whose LDS tiles or launch plans do not fit a shape are found by dnb_block_create
     (DNB_E_UNSUPPORTED), not by a failing launch in the middle of a backward pass: the fp32 fused
-    schedule's 3x3 weight gradient with rows of 256 pixels; the bf16 3x3 with rows of 80 pixels
+    schedule's 3x3 weight gradient, and the any-shape 3x3 kernels of the materialised schedules, with
+    rows of 256 pixels; the bf16 3x3 with rows of 80 pixels
     once the fused schedule's folded BN parameters share its LDS (the materialised schedules still
     take them), and rows of 84 pixels in any schedule."""
     def status(**kw):
@@ -72,7 +73,8 @@ def test_shapes_whose_tiles_do_not_fit_are_refused_at_create(dnb):
             return e.status
     assert status(schedule=2, bottleneck=24, w=128) == 0
     assert status(schedule=2, bottleneck=24, w=256) == dnb.DNB_E_UNSUPPORTED
-    assert status(schedule=0, bottleneck=24, w=256) == 0        # the materialised schedules have generic kernels
+    assert status(schedule=0, bottleneck=24, w=128) == 0        # the materialised schedules have any-shape kernels,
+    assert status(schedule=0, bottleneck=24, w=256) == dnb.DNB_E_UNSUPPORTED   # whose 3x3 tiles stop fitting LDS above ~136-pixel rows
     bf = dict(dtype=dnb.DNB_BF16, layout=dnb.DNB_NHWC, c0=96, growth=48, bottleneck=192)
     assert status(schedule=2, w=76, **bf) == 0
     assert status(schedule=2, w=80, **bf) == dnb.DNB_E_UNSUPPORTED
