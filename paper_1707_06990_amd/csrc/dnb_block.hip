@@ -487,15 +487,15 @@ int dnb_block_create(const dnb_block_desc* desc, dnb_block** out) {
         conv_wgrad_fast_partial_floats(d.n, d.c0, d.bottleneck, d.h, d.w, 1) == 0)
       return DNB_E_UNSUPPORTED;
   }
+  const int64_t hw = (int64_t)d.h * d.w, P = hw * d.n;
+  const int64_t cout = (int64_t)d.c0 + (int64_t)d.layers * d.growth;
+  if (cout * P >= (int64_t)1 << 31 || (int64_t)d.bottleneck * P >= (int64_t)1 << 31) return DNB_E_RANGE;
   if (!bf16 && d.schedule != DNB_SCHED_FUSED) {
     // the materialised fp32 schedules fall back to the any-shape kernels: their 3x3 tiles (64 pixels
     // plus a halo of two rows) must fit LDS, else the shape is refused here rather than at launch
     const int cin3 = d.bottleneck > 0 ? d.bottleneck : d.c0 + (d.layers - 1) * d.growth;
     if (!conv_generic_fits(d.n, cin3, d.growth, d.h, d.w, 9)) return DNB_E_UNSUPPORTED;
   }
-  const int64_t hw = (int64_t)d.h * d.w, P = hw * d.n;
-  const int64_t cout = (int64_t)d.c0 + (int64_t)d.layers * d.growth;
-  if (cout * P >= (int64_t)1 << 31 || (int64_t)d.bottleneck * P >= (int64_t)1 << 31) return DNB_E_RANGE;
 
   dnb_block* b = new (std::nothrow) dnb_block();
   if (!b) return DNB_E_NOMEM;
