@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--serial", action="store_true", help="no helper streams in backward (the library's default for fp32)")
     ap.add_argument("--concurrent", action="store_true", help="weight gradients on helper streams in backward (the library's default for bf16)")
     ap.add_argument("--forward-only", action="store_true", help="time the forward pass alone (diagnostic, not the metric)")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="skip the other workloads (config3: whole network; config4 / config5: dense-block sets) that the "
+                         "default run times after the metric's workload and reports as objects of their own")
     return ap.parse_args()
 
 
@@ -72,6 +75,7 @@ class BlockRun:
     def __init__(self, dnb, torch, wl, cfg, schedule, seed, bf16=False):
         from harness import dev, pack_params_gpu
         self.cfg = cfg
+        self.dnb = dnb
         kw = dict(dtype=dnb.DNB_BF16, layout=dnb.DNB_NHWC) if bf16 else {}
         self.h = dnb.dnb_block_create(cfg.n, cfg.c0, cfg.h, cfg.w, cfg.layers, cfg.growth, cfg.bottleneck,
                                       schedule=schedule, eps=cfg.eps, **kw)
@@ -88,6 +92,11 @@ class BlockRun:
         self.dx0 = torch.empty_like(self.x0)
         self.ws = torch.empty(dnb.dnb_block_workspace_bytes(self.h), dtype=torch.uint8, device="cuda")
         self.mem = dnb.dnb_block_memory_breakdown(self.h)
+
+    def close(self):
+        if self.h is not None:
+            self.dnb.dnb_block_destroy(self.h)
+            self.h = None
 
 
 class NetRun:
@@ -184,12 +193,23 @@ def event_time_ms(torch, fn, reps):
     return e0.elapsed_time(e1) / reps
 
 
-DOMINANT_KERNEL = "k_wgrad_pair<3, 4, 1, 3, true>"
-# HBM bytes per launch of that kernel (average over the launches timed below) from the two
-# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, each scaled by the copy kernel of known size),
-# summarised in profiles/; valid for that workload only.
-MEASURED_TRAFFIC = {"config2:64": 190400000}   # profiles/bc100_b64_fp32_wgrad_pair_hbm_traffic.txt
-HBM_PEAK_GBS = 8000.0
+# The kernel with the largest share of the step in the committed rocprofv3 summaries (profiles/), per
+# workload, and the summary that holds its measured HBM bytes per launch (two rocprofv3 --pmc runs,
+# FETCH_SIZE then WRITE_SIZE, each scaled by the copy kernel of known size): the figure is read from
+# the line "traffic_bytes_per_launch: N" of that file, so it is whatever the committed profile says.
+DOMINANT = {"config2:64": ("k_wgrad_pair<3, 4, 1, 3, true>", "bc100_b64_fp32_wgrad_pair_hbm_traffic.txt"),
+            "config3:64": ("k_wgrad_pair<3, 4, 2, 2, true>", "bc250_b64_fp32_wgrad_pair_hbm_traffic.txt")}
+
+
+def measured_traffic(key):
+    import re
+    if key not in DOMINANT:
+        return None
+    path = os.path.join(ROOT, "profiles", DOMINANT[key][1])
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"^traffic_bytes_per_launch:\s*(\d+)", open(path).read(), flags=re.M)
+    return int(m.group(1)) if m else None
 
 
 def dominant_kernel_roofline(dnb, torch, runs, traffic_key):
@@ -241,12 +261,14 @@ def dominant_kernel_roofline(dnb, torch, runs, traffic_key):
         launches += 1
     ms = ms_sum / launches
     t_hbm, t_mfma = nbytes / (HBM_PEAK_GBS * 1e9), flops / (MFMA_F32_PEAK_TF * 1e12)
-    common = {"kernel": DOMINANT_KERNEL + " (a layer's 1x1 and 3x3 weight gradients and its BN1 backward reduction in one launch)",
-              "traffic": MEASURED_TRAFFIC.get(traffic_key), "avg_launch_ms": round(ms, 5),
+    common = {"kernel": DOMINANT.get(traffic_key, ("k_wgrad_pair",))[0] +
+              " (a layer's 1x1 and 3x3 weight gradients and its BN1 backward reduction in one launch)",
+              "traffic": measured_traffic(traffic_key), "avg_launch_ms": round(ms, 5),
               "algorithmic_flops_per_launch": int(flops / launches),
               "algorithmic_bytes_per_launch": int(nbytes / launches), "launches_averaged": launches * reps,
               "shapes": "B = %d, k = %d over P = %d pixels, C_l = %d..%d (the %d layers of the first dense block with "
                         "C_l >= 49)" % (B, k, n * hw, cs[0], cs[-1], launches)}
+    del y, G, db, bact
     if t_hbm >= t_mfma:
         achieved = nbytes / (ms_sum * 1e-3) / 1e9
         return dict({"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -304,6 +326,66 @@ def cpu_baseline_net(wl, ncfg):
                       f"(float64, store-everything schedule, fwd+bwd), {t:.1f} s"}
 
 
+def extra_fp32_net(dnb, torch, wl, name, steps, warmup):
+    """Another CIFAR-shaped fp32 workload timed like the metric's: whole training step under the
+    three schedules, exact peak bytes, recompute overhead, roofline of its dominant kernel."""
+    sched = {"shared": dnb.DNB_SCHED_SHARED, "store_all": dnb.DNB_SCHED_STORE_ALL, "fused": dnb.DNB_SCHED_FUSED}
+    blocks, wname = workload_blocks(wl, name, 0)
+    batch = blocks[0].n
+    ncfg = wl.net_config3(batch) if name == "config3" else wl.net_config2(batch)
+    out = {"workload": wname.replace("3 dense blocks", "whole network: stem, 3 dense blocks").replace(
+        "layers (fwd+bwd)", "layers, 2 transitions, head, softmax cross-entropy (fwd+bwd)"), "steps": steps, "warmup": warmup}
+    t = {}
+    for sname in ("fused", "shared", "store_all"):
+        r = NetRun(dnb, torch, wl, ncfg, sched[sname])
+        t[sname] = time_steps(torch, make_net_step(dnb, r), steps, warmup, True)
+        out[sname] = {"images_per_s": round(batch * steps / t[sname], 2), "ms_per_step": round(1e3 * t[sname] / steps, 4),
+                      "network_feature_map_bytes": r.peak}
+        hs = [dnb.dnb_block_create(c.n, c.c0, c.h, c.w, c.layers, c.growth, c.bottleneck, schedule=sched[sname]) for c in blocks]
+        out[sname]["dense_block_feature_map_bytes"] = sum(dnb.dnb_block_peak_bytes(h) for h in hs)
+        for h in hs:
+            dnb.dnb_block_destroy(h)
+        dnb.dnb_net_destroy(r.h)
+        del r
+        torch.cuda.empty_cache()
+    out["recompute_overhead"] = round(t["shared"] / t["store_all"] - 1.0, 4)
+    out["fused_vs_store_all_time"] = round(t["fused"] / t["store_all"] - 1.0, 4)
+    runs = [BlockRun(dnb, torch, wl, blocks[0], sched["fused"], 0)]
+    out["roofline"] = dominant_kernel_roofline(dnb, torch, runs, f"{name}:{batch}")
+    runs[0].close()
+    del runs
+    torch.cuda.empty_cache()
+    return out
+
+
+def extra_bf16_blocks(dnb, torch, wl, name, steps, warmup):
+    """The dense-block set of an ImageNet-shaped bf16 / NHWC workload (batch 32): the fused schedule
+    as the library runs it by default (weight gradients on a helper stream) and, for the recompute
+    overhead, the three schedules in program order on one stream (the materialised ones only run
+    that way), with their exact peak feature-map bytes."""
+    sched = {"shared": dnb.DNB_SCHED_SHARED, "store_all": dnb.DNB_SCHED_STORE_ALL, "fused": dnb.DNB_SCHED_FUSED}
+    blocks, wname = workload_blocks(wl, name, 0)
+    batch = blocks[0].n
+    out = {"workload": wname, "steps": steps, "warmup": warmup}
+    t = {}
+    for label, sname, serial in (("fused", "fused", False), ("fused_one_stream", "fused", True), ("shared", "shared", True),
+                                 ("store_all", "store_all", True)):
+        runs = [BlockRun(dnb, torch, wl, c, sched[sname], 10 * i, True) for i, c in enumerate(blocks)]
+        if serial:
+            for r in runs:
+                dnb.dnb_block_set_concurrency(r.h, False)
+        t[label] = time_steps(torch, make_step(dnb, runs), steps, warmup, True)
+        out[label] = {"images_per_s": round(batch * steps / t[label], 2), "ms_per_step": round(1e3 * t[label] / steps, 4),
+                      "feature_map_bytes": sum(r.mem["peak_bytes"] for r in runs)}
+        for r in runs:
+            r.close()
+        del runs
+        torch.cuda.empty_cache()
+    out["recompute_overhead"] = round(t["shared"] / t["store_all"] - 1.0, 4)
+    out["fused_vs_store_all_time"] = round(t["fused_one_stream"] / t["store_all"] - 1.0, 4)
+    return out
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -325,9 +407,6 @@ def main():
     use_graph = not a.no_graph
 
     bf16 = a.workload in ("config4", "config5")
-    if bf16 and a.schedule != "fused":
-        print("bench.py: the bf16 NHWC path has the fused schedule only", file=sys.stderr)
-        sys.exit(2)
 
     def measure(schedule):
         runs = [BlockRun(dnb, torch, wl, c, sched[schedule], 10 * i, bf16) for i, c in enumerate(blocks)]
@@ -410,6 +489,14 @@ def main():
             torch.cuda.empty_cache()
         out["recompute_overhead"] = round(t["shared"] / t["store_all"] - 1.0, 4)
         out["fused_vs_store_all_time"] = round(t["fused"] / t["store_all"] - 1.0, 4)
+    default_run = (a.workload == "config2" and net_scope and not a.batch and a.schedule == "fused" and use_graph
+                   and not (a.serial or a.concurrent or a.forward_only or a.no_compare))
+    if default_run and not a.no_extra:
+        # the other workloads, so that one run of the default command measures them all: the largest
+        # fp32 network as a whole training step, the two bf16 workloads as their dense-block sets
+        out["config3"] = extra_fp32_net(dnb, torch, wl, "config3", 10, 3)
+        out["config4_dense_blocks"] = extra_bf16_blocks(dnb, torch, wl, "config4", 10, 3)
+        out["config5_dense_blocks"] = extra_bf16_blocks(dnb, torch, wl, "config5", 10, 3)
     if not a.no_cpu_baseline and not bf16:
         out["cpu_baseline"] = cpu_baseline_net(wl, ncfg) if net_scope else cpu_baseline(wl, blocks)
     print(json.dumps(out), flush=True)
