@@ -153,3 +153,22 @@ def run_net_gpu(dnb, oracle, cfg, x, labels, params, schedule, concurrency=None,
         return s, flat, float(loss.item()), logits.cpu().numpy(), dp.cpu().numpy()
     finally:
         dnb.dnb_net_destroy(net)
+
+
+def pack_inet(orc, s, params):
+    """Named tensors of workloads.make_inet_inputs -> the oracle's flat pack of the ImageNet-shaped network."""
+    flat = np.zeros(orc.inet_param_count(s))
+    sl = orc.inet_param_slices(s)
+    for name in ("W", "g", "b"):
+        flat[sl[f"stem.{name}"]] = params["stem"][name].ravel()
+    for b in range(4):
+        bs = s.block(b)
+        blk = np.zeros(orc.param_count(bs))
+        for l, p in enumerate(params[f"block{b}"], start=1):
+            for name, arr in p.items():
+                blk[orc.param_slice(bs, l, NAMES.index(name))] = arr.ravel()
+        flat[sl[f"block{b}"]] = blk
+        pre = f"trans{b}" if b < 3 else "tail"
+        for name, arr in params[pre].items():
+            flat[sl[f"{pre}.{name}"]] = arr.ravel()
+    return flat

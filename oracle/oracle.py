@@ -17,6 +17,7 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "dnb_oracle.c")
 _SRC_NET = os.path.join(_HERE, "dnb_net_oracle.c")
+_SRC_INET = os.path.join(_HERE, "dnb_inet_oracle.c")
 _LIB = os.path.join(_HERE, "libdnb_oracle.so")
 
 G1, B1, W1, G2, B2, W3 = range(6)
@@ -25,9 +26,9 @@ PARAM_NAMES = ("g1", "b1", "W1", "g2", "b2", "W3")
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (OpenMP, -O2).  Returns the library path."""
-    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_NET))
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_NET), os.path.getmtime(_SRC_INET))
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
-        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-o", _LIB, _SRC, _SRC_NET, "-lm"]
+        cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-o", _LIB, _SRC, _SRC_NET, _SRC_INET, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -40,6 +41,11 @@ class _Desc(C.Structure):
 
 class _NetDesc(C.Structure):
     _fields_ = [("n", C.c_int32), ("image", C.c_int32), ("depth", C.c_int32), ("growth", C.c_int32),
+                ("classes", C.c_int32), ("eps", C.c_double)]
+
+
+class _InetDesc(C.Structure):
+    _fields_ = [("n", C.c_int32), ("image", C.c_int32), ("growth", C.c_int32), ("layers", C.c_int32 * 4),
                 ("classes", C.c_int32), ("eps", C.c_double)]
 
 
@@ -98,6 +104,23 @@ def lib():
         _lib.dnbo_net_decision_count.argtypes = [nd]
         _lib.dnbo_net_step_masks.restype = C.c_double
         _lib.dnbo_net_step_masks.argtypes = [nd, _dp, C.POINTER(C.c_int32), _dp, _dp, _dp, C.c_int, C.c_void_p, _dp]
+        idp = C.POINTER(_InetDesc)
+        _lib.dnbo_inet_param_count.restype = C.c_int64
+        _lib.dnbo_inet_param_count.argtypes = [idp]
+        _lib.dnbo_inet_param_offset.restype = C.c_int64
+        _lib.dnbo_inet_param_offset.argtypes = [idp, C.c_int, C.POINTER(C.c_int64)]
+        _lib.dnbo_inet_decision_counts.restype = None
+        _lib.dnbo_inet_decision_counts.argtypes = [idp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+        _lib.dnbo_inet_step.restype = C.c_double
+        _lib.dnbo_inet_step.argtypes = [idp, _dp, C.POINTER(C.c_int32), _dp, _dp, _dp, C.c_int, C.c_void_p, C.c_void_p, _dp,
+                                        C.c_int]
+        for nm in ("dnbo_conv_forward_strided", "dnbo_conv_wgrad_strided", "dnbo_conv_dgrad_strided"):
+            getattr(_lib, nm).restype = None
+            getattr(_lib, nm).argtypes = [_dp, _dp, i64, i64, i64, i64, i64, i64, i64, i64, _dp]
+        _lib.dnbo_maxpool3s2.restype = None
+        _lib.dnbo_maxpool3s2.argtypes = [_dp, i64, i64, i64, i64, _dp, C.c_void_p, C.c_int, _dp, _dp]
+        _lib.dnbo_maxpool3s2_backward.restype = None
+        _lib.dnbo_maxpool3s2_backward.argtypes = [_dp, C.c_void_p, i64, i64, i64, i64, _dp]
         _lib.dnbo_avgpool2.restype = None
         _lib.dnbo_avgpool2.argtypes = [_dp, i64, i64, i64, i64, _dp]
         _lib.dnbo_avgpool2_backward.restype = None
@@ -483,3 +506,144 @@ def softmax_xent(logits, labels):
     d = np.zeros_like(logits)
     loss = lib().dnbo_softmax_xent(_p(logits), lab.ctypes.data_as(C.POINTER(C.c_int32)), n, classes, _p(d))
     return float(loss), d
+
+
+# ------------------------------------------------------------------ ImageNet-shaped network (four dense blocks)
+
+def conv_forward_strided(x, wgt, stride, pad):
+    x, wgt = _f64(x), _f64(wgt)
+    n, ci, h, w = x.shape
+    co, _, ks, _ = wgt.shape
+    ho, wo = (h + 2 * pad - ks) // stride + 1, (w + 2 * pad - ks) // stride + 1
+    out = np.zeros((n, co, ho, wo))
+    lib().dnbo_conv_forward_strided(_p(x), _p(wgt), n, ci, co, h, w, ks, stride, pad, _p(out))
+    return out
+
+
+def conv_wgrad_strided(x, dout, ks, stride, pad):
+    x, dout = _f64(x), _f64(dout)
+    n, ci, h, w = x.shape
+    co = dout.shape[1]
+    dw = np.zeros((co, ci, ks, ks))
+    lib().dnbo_conv_wgrad_strided(_p(x), _p(dout), n, ci, co, h, w, ks, stride, pad, _p(dw))
+    return dw
+
+
+def conv_dgrad_strided(dout, wgt, h, w, stride, pad):
+    dout, wgt = _f64(dout), _f64(wgt)
+    n, co = dout.shape[:2]
+    ci, ks = wgt.shape[1], wgt.shape[2]
+    din = np.zeros((n, ci, h, w))
+    lib().dnbo_conv_dgrad_strided(_p(dout), _p(wgt), n, ci, co, h, w, ks, stride, pad, _p(din))
+    return din
+
+
+def maxpool3s2(x, positions=None, inv_rms=None):
+    """3x3 max pooling, stride 2, pad 1.  Returns (out, positions) with positions the window index
+    3*i + j of each maximum (first in scan order among equals); if `positions` is given they are
+    imposed instead and (out, (count, margin)) of the differing ones is returned."""
+    x = _f64(x)
+    n, c, h, w = x.shape
+    out = np.zeros((n, c, h // 2, w // 2))
+    if positions is None:
+        idx = np.zeros(out.shape, dtype=np.uint8)
+        lib().dnbo_maxpool3s2(_p(x), n, c, h, w, _p(out), idx.ctypes.data_as(C.c_void_p), 0, None, None)
+        return out, idx
+    idx = np.ascontiguousarray(np.asarray(positions, dtype=np.uint8).reshape(out.shape))
+    stat = np.zeros(2)
+    ir = _f64(inv_rms) if inv_rms is not None else np.ones(c)
+    lib().dnbo_maxpool3s2(_p(x), n, c, h, w, _p(out), idx.ctypes.data_as(C.c_void_p), 1, _p(ir), _p(stat))
+    return out, (int(stat[0]), float(stat[1]))
+
+
+def maxpool3s2_backward(dout, positions, h, w):
+    dout = _f64(dout)
+    n, c = dout.shape[:2]
+    idx = np.ascontiguousarray(np.asarray(positions, dtype=np.uint8).reshape(dout.shape))
+    din = np.zeros((n, c, h, w))
+    lib().dnbo_maxpool3s2_backward(_p(dout), idx.ctypes.data_as(C.c_void_p), n, c, h, w, _p(din))
+    return din
+
+
+@dataclass(frozen=True)
+class InetShape:
+    n: int
+    image: int
+    growth: int
+    layers: tuple
+    classes: int
+    eps: float = 1e-5
+
+    def _c(self) -> _InetDesc:
+        return _InetDesc(self.n, self.image, self.growth, (C.c_int32 * 4)(*self.layers), self.classes, self.eps)
+
+    def block(self, b: int) -> BlockShape:
+        c, s = 2 * self.growth, self.image // 4
+        for i in range(b):
+            c = (c + self.layers[i] * self.growth) // 2
+            s //= 2
+        return BlockShape(self.n, c, s, s, self.layers[b], self.growth, 4 * self.growth, self.eps)
+
+
+def inet_param_count(s: InetShape) -> int:
+    d = s._c()
+    return int(lib().dnbo_inet_param_count(C.byref(d)))
+
+
+def inet_param_slices(s: InetShape) -> dict:
+    """Named slices of the network pack: stem.W, stem.g, stem.b, block0..3, trans0..2.{g,b,W}, tail.{g,b,Wl,bl}."""
+    d = s._c()
+    def sl(which):
+        cnt = C.c_int64()
+        off = int(lib().dnbo_inet_param_offset(C.byref(d), which, C.byref(cnt)))
+        return slice(off, off + int(cnt.value))
+    out = {"stem.W": sl(0), "stem.g": sl(1), "stem.b": sl(2)}
+    for b in range(4):
+        out[f"block{b}"] = sl(3 + 4 * b)
+        pre = f"trans{b}" if b < 3 else "tail"
+        out[f"{pre}.g"], out[f"{pre}.b"] = sl(4 + 4 * b), sl(5 + 4 * b)
+        out[f"{pre}.W" if b < 3 else "tail.Wl"] = sl(6 + 4 * b)
+    out["tail.bl"] = sl(19)
+    return out
+
+
+def inet_decision_counts(s: InetShape):
+    d = s._c()
+    a, b = C.c_int64(), C.c_int64()
+    lib().dnbo_inet_decision_counts(C.byref(d), C.byref(a), C.byref(b))
+    return int(a.value), int(b.value)
+
+
+def inet_step(s: InetShape, x, labels, params, backward: bool = True, decisions=None, bf16_storage: bool = False):
+    """One training step.  decisions=None: plain, returns (loss, dparams, logits).  decisions="write":
+    returns (loss, dparams, logits, (relu, pool)) with the step's own ReLU decisions and pooling
+    positions.  decisions=(relu, pool): they are imposed; returns (loss, dparams, logits, stats) with
+    stats = dict(relu_count, relu_margin, pool_count, pool_margin) of the differing ones."""
+    d = s._c()
+    x = _f64(x).reshape(s.n, 3, s.image, s.image)
+    params = _f64(params).reshape(-1)
+    assert params.size == inet_param_count(s)
+    lab = np.ascontiguousarray(np.asarray(labels, dtype=np.int32))
+    logits = np.zeros((s.n, s.classes))
+    dparams = np.zeros_like(params) if backward else None
+    nr, npool = inet_decision_counts(s)
+    stats = np.zeros(4)
+    if decisions is None:
+        mode, m, pl = -1, None, None
+    elif isinstance(decisions, str):
+        mode, m, pl = 0, np.zeros(nr, dtype=np.uint8), np.zeros(npool, dtype=np.uint8)
+    else:
+        mode = 1
+        m = np.ascontiguousarray(np.asarray(decisions[0], dtype=np.uint8).reshape(-1))
+        pl = np.ascontiguousarray(np.asarray(decisions[1], dtype=np.uint8).reshape(-1))
+        assert m.size == nr and pl.size == npool
+    vp = lambda a: a.ctypes.data_as(C.c_void_p) if a is not None else None
+    loss = lib().dnbo_inet_step(C.byref(d), _p(x), lab.ctypes.data_as(C.POINTER(C.c_int32)), _p(params),
+                                _p(dparams) if backward else None, _p(logits), mode, vp(m), vp(pl), _p(stats),
+                                1 if bf16_storage else 0)
+    if decisions is None:
+        return float(loss), dparams, logits
+    if mode == 0:
+        return float(loss), dparams, logits, (m, pl)
+    return float(loss), dparams, logits, dict(relu_count=int(stats[0]), relu_margin=float(stats[1]),
+                                               pool_count=int(stats[2]), pool_margin=float(stats[3]))

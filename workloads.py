@@ -199,3 +199,71 @@ def net_config2(batch: int = 64) -> NetCfg:
 def net_config3(batch: int = 64) -> NetCfg:
     """DenseNet-BC L=250 k=24, 32x32 inputs, 100 classes."""
     return NetCfg(batch, 32, 250, 24, 100)
+
+
+# --------------------------------------------------------------- whole ImageNet-shaped networks
+
+@dataclass(frozen=True)
+class InetCfg:
+    """ImageNet-shaped DenseNet-BC on square 3-channel images: 7x7 stride-2 stem to 2k channels,
+    BN-ReLU, 3x3 stride-2 max pool, four dense blocks of layers[b] bottleneck layers (B = 4k),
+    transitions with compression 0.5 and 2x2 average pooling, linear head."""
+    n: int
+    image: int
+    growth: int
+    layers: Tuple[int, int, int, int]
+    classes: int
+    eps: float = 1e-5
+
+    def blocks(self) -> List[BlockCfg]:
+        c, s, out = 2 * self.growth, self.image // 4, []
+        for m in self.layers:
+            out.append(BlockCfg(self.n, c, s, s, m, self.growth, 4 * self.growth, self.eps))
+            c = (c + m * self.growth) // 2
+            s //= 2
+        return out
+
+
+def make_inet_inputs(cfg: InetCfg, seed_x: int = 0, seed_w: int = 1, seed_t: int = 2, affine: str = "ones"):
+    """Returns (x, labels, params): x (n,3,image,image) float32 ~ N(0,1); labels int32 uniform in
+    [0, classes); params a dict: 'stem' dict W (2k,3,7,7), g, b; 'block0..3' lists of per-layer dicts
+    as in make_block_inputs; 'trans0..2' dicts g, b, W (C/2, C); 'tail' dict g, b, Wl (classes, C),
+    bl (zeros).  Conv and linear weights He-normal, BN affine as in make_block_inputs."""
+    rx = np.random.default_rng(seed_x)
+    rw = np.random.default_rng(seed_w)
+    rt = np.random.default_rng(seed_t)
+    x = rx.standard_normal((cfg.n, 3, cfg.image, cfg.image)).astype(np.float32)
+    labels = rt.integers(0, cfg.classes, size=cfg.n).astype(np.int32)
+
+    def he(shape):
+        return (rw.standard_normal(shape) * np.sqrt(2.0 / int(np.prod(shape[1:])))).astype(np.float32)
+
+    def gam(c):
+        return (1.0 + 0.25 * rw.standard_normal(c)).astype(np.float32) if affine == "random" else np.ones(c, np.float32)
+
+    def bet(c):
+        return (0.25 * rw.standard_normal(c)).astype(np.float32) if affine == "random" else np.zeros(c, np.float32)
+
+    cs = 2 * cfg.growth
+    params = {"stem": {"W": he((cs, 3, 7, 7)), "g": gam(cs), "b": bet(cs)}}
+    for b, bc in enumerate(cfg.blocks()):
+        tiny = BlockCfg(1, bc.c0, 1, 1, bc.layers, bc.growth, bc.bottleneck, bc.eps)   # the parameters do not depend on n, h, w
+        _, layers, _ = make_block_inputs(tiny, seed_x + 100 + b, seed_w + 100 + b, seed_t + 100 + b, affine)
+        params[f"block{b}"] = layers
+        c = bc.c_out
+        if b < 3:
+            params[f"trans{b}"] = {"g": gam(c), "b": bet(c), "W": he((c // 2, c))}
+        else:
+            params["tail"] = {"g": gam(c), "b": bet(c), "Wl": he((cfg.classes, c)),
+                              "bl": np.zeros(cfg.classes, np.float32)}
+    return x, labels, params
+
+
+def inet_config4(batch: int = 32) -> InetCfg:
+    """DenseNet-161-shaped: k = 48, blocks 6-12-36-24, 224x224 inputs, 1000 classes."""
+    return InetCfg(batch, 224, 48, (6, 12, 36, 24), 1000)
+
+
+def inet_config5(batch: int = 32) -> InetCfg:
+    """DenseNet-264-shaped: k = 32, blocks 6-12-64-48, 224x224 inputs, 1000 classes."""
+    return InetCfg(batch, 224, 32, (6, 12, 64, 48), 1000)
