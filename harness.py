@@ -172,3 +172,56 @@ def pack_inet(orc, s, params):
         for name, arr in params[pre].items():
             flat[sl[f"{pre}.{name}"]] = arr.ravel()
     return flat
+
+
+def run_inet_gpu(dnb, oracle, cfg, x, labels, params, schedule=2, decisions=False):
+    """One training step of the ImageNet-shaped network through the C ABI (x: (n,3,S,S) float32 holding
+    bf16 values).  Returns (shape, flat oracle pack, loss, logits, dparams[, (relu, pool)]); the
+    decision bytes come back in the oracle's (n, c, h, w) order."""
+    s = oracle.InetShape(cfg.n, cfg.image, cfg.growth, tuple(cfg.layers), cfg.classes, cfg.eps)
+    flat = pack_inet(oracle, s, params)   # the two packs have the same layout (checked by the host tests)
+    net = dnb.dnb_inet_create(cfg.n, cfg.image, cfg.growth, cfg.layers, cfg.classes, schedule=schedule, eps=cfg.eps)
+    try:
+        assert dnb.dnb_inet_param_count(net) == flat.size
+        p = dev(flat.astype(np.float32))
+        dp = torch.full_like(p, float("nan"))
+        guard = 1 << 20
+        nbytes = dnb.dnb_inet_workspace_bytes(net)
+        ws = torch.empty(nbytes + guard, dtype=torch.uint8, device="cuda")
+        ws.fill_(0xFF)
+        xd = torch.from_numpy(np.ascontiguousarray(x)).permute(0, 2, 3, 1).contiguous().to("cuda", torch.bfloat16)
+        lab = torch.from_numpy(labels).to("cuda")
+        loss = torch.full((1,), float("nan"), device="cuda")
+        logits = torch.full((cfg.n, cfg.classes), float("nan"), device="cuda")
+        dnb.dnb_inet_forward(net, xd, lab, p, loss, logits, ws)
+        dec = None
+        if decisions:
+            relu = torch.full((dnb.dnb_inet_relu_decision_bytes(net),), 7, dtype=torch.uint8, device="cuda")
+            pool = torch.full((dnb.dnb_inet_pool_position_bytes(net),), 77, dtype=torch.uint8, device="cuda")
+            dnb.dnb_inet_decisions(net, p, ws, relu, pool)
+        dnb.dnb_inet_backward(net, xd, p, dp, ws)
+        torch.cuda.synchronize()
+        assert bool((ws[nbytes:] == 0xFF).all()), "the step wrote behind its workspace"
+        out = [s, flat, float(loss.item()), logits.cpu().numpy(), dp.cpu().numpy()]
+        if decisions:
+            relu, pool = relu.cpu().numpy(), pool.cpu().numpy()
+            # (n, h, w, c) per tensor -> (n, c, h, w), tensors in the same order
+            pieces, o = [], 0
+            def take(n_, h, w, c):
+                nonlocal o
+                cnt = n_ * h * w * c
+                pieces.append(relu[o:o + cnt].reshape(n_, h, w, c).transpose(0, 3, 1, 2).ravel())
+                o += cnt
+            S2, S4, cs = cfg.image // 2, cfg.image // 4, 2 * cfg.growth
+            take(cfg.n, S2, S2, cs)
+            for bc in cfg.blocks():
+                for l in range(1, bc.layers + 1):
+                    take(bc.n, bc.h, bc.w, bc.c_in(l))
+                for l in range(1, bc.layers + 1):
+                    take(bc.n, bc.h, bc.w, bc.bottleneck)
+                take(bc.n, bc.h, bc.w, bc.c_out)
+            assert o == relu.size
+            out.append((np.concatenate(pieces), pool.reshape(cfg.n, S4, S4, cs).transpose(0, 3, 1, 2).ravel()))
+        return tuple(out)
+    finally:
+        dnb.dnb_inet_destroy(net)

@@ -360,6 +360,56 @@ int dnb_net_forward(dnb_net* net, const void* x, const int32_t* labels, const vo
 int dnb_net_backward(dnb_net* net, const void* x, const void* params, void* dparams, void* workspace,
                      void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Whole training step of an ImageNet-shaped DenseNet-BC (bf16 feature maps, NHWC; fp32 accumulation,
+ * statistics, parameters and parameter gradients): four dense blocks joined by the network's glue
+ * (paper Section 2, "DenseNet Architecture"; the ImageNet models of Section 5 have four blocks).
+ *   stem      7x7 conv, stride 2, pad 3, 3 -> 2k channels, no bias; BN -> ReLU;
+ *             3x3 max pool, stride 2, pad 1 (ties: first position in window scan order)
+ *   4 x       dense block of layers[b] bottleneck layers (B = 4k), run under `schedule`
+ *   between   transition: BN -> ReLU -> 1x1 conv (C -> C/2) -> 2x2 average pool, stride 2
+ *   tail      BN -> ReLU -> global average pool -> linear (+bias) to `classes`
+ *   loss      mean over the batch of the softmax cross-entropy
+ * Parameter pack (fp32; gradients same layout; query the offsets):
+ *   stem W[2k][3][7][7] g[2k] b[2k] | block 0 | trans 0: g[C] b[C] W[C/2][C] | block 1 | trans 1 |
+ *   block 2 | trans 2 | block 3 | tail: g[C] b[C] Wl[classes][C] bl[classes]
+ * x is (n, image, image, 3) bf16 (2-byte aligned), labels n int32: device pointers.  image is a
+ * multiple of 32; 2k is 16, 32, 64 or 96 (else DNB_E_UNSUPPORTED).  Errors, ownership and the
+ * forward-then-backward contract as for dnb_net_*. */
+typedef struct dnb_inet dnb_inet;
+typedef struct {
+  int32_t n, image;     /* batch; input height = width */
+  int32_t growth;       /* k */
+  int32_t layers[4];    /* bottleneck layers of the four dense blocks */
+  int32_t classes;
+  int32_t schedule;     /* DNB_SCHED_* of the dense blocks */
+  float eps;
+} dnb_inet_desc;
+/* parts of the pack for dnb_inet_param_offset: DNB_IP_BLOCK0 + 4*b + {0: block b, 1: g, 2: b of the
+ * BN that follows it, 3: W of transition b, or Wl of the tail for b = 3} */
+enum { DNB_IP_STEM_W = 0, DNB_IP_STEM_G = 1, DNB_IP_STEM_B = 2, DNB_IP_BLOCK0 = 3, DNB_IP_TAIL_BL = 19 };
+
+int dnb_inet_create(const dnb_inet_desc* desc, dnb_inet** out);
+void dnb_inet_destroy(dnb_inet* net);
+size_t dnb_inet_param_count(const dnb_inet* net);
+int dnb_inet_param_offset(const dnb_inet* net, int part, size_t* offset, size_t* count);
+size_t dnb_inet_workspace_bytes(const dnb_inet* net);
+size_t dnb_inet_peak_bytes(const dnb_inet* net);   /* feature-map bytes: the blocks' exact accounting plus the glue's */
+int dnb_inet_set_concurrency(dnb_inet* net, int enable);
+int dnb_inet_forward(dnb_inet* net, const void* x, const int32_t* labels, const void* params, float* loss,
+                     float* logits, void* workspace, void* stream);
+int dnb_inet_backward(dnb_inet* net, const void* x, const void* params, void* dparams, void* workspace,
+                      void* stream);
+/* The integers the step decides in floating point, as its kernels take them (for checking results
+ * against an evaluation in another precision): every ReLU decision, one byte each -- the stem's BN
+ * (n, image/2, image/2, 2k), then per block its d1, its d2 (see dnb_block_relu_decisions) and the
+ * decisions of the BN that follows it (n, h_b, w_b, C_out_b) -- and the max pool's positions 3*i + j
+ * inside each window, (n, image/4, image/4, 2k).  Call after dnb_inet_forward, same workspace and
+ * stream; relu and pool are device pointers. */
+size_t dnb_inet_relu_decision_bytes(const dnb_inet* net);
+size_t dnb_inet_pool_position_bytes(const dnb_inet* net);
+int dnb_inet_decisions(dnb_inet* net, const void* params, const void* workspace, void* relu, void* pool, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -451,6 +451,7 @@ double dnbo_inet_step(const dnbo_inet_desc* d, const double* x, const int32_t* l
         /* through the stem: pooling backward to the maxima's positions, BN+ReLU backward, weight gradient */
         double* da0 = (double*)malloc((size_t)(n * cs * S2 * S2) * sizeof(double));
         dnbo_maxpool3s2_backward(dfeat, pidx, n, cs, S2, S2, da0);
+        quant(da0, n * cs * S2 * S2, q); /* kept in bf16 between the pooling's and the BN's backward */
         if (use && mode == 1) dnbo_relu_backward_decisions(m_stem, da0, da0, n * cs * S2 * S2);
         else dnbo_relu_backward(a0, da0, da0, n * cs * S2 * S2);
         dnbo_bn_backward(s, da0, n, cs, S2 * S2, gs, smu, svar, d->eps, da0, dparams + (gs - params), dparams + (bs - params));

@@ -33,6 +33,11 @@ class dnb_net_desc(C.Structure):
                 ("classes", C.c_int32), ("schedule", C.c_int32), ("eps", C.c_float)]
 
 
+class dnb_inet_desc(C.Structure):
+    _fields_ = [("n", C.c_int32), ("image", C.c_int32), ("growth", C.c_int32), ("layers", C.c_int32 * 4),
+                ("classes", C.c_int32), ("schedule", C.c_int32), ("eps", C.c_float)]
+
+
 class dnb_block_memory(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in ("stored_fwd_bytes", "shared_fwd_bytes", "grad_bytes", "peak_bytes",
                                            "stats_bytes", "scratch_bytes", "workspace_bytes")]
@@ -105,6 +110,18 @@ _SIGS = {
     "dnb_net_set_concurrency": (C.c_int, [_vp, C.c_int]),
     "dnb_net_forward": (C.c_int, [_vp] * 8),
     "dnb_net_backward": (C.c_int, [_vp] * 6),
+    "dnb_inet_create": (C.c_int, [C.POINTER(dnb_inet_desc), C.POINTER(_vp)]),
+    "dnb_inet_destroy": (None, [_vp]),
+    "dnb_inet_param_count": (_sz, [_vp]),
+    "dnb_inet_param_offset": (C.c_int, [_vp, C.c_int, C.POINTER(_sz), C.POINTER(_sz)]),
+    "dnb_inet_workspace_bytes": (_sz, [_vp]),
+    "dnb_inet_peak_bytes": (_sz, [_vp]),
+    "dnb_inet_set_concurrency": (C.c_int, [_vp, C.c_int]),
+    "dnb_inet_forward": (C.c_int, [_vp] * 8),
+    "dnb_inet_backward": (C.c_int, [_vp] * 6),
+    "dnb_inet_relu_decision_bytes": (_sz, [_vp]),
+    "dnb_inet_pool_position_bytes": (_sz, [_vp]),
+    "dnb_inet_decisions": (C.c_int, [_vp] * 6),
 }
 for _name, (_res, _args) in _SIGS.items():
     _f = getattr(_lib, _name)
@@ -405,3 +422,60 @@ def dnb_net_forward(net, x, labels, params, loss, logits, workspace, stream=None
 
 def dnb_net_backward(net, x, params, dparams, workspace, stream=None) -> None:
     _check(_lib.dnb_net_backward(net, _ptr(x), _ptr(params), _ptr(dparams), _ptr(workspace), _stream(stream)))
+
+
+DNB_IP_STEM_W, DNB_IP_STEM_G, DNB_IP_STEM_B, DNB_IP_BLOCK0, DNB_IP_TAIL_BL = 0, 1, 2, 3, 19
+
+
+def dnb_inet_create(n, image, growth, layers, classes, schedule=DNB_SCHED_FUSED, eps=1e-5):
+    desc = dnb_inet_desc(n, image, growth, (C.c_int32 * 4)(*layers), classes, schedule, eps)
+    out = _vp()
+    _check(_lib.dnb_inet_create(C.byref(desc), C.byref(out)))
+    return out
+
+
+def dnb_inet_destroy(net) -> None:
+    _lib.dnb_inet_destroy(net)
+
+
+def dnb_inet_param_count(net) -> int:
+    return int(_lib.dnb_inet_param_count(net))
+
+
+def dnb_inet_param_offset(net, part: int):
+    off, cnt = _sz(), _sz()
+    _check(_lib.dnb_inet_param_offset(net, part, C.byref(off), C.byref(cnt)))
+    return int(off.value), int(cnt.value)
+
+
+def dnb_inet_workspace_bytes(net) -> int:
+    return int(_lib.dnb_inet_workspace_bytes(net))
+
+
+def dnb_inet_peak_bytes(net) -> int:
+    return int(_lib.dnb_inet_peak_bytes(net))
+
+
+def dnb_inet_set_concurrency(net, enable: bool) -> None:
+    _check(_lib.dnb_inet_set_concurrency(net, 1 if enable else 0))
+
+
+def dnb_inet_forward(net, x, labels, params, loss, logits, workspace, stream=None) -> None:
+    _check(_lib.dnb_inet_forward(net, _ptr(x), _ptr(labels), _ptr(params), _ptr(loss), _ptr(logits), _ptr(workspace),
+                                 _stream(stream)))
+
+
+def dnb_inet_backward(net, x, params, dparams, workspace, stream=None) -> None:
+    _check(_lib.dnb_inet_backward(net, _ptr(x), _ptr(params), _ptr(dparams), _ptr(workspace), _stream(stream)))
+
+
+def dnb_inet_relu_decision_bytes(net) -> int:
+    return int(_lib.dnb_inet_relu_decision_bytes(net))
+
+
+def dnb_inet_pool_position_bytes(net) -> int:
+    return int(_lib.dnb_inet_pool_position_bytes(net))
+
+
+def dnb_inet_decisions(net, params, workspace, relu, pool, stream=None) -> None:
+    _check(_lib.dnb_inet_decisions(net, _ptr(params), _ptr(workspace), _ptr(relu), _ptr(pool), _stream(stream)))

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdnb.so")
-SOURCES = ["dnb_elem.hip", "dnb_conv_f32.hip", "dnb_conv_f32_fast.hip", "dnb_nhwc_bf16.hip", "dnb_block.hip", "dnb_net.hip"]
+SOURCES = ["dnb_elem.hip", "dnb_conv_f32.hip", "dnb_conv_f32_fast.hip", "dnb_nhwc_bf16.hip", "dnb_block.hip", "dnb_net.hip", "dnb_inet.hip"]
 # Packed-fp32 instruction selection is switched off for all device code on this target.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -120,6 +120,18 @@ hipError_t launch_relu_decisions(const float* u, int64_t stride, int n, int c, i
                      c, hw, 0, gamma, beta, mean, istd, out);
   return hipGetLastError();
 }
+
+hipError_t launch_relu_decisions_rows(const void* u, int64_t ld, int64_t P, int c, const float* gamma, const float* beta,
+                                      const float* mean, const float* istd, unsigned char* out, hipStream_t st) {
+  if (P >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
+  const int64_t total = P * c;
+  int64_t g = (total + 256 * 8 - 1) / (256 * 8);
+  if (g < 1) g = 1;
+  if (g > 65535) g = 65535;
+  hipLaunchKernelGGL(k_relu_decisions<unsigned short>, dim3((unsigned)g), dim3(256), 0, st, (const unsigned short*)u,
+                     (int64_t)0, (int64_t)1, ld, 1, c, (int)P, 1, gamma, beta, mean, istd, out);
+  return hipGetLastError();
+}
 }  // namespace dnb
 
 namespace {

@@ -64,6 +64,16 @@ hipError_t launch_relu_decisions(const float* u, int64_t stride, int n, int c, i
                                  const float* beta, const float* mean, const float* istd, unsigned char* out,
                                  hipStream_t st);
 
+// the same for a bf16 tensor of P rows of c channels (pixel stride ld): out[p*c + ch]
+hipError_t launch_relu_decisions_rows(const void* u, int64_t ld, int64_t P, int c, const float* gamma, const float* beta,
+                                      const float* mean, const float* istd, unsigned char* out, hipStream_t st);
+
+// ---- the classifier head of the network steps (fp32): linear + mean softmax cross-entropy, and its backward
+hipError_t launch_head_forward(const float* pooled, const float* wl, const float* bl, const int32_t* labels, float* logits,
+                               float* dlogits, float* terms, float* loss, int n, int c, int classes, hipStream_t st);
+hipError_t launch_head_backward(const float* dlogits, const float* pooled, const float* wl, float* dpooled, float* dwl,
+                                float* dbl, int n, int c, int classes, hipStream_t st);
+
 // ---- convolutions (MFMA implicit GEMM, fp32) -----------------------------------------------
 
 // Weight addressing for the implicit-GEMM kernel: element (m = output channel, c = input

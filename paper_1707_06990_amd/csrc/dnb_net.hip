@@ -162,6 +162,27 @@ inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) &
 }  // namespace
 }  // namespace dnb
 
+namespace dnb {
+// The classifier head shared by the two network steps: logits = pooled . Wl^T + bl, mean softmax
+// cross-entropy with its gradient (all fp32), and the head's backward pass.
+hipError_t launch_head_forward(const float* pooled, const float* wl, const float* bl, const int32_t* labels, float* logits,
+                               float* dlogits, float* terms, float* loss, int n, int c, int classes, hipStream_t st) {
+  hipLaunchKernelGGL(k_linear, dim3(grid_for((int64_t)n * classes, kT / 64)), dim3(kT), 0, st, pooled, wl, bl, logits, n, c,
+                     classes);
+  hipLaunchKernelGGL(k_softmax_xent, dim3(1), dim3(kT), 0, st, logits, labels, dlogits, terms, loss, n, classes);
+  return hipGetLastError();
+}
+
+hipError_t launch_head_backward(const float* dlogits, const float* pooled, const float* wl, float* dpooled, float* dwl,
+                                float* dbl, int n, int c, int classes, hipStream_t st) {
+  hipLaunchKernelGGL(k_linear_bwd_data, dim3(grid_for((int64_t)n * c, kT)), dim3(kT), 0, st, dlogits, wl, dpooled, n, c,
+                     classes);
+  hipLaunchKernelGGL(k_linear_bwd_weights, dim3(grid_for((int64_t)classes * c, kT)), dim3(kT), 0, st, dlogits, pooled, dwl,
+                     dbl, n, c, classes);
+  return hipGetLastError();
+}
+}  // namespace dnb
+
 using namespace dnb;
 
 struct dnb_net {
@@ -416,11 +437,9 @@ int dnb_net_forward(dnb_net* net, const void* xv, const int32_t* labels, const v
       float* logits = (float*)(ws + net->o_logits);
       const int64_t planes = (int64_t)n * co;
       hipLaunchKernelGGL(k_global_avgpool, dim3(grid_for(planes, kT / 64)), dim3(kT), 0, st, tz, pooled, planes, hw);
-      hipLaunchKernelGGL(k_linear, dim3(grid_for((int64_t)n * d.classes, kT / 64)), dim3(kT), 0, st, pooled,
-                         params + net->p_w[2], params + net->p_bl, logits, n, co, d.classes);
-      hipLaunchKernelGGL(k_softmax_xent, dim3(1), dim3(kT), 0, st, logits, labels, (float*)(ws + net->o_dlogits),
-                         (float*)(ws + net->o_terms), loss, n, d.classes);
       DNB_TRYH(hipGetLastError());
+      DNB_TRYH(launch_head_forward(pooled, params + net->p_w[2], params + net->p_bl, labels, logits,
+                                   (float*)(ws + net->o_dlogits), (float*)(ws + net->o_terms), loss, n, co, d.classes, st));
       if (logits_out)
         DNB_TRYH(launch_copy_slab(logits, (int64_t)n * d.classes, logits_out, (int64_t)n * d.classes, 1,
                                   (int64_t)n * d.classes, st));
@@ -451,10 +470,8 @@ int dnb_net_backward(dnb_net* net, const void* xv, const void* paramsv, void* dp
     const float* dlogits = (const float*)(ws + net->o_dlogits);
     const float* pooled = (const float*)(ws + net->o_pooled);
     float* dpooled = (float*)(ws + net->o_dpooled);
-    hipLaunchKernelGGL(k_linear_bwd_data, dim3(grid_for((int64_t)n * C, kT)), dim3(kT), 0, st, dlogits,
-                       params + net->p_w[2], dpooled, n, C, d.classes);
-    hipLaunchKernelGGL(k_linear_bwd_weights, dim3(grid_for((int64_t)d.classes * C, kT)), dim3(kT), 0, st, dlogits,
-                       pooled, dparams + net->p_w[2], dparams + net->p_bl, n, C, d.classes);
+    DNB_TRYH(launch_head_backward(dlogits, pooled, params + net->p_w[2], dpooled, dparams + net->p_w[2],
+                                  dparams + net->p_bl, n, C, d.classes, st));
     hipLaunchKernelGGL(k_global_avgpool_bwd, dim3(grid_for((int64_t)n * C * hw, kT * 4)), dim3(kT), 0, st, dpooled,
                        dtz, (int64_t)n * C, hw);
     DNB_TRYH(hipGetLastError());

@@ -324,3 +324,46 @@ def test_net_workspace_pieces_hold_their_largest_writer(dnb, depth, growth, n):
     for key, nbytes in need.items():
         assert size[key] >= nbytes, (key, size[key], nbytes)
     dnb.dnb_net_destroy(net)
+
+
+INET_PARTS = {"stem.W": 0, "stem.g": 1, "stem.b": 2, "tail.bl": 19}
+for _b in range(4):
+    INET_PARTS[f"block{_b}"] = 3 + 4 * _b
+    _pre = f"trans{_b}" if _b < 3 else "tail"
+    INET_PARTS[f"{_pre}.g"], INET_PARTS[f"{_pre}.b"] = 4 + 4 * _b, 5 + 4 * _b
+    INET_PARTS[f"{_pre}.W" if _b < 3 else "tail.Wl"] = 6 + 4 * _b
+
+
+@pytest.mark.parametrize("cfg", [wl.InetCfg(2, 64, 8, (2, 2, 2, 2), 5), wl.inet_config4(), wl.inet_config5()],
+                         ids=["tiny", "densenet161", "densenet264"])
+def test_inet_param_layout_matches_oracle_and_bytes(dnb, oracle, cfg):
+    s = oracle.InetShape(cfg.n, cfg.image, cfg.growth, tuple(cfg.layers), cfg.classes, cfg.eps)
+    net = dnb.dnb_inet_create(cfg.n, cfg.image, cfg.growth, cfg.layers, cfg.classes, schedule=2)
+    assert dnb.dnb_inet_param_count(net) == oracle.inet_param_count(s)
+    for name, sl in oracle.inet_param_slices(s).items():
+        off, cnt = dnb.dnb_inet_param_offset(net, INET_PARTS[name])
+        assert (off, off + cnt) == (sl.start, sl.stop), name
+    with pytest.raises(dnb.binding.DnbError):
+        dnb.dnb_inet_param_offset(net, 20)
+    nr, npool = oracle.inet_decision_counts(s)
+    assert dnb.dnb_inet_relu_decision_bytes(net) == nr and dnb.dnb_inet_pool_position_bytes(net) == npool
+    blocks = cfg.blocks()
+    cs, S2, S4 = 2 * cfg.growth, cfg.image // 2, cfg.image // 4
+    glue = cfg.n * S2 * S2 * cs * 2 * 2 + cfg.n * S4 * S4 * cs                 # stem output and its gradient, pooling positions
+    glue += sum((b.c0 + b.c_out) * b.pixels * 2 for b in blocks)              # block inputs and outputs
+    glue += 2 * max((b.c_out // 2) * b.pixels for b in blocks[:3]) * 2        # transition conv output and its gradient
+    glue += 2 * max(b.c_out * b.pixels for b in blocks) * 2 + max(b.c0 * b.pixels for b in blocks) * 2   # gradient buffers
+    inner = sum((b.layers * b.bottleneck) * b.pixels * 2 + b.c_out * b.pixels * 4 + (b.c_in(b.layers) + b.bottleneck) * b.pixels * 2
+                for b in blocks)
+    assert dnb.dnb_inet_peak_bytes(net) == glue + inner <= dnb.dnb_inet_workspace_bytes(net)
+    dnb.dnb_inet_destroy(net)
+
+
+@pytest.mark.parametrize("kw,code", [(dict(n=0), -1), (dict(image=48), -1), (dict(layers=(2, 0, 2, 2)), -1), (dict(classes=0), -1),
+                                     (dict(growth=12), -5), (dict(growth=8, layers=(1, 2, 2, 2)), -5)])
+def test_inet_descriptor_validation(dnb, kw, code):
+    base = dict(n=2, image=64, growth=8, layers=(2, 2, 2, 2), classes=5)
+    base.update(kw)
+    with pytest.raises(dnb.binding.DnbError) as e:
+        dnb.dnb_inet_create(**base)
+    assert e.value.status == code
