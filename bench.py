@@ -136,6 +136,58 @@ class NetRun:
         self.workspace = dnb.dnb_net_workspace_bytes(self.h)
 
 
+class InetRun:
+    """Device buffers + handle of one whole ImageNet-shaped network (bf16 NHWC)."""
+
+    def __init__(self, dnb, torch, wl, icfg, schedule):
+        import numpy as np
+        from harness import dev, pack_params_gpu
+        self.cfg = icfg
+        self.dnb = dnb
+        self.h = dnb.dnb_inet_create(icfg.n, icfg.image, icfg.growth, icfg.layers, icfg.classes, schedule=schedule, eps=icfg.eps)
+        x, labels, params = wl.make_inet_inputs(icfg)
+        flat = np.zeros(dnb.dnb_inet_param_count(self.h), dtype=np.float32)
+
+        def put(part, arr):
+            off, cnt = dnb.dnb_inet_param_offset(self.h, part)
+            assert cnt == arr.size
+            flat[off:off + cnt] = np.asarray(arr, dtype=np.float32).ravel()
+
+        put(dnb.DNB_IP_STEM_W, params["stem"]["W"])
+        put(dnb.DNB_IP_STEM_G, params["stem"]["g"])
+        put(dnb.DNB_IP_STEM_B, params["stem"]["b"])
+        for b, bc in enumerate(icfg.blocks()):
+            hb = dnb.dnb_block_create(1, bc.c0, 8, 8, bc.layers, bc.growth, bc.bottleneck, eps=bc.eps)   # the pack layout only
+            put(dnb.DNB_IP_BLOCK0 + 4 * b, pack_params_gpu(dnb, hb, params[f"block{b}"]))
+            dnb.dnb_block_destroy(hb)
+            pre = params[f"trans{b}"] if b < 3 else params["tail"]
+            put(dnb.DNB_IP_BLOCK0 + 4 * b + 1, pre["g"])
+            put(dnb.DNB_IP_BLOCK0 + 4 * b + 2, pre["b"])
+            put(dnb.DNB_IP_BLOCK0 + 4 * b + 3, pre["W"] if b < 3 else pre["Wl"])
+        put(dnb.DNB_IP_TAIL_BL, params["tail"]["bl"])
+        self.x = torch.from_numpy(x).permute(0, 2, 3, 1).contiguous().to("cuda", torch.bfloat16)
+        self.labels = torch.from_numpy(labels).to("cuda")
+        self.params = dev(flat)
+        self.dparams = torch.empty_like(self.params)
+        self.loss = torch.zeros(1, device="cuda")
+        self.ws = torch.empty(dnb.dnb_inet_workspace_bytes(self.h), dtype=torch.uint8, device="cuda")
+        self.peak = dnb.dnb_inet_peak_bytes(self.h)
+        self.workspace = dnb.dnb_inet_workspace_bytes(self.h)
+
+    def close(self):
+        if self.h is not None:
+            self.dnb.dnb_inet_destroy(self.h)
+            self.h = None
+
+
+def make_inet_step(dnb, r, forward_only=False):
+    def step():
+        dnb.dnb_inet_forward(r.h, r.x, r.labels, r.params, r.loss, None, r.ws)
+        if not forward_only:
+            dnb.dnb_inet_backward(r.h, r.x, r.params, r.dparams, r.ws)
+    return step
+
+
 def make_net_step(dnb, r, forward_only=False):
     def step():
         dnb.dnb_net_forward(r.h, r.x, r.labels, r.params, r.loss, None, r.ws)
@@ -386,6 +438,33 @@ def extra_bf16_blocks(dnb, torch, wl, name, steps, warmup):
     return out
 
 
+def extra_bf16_net(dnb, torch, wl, name, steps, warmup):
+    """The whole training step of an ImageNet-shaped bf16 / NHWC workload (batch 32, 224x224 inputs:
+    stem, max pool, four dense blocks, transitions, head, loss): the fused schedule as the library
+    runs it by default and the three schedules in program order on one stream, with the exact
+    feature-map bytes of the whole network."""
+    sched = {"shared": dnb.DNB_SCHED_SHARED, "store_all": dnb.DNB_SCHED_STORE_ALL, "fused": dnb.DNB_SCHED_FUSED}
+    icfg = wl.inet_config4() if name == "config4" else wl.inet_config5()
+    shape = "DenseNet-161-shaped k=48, blocks 6-12-36-24" if name == "config4" else "DenseNet-264-shaped k=32, blocks 6-12-64-48"
+    out = {"workload": f"{shape}, batch {icfg.n}, 3x224x224 inputs, bf16 NHWC, whole network: 7x7 stride-2 stem, max pool, 4 dense "
+                       "blocks, 3 transitions, head, softmax cross-entropy (fwd+bwd)", "steps": steps, "warmup": warmup}
+    t = {}
+    for label, sname, serial in (("fused", "fused", False), ("fused_one_stream", "fused", True), ("shared", "shared", True),
+                                 ("store_all", "store_all", True)):
+        r = InetRun(dnb, torch, wl, icfg, sched[sname])
+        if serial:
+            dnb.dnb_inet_set_concurrency(r.h, False)
+        t[label] = time_steps(torch, make_inet_step(dnb, r), steps, warmup, True)
+        out[label] = {"images_per_s": round(icfg.n * steps / t[label], 2), "ms_per_step": round(1e3 * t[label] / steps, 4),
+                      "network_feature_map_bytes": r.peak, "workspace_bytes": r.workspace}
+        r.close()
+        del r
+        torch.cuda.empty_cache()
+    out["recompute_overhead"] = round(t["shared"] / t["store_all"] - 1.0, 4)
+    out["fused_vs_store_all_time"] = round(t["fused_one_stream"] / t["store_all"] - 1.0, 4)
+    return out
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -416,9 +495,20 @@ def main():
         secs = time_steps(torch, make_step(dnb, runs, a.forward_only), a.steps, a.warmup, use_graph)
         return runs, secs
 
+    if bf16 and a.only_block < 0 and a.scope in ("auto", "net"):
+        # the ImageNet-shaped workloads as whole training steps (diagnostic line of their own)
+        res = extra_bf16_net(dnb, torch, wl, a.workload, a.steps, a.warmup)
+        res["dense_blocks_only"] = extra_bf16_blocks(dnb, torch, wl, a.workload, a.steps, a.warmup)
+        print(json.dumps({"metric": "train images/sec per MI355X (fwd+bwd) + peak feature-map bytes vs depth",
+                          "value": res["fused"]["images_per_s"], "unit": "images/s", "n_gpus": 1, "steps": a.steps,
+                          "warmup": a.warmup, "ms_per_step": res["fused"]["ms_per_step"], "higher_is_better": True,
+                          "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": res["workload"], "schedule": "fused", "launch": "hip_graph",
+                                     "global_batch": 32}, "detail": res}), flush=True)
+        return
     net_scope = a.scope == "net" or (a.scope == "auto" and a.workload in ("config2", "config3") and a.only_block < 0)
     if net_scope and a.workload not in ("config2", "config3"):
-        print("bench.py: the whole-network step is built for the CIFAR-shaped fp32 networks (config2, config3)", file=sys.stderr)
+        print("bench.py: --scope net with --only-block is not a combination", file=sys.stderr)
         sys.exit(2)
     ncfg = None
     if net_scope:
@@ -495,8 +585,10 @@ def main():
         # the other workloads, so that one run of the default command measures them all: the largest
         # fp32 network as a whole training step, the two bf16 workloads as their dense-block sets
         out["config3"] = extra_fp32_net(dnb, torch, wl, "config3", 10, 3)
-        out["config4_dense_blocks"] = extra_bf16_blocks(dnb, torch, wl, "config4", 10, 3)
-        out["config5_dense_blocks"] = extra_bf16_blocks(dnb, torch, wl, "config5", 10, 3)
+        out["config4"] = extra_bf16_net(dnb, torch, wl, "config4", 10, 3)
+        out["config4"]["dense_blocks_only"] = extra_bf16_blocks(dnb, torch, wl, "config4", 10, 3)
+        out["config5"] = extra_bf16_net(dnb, torch, wl, "config5", 10, 3)
+        out["config5"]["dense_blocks_only"] = extra_bf16_blocks(dnb, torch, wl, "config5", 10, 3)
     if not a.no_cpu_baseline and not bf16:
         out["cpu_baseline"] = cpu_baseline_net(wl, ncfg) if net_scope else cpu_baseline(wl, blocks)
     print(json.dumps(out), flush=True)
