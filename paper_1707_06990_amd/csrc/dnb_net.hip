@@ -83,23 +83,30 @@ __global__ __launch_bounds__(kT) void k_linear(const float* __restrict__ f, cons
   if (lane == 0) logits[idx] = s + bl[o];
 }
 
-// Per sample: log-sum-exp, loss term, dlogits = (softmax - onehot)/n.  Then the loss terms are
-// added in sample order by thread 0 (n is a batch size: a few hundred at most).  One workgroup.
+// Per sample: log-sum-exp, loss term, dlogits = (softmax - onehot)/n.  One workgroup; each wave takes
+// samples wave, wave + 4, ... and its lanes stride over the classes (butterfly maximum and sum, so
+// every lane holds the same values).  Then the loss terms are added in sample order by thread 0 (n
+// is a batch size: a few hundred at most).
 __global__ __launch_bounds__(kT) void k_softmax_xent(const float* __restrict__ logits,
                                                      const int32_t* __restrict__ labels, float* __restrict__ dlogits,
                                                      float* __restrict__ terms, float* __restrict__ loss, int n,
                                                      int classes) {
-  for (int i = threadIdx.x; i < n; i += kT) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int i = wave; i < n; i += kT / 64) {
     const float* z = logits + (int64_t)i * classes;
-    float mx = z[0];
-    for (int o = 1; o < classes; ++o) mx = fmaxf(mx, z[o]);
+    float mx = -3.4e38f;
+    for (int o = lane; o < classes; o += 64) mx = fmaxf(mx, z[o]);
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
     float se = 0.f;
-    for (int o = 0; o < classes; ++o) se += expf(z[o] - mx);
+    for (int o = lane; o < classes; o += 64) se += expf(z[o] - mx);
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) se += __shfl_xor(se, off, 64);
     const float lse = mx + logf(se);
     const int lab = labels[i];
     const bool valid = lab >= 0 && lab < classes;  // a sample with a label out of range adds nothing
-    terms[i] = valid ? lse - z[lab] : 0.f;
-    for (int o = 0; o < classes; ++o)
+    if (lane == 0) terms[i] = valid ? lse - z[lab] : 0.f;
+    for (int o = lane; o < classes; o += 64)
       dlogits[(int64_t)i * classes + o] = valid ? (expf(z[o] - lse) - (o == lab ? 1.f : 0.f)) / (float)n : 0.f;
   }
   __syncthreads();
@@ -110,16 +117,26 @@ __global__ __launch_bounds__(kT) void k_softmax_xent(const float* __restrict__ l
   }
 }
 
-// df[i][j] = sum_o dlogits[i][o] Wl[o][j]   (thread per (i, j))
+// df[i][j] = sum_o dlogits[i][o] Wl[o][j]: a thread owns column j for a group of 8 samples, so a weight
+// is read once per 8 samples (the dlogits reads are the same for the whole wave).  grid (ceil(c/256), ceil(n/8)).
 __global__ __launch_bounds__(kT) void k_linear_bwd_data(const float* __restrict__ dlogits,
                                                         const float* __restrict__ wl, float* __restrict__ df, int n,
                                                         int c, int classes) {
-  const int idx = blockIdx.x * kT + threadIdx.x;
-  if (idx >= n * c) return;
-  const int i = idx / c, j = idx - i * c;
-  float s = 0.f;
-  for (int o = 0; o < classes; ++o) s = __fmaf_rn(dlogits[(int64_t)i * classes + o], wl[(int64_t)o * c + j], s);
-  df[idx] = s;
+  const int j = blockIdx.x * kT + threadIdx.x, i0 = blockIdx.y * 8;
+  if (j >= c) return;
+  const int ni = min(8, n - i0);
+  float acc[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) acc[u] = 0.f;
+  for (int o = 0; o < classes; ++o) {
+    const float w = wl[(int64_t)o * c + j];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (u < ni) acc[u] = __fmaf_rn(dlogits[(int64_t)(i0 + u) * classes + o], w, acc[u]);
+  }
+#pragma unroll
+  for (int u = 0; u < 8; ++u)
+    if (u < ni) df[(int64_t)(i0 + u) * c + j] = acc[u];
 }
 
 // dWl[o][j] = sum_i dlogits[i][o] f[i][j] (thread per (o, j)); dbl[o] = sum_i dlogits[i][o] (j == 0).
@@ -175,8 +192,8 @@ hipError_t launch_head_forward(const float* pooled, const float* wl, const float
 
 hipError_t launch_head_backward(const float* dlogits, const float* pooled, const float* wl, float* dpooled, float* dwl,
                                 float* dbl, int n, int c, int classes, hipStream_t st) {
-  hipLaunchKernelGGL(k_linear_bwd_data, dim3(grid_for((int64_t)n * c, kT)), dim3(kT), 0, st, dlogits, wl, dpooled, n, c,
-                     classes);
+  hipLaunchKernelGGL(k_linear_bwd_data, dim3((unsigned)((c + kT - 1) / kT), (unsigned)((n + 7) / 8)), dim3(kT), 0, st, dlogits,
+                     wl, dpooled, n, c, classes);
   hipLaunchKernelGGL(k_linear_bwd_weights, dim3(grid_for((int64_t)classes * c, kT)), dim3(kT), 0, st, dlogits, pooled, dwl,
                      dbl, n, c, classes);
   return hipGetLastError();
