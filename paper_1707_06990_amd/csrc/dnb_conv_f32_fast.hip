@@ -761,7 +761,7 @@ struct Wg1Args {
 };
 
 // the work of workgroup (bx, by, bz) of the 1x1 weight gradient's grid
-template <int MTW, int CTW, bool PRO>
+template <int MTW, int CTW, bool PRO, int NST>
 __device__ __forceinline__ void wgrad1x1_body(const Wg1Args& A, int bx, int by, int bz) {
   extern __shared__ float lds[];
   const float* __restrict__ a = A.a;
@@ -786,8 +786,8 @@ __device__ __forceinline__ void wgrad1x1_body(const Wg1Args& A, int bx, int by, 
     fl[y] = (PRO && c < cin) ? fold[c] : make_float2(1.f, 0.f);
   }
 
-  // Operands are requested two steps ahead into two register stages (loop unrolled by two so
-  // the stages are indexed statically).  Every load is unconditional at an address clamped into
+  // Operands are requested NST steps ahead into NST register stages (loop unrolled by NST so the
+  // stages are indexed statically).  Every load is unconditional at an address clamped into
   // the tensors, so a step waits for its own operands only; what a clamped load stands in for
   // (a step past the range, pixels past the image) is zeroed when the stage is consumed, and
   // rows past cout / cin are computed on repeated data and never stored.
@@ -821,7 +821,7 @@ __device__ __forceinline__ void wgrad1x1_body(const Wg1Args& A, int bx, int by, 
         Bu[y].w = fmaxf(__fmaf_rn(Bu[y].w, fl[y].x, fl[y].y), 0.f);
       }
     }
-    request(s + 8, A, Bv);  // this stage's next use
+    request(s + 4 * NST, A, Bv);  // this stage's next use
 #pragma unroll
     for (int e = 0; e < 4; ++e)
 #pragma unroll
@@ -830,13 +830,14 @@ __device__ __forceinline__ void wgrad1x1_body(const Wg1Args& A, int bx, int by, 
         for (int y = 0; y < CTW; ++y) acc[x * CTW + y] = mfma16(elem(Au[x], e), elem(Bu[y], e), acc[x * CTW + y]);
   };
   {
-    float4 A0[MTW], B0[CTW], A1[MTW], B1[CTW];
+    float4 As[NST][MTW], Bs[NST][CTW];
     const int s0 = s_begin + wave;
-    request(s0, A0, B0);
-    request(s0 + 4, A1, B1);
-    for (int s = s0; s < s_end; s += 8) {
-      step(s, A0, B0);
-      step(s + 4, A1, B1);
+#pragma unroll
+    for (int i = 0; i < NST; ++i) request(s0 + 4 * i, As[i], Bs[i]);
+    for (int s = s0; s < s_end; s += 4 * NST) {
+#pragma unroll
+      for (int i = 0; i < NST; ++i)
+        if (i == 0 || s + 4 * i < s_end) step(s + 4 * i, As[i], Bs[i]);
     }
   }
 
@@ -863,7 +864,7 @@ __global__ __launch_bounds__(256) void k_wgrad1x1_fast(Wg1Args A, SumRole sr, in
     if (wg < sr.wgs) sum_role(sr, wg);
     return;
   }
-  wgrad1x1_body<MTW, CTW, PRO>(A, blockIdx.x, blockIdx.y, blockIdx.z);
+  wgrad1x1_body<MTW, CTW, PRO, 2>(A, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 // ------------------------------------------------------------------------------- 3x3 wgrad
@@ -1081,14 +1082,31 @@ __global__ __launch_bounds__(256) void k_wgrad3x3_fast(Wg3Args A, SumRole sr, in
 // everything that follows them): a 1-D grid whose first n1 workgroups are the 1x1's (few and long,
 // so they start first: 41.9 -> 38.4 us per launch on the first dense block of DenseNet-BC-100
 // against the 3x3's first), the next n3 the 3x3's, then the BN backward reduction carried along
-// (before the 3x3's it measured slower, after the sums the same), then the two pending sums.
+// (before the 3x3's it measured slower, after the sums the same; spread evenly among the weight
+// gradients' workgroups, so that traffic and matrix work share every CU for the whole launch,
+// 36.7 -> 44.1 us: a streaming workgroup takes the place of a second matrix one, and one wave per
+// SIMD does not cover the operand latency), then the two pending sums.
+// Three waves per SIMD asked of the register allocator: left alone it spends accumulation registers
+// freely (139 + 52 on the k = 24 shapes) and two waves per SIMD do not cover the operand latency of
+// the 1x1 role; 140 registers hold the same code without spilling.
 template <int M1, int C1, int M3, int C3, bool PRO>
-__global__ __launch_bounds__(256) void k_wgrad_pair(Wg1Args A1, int gy1, int gz1, int n1, Wg3Args A3, int gy3, int gz3,
+__global__ __launch_bounds__(256, 3) void k_wgrad_pair(Wg1Args A1, int gx1, int gy1, int gz1, int n1, Wg3Args A3, int gy3, int gz3,
                                                     int n3, SumRole s1, SumRole s3, BnBwdPartialArgs bn, int nbn) {
   int id = blockIdx.x;
   if (id < n1) {
-    const int bz = id % gz1, by = (id / gz1) % gy1, bx = id / (gz1 * gy1);
-    wgrad1x1_body<M1, C1, PRO>(A1, bx, by, bz);
+    // Workgroups go to the 8 XCDs in turn (id % 8), each with an L2 of its own.  All the (c, m)
+    // tile columns of one pixel range read the same gradient rows, and the m groups of a c column
+    // the same feature rows: pixel range bx is given to XCD bx % 8 whole, so that these rows come
+    // from HBM once and from that XCD's L2 afterwards (measured HBM bytes per launch 190 -> 176 MB
+    // on DenseNet-BC-100's first block, 776 -> 556 MB on DenseNet-BC-250's).  n1 counts
+    // ceil(gx1 / 8) ranges per XCD; the ids past the last range have no work.
+    const int xcd = id & 7, slot = id >> 3, cols = gy1 * gz1;
+    const int col = slot % cols, bx = (slot / cols) * 8 + xcd;
+    if (bx >= gx1) return;
+    // three operand stages beside the narrow 3x3 tiles of k = 12 nets (37.8 -> 37.5 us per launch on
+    // the first dense block of DenseNet-BC-100), two beside the wide ones (157 against 162 us on
+    // DenseNet-BC-250's, where the third stage's registers come out of the same two waves per SIMD)
+    wgrad1x1_body<M1, C1, PRO, (M3 == 1 ? 3 : 2)>(A1, bx, col / gz1, col % gz1);
     return;
   }
   id -= n1;
@@ -1540,7 +1558,7 @@ bool launch_wgrad_pair_fast(const float* in1, int64_t in1_stride, const float* g
   const int hw = h * w;
   const Wg1Args A1{in1, in1_stride, g1, g1_stride, part1, cin1, B, hw, p1.spi, p1.total_steps, p1.steps_per_wg, fold1};
   const Wg3Args A3{in3, in3_stride, g3, g3_stride, part3, B, cout3, h, w, p3.tiles_per_img, p3.nms, p3.PA, fold3};
-  const int n1 = p1.gx * p1.gy * p1.gz, n3 = p3.gx * p3.gy * p3.gz;
+  const int n1 = (p1.gx + 7) / 8 * 8 * p1.gy * p1.gz, n3 = p3.gx * p3.gy * p3.gz;  // 1x1: whole pixel ranges per XCD
   const BnBwdPartialArgs bna = bn ? *bn : BnBwdPartialArgs{};
   const int nbn = bn ? bn->c * bn->splits : 0;
   const dim3 grid((unsigned)(n1 + n3 + nbn + s1.wgs + s3.wgs));
@@ -1548,8 +1566,8 @@ bool launch_wgrad_pair_fast(const float* in1, int64_t in1_stride, const float* g
 #define DNB_P(C1, M3, C3)                                                                                             \
   do {                                                                                                                \
     if (fold1) hipExtLaunchKernelGGL((k_wgrad_pair<3, C1, M3, C3, true>), grid, dim3(256), lds, st, ev0, ev1, 0, A1,  \
-                                     p1.gy, p1.gz, n1, A3, p3.gy, p3.gz, n3, s1, s3, bna, nbn);                       \
-    else hipExtLaunchKernelGGL((k_wgrad_pair<3, C1, M3, C3, false>), grid, dim3(256), lds, st, ev0, ev1, 0, A1, p1.gy, \
+                                     p1.gx, p1.gy, p1.gz, n1, A3, p3.gy, p3.gz, n3, s1, s3, bna, nbn);                       \
+    else hipExtLaunchKernelGGL((k_wgrad_pair<3, C1, M3, C3, false>), grid, dim3(256), lds, st, ev0, ev1, 0, A1, p1.gx, p1.gy, \
                                p1.gz, n1, A3, p3.gy, p3.gz, n3, s1, s3, bna, nbn);                                    \
   } while (0)
 #define DNB_P1(M3, C3)                                                                          \
