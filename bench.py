@@ -410,7 +410,7 @@ def extra_fp32_net(dnb, torch, wl, name, steps, warmup):
     return out
 
 
-def extra_bf16_blocks(dnb, torch, wl, name, steps, warmup):
+def extra_bf16_blocks(dnb, torch, wl, name, steps, warmup, use_graph=True, compare=True):
     """The dense-block set of an ImageNet-shaped bf16 / NHWC workload (batch 32): the fused schedule
     as the library runs it by default (weight gradients on a helper stream) and, for the recompute
     overhead, the three schedules in program order on one stream (the materialised ones only run
@@ -422,23 +422,26 @@ def extra_bf16_blocks(dnb, torch, wl, name, steps, warmup):
     t = {}
     for label, sname, serial in (("fused", "fused", False), ("fused_one_stream", "fused", True), ("shared", "shared", True),
                                  ("store_all", "store_all", True)):
+        if not compare and label != "fused":
+            continue
         runs = [BlockRun(dnb, torch, wl, c, sched[sname], 10 * i, True) for i, c in enumerate(blocks)]
         if serial:
             for r in runs:
                 dnb.dnb_block_set_concurrency(r.h, False)
-        t[label] = time_steps(torch, make_step(dnb, runs), steps, warmup, True)
+        t[label] = time_steps(torch, make_step(dnb, runs), steps, warmup, use_graph)
         out[label] = {"images_per_s": round(batch * steps / t[label], 2), "ms_per_step": round(1e3 * t[label] / steps, 4),
                       "feature_map_bytes": sum(r.mem["peak_bytes"] for r in runs)}
         for r in runs:
             r.close()
         del runs
         torch.cuda.empty_cache()
-    out["recompute_overhead"] = round(t["shared"] / t["store_all"] - 1.0, 4)
-    out["fused_vs_store_all_time"] = round(t["fused_one_stream"] / t["store_all"] - 1.0, 4)
+    if compare:
+        out["recompute_overhead"] = round(t["shared"] / t["store_all"] - 1.0, 4)
+        out["fused_vs_store_all_time"] = round(t["fused_one_stream"] / t["store_all"] - 1.0, 4)
     return out
 
 
-def extra_bf16_net(dnb, torch, wl, name, steps, warmup):
+def extra_bf16_net(dnb, torch, wl, name, steps, warmup, use_graph=True, compare=True):
     """The whole training step of an ImageNet-shaped bf16 / NHWC workload (batch 32, 224x224 inputs:
     stem, max pool, four dense blocks, transitions, head, loss): the fused schedule as the library
     runs it by default and the three schedules in program order on one stream, with the exact
@@ -451,17 +454,20 @@ def extra_bf16_net(dnb, torch, wl, name, steps, warmup):
     t = {}
     for label, sname, serial in (("fused", "fused", False), ("fused_one_stream", "fused", True), ("shared", "shared", True),
                                  ("store_all", "store_all", True)):
+        if not compare and label != "fused":
+            continue
         r = InetRun(dnb, torch, wl, icfg, sched[sname])
         if serial:
             dnb.dnb_inet_set_concurrency(r.h, False)
-        t[label] = time_steps(torch, make_inet_step(dnb, r), steps, warmup, True)
+        t[label] = time_steps(torch, make_inet_step(dnb, r), steps, warmup, use_graph)
         out[label] = {"images_per_s": round(icfg.n * steps / t[label], 2), "ms_per_step": round(1e3 * t[label] / steps, 4),
                       "network_feature_map_bytes": r.peak, "workspace_bytes": r.workspace}
         r.close()
         del r
         torch.cuda.empty_cache()
-    out["recompute_overhead"] = round(t["shared"] / t["store_all"] - 1.0, 4)
-    out["fused_vs_store_all_time"] = round(t["fused_one_stream"] / t["store_all"] - 1.0, 4)
+    if compare:
+        out["recompute_overhead"] = round(t["shared"] / t["store_all"] - 1.0, 4)
+        out["fused_vs_store_all_time"] = round(t["fused_one_stream"] / t["store_all"] - 1.0, 4)
     return out
 
 
@@ -497,14 +503,14 @@ def main():
 
     if bf16 and a.only_block < 0 and a.scope in ("auto", "net"):
         # the ImageNet-shaped workloads as whole training steps (diagnostic line of their own)
-        res = extra_bf16_net(dnb, torch, wl, a.workload, a.steps, a.warmup)
-        res["dense_blocks_only"] = extra_bf16_blocks(dnb, torch, wl, a.workload, a.steps, a.warmup)
+        res = extra_bf16_net(dnb, torch, wl, a.workload, a.steps, a.warmup, use_graph, not a.no_compare)
+        res["dense_blocks_only"] = extra_bf16_blocks(dnb, torch, wl, a.workload, a.steps, a.warmup, use_graph, not a.no_compare)
         print(json.dumps({"metric": "train images/sec per MI355X (fwd+bwd) + peak feature-map bytes vs depth",
                           "value": res["fused"]["images_per_s"], "unit": "images/s", "n_gpus": 1, "steps": a.steps,
                           "warmup": a.warmup, "ms_per_step": res["fused"]["ms_per_step"], "higher_is_better": True,
                           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-                          "config": {"workload": res["workload"], "schedule": "fused", "launch": "hip_graph",
-                                     "global_batch": 32}, "detail": res}), flush=True)
+                          "config": {"workload": res["workload"], "schedule": "fused",
+                                     "launch": "hip_graph" if use_graph else "eager", "global_batch": 32}, "detail": res}), flush=True)
         return
     net_scope = a.scope == "net" or (a.scope == "auto" and a.workload in ("config2", "config3") and a.only_block < 0)
     if net_scope and a.workload not in ("config2", "config3"):

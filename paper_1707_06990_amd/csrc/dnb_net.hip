@@ -117,26 +117,53 @@ __global__ __launch_bounds__(kT) void k_softmax_xent(const float* __restrict__ l
   }
 }
 
-// df[i][j] = sum_o dlogits[i][o] Wl[o][j]: a thread owns column j for a group of 8 samples, so a weight
-// is read once per 8 samples (the dlogits reads are the same for the whole wave).  grid (ceil(c/256), ceil(n/8)).
-__global__ __launch_bounds__(kT) void k_linear_bwd_data(const float* __restrict__ dlogits,
-                                                        const float* __restrict__ wl, float* __restrict__ df, int n,
-                                                        int c, int classes) {
-  const int j = blockIdx.x * kT + threadIdx.x, i0 = blockIdx.y * 8;
-  if (j >= c) return;
-  const int ni = min(8, n - i0);
+// df[i][j] = sum_o dlogits[i][o] Wl[o][j].  A workgroup owns 64 columns j for a group of 8 samples; its 16
+// waves take a sixteenth of the classes each (a weight row segment is one coalesced 256-byte read per wave
+// and class, used for the 8 samples; the dlogits reads are the same for the whole wave), four classes'
+// loads issued before the first is used.  The waves' sums are added through LDS in wave order.
+// grid (ceil(c/64), ceil(n/8)), 1024 threads.
+constexpr int kLbdWaves = 16;
+__global__ __launch_bounds__(64 * kLbdWaves) void k_linear_bwd_data(const float* __restrict__ dlogits,
+                                                                    const float* __restrict__ wl, float* __restrict__ df,
+                                                                    int n, int c, int classes) {
+  __shared__ float sh[kLbdWaves - 1][8][64];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = blockIdx.x * 64 + lane, jc = min(j, c - 1), i0 = blockIdx.y * 8;
+  const int per = (classes + kLbdWaves - 1) / kLbdWaves, o0 = wave * per, o1 = min(classes, o0 + per);
+  const float* drow[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) drow[u] = dlogits + (int64_t)min(i0 + u, n - 1) * classes;  // rows past n: computed, not stored
   float acc[8];
 #pragma unroll
   for (int u = 0; u < 8; ++u) acc[u] = 0.f;
-  for (int o = 0; o < classes; ++o) {
-    const float w = wl[(int64_t)o * c + j];
+  for (int o = o0; o < o1; o += 4) {
+    float w[4];
+    int oo[4];
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
-      if (u < ni) acc[u] = __fmaf_rn(dlogits[(int64_t)(i0 + u) * classes + o], w, acc[u]);
+    for (int v = 0; v < 4; ++v) {
+      oo[v] = min(o + v, o1 - 1);
+      w[v] = wl[(int64_t)oo[v] * c + jc];
+    }
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const float wv = o + v < o1 ? w[v] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc[u] = __fmaf_rn(drow[u][oo[v]], wv, acc[u]);
+    }
   }
+  if (wave > 0) {
 #pragma unroll
-  for (int u = 0; u < 8; ++u)
-    if (u < ni) df[(int64_t)(i0 + u) * c + j] = acc[u];
+    for (int u = 0; u < 8; ++u) sh[wave - 1][u][lane] = acc[u];
+  }
+  __syncthreads();
+  if (wave == 0 && j < c) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      float t = acc[u];
+      for (int w2 = 0; w2 < kLbdWaves - 1; ++w2) t += sh[w2][u][lane];
+      if (i0 + u < n) df[(int64_t)(i0 + u) * c + j] = t;
+    }
+  }
 }
 
 // dWl[o][j] = sum_i dlogits[i][o] f[i][j] (thread per (o, j)); dbl[o] = sum_i dlogits[i][o] (j == 0).
@@ -192,8 +219,8 @@ hipError_t launch_head_forward(const float* pooled, const float* wl, const float
 
 hipError_t launch_head_backward(const float* dlogits, const float* pooled, const float* wl, float* dpooled, float* dwl,
                                 float* dbl, int n, int c, int classes, hipStream_t st) {
-  hipLaunchKernelGGL(k_linear_bwd_data, dim3((unsigned)((c + kT - 1) / kT), (unsigned)((n + 7) / 8)), dim3(kT), 0, st, dlogits,
-                     wl, dpooled, n, c, classes);
+  hipLaunchKernelGGL(k_linear_bwd_data, dim3((unsigned)((c + 63) / 64), (unsigned)((n + 7) / 8)), dim3(64 * kLbdWaves), 0, st,
+                     dlogits, wl, dpooled, n, c, classes);
   hipLaunchKernelGGL(k_linear_bwd_weights, dim3(grid_for((int64_t)classes * c, kT)), dim3(kT), 0, st, dlogits, pooled, dwl,
                      dbl, n, c, classes);
   return hipGetLastError();
