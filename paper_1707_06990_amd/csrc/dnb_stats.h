@@ -52,9 +52,22 @@ __device__ __forceinline__ Stat3 stat_merge_wave(Stat3 v) {
 // per-wave results in wave order.  `sh` needs 3 floats per wave.  Result in every thread.
 __device__ __forceinline__ Stat3 stat_merge_block(const float* __restrict__ p, int T, float* sh) {
   Stat3 v{0.f, 0.f, 0.f};
-  for (int i = threadIdx.x; i < T; i += blockDim.x) {
-    Stat3 o{p[3 * i], p[3 * i + 1], p[3 * i + 2]};
-    v = stat_combine(v, o);
+  // four of the thread's partials are requested before the first is folded in (a fold per load
+  // would wait out one memory latency per partial); loads past T repeat the last partial and
+  // enter as empty sets, which stat_combine passes through unchanged
+  const int bd = blockDim.x;
+  for (int i = threadIdx.x; i < T; i += 4 * bd) {
+    Stat3 o[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int q = min(i + u * bd, T - 1);
+      o[u] = Stat3{p[3 * q], p[3 * q + 1], p[3 * q + 2]};
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (i + u * bd >= T) o[u] = Stat3{0.f, 0.f, 0.f};
+      v = stat_combine(v, o[u]);
+    }
   }
   v = stat_merge_wave(v);
   const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
