@@ -1098,7 +1098,7 @@ __global__ __launch_bounds__(256, 3) void k_wgrad_pair(Wg1Args A1, int gx1, int 
     // tile columns of one pixel range read the same gradient rows, and the m groups of a c column
     // the same feature rows: pixel range bx is given to XCD bx % 8 whole, so that these rows come
     // from HBM once and from that XCD's L2 afterwards (measured HBM bytes per launch 190 -> 176 MB
-    // on DenseNet-BC-100's first block, 776 -> 556 MB on DenseNet-BC-250's).  n1 counts
+    // on DenseNet-BC-100's first block, 776 -> 562 MB on DenseNet-BC-250's).  n1 counts
     // ceil(gx1 / 8) ranges per XCD; the ids past the last range have no work.
     const int xcd = id & 7, slot = id >> 3, cols = gy1 * gz1;
     const int col = slot % cols, bx = (slot / cols) * 8 + xcd;
