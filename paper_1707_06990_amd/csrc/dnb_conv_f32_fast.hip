@@ -1178,6 +1178,8 @@ __global__ __launch_bounds__(256) void k_bn_fold(const float* __restrict__ gamma
                                                 float2* __restrict__ fold) {
   __shared__ float sh[12];
   const int ch = blockIdx.x;
+  // requested before the merge: behind its barriers they would cost a second memory round trip
+  const float ga = gamma[ch], be = beta[ch];
   float mu, is;
   if (ch >= fresh_lo && ch < fresh_hi) {
     const Stat3 r = stat_merge_block(part + (int64_t)(ch - fresh_lo) * T * 3, T, sh);
@@ -1190,7 +1192,7 @@ __global__ __launch_bounds__(256) void k_bn_fold(const float* __restrict__ gamma
   }
   if (threadIdx.x == 0) {
     float sc, sf;
-    bn_fold(gamma[ch], beta[ch], mu, is, sc, sf);
+    bn_fold(ga, be, mu, is, sc, sf);
     fold[ch] = make_float2(sc, sf);
   }
 }

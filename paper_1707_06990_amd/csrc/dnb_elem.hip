@@ -221,6 +221,36 @@ __global__ __launch_bounds__(kThreads) void k_bn_bwd_apply(
     const float* __restrict__ part, int psplits, float* __restrict__ dgamma, float* __restrict__ dbeta) {
   __shared__ float sh[2];
   const int ch = blockIdx.x, n0 = blockIdx.y * ipb, ni = min(n, n0 + ipb) - n0;
+  // Everything that does not depend on the sums is requested before the barrier below: the
+  // channel's constants and the thread's first four positions (behind the barrier each would
+  // cost one more memory round trip, which is what a small slab's launch consists of).
+  const float mu = mean[ch], is = istd[ch], ga = gamma[ch], be = beta[ch];
+  const int hwv = hw / V;
+  const int64_t inner = (int64_t)ch * hw;
+  const float* xp = x + (int64_t)n0 * x_stride + inner;
+  const float* gp = dact + (int64_t)n0 * dact_stride + inner;
+  float* dp = du + (int64_t)n0 * du_stride + inner;
+  RowIter it(hwv, threadIdx.x, blockDim.x);
+  float t[4][V], g[4][V], r[4][V];
+  float* d[4];
+  bool ok[4];
+  // four positions per pass, all loads issued before the first is consumed (as in the partial
+  // kernel; a position past the range repeats the last image's and is not stored); dact may
+  // alias du: a thread reads its four positions before it writes them
+  auto request = [&]() {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      ok[u] = it.img < ni;
+      const int im = ok[u] ? it.img : ni - 1;
+      const int64_t qo = (int64_t)it.q * V;
+      Vec<V>::ld(xp + (int64_t)im * x_stride + qo, t[u]);
+      Vec<V>::ld(gp + (int64_t)im * dact_stride + qo, g[u]);
+      d[u] = dp + (int64_t)im * du_stride + qo;
+      if (ACC) Vec<V>::ld(d[u], r[u]);
+      it.next();
+    }
+  };
+  request();
   if (threadIdx.x < 64) {
     const int lane = threadIdx.x;
     float sb = 0.f, sg = 0.f;
@@ -237,31 +267,9 @@ __global__ __launch_bounds__(kThreads) void k_bn_bwd_apply(
   }
   __syncthreads();
   const float mb = sh[0] * inv_p, mg = sh[1] * inv_p;
-  const float mu = mean[ch], is = istd[ch];
   float scale, shift;
-  bn_fold(gamma[ch], beta[ch], mu, is, scale, shift);
-  const int hwv = hw / V;
-  const int64_t inner = (int64_t)ch * hw;
-  const float* xp = x + (int64_t)n0 * x_stride + inner;
-  const float* gp = dact + (int64_t)n0 * dact_stride + inner;
-  float* dp = du + (int64_t)n0 * du_stride + inner;
-  // four positions per pass, all loads issued before the first is consumed (as in the partial
-  // kernel); dact may alias du: a thread reads its four positions before it writes them
-  for (RowIter it(hwv, threadIdx.x, blockDim.x); it.img < ni;) {
-    float t[4][V], g[4][V], r[4][V];
-    float* d[4];
-    bool ok[4];
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      ok[u] = it.img < ni;
-      const int im = ok[u] ? it.img : ni - 1;
-      const int64_t qo = (int64_t)it.q * V;
-      Vec<V>::ld(xp + (int64_t)im * x_stride + qo, t[u]);
-      Vec<V>::ld(gp + (int64_t)im * dact_stride + qo, g[u]);
-      d[u] = dp + (int64_t)im * du_stride + qo;
-      if (ACC) Vec<V>::ld(d[u], r[u]);
-      it.next();
-    }
+  bn_fold(ga, be, mu, is, scale, shift);
+  for (;;) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       if (ok[u]) {
@@ -275,6 +283,8 @@ __global__ __launch_bounds__(kThreads) void k_bn_bwd_apply(
         Vec<V>::st(d[u], r[u]);
       }
     }
+    if (!(it.img < ni)) break;
+    request();
   }
 }
 
