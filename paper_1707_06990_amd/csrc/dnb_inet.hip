@@ -48,33 +48,41 @@ __device__ __forceinline__ void stage_patch(const u16* __restrict__ x, int S, in
   }
 }
 
+// The stem conv's weights as its kernel reads them: Wt[t][c] = W (C, 3, 7, 7) rounded to bf16 (as every
+// conv of this path reads its weights), tap-major with t = (ky*7 + kx)*3 + ci.
+__global__ __launch_bounds__(256) void k_stem_pack_w(const float* __restrict__ W, float* __restrict__ Wt, int C) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= kTaps * C) return;
+  const int t = i / C, c = i - t * C;
+  const int ci = t % 3, kk = t / 3, ky = kk / 7, kx = kk - ky * 7;
+  Wt[i] = bf2f(f2bf(W[((c * 3 + ci) * 7 + ky) * 7 + kx]));
+}
+
 // Stem convolution: out (n, S/2, S/2, C) bf16 = conv7x7 stride 2 pad 3 of x (n, S, S, 3) bf16 with the
-// weights W (C, 3, 7, 7) fp32 rounded to bf16 as every conv of this path reads its weights; fp32
-// accumulation.  One workgroup per 8x8 output tile: weights (tap-major) and the 21x21x3 input patch
-// in LDS; a thread owns one pixel and C/4 = 4*NV channels (each wave one channel group, so its
-// weight reads are broadcasts).  grid (tiles, n), 256 threads.
+// packed weights Wt (147, C); fp32 accumulation.  One workgroup per 8x8 output tile with the 21x21x3
+// input patch in LDS; a thread owns one pixel and C/4 = 4*NV channels.  Each wave is one channel
+// group, so its weight addresses are the same for all lanes: they are read through the scalar
+// cache straight into the FMAs' scalar operand, and LDS serves only the one patch value per tap
+// (with the weights in LDS as well, six 16-byte broadcast reads per 24 FMAs kept the CU's one LDS
+// twice as busy as its four vector units: 394 us per launch at C = 96, batch 32).
+// grid (tiles, n), 256 threads.
 template <int NV>
-__global__ __launch_bounds__(256) void k_stem_conv7(const u16* __restrict__ x, const float* __restrict__ W,
+__global__ __launch_bounds__(256) void k_stem_conv7(const u16* __restrict__ x, const float* __restrict__ Wt,
                                                     u16* __restrict__ out, int S) {
   constexpr int C = 16 * NV, CPG = 4 * NV;
   extern __shared__ float lds[];
-  float* wl = lds;                     // [147][C]
-  float* patch = lds + kTaps * C;      // [21*21*3]
+  float* patch = lds;                  // [21*21*3]
   const int So = S / 2, tiles = So / kTile;
   const int img = blockIdx.y, ty = blockIdx.x / tiles, tx = blockIdx.x - ty * tiles;
-  for (int i = threadIdx.x; i < kTaps * C; i += 256) {
-    const int t = i / C, c = i - t * C;            // t = (ky*7 + kx)*3 + ci
-    const int ci = t % 3, kk = t / 3, ky = kk / 7, kx = kk - ky * 7;
-    wl[i] = bf2f(f2bf(W[((c * 3 + ci) * 7 + ky) * 7 + kx]));
-  }
   stage_patch(x, S, img, ty, tx, patch);
   __syncthreads();
-  const int p = threadIdx.x & 63, grp = threadIdx.x >> 6, py = p >> 3, px = p & 7;
+  const int p = threadIdx.x & 63, py = p >> 3, px = p & 7;
+  const int grp = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // the same for the whole wave
   float4 acc[NV];
 #pragma unroll
   for (int q = 0; q < NV; ++q) acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
   const float* pb = patch + ((2 * py) * kPatch + 2 * px) * 3;
-  const float* wb = wl + grp * CPG;
+  const float* wb = Wt + grp * CPG;
   for (int ky = 0; ky < 7; ++ky) {
 #pragma unroll
     for (int kxc = 0; kxc < 21; ++kxc) {   // (kx, ci) pairs are contiguous in the patch row and in t
@@ -360,15 +368,17 @@ inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) &
 
 constexpr int kStemWgradWorkgroups = 512;
 
-hipError_t launch_stem_conv(const u16* x, const float* W, u16* out, int n, int S, int C, hipStream_t st) {
+// Wt: scratch of 147*C floats for the packed weights
+hipError_t launch_stem_conv(const u16* x, const float* W, float* Wt, u16* out, int n, int S, int C, hipStream_t st) {
   const int tiles = (S / 2) / kTile;
   const dim3 grid((unsigned)(tiles * tiles), (unsigned)n);
-  const size_t lds = ((size_t)kTaps * C + kPatch * kPatch * 3) * sizeof(float);
+  const size_t lds = (size_t)kPatch * kPatch * 3 * sizeof(float);
+  hipLaunchKernelGGL(k_stem_pack_w, dim3((unsigned)((kTaps * C + 255) / 256)), dim3(256), 0, st, W, Wt, C);
   switch (C / 16) {
-    case 1: hipLaunchKernelGGL(k_stem_conv7<1>, grid, dim3(256), lds, st, x, W, out, S); break;
-    case 2: hipLaunchKernelGGL(k_stem_conv7<2>, grid, dim3(256), lds, st, x, W, out, S); break;
-    case 4: hipLaunchKernelGGL(k_stem_conv7<4>, grid, dim3(256), lds, st, x, W, out, S); break;
-    case 6: hipLaunchKernelGGL(k_stem_conv7<6>, grid, dim3(256), lds, st, x, W, out, S); break;
+    case 1: hipLaunchKernelGGL(k_stem_conv7<1>, grid, dim3(256), lds, st, x, Wt, out, S); break;
+    case 2: hipLaunchKernelGGL(k_stem_conv7<2>, grid, dim3(256), lds, st, x, Wt, out, S); break;
+    case 4: hipLaunchKernelGGL(k_stem_conv7<4>, grid, dim3(256), lds, st, x, Wt, out, S); break;
+    case 6: hipLaunchKernelGGL(k_stem_conv7<6>, grid, dim3(256), lds, st, x, Wt, out, S); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -409,7 +419,7 @@ struct dnb_inet {
   // workspace offsets (bytes)
   size_t o_s, o_pos, o_fold_s, o_stat_s;
   size_t o_feat[4], o_y[4], o_ws[4], o_stat[4], o_fold[4], o_pack[3], o_tconv;
-  size_t o_gy, o_dtz, o_dconv, o_dfeat, o_da0, o_part;
+  size_t o_gy, o_dtz, o_dconv, o_dfeat, o_da0, o_part, o_stem_wt;
   size_t o_pooled, o_dpooled, o_logits, o_dlogits, o_terms;
   size_t ws_bytes, glue_feature_bytes;
 };
@@ -508,6 +518,7 @@ int dnb_inet_create(const dnb_inet_desc* desc, dnb_inet** out) {
   net->o_dfeat = carve(feat_max * 2, true);   // gradient of a block input
   net->o_da0 = carve(Ps * cs * 2, true);      // gradient of the stem's BN+ReLU output, then of the stem conv's output
   net->o_part = carve(part * 4, false);
+  net->o_stem_wt = carve((size_t)kTaps * cs * 4, false);
   const size_t C = (size_t)net->cout[3];
   net->o_pooled = carve((size_t)d.n * C * 4, false);
   net->o_dpooled = carve((size_t)d.n * C * 4, false);
@@ -584,7 +595,7 @@ int dnb_inet_forward(dnb_inet* net, const void* xv, const int32_t* labels, const
   u16* s = (u16*)(ws + net->o_s);
   float* mean_s = (float*)(ws + net->o_stat_s);
   float2* fold_s = (float2*)(ws + net->o_fold_s);
-  DNB_TRYH(launch_stem_conv(x, params + net->p_stem_w, s, n, S, cs, st));
+  DNB_TRYH(launch_stem_conv(x, params + net->p_stem_w, (float*)(ws + net->o_stem_wt), s, n, S, cs, st));
   int T = 0;
   DNB_TRYH(nhwc::stats_partial(s, cs, Ps, cs, part, &T, st));
   DNB_TRYH(launch_bn_fold(params + net->p_stem_g, params + net->p_stem_b, mean_s, mean_s + cs, part, T, 0, cs, d.eps, cs,
