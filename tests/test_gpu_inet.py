@@ -86,3 +86,47 @@ def test_inet_full_widths_and_depths_at_batch_2(dnb, oracle, which):
     1000 classes) at batch 2, which the oracle finishes in seconds."""
     cfg = wl.inet_config4(2) if which == "config4" else wl.inet_config5(2)
     check_step(dnb, oracle, cfg)
+
+
+def test_inet_hip_graph_replays_match_eager(dnb, oracle):
+    """The whole ImageNet-shaped step captured in a HIP graph with the library's default stream order
+    (the blocks' backward passes fork onto their helper stream and join again), as bench.py times it:
+    every replay, with eager work and synchronisation in between and the workspace poisoned before
+    it, reproduces the eager bits of the loss, the logits and every parameter gradient."""
+    from harness import dev, pack_inet
+    cfg = CFGS[1]
+    x, labels, params = wl.make_inet_inputs(cfg, affine="random")
+    x = to_bf16_values(x)
+    s, flat, loss0, logits0, dp0 = run_inet_gpu(dnb, oracle, cfg, x, labels, params, 2)
+    net = dnb.dnb_inet_create(cfg.n, cfg.image, cfg.growth, cfg.layers, cfg.classes, schedule=2, eps=cfg.eps)
+    p = dev(flat.astype(np.float32))
+    dp = torch.zeros_like(p)
+    ws = torch.zeros(dnb.dnb_inet_workspace_bytes(net), dtype=torch.uint8, device="cuda")
+    xd = torch.from_numpy(np.ascontiguousarray(x)).permute(0, 2, 3, 1).contiguous().to("cuda", torch.bfloat16)
+    lab = torch.from_numpy(labels).to("cuda")
+    loss = torch.zeros((1,), device="cuda")
+    logits = torch.zeros((cfg.n, cfg.classes), device="cuda")
+
+    def step():
+        dnb.dnb_inet_forward(net, xd, lab, p, loss, logits, ws)
+        dnb.dnb_inet_backward(net, xd, p, dp, ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep in range(4):
+        dp.fill_(float("nan")); logits.fill_(float("nan")); loss.fill_(float("nan")); ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert float(loss.item()) == loss0, rep
+        assert np.array_equal(logits.cpu().numpy(), logits0), rep
+        assert np.array_equal(dp.cpu().numpy(), dp0), rep
+        _ = (torch.randn(1000, device="cuda") * 2).sum().item()  # unrelated eager work between replays
+    dnb.dnb_inet_destroy(net)

@@ -41,6 +41,48 @@ def test_net_schedules_agree_and_replays_are_deterministic(dnb, oracle):
     assert np.array_equal(a[3], b[3]) and np.array_equal(a[4], b[4]) and np.array_equal(a[4], c[4])
 
 
+@pytest.mark.parametrize("schedule", [0, 2])
+def test_net_hip_graph_replays_match_eager(dnb, oracle, schedule):
+    """The whole CIFAR-shaped step captured in a HIP graph, as bench.py times it: every replay, with
+    eager work and synchronisation in between and the workspace poisoned before it, reproduces the
+    eager bits of the loss, the logits and every parameter gradient."""
+    cfg = CFGS[2]
+    x, labels, params = wl.make_net_inputs(cfg, affine="random")
+    s, flat, loss0, logits0, dp0 = run_net_gpu(dnb, oracle, cfg, x, labels, params, schedule)
+    net = dnb.dnb_net_create(cfg.n, cfg.image, cfg.depth, cfg.growth, cfg.classes, schedule=schedule, eps=cfg.eps)
+    p = dev(flat.astype(np.float32))
+    dp = torch.zeros_like(p)
+    ws = torch.zeros(dnb.dnb_net_workspace_bytes(net), dtype=torch.uint8, device="cuda")
+    xd = dev(x)
+    lab = torch.from_numpy(labels).to("cuda")
+    loss = torch.zeros((1,), device="cuda")
+    logits = torch.zeros((cfg.n, cfg.classes), device="cuda")
+
+    def step():
+        dnb.dnb_net_forward(net, xd, lab, p, loss, logits, ws)
+        dnb.dnb_net_backward(net, xd, p, dp, ws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep in range(4):
+        dp.fill_(float("nan")); logits.fill_(float("nan")); loss.fill_(float("nan")); ws.fill_(0xFF)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert float(loss.item()) == loss0, rep
+        assert np.array_equal(logits.cpu().numpy(), logits0), rep
+        assert np.array_equal(dp.cpu().numpy(), dp0), rep
+        _ = (torch.randn(1000, device="cuda") * 2).sum().item()  # unrelated eager work between replays
+    dnb.dnb_net_destroy(net)
+
+
 def test_net_with_sixteen_layers_per_block_at_small_batch(dnb, oracle):
     """Depth 100 (16 layers per block): the input of the second block (108 channels at 16x16) is
     larger than that of the first (24 channels at 32x32), so the buffers the blocks share for their
