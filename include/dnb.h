@@ -360,6 +360,20 @@ int dnb_net_forward(dnb_net* net, const void* x, const int32_t* labels, const vo
 int dnb_net_backward(dnb_net* net, const void* x, const void* params, void* dparams, void* workspace,
                      void* stream);
 
+/* The classifier head both network steps end in (paper Section 2, "DenseNet Architecture": after the
+ * last dense block the features are pooled globally and classified; trained with the softmax loss), as
+ * single operations.  All tensors fp32, row-major, device pointers.
+ * forward:  logits (n, classes) = pooled (n, c) . wl (classes, c)^T + bl (classes);
+ *           loss = mean over the batch of -log softmax(logits)[label]; dlogits (n, classes) = its
+ *           gradient; a sample whose label is outside [0, classes) adds nothing to either.
+ *           terms: n floats of scratch.
+ * backward: dpooled (n, c) = dlogits . wl; dwl (classes, c) = dlogits^T . pooled; dbl = column sums of dlogits.
+ * DNB_E_RANGE beyond n = 4096, classes = 65536, c = 2^20. */
+int dnb_op_head_forward(const void* pooled, const void* wl, const void* bl, const int32_t* labels, void* logits,
+                        void* dlogits, void* terms, float* loss, int64_t n, int64_t c, int64_t classes, void* stream);
+int dnb_op_head_backward(const void* dlogits, const void* pooled, const void* wl, void* dpooled, void* dwl, void* dbl,
+                         int64_t n, int64_t c, int64_t classes, void* stream);
+
 /* ------------------------------------------------------------------------------------------
  * Whole training step of an ImageNet-shaped DenseNet-BC (bf16 feature maps, NHWC; fp32 accumulation,
  * statistics, parameters and parameter gradients): four dense blocks joined by the network's glue
@@ -409,6 +423,29 @@ int dnb_inet_backward(dnb_inet* net, const void* x, const void* params, void* dp
 size_t dnb_inet_relu_decision_bytes(const dnb_inet* net);
 size_t dnb_inet_pool_position_bytes(const dnb_inet* net);
 int dnb_inet_decisions(dnb_inet* net, const void* params, const void* workspace, void* relu, void* pool, void* stream);
+
+/* The glue kernels of the ImageNet-shaped step as single operations (paper Section 2, "DenseNet
+ * Architecture": a convolution and pooling before the first dense block; the ImageNet models of
+ * Section 5).  Tensors NHWC bf16 unless stated, device pointers; h, w even, c a multiple of 8.
+ * stem_conv7:  out (n, image/2, image/2, channels) = 7x7 stride-2 pad-3 cross-correlation of
+ *              x (n, image, image, 3) with w (channels, 3, 7, 7) fp32 rounded to bf16, fp32 accumulation.
+ * stem_wgrad7: dw (channels, 3, 7, 7) fp32 = its weight gradient for g (n, image/2, image/2, channels).
+ *              scratch: dnb_op_stem_scratch_bytes for either; channels 16, 32, 64 or 96, image a multiple
+ *              of 32 (else DNB_E_UNSUPPORTED / DNB_E_BADDESC).
+ * maxpool3s2_bnrelu: out (n, h/2, w/2, c) = 3x3 stride-2 pad-1 max pool of max(0, s*scale + shift),
+ *              fold = c (scale, shift) pairs fp32; pos (n, h/2, w/2, c) bytes = 3*i + j of the maximum
+ *              inside its window, the first in row-by-row scan order among equals, padding excluded.
+ * maxpool3s2_backward: din (n, h, w, c) = adjoint of the pooling: every window's gradient goes to the
+ *              position recorded in pos; an input position adds its windows' gradients in fp32. */
+size_t dnb_op_stem_scratch_bytes(int64_t n, int64_t image, int64_t channels);
+int dnb_op_stem_conv7(const void* x, const void* w, void* out, int64_t n, int64_t image, int64_t channels, void* scratch,
+                      void* stream);
+int dnb_op_stem_wgrad7(const void* x, const void* g, void* dw, int64_t n, int64_t image, int64_t channels, void* scratch,
+                       void* stream);
+int dnb_op_maxpool3s2_bnrelu(const void* s, const void* fold, void* out, void* pos, int64_t n, int64_t h, int64_t w,
+                             int64_t c, void* stream);
+int dnb_op_maxpool3s2_backward(const void* dout, const void* pos, void* din, int64_t n, int64_t h, int64_t w, int64_t c,
+                               void* stream);
 
 #ifdef __cplusplus
 }

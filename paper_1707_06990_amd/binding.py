@@ -122,6 +122,13 @@ _SIGS = {
     "dnb_inet_relu_decision_bytes": (_sz, [_vp]),
     "dnb_inet_pool_position_bytes": (_sz, [_vp]),
     "dnb_inet_decisions": (C.c_int, [_vp] * 6),
+    "dnb_op_head_forward": (C.c_int, [_vp] * 8 + [_i64, _i64, _i64, _vp]),
+    "dnb_op_head_backward": (C.c_int, [_vp] * 6 + [_i64, _i64, _i64, _vp]),
+    "dnb_op_stem_scratch_bytes": (_sz, [_i64, _i64, _i64]),
+    "dnb_op_stem_conv7": (C.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp]),
+    "dnb_op_stem_wgrad7": (C.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp]),
+    "dnb_op_maxpool3s2_bnrelu": (C.c_int, [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp]),
+    "dnb_op_maxpool3s2_backward": (C.c_int, [_vp, _vp, _vp, _i64, _i64, _i64, _i64, _vp]),
 }
 for _name, (_res, _args) in _SIGS.items():
     _f = getattr(_lib, _name)
@@ -479,3 +486,33 @@ def dnb_inet_pool_position_bytes(net) -> int:
 
 def dnb_inet_decisions(net, params, workspace, relu, pool, stream=None) -> None:
     _check(_lib.dnb_inet_decisions(net, _ptr(params), _ptr(workspace), _ptr(relu), _ptr(pool), _stream(stream)))
+
+
+def dnb_op_head_forward(pooled, wl, bl, labels, logits, dlogits, terms, loss, n, c, classes, stream=None) -> None:
+    _check(_lib.dnb_op_head_forward(_ptr(pooled), _ptr(wl), _ptr(bl), _ptr(labels), _ptr(logits), _ptr(dlogits),
+                                    _ptr(terms), _ptr(loss), n, c, classes, _stream(stream)))
+
+
+def dnb_op_head_backward(dlogits, pooled, wl, dpooled, dwl, dbl, n, c, classes, stream=None) -> None:
+    _check(_lib.dnb_op_head_backward(_ptr(dlogits), _ptr(pooled), _ptr(wl), _ptr(dpooled), _ptr(dwl), _ptr(dbl),
+                                     n, c, classes, _stream(stream)))
+
+
+def dnb_op_stem_scratch_bytes(n, image, channels) -> int:
+    return int(_lib.dnb_op_stem_scratch_bytes(n, image, channels))
+
+
+def dnb_op_stem_conv7(x, w, out, n, image, channels, scratch, stream=None) -> None:
+    _check(_lib.dnb_op_stem_conv7(_ptr(x), _ptr(w), _ptr(out), n, image, channels, _ptr(scratch), _stream(stream)))
+
+
+def dnb_op_stem_wgrad7(x, g, dw, n, image, channels, scratch, stream=None) -> None:
+    _check(_lib.dnb_op_stem_wgrad7(_ptr(x), _ptr(g), _ptr(dw), n, image, channels, _ptr(scratch), _stream(stream)))
+
+
+def dnb_op_maxpool3s2_bnrelu(s, fold, out, pos, n, h, w, c, stream=None) -> None:
+    _check(_lib.dnb_op_maxpool3s2_bnrelu(_ptr(s), _ptr(fold), _ptr(out), _ptr(pos), n, h, w, c, _stream(stream)))
+
+
+def dnb_op_maxpool3s2_backward(dout, pos, din, n, h, w, c, stream=None) -> None:
+    _check(_lib.dnb_op_maxpool3s2_backward(_ptr(dout), _ptr(pos), _ptr(din), n, h, w, c, _stream(stream)))

@@ -756,4 +756,75 @@ int dnb_inet_decisions(dnb_inet* net, const void* paramsv, const void* wsv, void
   return DNB_OK;
 }
 
+// ---- the glue kernels as single operations
+
+static int stem_shape_ok(int64_t n, int64_t image, int64_t channels) {
+  if (n < 1 || image < 32 || image % 32 != 0) return DNB_E_BADDESC;
+  if (n > 4096 || image > 1024) return DNB_E_RANGE;
+  if (channels != 16 && channels != 32 && channels != 64 && channels != 96) return DNB_E_UNSUPPORTED;
+  return DNB_OK;
+}
+
+size_t dnb_op_stem_scratch_bytes(int64_t n, int64_t image, int64_t channels) {
+  if (stem_shape_ok(n, image, channels) != DNB_OK) return 0;
+  const size_t wt = (size_t)kTaps * channels * 4;
+  const size_t part = (size_t)stem_wgrad_groups((int)n, (int)image) * channels * kTaps * 4;
+  return wt > part ? wt : part;
+}
+
+int dnb_op_stem_conv7(const void* x, const void* w, void* out, int64_t n, int64_t image, int64_t channels, void* scratch,
+                      void* stream) {
+  if (!x || !w || !out || !scratch) return DNB_E_NULL;
+  const int rc = stem_shape_ok(n, image, channels);
+  if (rc != DNB_OK) return rc;
+  if ((reinterpret_cast<uintptr_t>(x) & 1u) || (reinterpret_cast<uintptr_t>(w) & 3u) || misaligned(out) || misaligned(scratch))
+    return DNB_E_ALIGN;
+  DNB_TRYH(launch_stem_conv((const u16*)x, (const float*)w, (float*)scratch, (u16*)out, (int)n, (int)image, (int)channels,
+                            (hipStream_t)stream));
+  return DNB_OK;
+}
+
+int dnb_op_stem_wgrad7(const void* x, const void* g, void* dw, int64_t n, int64_t image, int64_t channels, void* scratch,
+                       void* stream) {
+  if (!x || !g || !dw || !scratch) return DNB_E_NULL;
+  const int rc = stem_shape_ok(n, image, channels);
+  if (rc != DNB_OK) return rc;
+  if ((reinterpret_cast<uintptr_t>(x) & 1u) || misaligned(g) || (reinterpret_cast<uintptr_t>(dw) & 3u) || misaligned(scratch))
+    return DNB_E_ALIGN;
+  DNB_TRYH(launch_stem_wgrad((const u16*)x, (const u16*)g, (float*)scratch, (float*)dw, (int)n, (int)image, (int)channels,
+                             (hipStream_t)stream));
+  return DNB_OK;
+}
+
+static int pool_shape_ok(int64_t n, int64_t h, int64_t w, int64_t c) {
+  if (n < 1 || h < 2 || w < 2 || c < 8 || h % 2 || w % 2 || c % 8) return DNB_E_BADDESC;
+  if (n > 4096 || h > 4096 || w > 4096 || c > 65536) return DNB_E_RANGE;
+  return DNB_OK;
+}
+
+int dnb_op_maxpool3s2_bnrelu(const void* s, const void* fold, void* out, void* pos, int64_t n, int64_t h, int64_t w,
+                             int64_t c, void* stream) {
+  if (!s || !fold || !out || !pos) return DNB_E_NULL;
+  const int rc = pool_shape_ok(n, h, w, c);
+  if (rc != DNB_OK) return rc;
+  if (misaligned(s) || (reinterpret_cast<uintptr_t>(fold) & 7u) || misaligned(out) || (reinterpret_cast<uintptr_t>(pos) & 7u))
+    return DNB_E_ALIGN;
+  hipLaunchKernelGGL(k_maxpool_bnrelu, dim3(grid_for(n * (h / 2) * (w / 2) * (c / 8), 256)), dim3(256), 0, (hipStream_t)stream,
+                     (const u16*)s, (const float2*)fold, (u16*)out, (unsigned char*)pos, (int)n, (int)h, (int)w, (int)c);
+  DNB_TRYH(hipGetLastError());
+  return DNB_OK;
+}
+
+int dnb_op_maxpool3s2_backward(const void* dout, const void* pos, void* din, int64_t n, int64_t h, int64_t w, int64_t c,
+                               void* stream) {
+  if (!dout || !pos || !din) return DNB_E_NULL;
+  const int rc = pool_shape_ok(n, h, w, c);
+  if (rc != DNB_OK) return rc;
+  if (misaligned(dout) || (reinterpret_cast<uintptr_t>(pos) & 7u) || misaligned(din)) return DNB_E_ALIGN;
+  hipLaunchKernelGGL(k_maxpool_bwd, dim3(grid_for(n * h * w * (c / 8), 256)), dim3(256), 0, (hipStream_t)stream,
+                     (const u16*)dout, (const unsigned char*)pos, (u16*)din, (int)n, (int)h, (int)w, (int)c);
+  DNB_TRYH(hipGetLastError());
+  return DNB_OK;
+}
+
 }  // extern "C"

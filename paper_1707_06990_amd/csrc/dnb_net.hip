@@ -246,6 +246,26 @@ struct dnb_net {
 
 extern "C" {
 
+int dnb_op_head_forward(const void* pooled, const void* wl, const void* bl, const int32_t* labels, void* logits,
+                        void* dlogits, void* terms, float* loss, int64_t n, int64_t c, int64_t classes, void* stream) {
+  if (!pooled || !wl || !bl || !labels || !logits || !dlogits || !terms || !loss) return DNB_E_NULL;
+  if (n < 1 || c < 1 || classes < 1 || n > 4096 || classes > 65536 || c > ((int64_t)1 << 20)) return DNB_E_RANGE;
+  if (launch_head_forward((const float*)pooled, (const float*)wl, (const float*)bl, labels, (float*)logits, (float*)dlogits,
+                          (float*)terms, loss, (int)n, (int)c, (int)classes, (hipStream_t)stream) != hipSuccess)
+    return DNB_E_LAUNCH;
+  return DNB_OK;
+}
+
+int dnb_op_head_backward(const void* dlogits, const void* pooled, const void* wl, void* dpooled, void* dwl, void* dbl,
+                         int64_t n, int64_t c, int64_t classes, void* stream) {
+  if (!dlogits || !pooled || !wl || !dpooled || !dwl || !dbl) return DNB_E_NULL;
+  if (n < 1 || c < 1 || classes < 1 || n > 4096 || classes > 65536 || c > ((int64_t)1 << 20)) return DNB_E_RANGE;
+  if (launch_head_backward((const float*)dlogits, (const float*)pooled, (const float*)wl, (float*)dpooled, (float*)dwl,
+                           (float*)dbl, (int)n, (int)c, (int)classes, (hipStream_t)stream) != hipSuccess)
+    return DNB_E_LAUNCH;
+  return DNB_OK;
+}
+
 int dnb_net_create(const dnb_net_desc* desc, dnb_net** out) {
   if (!desc || !out) return DNB_E_NULL;
   const dnb_net_desc& d = *desc;
